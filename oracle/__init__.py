@@ -1,0 +1,206 @@
+"""ctypes front end of the CPU oracle (test infrastructure, not the product).
+
+Only tests, the smoke check and the CPU-baseline leg of the benchmark may import this.
+It imports nothing from the GPU package.  Arrays are numpy; K/V/Q are float32 values that
+the caller has already rounded to the storage type under test.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "dynakv_oracle.cpp")
+_LIB = os.path.join(_HERE, "libdynakv_oracle.so")
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with g++ (no fast-math, no contraction; fma() is explicit in the source)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        flags = ["-O2", "-std=c++17", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off", "-Wall"]
+        try:
+            with open("/proc/cpuinfo") as f:
+                if " fma " in f.read():
+                    flags.append("-mfma")  # lets std::fma compile to one instruction; results are identical
+        except OSError:
+            pass
+        tmp = _LIB + ".tmp%d" % os.getpid()
+        subprocess.check_call(["g++", *flags, _SRC, "-o", tmp])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+class _Cfg(C.Structure):
+    _fields_ = [(k, C.c_int32) for k in ("n_units", "group_size", "head_dim", "n_clusters_init", "max_clusters",
+                                          "max_tokens", "kmeans_iters", "buffer_max", "group_reduce")] + \
+               [(k, C.c_float) for k in ("var_alpha", "size_factor", "softmax_scale")] + [("seed", C.c_uint64)]
+
+
+@dataclass
+class OracleConfig:
+    n_units: int
+    group_size: int
+    head_dim: int
+    n_clusters_init: int
+    max_clusters: int
+    max_tokens: int
+    kmeans_iters: int = 10
+    buffer_max: int = 16
+    group_reduce: int = 0
+    var_alpha: float = 0.0
+    size_factor: float = 0.0
+    softmax_scale: float = 0.0
+    seed: int = 0
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = C.CDLL(build())
+        lib.oracle_create.restype = C.c_void_p
+        lib.oracle_create.argtypes = [C.POINTER(_Cfg)]
+        lib.oracle_destroy.argtypes = [C.c_void_p]
+        lib.oracle_set_threads.argtypes = [C.c_void_p, C.c_int]
+        lib.oracle_threads_used.argtypes = [C.c_void_p]
+        lib.oracle_build_index.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
+        lib.oracle_retrieve_attend.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
+        lib.oracle_append.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+        lib.oracle_split.argtypes = [C.c_void_p]
+        for f in ("oracle_num_clusters", "oracle_num_tokens", "oracle_error", "oracle_last_assign"):
+            getattr(lib, f).argtypes = [C.c_void_p, C.c_int]
+        lib.oracle_tau.argtypes = [C.c_void_p, C.c_int]
+        lib.oracle_tau.restype = C.c_double
+        lib.oracle_get_clusters.argtypes = [C.c_void_p, C.c_int] + [C.c_void_p] * 5
+        lib.oracle_get_members.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
+        lib.oracle_get_selected.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_int]
+        lib.oracle_get_gather.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_int]
+        lib.oracle_get_scores.argtypes = [C.c_void_p, C.c_int, C.c_void_p]
+        lib.oracle_get_diagnostics.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
+        _lib = lib
+    return _lib
+
+
+def _f32(a):
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    return a, a.ctypes.data
+
+
+class Oracle:
+    """One index over `n_units` independent units, driven call by call like the GPU library."""
+
+    def __init__(self, cfg: OracleConfig, threads: int = 0):
+        self.cfg = cfg
+        self._lib = _load()
+        c = _Cfg(**{k: getattr(cfg, k) for k, _ in _Cfg._fields_})
+        self._h = self._lib.oracle_create(C.byref(c))
+        if threads:
+            self._lib.oracle_set_threads(self._h, threads)
+
+    def __del__(self):
+        if getattr(self, "_h", None):
+            self._lib.oracle_destroy(self._h)
+            self._h = None
+
+    @property
+    def threads_used(self) -> int:
+        return self._lib.oracle_threads_used(self._h)
+
+    # ---- the four calls -------------------------------------------------------------------
+    def build_index(self, K, V, init_idx=None):
+        """K, V: [U, N0, d].  Returns the k-means objective per unit and iteration, [U, iters]."""
+        K, kp = _f32(K)
+        V, vp = _f32(V)
+        U, N0, d = K.shape
+        assert (U, d) == (self.cfg.n_units, self.cfg.head_dim) and V.shape == K.shape
+        ip = None
+        if init_idx is not None:
+            init_idx = np.ascontiguousarray(init_idx, dtype=np.int32)
+            assert init_idx.shape == (U, self.cfg.n_clusters_init)
+            ip = init_idx.ctypes.data
+        J = np.zeros((U, self.cfg.kmeans_iters), dtype=np.float64)
+        rc = self._lib.oracle_build_index(self._h, kp, vp, N0, ip, J.ctypes.data)
+        if rc:
+            raise ValueError("oracle_build_index: invalid sizes")
+        return J
+
+    def retrieve_attend(self, Q, budget: int):
+        """Q: [U, G, d].  Returns (out [U, G, d] float64, lse [U, G] float64)."""
+        Q, qp = _f32(Q)
+        U, G, d = Q.shape
+        assert (U, G, d) == (self.cfg.n_units, self.cfg.group_size, self.cfg.head_dim)
+        out = np.zeros((U, G, d), dtype=np.float64)
+        lse = np.zeros((U, G), dtype=np.float64)
+        self._lib.oracle_retrieve_attend(self._h, qp, int(budget), out.ctypes.data, lse.ctypes.data)
+        return out, lse
+
+    def append(self, k, v):
+        k, kp = _f32(k)
+        v, vp = _f32(v)
+        assert k.shape == (self.cfg.n_units, self.cfg.head_dim) and v.shape == k.shape
+        self._lib.oracle_append(self._h, kp, vp)
+
+    def split(self):
+        self._lib.oracle_split(self._h)
+
+    # ---- state ------------------------------------------------------------------------------
+    def num_clusters(self, u): return self._lib.oracle_num_clusters(self._h, u)
+    def num_tokens(self, u): return self._lib.oracle_num_tokens(self._h, u)
+    def error(self, u): return self._lib.oracle_error(self._h, u)
+    def tau(self, u): return self._lib.oracle_tau(self._h, u)
+    def last_assign(self, u): return self._lib.oracle_last_assign(self._h, u)
+
+    def clusters(self, u):
+        """dict(centroids [M, d] f32, n, b, flag [M] i32, M2 [M] f64)."""
+        M, d = self.num_clusters(u), self.cfg.head_dim
+        r = np.zeros((M, d), np.float32)
+        n, b, f = (np.zeros(M, np.int32) for _ in range(3))
+        M2 = np.zeros(M, np.float64)
+        self._lib.oracle_get_clusters(self._h, u, r.ctypes.data, n.ctypes.data, b.ctypes.data, f.ctypes.data,
+                                      M2.ctypes.data)
+        return dict(centroids=r, n=n, b=b, flag=f, M2=M2)
+
+    def members(self, u):
+        """(offsets [M+1], positions [N]): members of cluster j are positions[offsets[j]:offsets[j+1]]."""
+        M, N = self.num_clusters(u), self.num_tokens(u)
+        off = np.zeros(M + 1, np.int32)
+        mem = np.zeros(max(N, 1), np.int32)
+        self._lib.oracle_get_members(self._h, u, off.ctypes.data, mem.ctypes.data)
+        return off, mem[:N]
+
+    def labels(self, u):
+        off, mem = self.members(u)
+        lab = np.full(self.num_tokens(u), -1, np.int32)
+        for j in range(len(off) - 1):
+            lab[mem[off[j]:off[j + 1]]] = j
+        return lab
+
+    def selected(self, u):
+        ids = np.zeros(max(self.num_clusters(u), 1), np.int32)
+        n = self._lib.oracle_get_selected(self._h, u, ids.ctypes.data, len(ids))
+        return ids[:n]
+
+    def gather(self, u):
+        pos = np.zeros(max(self.num_tokens(u), 1), np.int32)
+        n = self._lib.oracle_get_gather(self._h, u, pos.ctypes.data, len(pos))
+        return pos[:n]
+
+    def scores(self, u):
+        s = np.zeros(self.num_clusters(u), np.float32)
+        self._lib.oracle_get_scores(self._h, u, s.ctypes.data)
+        return s
+
+    def diagnostics(self, u):
+        mg = np.zeros(3, np.float64)
+        ties = np.zeros(5, np.int64)
+        ev = np.zeros(3, np.int64)
+        self._lib.oracle_get_diagnostics(self._h, u, mg.ctypes.data, ties.ctypes.data, ev.ctypes.data)
+        return dict(margin_assign=mg[0], margin_trigger=mg[1], margin_select=mg[2],
+                    ties=dict(zip(("kmeans", "assign", "trigger", "select", "split_side"), ties.tolist())),
+                    splits=int(ev[0]), failed_splits=int(ev[1]), forced_splits=int(ev[2]))

@@ -1,0 +1,437 @@
+"""Pins of the CPU oracle against things other than itself (CPU only).
+
+Library routines on special cases (scipy cdist, scikit-learn Lloyd, torch dense attention), closed forms,
+invariants of the partition (Eq. 3), brute force on tiny inputs and hand-computed fixtures.
+"""
+import json
+import os
+
+import numpy as np
+import pytest
+import torch
+from scipy.spatial.distance import cdist
+
+from oracle import Oracle, OracleConfig
+from paper_2511_07427_amd.workload import CONFIGS, generate
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def cfg(U=1, G=1, d=2, M0=2, maxc=8, maxt=64, iters=3, bmax=16, alpha=0.0, size=0.0, reduce=0, scale=0.0):
+    return OracleConfig(U, G, d, M0, maxc, maxt, iters, bmax, reduce, alpha, size, scale, 0)
+
+
+def blobs(rng, n, d, k, sep=6.0, std=0.5):
+    c = rng.standard_normal((k, d)) * sep
+    lab = rng.integers(0, k, n)
+    return (c[lab] + std * rng.standard_normal((n, d))).astype(np.float32), c
+
+
+def dense_attention(Q, K, V, scale):
+    q, k, v = (torch.from_numpy(np.asarray(a, np.float64)) for a in (Q, K, V))
+    out = torch.nn.functional.scaled_dot_product_attention(q[None], k[None], v[None], scale=scale)[0]
+    lse = torch.logsumexp(scale * q @ k.T, dim=-1)
+    return out.numpy(), lse.numpy()
+
+
+# ---------------------------------------------------------------- k-means (Section 4.1, Eq. 3-4)
+
+def test_assignment_is_cdist_argmin():
+    rng = np.random.default_rng(1)
+    X = rng.standard_normal((1, 500, 16)).astype(np.float32)
+    init = rng.choice(500, 24, replace=False)[None].astype(np.int32)
+    o = Oracle(cfg(d=16, M0=24, maxc=24, maxt=500, iters=1))
+    J = o.build_index(X, X, init)
+    D = cdist(X[0].astype(np.float64), X[0][init[0]].astype(np.float64), "sqeuclidean")
+    np.testing.assert_array_equal(o.labels(0), D.argmin(1))
+    assert J[0, 0] == pytest.approx(D.min(1).sum(), rel=1e-12)
+
+
+def test_lloyd_matches_sklearn_and_objective_decreases():
+    from sklearn.cluster import KMeans
+    rng = np.random.default_rng(2)
+    X, _ = blobs(rng, 600, 8, 6)
+    init = rng.choice(600, 6, replace=False).astype(np.int32)
+    T = 5
+    o = Oracle(cfg(d=8, M0=6, maxc=6, maxt=600, iters=T))
+    J = o.build_index(X[None], X[None], init[None])
+    assert np.all(np.diff(J[0]) <= 1e-9 * J[0, 0])
+    Xd = X.astype(np.float64)
+    full = KMeans(6, init=Xd[init], n_init=1, algorithm="lloyd", max_iter=T, tol=0).fit(Xd)
+    prev = KMeans(6, init=Xd[init], n_init=1, algorithm="lloyd", max_iter=T - 1, tol=0).fit(Xd)
+    c = o.clusters(0)
+    assert c["n"].min() > 0
+    # centres after T updates; labels are those of the T-th assignment (= against the centres after T-1 updates)
+    np.testing.assert_allclose(c["centroids"], full.cluster_centers_, rtol=1e-6, atol=1e-6)
+    np.testing.assert_array_equal(o.labels(0), prev.labels_)
+
+
+def test_kmeans_closed_forms():
+    rng = np.random.default_rng(3)
+    X = rng.standard_normal((1, 200, 5)).astype(np.float32)
+    o = Oracle(cfg(d=5, M0=1, maxc=2, maxt=200, iters=2))
+    J = o.build_index(X, X, np.zeros((1, 1), np.int32))
+    Xd = X[0].astype(np.float64)
+    np.testing.assert_allclose(o.clusters(0)["centroids"][0], Xd.mean(0), rtol=1e-6, atol=1e-7)
+    assert J[0, 1] == pytest.approx(200 * np.trace(np.cov(Xd.T, bias=True)), rel=1e-6)
+    assert o.clusters(0)["M2"][0] == pytest.approx(J[0, 1], rel=1e-6)
+    # every point its own centre: objective 0, each cluster one member
+    o = Oracle(cfg(d=5, M0=200, maxc=200, maxt=200, iters=2))
+    J = o.build_index(X, X, np.arange(200, dtype=np.int32)[None])
+    assert J[0, 0] == 0.0 and J[0, 1] == 0.0
+    np.testing.assert_array_equal(o.labels(0), np.arange(200))
+
+
+def test_centroid_is_member_mean_and_variance_is_mean_sqdist():
+    s = CONFIGS["tiny"]
+    w = generate(s)
+    o = Oracle(OracleConfig(1, 4, 128, 32, 128, s.max_tokens, 10, 16, 0, 1.5, 0.0, 0.0, 0))
+    J = o.build_index(w["K0"], w["V0"], w["init_idx"])
+    assert np.all(np.diff(J[0]) <= 0)
+    c, (off, mem) = o.clusters(0), o.members(0)
+    X = w["K0"][0].astype(np.float64)
+    tot = 0.0
+    for j in range(32):
+        m = mem[off[j]:off[j + 1]]
+        assert len(m) == c["n"][j] and np.all(np.diff(m) > 0)
+        np.testing.assert_allclose(c["centroids"][j], X[m].mean(0), rtol=2e-7, atol=1e-7)       # Eq. 4
+        ss = ((X[m] - c["centroids"][j].astype(np.float64)) ** 2).sum()
+        assert c["M2"][j] == pytest.approx(ss, rel=1e-12)
+        tot += ss
+    assert o.tau(0) == pytest.approx(1.5 * tot / 2048, rel=1e-12)
+    assert sorted(mem.tolist()) == list(range(2048))                                          # Eq. 3
+
+
+def test_empty_cluster_is_reseeded_with_the_farthest_point():
+    # two coincident initial centres: the second gets no point in iteration 1 and must take the farthest one
+    X = np.array([[0, 0], [0, 0], [1, 0], [0, 1], [50, 50]], np.float32)[None]
+    o = Oracle(cfg(M0=2, iters=3, maxt=5))
+    J = o.build_index(X, X, np.array([[0, 1]], np.int32))
+    assert np.all(np.diff(J[0]) <= 0)
+    np.testing.assert_array_equal(o.labels(0), [0, 0, 0, 0, 1])
+    np.testing.assert_allclose(o.clusters(0)["centroids"], [[0.25, 0.25], [50, 50]])
+
+
+def test_seeded_init_is_deterministic_and_gives_a_partition():
+    rng = np.random.default_rng(4)
+    X = rng.standard_normal((2, 300, 4)).astype(np.float32)
+    a, b = Oracle(cfg(U=2, d=4, M0=7, maxc=7, maxt=300)), Oracle(cfg(U=2, d=4, M0=7, maxc=7, maxt=300))
+    a.build_index(X, X)
+    b.build_index(X, X)
+    for u in range(2):
+        np.testing.assert_array_equal(a.labels(u), b.labels(u))
+        assert sorted(a.members(u)[1].tolist()) == list(range(300))
+
+
+# ---------------------------------------------------------------- hand examples
+
+def _example1():
+    g = json.load(open(os.path.join(GOLD, "hand_example_1_retrieve.json")))
+    K = np.array(g["keys"], np.float32)[None]
+    V = np.array(g["values"], np.float32)[None]
+    return g, K, V
+
+
+def test_hand_example_1_build_select_attend():
+    g, K, V = _example1()
+    o = Oracle(cfg(maxt=16))
+    o.build_index(K, V, np.array([g["init_idx"]], np.int32))
+    c, (off, mem) = o.clusters(0), o.members(0)
+    for j, m in enumerate(g["clusters"]["members"]):
+        assert mem[off[j]:off[j + 1]].tolist() == m
+    np.testing.assert_allclose(c["centroids"], g["clusters"]["centroids"], rtol=0, atol=0)
+    assert c["n"].tolist() == g["clusters"]["n"]
+    np.testing.assert_allclose(c["M2"], g["clusters"]["M2"], rtol=1e-15)
+    np.testing.assert_allclose(c["M2"] / c["n"], g["clusters"]["variance"], rtol=1e-15)
+    q = np.array(g["query"], np.float32)[None, None]
+    out, lse = o.retrieve_attend(q, 2)
+    np.testing.assert_allclose(o.scores(0), g["scores"], rtol=1e-7)
+    assert o.selected(0).tolist() == g["budget_2"]["selected"]
+    assert o.gather(0).tolist() == g["budget_2"]["gather"]
+    np.testing.assert_allclose(out[0, 0], g["budget_2"]["out"], atol=1e-7)
+    out, lse = o.retrieve_attend(q, 6)
+    assert o.selected(0).tolist() == g["budget_6"]["selected"]
+    assert o.gather(0).tolist() == g["budget_6"]["gather"]
+    ref, rl = dense_attention(q[0], K[0], V[0], 1 / np.sqrt(2))
+    np.testing.assert_allclose(out[0], ref, rtol=1e-12)
+    np.testing.assert_allclose(lse[0], rl, rtol=1e-12)
+    # budget between the two sizes: the better cluster fits, the next does not, nothing is skipped or cut
+    out, _ = o.retrieve_attend(q, 5)
+    assert o.selected(0).tolist() == [1]
+
+
+def test_hand_example_2_updatevar_and_flag():
+    g1, K, V = _example1()
+    g = json.load(open(os.path.join(GOLD, "hand_example_2_updatevar.json")))
+    k = np.array([g["new_key"]], np.float32)
+    D = cdist(k.astype(np.float64), np.array(g1["clusters"]["centroids"]), "sqeuclidean")[0]
+    np.testing.assert_allclose(D, g["sqdist_to_centroids"])
+    pts = np.array(g1["keys"][:4] + [g["new_key"]], np.float64)
+    np.testing.assert_allclose(((pts - g["tentative"]["centroid"]) ** 2).sum(1), g["tentative"]["two_pass_sqdist"])
+    assert sum(g["tentative"]["two_pass_sqdist"]) == pytest.approx(g["tentative"]["M2"])
+
+    o = Oracle(cfg(maxt=16, alpha=g["var_alpha"]))
+    o.build_index(K, V, np.array([g1["init_idx"]], np.int32))
+    assert o.tau(0) == pytest.approx(g["tau"], rel=1e-15)
+    o.retrieve_attend(np.array([[[-1, -1]]], np.float32), 1)   # active set without cluster 0
+    o.append(k, k)
+    assert o.last_assign(0) == g["assigned"]
+    c, (off, mem) = o.clusters(0), o.members(0)
+    a = g["after"]
+    assert (c["flag"][0], c["b"][0], c["n"][0]) == (a["flag"], a["b"], a["n"])
+    np.testing.assert_array_equal(c["centroids"][0], np.array(a["centroid"], np.float32))
+    assert c["M2"][0] == a["M2"]
+    assert mem[off[0]:off[1]].tolist() == a["members"]
+    assert o.diagnostics(0)["margin_trigger"] == pytest.approx((0.8 - 0.75) / 1.0)
+    # a second entry of a flagged cluster only grows the buffer
+    o.append(np.array([[0.5, 0.5]], np.float32), k)
+    c = o.clusters(0)
+    assert (c["flag"][0], c["b"][0], c["n"][0]) == (1, 2, 4)
+
+    b = g["with_tau_above"]
+    o = Oracle(cfg(maxt=16, alpha=b["var_alpha"]))
+    o.build_index(K, V, np.array([g1["init_idx"]], np.int32))
+    o.append(k, k)
+    c = o.clusters(0)
+    assert (c["flag"][0], c["b"][0], c["n"][0]) == (b["flag"], b["b"], b["n"])
+    np.testing.assert_allclose(c["centroids"][0], b["centroid"], rtol=1e-7)
+    assert c["M2"][0] == pytest.approx(b["M2"], rel=1e-7)
+
+
+@pytest.mark.parametrize("bmax", [0, 16])
+def test_hand_example_3_split(bmax):
+    g = json.load(open(os.path.join(GOLD, "hand_example_3_split.json")))
+    K = np.array(g["keys"], np.float32)[None]
+    o = Oracle(cfg(maxt=16, alpha=1.5, bmax=bmax))
+    o.build_index(K, K, np.array([g["init_idx"]], np.int32))
+    k = np.array([g["new_key"]], np.float32)
+    o.retrieve_attend(np.array([[[1, 1]]], np.float32), 4)    # active set = {cluster 0}
+    assert o.selected(0).tolist() == [0]
+    o.append(k, k)
+    assert o.last_assign(0) == g["assigned"]
+    c = o.clusters(0)
+    assert (c["flag"][0], c["b"][0], c["n"][0]) == (1, 1, 4)
+    o.split()
+    assert o.num_clusters(0) == 3
+    c, (off, mem) = o.clusters(0), o.members(0)
+    for ch in (g["split"]["stay"], g["split"]["moved"]):
+        j = ch["id"]
+        assert mem[off[j]:off[j + 1]].tolist() == ch["members"]
+        np.testing.assert_array_equal(c["centroids"][j], np.array(ch["centroid"], np.float32))
+        assert (c["n"][j], c["b"][j], c["flag"][j]) == (ch["n"], 0, 0)
+        assert c["M2"][j] == pytest.approx(ch["M2"], abs=1e-15)
+    assert o.diagnostics(0)["splits"] == 1
+
+
+def test_delayed_split_waits_for_retrieval_and_forced_split_fires_at_bmax():
+    g = json.load(open(os.path.join(GOLD, "hand_example_3_split.json")))
+    K = np.array(g["keys"], np.float32)[None]
+    o = Oracle(cfg(maxt=32, alpha=1.5, bmax=3))
+    o.build_index(K, K, np.array([g["init_idx"]], np.int32))
+    far = np.array([[[-10, -11]]], np.float32)                 # retrieves cluster 1 only (budget 2)
+    k = np.array([g["new_key"]], np.float32)
+    for step in range(3):
+        o.retrieve_attend(far, 2)
+        assert o.selected(0).tolist() == [1]
+        o.append(k + step, k)
+        o.split()
+        c = o.clusters(0)
+        if step < 2:                                          # buffered, not split: cluster 0 is not resident
+            assert (c["flag"][0], c["b"][0], o.num_clusters(0)) == (1, step + 1, 2)
+            assert c["n"][0] == 4 and c["M2"][0] == 2.0
+    d = o.diagnostics(0)
+    assert (d["splits"], d["forced_splits"], o.num_clusters(0)) == (1, 1, 3)
+    off, mem = o.members(0)
+    assert mem[off[0]:off[1]].tolist() == [0, 1, 2, 3] and mem[off[2]:off[3]].tolist() == [6, 7, 8]
+    c = o.clusters(0)
+    assert c["flag"].sum() == 0 and c["b"].sum() == 0
+    # same inputs, but the flagged cluster is retrieved at step 2: the delayed split happens there
+    o = Oracle(cfg(maxt=32, alpha=1.5, bmax=16))
+    o.build_index(K, K, np.array([g["init_idx"]], np.int32))
+    o.retrieve_attend(far, 2); o.append(k, k); o.split()
+    assert o.num_clusters(0) == 2
+    o.retrieve_attend(np.array([[[1, 1]]], np.float32), 5); o.append(k + 1, k); o.split()
+    assert o.num_clusters(0) == 3 and o.diagnostics(0)["forced_splits"] == 0
+    off, mem = o.members(0)
+    assert mem[off[2]:off[3]].tolist() == [6, 7]
+
+
+def test_ties_go_to_the_lowest_index():
+    K = np.array([[0, 0], [2, 0], [0, 0.5], [2, 0.5]], np.float32)[None]
+    o = Oracle(cfg(M0=2, iters=1, maxt=8))
+    o.build_index(K, K, np.array([[0, 1]], np.int32))
+    np.testing.assert_allclose(o.clusters(0)["centroids"], [[0, 0.25], [2, 0.25]])
+    o.append(np.array([[1, 0.25]], np.float32), np.zeros((1, 2), np.float32))    # equidistant
+    assert o.last_assign(0) == 0
+    out, _ = o.retrieve_attend(np.array([[[0, 1]]], np.float32), 2)              # equal scores, budget for one
+    assert o.selected(0).tolist() == [0]
+
+
+# ---------------------------------------------------------------- decode properties on a realistic workload
+
+@pytest.fixture(scope="module")
+def tiny_run():
+    s = CONFIGS["tiny"].scaled(var_alpha=1.2)
+    w = generate(s)
+    o = Oracle(OracleConfig(1, 4, 128, 32, 128, s.max_tokens, 10, 4, 0, s.var_alpha, s.size_factor, 0.0, 0))
+    o.build_index(w["K0"], w["V0"], w["init_idx"])
+    return s, w, o
+
+
+def test_trajectory_invariants_and_split_partition(tiny_run):
+    s, w, o = tiny_run
+    allK = np.concatenate([w["K0"][0], w["Knew"][:, 0]]).astype(np.float64)
+    n_split_seen = 0
+    for t in range(s.steps):
+        o.retrieve_attend(w["Q"][t], s.budget)
+        sel, gat = o.selected(0), o.gather(0)
+        off, mem = o.members(0)
+        sizes = np.diff(off)
+        assert sizes[sel].sum() == len(gat) <= s.budget
+        sc = o.scores(0)
+        rest = np.setdiff1d(np.arange(len(sc)), sel)
+        assert len(rest) == 0 or sc[sel].min() >= sc[rest].max()             # a prefix of the score order
+        o.append(w["Knew"][t], w["Vnew"][t])
+        before = {j: mem[off[j]:off[j + 1]].tolist() for j in range(len(sizes))}
+        j = o.last_assign(0)
+        before[j] = before[j] + [s.prefill + t]
+        M_before = o.num_clusters(0)
+        o.split()
+        c, (off, mem) = o.clusters(0), o.members(0)
+        M = o.num_clusters(0)
+        assert sorted(mem.tolist()) == list(range(s.prefill + t + 1))          # every token in exactly one cluster
+        np.testing.assert_array_equal(np.diff(off), c["n"] + c["b"])
+        assert np.all((c["b"] > 0) == (c["flag"] > 0))
+        assert c["b"].sum() < 4 or M > M_before                               # buffers stay under B_max
+        for new in range(M_before, M):                                         # children partition the parent
+            parents = [p for p in before if set(mem[off[new]:off[new + 1]]) <= set(before[p])]
+            assert len(parents) == 1
+            p = parents[0]
+            kid, stay = mem[off[new]:off[new + 1]].tolist(), mem[off[p]:off[p + 1]].tolist()
+            assert sorted(kid + stay) == before[p] and kid == sorted(kid) and stay == sorted(stay)
+            assert stay[0] == before[p][0]
+            for jj in (p, new):                                               # exact statistics after a split
+                m = mem[off[jj]:off[jj + 1]]
+                np.testing.assert_allclose(c["centroids"][jj], allK[m].mean(0), rtol=2e-7, atol=1e-7)
+                ss = ((allK[m] - c["centroids"][jj].astype(np.float64)) ** 2).sum()
+                assert c["M2"][jj] == pytest.approx(ss, rel=1e-12, abs=1e-12)
+            n_split_seen += 1
+    assert n_split_seen == o.diagnostics(0)["splits"] > 0
+
+
+def test_updatevar_is_the_two_pass_variance():
+    s = CONFIGS["tiny"]
+    w = generate(s)
+    o = Oracle(OracleConfig(1, 4, 128, 32, 32, s.max_tokens, 10, 16, 0, 0.0, 0.0, 0.0, 0))   # no trigger at all
+    o.build_index(w["K0"], w["V0"], w["init_idx"])
+    for t in range(s.steps):
+        o.append(w["Knew"][t], w["Vnew"][t])
+    allK = np.concatenate([w["K0"][0], w["Knew"][:, 0]]).astype(np.float64)
+    c, (off, mem) = o.clusters(0), o.members(0)
+    assert c["flag"].sum() == 0 and c["n"].sum() == s.max_tokens
+    for j in range(32):
+        X = allK[mem[off[j]:off[j + 1]]]
+        np.testing.assert_allclose(c["centroids"][j], X.mean(0), rtol=1e-5, atol=1e-6)
+        assert c["M2"][j] == pytest.approx(((X - X.mean(0)) ** 2).sum(), rel=1e-6)
+
+
+def test_full_budget_is_dense_attention_and_order_does_not_matter(tiny_run):
+    s, w, _ = tiny_run
+    rng = np.random.default_rng(7)
+    K, V, Q = w["K0"][:, :512], w["V0"][:, :512], w["Q"][0]
+    init = rng.choice(512, 16, replace=False).astype(np.int32)[None]
+    o = Oracle(OracleConfig(1, 4, 128, 16, 16, 600, 4, 16, 0, 0.0, 0.0, 0.0, 0))
+    o.build_index(K, V, init)
+    out, lse = o.retrieve_attend(Q, 512)
+    assert len(o.selected(0)) == 16 and sorted(o.gather(0).tolist()) == list(range(512))
+    ref, rl = dense_attention(Q[0], K[0], V[0], 1 / np.sqrt(128))
+    np.testing.assert_allclose(out[0], ref, rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(lse[0], rl, rtol=1e-12)
+    # the same tokens in another order give the same attention; huge logits do not overflow
+    perm = rng.permutation(512)
+    o2 = Oracle(OracleConfig(1, 4, 128, 16, 16, 600, 4, 16, 0, 0.0, 0.0, 0.0, 0))
+    o2.build_index(K[:, perm], V[:, perm], init)
+    out2, _ = o2.retrieve_attend(Q, 512)
+    np.testing.assert_allclose(out2, out, rtol=1e-10, atol=1e-12)
+    out3, lse3 = o.retrieve_attend(Q * 300, 512)
+    assert np.isfinite(out3).all() and np.isfinite(lse3).all()
+    # a partial retrieval equals dense attention restricted to the gathered tokens
+    out4, lse4 = o.retrieve_attend(Q, 200)
+    g = o.gather(0)
+    assert 0 < len(g) <= 200
+    ref, rl = dense_attention(Q[0], K[0][g], V[0][g], 1 / np.sqrt(128))
+    np.testing.assert_allclose(out4[0], ref, rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(lse4[0], rl, rtol=1e-12)
+
+
+def test_scores_group_reduce_and_scale():
+    rng = np.random.default_rng(8)
+    X = rng.standard_normal((1, 64, 8)).astype(np.float32)
+    Q = rng.standard_normal((1, 3, 8)).astype(np.float32)
+    init = np.arange(5, dtype=np.int32)[None]
+    for red in (0, 1):
+        for scale in (0.0, 0.25):
+            o = Oracle(cfg(G=3, d=8, M0=5, maxc=5, maxt=64, iters=2, reduce=red, scale=scale))
+            o.build_index(X, X, init)
+            o.retrieve_attend(Q, 10)
+            S = Q[0].astype(np.float64) @ o.clusters(0)["centroids"].astype(np.float64).T
+            want = (S.max(0) if red == 0 else S.sum(0)) * (scale or 1 / np.sqrt(8))
+            np.testing.assert_allclose(o.scores(0), want, rtol=3e-7, atol=1e-7)
+
+
+def test_selection_is_the_longest_fitting_prefix_brute_force():
+    rng = np.random.default_rng(9)
+    for trial in range(40):
+        M = int(rng.integers(2, 8))
+        X, _ = blobs(rng, 60, 4, M)
+        init = rng.choice(60, M, replace=False).astype(np.int32)[None]
+        o = Oracle(cfg(G=2, d=4, M0=M, maxc=M, maxt=60, iters=3))
+        o.build_index(X[None], X[None], init)
+        Q = rng.standard_normal((1, 2, 4)).astype(np.float32)
+        sizes = o.clusters(0)["n"]
+        prev = -1
+        for B in range(1, 61, 3):
+            o.retrieve_attend(Q, B)
+            sc = o.scores(0)
+            order = sorted(range(M), key=lambda j: (-sc[j], j))
+            best = max(k for k in range(M + 1) if sizes[order[:k]].sum() <= B)   # try every prefix length
+            sel, g = o.selected(0).tolist(), o.gather(0)
+            if best == 0:
+                off, mem = o.members(0)
+                assert sel == order[:1] and g.tolist() == mem[off[sel[0]]:off[sel[0] + 1]][:B].tolist()
+            else:
+                assert sel == order[:best] and len(g) == sizes[sel].sum() <= B
+            assert len(g) >= prev or best == 0
+            prev = len(g)
+
+
+def test_full_budget_splits_every_flagged_cluster_at_once_and_keeps_every_token():
+    s = CONFIGS["tiny"].scaled(var_alpha=1.2)
+    w = generate(s)
+    runs = {}
+    for name, bmax, budget in (("all_resident", 0, 64), ("full_budget", 16, 10 ** 6)):
+        o = Oracle(OracleConfig(1, 4, 128, 32, 128, s.max_tokens, 10, bmax, 0, s.var_alpha, s.size_factor, 0.0, 0))
+        o.build_index(w["K0"], w["V0"], w["init_idx"])
+        for t in range(s.steps):
+            o.retrieve_attend(w["Q"][t], budget)
+            o.append(w["Knew"][t], w["Vnew"][t])
+            o.split()
+            assert o.clusters(0)["flag"].sum() == 0
+        runs[name] = o
+    a, b = runs["all_resident"], runs["full_budget"]
+    assert a.num_clusters(0) == b.num_clusters(0) > 32
+    np.testing.assert_array_equal(a.labels(0), b.labels(0))
+
+
+def test_capacity_errors_leave_state_consistent():
+    g = json.load(open(os.path.join(GOLD, "hand_example_3_split.json")))
+    K = np.array(g["keys"], np.float32)[None]
+    o = Oracle(cfg(maxc=2, maxt=7, alpha=1.5, bmax=0))
+    o.build_index(K, K, np.array([g["init_idx"]], np.int32))
+    k = np.array([g["new_key"]], np.float32)
+    o.append(k, k); o.split()
+    assert o.num_clusters(0) == 2 and o.error(0) == 2 and o.clusters(0)["flag"][0] == 1
+    o.append(k, k)
+    assert o.num_tokens(0) == 7 and o.error(0) == 3
+    with pytest.raises(ValueError):
+        Oracle(cfg(maxt=4)).build_index(K, K, np.array([[0, 4]], np.int32))
