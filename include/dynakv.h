@@ -1,0 +1,162 @@
+/* dynakv.h - C ABI of the MI355X (gfx950) library for cluster-indexed sparse attention over an
+ * HBM-resident KVCache, following the adaptive KVCache management of the DynaKV paper
+ * (Section 4: problem formulation Eq. 1-5, Algorithm 1, Section 4.2; k-means and the
+ * overflow-safe attention over reordered KV of Section 7).
+ *
+ * One index holds U independent units (one per layer x sequence x KV head).  Per unit it keeps the
+ * partition of the KVCache into clusters (Eq. 3), one float32 centroid per cluster (Eq. 4), the
+ * per-cluster state of Algorithm 1 (size n_j, M2_j = n_j * variance, buffer count |Buf_j|, split
+ * flag f_j), the head-specific threshold tau, and the keys/values themselves in cluster-contiguous
+ * pages of 16 tokens.
+ *
+ * Conventions for every call
+ *   memory    - every pointer marked "device" is device memory owned by the caller (in practice a
+ *               torch tensor).  The library allocates no device memory and frees none; all of its
+ *               state lives in the caller's workspace, which must outlive the handle.  Pointers
+ *               marked "host" are ordinary host memory.
+ *   streams   - `stream` is a hipStream_t (null = default stream).  Work is enqueued there and the
+ *               call returns without waiting; inputs and outputs must stay valid until the stream
+ *               has passed the call.  One handle is driven from one stream at a time.
+ *   errors    - host-detectable misuse returns a status and enqueues nothing.  Conditions only
+ *               the device can see (token, cluster or page capacity exhausted) set a sticky
+ *               per-unit error word; the offending operation leaves the unit's state unchanged
+ *               (a split that has no room leaves its cluster flagged); dynakv_export_state
+ *               reports the word.
+ *   numerics  - decisions (nearest cluster, split trigger, 2-means sides, cluster order) are taken
+ *               on float64 values accumulated left to right over the coordinate index, so that
+ *               they can be reproduced exactly; cluster scores are rounded to float32 before they
+ *               are ordered; ties go to the lowest index.  Attention uses matrix cores with
+ *               float32 accumulation.
+ */
+#ifndef DYNAKV_H
+#define DYNAKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dynakv_index dynakv_index_t; /* opaque host-side handle */
+
+typedef enum {
+  DYNAKV_OK = 0,
+  DYNAKV_EINVAL = 1,    /* bad argument or unsupported size */
+  DYNAKV_ECAPACITY = 2, /* workspace too small */
+  DYNAKV_ESTATE = 3,    /* call out of order (decode call before dynakv_build_index) */
+  DYNAKV_EHIP = 4       /* a HIP runtime call failed */
+} dynakv_status_t;
+
+typedef enum { DYNAKV_F32 = 0, DYNAKV_F16 = 1, DYNAKV_BF16 = 2 } dynakv_dtype_t;
+typedef enum { DYNAKV_GROUP_MAX = 0, DYNAKV_GROUP_SUM = 1 } dynakv_group_reduce_t;
+
+/* bits of the per-unit device error word */
+#define DYNAKV_ERR_TOKENS 1   /* append refused: max_tokens or page pool exhausted            */
+#define DYNAKV_ERR_CLUSTERS 2 /* split refused: max_clusters reached (cluster stays flagged)   */
+#define DYNAKV_ERR_SPLIT_SIZE 4 /* split refused: cluster larger than the split kernel handles */
+
+typedef struct {
+  int32_t n_units;         /* U >= 1                                                            */
+  int32_t group_size;      /* G, query heads per KV head, 1..16                                 */
+  int32_t head_dim;        /* d; must be 128                                                    */
+  int32_t dtype;           /* dynakv_dtype_t of K, V and Q                                      */
+  int32_t n_clusters_init; /* M0, clusters built at prefill                                     */
+  int32_t max_clusters;    /* capacity per unit, splits included; M0..8192                      */
+  int32_t max_tokens;      /* capacity per unit                                                 */
+  int32_t kmeans_iters;    /* Lloyd iterations at prefill, >= 1, no early exit                  */
+  int32_t buffer_max;      /* B_max of Algorithm 1; 0 = every cluster counts as resident        */
+  int32_t group_reduce;    /* dynakv_group_reduce_t: how G head scores become one cluster score */
+  float var_alpha;         /* tau = var_alpha * (k-means objective / N0) per unit; <= 0: off    */
+  float size_factor;       /* also flag when n' > size_factor * (N+1)/M; <= 0: off              */
+  float softmax_scale;     /* 0 = 1/sqrt(head_dim)                                              */
+  int32_t reserved;        /* must be 0                                                         */
+} dynakv_config_t;
+
+/* Bytes of device workspace an index of this configuration needs (0 if the configuration is invalid). */
+size_t dynakv_workspace_bytes(const dynakv_config_t* cfg);
+
+/* Creates the host-side handle over `workspace` (device, `bytes` long, 256-byte aligned).  Nothing is
+ * enqueued; the workspace is initialised by dynakv_build_index.  EINVAL / ECAPACITY on bad input. */
+dynakv_status_t dynakv_create(const dynakv_config_t* cfg, void* workspace, size_t bytes, dynakv_index_t** out);
+
+/* Frees the host-side handle only. */
+dynakv_status_t dynakv_destroy(dynakv_index_t* index);
+
+/* Prefill (Algorithm 1, prefill block; Section 4.1 Eq. 3-4): Lloyd's k-means of each unit's keys into M0
+ * clusters, then n_j, r_j, M2_j, tau, empty buffers and flags, and the cluster-contiguous page layout.
+ *   K, V      device, [U][n_tokens][head_dim] in cfg.dtype, contiguous; read only
+ *   n_tokens  M0 <= n_tokens <= min(max_tokens, 16384)
+ *   init_idx  device, int32 [U][M0]: positions of the M0 distinct keys used as initial centres
+ * Empty clusters are re-seeded with the points farthest from their centres in every iteration but the
+ * last.  Resets any earlier state of the index. */
+dynakv_status_t dynakv_build_index(dynakv_index_t* index, const void* K, const void* V, int32_t n_tokens,
+                                   const int32_t* init_idx, void* stream);
+
+/* One retrieval (Algorithm 1 "load top-k clusters by query-centroid similarity"; Section 4.1) followed by
+ * softmax attention over the retrieved entries (Section 7, attention over reordered KV):
+ * score_j = float32(scale * reduce_g <q_g, r_j>); clusters are taken in (score desc, id asc) order while
+ * their stored sizes n_j + |Buf_j| fit in `token_budget`, stopping at the first that does not fit; if
+ * even the best cluster does not fit, its first `token_budget` entries are taken.  The selected set
+ * becomes the active set P_req that dynakv_split consults.
+ *   Q     device, [U][G][head_dim] in cfg.dtype
+ *   out   device, float32 [U][G][head_dim]: softmax(scale * q K_sel^T) V_sel; zeros if nothing is selected
+ *   lse   device, float32 [U][G] or null: log-sum-exp of the scaled logits (-inf if nothing is selected)
+ * The new token of the step is not part of the index yet; merge it through `lse` if needed. */
+dynakv_status_t dynakv_retrieve_attend(dynakv_index_t* index, const void* Q, int32_t token_budget, float* out,
+                                       float* lse, void* stream);
+
+/* Adds one entry per unit (Algorithm 1: assign to the nearest cluster, UpdateVar, threshold test, then
+ * AddEntry + UpdateStats or buffer + flag; Section 4.2).  The entry is always stored at the tail of its
+ * cluster's pages; a cluster whose tentative variance exceeds tau (or whose tentative size exceeds the
+ * size trigger) is flagged and keeps its statistics frozen, later entries of a flagged cluster count as
+ * buffered.
+ *   k_new, v_new  device, [U][head_dim] in cfg.dtype */
+dynakv_status_t dynakv_append(dynakv_index_t* index, const void* k_new, const void* v_new, void* stream);
+
+/* Algorithm 1, "delayed cluster splitting": splits every flagged cluster that the last retrieval selected
+ * (all flagged clusters if buffer_max = 0), in ascending id; then, if the buffers together hold at least
+ * buffer_max entries, also the flagged cluster with the most buffered entries.  A split is a 2-means of
+ * the cluster's keys (seeds: the member farthest from the mean, then the member farthest from that one;
+ * at most 16 Lloyd rounds); the child holding the earliest entry keeps the id, the other takes the next
+ * free id; both get exact statistics.  A cluster that cannot be split (fewer than 2 entries, or all
+ * equal) is unflagged with exact statistics. */
+dynakv_status_t dynakv_split(dynakv_index_t* index, void* stream);
+
+/* Snapshot for tests and debugging.  Every field is a device pointer or null (null = skip). */
+typedef struct {
+  int32_t* n_clusters;   /* [U]                 M_t                                              */
+  int32_t* n_tokens;     /* [U]                 N_t                                              */
+  int32_t* error;        /* [U]                 DYNAKV_ERR_* bits                                */
+  double* tau;           /* [U]                                                                  */
+  float* centroids;      /* [U][max_clusters][head_dim]                                          */
+  int32_t* size;         /* [U][max_clusters]   n_j                                              */
+  int32_t* buffered;     /* [U][max_clusters]   |Buf_j|                                          */
+  int32_t* flag;         /* [U][max_clusters]   f_j                                              */
+  double* m2;            /* [U][max_clusters]   M2_j                                             */
+  int32_t* offsets;      /* [U][max_clusters+1] members of cluster j: members[offsets[j]..offsets[j+1]) */
+  int32_t* members;      /* [U][max_tokens]     token positions in storage order                 */
+  float* scores;         /* [U][max_clusters]   scores of the last retrieval                     */
+  int32_t* n_selected;   /* [U]                 clusters selected by the last retrieval          */
+  int32_t* selected;     /* [U][max_clusters]   their ids in score order                         */
+  int32_t* n_gathered;   /* [U]                 entries attended by the last retrieval           */
+  int32_t* gathered;     /* [U][max_tokens]     their token positions in gather order            */
+  int32_t* last_assign;  /* [U]                 cluster chosen by the last append                */
+  int64_t* counters;     /* [U][4]              splits, failed splits, forced splits, pages in use */
+} dynakv_state_t;
+
+/* Copies the requested parts of the state (enqueued on `stream`; the caller synchronises before reading). */
+dynakv_status_t dynakv_export_state(dynakv_index_t* index, const dynakv_state_t* dst, void* stream);
+
+/* Timing aid: when enabled, the dominant kernel of dynakv_retrieve_attend (gather + attention) is bracketed
+ * by HIP events on its own stream.  dynakv_profile_read synchronises those events and returns the number of
+ * launches and their summed duration in milliseconds since the last enable. */
+dynakv_status_t dynakv_profile_enable(dynakv_index_t* index, int32_t max_launches);
+dynakv_status_t dynakv_profile_read(dynakv_index_t* index, int32_t* n_launches, double* total_ms);
+
+const char* dynakv_strerror(dynakv_status_t status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DYNAKV_H */

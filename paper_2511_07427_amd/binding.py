@@ -1,0 +1,180 @@
+"""Thin ctypes binding of libdynakv.so: same names as the C ABI, argument marshalling only.
+
+torch owns device memory and streams; every step of the path runs in the library's kernels.  There is
+no fallback: if the library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdynakv.so")
+
+DTYPES = {"f32": 0, "f16": 1, "bf16": 2}
+TORCH_DTYPES = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+ERR_TOKENS, ERR_CLUSTERS, ERR_SPLIT_SIZE = 1, 2, 4
+
+
+class _Cfg(C.Structure):
+    _fields_ = [(k, C.c_int32) for k in ("n_units", "group_size", "head_dim", "dtype", "n_clusters_init",
+                                          "max_clusters", "max_tokens", "kmeans_iters", "buffer_max",
+                                          "group_reduce")] + \
+               [(k, C.c_float) for k in ("var_alpha", "size_factor", "softmax_scale")] + [("reserved", C.c_int32)]
+
+
+_STATE_FIELDS = ("n_clusters", "n_tokens", "error", "tau", "centroids", "size", "buffered", "flag", "m2", "offsets",
+                 "members", "scores", "n_selected", "selected", "n_gathered", "gathered", "last_assign", "counters")
+
+
+class _State(C.Structure):
+    _fields_ = [(k, C.c_void_p) for k in _STATE_FIELDS]
+
+
+@dataclass
+class Config:
+    n_units: int
+    group_size: int
+    dtype: str
+    n_clusters_init: int
+    max_clusters: int
+    max_tokens: int
+    kmeans_iters: int = 10
+    buffer_max: int = 16
+    group_reduce: int = 0
+    var_alpha: float = 0.0
+    size_factor: float = 0.0
+    softmax_scale: float = 0.0
+    head_dim: int = 128
+
+
+_lib = None
+
+
+def load():
+    """Loads the built library; raises if it is missing (build it with paper_2511_07427_amd/build.py)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libdynakv.so is not built: run `python paper_2511_07427_amd/build.py`")
+        lib = C.CDLL(LIB_PATH)
+        vp, i32 = C.c_void_p, C.c_int32
+        lib.dynakv_workspace_bytes.restype = C.c_size_t
+        lib.dynakv_workspace_bytes.argtypes = [C.POINTER(_Cfg)]
+        lib.dynakv_create.argtypes = [C.POINTER(_Cfg), vp, C.c_size_t, C.POINTER(vp)]
+        lib.dynakv_destroy.argtypes = [vp]
+        lib.dynakv_build_index.argtypes = [vp, vp, vp, i32, vp, vp]
+        lib.dynakv_retrieve_attend.argtypes = [vp, vp, i32, vp, vp, vp]
+        lib.dynakv_append.argtypes = [vp, vp, vp, vp]
+        lib.dynakv_split.argtypes = [vp, vp]
+        lib.dynakv_export_state.argtypes = [vp, C.POINTER(_State), vp]
+        lib.dynakv_profile_enable.argtypes = [vp, i32]
+        lib.dynakv_profile_read.argtypes = [vp, C.POINTER(i32), C.POINTER(C.c_double)]
+        lib.dynakv_strerror.restype = C.c_char_p
+        lib.dynakv_strerror.argtypes = [C.c_int]
+        _lib = lib
+    return _lib
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise RuntimeError("%s: %s" % (what, load().dynakv_strerror(rc).decode()))
+
+
+def _cfg(cfg: Config) -> _Cfg:
+    return _Cfg(cfg.n_units, cfg.group_size, cfg.head_dim, DTYPES[cfg.dtype], cfg.n_clusters_init, cfg.max_clusters,
+                cfg.max_tokens, cfg.kmeans_iters, cfg.buffer_max, cfg.group_reduce, cfg.var_alpha, cfg.size_factor,
+                cfg.softmax_scale, 0)
+
+
+def dynakv_workspace_bytes(cfg: Config) -> int:
+    return load().dynakv_workspace_bytes(C.byref(_cfg(cfg)))
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dev(t: torch.Tensor, dtype, shape=None) -> int:
+    assert t.is_cuda and t.is_contiguous() and t.dtype == dtype, (t.device, t.dtype, dtype)
+    if shape is not None:
+        assert tuple(t.shape) == tuple(shape), (tuple(t.shape), tuple(shape))
+    return t.data_ptr()
+
+
+class Index:
+    """One index (dynakv_index_t) over a workspace tensor it keeps alive.  Work goes to torch's current stream."""
+
+    def __init__(self, cfg: Config, device="cuda:0"):
+        self.cfg = cfg
+        self._lib = load()
+        self._c = _cfg(cfg)
+        nbytes = self._lib.dynakv_workspace_bytes(C.byref(self._c))
+        if nbytes == 0:
+            raise ValueError("dynakv: invalid configuration %r" % (cfg,))
+        self.device = torch.device(device)
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        h = C.c_void_p()
+        _check(self._lib.dynakv_create(C.byref(self._c), self.workspace.data_ptr(), nbytes, C.byref(h)), "dynakv_create")
+        self._h = h
+        self._tdtype = TORCH_DTYPES[cfg.dtype]
+
+    def __del__(self):
+        if getattr(self, "_h", None):
+            self._lib.dynakv_destroy(self._h)
+            self._h = None
+
+    # ---- the four calls ---------------------------------------------------------------------
+    def dynakv_build_index(self, K: torch.Tensor, V: torch.Tensor, init_idx: torch.Tensor):
+        c = self.cfg
+        n = K.shape[1]
+        kp = _dev(K, self._tdtype, (c.n_units, n, c.head_dim))
+        vp = _dev(V, self._tdtype, (c.n_units, n, c.head_dim))
+        ip = _dev(init_idx, torch.int32, (c.n_units, c.n_clusters_init))
+        _check(self._lib.dynakv_build_index(self._h, kp, vp, n, ip, _stream()), "dynakv_build_index")
+
+    def dynakv_retrieve_attend(self, Q: torch.Tensor, token_budget: int, out: torch.Tensor, lse: torch.Tensor | None):
+        c = self.cfg
+        qp = _dev(Q, self._tdtype, (c.n_units, c.group_size, c.head_dim))
+        op = _dev(out, torch.float32, (c.n_units, c.group_size, c.head_dim))
+        lp = _dev(lse, torch.float32, (c.n_units, c.group_size)) if lse is not None else None
+        _check(self._lib.dynakv_retrieve_attend(self._h, qp, int(token_budget), op, lp, _stream()),
+               "dynakv_retrieve_attend")
+
+    def dynakv_append(self, k_new: torch.Tensor, v_new: torch.Tensor):
+        c = self.cfg
+        kp = _dev(k_new, self._tdtype, (c.n_units, c.head_dim))
+        vp = _dev(v_new, self._tdtype, (c.n_units, c.head_dim))
+        _check(self._lib.dynakv_append(self._h, kp, vp, _stream()), "dynakv_append")
+
+    def dynakv_split(self):
+        _check(self._lib.dynakv_split(self._h, _stream()), "dynakv_split")
+
+    # ---- timing aid ---------------------------------------------------------------------------
+    def dynakv_profile_enable(self, max_launches: int):
+        _check(self._lib.dynakv_profile_enable(self._h, int(max_launches)), "dynakv_profile_enable")
+
+    def dynakv_profile_read(self):
+        n, ms = C.c_int32(), C.c_double()
+        _check(self._lib.dynakv_profile_read(self._h, C.byref(n), C.byref(ms)), "dynakv_profile_read")
+        return n.value, ms.value
+
+    # ---- snapshot -------------------------------------------------------------------------------
+    def dynakv_export_state(self, fields=_STATE_FIELDS):
+        """Returns the requested parts of the state as CPU tensors (synchronises the current stream)."""
+        c = self.cfg
+        U, M, N, d = c.n_units, c.max_clusters, c.max_tokens, c.head_dim
+        i32, f32, f64, i64 = torch.int32, torch.float32, torch.float64, torch.int64
+        spec = dict(n_clusters=((U,), i32), n_tokens=((U,), i32), error=((U,), i32), tau=((U,), f64),
+                    centroids=((U, M, d), f32), size=((U, M), i32), buffered=((U, M), i32), flag=((U, M), i32),
+                    m2=((U, M), f64), offsets=((U, M + 1), i32), members=((U, N), i32), scores=((U, M), f32),
+                    n_selected=((U,), i32), selected=((U, M), i32), n_gathered=((U,), i32), gathered=((U, N), i32),
+                    last_assign=((U,), i32), counters=((U, 4), i64))
+        bufs = {k: torch.zeros(spec[k][0], dtype=spec[k][1], device=self.device) for k in fields}
+        st = _State(**{k: (bufs[k].data_ptr() if k in bufs else None) for k in _STATE_FIELDS})
+        _check(self._lib.dynakv_export_state(self._h, C.byref(st), _stream()), "dynakv_export_state")
+        torch.cuda.current_stream().synchronize()
+        return {k: v.cpu() for k, v in bufs.items()}

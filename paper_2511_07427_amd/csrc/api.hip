@@ -1,0 +1,201 @@
+// Host side of the C ABI declared in include/dynakv.h: argument checks, the carving of the caller's
+// workspace into the arrays of `View`, and the kernel launches of every call.
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "common.hpp"
+
+using namespace dynakv;
+
+struct dynakv_index {
+  dynakv_config_t cfg;
+  View view;
+  void* workspace;
+  size_t bytes;
+  bool built;
+  // optional timing of the gather + attention kernel
+  bool profiling;
+  std::vector<hipEvent_t> ev;   // start/stop pairs
+  int n_prof;
+};
+
+namespace {
+
+bool config_ok(const dynakv_config_t* c) {
+  if (!c) return false;
+  if (c->n_units < 1 || c->group_size < 1 || c->group_size > 16 || c->head_dim != kHeadDim) return false;
+  if (c->dtype != DYNAKV_F32 && c->dtype != DYNAKV_F16 && c->dtype != DYNAKV_BF16) return false;
+  if (c->n_clusters_init < 1 || c->max_clusters < c->n_clusters_init || c->max_clusters > kMaxClusters) return false;
+  if (c->max_tokens < c->n_clusters_init || c->max_tokens > (1 << 24)) return false;
+  if (c->kmeans_iters < 1 || c->buffer_max < 0) return false;
+  if (c->group_reduce != DYNAKV_GROUP_MAX && c->group_reduce != DYNAKV_GROUP_SUM) return false;
+  if (c->softmax_scale < 0.f || c->reserved != 0) return false;
+  return true;
+}
+
+int kv_splits(int U) {
+  int S = (1024 + U - 1) / U;
+  if (const char* e = std::getenv("DYNAKV_KV_SPLITS")) S = std::atoi(e);
+  return S < 1 ? 1 : (S > kMaxKvSplits ? kMaxKvSplits : S);
+}
+
+// Pages per unit: every token, one partly filled page per cluster, and room for a split to write both
+// children before the parent's pages are recycled.
+int pages_per_unit(const dynakv_config_t& c) {
+  return (c.max_tokens + kPageTokens - 1) / kPageTokens + c.max_clusters + kMaxSplitMembers / kPageTokens + 2;
+}
+
+// Lays the arrays of `View` out in a workspace starting at `base` (may be null: size only).
+size_t carve(const dynakv_config_t& c, char* base, View* out) {
+  View v;
+  std::memset(&v, 0, sizeof(v));
+  v.U = c.n_units; v.G = c.group_size; v.dtype = c.dtype; v.M0 = c.n_clusters_init; v.Mcap = c.max_clusters;
+  v.Ncap = c.max_tokens; v.Pcap = pages_per_unit(c); v.Bmax = c.buffer_max; v.group_reduce = c.group_reduce;
+  v.S = kv_splits(c.n_units);
+  v.var_alpha = c.var_alpha; v.size_factor = c.size_factor;
+  v.scale_d = c.softmax_scale > 0.f ? (double)c.softmax_scale : 1.0 / std::sqrt((double)c.head_dim);
+  v.scale_f = (float)v.scale_d;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    char* p = base ? base + off : nullptr;
+    off += (bytes + 255) & ~(size_t)255;
+    return p;
+  };
+  const size_t U = v.U, UM = U * v.Mcap, UP = U * v.Pcap, UN = U * v.Ncap;
+  v.M = (int*)take(U * 4); v.N = (int*)take(U * 4); v.err = (int*)take(U * 4); v.tau = (double*)take(U * 8);
+  v.nflag = (int*)take(U * 4); v.n_sel = (int*)take(U * 4); v.t_sel = (int*)take(U * 4); v.n_list = (int*)take(U * 4);
+  v.ticket = (int*)take(U * 4); v.bump = (int*)take(U * 4); v.free_top = (int*)take(U * 4);
+  v.last_assign = (int*)take(U * 4); v.counters = (long long*)take(U * 4 * 8);
+  v.R = (float*)take(UM * kHeadDim * 4);
+  v.cn = (int*)take(UM * 4); v.cb = (int*)take(UM * 4); v.cflag = (int*)take(UM * 4); v.cM2 = (double*)take(UM * 8);
+  v.chead = (int*)take(UM * 4); v.ctail = (int*)take(UM * 4); v.score = (float*)take(UM * 4);
+  v.sel_ids = (int*)take(UM * 4); v.in_req = (unsigned char*)take(UM); v.tok_off = (int*)take(UM * 4);
+  v.pg_off = (int*)take(UM * 4);
+  v.pages = take(UP * (size_t)kPageElems * elem_size(c.dtype));
+  v.ppos = (int*)take(UP * kPageTokens * 4); v.pnext = (int*)take(UP * 4); v.freelist = (int*)take(UP * 4);
+  v.plist = (int*)take(UP * 4); v.plist_off = (int*)take(UP * 4);
+  v.part = (float*)take(U * v.S * v.G * (kHeadDim + 2) * 4);
+  v.labels = (int*)take(UN * 4); v.order = (int*)take(UN * 4); v.dist = (double*)take(UN * 8);
+  v.koff = (int*)take(U * (v.Mcap + 1) * 4);
+  if (out) *out = v;
+  return off;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t dynakv_workspace_bytes(const dynakv_config_t* cfg) {
+  if (!config_ok(cfg)) return 0;
+  return carve(*cfg, nullptr, nullptr);
+}
+
+dynakv_status_t dynakv_create(const dynakv_config_t* cfg, void* workspace, size_t bytes, dynakv_index_t** out) {
+  if (!out) return DYNAKV_EINVAL;
+  *out = nullptr;
+  if (!config_ok(cfg) || !workspace || ((uintptr_t)workspace & 255)) return DYNAKV_EINVAL;
+  if (bytes < carve(*cfg, nullptr, nullptr)) return DYNAKV_ECAPACITY;
+  dynakv_index* ix = new (std::nothrow) dynakv_index();
+  if (!ix) return DYNAKV_EINVAL;
+  ix->cfg = *cfg;
+  ix->workspace = workspace;
+  ix->bytes = carve(*cfg, (char*)workspace, &ix->view);
+  ix->built = false;
+  ix->profiling = false;
+  ix->n_prof = 0;
+  *out = ix;
+  return DYNAKV_OK;
+}
+
+dynakv_status_t dynakv_destroy(dynakv_index_t* ix) {
+  if (!ix) return DYNAKV_EINVAL;
+  for (hipEvent_t e : ix->ev) (void)hipEventDestroy(e);
+  delete ix;
+  return DYNAKV_OK;
+}
+
+dynakv_status_t dynakv_build_index(dynakv_index_t* ix, const void* K, const void* V, int32_t n_tokens,
+                                   const int32_t* init_idx, void* stream) {
+  if (!ix || !K || !V || !init_idx) return DYNAKV_EINVAL;
+  if (n_tokens < ix->cfg.n_clusters_init || n_tokens > ix->cfg.max_tokens || n_tokens > kMaxPrefill) return DYNAKV_EINVAL;
+  const hipError_t e = launch_build_index(ix->view, K, V, n_tokens, init_idx, ix->cfg.kmeans_iters, ix->workspace,
+                                          ix->bytes, (hipStream_t)stream);
+  if (e != hipSuccess) return DYNAKV_EHIP;
+  ix->built = true;
+  return DYNAKV_OK;
+}
+
+dynakv_status_t dynakv_retrieve_attend(dynakv_index_t* ix, const void* Q, int32_t token_budget, float* out, float* lse,
+                                       void* stream) {
+  if (!ix || !Q || !out || token_budget < 0) return DYNAKV_EINVAL;
+  if (!ix->built) return DYNAKV_ESTATE;
+  hipStream_t st = (hipStream_t)stream;
+  if (launch_score_select(ix->view, Q, token_budget, st) != hipSuccess) return DYNAKV_EHIP;
+  const bool prof = ix->profiling && 2 * (ix->n_prof + 1) <= (int)ix->ev.size();
+  if (prof && hipEventRecord(ix->ev[2 * ix->n_prof], st) != hipSuccess) return DYNAKV_EHIP;
+  if (launch_gather_attend(ix->view, Q, out, lse, st) != hipSuccess) return DYNAKV_EHIP;
+  if (prof) {
+    if (hipEventRecord(ix->ev[2 * ix->n_prof + 1], st) != hipSuccess) return DYNAKV_EHIP;
+    ++ix->n_prof;
+  }
+  return DYNAKV_OK;
+}
+
+dynakv_status_t dynakv_append(dynakv_index_t* ix, const void* k_new, const void* v_new, void* stream) {
+  if (!ix || !k_new || !v_new) return DYNAKV_EINVAL;
+  if (!ix->built) return DYNAKV_ESTATE;
+  return launch_append(ix->view, k_new, v_new, (hipStream_t)stream) == hipSuccess ? DYNAKV_OK : DYNAKV_EHIP;
+}
+
+dynakv_status_t dynakv_split(dynakv_index_t* ix, void* stream) {
+  if (!ix) return DYNAKV_EINVAL;
+  if (!ix->built) return DYNAKV_ESTATE;
+  return launch_split(ix->view, (hipStream_t)stream) == hipSuccess ? DYNAKV_OK : DYNAKV_EHIP;
+}
+
+dynakv_status_t dynakv_export_state(dynakv_index_t* ix, const dynakv_state_t* dst, void* stream) {
+  if (!ix || !dst) return DYNAKV_EINVAL;
+  if (!ix->built) return DYNAKV_ESTATE;
+  return launch_export(ix->view, *dst, (hipStream_t)stream) == hipSuccess ? DYNAKV_OK : DYNAKV_EHIP;
+}
+
+dynakv_status_t dynakv_profile_enable(dynakv_index_t* ix, int32_t max_launches) {
+  if (!ix || max_launches < 0 || max_launches > (1 << 20)) return DYNAKV_EINVAL;
+  while ((int)ix->ev.size() < 2 * max_launches) {
+    hipEvent_t e;
+    if (hipEventCreate(&e) != hipSuccess) return DYNAKV_EHIP;
+    ix->ev.push_back(e);
+  }
+  ix->profiling = max_launches > 0;
+  ix->n_prof = 0;
+  return DYNAKV_OK;
+}
+
+dynakv_status_t dynakv_profile_read(dynakv_index_t* ix, int32_t* n_launches, double* total_ms) {
+  if (!ix || !n_launches || !total_ms) return DYNAKV_EINVAL;
+  double tot = 0.0;
+  for (int i = 0; i < ix->n_prof; ++i) {
+    if (hipEventSynchronize(ix->ev[2 * i + 1]) != hipSuccess) return DYNAKV_EHIP;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, ix->ev[2 * i], ix->ev[2 * i + 1]) != hipSuccess) return DYNAKV_EHIP;
+    tot += ms;
+  }
+  *n_launches = ix->n_prof;
+  *total_ms = tot;
+  return DYNAKV_OK;
+}
+
+const char* dynakv_strerror(dynakv_status_t s) {
+  switch (s) {
+    case DYNAKV_OK: return "ok";
+    case DYNAKV_EINVAL: return "invalid argument or unsupported size";
+    case DYNAKV_ECAPACITY: return "workspace too small";
+    case DYNAKV_ESTATE: return "call out of order: build the index first";
+    case DYNAKV_EHIP: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+}  // extern "C"

@@ -1,0 +1,185 @@
+// Shared declarations of the gfx950 library: the device-side view of an index, the page layout,
+// and small block-level helpers.  Everything here is for the HIP path only.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/dynakv.h"
+
+namespace dynakv {
+
+constexpr int kHeadDim = 128;
+constexpr int kPageTokens = 16;                 // tokens per page = one MFMA tile of rows
+constexpr int kPageElems = 2 * kPageTokens * kHeadDim;  // K region then V region
+constexpr int kMaxClusters = 8192;              // selection sorts one unit's clusters in LDS
+constexpr int kMaxPrefill = 16384;              // k-means sorts one unit's labels in LDS
+constexpr int kMaxSplitMembers = 8192;          // largest cluster the split kernel handles
+constexpr int kMaxKvSplits = 64;                // workgroups that share one unit's gathered pages
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+// Device-side view of one index.  All arrays live in the caller's workspace.
+struct View {
+  // configuration
+  int U, G, dtype, M0, Mcap, Ncap, Pcap, Bmax, group_reduce, S;
+  float var_alpha, size_factor, scale_f;
+  double scale_d;
+  // per unit
+  int* M;            // [U] clusters in use
+  int* N;            // [U] tokens stored
+  int* err;          // [U] sticky DYNAKV_ERR_* bits
+  double* tau;       // [U] split threshold on the variance
+  int* nflag;        // [U] clusters currently flagged
+  int* n_sel;        // [U] clusters selected by the last retrieval
+  int* t_sel;        // [U] entries gathered by the last retrieval
+  int* n_list;       // [U] pages in the gather list
+  int* ticket;       // [U] arrival counter of the split-KV workgroups
+  int* bump;         // [U] pages handed out from the pool so far
+  int* free_top;     // [U] entries on the free-page stack
+  int* last_assign;  // [U]
+  long long* counters;  // [U][4] splits, failed, forced, (unused)
+  // per cluster [U][Mcap]
+  float* R;          // [U][Mcap][128] centroids
+  int* cn;           // committed size n_j
+  int* cb;           // buffered entries |Buf_j|
+  int* cflag;        // f_j
+  double* cM2;       // M2_j
+  int* chead;        // first page (-1: none)
+  int* ctail;        // last page
+  float* score;      // last scores
+  int* sel_ids;      // ids in score order
+  unsigned char* in_req;  // membership in the last active set
+  int* tok_off;      // scratch: exclusive prefix of sizes in score order
+  int* pg_off;       // scratch: exclusive prefix of page counts in score order
+  // pages [U][Pcap]
+  char* pages;       // [U][Pcap][kPageElems * elem size]
+  int* ppos;         // [U][Pcap][16] token position of every slot
+  int* pnext;        // [U][Pcap] next page of the same cluster (-1: last)
+  int* freelist;     // [U][Pcap] stack of recycled pages
+  int* plist;        // [U][Pcap] gather list: page * 32 + valid tokens
+  int* plist_off;    // [U][Pcap] gather offset of the page's first token
+  // split-KV partial results
+  float* part;       // [U][S][G][130]: 128 accumulators, running max (log2 domain), denominator
+  // k-means / split scratch [U][Ncap]
+  int* labels;
+  int* order;        // positions sorted by (label, position)
+  double* dist;
+  int* koff;         // [U][Mcap+1] start of every cluster in `order`
+};
+
+__host__ __device__ inline int elem_size(int dtype) { return dtype == DYNAKV_F32 ? 4 : 2; }
+
+// ---- page layout -----------------------------------------------------------------------------
+// A page stores 16 tokens in the register order of the matrix instructions that consume it, so
+// that one wavefront load of 16 bytes per lane is fully contiguous.
+//   16-bit types: K region [4 k-steps][64 lanes][8]: lane = (d%32)/8*16 + slot holds dims 32*ks + 8*(lane/16) + e
+//                 V region [4][64 lanes][2][4]:      lane = slot/4*16 + d%16 holds tokens 4*(lane/16) + i of
+//                                                    columns 16*(2*c + h) + lane%16
+//   float32:      K region [8][64 lanes][4]:         dims 16*s + 4*(lane/16) + i
+//                 V region [8][64 lanes][4]:         tokens 4*(lane/16) + kk of column 16*cb + lane%16
+// Offsets are in elements from the start of the page; the V region starts at 2048.
+__host__ __device__ inline int k_index16(int slot, int d) {
+  return (d >> 5) * 512 + ((((d & 31) >> 3) << 4) + slot) * 8 + (d & 7);
+}
+__host__ __device__ inline int v_index16(int slot, int d) {
+  const int cb = d >> 4;
+  return 2048 + (cb >> 1) * 512 + (((slot >> 2) << 4) + (d & 15)) * 8 + (cb & 1) * 4 + (slot & 3);
+}
+__host__ __device__ inline int k_index32(int slot, int d) {
+  return (d >> 4) * 256 + ((((d & 15) >> 2) << 4) + slot) * 4 + (d & 3);
+}
+__host__ __device__ inline int v_index32(int slot, int d) {
+  return 2048 + (d >> 4) * 256 + (((slot >> 2) << 4) + (d & 15)) * 4 + (slot & 3);
+}
+__host__ __device__ inline int k_index(int dtype, int slot, int d) {
+  return dtype == DYNAKV_F32 ? k_index32(slot, d) : k_index16(slot, d);
+}
+__host__ __device__ inline int v_index(int dtype, int slot, int d) {
+  return dtype == DYNAKV_F32 ? v_index32(slot, d) : v_index16(slot, d);
+}
+
+// ---- element access -----------------------------------------------------------------------------
+__device__ inline float bf16_to_float(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+__device__ inline float f16_to_float(uint16_t h) { return (float)__builtin_bit_cast(_Float16, h); }
+
+// Element `i` of an array of the index's storage type, as float (exact).
+__device__ inline float load_elem(const void* base, size_t i, int dtype) {
+  if (dtype == DYNAKV_F32) return ((const float*)base)[i];
+  const uint16_t h = ((const uint16_t*)base)[i];
+  return dtype == DYNAKV_F16 ? f16_to_float(h) : bf16_to_float(h);
+}
+// Copies element `i` of `src` to element `j` of `dst` (same storage type, bits unchanged).
+__device__ inline void copy_elem(void* dst, size_t j, const void* src, size_t i, int dtype) {
+  if (dtype == DYNAKV_F32) ((uint32_t*)dst)[j] = ((const uint32_t*)src)[i];
+  else ((uint16_t*)dst)[j] = ((const uint16_t*)src)[i];
+}
+
+__device__ inline char* page_ptr(const View& v, int u, int page) {
+  return v.pages + ((size_t)u * v.Pcap + page) * ((size_t)kPageElems * elem_size(v.dtype));
+}
+// Key coordinate d of the token in `slot` of `page`, as float.
+__device__ inline float page_key(const View& v, int u, int page, int slot, int d) {
+  return load_elem(page_ptr(v, u, page), k_index(v.dtype, slot, d), v.dtype);
+}
+
+// ---- block helpers ------------------------------------------------------------------------------
+// Exclusive prefix sum over the threads of a block (blockDim.x a multiple of 64, at most 1024).
+// `sm` needs 64 ints.  Returns the prefix of this thread; `total` receives the block sum.
+__device__ inline int block_excl_scan(int val, int* sm, int& total) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  int x = val;
+  for (int o = 1; o < 64; o <<= 1) {
+    const int y = __shfl_up(x, o);
+    if (lane >= o) x += y;
+  }
+  __syncthreads();
+  if (lane == 63) sm[w] = x;
+  __syncthreads();
+  if (w == 0) {
+    int t = lane < nw ? sm[lane] : 0;
+    for (int o = 1; o < 64; o <<= 1) {
+      const int y = __shfl_up(t, o);
+      if (lane >= o) t += y;
+    }
+    sm[lane] = t;
+  }
+  __syncthreads();
+  const int base = w ? sm[w - 1] : 0;
+  total = sm[nw - 1];
+  return base + x - val;
+}
+
+// Takes a page from the unit's free stack, else from the untouched tail of its pool; -1 if none is left.
+// One thread per unit calls this at a time.
+__device__ inline int alloc_page(const View& v, int u) {
+  int top = v.free_top[u];
+  if (top > 0) {
+    --top;
+    v.free_top[u] = top;
+    return v.freelist[(size_t)u * v.Pcap + top];
+  }
+  const int b = v.bump[u];
+  if (b < v.Pcap) {
+    v.bump[u] = b + 1;
+    return b;
+  }
+  return -1;
+}
+__device__ inline int pages_available(const View& v, int u) { return v.free_top[u] + (v.Pcap - v.bump[u]); }
+__device__ inline void free_page(const View& v, int u, int page) {
+  const int top = v.free_top[u];
+  v.freelist[(size_t)u * v.Pcap + top] = page;
+  v.free_top[u] = top + 1;
+}
+
+// ---- launchers (one per source file) ------------------------------------------------------------
+hipError_t launch_build_index(const View& v, const void* K, const void* V, int n_tokens, const int* init_idx,
+                              int iters, void* workspace, size_t workspace_bytes, hipStream_t st);
+hipError_t launch_score_select(const View& v, const void* Q, int budget, hipStream_t st);
+hipError_t launch_gather_attend(const View& v, const void* Q, float* out, float* lse, hipStream_t st);
+hipError_t launch_append(const View& v, const void* k, const void* val, hipStream_t st);
+hipError_t launch_split(const View& v, hipStream_t st);
+hipError_t launch_export(const View& v, const dynakv_state_t& dst, hipStream_t st);
+
+}  // namespace dynakv

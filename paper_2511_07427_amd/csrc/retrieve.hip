@@ -1,0 +1,404 @@
+// Decode, first half of a step (Algorithm 1 "load top-k clusters by query-centroid similarity";
+// Section 4.1; attention over the reordered entries, Section 7):
+//   score_kernel   - float64 inner products <q_g, r_j>, reduced over the query group, rounded to float32
+//   select_kernel  - order by (score desc, id asc), longest prefix under the token budget, gather list
+//   gather_attend  - streams the selected clusters' pages once; QK^T and PV on matrix cores with an
+//                    online (running-max) softmax, so any gather order is overflow-safe; split over
+//                    several workgroups per unit and merged by the last one to arrive.
+#include "common.hpp"
+
+namespace dynakv {
+
+namespace {
+
+// ------------------------------------------------------------------------------------------- scores
+template <int GP>
+__global__ __launch_bounds__(256) void score_kernel(View v, const void* Q) {
+  __shared__ double qs[kHeadDim][GP];
+  const int u = blockIdx.y, tid = threadIdx.x;
+  const int M = v.M[u];
+  if (blockIdx.x * 256 >= M) return;
+  for (int t = tid; t < GP * kHeadDim; t += 256) {
+    const int g = t / kHeadDim, d = t % kHeadDim;
+    qs[d][g] = g < v.G ? (double)load_elem(Q, ((size_t)u * v.G + g) * kHeadDim + d, v.dtype) : 0.0;
+  }
+  __syncthreads();
+  const int j = blockIdx.x * 256 + tid;
+  if (j >= M) return;
+  const f4* r = (const f4*)(v.R + ((size_t)u * v.Mcap + j) * kHeadDim);
+  double acc[GP];
+#pragma unroll
+  for (int g = 0; g < GP; ++g) acc[g] = 0.0;
+#pragma unroll 2
+  for (int d4 = 0; d4 < kHeadDim / 4; ++d4) {
+    const f4 rv = r[d4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const double rd = (double)rv[e];
+#pragma unroll
+      for (int g = 0; g < GP; ++g) acc[g] = fma(qs[d4 * 4 + e][g], rd, acc[g]);
+    }
+  }
+  double red = acc[0];
+#pragma unroll
+  for (int g = 1; g < GP; ++g)
+    if (g < v.G) red = v.group_reduce == DYNAKV_GROUP_MAX ? fmax(red, acc[g]) : red + acc[g];
+  v.score[(size_t)u * v.Mcap + j] = (float)(red * v.scale_d);
+}
+
+// ------------------------------------------------------------------------------------------- selection
+__device__ inline uint32_t orderable(float f) {
+  const uint32_t b = __float_as_uint(f);
+  return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+// One workgroup per unit.
+__global__ __launch_bounds__(1024) void select_kernel(View v, int budget) {
+  __shared__ uint32_t skey[kMaxClusters];
+  __shared__ uint16_t sid[kMaxClusters];
+  __shared__ int sm[64];
+  __shared__ int s_cut, s_tsel;
+  const int u = blockIdx.x, tid = threadIdx.x;
+  const int M = v.M[u];
+  const size_t cb = (size_t)u * v.Mcap;
+  int Mpad = 2;
+  while (Mpad < M) Mpad <<= 1;
+  for (int i = tid; i < Mpad; i += 1024) {
+    skey[i] = i < M ? orderable(v.score[cb + i]) : 0u;
+    sid[i] = i < M ? (uint16_t)i : (uint16_t)0xFFFF;
+  }
+  if (tid == 0) { s_cut = 0; s_tsel = 0; }
+  __syncthreads();
+  // bitonic sort: a goes before b if its score is larger, or equal with the smaller id
+  for (int k = 2; k <= Mpad; k <<= 1)
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      for (int i = tid; i < Mpad; i += 1024) {
+        const int ixj = i ^ j;
+        if (ixj > i) {
+          const uint32_t ka = skey[i], kb = skey[ixj];
+          const uint16_t ia = sid[i], ib = sid[ixj];
+          const bool b_first = kb > ka || (kb == ka && ib < ia);
+          const bool up = (i & k) == 0;
+          if (b_first == up) { skey[i] = kb; skey[ixj] = ka; sid[i] = ib; sid[ixj] = ia; }
+        }
+      }
+      __syncthreads();
+    }
+  // token prefix in score order: 8 consecutive ranks per thread
+  int sz[8], tot = 0;
+  for (int k = 0; k < 8; ++k) {
+    const int p = tid * 8 + k;
+    sz[k] = p < M ? v.cn[cb + sid[p]] + v.cb[cb + sid[p]] : 0;
+    tot += sz[k];
+  }
+  int total;
+  int run = block_excl_scan(tot, sm, total);
+  int cnt = 0, fit = 0;
+  for (int k = 0; k < 8; ++k) {
+    const int p = tid * 8 + k;
+    if (p < M) {
+      v.tok_off[cb + p] = run;
+      run += sz[k];
+      if (run <= budget) { ++cnt; fit = run; }   // prefix sums are monotone: these ranks form a prefix
+    }
+  }
+  if (cnt) { atomicAdd(&s_cut, cnt); atomicMax(&s_tsel, fit); }
+  __syncthreads();
+  int cut = s_cut, tsel = s_tsel;
+  const bool truncated = cut == 0 && M > 0 && budget > 0;     // best cluster alone is over budget
+  if (truncated) { cut = 1; tsel = budget; }
+  // page prefix over the selected ranks
+  int np[8];
+  tot = 0;
+  for (int k = 0; k < 8; ++k) {
+    const int p = tid * 8 + k;
+    const int s = truncated ? budget : sz[k];
+    np[k] = p < cut ? (s + kPageTokens - 1) / kPageTokens : 0;
+    tot += np[k];
+  }
+  run = block_excl_scan(tot, sm, total);
+  for (int k = 0; k < 8; ++k) {
+    const int p = tid * 8 + k;
+    if (p < M) { v.pg_off[cb + p] = run; run += np[k]; }
+  }
+  __syncthreads();
+  // active set, id list and gather list
+  int* plist = v.plist + (size_t)u * v.Pcap;
+  int* poff = v.plist_off + (size_t)u * v.Pcap;
+  for (int p = tid; p < M; p += 1024) {
+    const int id = sid[p];
+    v.sel_ids[cb + p] = id;
+    v.in_req[cb + id] = p < cut;
+    if (p < cut) {
+      int left = truncated ? budget : v.cn[cb + id] + v.cb[cb + id];
+      int page = v.chead[cb + id], w = v.pg_off[cb + p], t0 = v.tok_off[cb + p];
+      while (left > 0 && page >= 0) {
+        const int nv = min(left, kPageTokens);
+        plist[w] = page * 32 + nv;
+        poff[w] = t0;
+        ++w; t0 += nv; left -= nv;
+        page = v.pnext[(size_t)u * v.Pcap + page];
+      }
+    }
+  }
+  if (tid == 0) { v.n_sel[u] = cut; v.t_sel[u] = tsel; v.n_list[u] = total; v.ticket[u] = 0; }
+}
+
+// ------------------------------------------------------------------------------------------- attention
+typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+typedef __bf16 b8 __attribute__((ext_vector_type(8)));
+typedef short s4 __attribute__((ext_vector_type(4)));
+
+constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
+
+// Fragments of one page and of the query group, per storage type.  qk() returns S^T[token 4*(lane/16)+i]
+// [head lane%16]; pv() adds P^T-weighted V^T into acc[cb][i] = O^T[column 16*cb + 4*(lane/16) + i][head lane%16].
+template <int DT>
+struct Frag;
+
+template <>
+struct Frag<DYNAKV_F32> {
+  struct KV { f4 k[8]; f4 v[8]; };
+  struct Qf { f4 b[8]; };
+  static __device__ void load_q(Qf& q, const void* Q, size_t row, int lg, bool ok) {
+    const float* p = (const float*)Q + row * kHeadDim + 4 * lg;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) q.b[s] = ok ? *(const f4*)(p + 16 * s) : f4{0, 0, 0, 0};
+  }
+  static __device__ void load(KV& f, const char* page, int lane, int nvalid) {
+    const f4* kp = (const f4*)page + lane;
+    const f4* vp = (const f4*)(page + 2048 * 4) + lane;
+    const bool kok = (lane & 15) < nvalid, vok = 4 * (lane >> 4) < nvalid;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) f.k[s] = kok ? kp[s * 64] : f4{0, 0, 0, 0};
+#pragma unroll
+    for (int c = 0; c < 8; ++c) f.v[c] = vok ? vp[c * 64] : f4{0, 0, 0, 0};
+  }
+  static __device__ f4 qk(const KV& f, const Qf& q) {
+    f4 a = {0, 0, 0, 0};
+#pragma unroll
+    for (int s = 0; s < 8; ++s)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) a = __builtin_amdgcn_mfma_f32_16x16x4f32(f.k[s][i], q.b[s][i], a, 0, 0, 0);
+    return a;
+  }
+  static __device__ void pv(f4 (&acc)[8], const KV& f, const float (&p)[4]) {
+#pragma unroll
+    for (int c = 0; c < 8; ++c)
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(f.v[c][kk], p[kk], acc[c], 0, 0, 0);
+  }
+};
+
+template <bool BF>
+struct Frag16 {
+  struct KV { uint4 k[4]; uint4 v[4]; };
+  struct Qf { uint4 b[4]; };
+  static __device__ void load_q(Qf& q, const void* Q, size_t row, int lg, bool ok) {
+    const uint16_t* p = (const uint16_t*)Q + row * kHeadDim + 8 * lg;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) q.b[s] = ok ? *(const uint4*)(p + 32 * s) : uint4{0, 0, 0, 0};
+  }
+  static __device__ void load(KV& f, const char* page, int lane, int nvalid) {
+    const uint4* kp = (const uint4*)page + lane;
+    const uint4* vp = (const uint4*)(page + 2048 * 2) + lane;
+    const bool kok = (lane & 15) < nvalid, vok = 4 * (lane >> 4) < nvalid;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) f.k[s] = kok ? kp[s * 64] : uint4{0, 0, 0, 0};
+#pragma unroll
+    for (int c = 0; c < 4; ++c) f.v[c] = vok ? vp[c * 64] : uint4{0, 0, 0, 0};
+  }
+  static __device__ f4 qk(const KV& f, const Qf& q) {
+    f4 a = {0, 0, 0, 0};
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      if constexpr (BF)
+        a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(b8, f.k[s]), __builtin_bit_cast(b8, q.b[s]), a, 0, 0, 0);
+      else
+        a = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h8, f.k[s]), __builtin_bit_cast(h8, q.b[s]), a, 0, 0, 0);
+    }
+    return a;
+  }
+  static __device__ f4 mma4(uint2 a, uint2 b, f4 c) {
+    if constexpr (BF)
+      return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s4, a), __builtin_bit_cast(s4, b), c, 0, 0, 0);
+    else
+      return __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(h4, a), __builtin_bit_cast(h4, b), c, 0, 0, 0);
+  }
+  // p is split into a rounded part and its remainder so that the product keeps float32-like accuracy
+  static __device__ void pv(f4 (&acc)[8], const KV& f, const float (&p)[4]) {
+    uint16_t hi[4], lo[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if constexpr (BF) {
+        const __bf16 h = (__bf16)p[i];
+        const __bf16 l = (__bf16)(p[i] - (float)h);
+        hi[i] = __builtin_bit_cast(uint16_t, h);
+        lo[i] = __builtin_bit_cast(uint16_t, l);
+      } else {
+        const _Float16 h = (_Float16)p[i];
+        const _Float16 l = (_Float16)(p[i] - (float)h);
+        hi[i] = __builtin_bit_cast(uint16_t, h);
+        lo[i] = __builtin_bit_cast(uint16_t, l);
+      }
+    }
+    const uint2 ph = {(uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16)};
+    const uint2 pl = {(uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16)};
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      const uint4 w = f.v[c >> 1];
+      const uint2 vf = (c & 1) ? uint2{w.z, w.w} : uint2{w.x, w.y};
+      acc[c] = mma4(vf, ph, acc[c]);
+      acc[c] = mma4(vf, pl, acc[c]);
+    }
+  }
+};
+template <> struct Frag<DYNAKV_F16> : Frag16<false> {};
+template <> struct Frag<DYNAKV_BF16> : Frag16<true> {};
+
+constexpr int kWaves = 4;   // wavefronts per workgroup of gather_attend
+
+// Merges `n` partial results (running max in the log2 domain, denominator, 128 accumulators per head)
+// that sit `stride` floats apart, for head g and column dc.
+__device__ inline void merge_partials(const float* mx, const float* den, const float* acc, int n, int stride,
+                                      float& M, float& L, float& O) {
+  M = -__builtin_inff();
+  for (int w = 0; w < n; ++w) M = fmaxf(M, mx[(size_t)w * stride]);
+  L = 0.f; O = 0.f;
+  for (int w = 0; w < n; ++w) {
+    const float mw = mx[(size_t)w * stride];
+    if (mw == -__builtin_inff()) continue;
+    const float sc = __builtin_amdgcn_exp2f(mw - M);
+    L += sc * den[(size_t)w * stride];
+    O += sc * acc[(size_t)w * stride];
+  }
+}
+
+template <int DT>
+__global__ __launch_bounds__(kWaves * 64) void gather_attend_kernel(View v, const void* Q, float* out, float* lse) {
+  using F = Frag<DT>;
+  constexpr int kPageBytes = kPageElems * (DT == DYNAKV_F32 ? 4 : 2);
+  __shared__ float sm_o[kWaves][16][kHeadDim + 2];   // per wave and head: accumulators, max, denominator
+  __shared__ int s_last;
+  const int u = blockIdx.y, s = blockIdx.x, S = gridDim.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int g = lane & 15, lg = lane >> 4, G = v.G;
+
+  typename F::Qf q;
+  F::load_q(q, Q, (size_t)u * G + (g < G ? g : 0), lg, g < G);
+  const int nlist = v.n_list[u];
+  const int* plist = v.plist + (size_t)u * v.Pcap;
+  const char* pages = v.pages + (size_t)u * v.Pcap * kPageBytes;
+  const float sc = v.scale_f * kLog2e;
+
+  float m = -__builtin_inff(), l = 0.f;
+  f4 acc[8];
+#pragma unroll
+  for (int c = 0; c < 8; ++c) acc[c] = f4{0, 0, 0, 0};
+
+  const int stride = S * kWaves;
+  int p = s * kWaves + wave;
+  typename F::KV cur, nxt;
+  int nv_cur = 0, nv_nxt = 0;
+  if (p < nlist) {
+    const int e = plist[p];
+    nv_cur = e & 31;
+    F::load(cur, pages + (size_t)(e >> 5) * kPageBytes, lane, nv_cur);
+  }
+  while (p < nlist) {
+    const int pn = p + stride;
+    if (pn < nlist) {                       // next page's loads are in flight while this one is consumed
+      const int e = plist[pn];
+      nv_nxt = e & 31;
+      F::load(nxt, pages + (size_t)(e >> 5) * kPageBytes, lane, nv_nxt);
+    }
+    const f4 sacc = F::qk(cur, q);
+    float s2[4], mx = -__builtin_inff();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      s2[i] = (4 * lg + i) < nv_cur ? sacc[i] * sc : -__builtin_inff();
+      mx = fmaxf(mx, s2[i]);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float mn = fmaxf(m, mx);          // finite: every listed page has a valid token
+    const float alpha = __builtin_amdgcn_exp2f(m - mn);
+    float pr[4], ps = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { pr[i] = __builtin_amdgcn_exp2f(s2[i] - mn); ps += pr[i]; }
+    l = l * alpha + ps;
+    m = mn;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) acc[c] *= alpha;
+    F::pv(acc, cur, pr);
+    p = pn;
+    cur = nxt;
+    nv_cur = nv_nxt;
+  }
+  l += __shfl_xor(l, 16);
+  l += __shfl_xor(l, 32);
+
+  // workgroup merge
+  if (g < G) {
+#pragma unroll
+    for (int c = 0; c < 8; ++c)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) sm_o[wave][g][16 * c + 4 * lg + i] = acc[c][i];
+    if (lg == 0) { sm_o[wave][g][kHeadDim] = m; sm_o[wave][g][kHeadDim + 1] = l; }
+  }
+  __syncthreads();
+  constexpr int kWs = 16 * (kHeadDim + 2);
+  float* part = v.part + ((size_t)u * S + s) * G * (kHeadDim + 2);
+  for (int t = threadIdx.x; t < G * kHeadDim; t += kWaves * 64) {
+    const int gg = t / kHeadDim, dc = t % kHeadDim;
+    float M, L, O;
+    merge_partials(&sm_o[0][gg][kHeadDim], &sm_o[0][gg][kHeadDim + 1], &sm_o[0][gg][dc], kWaves, kWs, M, L, O);
+    if (S == 1) {
+      out[((size_t)u * G + gg) * kHeadDim + dc] = L > 0.f ? O / L : 0.f;
+      if (lse && dc == 0) lse[(size_t)u * G + gg] = L > 0.f ? (M + __builtin_amdgcn_logf(L)) * kLn2 : -__builtin_inff();
+    } else {
+      part[gg * (kHeadDim + 2) + dc] = O;
+      if (dc == 0) { part[gg * (kHeadDim + 2) + kHeadDim] = M; part[gg * (kHeadDim + 2) + kHeadDim + 1] = L; }
+    }
+  }
+  if (S == 1) return;
+  // the last workgroup of the unit to arrive merges all partial results
+  __threadfence();
+  __syncthreads();
+  if (threadIdx.x == 0) s_last = atomicAdd(&v.ticket[u], 1) == S - 1;
+  __syncthreads();
+  if (!s_last) return;
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+  const float* all = v.part + (size_t)u * S * G * (kHeadDim + 2);
+  const int ps = G * (kHeadDim + 2);
+  for (int t = threadIdx.x; t < G * kHeadDim; t += kWaves * 64) {
+    const int gg = t / kHeadDim, dc = t % kHeadDim;
+    const float* b = all + gg * (kHeadDim + 2);
+    float M, L, O;
+    merge_partials(b + kHeadDim, b + kHeadDim + 1, b + dc, S, ps, M, L, O);
+    out[((size_t)u * G + gg) * kHeadDim + dc] = L > 0.f ? O / L : 0.f;
+    if (lse && dc == 0) lse[(size_t)u * G + gg] = L > 0.f ? (M + __builtin_amdgcn_logf(L)) * kLn2 : -__builtin_inff();
+  }
+}
+
+}  // namespace
+
+hipError_t launch_score_select(const View& v, const void* Q, int budget, hipStream_t st) {
+  const dim3 grid((v.Mcap + 255) / 256, v.U);
+  if (v.G <= 4) score_kernel<4><<<grid, 256, 0, st>>>(v, Q);
+  else if (v.G <= 8) score_kernel<8><<<grid, 256, 0, st>>>(v, Q);
+  else score_kernel<16><<<grid, 256, 0, st>>>(v, Q);
+  select_kernel<<<v.U, 1024, 0, st>>>(v, budget);
+  return hipGetLastError();
+}
+
+hipError_t launch_gather_attend(const View& v, const void* Q, float* out, float* lse, hipStream_t st) {
+  const dim3 grid(v.S, v.U);
+  if (v.dtype == DYNAKV_F32) gather_attend_kernel<DYNAKV_F32><<<grid, kWaves * 64, 0, st>>>(v, Q, out, lse);
+  else if (v.dtype == DYNAKV_F16) gather_attend_kernel<DYNAKV_F16><<<grid, kWaves * 64, 0, st>>>(v, Q, out, lse);
+  else gather_attend_kernel<DYNAKV_BF16><<<grid, kWaves * 64, 0, st>>>(v, Q, out, lse);
+  return hipGetLastError();
+}
+
+}  // namespace dynakv

@@ -1,0 +1,80 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every declared symbol, sizes
+workspaces, and rejects misuse with status codes before anything is enqueued."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2511_07427_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2511_07427_amd.build import build
+        build()
+    return binding.load()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    hdr = open(os.path.join(ROOT, "include", "dynakv.h")).read()
+    names = set(re.findall(r"\b(dynakv_[a-z_]+)\s*\(", hdr))
+    assert {"dynakv_build_index", "dynakv_append", "dynakv_split", "dynakv_retrieve_attend"} <= names
+    for n in sorted(names):
+        assert hasattr(lib, n), n
+
+
+def test_struct_sizes_match_the_header():
+    assert C.sizeof(binding._Cfg) == 14 * 4
+    assert C.sizeof(binding._State) == 18 * 8
+
+
+def _cfg(**kw):
+    base = dict(n_units=2, group_size=4, dtype="f16", n_clusters_init=8, max_clusters=32, max_tokens=256)
+    base.update(kw)
+    return binding.Config(**base)
+
+
+def test_workspace_bytes_and_invalid_configs(lib):
+    a = binding.dynakv_workspace_bytes(_cfg())
+    b = binding.dynakv_workspace_bytes(_cfg(n_units=4))
+    c = binding.dynakv_workspace_bytes(_cfg(dtype="f32"))
+    assert 0 < a < b and a < c and a % 256 == 0
+    for bad in (dict(n_units=0), dict(group_size=17), dict(head_dim=64), dict(max_clusters=4), dict(max_clusters=8193),
+                dict(kmeans_iters=0), dict(buffer_max=-1), dict(group_reduce=2), dict(max_tokens=4),
+                dict(softmax_scale=-1.0)):
+        assert binding.dynakv_workspace_bytes(_cfg(**bad)) == 0, bad
+
+
+def test_create_and_call_order_errors(lib):
+    cfg = binding._cfg(_cfg())
+    n = lib.dynakv_workspace_bytes(C.byref(cfg))
+    h = C.c_void_p()
+    fake = 1 << 20     # create only records the address; nothing is dereferenced without a GPU call
+    assert lib.dynakv_create(C.byref(cfg), None, n, C.byref(h)) == 1
+    assert lib.dynakv_create(C.byref(cfg), fake + 8, n, C.byref(h)) == 1          # misaligned
+    assert lib.dynakv_create(C.byref(cfg), fake, n - 1, C.byref(h)) == 2          # too small
+    assert lib.dynakv_create(C.byref(cfg), fake, n, C.byref(h)) == 0 and h.value
+    assert lib.dynakv_retrieve_attend(h, fake, 16, fake, None, None) == 3          # before build_index
+    assert lib.dynakv_append(h, fake, fake, None) == 3
+    assert lib.dynakv_split(h, None) == 3
+    assert lib.dynakv_build_index(h, fake, fake, 4, fake, None) == 1               # fewer tokens than clusters
+    assert lib.dynakv_build_index(h, fake, fake, 512, fake, None) == 1             # more than max_tokens
+    assert lib.dynakv_build_index(h, fake, None, 64, fake, None) == 1
+    assert lib.dynakv_destroy(h) == 0
+    assert lib.dynakv_strerror(3).decode().startswith("call out of order")
+
+
+def test_page_layout_is_a_bijection():
+    """The page layout formulas of csrc/common.hpp, retyped here only to check they tile a page exactly once."""
+    def k16(s, d): return (d >> 5) * 512 + ((((d & 31) >> 3) << 4) + s) * 8 + (d & 7)
+    def v16(s, d): return 2048 + ((d >> 4) >> 1) * 512 + (((s >> 2) << 4) + (d & 15)) * 8 + ((d >> 4) & 1) * 4 + (s & 3)
+    def k32(s, d): return (d >> 4) * 256 + ((((d & 15) >> 2) << 4) + s) * 4 + (d & 3)
+    def v32(s, d): return 2048 + (d >> 4) * 256 + (((s >> 2) << 4) + (d & 15)) * 4 + (s & 3)
+    for k, v in ((k16, v16), (k32, v32)):
+        idx = [f(s, d) for f in (k, v) for s in range(16) for d in range(128)]
+        assert sorted(idx) == list(range(4096))

@@ -1,0 +1,218 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle on the same seeded inputs.
+
+Sizes are chosen so the oracle finishes in seconds while every kernel still sees several tiles, ragged
+tails and (where the workload drifts) real splits.  Each of the five benchmark configurations appears
+with its own storage type, group size, cluster count and budget, on a few of its units.
+"""
+import json
+import os
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+
+import parity  # noqa: E402
+from parity import DEV, check_attention, compare_retrieval, compare_state, make_pair, run_trajectory, to_dev  # noqa: E402
+from paper_2511_07427_amd import binding  # noqa: E402
+from paper_2511_07427_amd.workload import CONFIGS, WorkloadSpec, generate  # noqa: E402
+
+pytestmark = pytest.mark.gpu
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+# --------------------------------------------------------------------------- the five configurations
+
+def test_cfg1_tiny_f32_full_trajectory():
+    s = CONFIGS["tiny"]
+    r = run_trajectory(s, [0], s.steps, check_every=1, full_every=16)
+    say("tiny:", {k: r[k] for k in ("worst_rel", "ties", "splits", "clusters")})
+    assert r["splits"] > 0
+
+
+def test_cfg1_tiny_with_variance_trigger_and_small_buffer():
+    s = CONFIGS["tiny"].scaled(var_alpha=1.2, buffer_max=4)
+    r = run_trajectory(s, [0], s.steps, budget=128, check_every=1, full_every=16)
+    say("tiny/var:", {k: r[k] for k in ("worst_rel", "ties", "splits", "forced", "clusters")})
+    assert r["splits"] > 0 and r["forced"] > 0
+
+
+def test_cfg2_llama_shaped_f16():
+    s = CONFIGS["llama3_8b"]
+    r = run_trajectory(s, [0, 17, 255], 384, check_every=4, full_every=64)
+    say("llama:", {k: r[k] for k in ("worst_rel", "ties", "splits", "forced", "clusters")})
+
+
+def test_cfg3_qwen_shaped_bf16_group_of_7():
+    s = CONFIGS["qwen25_7b"]
+    r = run_trajectory(s, [0, 111], 768, check_every=8, full_every=128)
+    say("qwen:", {k: r[k] for k in ("worst_rel", "ties", "splits", "forced", "clusters")})
+    assert r["splits"] > 0
+
+
+def test_cfg4_batched_shaped_f16():
+    s = CONFIGS["batched16"]
+    r = run_trajectory(s, [3, 64], 128, check_every=4, full_every=64)
+    say("batched:", {k: r[k] for k in ("worst_rel", "ties", "splits", "forced", "clusters")})
+
+
+def test_cfg5_long_shaped_bf16_group_of_8():
+    s = CONFIGS["long131k"].scaled(kmeans_iters=3)
+    r = run_trajectory(s, [5], 192, check_every=8, full_every=96)
+    say("long:", {k: r[k] for k in ("worst_rel", "ties", "splits", "forced", "clusters")})
+
+
+# --------------------------------------------------------------------------- hand-worked fixtures, padded to d = 128
+
+def _pad(a):
+    a = np.asarray(a, np.float32)
+    out = np.zeros(a.shape[:-1] + (128,), np.float32)
+    out[..., :a.shape[-1]] = a
+    return out
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_hand_examples_on_the_gpu(dtype):
+    g1 = json.load(open(os.path.join(GOLD, "hand_example_1_retrieve.json")))
+    g3 = json.load(open(os.path.join(GOLD, "hand_example_3_split.json")))
+    tdt = binding.TORCH_DTYPES[dtype]
+    scale = float(1 / np.sqrt(2))
+    # example 1: build, score, select, attend
+    cfg = binding.Config(1, 1, dtype, 2, 8, 64, kmeans_iters=3, softmax_scale=scale)
+    ix = binding.Index(cfg, DEV)
+    K = torch.from_numpy(_pad(g1["keys"]))[None].to(DEV).to(tdt)
+    V = torch.from_numpy(_pad(g1["values"]))[None].to(DEV).to(tdt)
+    ix.dynakv_build_index(K, V, torch.tensor([g1["init_idx"]], dtype=torch.int32, device=DEV))
+    st = ix.dynakv_export_state()
+    assert st["size"][0, :2].tolist() == g1["clusters"]["n"]
+    np.testing.assert_array_equal(st["centroids"][0, :2, :2].numpy(), np.array(g1["clusters"]["centroids"], np.float32))
+    np.testing.assert_array_equal(st["m2"][0, :2].numpy(), g1["clusters"]["M2"])
+    assert st["members"][0, :6].tolist() == sum(g1["clusters"]["members"], [])
+    q = torch.from_numpy(_pad([[g1["query"]]])).to(DEV).to(tdt)
+    out = torch.empty(1, 1, 128, device=DEV)
+    lse = torch.empty(1, 1, device=DEV)
+    ix.dynakv_retrieve_attend(q, 2, out, lse)
+    st = ix.dynakv_export_state()
+    assert st["selected"][0, :st["n_selected"][0]].tolist() == g1["budget_2"]["selected"]
+    assert st["gathered"][0, :st["n_gathered"][0]].tolist() == g1["budget_2"]["gather"]
+    np.testing.assert_allclose(st["scores"][0, :2].numpy(), g1["scores"], rtol=1e-6)
+    np.testing.assert_allclose(out[0, 0, :2].cpu().numpy(), g1["budget_2"]["out"], atol=2e-3 * 0.80443)
+    ix.dynakv_retrieve_attend(q, 6, out, lse)
+    st = ix.dynakv_export_state()
+    assert st["gathered"][0, :st["n_gathered"][0]].tolist() == g1["budget_6"]["gather"]
+    # example 3: append, flag, split
+    cfg = binding.Config(1, 1, dtype, 2, 8, 64, kmeans_iters=3, var_alpha=1.5, buffer_max=16, softmax_scale=scale)
+    ix = binding.Index(cfg, DEV)
+    K = torch.from_numpy(_pad(g3["keys"]))[None].to(DEV).to(tdt)
+    ix.dynakv_build_index(K, K, torch.tensor([g3["init_idx"]], dtype=torch.int32, device=DEV))
+    ix.dynakv_retrieve_attend(q, 4, out, lse)
+    k = torch.from_numpy(_pad([g3["new_key"]])).to(DEV).to(tdt)
+    ix.dynakv_append(k, k)
+    st = ix.dynakv_export_state()
+    assert (st["flag"][0, 0], st["buffered"][0, 0], st["size"][0, 0], st["last_assign"][0]) == (1, 1, 4, 0)
+    ix.dynakv_split()
+    st = ix.dynakv_export_state()
+    assert st["n_clusters"][0] == 3 and st["counters"][0, 0] == 1
+    for ch in (g3["split"]["stay"], g3["split"]["moved"]):
+        j = ch["id"]
+        lo, hi = st["offsets"][0, j], st["offsets"][0, j + 1]
+        assert st["members"][0, lo:hi].tolist() == ch["members"]
+        np.testing.assert_array_equal(st["centroids"][0, j, :2].numpy(), np.array(ch["centroid"], np.float32))
+        assert st["m2"][0, j] == pytest.approx(ch["M2"], abs=1e-12) and st["size"][0, j] == ch["n"]
+
+
+# --------------------------------------------------------------------------- budgets, dense limit, degenerate shapes
+
+def _dense(Q, K, V, scale):
+    q, k, v = (torch.from_numpy(np.asarray(a, np.float64)) for a in (Q, K, V))
+    lg = scale * torch.einsum("ugd,utd->ugt", q, k)
+    return torch.einsum("ugt,utd->ugd", torch.softmax(lg, -1), v).numpy(), torch.logsumexp(lg, -1).numpy()
+
+
+@pytest.mark.parametrize("dtype,G,N0,M0", [("f16", 4, 1000, 37), ("bf16", 16, 300, 300), ("f32", 1, 530, 1), ("f16", 5, 16, 16)])
+def test_budget_edges_and_dense_limit(dtype, G, N0, M0):
+    s = WorkloadSpec("edge", dtype, 2, G, N0, 40, M0, 10 ** 6, 8, 0.05, var_alpha=1.3, size_factor=2.0, seed=77)
+    w = generate(s)
+    ix, o = make_pair(s, 2, kmeans_iters=4)
+    ix.dynakv_build_index(to_dev(w["K0"], dtype), to_dev(w["V0"], dtype), torch.from_numpy(w["init_idx"]).to(DEV))
+    o.build_index(w["K0"], w["V0"], w["init_idx"])
+    compare_state(ix, o, "build")
+    out = torch.empty(2, G, 128, device=DEV)
+    lse = torch.empty(2, G, device=DEV)
+    Qd, Kd, Vd = to_dev(w["Q"], dtype), to_dev(w["Knew"], dtype), to_dev(w["Vnew"], dtype)
+    biggest = int(o.clusters(0)["n"].max())
+    budgets = [0, 1, max(1, biggest - 1), biggest, N0 // 3, N0 - 1, N0 + 100, 10 ** 6]
+    for t in range(s.steps):
+        B = budgets[t % len(budgets)]
+        ix.dynakv_retrieve_attend(Qd[t], B, out, lse)
+        oo, ol = o.retrieve_attend(w["Q"][t], B)
+        check_attention(out.cpu().numpy(), lse.cpu().numpy(), oo, ol, "edge step %d budget %d" % (t, B))
+        compare_retrieval(ix, o, "edge step %d budget %d" % (t, B))
+        if B >= N0 + t:   # everything retrieved: dense attention over the whole cache
+            allK = np.concatenate([w["K0"], w["Knew"][:t].transpose(1, 0, 2)], 1)
+            allV = np.concatenate([w["V0"], w["Vnew"][:t].transpose(1, 0, 2)], 1)
+            ref, rl = _dense(w["Q"][t], allK, allV, 1 / np.sqrt(128))
+            check_attention(out.cpu().numpy(), lse.cpu().numpy(), ref, rl, "dense step %d" % t)
+        ix.dynakv_append(Kd[t], Vd[t]); o.append(w["Knew"][t], w["Vnew"][t])
+        ix.dynakv_split(); o.split()
+        compare_state(ix, o, "edge step %d" % t, full=True)
+
+
+def test_group_sum_custom_scale_all_resident_and_huge_logits():
+    s = WorkloadSpec("opts", "f16", 3, 3, 700, 64, 24, 200, 6, 0.1, var_alpha=1.2, size_factor=0.0, buffer_max=0, seed=99)
+    r = run_trajectory(s, range(3), 64, group_reduce=1, softmax_scale=0.05, kmeans_iters=5, full_every=8)
+    say("opts:", {k: r[k] for k in ("worst_rel", "splits", "clusters")})
+    assert r["splits"] > 0
+    ix, o, w = r["index"], r["oracle"], r["workload"]
+    Q = w["Q"][0] * 200.0                      # logits far beyond exp's range without max subtraction
+    out = torch.empty(3, 3, 128, device=DEV)
+    lse = torch.empty(3, 3, device=DEV)
+    ix.dynakv_retrieve_attend(to_dev(Q, "f16"), 300, out, lse)
+    from paper_2511_07427_amd.workload import round_to_dtype
+    oo, ol = o.retrieve_attend(round_to_dtype(Q, "f16"), 300)
+    assert torch.isfinite(out).all() and torch.isfinite(lse).all()
+    den = np.maximum(np.abs(oo).max(-1), 1e-6)
+    assert (np.abs(out.cpu().numpy() - oo).max(-1) / den).max() <= 2e-3
+    assert np.abs(lse.cpu().numpy() - ol).max() <= 2e-3 * np.abs(ol).max()
+
+
+def test_capacity_limits_set_the_error_word_and_keep_state():
+    s = WorkloadSpec("cap", "f16", 1, 2, 64, 8, 4, 32, 4, 0.5, var_alpha=0.5, size_factor=0.0, buffer_max=0,
+                     max_cluster_factor=1, seed=5)
+    w = generate(s)
+    ix, o = make_pair(s, 1, max_tokens=68)
+    ix.dynakv_build_index(to_dev(w["K0"], "f16"), to_dev(w["V0"], "f16"), torch.from_numpy(w["init_idx"]).to(DEV))
+    o.build_index(w["K0"], w["V0"], w["init_idx"])
+    Kd, Vd = to_dev(w["Knew"], "f16"), to_dev(w["Vnew"], "f16")
+    for t in range(8):                          # 4 appends fit, then max_tokens; splits have no free cluster id
+        ix.dynakv_append(Kd[t], Vd[t]); o.append(w["Knew"][t], w["Vnew"][t])
+        ix.dynakv_split(); o.split()
+        compare_state(ix, o, "cap step %d" % t)
+    st = ix.dynakv_export_state(["error", "n_tokens", "n_clusters"])
+    assert st["n_tokens"][0] == 68 and st["n_clusters"][0] == 4
+    assert st["error"][0] & binding.ERR_TOKENS and st["error"][0] & binding.ERR_CLUSTERS
+
+
+def test_rebuild_resets_the_index_and_runs_are_deterministic():
+    s = CONFIGS["tiny"].scaled(prefill=777, n_clusters_init=19)
+    w = generate(s, steps=8)
+    ix, o = make_pair(s, 1)
+    K0, V0, init = to_dev(w["K0"], "f32"), to_dev(w["V0"], "f32"), torch.from_numpy(w["init_idx"]).to(DEV)
+    ix.dynakv_build_index(K0, V0, init)
+    for t in range(8):
+        ix.dynakv_append(to_dev(w["Knew"][t], "f32"), to_dev(w["Vnew"][t], "f32"))
+    a = ix.dynakv_export_state()
+    ix.dynakv_build_index(K0, V0, init)
+    o.build_index(w["K0"], w["V0"], w["init_idx"])
+    compare_state(ix, o, "rebuild")
+    for t in range(8):
+        ix.dynakv_append(to_dev(w["Knew"][t], "f32"), to_dev(w["Vnew"][t], "f32"))
+    b = ix.dynakv_export_state()
+    for k in a:
+        assert torch.equal(a[k], b[k]), k
