@@ -1,0 +1,165 @@
+"""Benchmark of the decode hot path on one MI355X.
+
+A step = dynakv_retrieve_attend + dynakv_append + dynakv_split over all units of the workload, on seeded
+synthetic drifting-mixture inputs already resident in HBM.  Prints one JSON line: decode steps/s, the
+roofline of the dominant kernel (gather + attention, HBM-bound), and the CPU oracle timed on a bounded
+sample of the same workload on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_PEAK_TFLOPS = 2500.0      # dense fp16/bf16, published
+
+
+def cpu_baseline(spec, n_units, steps, budget):
+    """The oracle as it stands, on a bounded sample: `n_units` units, k-means prefill plus `steps` decode steps."""
+    import numpy as np
+    from oracle import Oracle, OracleConfig
+    from paper_2511_07427_amd.workload import generate
+    w = generate(spec, units=range(n_units), steps=steps)
+    o = Oracle(OracleConfig(n_units, spec.group_size, spec.head_dim, spec.n_clusters_init, spec.max_clusters,
+                            spec.prefill + steps, spec.kmeans_iters, spec.buffer_max, 0, spec.var_alpha,
+                            spec.size_factor, 0.0, 0))
+    t0 = time.perf_counter()
+    o.build_index(w["K0"], w["V0"], w["init_idx"])
+    t1 = time.perf_counter()
+    for t in range(steps):
+        o.retrieve_attend(w["Q"][t], budget)
+        o.append(w["Knew"][t], w["Vnew"][t])
+        o.split()
+    t2 = time.perf_counter()
+    whole_job = steps / ((t2 - t1) * spec.n_units / n_units)      # all units at this per-unit rate, same cores
+    return dict(value=whole_job, unit="decode steps/s", cores=o.threads_used, kind="oracle",
+                sample="%d of %d units, %d-token k-means prefill (%.1f s, not in value) then %d decode steps in %.1f s; "
+                       "scaled to all units" % (n_units, spec.n_units, spec.prefill, t1 - t0, steps, t2 - t1),
+                prefill_s_all_units=(t1 - t0) * spec.n_units / n_units)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=8192)
+    ap.add_argument("--warmup", type=int, default=64)
+    ap.add_argument("--config", default="llama3_8b")
+    ap.add_argument("--units", type=int, default=0, help="debug: use only the first UNITS units")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-events", action="store_true", help="skip the HIP events around the dominant kernel")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        sys.exit("bench.py: this path runs on one GPU; units are independent and shard without communication "
+                 "(see DESIGN.md), but no multi-GPU run exists here. Use --gpus 1.")
+
+    import numpy as np
+    import torch
+    from paper_2511_07427_amd import binding
+    from paper_2511_07427_amd.workload import CONFIGS, generate
+
+    spec = CONFIGS[a.config]
+    if a.units:
+        spec = spec.scaled(n_units=a.units)
+    T = a.warmup + a.steps
+    U, G, d = spec.n_units, spec.group_size, spec.head_dim
+    dev = torch.device("cuda:0")
+    tdt = binding.TORCH_DTYPES[spec.dtype]
+    esz = 4 if spec.dtype == "f32" else 2
+
+    t0 = time.perf_counter()
+    w = generate(spec, steps=T, workers=16)
+    gen_s = time.perf_counter() - t0
+    K0 = torch.from_numpy(w["K0"]).to(dev).to(tdt)
+    V0 = torch.from_numpy(w["V0"]).to(dev).to(tdt)
+    init = torch.from_numpy(w["init_idx"]).to(dev)
+    Q = torch.empty(T, U, G, d, dtype=tdt, device=dev)
+    Kn = torch.empty(T, U, d, dtype=tdt, device=dev)
+    Vn = torch.empty(T, U, d, dtype=tdt, device=dev)
+    for lo in range(0, T, 512):           # staged upload keeps the float32 host copies off the device
+        hi = min(T, lo + 512)
+        Q[lo:hi] = torch.from_numpy(w["Q"][lo:hi]).to(dev).to(tdt)
+        Kn[lo:hi] = torch.from_numpy(w["Knew"][lo:hi]).to(dev).to(tdt)
+        Vn[lo:hi] = torch.from_numpy(w["Vnew"][lo:hi]).to(dev).to(tdt)
+    del w
+
+    ix = binding.Index(binding.Config(U, G, spec.dtype, spec.n_clusters_init, spec.max_clusters, spec.prefill + T,
+                                      spec.kmeans_iters, spec.buffer_max, 0, spec.var_alpha, spec.size_factor, 0.0), dev)
+    out = torch.empty(U, G, d, dtype=torch.float32, device=dev)
+    lse = torch.empty(U, G, dtype=torch.float32, device=dev)
+    st = torch.cuda.current_stream()
+    stream = st.cuda_stream
+
+    # prefill (one-off, reported beside the decode figure)
+    ix.dynakv_build_index(K0, V0, init)          # first call also pays module loading
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(st)
+    ix.dynakv_build_index(K0, V0, init)
+    e1.record(st)
+    torch.cuda.synchronize()
+    prefill_ms = e0.elapsed_time(e1)
+    kmeans_flop = 2.0 * spec.prefill * spec.n_clusters_init * d * spec.kmeans_iters * U
+
+    qs, ks, os_, ls = Q.data_ptr(), Kn.data_ptr(), out.data_ptr(), lse.data_ptr()
+    q_stride, k_stride = U * G * d * esz, U * d * esz
+    step = ix.decode_step_ptrs
+    for t in range(a.warmup):
+        step(qs + t * q_stride, spec.budget, os_, ls, ks + t * k_stride, Vn.data_ptr() + t * k_stride, stream)
+    torch.cuda.synchronize()
+    c0 = ix.dynakv_export_state(["counters"])["counters"].numpy().copy()
+    if not a.no_kernel_events:
+        ix.dynakv_profile_enable(a.steps)
+    vs = Vn.data_ptr()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(a.warmup, T):
+        step(qs + t * q_stride, spec.budget, os_, ls, ks + t * k_stride, vs + t * k_stride, stream)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    state = ix.dynakv_export_state(["counters", "error", "n_clusters", "n_tokens"])
+    c1 = state["counters"].numpy()
+    assert int(state["error"].abs().sum()) == 0, "device error word set during the run"
+    assert int(state["n_tokens"].min()) == spec.prefill + T
+    gathered = int((c1[:, 4] - c0[:, 4]).sum())
+    retrievals = int((c1[:, 5] - c0[:, 5]).sum())
+    assert retrievals == a.steps * U
+
+    roof = None
+    if not a.no_kernel_events:
+        n, ms = ix.dynakv_profile_read()
+        assert n == a.steps
+        bytes_per_launch = gathered / a.steps * 2 * d * esz            # K and V of every gathered entry, once
+        achieved = bytes_per_launch / (ms / n * 1e-3) / 1e9
+        roof = dict(bound="hbm", kernel="gather_attend_kernel", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=achieved / HBM_PEAK_GBS, traffic=None, avg_launch_us=ms / n * 1e3,
+                    algorithmic_bytes_per_launch=bytes_per_launch, gathered_entries_per_unit=gathered / retrievals)
+
+    res = {
+        "metric": "decode steps/sec (index maint + retrieve + sparse attn)", "value": a.steps / dt,
+        "unit": "decode steps/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": dt / a.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": spec.dtype, "data": "synthetic",
+        "config": {"workload": "%s: %d units (layers x KV heads), G=%d, d=%d, %s, prefill %d, M0=%d clusters, "
+                               "token budget %d, decode steps %d..%d of a drifting %d-component mixture" %
+                               (spec.name, U, G, d, spec.dtype, spec.prefill, spec.n_clusters_init, spec.budget,
+                                a.warmup, T, spec.n_components),
+                   "kv_splits": ix and int(os.environ.get("DYNAKV_KV_SPLITS", "0")) or None},
+        "roofline": roof,
+        "prefill": {"ms": prefill_ms, "kmeans_algorithmic_tflops": kmeans_flop / (prefill_ms * 1e-3) / 1e12,
+                    "frac_of_mfma_peak": kmeans_flop / (prefill_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS},
+        "index": {"clusters_mean": float(state["n_clusters"].float().mean()), "splits": int(c1[:, 0].sum()),
+                  "forced_splits": int(c1[:, 2].sum()), "input_generation_s": gen_s},
+    }
+    if not a.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(spec, min(U, 16), 128, spec.budget)
+    print(json.dumps(res), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -142,7 +142,8 @@ typedef struct {
   int32_t* n_gathered;   /* [U]                 entries attended by the last retrieval           */
   int32_t* gathered;     /* [U][max_tokens]     their token positions in gather order            */
   int32_t* last_assign;  /* [U]                 cluster chosen by the last append                */
-  int64_t* counters;     /* [U][4]              splits, failed splits, forced splits, pages in use */
+  int64_t* counters;     /* [U][6]              splits, failed splits, forced splits, pages in use,
+                                                entries gathered so far, retrievals so far    */
 } dynakv_state_t;
 
 /* Copies the requested parts of the state (enqueued on `stream`; the caller synchronises before reading). */

@@ -153,6 +153,15 @@ class Index:
     def dynakv_split(self):
         _check(self._lib.dynakv_split(self._h, _stream()), "dynakv_split")
 
+    def decode_step_ptrs(self, q_ptr: int, budget: int, out_ptr: int, lse_ptr: int, k_ptr: int, v_ptr: int, stream: int):
+        """One decode step (retrieve_attend, append, split) on raw device addresses: the same three ABI calls
+        without per-call tensor checks, for loops where interpreter time would otherwise dominate."""
+        lib, h = self._lib, self._h
+        rc = lib.dynakv_retrieve_attend(h, q_ptr, budget, out_ptr, lse_ptr, stream) or \
+            lib.dynakv_append(h, k_ptr, v_ptr, stream) or lib.dynakv_split(h, stream)
+        if rc:
+            _check(rc, "decode step")
+
     # ---- timing aid ---------------------------------------------------------------------------
     def dynakv_profile_enable(self, max_launches: int):
         _check(self._lib.dynakv_profile_enable(self._h, int(max_launches)), "dynakv_profile_enable")
@@ -172,7 +181,7 @@ class Index:
                     centroids=((U, M, d), f32), size=((U, M), i32), buffered=((U, M), i32), flag=((U, M), i32),
                     m2=((U, M), f64), offsets=((U, M + 1), i32), members=((U, N), i32), scores=((U, M), f32),
                     n_selected=((U,), i32), selected=((U, M), i32), n_gathered=((U,), i32), gathered=((U, N), i32),
-                    last_assign=((U,), i32), counters=((U, 4), i64))
+                    last_assign=((U,), i32), counters=((U, 6), i64))
         bufs = {k: torch.zeros(spec[k][0], dtype=spec[k][1], device=self.device) for k in fields}
         st = _State(**{k: (bufs[k].data_ptr() if k in bufs else None) for k in _STATE_FIELDS})
         _check(self._lib.dynakv_export_state(self._h, C.byref(st), _stream()), "dynakv_export_state")

@@ -67,7 +67,7 @@ size_t carve(const dynakv_config_t& c, char* base, View* out) {
   v.M = (int*)take(U * 4); v.N = (int*)take(U * 4); v.err = (int*)take(U * 4); v.tau = (double*)take(U * 8);
   v.nflag = (int*)take(U * 4); v.n_sel = (int*)take(U * 4); v.t_sel = (int*)take(U * 4); v.n_list = (int*)take(U * 4);
   v.ticket = (int*)take(U * 4); v.bump = (int*)take(U * 4); v.free_top = (int*)take(U * 4);
-  v.last_assign = (int*)take(U * 4); v.counters = (long long*)take(U * 4 * 8);
+  v.last_assign = (int*)take(U * 4); v.counters = (long long*)take(U * kCounters * 8);
   v.R = (float*)take(UM * kHeadDim * 4);
   v.cn = (int*)take(UM * 4); v.cb = (int*)take(UM * 4); v.cflag = (int*)take(UM * 4); v.cM2 = (double*)take(UM * 8);
   v.chead = (int*)take(UM * 4); v.ctail = (int*)take(UM * 4); v.score = (float*)take(UM * 4);

@@ -15,7 +15,8 @@ constexpr int kPageElems = 2 * kPageTokens * kHeadDim;  // K region then V regio
 constexpr int kMaxClusters = 8192;              // selection sorts one unit's clusters in LDS
 constexpr int kMaxPrefill = 16384;              // k-means sorts one unit's labels in LDS
 constexpr int kMaxSplitMembers = 8192;          // largest cluster the split kernel handles
-constexpr int kMaxKvSplits = 64;                // workgroups that share one unit's gathered pages
+constexpr int kMaxKvSplits = 64;
+constexpr int kCounters = 6;                // workgroups that share one unit's gathered pages
 
 typedef float f4 __attribute__((ext_vector_type(4)));
 
@@ -38,7 +39,7 @@ struct View {
   int* bump;         // [U] pages handed out from the pool so far
   int* free_top;     // [U] entries on the free-page stack
   int* last_assign;  // [U]
-  long long* counters;  // [U][4] splits, failed, forced, (unused)
+  long long* counters;  // [U][6] splits, failed, forced, (unused), entries gathered, retrievals
   // per cluster [U][Mcap]
   float* R;          // [U][Mcap][128] centroids
   int* cn;           // committed size n_j

@@ -277,7 +277,7 @@ __device__ void split_cluster(const View& v, int u, int j, SplitSmem& s) {
     if (tid == 0) {
       v.cn[cbase + j] = m; v.cb[cbase + j] = 0; v.cflag[cbase + j] = 0; v.cM2[cbase + j] = s.m2[0];
       v.nflag[u] -= 1;
-      v.counters[(size_t)u * 4 + 1] += 1;
+      v.counters[(size_t)u * kCounters + 1] += 1;
     }
     __syncthreads();
     return;
@@ -334,7 +334,7 @@ __device__ void split_cluster(const View& v, int u, int j, SplitSmem& s) {
     v.M[u] = M + 1;
     for (int k = 0; k < s.nchain; ++k) free_page(v, u, s.chain[k]);
     v.nflag[u] -= 1;
-    v.counters[(size_t)u * 4 + 0] += 1;
+    v.counters[(size_t)u * kCounters + 0] += 1;
   }
   __syncthreads();
 }
@@ -381,7 +381,7 @@ __global__ __launch_bounds__(256) void split_kernel(View v) {
     const long long total = s_tot;
     __syncthreads();
     if (arg >= 0 && total >= v.Bmax) {
-      if (tid == 0) v.counters[(size_t)u * 4 + 2] += 1;
+      if (tid == 0) v.counters[(size_t)u * kCounters + 2] += 1;
       split_cluster(v, u, arg, s);
     }
   }
@@ -402,8 +402,8 @@ __global__ __launch_bounds__(1024) void export_kernel(View v, dynakv_state_t o) 
     if (o.n_gathered) o.n_gathered[u] = v.t_sel[u];
     if (o.last_assign) o.last_assign[u] = v.last_assign[u];
     if (o.counters) {
-      for (int k = 0; k < 3; ++k) o.counters[(size_t)u * 4 + k] = v.counters[(size_t)u * 4 + k];
-      o.counters[(size_t)u * 4 + 3] = v.bump[u] - v.free_top[u];
+      for (int k = 0; k < kCounters; ++k) o.counters[(size_t)u * kCounters + k] = v.counters[(size_t)u * kCounters + k];
+      o.counters[(size_t)u * kCounters + 3] = v.bump[u] - v.free_top[u];
     }
   }
   for (int j = tid; j < v.Mcap; j += 1024) {

@@ -141,7 +141,11 @@ __global__ __launch_bounds__(1024) void select_kernel(View v, int budget) {
       }
     }
   }
-  if (tid == 0) { v.n_sel[u] = cut; v.t_sel[u] = tsel; v.n_list[u] = total; v.ticket[u] = 0; }
+  if (tid == 0) {
+    v.n_sel[u] = cut; v.t_sel[u] = tsel; v.n_list[u] = total; v.ticket[u] = 0;
+    v.counters[(size_t)u * kCounters + 4] += tsel;
+    v.counters[(size_t)u * kCounters + 5] += 1;
+  }
 }
 
 // ------------------------------------------------------------------------------------------- attention
