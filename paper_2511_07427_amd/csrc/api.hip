@@ -35,10 +35,26 @@ bool config_ok(const dynakv_config_t* c) {
   return true;
 }
 
-int kv_splits(int U) {
-  int S = (1024 + U - 1) / U;
-  if (const char* e = std::getenv("DYNAKV_KV_SPLITS")) S = std::atoi(e);
-  return S < 1 ? 1 : (S > kMaxKvSplits ? kMaxKvSplits : S);
+int pow2_floor(int x) {
+  int p = 1;
+  while (2 * p <= x) p *= 2;
+  return p;
+}
+
+// Shape of the gather + attention launch: S workgroups per unit (at least one workgroup per compute unit
+// of the chip) of NW wavefronts each (about 4096 wavefronts in all; the workgroup merge needs
+// NW * G * 130 floats of LDS).  DYNAKV_KV_SPLITS / DYNAKV_ATT_WAVES override for tuning runs.
+void plan_attention(const dynakv_config_t& c, int* S, int* NW) {
+  int s = (256 + c.n_units - 1) / c.n_units;
+  int nw = pow2_floor(4096 / (c.n_units * s) > 0 ? 4096 / (c.n_units * s) : 1);
+  if (const char* e = std::getenv("DYNAKV_KV_SPLITS")) s = std::atoi(e);
+  if (const char* e = std::getenv("DYNAKV_ATT_WAVES")) nw = std::atoi(e);
+  const int lds_max = pow2_floor(65536 / (c.group_size * (kHeadDim + 2) * 4));
+  nw = nw < 4 ? 4 : (nw > 16 ? 16 : pow2_floor(nw));
+  if (nw > lds_max) nw = lds_max < 4 ? 4 : lds_max;
+  if (c.dtype == DYNAKV_F32) nw = 4;
+  *S = s < 1 ? 1 : (s > kMaxKvSplits ? kMaxKvSplits : s);
+  *NW = nw;
 }
 
 // Pages per unit: every token, one partly filled page per cluster, and room for a split to write both
@@ -53,7 +69,7 @@ size_t carve(const dynakv_config_t& c, char* base, View* out) {
   std::memset(&v, 0, sizeof(v));
   v.U = c.n_units; v.G = c.group_size; v.dtype = c.dtype; v.M0 = c.n_clusters_init; v.Mcap = c.max_clusters;
   v.Ncap = c.max_tokens; v.Pcap = pages_per_unit(c); v.Bmax = c.buffer_max; v.group_reduce = c.group_reduce;
-  v.S = kv_splits(c.n_units);
+  plan_attention(c, &v.S, &v.NW);
   v.var_alpha = c.var_alpha; v.size_factor = c.size_factor;
   v.scale_d = c.softmax_scale > 0.f ? (double)c.softmax_scale : 1.0 / std::sqrt((double)c.head_dim);
   v.scale_f = (float)v.scale_d;
@@ -68,9 +84,10 @@ size_t carve(const dynakv_config_t& c, char* base, View* out) {
   v.nflag = (int*)take(U * 4); v.n_sel = (int*)take(U * 4); v.t_sel = (int*)take(U * 4); v.n_list = (int*)take(U * 4);
   v.ticket = (int*)take(U * 4); v.bump = (int*)take(U * 4); v.free_top = (int*)take(U * 4);
   v.last_assign = (int*)take(U * 4); v.counters = (long long*)take(U * kCounters * 8);
-  v.R = (float*)take(UM * kHeadDim * 4);
+  v.Rstride = r_stride(v.Mcap);
+  v.R = (float*)take(U * v.Rstride * 4);
   v.cn = (int*)take(UM * 4); v.cb = (int*)take(UM * 4); v.cflag = (int*)take(UM * 4); v.cM2 = (double*)take(UM * 8);
-  v.chead = (int*)take(UM * 4); v.ctail = (int*)take(UM * 4); v.score = (float*)take(UM * 4);
+  v.cpg = (int*)take(UM * kInlinePages * 4); v.ctail = (int*)take(UM * 4); v.score = (float*)take(UM * 4);
   v.sel_ids = (int*)take(UM * 4); v.in_req = (unsigned char*)take(UM); v.tok_off = (int*)take(UM * 4);
   v.pg_off = (int*)take(UM * 4);
   v.pages = take(UP * (size_t)kPageElems * elem_size(c.dtype));

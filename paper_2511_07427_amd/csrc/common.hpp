@@ -14,16 +14,18 @@ constexpr int kPageTokens = 16;                 // tokens per page = one MFMA ti
 constexpr int kPageElems = 2 * kPageTokens * kHeadDim;  // K region then V region
 constexpr int kMaxClusters = 8192;              // selection sorts one unit's clusters in LDS
 constexpr int kMaxPrefill = 16384;              // k-means sorts one unit's labels in LDS
-constexpr int kMaxSplitMembers = 8192;          // largest cluster the split kernel handles
+constexpr int kMaxSplitMembers = 4096;          // largest cluster the split kernel handles
 constexpr int kMaxKvSplits = 64;
-constexpr int kCounters = 6;                // workgroups that share one unit's gathered pages
+constexpr int kCounters = 6;
+constexpr int kInlinePages = 8;                 // pages of a cluster found without walking its chain                // workgroups that share one unit's gathered pages
 
 typedef float f4 __attribute__((ext_vector_type(4)));
 
 // Device-side view of one index.  All arrays live in the caller's workspace.
 struct View {
   // configuration
-  int U, G, dtype, M0, Mcap, Ncap, Pcap, Bmax, group_reduce, S;
+  int U, G, dtype, M0, Mcap, Ncap, Pcap, Bmax, group_reduce, S, NW;
+  size_t Rstride;    // floats of centroid table per unit
   float var_alpha, size_factor, scale_f;
   double scale_d;
   // per unit
@@ -41,12 +43,12 @@ struct View {
   int* last_assign;  // [U]
   long long* counters;  // [U][6] splits, failed, forced, (unused), entries gathered, retrievals
   // per cluster [U][Mcap]
-  float* R;          // [U][Mcap][128] centroids
+  float* R;          // [U][Rstride] centroids, lane-interleaved: see r_index()
   int* cn;           // committed size n_j
   int* cb;           // buffered entries |Buf_j|
   int* cflag;        // f_j
   double* cM2;       // M2_j
-  int* chead;        // first page (-1: none)
+  int* cpg;          // [.][8] first pages of the cluster (-1: none); later pages follow pnext
   int* ctail;        // last page
   float* score;      // last scores
   int* sel_ids;      // ids in score order
@@ -100,6 +102,44 @@ __host__ __device__ inline int v_index(int dtype, int slot, int d) {
   return dtype == DYNAKV_F32 ? v_index32(slot, d) : v_index16(slot, d);
 }
 
+// ---- centroid table ------------------------------------------------------------------------------
+// Centroids are read by kernels in which lane l of a wavefront owns cluster 64*t + l.  The table is laid
+// out so that such a wavefront reads 16 contiguous bytes per lane: [tile of 64 clusters][d/4][64][4].
+__host__ __device__ inline size_t r_index(int j, int d) {
+  return ((size_t)(j >> 6) * (kHeadDim / 4) + (d >> 2)) * 256 + (size_t)(j & 63) * 4 + (d & 3);
+}
+__host__ __device__ inline size_t r_stride(int Mcap) { return (size_t)((Mcap + 63) / 64) * 64 * kHeadDim; }
+__device__ inline float* unit_R(const View& v, int u) { return v.R + (size_t)u * v.Rstride; }
+
+// Feeds the 128 coordinates of centroid j to f(d, value) in ascending d, with the loads of the next 32
+// coordinates in flight while the current 32 are consumed.  `first` holds coordinates 0..31, already
+// loaded by the caller (so that the caller can issue them before anything else it waits for).
+__device__ inline void load_centroid_head(const float* R, int j, f4 (&first)[8]) {
+  const f4* r = (const f4*)(R + r_index(j, 0));
+#pragma unroll
+  for (int i = 0; i < 8; ++i) first[i] = r[i * 64];
+}
+template <class F>
+__device__ inline void for_each_coord(const float* R, int j, f4 (&cur)[8], F&& f) {
+  const f4* r = (const f4*)(R + r_index(j, 0));
+  f4 nxt[8];
+#pragma unroll 1
+  for (int b = 0; b < 4; ++b) {
+    if (b < 3) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) nxt[i] = r[((b + 1) * 8 + i) * 64];
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) f(b * 32 + i * 4 + e, cur[i][e]);
+    if (b < 3) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) cur[i] = nxt[i];
+    }
+  }
+}
+
 // ---- element access -----------------------------------------------------------------------------
 __device__ inline float bf16_to_float(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
 __device__ inline float f16_to_float(uint16_t h) { return (float)__builtin_bit_cast(_Float16, h); }
@@ -149,6 +189,11 @@ __device__ inline int block_excl_scan(int val, int* sm, int& total) {
   const int base = w ? sm[w - 1] : 0;
   total = sm[nw - 1];
   return base + x - val;
+}
+
+// k-th page of the cluster with flat index cj (= u * Mcap + j); `prev` is its page k-1.
+__device__ inline int cluster_page(const View& v, int u, size_t cj, int k, int prev) {
+  return k < kInlinePages ? v.cpg[cj * kInlinePages + k] : v.pnext[(size_t)u * v.Pcap + prev];
 }
 
 // Takes a page from the unit's free stack, else from the untouched tail of its pool; -1 if none is left.

@@ -21,7 +21,7 @@ __global__ __launch_bounds__(128) void kmeans_init_kernel(View v, const void* X,
   const int u = blockIdx.y, j = blockIdx.x, d = threadIdx.x;
   int p = init_idx[(size_t)u * v.M0 + j];
   p = min(max(p, 0), N0 - 1);
-  v.R[((size_t)u * v.Mcap + j) * kHeadDim + d] = load_elem(X, ((size_t)u * N0 + p) * kHeadDim + d, v.dtype);
+  unit_R(v, u)[r_index(j, d)] = load_elem(X, ((size_t)u * N0 + p) * kHeadDim + d, v.dtype);
 }
 
 // One thread per point: nearest centre in exact float64, centres staged through LDS in tiles.
@@ -39,11 +39,11 @@ __global__ __launch_bounds__(256) void kmeans_assign_f64_kernel(View v, const vo
   }
   double best = __builtin_inf();
   int arg = 0;
-  const float* R = v.R + (size_t)u * v.Mcap * kHeadDim;
+  const float* R = unit_R(v, u);
   for (int j0 = 0; j0 < v.M0; j0 += kTileC) {
     const int nt = min(kTileC, v.M0 - j0);
     __syncthreads();
-    for (int t = threadIdx.x; t < nt * kHeadDim; t += 256) rs[t / kHeadDim][t % kHeadDim] = R[(size_t)j0 * kHeadDim + t];
+    for (int t = threadIdx.x; t < nt * kHeadDim; t += 256) rs[t / kHeadDim][t % kHeadDim] = R[r_index(j0 + t / kHeadDim, t % kHeadDim)];
     __syncthreads();
     for (int jj = 0; jj < nt; ++jj) {
       double acc = 0.0;
@@ -105,7 +105,7 @@ __global__ __launch_bounds__(256) void kmeans_update_kernel(View v, const void* 
   if (e == b) return;
   double s = 0.0;
   for (int q = b; q < e; ++q) s += (double)load_elem(X, ((size_t)u * N0 + order[q]) * kHeadDim + d, v.dtype);
-  v.R[((size_t)u * v.Mcap + j) * kHeadDim + d] = (float)(s / (double)(e - b));
+  unit_R(v, u)[r_index(j, d)] = (float)(s / (double)(e - b));
 }
 
 // One workgroup per unit: every empty cluster, in ascending id, takes the not-yet-taken point that is
@@ -145,7 +145,7 @@ __global__ __launch_bounds__(256) void kmeans_reseed_kernel(View v, const void* 
     __syncthreads();
     if (far < 0) break;                      // every point already taken
     if (tid < kHeadDim)
-      v.R[((size_t)u * v.Mcap + j) * kHeadDim + tid] = load_elem(X, ((size_t)u * N0 + far) * kHeadDim + tid, v.dtype);
+      unit_R(v, u)[r_index(j, tid)] = load_elem(X, ((size_t)u * N0 + far) * kHeadDim + tid, v.dtype);
     if (tid == 0) dist[far] = -2.0;          // taken
     __syncthreads();
   }
@@ -156,11 +156,11 @@ __global__ __launch_bounds__(256) void point_dist_kernel(View v, const void* X, 
   const int u = blockIdx.y, i = blockIdx.x * 256 + threadIdx.x;
   if (i >= N0) return;
   const int j = v.labels[(size_t)u * v.Ncap + i];
-  const float* r = v.R + ((size_t)u * v.Mcap + j) * kHeadDim;
+  const float* R = unit_R(v, u);
   const size_t base = ((size_t)u * N0 + i) * kHeadDim;
   double acc = 0.0;
   for (int d = 0; d < kHeadDim; ++d) {
-    const double t = (double)load_elem(X, base + d, v.dtype) - (double)r[d];
+    const double t = (double)load_elem(X, base + d, v.dtype) - (double)R[r_index(j, d)];
     acc = fma(t, t, acc);
   }
   v.dist[(size_t)u * v.Ncap + i] = acc;
@@ -193,12 +193,13 @@ __global__ __launch_bounds__(1024) void finalize_kernel(View v, int N0) {
       v.cn[cb + j] = e - b;
       v.cM2[cb + j] = m2;
       v.pg_off[cb + j] = base;
-      v.chead[cb + j] = np[k] ? base : -1;
+      for (int p = 0; p < kInlinePages; ++p) v.cpg[(cb + j) * kInlinePages + p] = p < np[k] ? base + p : -1;
       v.ctail[cb + j] = np[k] ? base + np[k] - 1 : -1;
       for (int p = 0; p < np[k]; ++p) v.pnext[(size_t)u * v.Pcap + base + p] = p + 1 < np[k] ? base + p + 1 : -1;
       base += np[k];
     } else {
-      v.cn[cb + j] = 0; v.cM2[cb + j] = 0.0; v.chead[cb + j] = -1; v.ctail[cb + j] = -1;
+      v.cn[cb + j] = 0; v.cM2[cb + j] = 0.0; v.ctail[cb + j] = -1;
+      for (int p = 0; p < kInlinePages; ++p) v.cpg[(cb + j) * kInlinePages + p] = -1;
     }
     v.cb[cb + j] = 0; v.cflag[cb + j] = 0; v.in_req[cb + j] = 0;
   }

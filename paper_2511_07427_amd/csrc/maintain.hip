@@ -32,11 +32,14 @@ __device__ inline void block_arg_reduce(double val, int idx, double* sv, int* si
 
 // ------------------------------------------------------------------------------------------- append
 __global__ __launch_bounds__(256) void append_kernel(View v, const void* kin, const void* vin) {
-  __shared__ double kd[kHeadDim], r1[kHeadDim];
+  __shared__ double kd[kHeadDim], delta[kHeadDim], r1[kHeadDim];
   __shared__ double sv[256];
   __shared__ int si[256];
   __shared__ int s_ok, s_commit, s_page, s_slot;
   const int u = blockIdx.x, tid = threadIdx.x;
+  float* R = unit_R(v, u);
+  f4 row[8];
+  if ((size_t)(tid | 63) * kHeadDim < v.Rstride) load_centroid_head(R, tid, row);   // requested before anything else
   const int M = v.M[u], N = v.N[u];
   if (N >= v.Ncap || M <= 0) {
     if (tid == 0) v.err[u] |= DYNAKV_ERR_TOKENS;
@@ -45,25 +48,29 @@ __global__ __launch_bounds__(256) void append_kernel(View v, const void* kin, co
   if (tid < kHeadDim) kd[tid] = (double)load_elem(kin, (size_t)u * kHeadDim + tid, v.dtype);
   __syncthreads();
   const size_t cbase = (size_t)u * v.Mcap;
-  // nearest centre (squared Euclidean distance)
+  // nearest centre (squared Euclidean distance); lane = cluster, 16 contiguous bytes per lane and load
   double best = __builtin_inf();
   int arg = -1;
   for (int j = tid; j < M; j += 256) {
-    const f4* r = (const f4*)(v.R + (cbase + j) * kHeadDim);
+    if (j != tid) load_centroid_head(R, j, row);
     double acc = 0.0;
-#pragma unroll 2
-    for (int d4 = 0; d4 < kHeadDim / 4; ++d4) {
-      const f4 rv = r[d4];
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const double t = kd[d4 * 4 + e] - (double)rv[e];
-        acc = fma(t, t, acc);
-      }
-    }
+    for_each_coord(R, j, row, [&](int d, float rv) {
+      const double t = kd[d] - (double)rv;
+      acc = fma(t, t, acc);
+    });
     if (acc < best || arg < 0) { best = acc; arg = j; }
   }
   block_arg_reduce<false>(best, arg, sv, si);
   const int j = si[0];
+  __syncthreads();
+  // UpdateVar, element-wise part: delta_d = k_d - r_d, r'_d = r_d + delta_d / n'
+  const int n1 = v.cn[cbase + j] + 1;
+  if (tid < kHeadDim) {
+    const double r = (double)R[r_index(j, tid)];
+    const double dl = kd[tid] - r;
+    delta[tid] = dl;
+    r1[tid] = r + dl / (double)n1;
+  }
   __syncthreads();
   if (tid == 0) {
     const int sz = v.cn[cbase + j] + v.cb[cbase + j];
@@ -77,8 +84,8 @@ __global__ __launch_bounds__(256) void append_kernel(View v, const void* kin, co
         ok = 0;
       } else {
         v.pnext[(size_t)u * v.Pcap + np] = -1;
-        if (sz == 0) v.chead[cbase + j] = np;
-        else v.pnext[(size_t)u * v.Pcap + page] = np;
+        if (sz != 0) v.pnext[(size_t)u * v.Pcap + page] = np;
+        if (sz / kPageTokens < kInlinePages) v.cpg[(cbase + j) * kInlinePages + sz / kPageTokens] = np;
         v.ctail[cbase + j] = np;
         page = np;
       }
@@ -89,16 +96,9 @@ __global__ __launch_bounds__(256) void append_kernel(View v, const void* kin, co
       if (v.cflag[cbase + j]) {
         v.cb[cbase + j] += 1;             // goes to the buffer of a flagged cluster
       } else {
-        // UpdateVar: tentative n', r', M2' from (n, r, M2) and the new entry
-        const float* r = v.R + (cbase + j) * kHeadDim;
-        const int n1 = v.cn[cbase + j] + 1;
+        // UpdateVar, the running part: M2' = M2 + sum_d delta_d * (k_d - r'_d), left to right
         double M2 = v.cM2[cbase + j];
-        for (int d = 0; d < kHeadDim; ++d) {
-          const double delta = kd[d] - (double)r[d];
-          const double rd = (double)r[d] + delta / (double)n1;
-          r1[d] = rd;
-          M2 = fma(delta, kd[d] - rd, M2);
-        }
+        for (int d = 0; d < kHeadDim; ++d) M2 = fma(delta[d], kd[d] - r1[d], M2);
         const double var1 = M2 / (double)n1;
         bool trig = false;
         if (n1 >= 2) {
@@ -122,110 +122,171 @@ __global__ __launch_bounds__(256) void append_kernel(View v, const void* kin, co
   }
   __syncthreads();
   if (!s_ok) return;
-  if (s_commit && tid < kHeadDim) v.R[(cbase + j) * kHeadDim + tid] = (float)r1[tid];
+  if (s_commit && tid < kHeadDim) R[r_index(j, tid)] = (float)r1[tid];
   char* pg = page_ptr(v, u, s_page);
   if (tid < kHeadDim) copy_elem(pg, k_index(v.dtype, s_slot, tid), kin, (size_t)u * kHeadDim + tid, v.dtype);
   else copy_elem(pg, v_index(v.dtype, s_slot, tid - kHeadDim), vin, (size_t)u * kHeadDim + tid - kHeadDim, v.dtype);
 }
 
 // ------------------------------------------------------------------------------------------- split
+// Keys of the cluster being split are staged once in LDS (up to 128 members of a 16-bit type, 64 of
+// float32; rows padded so that "lane = member" and "lane = coordinate" reads are both conflict-free);
+// larger clusters fall back to reading their pages.
+constexpr int kStageRow16 = kHeadDim + 8, kStageRow32 = kHeadDim + 4;
+constexpr int kStageBytes = 128 * kStageRow16 * 2;
+
 struct SplitSmem {
   int chain[kMaxSplitMembers / kPageTokens];      // pages of the cluster being split
   int newpg[kMaxSplitMembers / kPageTokens + 2];  // pages of the two children
   unsigned char side[kMaxSplitMembers];
-  unsigned short rank[kMaxSplitMembers];           // rank of every member inside its child
+  unsigned short perm[kMaxSplitMembers];           // members of the staying child in order, then of the moved one
   double cA[kHeadDim], cB[kHeadDim];
   float rA[kHeadDim], rB[kHeadDim];
   double sv[256];
   int si[256];
+  double dl[128];                                  // member distances of a staged cluster
   int scan[64];
   int flag, count, nchain;
+  int M, nflag, a_top, a_bump;                     // the unit's counters, held here for the whole kernel
   double m2[2];
+  alignas(16) unsigned char stage[kStageBytes];
 };
 
-// squared distance of the key in (page, slot) to a float64 centre
-__device__ inline double sqdist_page_d(const View& v, int u, int page, int slot, const double* c) {
-  const char* pg = page_ptr(v, u, page);
-  double acc = 0.0;
-  for (int d = 0; d < kHeadDim; ++d) {
-    const double t = (double)load_elem(pg, k_index(v.dtype, slot, d), v.dtype) - c[d];
-    acc = fma(t, t, acc);
+// Access to the keys of the members, by member index: 8 consecutive coordinates at a time, or one.
+template <int DT, bool STAGED>
+struct Keys {
+  const View& v; const SplitSmem& s; int u;
+  __device__ void get8(int i, int d8, float (&x)[8]) const {
+    if constexpr (STAGED && DT == DYNAKV_F32) {
+      const f4* p = (const f4*)((const float*)s.stage + i * kStageRow32 + d8 * 8);
+      const f4 a = p[0], b = p[1];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { x[e] = a[e]; x[4 + e] = b[e]; }
+    } else if constexpr (STAGED) {
+      const uint4 w = *(const uint4*)((const uint16_t*)s.stage + i * kStageRow16 + d8 * 8);
+      const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const uint16_t h = (uint16_t)(ww[e >> 1] >> ((e & 1) * 16));
+        x[e] = DT == DYNAKV_F16 ? f16_to_float(h) : bf16_to_float(h);
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) x[e] = page_key(v, u, s.chain[i >> 4], i & 15, d8 * 8 + e);
+    }
   }
-  return acc;
-}
-__device__ inline double sqdist_page_f(const View& v, int u, int page, int slot, const float* c) {
-  const char* pg = page_ptr(v, u, page);
-  double acc = 0.0;
-  for (int d = 0; d < kHeadDim; ++d) {
-    const double t = (double)load_elem(pg, k_index(v.dtype, slot, d), v.dtype) - (double)c[d];
-    acc = fma(t, t, acc);
+  __device__ float get(int i, int d) const {
+    if constexpr (STAGED && DT == DYNAKV_F32) return ((const float*)s.stage)[i * kStageRow32 + d];
+    else if constexpr (STAGED) {
+      const uint16_t h = ((const uint16_t*)s.stage)[i * kStageRow16 + d];
+      return DT == DYNAKV_F16 ? f16_to_float(h) : bf16_to_float(h);
+    } else return page_key(v, u, s.chain[i >> 4], i & 15, d);
   }
-  return acc;
+};
+
+// Left-to-right float64 squared distances of member i to one or two centres (C = double or float).
+template <class K, class C>
+__device__ inline void sqdist_member(const K& ks, int i, const C* cA, const C* cB, double& dA, double& dB) {
+  double a = 0.0, b = 0.0;
+#pragma unroll 4
+  for (int d8 = 0; d8 < kHeadDim / 8; ++d8) {
+    float x[8];
+    ks.get8(i, d8, x);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const double xd = (double)x[e];
+      const double ta = xd - (double)cA[d8 * 8 + e];
+      a = fma(ta, ta, a);
+      if (cB) {
+        const double tb = xd - (double)cB[d8 * 8 + e];
+        b = fma(tb, tb, b);
+      }
+    }
+  }
+  dA = a; dB = b;
 }
 
-// Exact statistics of `n` members stored in order in pages pg[0..]: float32 mean into r (LDS) and to the
-// cluster record `id`, M2 about that mean into *m2.  Threads [t0, t0+128) own the coordinates; the
-// member distances go through dist[q0 .. q0+n).  Called by the whole block (contains barriers).
-__device__ inline void child_stats(const View& v, int u, SplitSmem& s, const int* pg, int n, int id, float* r,
-                                   int t0, int q0, double* m2) {
-  const int tid = threadIdx.x;
-  if (tid >= t0 && tid < t0 + kHeadDim) {
-    const int d = tid - t0;
+// Exact statistics of both children at once: members perm[0 .. nS) form cluster idS, perm[nS .. m) cluster idM
+// (idM < 0: there is no second child).  Threads 0..127 own the coordinates of the first, 128..255 of the
+// second.  float32 means go to rA / rB (LDS) and to the centroid table, M2 about those means to s.m2[].
+template <class K>
+__device__ inline void children_stats(const View& v, int u, SplitSmem& s, const K& ks, bool staged, int nS, int m,
+                                      int idS, int idM) {
+  const int tid = threadIdx.x, d = tid & (kHeadDim - 1), c = tid >> 7;
+  const int q0 = c ? nS : 0, q1 = c ? m : nS, id = c ? idM : idS;
+  float* r = c ? s.rB : s.rA;
+  {
     double sum = 0.0;
-    for (int i = 0; i < n; ++i) sum += (double)page_key(v, u, pg[i >> 4], i & 15, d);
-    r[d] = n ? (float)(sum / (double)n) : 0.f;
-    v.R[((size_t)u * v.Mcap + id) * kHeadDim + d] = r[d];
+#pragma unroll 8
+    for (int q = q0; q < q1; ++q) sum += (double)ks.get(s.perm[q], d);
+    r[d] = q1 > q0 ? (float)(sum / (double)(q1 - q0)) : 0.f;
+    if (id >= 0) unit_R(v, u)[r_index(id, d)] = r[d];
   }
   __syncthreads();
-  double* dist = v.dist + (size_t)u * v.Ncap + q0;
-  for (int i = tid; i < n; i += 256) dist[i] = sqdist_page_f(v, u, pg[i >> 4], i & 15, r);
+  double* dist = staged ? s.dl : v.dist + (size_t)u * v.Ncap;
+  for (int q = tid; q < m; q += 256) {
+    double da, db;
+    sqdist_member<K, float>(ks, s.perm[q], q < nS ? s.rA : s.rB, nullptr, da, db);
+    dist[q] = da;
+  }
   __syncthreads();
-  if (tid == t0) {
+  if (d == 0) {
     double acc = 0.0;
-    for (int i = 0; i < n; ++i) acc += dist[i];
-    *m2 = acc;
+#pragma unroll 8
+    for (int q = q0; q < q1; ++q) acc += dist[q];
+    s.m2[c] = acc;
   }
   __syncthreads();
 }
 
 // Splits cluster j of unit u (2-means; Algorithm 1 SplitCluster).  Whole block; all branches uniform.
-__device__ void split_cluster(const View& v, int u, int j, SplitSmem& s) {
+template <int DT, bool STAGED>
+__device__ __noinline__ void split_cluster_impl(const View& v, int u, int j, int m, SplitSmem& s) {
   const int tid = threadIdx.x;
   const size_t cbase = (size_t)u * v.Mcap;
-  const int m = v.cn[cbase + j] + v.cb[cbase + j];
-  if (m > kMaxSplitMembers) {
-    if (tid == 0) v.err[u] |= DYNAKV_ERR_SPLIT_SIZE;
-    return;
+  constexpr int kEs = DT == DYNAKV_F32 ? 4 : 2;
+  constexpr int kChunks = kHeadDim * kEs / 16;                      // 16-byte chunks per key
+  constexpr int kRowBytes = (DT == DYNAKV_F32 ? kStageRow32 : kStageRow16) * kEs;
+  char* const pool = v.pages + (size_t)u * v.Pcap * ((size_t)kPageElems * kEs);
+  const Keys<DT, STAGED> ks{v, s, u};
+  // byte offset of 16-byte chunk c of the key in `slot` inside its page
+  auto kchunk = [](int slot, int c) -> size_t {
+    return (size_t)(DT == DYNAKV_F32 ? k_index32(slot, 4 * c) : k_index16(slot, 8 * c)) * kEs;
+  };
+  if constexpr (STAGED) {                  // one pass over the cluster's keys; every later pass reads LDS
+#pragma unroll 4
+    for (int t = tid; t < m * kChunks; t += 256) {
+      const int i = t / kChunks, c = t % kChunks;
+      *(uint4*)(s.stage + (size_t)i * kRowBytes + c * 16) =
+          *(const uint4*)(pool + (size_t)s.chain[i >> 4] * (kPageElems * kEs) + kchunk(i & 15, c));
+    }
+    __syncthreads();
   }
-  __syncthreads();
-  if (tid == 0) {
-    int p = v.chead[cbase + j], k = 0;
-    while (p >= 0 && k < kMaxSplitMembers / kPageTokens) { s.chain[k++] = p; p = v.pnext[(size_t)u * v.Pcap + p]; }
-    s.nchain = k;
-  }
-  __syncthreads();
   bool can_split = m >= 2;
   if (can_split) {
     // seeds: A = member farthest from the mean of all members, B = member farthest from A
     if (tid < kHeadDim) {
       double sum = 0.0;
-      for (int i = 0; i < m; ++i) sum += (double)page_key(v, u, s.chain[i >> 4], i & 15, tid);
+#pragma unroll 8
+      for (int i = 0; i < m; ++i) sum += (double)ks.get(i, tid);
       s.cA[tid] = sum / (double)m;
     }
     __syncthreads();
-    double bv = -1.0; int bi = -1;
+    double bv = -1.0, dummy; int bi = -1;
     for (int i = tid; i < m; i += 256) {
-      const double t = sqdist_page_d(v, u, s.chain[i >> 4], i & 15, s.cA);
+      double t;
+      sqdist_member<decltype(ks), double>(ks, i, s.cA, nullptr, t, dummy);
       if (t > bv) { bv = t; bi = i; }
     }
     block_arg_reduce<true>(bv, bi, s.sv, s.si);
     const int a = s.si[0];
     __syncthreads();
-    if (tid < kHeadDim) s.cB[tid] = (double)page_key(v, u, s.chain[a >> 4], a & 15, tid);
+    if (tid < kHeadDim) s.cB[tid] = (double)ks.get(a, tid);
     __syncthreads();
     bv = -1.0; bi = -1;
     for (int i = tid; i < m; i += 256) {
-      const double t = sqdist_page_d(v, u, s.chain[i >> 4], i & 15, s.cB);
+      double t;
+      sqdist_member<decltype(ks), double>(ks, i, s.cB, nullptr, t, dummy);
       if (t > bv) { bv = t; bi = i; }
     }
     block_arg_reduce<true>(bv, bi, s.sv, s.si);
@@ -236,16 +297,15 @@ __device__ void split_cluster(const View& v, int u, int j, SplitSmem& s) {
     if (can_split) {
       if (tid < kHeadDim) { s.cA[tid] = s.cB[tid]; }
       __syncthreads();
-      if (tid < kHeadDim) s.cB[tid] = (double)page_key(v, u, s.chain[b >> 4], b & 15, tid);
+      if (tid < kHeadDim) s.cB[tid] = (double)ks.get(b, tid);
       for (int i = tid; i < m; i += 256) s.side[i] = 2;
+      if (tid == 0) { s.flag = 0; s.count = 0; }
       __syncthreads();
       for (int it = 0; it < 16; ++it) {
-        if (tid == 0) { s.flag = 0; s.count = 0; }
-        __syncthreads();
         int changed = 0, na = 0;
         for (int i = tid; i < m; i += 256) {
-          const double dA = sqdist_page_d(v, u, s.chain[i >> 4], i & 15, s.cA);
-          const double dB = sqdist_page_d(v, u, s.chain[i >> 4], i & 15, s.cB);
+          double dA, dB;
+          sqdist_member<decltype(ks), double>(ks, i, s.cA, s.cB, dA, dB);
           const unsigned char ns = dA <= dB ? 0 : 1;   // tie -> side A
           changed |= ns != s.side[i];
           s.side[i] = ns;
@@ -262,27 +322,30 @@ __device__ void split_cluster(const View& v, int u, int j, SplitSmem& s) {
         {
           const int d = tid & (kHeadDim - 1);
           const unsigned char mine = tid < kHeadDim ? 0 : 1;
-          double sum = 0.0;
-          for (int i = 0; i < m; ++i)
-            if (s.side[i] == mine) sum += (double)page_key(v, u, s.chain[i >> 4], i & 15, d);
+          double sum = 0.0;             // adding +0.0 for the other side's members leaves the sum unchanged
+#pragma unroll 8
+          for (int i = 0; i < m; ++i) sum += s.side[i] == mine ? (double)ks.get(i, d) : 0.0;
           if (mine == 0) s.cA[d] = sum / (double)nA;
           else s.cB[d] = sum / (double)(m - nA);
         }
+        if (tid == 0) { s.flag = 0; s.count = 0; }
         __syncthreads();
       }
     }
   }
   if (!can_split) {                       // unflag with exact statistics of the whole cluster
-    child_stats(v, u, s, s.chain, m, j, s.rA, 0, 0, &s.m2[0]);
+    for (int i = tid; i < m; i += 256) s.perm[i] = (unsigned short)i;
+    __syncthreads();
+    children_stats(v, u, s, ks, STAGED, m, m, j, -1);
     if (tid == 0) {
       v.cn[cbase + j] = m; v.cb[cbase + j] = 0; v.cflag[cbase + j] = 0; v.cM2[cbase + j] = s.m2[0];
-      v.nflag[u] -= 1;
+      s.nflag -= 1;
       v.counters[(size_t)u * kCounters + 1] += 1;
     }
     __syncthreads();
     return;
   }
-  const int M = v.M[u];
+  const int M = s.M;
   if (M >= v.Mcap) {
     if (tid == 0) v.err[u] |= DYNAKV_ERR_CLUSTERS;
     return;
@@ -295,50 +358,92 @@ __device__ void split_cluster(const View& v, int u, int j, SplitSmem& s) {
   for (int i = lo; i < hi; ++i) mine += s.side[i] == keep;
   int nS;
   int rs = block_excl_scan(mine, s.scan, nS);
-  int rm = lo - rs;
-  for (int i = lo; i < hi; ++i) s.rank[i] = (unsigned short)(s.side[i] == keep ? rs++ : rm++);
+  int rm = nS + lo - rs;
+  for (int i = lo; i < hi; ++i) s.perm[s.side[i] == keep ? rs++ : rm++] = (unsigned short)i;
   const int nM = m - nS;
   const int pS = (nS + kPageTokens - 1) / kPageTokens, pM = (nM + kPageTokens - 1) / kPageTokens;
-  if (pages_available(v, u) < pS + pM) {
+  const int need = pS + pM, top = s.a_top, bump = s.a_bump;
+  if (top + (v.Pcap - bump) < need) {
     if (tid == 0) v.err[u] |= DYNAKV_ERR_TOKENS;
     return;
   }
+  // fresh pages for both children (recycled pages first); the parent's pages are recycled afterwards
+  const int from_free = min(need, top);
+  for (int k = tid; k < need; k += 256)
+    s.newpg[k] = k < from_free ? v.freelist[(size_t)u * v.Pcap + top - 1 - k] : bump + (k - from_free);
   __syncthreads();
-  if (tid == 0) {
-    for (int k = 0; k < pS + pM; ++k) s.newpg[k] = alloc_page(v, u);
-    for (int k = 0; k < pS; ++k) v.pnext[(size_t)u * v.Pcap + s.newpg[k]] = k + 1 < pS ? s.newpg[k + 1] : -1;
-    for (int k = 0; k < pM; ++k) v.pnext[(size_t)u * v.Pcap + s.newpg[pS + k]] = k + 1 < pM ? s.newpg[pS + k + 1] : -1;
+  for (int k = tid; k < need; k += 256) {
+    const bool last = k == pS - 1 || k == need - 1;
+    v.pnext[(size_t)u * v.Pcap + s.newpg[k]] = last ? -1 : s.newpg[k + 1];
   }
-  __syncthreads();
-  // move every entry to its child's pages (both children get fresh pages; the old ones are recycled)
-  for (int i = 0; i < m; ++i) {
-    const int r = s.rank[i];
-    const int dpage = s.newpg[(s.side[i] == keep ? 0 : pS) + (r >> 4)], dslot = r & 15;
-    const int spage = s.chain[i >> 4], sslot = i & 15;
-    char* dp = page_ptr(v, u, dpage);
-    const char* sp = page_ptr(v, u, spage);
-    if (tid < kHeadDim) copy_elem(dp, k_index(v.dtype, dslot, tid), sp, k_index(v.dtype, sslot, tid), v.dtype);
-    else copy_elem(dp, v_index(v.dtype, dslot, tid - kHeadDim), sp, v_index(v.dtype, sslot, tid - kHeadDim), v.dtype);
-    if (tid == 0)
-      v.ppos[((size_t)u * v.Pcap + dpage) * kPageTokens + dslot] = v.ppos[((size_t)u * v.Pcap + spage) * kPageTokens + sslot];
+  // keys in 16-byte chunks, values element by element (their page layout interleaves four tokens)
+#pragma unroll 4
+  for (int t = tid; t < m * kChunks; t += 256) {
+    const int q = t / kChunks, c = t % kChunks;
+    const int i = s.perm[q];
+    const int r = q < nS ? q : q - nS;
+    const int dpage = s.newpg[(q < nS ? 0 : pS) + (r >> 4)];
+    uint4 w;
+    if constexpr (STAGED) w = *(const uint4*)(s.stage + (size_t)i * kRowBytes + c * 16);
+    else w = *(const uint4*)(pool + (size_t)s.chain[i >> 4] * (kPageElems * kEs) + kchunk(i & 15, c));
+    *(uint4*)(pool + (size_t)dpage * (kPageElems * kEs) + kchunk(r & 15, c)) = w;
   }
-  __syncthreads();
-  child_stats(v, u, s, s.newpg, nS, j, s.rA, 0, 0, &s.m2[0]);
-  child_stats(v, u, s, s.newpg + pS, nM, M, s.rB, kHeadDim, nS, &s.m2[1]);
+#pragma unroll 8
+  for (int t = tid; t < m * kHeadDim; t += 256) {
+    const int q = t >> 7, d = t & 127;
+    const int i = s.perm[q];
+    const int r = q < nS ? q : q - nS;
+    const int dpage = s.newpg[(q < nS ? 0 : pS) + (r >> 4)];
+    copy_elem(pool + (size_t)dpage * (kPageElems * kEs), v_index(DT, r & 15, d),
+              pool + (size_t)s.chain[i >> 4] * (kPageElems * kEs), v_index(DT, i & 15, d), DT);
+    if (d == 0)
+      v.ppos[((size_t)u * v.Pcap + dpage) * kPageTokens + (r & 15)] =
+          v.ppos[((size_t)u * v.Pcap + s.chain[i >> 4]) * kPageTokens + (i & 15)];
+  }
+  children_stats(v, u, s, ks, STAGED, nS, m, j, M);
+  for (int k = tid; k < s.nchain; k += 256) v.freelist[(size_t)u * v.Pcap + (top - from_free) + k] = s.chain[k];
+  if (tid < kInlinePages) {
+    v.cpg[(cbase + j) * kInlinePages + tid] = tid < pS ? s.newpg[tid] : -1;
+    v.cpg[(cbase + M) * kInlinePages + tid] = tid < pM ? s.newpg[pS + tid] : -1;
+  }
   if (tid == 0) {
     v.cn[cbase + j] = nS; v.cb[cbase + j] = 0; v.cflag[cbase + j] = 0; v.cM2[cbase + j] = s.m2[0];
-    v.chead[cbase + j] = s.newpg[0]; v.ctail[cbase + j] = s.newpg[pS - 1];
+    v.ctail[cbase + j] = s.newpg[pS - 1];
     v.cn[cbase + M] = nM; v.cb[cbase + M] = 0; v.cflag[cbase + M] = 0; v.cM2[cbase + M] = s.m2[1];
-    v.chead[cbase + M] = s.newpg[pS]; v.ctail[cbase + M] = s.newpg[pS + pM - 1];
+    v.ctail[cbase + M] = s.newpg[pS + pM - 1];
     v.in_req[cbase + M] = 0;
-    v.M[u] = M + 1;
-    for (int k = 0; k < s.nchain; ++k) free_page(v, u, s.chain[k]);
-    v.nflag[u] -= 1;
+    s.M = M + 1;
+    s.a_top = top - from_free + s.nchain;
+    s.a_bump = bump + (need - from_free);
+    s.nflag -= 1;
     v.counters[(size_t)u * kCounters + 0] += 1;
   }
   __syncthreads();
 }
 
+template <int DT>
+__device__ void split_cluster(const View& v, int u, int j, SplitSmem& s) {
+  const int tid = threadIdx.x;
+  const size_t cbase = (size_t)u * v.Mcap;
+  const int m = v.cn[cbase + j] + v.cb[cbase + j];
+  if (m > kMaxSplitMembers) {
+    if (tid == 0) v.err[u] |= DYNAKV_ERR_SPLIT_SIZE;
+    return;
+  }
+  __syncthreads();
+  const int npg = (m + kPageTokens - 1) / kPageTokens;
+  if (tid < kInlinePages && tid < npg) s.chain[tid] = v.cpg[(cbase + j) * kInlinePages + tid];
+  __syncthreads();
+  if (tid == 0) {
+    for (int k = kInlinePages; k < npg; ++k) s.chain[k] = v.pnext[(size_t)u * v.Pcap + s.chain[k - 1]];
+    s.nchain = npg;
+  }
+  __syncthreads();
+  if (m <= (DT == DYNAKV_F32 ? 64 : 128)) split_cluster_impl<DT, true>(v, u, j, m, s);
+  else split_cluster_impl<DT, false>(v, u, j, m, s);
+}
+
+template <int DT>
 __global__ __launch_bounds__(256) void split_kernel(View v) {
   __shared__ SplitSmem s;
   __shared__ int s_min;
@@ -347,6 +452,7 @@ __global__ __launch_bounds__(256) void split_kernel(View v) {
   if (v.nflag[u] == 0) return;
   const size_t cbase = (size_t)u * v.Mcap;
   const int M0 = v.M[u];
+  if (tid == 0) { s.M = M0; s.nflag = v.nflag[u]; s.a_top = v.free_top[u]; s.a_bump = v.bump[u]; }
   // delayed splits: flagged clusters that the last retrieval selected, ascending id
   int cursor = 0;
   while (true) {
@@ -358,13 +464,13 @@ __global__ __launch_bounds__(256) void split_kernel(View v) {
     const int j = s_min;
     __syncthreads();
     if (j == 0x7FFFFFFF) break;
-    split_cluster(v, u, j, s);
+    split_cluster<DT>(v, u, j, s);
     __syncthreads();
     cursor = j + 1;
   }
   // forced split once the buffers hold B_max entries: the flagged cluster with the fullest buffer
-  if (v.Bmax > 0) {
-    const int M = v.M[u];
+  if (v.Bmax > 0 && s.nflag > 0) {
+    const int M = s.M;
     if (tid == 0) s_tot = 0;
     __syncthreads();
     double bv = -1.0; int bi = -1;
@@ -382,9 +488,11 @@ __global__ __launch_bounds__(256) void split_kernel(View v) {
     __syncthreads();
     if (arg >= 0 && total >= v.Bmax) {
       if (tid == 0) v.counters[(size_t)u * kCounters + 2] += 1;
-      split_cluster(v, u, arg, s);
+      split_cluster<DT>(v, u, arg, s);
     }
   }
+  __syncthreads();
+  if (tid == 0) { v.M[u] = s.M; v.nflag[u] = s.nflag; v.free_top[u] = s.a_top; v.bump[u] = s.a_bump; }
 }
 
 // ------------------------------------------------------------------------------------------- export
@@ -415,9 +523,13 @@ __global__ __launch_bounds__(1024) void export_kernel(View v, dynakv_state_t o) 
     if (o.scores) o.scores[cbase + j] = in ? v.score[cbase + j] : 0.f;
     if (o.selected) o.selected[cbase + j] = j < v.n_sel[u] ? v.sel_ids[cbase + j] : -1;
   }
-  if (o.centroids)
-    for (size_t t = tid; t < (size_t)v.Mcap * kHeadDim; t += 1024)
-      o.centroids[cbase * kHeadDim + t] = t < (size_t)M * kHeadDim ? v.R[cbase * kHeadDim + t] : 0.f;
+  if (o.centroids) {
+    const float* R = unit_R(v, u);
+    for (size_t t = tid; t < (size_t)v.Mcap * kHeadDim; t += 1024) {
+      const int j = (int)(t >> 7), d = (int)(t & 127);
+      o.centroids[cbase * kHeadDim + t] = j < M ? R[r_index(j, d)] : 0.f;
+    }
+  }
   // member lists
   int sz[8], tot = 0;
   for (int k = 0; k < 8; ++k) {
@@ -437,13 +549,14 @@ __global__ __launch_bounds__(1024) void export_kernel(View v, dynakv_state_t o) 
   __syncthreads();
   if (o.members)
     for (int j = tid; j < M; j += 1024) {
-      int w = v.tok_off[cbase + j], left = v.cn[cbase + j] + v.cb[cbase + j], page = v.chead[cbase + j];
-      while (left > 0 && page >= 0) {
+      int w = v.tok_off[cbase + j], left = v.cn[cbase + j] + v.cb[cbase + j], page = -1;
+      for (int k = 0; left > 0; ++k) {
+        page = cluster_page(v, u, cbase + j, k, page);
+        if (page < 0) break;
         const int nv = min(left, kPageTokens);
         for (int sl = 0; sl < nv; ++sl)
           o.members[(size_t)u * v.Ncap + w + sl] = v.ppos[((size_t)u * v.Pcap + page) * kPageTokens + sl];
         w += nv; left -= nv;
-        page = v.pnext[(size_t)u * v.Pcap + page];
       }
     }
   if (o.gathered) {
@@ -463,7 +576,9 @@ hipError_t launch_append(const View& v, const void* k, const void* val, hipStrea
   return hipGetLastError();
 }
 hipError_t launch_split(const View& v, hipStream_t st) {
-  split_kernel<<<v.U, 256, 0, st>>>(v);
+  if (v.dtype == DYNAKV_F32) split_kernel<DYNAKV_F32><<<v.U, 256, 0, st>>>(v);
+  else if (v.dtype == DYNAKV_F16) split_kernel<DYNAKV_F16><<<v.U, 256, 0, st>>>(v);
+  else split_kernel<DYNAKV_BF16><<<v.U, 256, 0, st>>>(v);
   return hipGetLastError();
 }
 hipError_t launch_export(const View& v, const dynakv_state_t& dst, hipStream_t st) {

@@ -12,10 +12,17 @@ namespace dynakv {
 namespace {
 
 // ------------------------------------------------------------------------------------------- scores
+// Lane = cluster: the centroid table is lane-interleaved, so every load below is 1 KB contiguous per wavefront.
 template <int GP>
 __global__ __launch_bounds__(256) void score_kernel(View v, const void* Q) {
   __shared__ double qs[kHeadDim][GP];
   const int u = blockIdx.y, tid = threadIdx.x;
+  const int j = blockIdx.x * 256 + tid;
+  const float* R = unit_R(v, u);
+  // the first quarter of the row is requested before anything else (rows up to the table's padded end exist)
+  f4 row[8];
+  const bool in_table = (size_t)(j | 63) * kHeadDim < v.Rstride;
+  if (in_table) load_centroid_head(R, j, row);
   const int M = v.M[u];
   if (blockIdx.x * 256 >= M) return;
   for (int t = tid; t < GP * kHeadDim; t += 256) {
@@ -23,22 +30,16 @@ __global__ __launch_bounds__(256) void score_kernel(View v, const void* Q) {
     qs[d][g] = g < v.G ? (double)load_elem(Q, ((size_t)u * v.G + g) * kHeadDim + d, v.dtype) : 0.0;
   }
   __syncthreads();
-  const int j = blockIdx.x * 256 + tid;
-  if (j >= M) return;
-  const f4* r = (const f4*)(v.R + ((size_t)u * v.Mcap + j) * kHeadDim);
+  if ((j & ~63) >= M) return;                       // whole wavefront past the last cluster
   double acc[GP];
 #pragma unroll
   for (int g = 0; g < GP; ++g) acc[g] = 0.0;
-#pragma unroll 2
-  for (int d4 = 0; d4 < kHeadDim / 4; ++d4) {
-    const f4 rv = r[d4];
+  for_each_coord(R, j, row, [&](int d, float rv) {
+    const double rd = (double)rv;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const double rd = (double)rv[e];
-#pragma unroll
-      for (int g = 0; g < GP; ++g) acc[g] = fma(qs[d4 * 4 + e][g], rd, acc[g]);
-    }
-  }
+    for (int g = 0; g < GP; ++g) acc[g] = fma(qs[d][g], rd, acc[g]);
+  });
+  if (j >= M) return;
   double red = acc[0];
 #pragma unroll
   for (int g = 1; g < GP; ++g)
@@ -131,13 +132,14 @@ __global__ __launch_bounds__(1024) void select_kernel(View v, int budget) {
     v.in_req[cb + id] = p < cut;
     if (p < cut) {
       int left = truncated ? budget : v.cn[cb + id] + v.cb[cb + id];
-      int page = v.chead[cb + id], w = v.pg_off[cb + p], t0 = v.tok_off[cb + p];
-      while (left > 0 && page >= 0) {
+      int page = -1, w = v.pg_off[cb + p], t0 = v.tok_off[cb + p];
+      for (int k = 0; left > 0; ++k) {
+        page = cluster_page(v, u, cb + id, k, page);
+        if (page < 0) break;
         const int nv = min(left, kPageTokens);
         plist[w] = page * 32 + nv;
         poff[w] = t0;
         ++w; t0 += nv; left -= nv;
-        page = v.pnext[(size_t)u * v.Pcap + page];
       }
     }
   }
@@ -261,10 +263,8 @@ struct Frag16 {
 template <> struct Frag<DYNAKV_F16> : Frag16<false> {};
 template <> struct Frag<DYNAKV_BF16> : Frag16<true> {};
 
-constexpr int kWaves = 4;   // wavefronts per workgroup of gather_attend
-
-// Merges `n` partial results (running max in the log2 domain, denominator, 128 accumulators per head)
-// that sit `stride` floats apart, for head g and column dc.
+// Merges `n` partial results (running max in the log2 domain, denominator, one accumulator) that sit
+// `stride` floats apart.
 __device__ inline void merge_partials(const float* mx, const float* den, const float* acc, int n, int stride,
                                       float& M, float& L, float& O) {
   M = -__builtin_inff();
@@ -279,11 +279,46 @@ __device__ inline void merge_partials(const float* mx, const float* den, const f
   }
 }
 
-template <int DT>
-__global__ __launch_bounds__(kWaves * 64) void gather_attend_kernel(View v, const void* Q, float* out, float* lse) {
+// Per-wavefront running state of the online softmax.
+struct Softmax {
+  float m, l;
+  f4 acc[8];
+};
+
+// One page: S^T = K Q^T on the matrix cores, running max / rescale, O^T += V^T P^T.
+template <class F>
+__device__ inline void consume_page(Softmax& st, const typename F::KV& kv, const typename F::Qf& q, int nvalid, int lg,
+                                    float sc) {
+  const f4 sacc = F::qk(kv, q);
+  float s2[4], mx = -__builtin_inff();
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    s2[i] = (4 * lg + i) < nvalid ? sacc[i] * sc : -__builtin_inff();
+    mx = fmaxf(mx, s2[i]);
+  }
+  mx = fmaxf(mx, __shfl_xor(mx, 16));
+  mx = fmaxf(mx, __shfl_xor(mx, 32));
+  const float mn = fmaxf(st.m, mx);          // finite: every listed page has a valid token
+  const float alpha = __builtin_amdgcn_exp2f(st.m - mn);
+  float pr[4], ps = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) { pr[i] = __builtin_amdgcn_exp2f(s2[i] - mn); ps += pr[i]; }
+  st.l = st.l * alpha + ps;
+  st.m = mn;
+#pragma unroll
+  for (int c = 0; c < 8; ++c) st.acc[c] *= alpha;
+  F::pv(st.acc, kv, pr);
+}
+
+// grid (S, U); NW wavefronts per workgroup; the unit's gather list is dealt page by page to the S * NW
+// wavefronts.  Each wavefront first fetches its own list entries with one gathered load (lane i holds the
+// entry of its i-th page), so page addresses never wait on a dependent load inside the loop; with PF the
+// next page's loads are issued before the current page is consumed.
+template <int DT, int NW, bool PF>
+__global__ __launch_bounds__(NW * 64) void gather_attend_kernel(View v, const void* Q, float* out, float* lse) {
   using F = Frag<DT>;
   constexpr int kPageBytes = kPageElems * (DT == DYNAKV_F32 ? 4 : 2);
-  __shared__ float sm_o[kWaves][16][kHeadDim + 2];   // per wave and head: accumulators, max, denominator
+  extern __shared__ float sm_o[];            // [NW][G][130]: accumulators, max, denominator per wave and head
   __shared__ int s_last;
   const int u = blockIdx.y, s = blockIdx.x, S = gridDim.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -296,74 +331,70 @@ __global__ __launch_bounds__(kWaves * 64) void gather_attend_kernel(View v, cons
   const char* pages = v.pages + (size_t)u * v.Pcap * kPageBytes;
   const float sc = v.scale_f * kLog2e;
 
-  float m = -__builtin_inff(), l = 0.f;
-  f4 acc[8];
+  Softmax st;
+  st.m = -__builtin_inff(); st.l = 0.f;
 #pragma unroll
-  for (int c = 0; c < 8; ++c) acc[c] = f4{0, 0, 0, 0};
+  for (int c = 0; c < 8; ++c) st.acc[c] = f4{0, 0, 0, 0};
 
-  const int stride = S * kWaves;
-  int p = s * kWaves + wave;
-  typename F::KV cur, nxt;
-  int nv_cur = 0, nv_nxt = 0;
-  if (p < nlist) {
-    const int e = plist[p];
-    nv_cur = e & 31;
-    F::load(cur, pages + (size_t)(e >> 5) * kPageBytes, lane, nv_cur);
-  }
-  while (p < nlist) {
-    const int pn = p + stride;
-    if (pn < nlist) {                       // next page's loads are in flight while this one is consumed
-      const int e = plist[pn];
-      nv_nxt = e & 31;
-      F::load(nxt, pages + (size_t)(e >> 5) * kPageBytes, lane, nv_nxt);
+  const int stride = S * NW, p0 = s * NW + wave;
+  const int mine = p0 < nlist ? (nlist - p0 + stride - 1) / stride : 0;   // pages of this wavefront
+  for (int c0 = 0; c0 < mine; c0 += 64) {
+    const int cn = min(64, mine - c0);
+    const int e_l = lane < cn ? plist[p0 + (size_t)(c0 + lane) * stride] : 0;
+    if constexpr (PF) {
+      typename F::KV a, b;
+      int ea = __builtin_amdgcn_readlane(e_l, 0), eb = 0;
+      F::load(a, pages + (size_t)(ea >> 5) * kPageBytes, lane, ea & 31);
+      for (int i = 0; i < cn; i += 2) {
+        if (i + 1 < cn) {
+          eb = __builtin_amdgcn_readlane(e_l, i + 1);
+          F::load(b, pages + (size_t)(eb >> 5) * kPageBytes, lane, eb & 31);
+        }
+        consume_page<F>(st, a, q, ea & 31, lg, sc);
+        if (i + 1 < cn) {
+          if (i + 2 < cn) {
+            ea = __builtin_amdgcn_readlane(e_l, i + 2);
+            F::load(a, pages + (size_t)(ea >> 5) * kPageBytes, lane, ea & 31);
+          }
+          consume_page<F>(st, b, q, eb & 31, lg, sc);
+        }
+      }
+    } else {
+      for (int i = 0; i < cn; ++i) {
+        typename F::KV a;
+        const int e = __builtin_amdgcn_readlane(e_l, i);
+        F::load(a, pages + (size_t)(e >> 5) * kPageBytes, lane, e & 31);
+        consume_page<F>(st, a, q, e & 31, lg, sc);
+      }
     }
-    const f4 sacc = F::qk(cur, q);
-    float s2[4], mx = -__builtin_inff();
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      s2[i] = (4 * lg + i) < nv_cur ? sacc[i] * sc : -__builtin_inff();
-      mx = fmaxf(mx, s2[i]);
-    }
-    mx = fmaxf(mx, __shfl_xor(mx, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float mn = fmaxf(m, mx);          // finite: every listed page has a valid token
-    const float alpha = __builtin_amdgcn_exp2f(m - mn);
-    float pr[4], ps = 0.f;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) { pr[i] = __builtin_amdgcn_exp2f(s2[i] - mn); ps += pr[i]; }
-    l = l * alpha + ps;
-    m = mn;
-#pragma unroll
-    for (int c = 0; c < 8; ++c) acc[c] *= alpha;
-    F::pv(acc, cur, pr);
-    p = pn;
-    cur = nxt;
-    nv_cur = nv_nxt;
   }
+  float l = st.l;
   l += __shfl_xor(l, 16);
   l += __shfl_xor(l, 32);
 
   // workgroup merge
+  const int hs = kHeadDim + 2, ws = G * hs;
   if (g < G) {
+    float* o = sm_o + wave * ws + g * hs;
 #pragma unroll
     for (int c = 0; c < 8; ++c)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) sm_o[wave][g][16 * c + 4 * lg + i] = acc[c][i];
-    if (lg == 0) { sm_o[wave][g][kHeadDim] = m; sm_o[wave][g][kHeadDim + 1] = l; }
+      for (int i = 0; i < 4; ++i) o[16 * c + 4 * lg + i] = st.acc[c][i];
+    if (lg == 0) { o[kHeadDim] = st.m; o[kHeadDim + 1] = l; }
   }
   __syncthreads();
-  constexpr int kWs = 16 * (kHeadDim + 2);
-  float* part = v.part + ((size_t)u * S + s) * G * (kHeadDim + 2);
-  for (int t = threadIdx.x; t < G * kHeadDim; t += kWaves * 64) {
+  float* part = v.part + ((size_t)u * S + s) * ws;
+  for (int t = threadIdx.x; t < G * kHeadDim; t += NW * 64) {
     const int gg = t / kHeadDim, dc = t % kHeadDim;
+    const float* b = sm_o + gg * hs;
     float M, L, O;
-    merge_partials(&sm_o[0][gg][kHeadDim], &sm_o[0][gg][kHeadDim + 1], &sm_o[0][gg][dc], kWaves, kWs, M, L, O);
+    merge_partials(b + kHeadDim, b + kHeadDim + 1, b + dc, NW, ws, M, L, O);
     if (S == 1) {
       out[((size_t)u * G + gg) * kHeadDim + dc] = L > 0.f ? O / L : 0.f;
       if (lse && dc == 0) lse[(size_t)u * G + gg] = L > 0.f ? (M + __builtin_amdgcn_logf(L)) * kLn2 : -__builtin_inff();
     } else {
-      part[gg * (kHeadDim + 2) + dc] = O;
-      if (dc == 0) { part[gg * (kHeadDim + 2) + kHeadDim] = M; part[gg * (kHeadDim + 2) + kHeadDim + 1] = L; }
+      part[gg * hs + dc] = O;
+      if (dc == 0) { part[gg * hs + kHeadDim] = M; part[gg * hs + kHeadDim + 1] = L; }
     }
   }
   if (S == 1) return;
@@ -374,15 +405,29 @@ __global__ __launch_bounds__(kWaves * 64) void gather_attend_kernel(View v, cons
   __syncthreads();
   if (!s_last) return;
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-  const float* all = v.part + (size_t)u * S * G * (kHeadDim + 2);
-  const int ps = G * (kHeadDim + 2);
-  for (int t = threadIdx.x; t < G * kHeadDim; t += kWaves * 64) {
+  const float* all = v.part + (size_t)u * S * ws;
+  for (int t = threadIdx.x; t < G * kHeadDim; t += NW * 64) {
     const int gg = t / kHeadDim, dc = t % kHeadDim;
-    const float* b = all + gg * (kHeadDim + 2);
+    const float* b = all + gg * hs;
     float M, L, O;
-    merge_partials(b + kHeadDim, b + kHeadDim + 1, b + dc, S, ps, M, L, O);
+    merge_partials(b + kHeadDim, b + kHeadDim + 1, b + dc, S, ws, M, L, O);
     out[((size_t)u * G + gg) * kHeadDim + dc] = L > 0.f ? O / L : 0.f;
     if (lse && dc == 0) lse[(size_t)u * G + gg] = L > 0.f ? (M + __builtin_amdgcn_logf(L)) * kLn2 : -__builtin_inff();
+  }
+}
+
+template <int DT, int NW, bool PF>
+void launch_ga(const View& v, const void* Q, float* out, float* lse, hipStream_t st) {
+  const size_t lds = (size_t)NW * v.G * (kHeadDim + 2) * sizeof(float);
+  gather_attend_kernel<DT, NW, PF><<<dim3(v.S, v.U), NW * 64, lds, st>>>(v, Q, out, lse);
+}
+template <int DT>
+void launch_ga_dt(const View& v, const void* Q, float* out, float* lse, hipStream_t st) {
+  // 16 wavefronts hold one page each; fewer wavefronts keep a second page in flight instead
+  switch (v.NW) {
+    case 16: launch_ga<DT, 16, false>(v, Q, out, lse, st); break;
+    case 8: launch_ga<DT, 8, true>(v, Q, out, lse, st); break;
+    default: launch_ga<DT, 4, true>(v, Q, out, lse, st); break;
   }
 }
 
@@ -398,10 +443,9 @@ hipError_t launch_score_select(const View& v, const void* Q, int budget, hipStre
 }
 
 hipError_t launch_gather_attend(const View& v, const void* Q, float* out, float* lse, hipStream_t st) {
-  const dim3 grid(v.S, v.U);
-  if (v.dtype == DYNAKV_F32) gather_attend_kernel<DYNAKV_F32><<<grid, kWaves * 64, 0, st>>>(v, Q, out, lse);
-  else if (v.dtype == DYNAKV_F16) gather_attend_kernel<DYNAKV_F16><<<grid, kWaves * 64, 0, st>>>(v, Q, out, lse);
-  else gather_attend_kernel<DYNAKV_BF16><<<grid, kWaves * 64, 0, st>>>(v, Q, out, lse);
+  if (v.dtype == DYNAKV_F32) launch_ga<DYNAKV_F32, 4, true>(v, Q, out, lse, st);
+  else if (v.dtype == DYNAKV_F16) launch_ga_dt<DYNAKV_F16>(v, Q, out, lse, st);
+  else launch_ga_dt<DYNAKV_BF16>(v, Q, out, lse, st);
   return hipGetLastError();
 }
 
