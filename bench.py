@@ -124,7 +124,11 @@ def main():
     dt = time.perf_counter() - t0
     state = ix.dynakv_export_state(["counters", "error", "n_clusters", "n_tokens"])
     c1 = state["counters"].numpy()
-    assert int(state["error"].abs().sum()) == 0, "device error word set during the run"
+    if int(state["error"].abs().sum()) != 0:
+        bad = state["error"].nonzero().flatten().tolist()
+        sys.exit("bench.py: device error word set: units %s bits %s clusters %s tokens %s" %
+                 (bad[:8], state["error"][bad[:8]].tolist(), state["n_clusters"][bad[:8]].tolist(),
+                  state["n_tokens"][bad[:8]].tolist()))
     assert int(state["n_tokens"].min()) == spec.prefill + T
     gathered = int((c1[:, 4] - c0[:, 4]).sum())
     retrievals = int((c1[:, 5] - c0[:, 5]).sum())
@@ -157,7 +161,7 @@ def main():
                   "forced_splits": int(c1[:, 2].sum()), "input_generation_s": gen_s},
     }
     if not a.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline(spec, min(U, 16), 128, spec.budget)
+        res["cpu_baseline"] = cpu_baseline(spec, min(U, 32), 1536, spec.budget)
     print(json.dumps(res), flush=True)
 
 

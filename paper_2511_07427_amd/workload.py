@@ -32,7 +32,7 @@ class WorkloadSpec:
     spawn_every: int = 0
     spawn_n: int = 0
     var_alpha: float = 1.5
-    size_factor: float = 2.0
+    size_factor: float = 0.0
     buffer_max: int = 16
     kmeans_iters: int = 10
     head_dim: int = 128
@@ -55,17 +55,19 @@ class WorkloadSpec:
         return replace(self, **kw)
 
 
-# The five benchmark configurations.  Unstated knobs (drift of cfg 2 and 4, component counts of cfg 3-5,
-# the variance trigger of cfg 2-5) take the values the smallest configuration states or 1.5 x the
-# prefill objective; cfg 1 uses the size trigger only, as stated.
+# The five benchmark configurations.  Unstated knobs (drift of cfg 2 and 4, component counts of cfg 3-5) take
+# the values the smallest configuration states.  cfg 1 splits on size only (a cluster above twice the mean
+# size), as stated; cfg 2-5 split on the variance threshold of Algorithm 1 (tau = 1.5 x the prefill
+# objective per point): under drift the size rule feeds on itself (every split lowers the mean size).
 CONFIGS = {
-    "tiny": WorkloadSpec("tiny", "f32", 1, 4, 2048, 256, 32, 256, 16, 0.02, var_alpha=0.0, seed=251107000 + 1000),
+    "tiny": WorkloadSpec("tiny", "f32", 1, 4, 2048, 256, 32, 256, 16, 0.02, var_alpha=0.0, size_factor=2.0,
+                         seed=251107000 + 1000),
     "llama3_8b": WorkloadSpec("llama3_8b", "f16", 32 * 8, 4, 4096, 8192, 256, 1024, 64, 0.02, 1024, 2,
-                              seed=251107000 + 2000),
+                              max_cluster_factor=16, seed=251107000 + 2000),
     "qwen25_7b": WorkloadSpec("qwen25_7b", "bf16", 28 * 4, 7, 2048, 30000, 128, 2048, 64, 0.05,
                               max_cluster_factor=16, seed=251107000 + 3000),
     "batched16": WorkloadSpec("batched16", "f16", 16 * 8, 4, 8192, 24576, 512, 2048, 64, 0.02,
-                              seed=251107000 + 4000),
+                              max_cluster_factor=8, seed=251107000 + 4000),
     "long131k": WorkloadSpec("long131k", "bf16", 8, 8, 16384, 114688, 2048, 4096, 64, 0.1, 256, 1,
                              seed=251107000 + 5000),
 }
