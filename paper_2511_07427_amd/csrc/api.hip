@@ -96,6 +96,11 @@ size_t carve(const dynakv_config_t& c, char* base, View* out) {
   v.part = (float*)take(U * v.S * v.G * (kHeadDim + 2) * 4);
   v.labels = (int*)take(UN * 4); v.order = (int*)take(UN * 4); v.dist = (double*)take(UN * 8);
   v.koff = (int*)take(U * (v.Mcap + 1) * 4);
+  const size_t mpad = (size_t)((v.M0 + 31) / 32) * 32;
+  v.kmA_stride = mpad * kHeadDim * 3;                    // up to three 16-bit terms per coordinate
+  v.kmA = (uint16_t*)take(U * v.kmA_stride * 2);
+  v.hn = (float*)take(U * mpad * 4); v.rmax = (float*)take(U * 4);
+  v.nflagged = (int*)take(U * 4); v.has_empty = (int*)take(U * 4);
   if (out) *out = v;
   return off;
 }

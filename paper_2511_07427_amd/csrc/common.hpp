@@ -69,6 +69,13 @@ struct View {
   int* order;        // positions sorted by (label, position)
   double* dist;
   int* koff;         // [U][Mcap+1] start of every cluster in `order`
+  // k-means distance filter on the matrix cores
+  uint16_t* kmA;     // [U][kmA_stride] centroids split into 16-bit terms, in A-operand order (see kmeans.hip)
+  size_t kmA_stride; // 16-bit elements per unit
+  float* hn;         // [U][Mpad32] -|r_j|^2 / 2 (-inf for padding rows)
+  float* rmax;       // [U] max_j |r_j|
+  int* nflagged;     // [U] points whose filter gap is below the rounding bound (listed in `order`)
+  int* has_empty;    // [U] some cluster got no point in the last assignment
 };
 
 __host__ __device__ inline int elem_size(int dtype) { return dtype == DYNAKV_F32 ? 4 : 2; }
@@ -156,6 +163,24 @@ __device__ inline void copy_elem(void* dst, size_t j, const void* src, size_t i,
   else ((uint16_t*)dst)[j] = ((const uint16_t*)src)[i];
 }
 
+// Eight consecutive elements starting at element i (i a multiple of 8), as floats: two 16-byte loads for
+// float32, one for the 16-bit types.
+__device__ inline void load8(const void* base, size_t i, int dtype, float (&x)[8]) {
+  if (dtype == DYNAKV_F32) {
+    const f4 a = *(const f4*)((const float*)base + i), b = *(const f4*)((const float*)base + i + 4);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { x[e] = a[e]; x[4 + e] = b[e]; }
+  } else {
+    const uint4 w = *(const uint4*)((const uint16_t*)base + i);
+    const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const uint16_t h = (uint16_t)(ww[e >> 1] >> ((e & 1) * 16));
+      x[e] = dtype == DYNAKV_F16 ? f16_to_float(h) : bf16_to_float(h);
+    }
+  }
+}
+
 __device__ inline char* page_ptr(const View& v, int u, int page) {
   return v.pages + ((size_t)u * v.Pcap + page) * ((size_t)kPageElems * elem_size(v.dtype));
 }
@@ -196,10 +221,31 @@ __device__ inline int cluster_page(const View& v, int u, size_t cj, int k, int p
   return k < kInlinePages ? v.cpg[cj * kInlinePages + k] : v.pnext[(size_t)u * v.Pcap + prev];
 }
 
-// Takes a page from the unit's free stack, else from the untouched tail of its pool; -1 if none is left.
-// One thread per unit calls this at a time.
-__device__ inline int alloc_page(const View& v, int u) {
+// Block-wide arg-min / arg-max over (value, index) pairs held one per thread of a 256-thread block; ties go
+// to the lowest index; index < 0 means "no candidate".  Result in sv[0], si[0].
+template <bool MAX>
+__device__ inline void block_arg_reduce(double val, int idx, double* sv, int* si) {
+  const int tid = threadIdx.x;
+  sv[tid] = val; si[tid] = idx;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if (tid < o) {
+      const double ov = sv[tid + o];
+      const int oi = si[tid + o];
+      if (oi >= 0) {
+        const bool better = si[tid] < 0 || (MAX ? ov > sv[tid] : ov < sv[tid]) || (ov == sv[tid] && oi < si[tid]);
+        if (better) { sv[tid] = ov; si[tid] = oi; }
+      }
+    }
+    __syncthreads();
+  }
+}
+
+// Takes a page from the unit's free stack, else from the untouched tail of its pool (then *fresh = 1: the
+// caller must zero it before use); -1 if none is left.  One thread per unit calls this at a time.
+__device__ inline int alloc_page(const View& v, int u, int* fresh) {
   int top = v.free_top[u];
+  *fresh = 0;
   if (top > 0) {
     --top;
     v.free_top[u] = top;
@@ -208,6 +254,7 @@ __device__ inline int alloc_page(const View& v, int u) {
   const int b = v.bump[u];
   if (b < v.Pcap) {
     v.bump[u] = b + 1;
+    *fresh = 1;
     return b;
   }
   return -1;

@@ -12,8 +12,13 @@ namespace dynakv {
 
 namespace {
 
-__global__ void fill32_kernel(uint32_t* p, size_t n, uint32_t val) {
-  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = val;
+// Zeroes the pages the layout is about to use (unused slots of a page must hold finite values: masked
+// tokens are multiplied by P = 0).  Pages handed out later are zeroed when they leave the untouched pool.
+__global__ __launch_bounds__(256) void zero_pages_kernel(View v) {
+  const int u = blockIdx.y;
+  const size_t n16 = (size_t)v.bump[u] * kPageElems * elem_size(v.dtype) / 16;
+  uint4* p = (uint4*)page_ptr(v, u, 0);
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) p[i] = uint4{0, 0, 0, 0};
 }
 
 // R[u][j] = key at position init_idx[u][j]
@@ -35,7 +40,12 @@ __global__ __launch_bounds__(256) void kmeans_assign_f64_kernel(View v, const vo
   {
     const size_t base = ((size_t)u * N0 + (live ? i : 0)) * kHeadDim;
 #pragma unroll
-    for (int d = 0; d < kHeadDim; ++d) x[d] = load_elem(X, base + d, v.dtype);
+    for (int d8 = 0; d8 < kHeadDim / 8; ++d8) {
+      float t[8];
+      load8(X, base + d8 * 8, v.dtype, t);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) x[d8 * 8 + e] = t[e];
+    }
   }
   double best = __builtin_inf();
   int arg = 0;
@@ -84,28 +94,59 @@ __global__ __launch_bounds__(1024) void kmeans_sort_kernel(View v, int N0, int N
   int* order = v.order + (size_t)u * v.Ncap;
   int* koff = v.koff + (size_t)u * (v.Mcap + 1);
   const uint32_t pmask = (1u << pos_bits) - 1;
+  if (tid == 0) v.has_empty[u] = 0;
+  __syncthreads();
   for (int q = tid; q < N0; q += 1024) {
     const uint32_t kq = key[q];
     order[q] = (int)(kq & pmask);
     const int lq = (int)(kq >> pos_bits);
     const int lp = q ? (int)(key[q - 1] >> pos_bits) : -1;
     for (int l = lp + 1; l <= lq; ++l) koff[l] = q;          // also covers empty clusters in between
-    if (q == N0 - 1)
+    if (lq - lp > 1) v.has_empty[u] = 1;
+    if (q == N0 - 1) {
       for (int l = lq + 1; l <= v.M0; ++l) koff[l] = N0;
+      if (lq + 1 < v.M0) v.has_empty[u] = 1;
+    }
   }
 }
 
-// Thread (cluster, coordinate): centre = mean of the members, summed in ascending position (Eq. 4).
+// Wavefront per cluster, two coordinates per lane: centre = mean of the members, summed in ascending
+// position (Eq. 4).  The wavefront first fetches up to 64 member positions with one load, so the row loads
+// that follow do not wait on each other.  grid (ceil(M0/4), U).
 __global__ __launch_bounds__(256) void kmeans_update_kernel(View v, const void* X, int N0) {
-  const int u = blockIdx.y, j = blockIdx.x * 2 + (threadIdx.x >> 7), d = threadIdx.x & 127;
+  const int u = blockIdx.y, j = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (j >= v.M0) return;
   const int* koff = v.koff + (size_t)u * (v.Mcap + 1);
   const int* order = v.order + (size_t)u * v.Ncap;
   const int b = koff[j], e = koff[j + 1];
   if (e == b) return;
-  double s = 0.0;
-  for (int q = b; q < e; ++q) s += (double)load_elem(X, ((size_t)u * N0 + order[q]) * kHeadDim + d, v.dtype);
-  unit_R(v, u)[r_index(j, d)] = (float)(s / (double)(e - b));
+  double s0 = 0.0, s1 = 0.0;
+  for (int c0 = b; c0 < e; c0 += 64) {
+    const int cn = min(64, e - c0);
+    const int my = lane < cn ? order[c0 + lane] : 0;
+    for (int k0 = 0; k0 < cn; k0 += 8) {   // eight row loads in flight, then added in member order
+      float x0[8], x1[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const int pos = __builtin_amdgcn_readlane(my, min(k0 + k, 63));
+        const size_t i = ((size_t)u * N0 + pos) * kHeadDim + lane * 2;
+        if (k0 + k >= cn) { x0[k] = 0.f; x1[k] = 0.f; }    // +0.0 leaves the sums unchanged
+        else if (v.dtype == DYNAKV_F32) {
+          const float2 t = *(const float2*)((const float*)X + i);
+          x0[k] = t.x; x1[k] = t.y;
+        } else {
+          const uint32_t w = *(const uint32_t*)((const uint16_t*)X + i);
+          x0[k] = v.dtype == DYNAKV_F16 ? f16_to_float((uint16_t)w) : bf16_to_float((uint16_t)w);
+          x1[k] = v.dtype == DYNAKV_F16 ? f16_to_float((uint16_t)(w >> 16)) : bf16_to_float((uint16_t)(w >> 16));
+        }
+      }
+#pragma unroll
+      for (int k = 0; k < 8; ++k) { s0 += (double)x0[k]; s1 += (double)x1[k]; }
+    }
+  }
+  float* R = unit_R(v, u);
+  R[r_index(j, lane * 2)] = (float)(s0 / (double)(e - b));
+  R[r_index(j, lane * 2 + 1)] = (float)(s1 / (double)(e - b));
 }
 
 // One workgroup per unit: every empty cluster, in ascending id, takes the not-yet-taken point that is
@@ -117,12 +158,8 @@ __global__ __launch_bounds__(256) void kmeans_reseed_kernel(View v, const void* 
   const int u = blockIdx.x, tid = threadIdx.x;
   const int* koff = v.koff + (size_t)u * (v.Mcap + 1);
   double* dist = v.dist + (size_t)u * v.Ncap;
-  if (tid == 0) any_empty = 0;
-  __syncthreads();
-  for (int j = tid; j < v.M0; j += 256)
-    if (koff[j + 1] == koff[j]) any_empty = 1;
-  __syncthreads();
-  if (!any_empty) return;
+  if (!v.has_empty[u]) return;
+  (void)any_empty;
   for (int j = 0; j < v.M0; ++j) {
     if (koff[j + 1] != koff[j]) continue;   // uniform across the block
     double bv = -1.0;
@@ -151,6 +188,238 @@ __global__ __launch_bounds__(256) void kmeans_reseed_kernel(View v, const void* 
   }
 }
 
+// ---- assignment through the matrix cores --------------------------------------------------------------
+// Filter + exact re-check.  z_ij = <x_i, r_j> - |r_j|^2/2 orders the centres like the squared distance.  The
+// filter evaluates it with MFMA on 16-bit operands: x is exact in its storage type, r_j is split into two
+// (f16) or three (bf16) 16-bit terms whose sum carries float32 accuracy, accumulation is float32.  The error
+// of a filtered z is below eps_i = gamma * |x_i| * max_j |r_j|; a point whose best and second-best filtered
+// values are more than 2 eps_i apart has the same nearest centre in exact arithmetic, every other point is
+// listed and gets the exact float64 scan (kmeans_exact_kernel), so labels equal the float64 definition.
+typedef _Float16 h8v __attribute__((ext_vector_type(8)));
+typedef __bf16 b8v __attribute__((ext_vector_type(8)));
+typedef float f16v __attribute__((ext_vector_type(16)));
+constexpr float kFilterGamma = 1.0f / 8192.0f;   // >> 2^-22 operand error + float32 accumulation over 384 products
+
+// A-operand order of one 32-cluster tile: [term][k-step of 16][lane][8], lane = (k%16)/8*32 + row.
+__device__ inline size_t kmA_index(int nterms, int j, int term, int d) {
+  return ((((size_t)(j >> 5) * nterms + term) * 8 + (d >> 4)) * 64 + (((d & 15) >> 3) << 5) + (j & 31)) * 8 + (d & 7);
+}
+
+// Thread per centre (lane = centre, so the table reads are contiguous): splits r_j into 16-bit terms in
+// A-operand order, stores -|r_j|^2/2 and folds |r_j| into the unit's maximum.  grid (ceil(Mpad/256), U).
+__global__ void kmeans_reset_kernel(View v) {
+  const int u = blockIdx.x * 256 + threadIdx.x;
+  if (u < v.U) { v.rmax[u] = 0.f; v.nflagged[u] = 0; }
+}
+template <bool BF>
+__global__ __launch_bounds__(256) void kmeans_prep_kernel(View v) {
+  constexpr int NT = BF ? 3 : 2;
+  const int u = blockIdx.y, j = blockIdx.x * 256 + threadIdx.x;
+  const int mpad = (v.M0 + 31) / 32 * 32;
+  if (j >= mpad) return;
+  const float* R = unit_R(v, u);
+  uint16_t* A = v.kmA + (size_t)u * v.kmA_stride;
+  double nn = 0.0;
+  for (int d8 = 0; d8 < kHeadDim / 8; ++d8) {
+    float r[8];
+    if (j < v.M0) {
+      const f4 a = *(const f4*)(R + r_index(j, d8 * 8)), b = *(const f4*)(R + r_index(j, d8 * 8 + 4));
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { r[e] = a[e]; r[4 + e] = b[e]; }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) r[e] = 0.f;
+    }
+    uint16_t bits[NT][8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      nn += (double)r[e] * (double)r[e];
+      float rem = r[e];
+#pragma unroll
+      for (int t = 0; t < NT; ++t) {
+        float part;
+        if constexpr (BF) { const __bf16 b = (__bf16)rem; part = (float)b; bits[t][e] = __builtin_bit_cast(uint16_t, b); }
+        else { const _Float16 hh = (_Float16)rem; part = (float)hh; bits[t][e] = __builtin_bit_cast(uint16_t, hh); }
+        rem -= part;
+      }
+    }
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      uint4 w;
+      w.x = bits[t][0] | ((uint32_t)bits[t][1] << 16); w.y = bits[t][2] | ((uint32_t)bits[t][3] << 16);
+      w.z = bits[t][4] | ((uint32_t)bits[t][5] << 16); w.w = bits[t][6] | ((uint32_t)bits[t][7] << 16);
+      *(uint4*)(A + kmA_index(NT, j, t, d8 * 8)) = w;
+    }
+  }
+  v.hn[(size_t)u * mpad + j] = j < v.M0 ? (float)(-0.5 * nn) : -__builtin_inff();
+  if (j < v.M0) atomicMax((int*)&v.rmax[u], __float_as_int((float)sqrt(nn) * 1.000001f));   // non-negative floats order like ints
+}
+
+// grid (ceil(N0/256), U); 4 wavefronts x 64 points.  Z^T = R~ X^T in 32x32 tiles: lane (p, h) ends up with the
+// filtered values of point p for the centres 8*(i/4) + 4*h + i%4 of every tile, so the running best / second
+// best need no cross-lane work until the very end.
+template <bool BF>
+__global__ __launch_bounds__(256) void kmeans_assign_mfma_kernel(View v, const void* X, int N0) {
+  constexpr int NT = BF ? 3 : 2;
+  __shared__ uint4 sA[2][NT * 8 * 64];     // two tiles: the next one is fetched while this one is consumed
+  __shared__ float shn[2][32];
+  const int u = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int p = lane & 31, h = lane >> 5;
+  const int ntiles = (v.M0 + 31) / 32;
+  const int pbase = blockIdx.x * 256 + wave * 64;
+  uint4 bx[2][8];
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    const int pt = pbase + t * 32 + p;
+    const uint16_t* xr = (const uint16_t*)X + ((size_t)u * N0 + (pt < N0 ? pt : 0)) * kHeadDim + h * 8;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) bx[t][ks] = pt < N0 ? *(const uint4*)(xr + ks * 16) : uint4{0, 0, 0, 0};
+  }
+  float xnorm[2];                               // |x| of this lane's point, from the operand registers
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    float nn = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      const uint32_t ww[4] = {bx[t][ks].x, bx[t][ks].y, bx[t][ks].z, bx[t][ks].w};
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const uint16_t hh = (uint16_t)(ww[e >> 1] >> ((e & 1) * 16));
+        const float x = BF ? bf16_to_float(hh) : f16_to_float(hh);
+        nn += x * x;
+      }
+    }
+    nn += __shfl_xor(nn, 32);
+    xnorm[t] = __builtin_sqrtf(nn) * 1.0001f;
+  }
+  float best[2] = {-__builtin_inff(), -__builtin_inff()}, second[2] = {-__builtin_inff(), -__builtin_inff()};
+  int bidx[2] = {0, 0};
+  const uint4* gA = (const uint4*)(v.kmA + (size_t)u * v.kmA_stride);
+  const float* hn = v.hn + (size_t)u * ntiles * 32;
+  // Tiles travel global -> registers -> LDS one iteration ahead of their use (plain scalars, so that they stay
+  // in registers); the empty asm statement keeps the compiler from sinking the loads down to the LDS stores.
+  uint4 st0, st1, st2, st3, st4 = {0, 0, 0, 0}, st5 = {0, 0, 0, 0};
+  float sh = 0.f;
+#define KM_FETCH(tile)                                                        \
+  {                                                                           \
+    const uint4* g_ = gA + (size_t)(tile) * NT * 512 + tid;                   \
+    st0 = g_[0]; st1 = g_[256]; st2 = g_[512]; st3 = g_[768];                 \
+    if constexpr (NT == 3) { st4 = g_[1024]; st5 = g_[1280]; }                \
+    if (tid < 32) sh = hn[(tile) * 32 + tid];                                 \
+    asm volatile("" ::: "memory");                                            \
+  }
+#define KM_COMMIT(buf)                                                        \
+  {                                                                           \
+    uint4* d_ = sA[buf] + tid;                                                \
+    d_[0] = st0; d_[256] = st1; d_[512] = st2; d_[768] = st3;                 \
+    if constexpr (NT == 3) { d_[1024] = st4; d_[1280] = st5; }                \
+    if (tid < 32) shn[buf][tid] = sh;                                         \
+  }
+  KM_FETCH(0);
+  KM_COMMIT(0);
+  __syncthreads();
+  for (int tile = 0; tile < ntiles; ++tile) {
+    const int cur = tile & 1;
+    if (tile + 1 < ntiles) KM_FETCH(tile + 1);
+    f16v acc[2];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { acc[0][i] = shn[cur][8 * (i >> 2) + 4 * h + (i & 3)]; acc[1][i] = acc[0][i]; }
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+      for (int term = 0; term < NT; ++term) {
+        const uint4 a = sA[cur][(term * 8 + ks) * 64 + lane];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          if constexpr (BF)
+            acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(b8v, a), __builtin_bit_cast(b8v, bx[t][ks]), acc[t], 0, 0, 0);
+          else
+            acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(h8v, a), __builtin_bit_cast(h8v, bx[t][ks]), acc[t], 0, 0, 0);
+        }
+      }
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const float val = acc[t][i];
+        second[t] = fmaxf(second[t], fminf(best[t], val));
+        if (val > best[t]) { best[t] = val; bidx[t] = tile * 32 + 8 * (i >> 2) + 4 * h + (i & 3); }
+      }
+    if (tile + 1 < ntiles) KM_COMMIT(cur ^ 1);
+    __syncthreads();
+  }
+#undef KM_FETCH
+#undef KM_COMMIT
+  const float rmax = v.rmax[u];
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    const float ob = __shfl_xor(best[t], 32), os = __shfl_xor(second[t], 32);
+    const int oi = __shfl_xor(bidx[t], 32);
+    const float nb = fmaxf(best[t], ob), ns = fmaxf(fmaxf(second[t], os), fminf(best[t], ob));
+    const int idx = (ob > best[t] || (ob == best[t] && oi < bidx[t])) ? oi : bidx[t];
+    const int pt = pbase + t * 32 + p;
+    if (h == 0 && pt < N0) {
+      v.labels[(size_t)u * v.Ncap + pt] = idx;
+      const float eps = kFilterGamma * xnorm[t] * rmax + 2.4e-7f * rmax * rmax;
+      if (!(nb - ns > 2.f * eps)) v.order[(size_t)u * v.Ncap + atomicAdd(&v.nflagged[u], 1)] = pt;
+    }
+  }
+}
+
+// Exact nearest centre (float64, left to right, ties to the lowest id) of every listed point: one workgroup
+// per point, thread = centre, so the centroid table is read 1 KB per wavefront at a time.  grid (B, U).
+__global__ __launch_bounds__(256) void kmeans_exact_kernel(View v, const void* X, int N0) {
+  __shared__ double xd[kHeadDim];
+  __shared__ double sv[256];
+  __shared__ int si[256];
+  const int u = blockIdx.y, tid = threadIdx.x;
+  const int nf = v.nflagged[u];
+  const float* R = unit_R(v, u);
+  for (int f = blockIdx.x; f < nf; f += gridDim.x) {
+    const int pt = v.order[(size_t)u * v.Ncap + f];
+    __syncthreads();
+    if (tid < kHeadDim) xd[tid] = (double)load_elem(X, ((size_t)u * N0 + pt) * kHeadDim + tid, v.dtype);
+    __syncthreads();
+    double best = __builtin_inf();
+    int arg = -1;
+    for (int j = tid; j < v.M0; j += 256) {
+      f4 row[8];
+      load_centroid_head(R, j, row);
+      double acc = 0.0;
+      for_each_coord(R, j, row, [&](int d, float rv) {
+        const double t = xd[d] - (double)rv;
+        acc = fma(t, t, acc);
+      });
+      if (acc < best || arg < 0) { best = acc; arg = j; }
+    }
+    block_arg_reduce<false>(best, arg, sv, si);
+    if (tid == 0) v.labels[(size_t)u * v.Ncap + pt] = si[0];
+  }
+}
+
+// Only when some cluster came out empty: the distance of every point to the centre it was assigned to (the
+// centres of this assignment, i.e. before the update), which the re-seeding step ranks.
+__global__ __launch_bounds__(256) void kmeans_dist_kernel(View v, const void* X, int N0) {
+  const int u = blockIdx.y, i = blockIdx.x * 256 + threadIdx.x;
+  if (!v.has_empty[u] || i >= N0) return;
+  const int j = v.labels[(size_t)u * v.Ncap + i];
+  const float* R = unit_R(v, u);
+  const size_t base = ((size_t)u * N0 + i) * kHeadDim;
+  double acc = 0.0;
+#pragma unroll 4
+  for (int d8 = 0; d8 < kHeadDim / 8; ++d8) {
+    float x[8];
+    load8(X, base + d8 * 8, v.dtype, x);
+    const f4 ra = *(const f4*)(R + r_index(j, d8 * 8)), rb = *(const f4*)(R + r_index(j, d8 * 8 + 4));
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const double t = (double)x[e] - (double)(e < 4 ? ra[e] : rb[e - 4]);
+      acc = fma(t, t, acc);
+    }
+  }
+  v.dist[(size_t)u * v.Ncap + i] = acc;
+}
+
 // dist[i] = squared distance of point i to the (updated) centre of its own cluster
 __global__ __launch_bounds__(256) void point_dist_kernel(View v, const void* X, int N0) {
   const int u = blockIdx.y, i = blockIdx.x * 256 + threadIdx.x;
@@ -159,9 +428,16 @@ __global__ __launch_bounds__(256) void point_dist_kernel(View v, const void* X, 
   const float* R = unit_R(v, u);
   const size_t base = ((size_t)u * N0 + i) * kHeadDim;
   double acc = 0.0;
-  for (int d = 0; d < kHeadDim; ++d) {
-    const double t = (double)load_elem(X, base + d, v.dtype) - (double)R[r_index(j, d)];
-    acc = fma(t, t, acc);
+#pragma unroll 4
+  for (int d8 = 0; d8 < kHeadDim / 8; ++d8) {
+    float x[8];
+    load8(X, base + d8 * 8, v.dtype, x);
+    const f4 ra = *(const f4*)(R + r_index(j, d8 * 8)), rb = *(const f4*)(R + r_index(j, d8 * 8 + 4));
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const double t = (double)x[e] - (double)(e < 4 ? ra[e] : rb[e - 4]);
+      acc = fma(t, t, acc);
+    }
   }
   v.dist[(size_t)u * v.Ncap + i] = acc;
 }
@@ -214,7 +490,8 @@ __global__ __launch_bounds__(1024) void finalize_kernel(View v, int N0) {
   }
 }
 
-// 16 consecutive entries of the sorted order per workgroup: copy K and V into their page slots.
+// 16 consecutive entries of the sorted order per workgroup, 16 threads per entry, 8 coordinates per thread:
+// keys move as whole 16-byte operand chunks, values are scattered into the token-interleaved V layout.
 __global__ __launch_bounds__(256) void layout_copy_kernel(View v, const void* K, const void* V, int N0) {
   const int u = blockIdx.y, q = blockIdx.x * 16 + (threadIdx.x >> 4), c = threadIdx.x & 15;
   if (q >= N0) return;
@@ -223,11 +500,21 @@ __global__ __launch_bounds__(256) void layout_copy_kernel(View v, const void* K,
   const int rank = q - v.koff[(size_t)u * (v.Mcap + 1) + j];
   const int page = v.pg_off[(size_t)u * v.Mcap + j] + rank / kPageTokens, slot = rank % kPageTokens;
   char* pg = page_ptr(v, u, page);
-  const size_t src = ((size_t)u * N0 + pos) * kHeadDim;
-  for (int e = 0; e < 8; ++e) {
-    const int d = c * 8 + e;
-    copy_elem(pg, k_index(v.dtype, slot, d), K, src + d, v.dtype);
-    copy_elem(pg, v_index(v.dtype, slot, d), V, src + d, v.dtype);
+  const size_t src = ((size_t)u * N0 + pos) * kHeadDim + c * 8;
+  if (v.dtype == DYNAKV_F32) {
+    const f4* ks = (const f4*)((const float*)K + src);
+    const f4* vs = (const f4*)((const float*)V + src);
+    *(f4*)((float*)pg + k_index32(slot, c * 8)) = ks[0];
+    *(f4*)((float*)pg + k_index32(slot, c * 8 + 4)) = ks[1];
+    const f4 a = vs[0], b = vs[1];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ((float*)pg)[v_index32(slot, c * 8 + e)] = e < 4 ? a[e] : b[e - 4];
+  } else {
+    *(uint4*)((uint16_t*)pg + k_index16(slot, c * 8)) = *(const uint4*)((const uint16_t*)K + src);
+    const uint4 w = *(const uint4*)((const uint16_t*)V + src);
+    const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ((uint16_t*)pg)[v_index16(slot, c * 8 + e)] = (uint16_t)(ww[e >> 1] >> ((e & 1) * 16));
   }
   if (c == 0) v.ppos[((size_t)u * v.Pcap + page) * kPageTokens + slot] = pos;
 }
@@ -236,20 +523,36 @@ __global__ __launch_bounds__(256) void layout_copy_kernel(View v, const void* K,
 
 hipError_t launch_build_index(const View& v, const void* K, const void* V, int N0, const int* init_idx, int iters,
                               void* ws, size_t ws_bytes, hipStream_t st) {
-  // the whole workspace starts from zero: unused page slots must hold finite values
-  fill32_kernel<<<2048, 256, 0, st>>>((uint32_t*)ws, ws_bytes / 4, 0u);
+  (void)ws; (void)ws_bytes;
   kmeans_init_kernel<<<dim3(v.M0, v.U), 128, 0, st>>>(v, K, N0, init_idx);
   int Npad = 2, pos_bits = 1;
   while (Npad < N0) { Npad <<= 1; ++pos_bits; }
   const dim3 gpts((N0 + 255) / 256, v.U);
+  const bool mfma = v.dtype != DYNAKV_F32;     // float32 keys keep the plain float64 scan
+  const dim3 gprep(((v.M0 + 31) / 32 * 32 + 255) / 256, v.U);
   for (int it = 0; it < iters; ++it) {
-    kmeans_assign_f64_kernel<<<gpts, 256, 0, st>>>(v, K, N0);
+    if (mfma) {
+      if (v.dtype == DYNAKV_F16) {
+        kmeans_reset_kernel<<<(v.U + 255) / 256, 256, 0, st>>>(v);
+        kmeans_prep_kernel<false><<<gprep, 256, 0, st>>>(v);
+        kmeans_assign_mfma_kernel<false><<<gpts, 256, 0, st>>>(v, K, N0);
+      } else {
+        kmeans_reset_kernel<<<(v.U + 255) / 256, 256, 0, st>>>(v);
+        kmeans_prep_kernel<true><<<gprep, 256, 0, st>>>(v);
+        kmeans_assign_mfma_kernel<true><<<gpts, 256, 0, st>>>(v, K, N0);
+      }
+      kmeans_exact_kernel<<<dim3(64, v.U), 256, 0, st>>>(v, K, N0);
+    } else {
+      kmeans_assign_f64_kernel<<<gpts, 256, 0, st>>>(v, K, N0);
+    }
     kmeans_sort_kernel<<<v.U, 1024, 0, st>>>(v, N0, Npad, pos_bits);
-    kmeans_update_kernel<<<dim3((v.M0 + 1) / 2, v.U), 256, 0, st>>>(v, K, N0);
+    if (it + 1 < iters) kmeans_dist_kernel<<<gpts, 256, 0, st>>>(v, K, N0);
+    kmeans_update_kernel<<<dim3((v.M0 + 3) / 4, v.U), 256, 0, st>>>(v, K, N0);
     if (it + 1 < iters) kmeans_reseed_kernel<<<v.U, 256, 0, st>>>(v, K, N0);
   }
   point_dist_kernel<<<gpts, 256, 0, st>>>(v, K, N0);
   finalize_kernel<<<v.U, 1024, 0, st>>>(v, N0);
+  zero_pages_kernel<<<dim3(16, v.U), 256, 0, st>>>(v);
   layout_copy_kernel<<<dim3((N0 + 15) / 16, v.U), 256, 0, st>>>(v, K, V, N0);
   return hipGetLastError();
 }

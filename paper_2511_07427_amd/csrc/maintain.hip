@@ -10,32 +10,12 @@ namespace dynakv {
 
 namespace {
 
-// Block-wide arg-min / arg-max over (value, index) pairs held one per thread; ties go to the lowest
-// index; index < 0 means "no candidate".  256 threads.
-template <bool MAX>
-__device__ inline void block_arg_reduce(double val, int idx, double* sv, int* si) {
-  const int tid = threadIdx.x;
-  sv[tid] = val; si[tid] = idx;
-  __syncthreads();
-  for (int o = 128; o > 0; o >>= 1) {
-    if (tid < o) {
-      const double ov = sv[tid + o];
-      const int oi = si[tid + o];
-      if (oi >= 0) {
-        const bool better = si[tid] < 0 || (MAX ? ov > sv[tid] : ov < sv[tid]) || (ov == sv[tid] && oi < si[tid]);
-        if (better) { sv[tid] = ov; si[tid] = oi; }
-      }
-    }
-    __syncthreads();
-  }
-}
-
 // ------------------------------------------------------------------------------------------- append
 __global__ __launch_bounds__(256) void append_kernel(View v, const void* kin, const void* vin) {
   __shared__ double kd[kHeadDim], delta[kHeadDim], r1[kHeadDim];
   __shared__ double sv[256];
   __shared__ int si[256];
-  __shared__ int s_ok, s_commit, s_page, s_slot;
+  __shared__ int s_ok, s_commit, s_page, s_slot, s_fresh;
   const int u = blockIdx.x, tid = threadIdx.x;
   float* R = unit_R(v, u);
   f4 row[8];
@@ -76,9 +56,9 @@ __global__ __launch_bounds__(256) void append_kernel(View v, const void* kin, co
     const int sz = v.cn[cbase + j] + v.cb[cbase + j];
     const int slot = sz % kPageTokens;
     int page = v.ctail[cbase + j];
-    int ok = 1;
+    int ok = 1, fresh = 0;
     if (slot == 0) {                      // no page yet, or the tail page is full
-      const int np = alloc_page(v, u);
+      const int np = alloc_page(v, u, &fresh);
       if (np < 0) {
         v.err[u] |= DYNAKV_ERR_TOKENS;
         ok = 0;
@@ -118,12 +98,17 @@ __global__ __launch_bounds__(256) void append_kernel(View v, const void* kin, co
       v.N[u] = N + 1;
       v.ppos[((size_t)u * v.Pcap + page) * kPageTokens + slot] = N;
     }
-    s_ok = ok; s_commit = commit; s_page = page; s_slot = slot;
+    s_ok = ok; s_commit = commit; s_page = page; s_slot = slot; s_fresh = fresh;
   }
   __syncthreads();
   if (!s_ok) return;
   if (s_commit && tid < kHeadDim) R[r_index(j, tid)] = (float)r1[tid];
   char* pg = page_ptr(v, u, s_page);
+  if (s_fresh) {                          // first use of this page: unused slots must hold finite values
+    const int n16 = kPageElems * elem_size(v.dtype) / 16;
+    for (int i = tid; i < n16; i += 256) ((uint4*)pg)[i] = uint4{0, 0, 0, 0};
+    __syncthreads();
+  }
   if (tid < kHeadDim) copy_elem(pg, k_index(v.dtype, s_slot, tid), kin, (size_t)u * kHeadDim + tid, v.dtype);
   else copy_elem(pg, v_index(v.dtype, s_slot, tid - kHeadDim), vin, (size_t)u * kHeadDim + tid - kHeadDim, v.dtype);
 }
@@ -375,6 +360,12 @@ __device__ __noinline__ void split_cluster_impl(const View& v, int u, int j, int
   for (int k = tid; k < need; k += 256) {
     const bool last = k == pS - 1 || k == need - 1;
     v.pnext[(size_t)u * v.Pcap + s.newpg[k]] = last ? -1 : s.newpg[k + 1];
+  }
+  if (need > from_free) {                 // pages never used before are zeroed first
+    constexpr int n16 = kPageElems * kEs / 16;
+    for (int t = tid; t < (need - from_free) * n16; t += 256)
+      ((uint4*)(pool + (size_t)s.newpg[from_free + t / n16] * (kPageElems * kEs)))[t % n16] = uint4{0, 0, 0, 0};
+    __syncthreads();
   }
   // keys in 16-byte chunks, values element by element (their page layout interleaves four tokens)
 #pragma unroll 4

@@ -21,10 +21,11 @@ __global__ __launch_bounds__(256) void score_kernel(View v, const void* Q) {
   const float* R = unit_R(v, u);
   // the first quarter of the row is requested before anything else (rows up to the table's padded end exist)
   f4 row[8];
-  const bool in_table = (size_t)(j | 63) * kHeadDim < v.Rstride;
-  if (in_table) load_centroid_head(R, j, row);
+  const bool early = blockIdx.x * 256 < v.M0;        // these rows exist in every state: M never drops below M0
+  if (early) load_centroid_head(R, j, row);
   const int M = v.M[u];
   if (blockIdx.x * 256 >= M) return;
+  if (!early && (j & ~63) < M) load_centroid_head(R, j, row);
   for (int t = tid; t < GP * kHeadDim; t += 256) {
     const int g = t / kHeadDim, d = t % kHeadDim;
     qs[d][g] = g < v.G ? (double)load_elem(Q, ((size_t)u * v.G + g) * kHeadDim + d, v.dtype) : 0.0;
