@@ -132,17 +132,23 @@ def main():
     assert int(state["n_tokens"].min()) == spec.prefill + T
     gathered = int((c1[:, 4] - c0[:, 4]).sum())
     retrievals = int((c1[:, 5] - c0[:, 5]).sum())
+    scored = int((c1[:, 6] - c0[:, 6]).sum())
     assert retrievals == a.steps * U
 
     roof = None
     if not a.no_kernel_events:
         n, ms = ix.dynakv_profile_read()
         assert n == a.steps
-        bytes_per_launch = gathered / a.steps * 2 * d * esz            # K and V of every gathered entry, once
+        kernel = ix.dynakv_profiled_kernel()
+        kv_bytes = gathered / a.steps * 2 * d * esz                    # K and V of every gathered entry, once
+        centroid_bytes = scored / a.steps * d * 4 if kernel == "retrieve_fused_kernel" else 0.0   # float32 table, once
+        bytes_per_launch = kv_bytes + centroid_bytes
         achieved = bytes_per_launch / (ms / n * 1e-3) / 1e9
-        roof = dict(bound="hbm", kernel="gather_attend_kernel", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s",
+        roof = dict(bound="hbm", kernel=kernel, achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=achieved / HBM_PEAK_GBS, traffic=None, avg_launch_us=ms / n * 1e3,
-                    algorithmic_bytes_per_launch=bytes_per_launch, gathered_entries_per_unit=gathered / retrievals)
+                    algorithmic_bytes_per_launch=bytes_per_launch, kv_bytes_per_launch=kv_bytes,
+                    centroid_bytes_per_launch=centroid_bytes, gathered_entries_per_unit=gathered / retrievals,
+                    clusters_per_unit=scored / retrievals)
 
     res = {
         "metric": "decode steps/sec (index maint + retrieve + sparse attn)", "value": a.steps / dt,

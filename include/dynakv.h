@@ -142,18 +142,22 @@ typedef struct {
   int32_t* n_gathered;   /* [U]                 entries attended by the last retrieval           */
   int32_t* gathered;     /* [U][max_tokens]     their token positions in gather order            */
   int32_t* last_assign;  /* [U]                 cluster chosen by the last append                */
-  int64_t* counters;     /* [U][6]              splits, failed splits, forced splits, pages in use,
-                                                entries gathered so far, retrievals so far    */
+  int64_t* counters;     /* [U][8]              splits, failed splits, forced splits, pages in use,
+                                                entries gathered, retrievals, clusters scored
+                                                (all since build_index), reserved             */
 } dynakv_state_t;
 
 /* Copies the requested parts of the state (enqueued on `stream`; the caller synchronises before reading). */
 dynakv_status_t dynakv_export_state(dynakv_index_t* index, const dynakv_state_t* dst, void* stream);
 
-/* Timing aid: when enabled, the dominant kernel of dynakv_retrieve_attend (gather + attention) is bracketed
- * by HIP events on its own stream.  dynakv_profile_read synchronises those events and returns the number of
+/* Timing aid: when enabled, the dominant kernel of dynakv_retrieve_attend (gather + attention; with at least
+ * 256 units the single kernel that also scores and selects) is bracketed by HIP events on its own stream.  dynakv_profile_read synchronises those events and returns the number of
  * launches and their summed duration in milliseconds since the last enable. */
 dynakv_status_t dynakv_profile_enable(dynakv_index_t* index, int32_t max_launches);
 dynakv_status_t dynakv_profile_read(dynakv_index_t* index, int32_t* n_launches, double* total_ms);
+/* Name of the kernel those events bracket: "retrieve_fused_kernel" (scores + selection + gather + attention in
+ * one launch) or "gather_attend_kernel". */
+const char* dynakv_profiled_kernel(dynakv_index_t* index);
 
 const char* dynakv_strerror(dynakv_status_t status);
 

@@ -73,6 +73,8 @@ def load():
         lib.dynakv_export_state.argtypes = [vp, C.POINTER(_State), vp]
         lib.dynakv_profile_enable.argtypes = [vp, i32]
         lib.dynakv_profile_read.argtypes = [vp, C.POINTER(i32), C.POINTER(C.c_double)]
+        lib.dynakv_profiled_kernel.restype = C.c_char_p
+        lib.dynakv_profiled_kernel.argtypes = [vp]
         lib.dynakv_strerror.restype = C.c_char_p
         lib.dynakv_strerror.argtypes = [C.c_int]
         _lib = lib
@@ -171,6 +173,9 @@ class Index:
         _check(self._lib.dynakv_profile_read(self._h, C.byref(n), C.byref(ms)), "dynakv_profile_read")
         return n.value, ms.value
 
+    def dynakv_profiled_kernel(self) -> str:
+        return self._lib.dynakv_profiled_kernel(self._h).decode()
+
     # ---- snapshot -------------------------------------------------------------------------------
     def dynakv_export_state(self, fields=_STATE_FIELDS):
         """Returns the requested parts of the state as CPU tensors (synchronises the current stream)."""
@@ -181,7 +186,7 @@ class Index:
                     centroids=((U, M, d), f32), size=((U, M), i32), buffered=((U, M), i32), flag=((U, M), i32),
                     m2=((U, M), f64), offsets=((U, M + 1), i32), members=((U, N), i32), scores=((U, M), f32),
                     n_selected=((U,), i32), selected=((U, M), i32), n_gathered=((U,), i32), gathered=((U, N), i32),
-                    last_assign=((U,), i32), counters=((U, 6), i64))
+                    last_assign=((U,), i32), counters=((U, 8), i64))
         bufs = {k: torch.zeros(spec[k][0], dtype=spec[k][1], device=self.device) for k in fields}
         st = _State(**{k: (bufs[k].data_ptr() if k in bufs else None) for k in _STATE_FIELDS})
         _check(self._lib.dynakv_export_state(self._h, C.byref(st), _stream()), "dynakv_export_state")

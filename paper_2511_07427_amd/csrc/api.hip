@@ -52,6 +52,7 @@ void plan_attention(const dynakv_config_t& c, int* S, int* NW) {
   const int lds_max = pow2_floor(65536 / (c.group_size * (kHeadDim + 2) * 4));
   nw = nw < 4 ? 4 : (nw > 16 ? 16 : pow2_floor(nw));
   if (nw > lds_max) nw = lds_max < 4 ? 4 : lds_max;
+  if (c.group_size > 4 && nw > 8) nw = 8;    // 64 head rows fit the merge buffer of the single-kernel retrieval
   if (c.dtype == DYNAKV_F32) nw = 4;
   *S = s < 1 ? 1 : (s > kMaxKvSplits ? kMaxKvSplits : s);
   *NW = nw;
@@ -70,6 +71,7 @@ size_t carve(const dynakv_config_t& c, char* base, View* out) {
   v.U = c.n_units; v.G = c.group_size; v.dtype = c.dtype; v.M0 = c.n_clusters_init; v.Mcap = c.max_clusters;
   v.Ncap = c.max_tokens; v.Pcap = pages_per_unit(c); v.Bmax = c.buffer_max; v.group_reduce = c.group_reduce;
   plan_attention(c, &v.S, &v.NW);
+  v.fuse = std::getenv("DYNAKV_NO_FUSE") ? 0 : 1;       // tuning / test switch
   v.var_alpha = c.var_alpha; v.size_factor = c.size_factor;
   v.scale_d = c.softmax_scale > 0.f ? (double)c.softmax_scale : 1.0 / std::sqrt((double)c.head_dim);
   v.scale_f = (float)v.scale_d;
@@ -154,10 +156,15 @@ dynakv_status_t dynakv_retrieve_attend(dynakv_index_t* ix, const void* Q, int32_
   if (!ix || !Q || !out || token_budget < 0) return DYNAKV_EINVAL;
   if (!ix->built) return DYNAKV_ESTATE;
   hipStream_t st = (hipStream_t)stream;
-  if (launch_score_select(ix->view, Q, token_budget, st) != hipSuccess) return DYNAKV_EHIP;
+  const bool fused = retrieve_is_fused(ix->view);
+  if (!fused && launch_score_select(ix->view, Q, token_budget, st) != hipSuccess) return DYNAKV_EHIP;
   const bool prof = ix->profiling && 2 * (ix->n_prof + 1) <= (int)ix->ev.size();
   if (prof && hipEventRecord(ix->ev[2 * ix->n_prof], st) != hipSuccess) return DYNAKV_EHIP;
-  if (launch_gather_attend(ix->view, Q, out, lse, st) != hipSuccess) return DYNAKV_EHIP;
+  if (fused) {
+    if (launch_retrieve_fused(ix->view, Q, token_budget, out, lse, st) != hipSuccess) return DYNAKV_EHIP;
+  } else if (launch_gather_attend(ix->view, Q, out, lse, st) != hipSuccess) {
+    return DYNAKV_EHIP;
+  }
   if (prof) {
     if (hipEventRecord(ix->ev[2 * ix->n_prof + 1], st) != hipSuccess) return DYNAKV_EHIP;
     ++ix->n_prof;
@@ -207,6 +214,10 @@ dynakv_status_t dynakv_profile_read(dynakv_index_t* ix, int32_t* n_launches, dou
   *n_launches = ix->n_prof;
   *total_ms = tot;
   return DYNAKV_OK;
+}
+
+const char* dynakv_profiled_kernel(dynakv_index_t* ix) {
+  return ix && retrieve_is_fused(ix->view) ? "retrieve_fused_kernel" : "gather_attend_kernel";
 }
 
 const char* dynakv_strerror(dynakv_status_t s) {

@@ -16,7 +16,7 @@ constexpr int kMaxClusters = 8192;              // selection sorts one unit's cl
 constexpr int kMaxPrefill = 16384;              // k-means sorts one unit's labels in LDS
 constexpr int kMaxSplitMembers = 4096;          // largest cluster the split kernel handles
 constexpr int kMaxKvSplits = 64;
-constexpr int kCounters = 6;
+constexpr int kCounters = 8;
 constexpr int kInlinePages = 8;                 // pages of a cluster found without walking its chain                // workgroups that share one unit's gathered pages
 
 typedef float f4 __attribute__((ext_vector_type(4)));
@@ -24,7 +24,7 @@ typedef float f4 __attribute__((ext_vector_type(4)));
 // Device-side view of one index.  All arrays live in the caller's workspace.
 struct View {
   // configuration
-  int U, G, dtype, M0, Mcap, Ncap, Pcap, Bmax, group_reduce, S, NW;
+  int U, G, dtype, M0, Mcap, Ncap, Pcap, Bmax, group_reduce, S, NW, fuse;
   size_t Rstride;    // floats of centroid table per unit
   float var_alpha, size_factor, scale_f;
   double scale_d;
@@ -41,7 +41,7 @@ struct View {
   int* bump;         // [U] pages handed out from the pool so far
   int* free_top;     // [U] entries on the free-page stack
   int* last_assign;  // [U]
-  long long* counters;  // [U][6] splits, failed, forced, (unused), entries gathered, retrievals
+  long long* counters;  // [U][8] splits, failed, forced, (unused), entries gathered, retrievals, clusters scored, -
   // per cluster [U][Mcap]
   float* R;          // [U][Rstride] centroids, lane-interleaved: see r_index()
   int* cn;           // committed size n_j
@@ -270,6 +270,8 @@ __device__ inline void free_page(const View& v, int u, int page) {
 hipError_t launch_build_index(const View& v, const void* K, const void* V, int n_tokens, const int* init_idx,
                               int iters, void* workspace, size_t workspace_bytes, hipStream_t st);
 hipError_t launch_score_select(const View& v, const void* Q, int budget, hipStream_t st);
+bool retrieve_is_fused(const View& v);
+hipError_t launch_retrieve_fused(const View& v, const void* Q, int budget, float* out, float* lse, hipStream_t st);
 hipError_t launch_gather_attend(const View& v, const void* Q, float* out, float* lse, hipStream_t st);
 hipError_t launch_append(const View& v, const void* k, const void* val, hipStream_t st);
 hipError_t launch_split(const View& v, hipStream_t st);

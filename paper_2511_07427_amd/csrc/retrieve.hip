@@ -54,27 +54,25 @@ __device__ inline uint32_t orderable(float f) {
   return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
 
-// One workgroup per unit.
-__global__ __launch_bounds__(1024) void select_kernel(View v, int budget) {
-  __shared__ uint32_t skey[kMaxClusters];
-  __shared__ uint16_t sid[kMaxClusters];
-  __shared__ int sm[64];
-  __shared__ int s_cut, s_tsel;
-  const int u = blockIdx.x, tid = threadIdx.x;
-  const int M = v.M[u];
+// Selection for one unit, run by a whole workgroup of NT threads.  On entry skey/sid hold the orderable
+// scores and ids of the unit's M clusters, padded with (0, 0xFFFF) up to the next power of two.  Sorts them
+// by (score desc, id asc), takes the longest prefix whose stored sizes fit the budget, records the active set
+// and writes the gather list (page * 32 + valid tokens, in gather order) to the workspace and, as far as it
+// fits, to `lds_list`.  Returns the number of gather-list entries.
+template <int NT>
+__device__ inline int select_phase(const View& v, int u, int M, int budget, uint32_t* skey, uint16_t* sid, int* sm,
+                                   int* s_cut, int* s_tsel, int* lds_list, int lds_cap) {
+  constexpr int KCH = kMaxClusters / NT;      // consecutive ranks per thread in the prefix sums
+  const int tid = threadIdx.x;
   const size_t cb = (size_t)u * v.Mcap;
   int Mpad = 2;
   while (Mpad < M) Mpad <<= 1;
-  for (int i = tid; i < Mpad; i += 1024) {
-    skey[i] = i < M ? orderable(v.score[cb + i]) : 0u;
-    sid[i] = i < M ? (uint16_t)i : (uint16_t)0xFFFF;
-  }
-  if (tid == 0) { s_cut = 0; s_tsel = 0; }
+  if (tid == 0) { *s_cut = 0; *s_tsel = 0; }
   __syncthreads();
   // bitonic sort: a goes before b if its score is larger, or equal with the smaller id
   for (int k = 2; k <= Mpad; k <<= 1)
     for (int j = k >> 1; j > 0; j >>= 1) {
-      for (int i = tid; i < Mpad; i += 1024) {
+      for (int i = tid; i < Mpad; i += NT) {
         const int ixj = i ^ j;
         if (ixj > i) {
           const uint32_t ka = skey[i], kb = skey[ixj];
@@ -86,48 +84,51 @@ __global__ __launch_bounds__(1024) void select_kernel(View v, int budget) {
       }
       __syncthreads();
     }
-  // token prefix in score order: 8 consecutive ranks per thread
-  int sz[8], tot = 0;
-  for (int k = 0; k < 8; ++k) {
-    const int p = tid * 8 + k;
+  // token prefix in score order: KCH consecutive ranks per thread
+  int sz[KCH], tot = 0;
+#pragma unroll
+  for (int k = 0; k < KCH; ++k) {
+    const int p = tid * KCH + k;
     sz[k] = p < M ? v.cn[cb + sid[p]] + v.cb[cb + sid[p]] : 0;
     tot += sz[k];
   }
   int total;
   int run = block_excl_scan(tot, sm, total);
   int cnt = 0, fit = 0;
-  for (int k = 0; k < 8; ++k) {
-    const int p = tid * 8 + k;
+#pragma unroll
+  for (int k = 0; k < KCH; ++k) {
+    const int p = tid * KCH + k;
     if (p < M) {
       v.tok_off[cb + p] = run;
       run += sz[k];
       if (run <= budget) { ++cnt; fit = run; }   // prefix sums are monotone: these ranks form a prefix
     }
   }
-  if (cnt) { atomicAdd(&s_cut, cnt); atomicMax(&s_tsel, fit); }
+  if (cnt) { atomicAdd(s_cut, cnt); atomicMax(s_tsel, fit); }
   __syncthreads();
-  int cut = s_cut, tsel = s_tsel;
+  int cut = *s_cut, tsel = *s_tsel;
   const bool truncated = cut == 0 && M > 0 && budget > 0;     // best cluster alone is over budget
   if (truncated) { cut = 1; tsel = budget; }
   // page prefix over the selected ranks
-  int np[8];
   tot = 0;
-  for (int k = 0; k < 8; ++k) {
-    const int p = tid * 8 + k;
+#pragma unroll
+  for (int k = 0; k < KCH; ++k) {
+    const int p = tid * KCH + k;
     const int s = truncated ? budget : sz[k];
-    np[k] = p < cut ? (s + kPageTokens - 1) / kPageTokens : 0;
-    tot += np[k];
+    sz[k] = p < cut ? (s + kPageTokens - 1) / kPageTokens : 0;
+    tot += sz[k];
   }
   run = block_excl_scan(tot, sm, total);
-  for (int k = 0; k < 8; ++k) {
-    const int p = tid * 8 + k;
-    if (p < M) { v.pg_off[cb + p] = run; run += np[k]; }
+#pragma unroll
+  for (int k = 0; k < KCH; ++k) {
+    const int p = tid * KCH + k;
+    if (p < M) { v.pg_off[cb + p] = run; run += sz[k]; }
   }
   __syncthreads();
   // active set, id list and gather list
   int* plist = v.plist + (size_t)u * v.Pcap;
   int* poff = v.plist_off + (size_t)u * v.Pcap;
-  for (int p = tid; p < M; p += 1024) {
+  for (int p = tid; p < M; p += NT) {
     const int id = sid[p];
     v.sel_ids[cb + p] = id;
     v.in_req[cb + id] = p < cut;
@@ -139,6 +140,7 @@ __global__ __launch_bounds__(1024) void select_kernel(View v, int budget) {
         if (page < 0) break;
         const int nv = min(left, kPageTokens);
         plist[w] = page * 32 + nv;
+        if (w < lds_cap) lds_list[w] = page * 32 + nv;
         poff[w] = t0;
         ++w; t0 += nv; left -= nv;
       }
@@ -148,7 +150,26 @@ __global__ __launch_bounds__(1024) void select_kernel(View v, int budget) {
     v.n_sel[u] = cut; v.t_sel[u] = tsel; v.n_list[u] = total; v.ticket[u] = 0;
     v.counters[(size_t)u * kCounters + 4] += tsel;
     v.counters[(size_t)u * kCounters + 5] += 1;
+    v.counters[(size_t)u * kCounters + 6] += M;
   }
+  return total;
+}
+
+// One workgroup per unit.
+__global__ __launch_bounds__(1024) void select_kernel(View v, int budget) {
+  __shared__ uint32_t skey[kMaxClusters];
+  __shared__ uint16_t sid[kMaxClusters];
+  __shared__ int sm[64];
+  __shared__ int s_cut, s_tsel;
+  const int u = blockIdx.x, tid = threadIdx.x;
+  const int M = v.M[u];
+  int Mpad = 2;
+  while (Mpad < M) Mpad <<= 1;
+  for (int i = tid; i < Mpad; i += 1024) {
+    skey[i] = i < M ? orderable(v.score[(size_t)u * v.Mcap + i]) : 0u;
+    sid[i] = i < M ? (uint16_t)i : (uint16_t)0xFFFF;
+  }
+  select_phase<1024>(v, u, M, budget, skey, sid, sm, &s_cut, &s_tsel, nullptr, 0);
 }
 
 // ------------------------------------------------------------------------------------------- attention
@@ -417,6 +438,114 @@ __global__ __launch_bounds__(NW * 64) void gather_attend_kernel(View v, const vo
   }
 }
 
+// Whole retrieval of one unit in one workgroup (used when there is at least one unit per compute unit):
+// scores -> LDS, sort and budget cut in LDS, gather list in LDS, then the same page loop and merge as
+// gather_attend_kernel.  Saves two launches and every trip through the workspace between the phases.
+constexpr int kFusedClusters = 4096;   // clusters per unit the fused kernel can sort
+constexpr int kFusedList = 2048;       // gather-list entries it keeps in LDS (longer lists are read from the workspace)
+
+template <int DT, int NW, int GP>
+__global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const void* Q, int budget, float* out,
+                                                                float* lse) {
+  using F = Frag<DT>;
+  constexpr int NT = NW * 64;
+  constexpr int kPageBytes = kPageElems * (DT == DYNAKV_F32 ? 4 : 2);
+  constexpr int kMergeBytes = 64 * (kHeadDim + 2) * 4;          // NW * G <= 64 head rows
+  __shared__ __align__(16) unsigned char smem[kMergeBytes];     // sort arrays + list, later the merge buffer
+  __shared__ double qs[kHeadDim][GP];
+  __shared__ int sm[64];
+  __shared__ int s_cut, s_tsel;
+  uint32_t* skey = (uint32_t*)smem;                                   // [4096]
+  uint16_t* sid = (uint16_t*)(smem + kFusedClusters * 4);             // [4096]
+  int* list = (int*)(smem + kFusedClusters * 6);                      // [2048]
+  float* sm_o = (float*)smem;
+  const int u = blockIdx.x, tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int G = v.G;
+  const float* R = unit_R(v, u);
+
+  // ---- scores (float64, one lane per cluster)
+  f4 row[8];
+  const bool early = (tid & ~63) < v.M0;
+  if (early) load_centroid_head(R, tid, row);
+  const int M = v.M[u];
+  for (int t = tid; t < GP * kHeadDim; t += NT) {
+    const int g = t / kHeadDim, d = t % kHeadDim;
+    qs[d][g] = g < G ? (double)load_elem(Q, ((size_t)u * G + g) * kHeadDim + d, v.dtype) : 0.0;
+  }
+  int Mpad = 2;
+  while (Mpad < M) Mpad <<= 1;
+  for (int i = M + tid; i < Mpad; i += NT) { skey[i] = 0u; sid[i] = (uint16_t)0xFFFF; }
+  __syncthreads();
+  for (int j = tid; (j & ~63) < M; j += NT) {
+    if (!(early && j == tid)) load_centroid_head(R, j, row);
+    double acc[GP];
+#pragma unroll
+    for (int g = 0; g < GP; ++g) acc[g] = 0.0;
+    for_each_coord(R, j, row, [&](int d, float rv) {
+      const double rd = (double)rv;
+#pragma unroll
+      for (int g = 0; g < GP; ++g) acc[g] = fma(qs[d][g], rd, acc[g]);
+    });
+    if (j < M) {
+      double red = acc[0];
+#pragma unroll
+      for (int g = 1; g < GP; ++g)
+        if (g < G) red = v.group_reduce == DYNAKV_GROUP_MAX ? fmax(red, acc[g]) : red + acc[g];
+      const float sc = (float)(red * v.scale_d);
+      v.score[(size_t)u * v.Mcap + j] = sc;
+      skey[j] = orderable(sc);
+      sid[j] = (uint16_t)j;
+    }
+  }
+  __syncthreads();
+
+  // ---- selection
+  const int nlist = select_phase<NT>(v, u, M, budget, skey, sid, sm, &s_cut, &s_tsel, list, kFusedList);
+  __syncthreads();
+
+  // ---- gather + attention
+  const int g = lane & 15, lg = lane >> 4;
+  typename F::Qf q;
+  F::load_q(q, Q, (size_t)u * G + (g < G ? g : 0), lg, g < G);
+  const int* plist = v.plist + (size_t)u * v.Pcap;
+  const char* pages = v.pages + (size_t)u * v.Pcap * kPageBytes;
+  const float sc = v.scale_f * kLog2e;
+  Softmax st;
+  st.m = -__builtin_inff(); st.l = 0.f;
+#pragma unroll
+  for (int c = 0; c < 8; ++c) st.acc[c] = f4{0, 0, 0, 0};
+  const bool in_lds = nlist <= kFusedList;
+  for (int p = wave; p < nlist; p += NW) {
+    typename F::KV a;
+    const int e = in_lds ? list[p] : plist[p];
+    F::load(a, pages + (size_t)(e >> 5) * kPageBytes, lane, e & 31);
+    consume_page<F>(st, a, q, e & 31, lg, sc);
+  }
+  float l = st.l;
+  l += __shfl_xor(l, 16);
+  l += __shfl_xor(l, 32);
+  __syncthreads();                                    // the list is dead: its space becomes the merge buffer
+  const int hs = kHeadDim + 2, ws = G * hs;
+  if (g < G) {
+    float* o = sm_o + wave * ws + g * hs;
+#pragma unroll
+    for (int c = 0; c < 8; ++c)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) o[16 * c + 4 * lg + i] = st.acc[c][i];
+    if (lg == 0) { o[kHeadDim] = st.m; o[kHeadDim + 1] = l; }
+  }
+  __syncthreads();
+  for (int t = tid; t < G * kHeadDim; t += NT) {
+    const int gg = t / kHeadDim, dc = t % kHeadDim;
+    const float* b = sm_o + gg * hs;
+    float Mx, L, O;
+    merge_partials(b + kHeadDim, b + kHeadDim + 1, b + dc, NW, ws, Mx, L, O);
+    out[((size_t)u * G + gg) * kHeadDim + dc] = L > 0.f ? O / L : 0.f;
+    if (lse && dc == 0) lse[(size_t)u * G + gg] = L > 0.f ? (Mx + __builtin_amdgcn_logf(L)) * kLn2 : -__builtin_inff();
+  }
+}
+
 template <int DT, int NW, bool PF>
 void launch_ga(const View& v, const void* Q, float* out, float* lse, hipStream_t st) {
   const size_t lds = (size_t)NW * v.G * (kHeadDim + 2) * sizeof(float);
@@ -433,6 +562,23 @@ void launch_ga_dt(const View& v, const void* Q, float* out, float* lse, hipStrea
 }
 
 }  // namespace
+
+bool retrieve_is_fused(const View& v) {
+  return v.fuse && v.S == 1 && v.dtype != DYNAKV_F32 && v.Mcap <= kFusedClusters &&
+         ((v.NW == 16 && v.G <= 4) || (v.NW == 8 && v.G <= 8));
+}
+
+template <int DT>
+static void launch_fused(const View& v, const void* Q, int budget, float* out, float* lse, hipStream_t st) {
+  if (v.NW == 16) retrieve_fused_kernel<DT, 16, 4><<<v.U, 1024, 0, st>>>(v, Q, budget, out, lse);
+  else retrieve_fused_kernel<DT, 8, 8><<<v.U, 512, 0, st>>>(v, Q, budget, out, lse);
+}
+
+hipError_t launch_retrieve_fused(const View& v, const void* Q, int budget, float* out, float* lse, hipStream_t st) {
+  if (v.dtype == DYNAKV_F16) launch_fused<DYNAKV_F16>(v, Q, budget, out, lse, st);
+  else launch_fused<DYNAKV_BF16>(v, Q, budget, out, lse, st);
+  return hipGetLastError();
+}
 
 hipError_t launch_score_select(const View& v, const void* Q, int budget, hipStream_t st) {
   const dim3 grid((v.Mcap + 255) / 256, v.U);

@@ -68,6 +68,26 @@ def test_cfg5_long_shaped_bf16_group_of_8():
     say("long:", {k: r[k] for k in ("worst_rel", "ties", "splits", "forced", "clusters")})
 
 
+# --------------------------------------------------------------------------- launch shapes of the retrieval
+
+@pytest.mark.parametrize("name,units,steps,env", [
+    ("llama3_8b", [1, 2], 96, {"DYNAKV_KV_SPLITS": "1"}),                          # one kernel per retrieval, 16 wavefronts
+    ("qwen25_7b", [3], 160, {"DYNAKV_KV_SPLITS": "1"}),                            # one kernel, 8 wavefronts, G = 7
+    ("llama3_8b", [4], 64, {"DYNAKV_KV_SPLITS": "1", "DYNAKV_NO_FUSE": "1"}),      # three kernels, no split-KV
+    ("long131k", [2], 48, {"DYNAKV_KV_SPLITS": "3", "DYNAKV_ATT_WAVES": "8"}),     # split-KV with prefetching wavefronts
+])
+def test_every_launch_shape_of_retrieve_attend(name, units, steps, env, monkeypatch):
+    for k, val in env.items():
+        monkeypatch.setenv(k, val)
+    s = CONFIGS[name]
+    if name == "long131k":
+        s = s.scaled(kmeans_iters=2)
+    if name == "llama3_8b":
+        s = s.scaled(max_cluster_factor=8)
+    r = run_trajectory(s, units, steps, check_every=2, full_every=32)
+    say(name, env, {k: r[k] for k in ("worst_rel", "splits", "clusters")})
+
+
 # --------------------------------------------------------------------------- hand-worked fixtures, padded to d = 128
 
 def _pad(a):
