@@ -9,8 +9,9 @@
 // Arithmetic contract (so that every integer decision below is reproducible elsewhere):
 //   * inputs are float32 values (already rounded to the K/V storage type by the caller);
 //   * every dot product, squared distance, sum, mean and variance is accumulated in
-//     float64, LEFT TO RIGHT over the coordinate index 0..d-1 (and over members in storage
-//     order), one fused multiply-add per term;
+//     float64; sums over the coordinate index 0..d-1 run in one fixed order (blocks of 8 left
+//     to right from zero, block sums added left to right: see blocked_sum), sums over members
+//     run in storage order, one fused multiply-add per term;
 //   * centroids are STORED as float32 (rounded once per update); M2 (= n * variance) and the
 //     split threshold tau are stored as float64; cluster scores are rounded to float32
 //     before they are ordered; ties go to the lowest index.
@@ -87,31 +88,42 @@ struct Oracle {
 
 constexpr double kTieMargin = 1e-4;
 
-// ---- the two arithmetic primitives everything else is made of ------------------------
+// ---- the arithmetic primitives everything else is made of ---------------------------------
 
-// Left-to-right float64 dot product of two float32 vectors.
-inline double dot_ff(const float* a, const float* b, int d) {
-  double acc = 0.0;
-  for (int i = 0; i < d; ++i) acc = std::fma((double)a[i], (double)b[i], acc);
-  return acc;
-}
-// Left-to-right float64 squared distance between a float32 point and a float32 centre.
-inline double sqdist_ff(const float* x, const float* c, int d) {
-  double acc = 0.0;
-  for (int i = 0; i < d; ++i) {
-    const double t = (double)x[i] - (double)c[i];
-    acc = std::fma(t, t, acc);
+// Fixed summation order of every sum over the coordinate index ("blocked order"): the terms are taken in
+// blocks of 8 consecutive coordinates; inside a block they are accumulated left to right from zero, one
+// fused multiply-add per term; the block sums are then added left to right.  The paper fixes no order;
+// this one is part of this repository's arithmetic contract (short dependency chains on a GPU).
+constexpr int kBlock = 8;
+// sum over i of one term per coordinate, in the order above; fma_term(i, acc) returns fma(factors of term i, acc)
+template <class F>
+inline double blocked_sum(int d, F&& fma_term) {
+  double total = 0.0;
+  for (int i0 = 0; i0 < d; i0 += kBlock) {
+    double acc = 0.0;
+    for (int i = i0; i < std::min(d, i0 + kBlock); ++i) acc = fma_term(i, acc);
+    total += acc;
   }
-  return acc;
+  return total;
+}
+
+// float64 dot product of two float32 vectors.
+inline double dot_ff(const float* a, const float* b, int d) {
+  return blocked_sum(d, [&](int i, double acc) { return std::fma((double)a[i], (double)b[i], acc); });
+}
+// float64 squared distance between a float32 point and a float32 centre.
+inline double sqdist_ff(const float* x, const float* c, int d) {
+  return blocked_sum(d, [&](int i, double acc) {
+    const double t = (double)x[i] - (double)c[i];
+    return std::fma(t, t, acc);
+  });
 }
 // Same, centre held in float64 (used inside a split, where centres are not rounded).
 inline double sqdist_fd(const float* x, const double* c, int d) {
-  double acc = 0.0;
-  for (int i = 0; i < d; ++i) {
+  return blocked_sum(d, [&](int i, double acc) {
     const double t = (double)x[i] - c[i];
-    acc = std::fma(t, t, acc);
-  }
-  return acc;
+    return std::fma(t, t, acc);
+  });
 }
 
 inline double norm_margin(double gap, double a, double b) {
@@ -357,12 +369,10 @@ void append_unit(const Config& c, Unit& u, const float* k, const float* v) {
   // UpdateVar: tentative size, centroid and M2 from (n, r, M2) and the new entry alone
   const int32_t n1 = cl.n + 1;
   std::vector<double> r1(d);
-  double M2 = cl.M2;
-  for (int i = 0; i < d; ++i) {
-    const double delta = (double)k[i] - (double)cl.r[i];
-    r1[i] = (double)cl.r[i] + delta / (double)n1;
-    M2 = std::fma(delta, (double)k[i] - r1[i], M2);
-  }
+  for (int i = 0; i < d; ++i) r1[i] = (double)cl.r[i] + ((double)k[i] - (double)cl.r[i]) / (double)n1;
+  const double M2 = cl.M2 + blocked_sum(d, [&](int i, double acc) {
+    return std::fma((double)k[i] - (double)cl.r[i], (double)k[i] - r1[i], acc);   // delta_i * (k_i - r'_i)
+  });
   const double var1 = M2 / (double)n1;
   bool trig = false;
   if (n1 >= 2) {

@@ -118,31 +118,79 @@ __host__ __device__ inline size_t r_index(int j, int d) {
 __host__ __device__ inline size_t r_stride(int Mcap) { return (size_t)((Mcap + 63) / 64) * 64 * kHeadDim; }
 __device__ inline float* unit_R(const View& v, int u) { return v.R + (size_t)u * v.Rstride; }
 
-// Feeds the 128 coordinates of centroid j to f(d, value) in ascending d, with the loads of the next 32
-// coordinates in flight while the current 32 are consumed.  `first` holds coordinates 0..31, already
-// loaded by the caller (so that the caller can issue them before anything else it waits for).
+// ---- the fixed summation order ----------------------------------------------------------------------
+// Every float64 sum over the 128 coordinates runs in one order: blocks of 8 consecutive coordinates are
+// accumulated left to right from zero (one fused multiply-add per term), and the 16 block sums are added left
+// to right.  Dependency chains stay short, and the value is the same whether one lane owns the whole sum or 16
+// lanes own one block each.
+
+// One thread: block_sum(k) returns the sum of block k (k = 0..15, called in ascending k).
+template <class F>
+__device__ __forceinline__ double blocked16(F&& block_sum) {
+  double total = 0.0;
+#pragma unroll 4
+  for (int k = 0; k < 16; ++k) total += block_sum(k);
+  return total;
+}
+// Four consecutive lanes (one DPP quad), lane q holding the sums of blocks 4q..4q+3 in bs[]: every lane of
+// the quad gets the total ((s0 + s1) + s2) + ... + s15, added strictly left to right.
+__device__ inline double blocked16_quad(const double (&bs)[4]) {
+  const int q = threadIdx.x & 3;
+  double t = 0.0;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    double in = 0.0;
+    if (r > 0) {   // running total of the lane to the left: quad_perm [0, 0, 1, 2]
+      const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(t), 0x90, 0xF, 0xF, false);
+      const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(t), 0x90, 0xF, 0xF, false);
+      in = __hiloint2double(hi, lo);
+    }
+    const double mine = (((in + bs[0]) + bs[1]) + bs[2]) + bs[3];
+    if (q == r) t = mine;
+  }
+  const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(t), 0xFF, 0xF, 0xF, false);   // quad_perm [3, 3, 3, 3]
+  const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(t), 0xFF, 0xF, 0xF, false);
+  return __hiloint2double(hi, lo);
+}
+
+// Centroid j of the lane-interleaved table against NACC operands at once: out[a] = sum over d of the terms that
+// term(d, r_d, acc) adds into acc[a] with one fma each, in the order above.  The loads of the next 32
+// coordinates are in flight while the current 32 are consumed; `cur` holds coordinates 0..31, loaded by the
+// caller with load_centroid_head (so that it can issue them before anything else it waits for).
 __device__ inline void load_centroid_head(const float* R, int j, f4 (&first)[8]) {
   const f4* r = (const f4*)(R + r_index(j, 0));
 #pragma unroll
   for (int i = 0; i < 8; ++i) first[i] = r[i * 64];
 }
-template <class F>
-__device__ inline void for_each_coord(const float* R, int j, f4 (&cur)[8], F&& f) {
+template <int NACC, bool PREFETCH = true, class F>
+__device__ __forceinline__ void centroid_sums(const float* R, int j, f4 (&cur)[8], double (&out)[NACC], F&& term) {
   const f4* r = (const f4*)(R + r_index(j, 0));
-  f4 nxt[8];
+  f4 nxt[PREFETCH ? 8 : 1];
+#pragma unroll
+  for (int a = 0; a < NACC; ++a) out[a] = 0.0;
 #pragma unroll 1
   for (int b = 0; b < 4; ++b) {
-    if (b < 3) {
+    if (PREFETCH && b < 3) {
 #pragma unroll
       for (int i = 0; i < 8; ++i) nxt[i] = r[((b + 1) * 8 + i) * 64];
     }
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
+    for (int k = 0; k < 4; ++k) {             // four blocks of 8 coordinates
+      double acc[NACC];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) f(b * 32 + i * 4 + e, cur[i][e]);
+      for (int a = 0; a < NACC; ++a) acc[a] = 0.0;
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) term(b * 32 + k * 8 + i * 4 + e, cur[k * 2 + i][e], acc);
+        if (!PREFETCH) asm volatile("" ::: "memory");   // lean variant: operand loads stay four coordinates deep
+      }
+#pragma unroll
+      for (int a = 0; a < NACC; ++a) out[a] += acc[a];
+    }
     if (b < 3) {
 #pragma unroll
-      for (int i = 0; i < 8; ++i) cur[i] = nxt[i];
+      for (int i = 0; i < 8; ++i) cur[i] = PREFETCH ? nxt[i] : r[((b + 1) * 8 + i) * 64];
     }
   }
 }

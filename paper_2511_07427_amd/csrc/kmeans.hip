@@ -56,12 +56,20 @@ __global__ __launch_bounds__(256) void kmeans_assign_f64_kernel(View v, const vo
     for (int t = threadIdx.x; t < nt * kHeadDim; t += 256) rs[t / kHeadDim][t % kHeadDim] = R[r_index(j0 + t / kHeadDim, t % kHeadDim)];
     __syncthreads();
     for (int jj = 0; jj < nt; ++jj) {
+      double blk[16];
+#pragma unroll
+      for (int k = 0; k < 16; ++k) {
+        double a = 0.0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const double t = (double)x[k * 8 + e] - (double)rs[jj][k * 8 + e];
+          a = fma(t, t, a);
+        }
+        blk[k] = a;
+      }
       double acc = 0.0;
 #pragma unroll
-      for (int d = 0; d < kHeadDim; ++d) {
-        const double t = (double)x[d] - (double)rs[jj][d];
-        acc = fma(t, t, acc);
-      }
+      for (int k = 0; k < 16; ++k) acc += blk[k];
       if (acc < best) { best = acc; arg = j0 + jj; }
     }
   }
@@ -385,11 +393,12 @@ __global__ __launch_bounds__(256) void kmeans_exact_kernel(View v, const void* X
     for (int j = tid; j < v.M0; j += 256) {
       f4 row[8];
       load_centroid_head(R, j, row);
-      double acc = 0.0;
-      for_each_coord(R, j, row, [&](int d, float rv) {
+      double dist[1];
+      centroid_sums<1>(R, j, row, dist, [&](int d, float rv, double (&a)[1]) __attribute__((always_inline)) {
         const double t = xd[d] - (double)rv;
-        acc = fma(t, t, acc);
+        a[0] = fma(t, t, a[0]);
       });
+      const double acc = dist[0];
       if (acc < best || arg < 0) { best = acc; arg = j; }
     }
     block_arg_reduce<false>(best, arg, sv, si);
@@ -405,19 +414,18 @@ __global__ __launch_bounds__(256) void kmeans_dist_kernel(View v, const void* X,
   const int j = v.labels[(size_t)u * v.Ncap + i];
   const float* R = unit_R(v, u);
   const size_t base = ((size_t)u * N0 + i) * kHeadDim;
-  double acc = 0.0;
-#pragma unroll 4
-  for (int d8 = 0; d8 < kHeadDim / 8; ++d8) {
+  v.dist[(size_t)u * v.Ncap + i] = blocked16([&](int k) __attribute__((always_inline)) {
     float x[8];
-    load8(X, base + d8 * 8, v.dtype, x);
-    const f4 ra = *(const f4*)(R + r_index(j, d8 * 8)), rb = *(const f4*)(R + r_index(j, d8 * 8 + 4));
+    load8(X, base + k * 8, v.dtype, x);
+    const f4 ra = *(const f4*)(R + r_index(j, k * 8)), rb = *(const f4*)(R + r_index(j, k * 8 + 4));
+    double acc = 0.0;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       const double t = (double)x[e] - (double)(e < 4 ? ra[e] : rb[e - 4]);
       acc = fma(t, t, acc);
     }
-  }
-  v.dist[(size_t)u * v.Ncap + i] = acc;
+    return acc;
+  });
 }
 
 // dist[i] = squared distance of point i to the (updated) centre of its own cluster
@@ -427,19 +435,18 @@ __global__ __launch_bounds__(256) void point_dist_kernel(View v, const void* X, 
   const int j = v.labels[(size_t)u * v.Ncap + i];
   const float* R = unit_R(v, u);
   const size_t base = ((size_t)u * N0 + i) * kHeadDim;
-  double acc = 0.0;
-#pragma unroll 4
-  for (int d8 = 0; d8 < kHeadDim / 8; ++d8) {
+  v.dist[(size_t)u * v.Ncap + i] = blocked16([&](int k) __attribute__((always_inline)) {
     float x[8];
-    load8(X, base + d8 * 8, v.dtype, x);
-    const f4 ra = *(const f4*)(R + r_index(j, d8 * 8)), rb = *(const f4*)(R + r_index(j, d8 * 8 + 4));
+    load8(X, base + k * 8, v.dtype, x);
+    const f4 ra = *(const f4*)(R + r_index(j, k * 8)), rb = *(const f4*)(R + r_index(j, k * 8 + 4));
+    double acc = 0.0;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       const double t = (double)x[e] - (double)(e < 4 ? ra[e] : rb[e - 4]);
       acc = fma(t, t, acc);
     }
-  }
-  v.dist[(size_t)u * v.Ncap + i] = acc;
+    return acc;
+  });
 }
 
 // One workgroup per unit: per-cluster n, M2 (members in order), page chains, tau, counters.

@@ -33,11 +33,12 @@ __global__ __launch_bounds__(256) void append_kernel(View v, const void* kin, co
   int arg = -1;
   for (int j = tid; j < M; j += 256) {
     if (j != tid) load_centroid_head(R, j, row);
-    double acc = 0.0;
-    for_each_coord(R, j, row, [&](int d, float rv) {
+    double dist[1];
+    centroid_sums<1>(R, j, row, dist, [&](int d, float rv, double (&a)[1]) __attribute__((always_inline)) {
       const double t = kd[d] - (double)rv;
-      acc = fma(t, t, acc);
+      a[0] = fma(t, t, a[0]);
     });
+    const double acc = dist[0];
     if (acc < best || arg < 0) { best = acc; arg = j; }
   }
   block_arg_reduce<false>(best, arg, sv, si);
@@ -76,9 +77,13 @@ __global__ __launch_bounds__(256) void append_kernel(View v, const void* kin, co
       if (v.cflag[cbase + j]) {
         v.cb[cbase + j] += 1;             // goes to the buffer of a flagged cluster
       } else {
-        // UpdateVar, the running part: M2' = M2 + sum_d delta_d * (k_d - r'_d), left to right
-        double M2 = v.cM2[cbase + j];
-        for (int d = 0; d < kHeadDim; ++d) M2 = fma(delta[d], kd[d] - r1[d], M2);
+        // UpdateVar, the running part: M2' = M2 + sum_d delta_d * (k_d - r'_d)
+        const double M2 = v.cM2[cbase + j] + blocked16([&](int k) __attribute__((always_inline)) {
+          double a = 0.0;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) a = fma(delta[k * 8 + e], kd[k * 8 + e] - r1[k * 8 + e], a);
+          return a;
+        });
         const double var1 = M2 / (double)n1;
         bool trig = false;
         if (n1 >= 2) {
@@ -127,8 +132,8 @@ struct SplitSmem {
   unsigned short perm[kMaxSplitMembers];           // members of the staying child in order, then of the moved one
   double cA[kHeadDim], cB[kHeadDim];
   float rA[kHeadDim], rB[kHeadDim];
-  double sv[256];
-  int si[256];
+  double sv[16];
+  int si[16];
   double dl[128];                                  // member distances of a staged cluster
   int scan[64];
   int flag, count, nchain;
@@ -169,26 +174,97 @@ struct Keys {
   }
 };
 
-// Left-to-right float64 squared distances of member i to one or two centres (C = double or float).
+constexpr int kSplitThreads = 512;
+
+// Arg-max over (value, index) pairs held one per thread of the whole block; ties go to the lowest index;
+// index < 0 means "no candidate".  Wavefront shuffles first, then the 16 wavefront winners through LDS.
+__device__ inline void block_argmax(double val, int idx, double* sv, int* si) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  for (int o = 32; o > 0; o >>= 1) {
+    const double ov = __shfl_xor(val, o);
+    const int oi = __shfl_xor(idx, o);
+    if (oi >= 0 && (idx < 0 || ov > val || (ov == val && oi < idx))) { val = ov; idx = oi; }
+  }
+  __syncthreads();
+  if (lane == 0) { sv[w] = val; si[w] = idx; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int k = 1; k < kSplitThreads / 64; ++k)
+      if (si[k] >= 0 && (si[0] < 0 || sv[k] > sv[0] || (sv[k] == sv[0] && si[k] < si[0]))) { sv[0] = sv[k]; si[0] = si[k]; }
+  }
+  __syncthreads();
+}
+
+// Squared distances of member i to one or two centres (C = double or float) in the fixed summation order.
+// Called by the four lanes of a quad at once: lane q accumulates blocks 4q..4q+3 (coordinates 32q..32q+31),
+// the block sums are then added left to right across the quad; every lane returns the totals.
 template <class K, class C>
-__device__ inline void sqdist_member(const K& ks, int i, const C* cA, const C* cB, double& dA, double& dB) {
-  double a = 0.0, b = 0.0;
-#pragma unroll 4
-  for (int d8 = 0; d8 < kHeadDim / 8; ++d8) {
+__device__ inline void quad_sqdist(const K& ks, int i, int q, const C* cA, const C* cB, double& dA, double& dB) {
+  double sa[4], sb[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    // every operand of the block is requested before the first use, so the LDS latency is paid once per block
     float x[8];
-    ks.get8(i, d8, x);
+    C ca[8], cb[8];
+    ks.get8(i, q * 4 + k, x);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { ca[e] = cA[(q * 4 + k) * 8 + e]; cb[e] = cB ? cB[(q * 4 + k) * 8 + e] : C(0); }
+    asm volatile("" ::: "memory");
+    double a = 0.0, b = 0.0;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       const double xd = (double)x[e];
-      const double ta = xd - (double)cA[d8 * 8 + e];
+      const double ta = xd - (double)ca[e];
       a = fma(ta, ta, a);
       if (cB) {
-        const double tb = xd - (double)cB[d8 * 8 + e];
+        const double tb = xd - (double)cb[e];
         b = fma(tb, tb, b);
       }
     }
+    sa[k] = a; sb[k] = b;
   }
-  dA = a; dB = b;
+  dA = blocked16_quad(sa);
+  dB = cB ? blocked16_quad(sb) : 0.0;
+}
+
+// Sum over r = 0..n-1, in that order, of key(r) for the r that use(r) accepts: eight operands are requested
+// at a time (clamped, so the loads do not depend on the test), then added one by one; a rejected or
+// out-of-range term adds +0.0, which leaves the float64 sum unchanged.
+template <class Key, class Use>
+__device__ inline double ordered_sum(int n, Key&& key, Use&& use) {
+  double sum = 0.0;
+  for (int r0 = 0; r0 < n; r0 += 8) {
+    float x[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int r = min(r0 + k, n - 1);
+      const float kv = key(r);
+      x[k] = (r0 + k < n && use(r)) ? kv : 0.f;
+    }
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int k = 0; k < 8; ++k) sum += (double)x[k];
+  }
+  return sum;
+}
+
+// Arg-max of dist[0..n) (ties to the lowest index) by one thread, eight loads at a time; result in sv[0], si[0].
+__device__ inline void serial_argmax(const double* dist, int n, double* sv, int* si) {
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double bv = -1.0; int bi = -1;
+    for (int r0 = 0; r0 < n; r0 += 8) {
+      double x[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) x[k] = dist[min(r0 + k, n - 1)];
+      asm volatile("" ::: "memory");
+#pragma unroll
+      for (int k = 0; k < 8; ++k)
+        if (r0 + k < n && x[k] > bv) { bv = x[k]; bi = r0 + k; }
+    }
+    sv[0] = bv; si[0] = bi;
+  }
+  __syncthreads();
 }
 
 // Exact statistics of both children at once: members perm[0 .. nS) form cluster idS, perm[nS .. m) cluster idM
@@ -197,28 +273,35 @@ __device__ inline void sqdist_member(const K& ks, int i, const C* cA, const C* c
 template <class K>
 __device__ inline void children_stats(const View& v, int u, SplitSmem& s, const K& ks, bool staged, int nS, int m,
                                       int idS, int idM) {
-  const int tid = threadIdx.x, d = tid & (kHeadDim - 1), c = tid >> 7;
+  const int tid = threadIdx.x, d = tid & (kHeadDim - 1), c = (tid >> 7) & 1;
   const int q0 = c ? nS : 0, q1 = c ? m : nS, id = c ? idM : idS;
-  float* r = c ? s.rB : s.rA;
-  {
-    double sum = 0.0;
-#pragma unroll 8
-    for (int q = q0; q < q1; ++q) sum += (double)ks.get(s.perm[q], d);
+  if (tid < 2 * kHeadDim) {
+    float* r = c ? s.rB : s.rA;
+    const double sum = ordered_sum(q1 - q0, [&](int r) { return ks.get(s.perm[q0 + r], d); }, [](int) { return true; });
     r[d] = q1 > q0 ? (float)(sum / (double)(q1 - q0)) : 0.f;
     if (id >= 0) unit_R(v, u)[r_index(id, d)] = r[d];
   }
   __syncthreads();
   double* dist = staged ? s.dl : v.dist + (size_t)u * v.Ncap;
-  for (int q = tid; q < m; q += 256) {
+  const int grp = tid >> 2, k = tid & 3;
+  for (int base = 0; base < m; base += kSplitThreads / 4) {
+    if (base + (int)((tid & ~63) >> 2) >= m) continue;      // this wavefront has no member
+    const int q = base + grp, qc = min(q, m - 1);
     double da, db;
-    sqdist_member<K, float>(ks, s.perm[q], q < nS ? s.rA : s.rB, nullptr, da, db);
-    dist[q] = da;
+    quad_sqdist<K, float>(ks, s.perm[qc], k, qc < nS ? s.rA : s.rB, nullptr, da, db);
+    if (k == 0 && q < m) dist[q] = da;
   }
   __syncthreads();
-  if (d == 0) {
+  if (d == 0 && tid < 2 * kHeadDim) {
     double acc = 0.0;
-#pragma unroll 8
-    for (int q = q0; q < q1; ++q) acc += dist[q];
+    for (int r0 = q0; r0 < q1; r0 += 8) {
+      double x[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) x[k] = r0 + k < q1 ? dist[r0 + k] : 0.0;
+      asm volatile("" ::: "memory");
+#pragma unroll
+      for (int k = 0; k < 8; ++k) acc += x[k];
+    }
     s.m2[c] = acc;
   }
   __syncthreads();
@@ -227,7 +310,9 @@ __device__ inline void children_stats(const View& v, int u, SplitSmem& s, const 
 // Splits cluster j of unit u (2-means; Algorithm 1 SplitCluster).  Whole block; all branches uniform.
 template <int DT, bool STAGED>
 __device__ __noinline__ void split_cluster_impl(const View& v, int u, int j, int m, SplitSmem& s) {
-  const int tid = threadIdx.x;
+  constexpr int NT = kSplitThreads;
+  const int tid = threadIdx.x, grp = tid >> 2, kb = tid & 3;
+  const int wave_first = (tid & ~63) >> 2;                    // first member this wavefront would take in a pass
   const size_t cbase = (size_t)u * v.Mcap;
   constexpr int kEs = DT == DYNAKV_F32 ? 4 : 2;
   constexpr int kChunks = kHeadDim * kEs / 16;                      // 16-byte chunks per key
@@ -239,8 +324,7 @@ __device__ __noinline__ void split_cluster_impl(const View& v, int u, int j, int
     return (size_t)(DT == DYNAKV_F32 ? k_index32(slot, 4 * c) : k_index16(slot, 8 * c)) * kEs;
   };
   if constexpr (STAGED) {                  // one pass over the cluster's keys; every later pass reads LDS
-#pragma unroll 4
-    for (int t = tid; t < m * kChunks; t += 256) {
+    for (int t = tid; t < m * kChunks; t += NT) {
       const int i = t / kChunks, c = t % kChunks;
       *(uint4*)(s.stage + (size_t)i * kRowBytes + c * 16) =
           *(const uint4*)(pool + (size_t)s.chain[i >> 4] * (kPageElems * kEs) + kchunk(i & 15, c));
@@ -251,30 +335,32 @@ __device__ __noinline__ void split_cluster_impl(const View& v, int u, int j, int
   if (can_split) {
     // seeds: A = member farthest from the mean of all members, B = member farthest from A
     if (tid < kHeadDim) {
-      double sum = 0.0;
-#pragma unroll 8
-      for (int i = 0; i < m; ++i) sum += (double)ks.get(i, tid);
+      const double sum = ordered_sum(m, [&](int i) { return ks.get(i, tid); }, [](int) { return true; });
       s.cA[tid] = sum / (double)m;
     }
     __syncthreads();
-    double bv = -1.0, dummy; int bi = -1;
-    for (int i = tid; i < m; i += 256) {
+    double dummy;
+    double* const seed_dist = STAGED ? s.dl : v.dist + (size_t)u * v.Ncap;
+    for (int base = 0; base < m; base += NT / 4) {
+      if (base + wave_first >= m) continue;
+      const int i = base + grp;
       double t;
-      sqdist_member<decltype(ks), double>(ks, i, s.cA, nullptr, t, dummy);
-      if (t > bv) { bv = t; bi = i; }
+      quad_sqdist<decltype(ks), double>(ks, min(i, m - 1), kb, s.cA, nullptr, t, dummy);
+      if (kb == 0 && i < m) seed_dist[i] = t;
     }
-    block_arg_reduce<true>(bv, bi, s.sv, s.si);
+    serial_argmax(seed_dist, m, s.sv, s.si);
     const int a = s.si[0];
     __syncthreads();
     if (tid < kHeadDim) s.cB[tid] = (double)ks.get(a, tid);
     __syncthreads();
-    bv = -1.0; bi = -1;
-    for (int i = tid; i < m; i += 256) {
+    for (int base = 0; base < m; base += NT / 4) {
+      if (base + wave_first >= m) continue;
+      const int i = base + grp;
       double t;
-      sqdist_member<decltype(ks), double>(ks, i, s.cB, nullptr, t, dummy);
-      if (t > bv) { bv = t; bi = i; }
+      quad_sqdist<decltype(ks), double>(ks, min(i, m - 1), kb, s.cB, nullptr, t, dummy);
+      if (kb == 0 && i < m) seed_dist[i] = t;
     }
-    block_arg_reduce<true>(bv, bi, s.sv, s.si);
+    serial_argmax(seed_dist, m, s.sv, s.si);
     const int b = s.si[0];
     const double db = s.sv[0];
     __syncthreads();
@@ -283,18 +369,22 @@ __device__ __noinline__ void split_cluster_impl(const View& v, int u, int j, int
       if (tid < kHeadDim) { s.cA[tid] = s.cB[tid]; }
       __syncthreads();
       if (tid < kHeadDim) s.cB[tid] = (double)ks.get(b, tid);
-      for (int i = tid; i < m; i += 256) s.side[i] = 2;
+      for (int i = tid; i < m; i += NT) s.side[i] = 2;
       if (tid == 0) { s.flag = 0; s.count = 0; }
       __syncthreads();
       for (int it = 0; it < 16; ++it) {
         int changed = 0, na = 0;
-        for (int i = tid; i < m; i += 256) {
+        for (int base = 0; base < m; base += NT / 4) {
+          if (base + wave_first >= m) continue;
+          const int i = base + grp;
           double dA, dB;
-          sqdist_member<decltype(ks), double>(ks, i, s.cA, s.cB, dA, dB);
-          const unsigned char ns = dA <= dB ? 0 : 1;   // tie -> side A
-          changed |= ns != s.side[i];
-          s.side[i] = ns;
-          na += ns == 0;
+          quad_sqdist<decltype(ks), double>(ks, min(i, m - 1), kb, s.cA, s.cB, dA, dB);
+          if (kb == 0 && i < m) {
+            const unsigned char ns = dA <= dB ? 0 : 1;   // tie -> side A
+            changed |= ns != s.side[i];
+            s.side[i] = ns;
+            na += ns == 0;
+          }
         }
         if (changed) s.flag = 1;
         if (na) atomicAdd(&s.count, na);
@@ -304,12 +394,10 @@ __device__ __noinline__ void split_cluster_impl(const View& v, int u, int j, int
         __syncthreads();
         if (!moved) break;
         if (nA == 0 || nA == m) { can_split = false; break; }
-        {
+        if (tid < 2 * kHeadDim) {
           const int d = tid & (kHeadDim - 1);
           const unsigned char mine = tid < kHeadDim ? 0 : 1;
-          double sum = 0.0;             // adding +0.0 for the other side's members leaves the sum unchanged
-#pragma unroll 8
-          for (int i = 0; i < m; ++i) sum += s.side[i] == mine ? (double)ks.get(i, d) : 0.0;
+          const double sum = ordered_sum(m, [&](int i) { return ks.get(i, d); }, [&](int i) { return s.side[i] == mine; });
           if (mine == 0) s.cA[d] = sum / (double)nA;
           else s.cB[d] = sum / (double)(m - nA);
         }
@@ -319,7 +407,7 @@ __device__ __noinline__ void split_cluster_impl(const View& v, int u, int j, int
     }
   }
   if (!can_split) {                       // unflag with exact statistics of the whole cluster
-    for (int i = tid; i < m; i += 256) s.perm[i] = (unsigned short)i;
+    for (int i = tid; i < m; i += NT) s.perm[i] = (unsigned short)i;
     __syncthreads();
     children_stats(v, u, s, ks, STAGED, m, m, j, -1);
     if (tid == 0) {
@@ -337,7 +425,7 @@ __device__ __noinline__ void split_cluster_impl(const View& v, int u, int j, int
   }
   // stable partition: the child that holds the earliest entry keeps id j
   const unsigned char keep = s.side[0];
-  const int chunk = (m + 255) / 256;
+  const int chunk = (m + NT - 1) / NT;
   const int lo = min(m, tid * chunk), hi = min(m, lo + chunk);
   int mine = 0;
   for (int i = lo; i < hi; ++i) mine += s.side[i] == keep;
@@ -354,22 +442,21 @@ __device__ __noinline__ void split_cluster_impl(const View& v, int u, int j, int
   }
   // fresh pages for both children (recycled pages first); the parent's pages are recycled afterwards
   const int from_free = min(need, top);
-  for (int k = tid; k < need; k += 256)
+  for (int k = tid; k < need; k += NT)
     s.newpg[k] = k < from_free ? v.freelist[(size_t)u * v.Pcap + top - 1 - k] : bump + (k - from_free);
   __syncthreads();
-  for (int k = tid; k < need; k += 256) {
+  for (int k = tid; k < need; k += NT) {
     const bool last = k == pS - 1 || k == need - 1;
     v.pnext[(size_t)u * v.Pcap + s.newpg[k]] = last ? -1 : s.newpg[k + 1];
   }
   if (need > from_free) {                 // pages never used before are zeroed first
     constexpr int n16 = kPageElems * kEs / 16;
-    for (int t = tid; t < (need - from_free) * n16; t += 256)
+    for (int t = tid; t < (need - from_free) * n16; t += NT)
       ((uint4*)(pool + (size_t)s.newpg[from_free + t / n16] * (kPageElems * kEs)))[t % n16] = uint4{0, 0, 0, 0};
     __syncthreads();
   }
   // keys in 16-byte chunks, values element by element (their page layout interleaves four tokens)
-#pragma unroll 4
-  for (int t = tid; t < m * kChunks; t += 256) {
+  for (int t = tid; t < m * kChunks; t += NT) {
     const int q = t / kChunks, c = t % kChunks;
     const int i = s.perm[q];
     const int r = q < nS ? q : q - nS;
@@ -379,8 +466,8 @@ __device__ __noinline__ void split_cluster_impl(const View& v, int u, int j, int
     else w = *(const uint4*)(pool + (size_t)s.chain[i >> 4] * (kPageElems * kEs) + kchunk(i & 15, c));
     *(uint4*)(pool + (size_t)dpage * (kPageElems * kEs) + kchunk(r & 15, c)) = w;
   }
-#pragma unroll 8
-  for (int t = tid; t < m * kHeadDim; t += 256) {
+#pragma unroll 4
+  for (int t = tid; t < m * kHeadDim; t += NT) {
     const int q = t >> 7, d = t & 127;
     const int i = s.perm[q];
     const int r = q < nS ? q : q - nS;
@@ -392,7 +479,7 @@ __device__ __noinline__ void split_cluster_impl(const View& v, int u, int j, int
           v.ppos[((size_t)u * v.Pcap + s.chain[i >> 4]) * kPageTokens + (i & 15)];
   }
   children_stats(v, u, s, ks, STAGED, nS, m, j, M);
-  for (int k = tid; k < s.nchain; k += 256) v.freelist[(size_t)u * v.Pcap + (top - from_free) + k] = s.chain[k];
+  for (int k = tid; k < s.nchain; k += NT) v.freelist[(size_t)u * v.Pcap + (top - from_free) + k] = s.chain[k];
   if (tid < kInlinePages) {
     v.cpg[(cbase + j) * kInlinePages + tid] = tid < pS ? s.newpg[tid] : -1;
     v.cpg[(cbase + M) * kInlinePages + tid] = tid < pM ? s.newpg[pS + tid] : -1;
@@ -435,7 +522,8 @@ __device__ void split_cluster(const View& v, int u, int j, SplitSmem& s) {
 }
 
 template <int DT>
-__global__ __launch_bounds__(256) void split_kernel(View v) {
+__global__ __launch_bounds__(kSplitThreads) void split_kernel(View v) {
+  constexpr int NT = kSplitThreads;
   __shared__ SplitSmem s;
   __shared__ int s_min;
   __shared__ long long s_tot;
@@ -449,7 +537,7 @@ __global__ __launch_bounds__(256) void split_kernel(View v) {
   while (true) {
     if (tid == 0) s_min = 0x7FFFFFFF;
     __syncthreads();
-    for (int j = cursor + tid; j < M0; j += 256)
+    for (int j = cursor + tid; j < M0; j += NT)
       if (v.cflag[cbase + j] && (v.Bmax == 0 || v.in_req[cbase + j])) { atomicMin(&s_min, j); break; }
     __syncthreads();
     const int j = s_min;
@@ -466,14 +554,14 @@ __global__ __launch_bounds__(256) void split_kernel(View v) {
     __syncthreads();
     double bv = -1.0; int bi = -1;
     long long tot = 0;
-    for (int j = tid; j < M; j += 256)
+    for (int j = tid; j < M; j += NT)
       if (v.cflag[cbase + j]) {
         const int b = v.cb[cbase + j];
         tot += b;
         if ((double)b > bv) { bv = (double)b; bi = j; }
       }
     if (tot) atomicAdd((unsigned long long*)&s_tot, (unsigned long long)tot);
-    block_arg_reduce<true>(bv, bi, s.sv, s.si);
+    block_argmax(bv, bi, s.sv, s.si);
     const int arg = s.si[0];
     const long long total = s_tot;
     __syncthreads();
@@ -567,9 +655,9 @@ hipError_t launch_append(const View& v, const void* k, const void* val, hipStrea
   return hipGetLastError();
 }
 hipError_t launch_split(const View& v, hipStream_t st) {
-  if (v.dtype == DYNAKV_F32) split_kernel<DYNAKV_F32><<<v.U, 256, 0, st>>>(v);
-  else if (v.dtype == DYNAKV_F16) split_kernel<DYNAKV_F16><<<v.U, 256, 0, st>>>(v);
-  else split_kernel<DYNAKV_BF16><<<v.U, 256, 0, st>>>(v);
+  if (v.dtype == DYNAKV_F32) split_kernel<DYNAKV_F32><<<v.U, kSplitThreads, 0, st>>>(v);
+  else if (v.dtype == DYNAKV_F16) split_kernel<DYNAKV_F16><<<v.U, kSplitThreads, 0, st>>>(v);
+  else split_kernel<DYNAKV_BF16><<<v.U, kSplitThreads, 0, st>>>(v);
   return hipGetLastError();
 }
 hipError_t launch_export(const View& v, const dynakv_state_t& dst, hipStream_t st) {

@@ -33,12 +33,10 @@ __global__ __launch_bounds__(256) void score_kernel(View v, const void* Q) {
   __syncthreads();
   if ((j & ~63) >= M) return;                       // whole wavefront past the last cluster
   double acc[GP];
-#pragma unroll
-  for (int g = 0; g < GP; ++g) acc[g] = 0.0;
-  for_each_coord(R, j, row, [&](int d, float rv) {
+  centroid_sums<GP>(R, j, row, acc, [&](int d, float rv, double (&a)[GP]) __attribute__((always_inline)) {
     const double rd = (double)rv;
 #pragma unroll
-    for (int g = 0; g < GP; ++g) acc[g] = fma(qs[d][g], rd, acc[g]);
+    for (int g = 0; g < GP; ++g) a[g] = fma(qs[d][g], rd, a[g]);
   });
   if (j >= M) return;
   double red = acc[0];
@@ -465,9 +463,6 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   const float* R = unit_R(v, u);
 
   // ---- scores (float64, one lane per cluster)
-  f4 row[8];
-  const bool early = (tid & ~63) < v.M0;
-  if (early) load_centroid_head(R, tid, row);
   const int M = v.M[u];
   for (int t = tid; t < GP * kHeadDim; t += NT) {
     const int g = t / kHeadDim, d = t % kHeadDim;
@@ -478,14 +473,13 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   for (int i = M + tid; i < Mpad; i += NT) { skey[i] = 0u; sid[i] = (uint16_t)0xFFFF; }
   __syncthreads();
   for (int j = tid; (j & ~63) < M; j += NT) {
-    if (!(early && j == tid)) load_centroid_head(R, j, row);
+    f4 row[8];
+    load_centroid_head(R, j, row);
     double acc[GP];
-#pragma unroll
-    for (int g = 0; g < GP; ++g) acc[g] = 0.0;
-    for_each_coord(R, j, row, [&](int d, float rv) {
+    centroid_sums<GP>(R, j, row, acc, [&](int d, float rv, double (&a)[GP]) __attribute__((always_inline)) {
       const double rd = (double)rv;
 #pragma unroll
-      for (int g = 0; g < GP; ++g) acc[g] = fma(qs[d][g], rd, acc[g]);
+      for (int g = 0; g < GP; ++g) a[g] = fma(qs[d][g], rd, a[g]);
     });
     if (j < M) {
       double red = acc[0];
@@ -515,12 +509,28 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   st.m = -__builtin_inff(); st.l = 0.f;
 #pragma unroll
   for (int c = 0; c < 8; ++c) st.acc[c] = f4{0, 0, 0, 0};
-  const bool in_lds = nlist <= kFusedList;
-  for (int p = wave; p < nlist; p += NW) {
-    typename F::KV a;
-    const int e = in_lds ? list[p] : plist[p];
-    F::load(a, pages + (size_t)(e >> 5) * kPageBytes, lane, e & 31);
-    consume_page<F>(st, a, q, e & 31, lg, sc);
+  const int* src = nlist <= kFusedList ? list : plist;
+  {                                                   // two pages in flight per wavefront
+    typename F::KV a, b;
+    int ea = 0, eb = 0;
+    if (wave < nlist) {
+      ea = src[wave];
+      F::load(a, pages + (size_t)(ea >> 5) * kPageBytes, lane, ea & 31);
+    }
+    for (int p = wave; p < nlist; p += 2 * NW) {
+      if (p + NW < nlist) {
+        eb = src[p + NW];
+        F::load(b, pages + (size_t)(eb >> 5) * kPageBytes, lane, eb & 31);
+      }
+      consume_page<F>(st, a, q, ea & 31, lg, sc);
+      if (p + NW < nlist) {
+        if (p + 2 * NW < nlist) {
+          ea = src[p + 2 * NW];
+          F::load(a, pages + (size_t)(ea >> 5) * kPageBytes, lane, ea & 31);
+        }
+        consume_page<F>(st, b, q, eb & 31, lg, sc);
+      }
+    }
   }
   float l = st.l;
   l += __shfl_xor(l, 16);
@@ -564,13 +574,13 @@ void launch_ga_dt(const View& v, const void* Q, float* out, float* lse, hipStrea
 }  // namespace
 
 bool retrieve_is_fused(const View& v) {
-  return v.fuse && v.S == 1 && v.dtype != DYNAKV_F32 && v.Mcap <= kFusedClusters &&
-         ((v.NW == 16 && v.G <= 4) || (v.NW == 8 && v.G <= 8));
+  return v.fuse && v.S == 1 && v.dtype != DYNAKV_F32 && v.Mcap <= kFusedClusters && v.G <= 8;
 }
 
 template <int DT>
 static void launch_fused(const View& v, const void* Q, int budget, float* out, float* lse, hipStream_t st) {
-  if (v.NW == 16) retrieve_fused_kernel<DT, 16, 4><<<v.U, 1024, 0, st>>>(v, Q, budget, out, lse);
+  // eight wavefronts: 256 registers per lane leave room for float64 scoring and a second page in flight
+  if (v.G <= 4) retrieve_fused_kernel<DT, 8, 4><<<v.U, 512, 0, st>>>(v, Q, budget, out, lse);
   else retrieve_fused_kernel<DT, 8, 8><<<v.U, 512, 0, st>>>(v, Q, budget, out, lse);
 }
 

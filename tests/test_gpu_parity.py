@@ -71,8 +71,8 @@ def test_cfg5_long_shaped_bf16_group_of_8():
 # --------------------------------------------------------------------------- launch shapes of the retrieval
 
 @pytest.mark.parametrize("name,units,steps,env", [
-    ("llama3_8b", [1, 2], 96, {"DYNAKV_KV_SPLITS": "1"}),                          # one kernel per retrieval, 16 wavefronts
-    ("qwen25_7b", [3], 160, {"DYNAKV_KV_SPLITS": "1"}),                            # one kernel, 8 wavefronts, G = 7
+    ("llama3_8b", [1, 2], 96, {"DYNAKV_KV_SPLITS": "1"}),                          # one kernel per retrieval, G = 4
+    ("qwen25_7b", [3], 160, {"DYNAKV_KV_SPLITS": "1"}),                            # one kernel per retrieval, G = 7
     ("llama3_8b", [4], 64, {"DYNAKV_KV_SPLITS": "1", "DYNAKV_NO_FUSE": "1"}),      # three kernels, no split-KV
     ("long131k", [2], 48, {"DYNAKV_KV_SPLITS": "3", "DYNAKV_ATT_WAVES": "8"}),     # split-KV with prefetching wavefronts
 ])
