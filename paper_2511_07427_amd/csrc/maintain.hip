@@ -174,7 +174,7 @@ struct Keys {
   }
 };
 
-constexpr int kSplitThreads = 512;
+constexpr int kSplitThreads = 256;
 
 // Arg-max over (value, index) pairs held one per thread of the whole block; ties go to the lowest index;
 // index < 0 means "no candidate".  Wavefront shuffles first, then the 16 wavefront winners through LDS.
@@ -309,7 +309,7 @@ __device__ inline void children_stats(const View& v, int u, SplitSmem& s, const 
 
 // Splits cluster j of unit u (2-means; Algorithm 1 SplitCluster).  Whole block; all branches uniform.
 template <int DT, bool STAGED>
-__device__ __noinline__ void split_cluster_impl(const View& v, int u, int j, int m, SplitSmem& s) {
+__device__ __forceinline__ void split_cluster_impl(const View& v, int u, int j, int m, SplitSmem& s) {
   constexpr int NT = kSplitThreads;
   const int tid = threadIdx.x, grp = tid >> 2, kb = tid & 3;
   const int wave_first = (tid & ~63) >> 2;                    // first member this wavefront would take in a pass
@@ -500,7 +500,7 @@ __device__ __noinline__ void split_cluster_impl(const View& v, int u, int j, int
 }
 
 template <int DT>
-__device__ void split_cluster(const View& v, int u, int j, SplitSmem& s) {
+__device__ __forceinline__ void split_cluster(const View& v, int u, int j, SplitSmem& s) {
   const int tid = threadIdx.x;
   const size_t cbase = (size_t)u * v.Mcap;
   const int m = v.cn[cbase + j] + v.cb[cbase + j];
@@ -532,43 +532,49 @@ __global__ __launch_bounds__(kSplitThreads) void split_kernel(View v) {
   const size_t cbase = (size_t)u * v.Mcap;
   const int M0 = v.M[u];
   if (tid == 0) { s.M = M0; s.nflag = v.nflag[u]; s.a_top = v.free_top[u]; s.a_bump = v.bump[u]; }
-  // delayed splits: flagged clusters that the last retrieval selected, ascending id
+  // One loop, one call site: first the delayed splits (flagged clusters that the last retrieval selected, in
+  // ascending id), then, once, the forced split of the fullest buffer if the buffers hold B_max entries.
   int cursor = 0;
+  bool forced_done = false;
   while (true) {
-    if (tid == 0) s_min = 0x7FFFFFFF;
-    __syncthreads();
-    for (int j = cursor + tid; j < M0; j += NT)
-      if (v.cflag[cbase + j] && (v.Bmax == 0 || v.in_req[cbase + j])) { atomicMin(&s_min, j); break; }
-    __syncthreads();
-    const int j = s_min;
-    __syncthreads();
-    if (j == 0x7FFFFFFF) break;
+    int j = -1;
+    if (!forced_done) {
+      if (tid == 0) s_min = 0x7FFFFFFF;
+      __syncthreads();
+      for (int c = cursor + tid; c < M0; c += NT)
+        if (v.cflag[cbase + c] && (v.Bmax == 0 || v.in_req[cbase + c])) { atomicMin(&s_min, c); break; }
+      __syncthreads();
+      j = s_min == 0x7FFFFFFF ? -1 : s_min;
+      __syncthreads();
+      if (j >= 0) cursor = j + 1;
+    }
+    if (j < 0) {
+      if (forced_done) break;
+      forced_done = true;
+      if (!(v.Bmax > 0 && s.nflag > 0)) break;
+      const int M = s.M;
+      if (tid == 0) s_tot = 0;
+      __syncthreads();
+      double bv = -1.0; int bi = -1;
+      long long tot = 0;
+      for (int c = tid; c < M; c += NT)
+        if (v.cflag[cbase + c]) {
+          const int b = v.cb[cbase + c];
+          tot += b;
+          if ((double)b > bv) { bv = (double)b; bi = c; }
+        }
+      if (tot) atomicAdd((unsigned long long*)&s_tot, (unsigned long long)tot);
+      block_argmax(bv, bi, s.sv, s.si);
+      const int arg = s.si[0];
+      const long long total = s_tot;
+      __syncthreads();
+      if (!(arg >= 0 && total >= v.Bmax)) break;
+      if (tid == 0) v.counters[(size_t)u * kCounters + 2] += 1;
+      j = arg;
+    }
     split_cluster<DT>(v, u, j, s);
     __syncthreads();
-    cursor = j + 1;
-  }
-  // forced split once the buffers hold B_max entries: the flagged cluster with the fullest buffer
-  if (v.Bmax > 0 && s.nflag > 0) {
-    const int M = s.M;
-    if (tid == 0) s_tot = 0;
-    __syncthreads();
-    double bv = -1.0; int bi = -1;
-    long long tot = 0;
-    for (int j = tid; j < M; j += NT)
-      if (v.cflag[cbase + j]) {
-        const int b = v.cb[cbase + j];
-        tot += b;
-        if ((double)b > bv) { bv = (double)b; bi = j; }
-      }
-    if (tot) atomicAdd((unsigned long long*)&s_tot, (unsigned long long)tot);
-    block_argmax(bv, bi, s.sv, s.si);
-    const int arg = s.si[0];
-    const long long total = s_tot;
-    __syncthreads();
-    if (arg >= 0 && total >= v.Bmax) {
-      if (tid == 0) v.counters[(size_t)u * kCounters + 2] += 1;
-      split_cluster<DT>(v, u, arg, s);
-    }
+    if (forced_done) break;
   }
   __syncthreads();
   if (tid == 0) { v.M[u] = s.M; v.nflag[u] = s.nflag; v.free_top[u] = s.a_top; v.bump[u] = s.a_bump; }
