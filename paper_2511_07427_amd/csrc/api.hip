@@ -69,7 +69,7 @@ size_t carve(const dynakv_config_t& c, char* base, View* out) {
   View v;
   std::memset(&v, 0, sizeof(v));
   v.U = c.n_units; v.G = c.group_size; v.dtype = c.dtype; v.M0 = c.n_clusters_init; v.Mcap = c.max_clusters;
-  v.Ncap = c.max_tokens; v.Pcap = pages_per_unit(c); v.Bmax = c.buffer_max; v.group_reduce = c.group_reduce;
+  v.Ncap = c.max_tokens; v.Pcap = pages_per_unit(c); v.Lcap = (c.max_tokens + 3) & ~3; v.Bmax = c.buffer_max; v.group_reduce = c.group_reduce;
   plan_attention(c, &v.S, &v.NW);
   v.fuse = std::getenv("DYNAKV_NO_FUSE") ? 0 : 1;       // tuning / test switch
   v.var_alpha = c.var_alpha; v.size_factor = c.size_factor;
@@ -94,7 +94,7 @@ size_t carve(const dynakv_config_t& c, char* base, View* out) {
   v.pg_off = (int*)take(UM * 4);
   v.pages = take(UP * (size_t)kPageElems * elem_size(c.dtype));
   v.ppos = (int*)take(UP * kPageTokens * 4); v.pnext = (int*)take(UP * 4); v.freelist = (int*)take(UP * 4);
-  v.plist = (int*)take(UP * 4); v.plist_off = (int*)take(UP * 4);
+  v.plist = (int*)take(U * v.Lcap * 4); v.plist_off = (int*)take(U * v.Lcap * 4);
   v.part = (float*)take(U * v.S * v.G * (kHeadDim + 2) * 4);
   v.labels = (int*)take(UN * 4); v.order = (int*)take(UN * 4); v.dist = (double*)take(UN * 8);
   v.koff = (int*)take(U * (v.Mcap + 1) * 4);

@@ -24,7 +24,7 @@ typedef float f4 __attribute__((ext_vector_type(4)));
 // Device-side view of one index.  All arrays live in the caller's workspace.
 struct View {
   // configuration
-  int U, G, dtype, M0, Mcap, Ncap, Pcap, Bmax, group_reduce, S, NW, fuse;
+  int U, G, dtype, M0, Mcap, Ncap, Pcap, Lcap, Bmax, group_reduce, S, NW, fuse;
   size_t Rstride;    // floats of centroid table per unit
   float var_alpha, size_factor, scale_f;
   double scale_d;
@@ -36,7 +36,7 @@ struct View {
   int* nflag;        // [U] clusters currently flagged
   int* n_sel;        // [U] clusters selected by the last retrieval
   int* t_sel;        // [U] entries gathered by the last retrieval
-  int* n_list;       // [U] pages in the gather list
+  int* n_list;       // [U] entries in the gather list
   int* ticket;       // [U] arrival counter of the split-KV workgroups
   int* bump;         // [U] pages handed out from the pool so far
   int* free_top;     // [U] entries on the free-page stack
@@ -54,14 +54,15 @@ struct View {
   int* sel_ids;      // ids in score order
   unsigned char* in_req;  // membership in the last active set
   int* tok_off;      // scratch: exclusive prefix of sizes in score order
-  int* pg_off;       // scratch: exclusive prefix of page counts in score order
+  int* pg_off;       // scratch: exclusive prefix of gather-list entry counts in score order
   // pages [U][Pcap]
   char* pages;       // [U][Pcap][kPageElems * elem size]
   int* ppos;         // [U][Pcap][16] token position of every slot
   int* pnext;        // [U][Pcap] next page of the same cluster (-1: last)
   int* freelist;     // [U][Pcap] stack of recycled pages
-  int* plist;        // [U][Pcap] gather list: page * 32 + valid tokens
-  int* plist_off;    // [U][Pcap] gather offset of the page's first token
+  // gather list [U][Lcap]: one entry per aligned group of four token slots of a page
+  int* plist;        // page * 16 + group * 4 + (valid tokens - 1)
+  int* plist_off;    // gather offset of the entry's first token
   // split-KV partial results
   float* part;       // [U][S][G][130]: 128 accumulators, running max (log2 domain), denominator
   // k-means / split scratch [U][Ncap]
@@ -162,37 +163,50 @@ __device__ inline void load_centroid_head(const float* R, int j, f4 (&first)[8])
 #pragma unroll
   for (int i = 0; i < 8; ++i) first[i] = r[i * 64];
 }
+// Coordinates 32b .. 32b+31 (held in cur) of the sums: four blocks of 8.
+template <int NACC, bool LEAN, class F>
+__device__ __forceinline__ void centroid_batch(int b, const f4 (&cur)[8], double (&out)[NACC], F&& term) {
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    double acc[NACC];
+#pragma unroll
+    for (int a = 0; a < NACC; ++a) acc[a] = 0.0;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) term(b * 32 + k * 8 + i * 4 + e, cur[k * 2 + i][e], acc);
+      if (LEAN) asm volatile("" ::: "memory");   // lean variant: operand loads stay four coordinates deep
+    }
+#pragma unroll
+    for (int a = 0; a < NACC; ++a) out[a] += acc[a];
+    __builtin_amdgcn_sched_barrier(0);   // keeps the operand loads of later blocks from piling up in registers
+  }
+}
 template <int NACC, bool PREFETCH = true, class F>
 __device__ __forceinline__ void centroid_sums(const float* R, int j, f4 (&cur)[8], double (&out)[NACC], F&& term) {
   const f4* r = (const f4*)(R + r_index(j, 0));
-  f4 nxt[PREFETCH ? 8 : 1];
 #pragma unroll
   for (int a = 0; a < NACC; ++a) out[a] = 0.0;
 #pragma unroll 1
-  for (int b = 0; b < 4; ++b) {
-    if (PREFETCH && b < 3) {
+  for (int b = 0; b < 3; ++b) {
+    if constexpr (PREFETCH) {
+      f4 nxt[8];
 #pragma unroll
       for (int i = 0; i < 8; ++i) nxt[i] = r[((b + 1) * 8 + i) * 64];
-    }
+      centroid_batch<NACC, false>(b, cur, out, term);
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {             // four blocks of 8 coordinates
-      double acc[NACC];
+      for (int i = 0; i < 8; ++i) cur[i] = nxt[i];
+    } else {
+      centroid_batch<NACC, true>(b, cur, out, term);
 #pragma unroll
-      for (int a = 0; a < NACC; ++a) acc[a] = 0.0;
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) term(b * 32 + k * 8 + i * 4 + e, cur[k * 2 + i][e], acc);
-        if (!PREFETCH) asm volatile("" ::: "memory");   // lean variant: operand loads stay four coordinates deep
-      }
-#pragma unroll
-      for (int a = 0; a < NACC; ++a) out[a] += acc[a];
-    }
-    if (b < 3) {
-#pragma unroll
-      for (int i = 0; i < 8; ++i) cur[i] = PREFETCH ? nxt[i] : r[((b + 1) * 8 + i) * 64];
+      for (int i = 0; i < 8; ++i) cur[i] = r[((b + 1) * 8 + i) * 64];
     }
   }
+  centroid_batch<NACC, !PREFETCH>(3, cur, out, term);
+  // the sums are complete here: without this, the compiler moves the last batch's arithmetic (not its operand
+  // loads) into whatever conditional block first uses the result, and the loaded operands pile up in registers
+#pragma unroll
+  for (int a = 0; a < NACC; ++a) asm volatile("" : "+v"(out[a]));
 }
 
 // ---- element access -----------------------------------------------------------------------------

@@ -647,9 +647,10 @@ __global__ __launch_bounds__(1024) void export_kernel(View v, dynakv_state_t o) 
   if (o.gathered) {
     const int nl = v.n_list[u];
     for (int w = tid; w < nl; w += 1024) {
-      const int e = v.plist[(size_t)u * v.Pcap + w], page = e >> 5, nv = e & 31, t0 = v.plist_off[(size_t)u * v.Pcap + w];
+      const int e = v.plist[(size_t)u * v.Lcap + w], t0 = v.plist_off[(size_t)u * v.Lcap + w];
+      const int page = e >> 4, first = ((e >> 2) & 3) * 4, nv = (e & 3) + 1;
       for (int sl = 0; sl < nv; ++sl)
-        o.gathered[(size_t)u * v.Ncap + t0 + sl] = v.ppos[((size_t)u * v.Pcap + page) * kPageTokens + sl];
+        o.gathered[(size_t)u * v.Ncap + t0 + sl] = v.ppos[((size_t)u * v.Pcap + page) * kPageTokens + first + sl];
     }
   }
 }

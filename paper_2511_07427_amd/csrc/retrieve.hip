@@ -52,22 +52,59 @@ __device__ inline uint32_t orderable(float f) {
   return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
 
-// Selection for one unit, run by a whole workgroup of NT threads.  On entry skey/sid hold the orderable
-// scores and ids of the unit's M clusters, padded with (0, 0xFFFF) up to the next power of two.  Sorts them
-// by (score desc, id asc), takes the longest prefix whose stored sizes fit the budget, records the active set
-// and writes the gather list (page * 32 + valid tokens, in gather order) to the workspace and, as far as it
-// fits, to `lds_list`.  Returns the number of gather-list entries.
+constexpr int kCountMax = 1024;     // selected clusters ordered by counting; larger selections take the full sort
+constexpr int kSelRegion = kCountMax * 12;   // bytes of candidate keys (8) and sizes (4)
+
+// LDS of the selection.  `region` holds the candidates of the fast path (or the ids of the full sort) and
+// needs max(kSelRegion, 2 * Mpad) bytes; `list` receives the first `list_cap` gather-list entries.
+struct SelectLds {
+  uint32_t* skey;          // [Mpad] orderable scores, padded with 0 up to the next power of two
+  const int* sw;           // [M] stored sizes, or null: they are read from the workspace
+  unsigned char* region;
+  int* hist;               // [4][256]
+  int* sm;                 // [64]
+  int* misc;               // [8]
+  int* list;
+  int list_cap;
+};
+
+// Gather-list entry: one aligned group of four token slots ("quad") of a page,
+// page * 16 + quad * 4 + (valid tokens - 1); `t0` is the gather offset of its first token.
+__device__ inline int emit_cluster(const View& v, int u, size_t cj, int take, int w, int t0, int* plist, int* poff,
+                                   int* lds_list, int lds_cap) {
+  int left = take, page = -1;
+  for (int k = 0; left > 0; ++k) {
+    page = cluster_page(v, u, cj, k, page);
+    if (page < 0) break;
+    const int nv = min(left, kPageTokens);
+    for (int qd = 0; 4 * qd < nv; ++qd) {
+      const int e = page * 16 + qd * 4 + (min(4, nv - 4 * qd) - 1);
+      plist[w] = e;
+      if (w < lds_cap) lds_list[w] = e;
+      poff[w] = t0 + 4 * qd;
+      ++w;
+    }
+    t0 += nv; left -= nv;
+  }
+  return w;
+}
+
+// Full sort (any selection size): bitonic sort of all clusters by (score desc, id asc), prefix sums over the
+// sorted sizes, cut at the budget.  Same results as select_phase below.
 template <int NT>
-__device__ inline int select_phase(const View& v, int u, int M, int budget, uint32_t* skey, uint16_t* sid, int* sm,
-                                   int* s_cut, int* s_tsel, int* lds_list, int lds_cap) {
+__device__ inline int select_sorted(const View& v, int u, int M, int budget, const SelectLds& s) {
   constexpr int KCH = kMaxClusters / NT;      // consecutive ranks per thread in the prefix sums
   const int tid = threadIdx.x;
   const size_t cb = (size_t)u * v.Mcap;
+  uint32_t* skey = s.skey;
+  uint16_t* sid = (uint16_t*)s.region;
+  int* s_cut = s.misc, *s_tsel = s.misc + 1;
   int Mpad = 2;
   while (Mpad < M) Mpad <<= 1;
+  for (int i = tid; i < Mpad; i += NT) sid[i] = i < M ? (uint16_t)i : (uint16_t)0xFFFF;
   if (tid == 0) { *s_cut = 0; *s_tsel = 0; }
   __syncthreads();
-  // bitonic sort: a goes before b if its score is larger, or equal with the smaller id
+  // a goes before b if its score is larger, or equal with the smaller id
   for (int k = 2; k <= Mpad; k <<= 1)
     for (int j = k >> 1; j > 0; j >>= 1) {
       for (int i = tid; i < Mpad; i += NT) {
@@ -91,7 +128,7 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, uint
     tot += sz[k];
   }
   int total;
-  int run = block_excl_scan(tot, sm, total);
+  int run = block_excl_scan(tot, s.sm, total);
   int cnt = 0, fit = 0;
 #pragma unroll
   for (int k = 0; k < KCH; ++k) {
@@ -107,42 +144,31 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, uint
   int cut = *s_cut, tsel = *s_tsel;
   const bool truncated = cut == 0 && M > 0 && budget > 0;     // best cluster alone is over budget
   if (truncated) { cut = 1; tsel = budget; }
-  // page prefix over the selected ranks
+  // quad prefix over the selected ranks
   tot = 0;
 #pragma unroll
   for (int k = 0; k < KCH; ++k) {
     const int p = tid * KCH + k;
-    const int s = truncated ? budget : sz[k];
-    sz[k] = p < cut ? (s + kPageTokens - 1) / kPageTokens : 0;
+    const int t = truncated ? budget : sz[k];
+    sz[k] = p < cut ? (t + 3) / 4 : 0;
     tot += sz[k];
   }
-  run = block_excl_scan(tot, sm, total);
+  run = block_excl_scan(tot, s.sm, total);
 #pragma unroll
   for (int k = 0; k < KCH; ++k) {
     const int p = tid * KCH + k;
     if (p < M) { v.pg_off[cb + p] = run; run += sz[k]; }
   }
   __syncthreads();
-  // active set, id list and gather list
-  int* plist = v.plist + (size_t)u * v.Pcap;
-  int* poff = v.plist_off + (size_t)u * v.Pcap;
+  int* plist = v.plist + (size_t)u * v.Lcap;
+  int* poff = v.plist_off + (size_t)u * v.Lcap;
   for (int p = tid; p < M; p += NT) {
     const int id = sid[p];
     v.sel_ids[cb + p] = id;
     v.in_req[cb + id] = p < cut;
-    if (p < cut) {
-      int left = truncated ? budget : v.cn[cb + id] + v.cb[cb + id];
-      int page = -1, w = v.pg_off[cb + p], t0 = v.tok_off[cb + p];
-      for (int k = 0; left > 0; ++k) {
-        page = cluster_page(v, u, cb + id, k, page);
-        if (page < 0) break;
-        const int nv = min(left, kPageTokens);
-        plist[w] = page * 32 + nv;
-        if (w < lds_cap) lds_list[w] = page * 32 + nv;
-        poff[w] = t0;
-        ++w; t0 += nv; left -= nv;
-      }
-    }
+    if (p < cut)
+      emit_cluster(v, u, cb + id, truncated ? budget : v.cn[cb + id] + v.cb[cb + id], v.pg_off[cb + p],
+                   v.tok_off[cb + p], plist, poff, s.list, s.list_cap);
   }
   if (tid == 0) {
     v.n_sel[u] = cut; v.t_sel[u] = tsel; v.n_list[u] = total; v.ticket[u] = 0;
@@ -153,21 +179,185 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, uint
   return total;
 }
 
+// Selection for one unit, run by a whole workgroup of NT threads (NT >= 256).  Clusters are ordered by
+// (score desc, id asc); the active set is the longest prefix of that order whose stored sizes fit the budget
+// (or the best cluster alone, cut to the budget, if even that one does not fit).  Records the active set and
+// writes the gather list in that order.  Returns the number of gather-list entries.
+//
+// Only the selected clusters are ordered.  The score at which the running size first exceeds the budget is
+// found by a radix search over the 32-bit orderable scores (four passes of size-weighted 256-bin histograms);
+// everything above it is selected, equal scores are taken by ascending id while they fit.  Each selected
+// cluster then finds its rank and its gather offsets by counting the selected clusters that precede it.
+template <int NT>
+__device__ inline int select_phase(const View& v, int u, int M, int budget, const SelectLds& s) {
+  const int tid = threadIdx.x, lane = tid & 63;
+  const size_t cb = (size_t)u * v.Mcap;
+  unsigned long long* ck = (unsigned long long*)s.region;       // (score << 16) | (0xFFFF - id): larger goes first
+  int* cw = (int*)(s.region + kCountMax * 8);
+#define DYNAKV_WEIGHT(j) (s.sw ? s.sw[j] : v.cn[cb + (j)] + v.cb[cb + (j)])
+  for (int i = tid; i < 1024; i += NT) s.hist[i] = 0;
+  if (tid < 8) s.misc[tid] = tid == 4 ? 0x7fffffff : 0;
+  __syncthreads();
+
+  uint32_t kstar = 0, mask = 0;
+  int above = 0, total = 0;
+  bool cross = true;
+  for (int pass = 0; pass < 4; ++pass) {
+    const int shift = 24 - 8 * pass;
+    int* h = s.hist + 256 * pass;
+    for (int j = tid; j < M; j += NT) {
+      const uint32_t k = s.skey[j];
+      if ((k & mask) == kstar) {
+        const int w = DYNAKV_WEIGHT(j);
+        if (w) atomicAdd(&h[(k >> shift) & 255], w);
+      }
+    }
+    __syncthreads();
+    // every wavefront: lane l owns the digits 255 - 4l .. 252 - 4l, highest first
+    int hv[4], t = 0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) { hv[k] = h[255 - (4 * lane + k)]; t += hv[k]; }
+    int inc = t;
+    for (int o = 1; o < 64; o <<= 1) {
+      const int y = __shfl_up(inc, o);
+      if (lane >= o) inc += y;
+    }
+    int run = above + inc - t, dstar = -1, ab = 0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      if (dstar < 0 && run + hv[k] > budget) { dstar = 255 - (4 * lane + k); ab = run; }
+      run += hv[k];
+    }
+    const unsigned long long bal = __ballot(dstar >= 0);
+    if (bal == 0) {                      // everything fits (first pass only)
+      cross = false;
+      total = __shfl(run, 63);
+      break;
+    }
+    const int src = __ffsll((long long)bal) - 1;
+    kstar |= (uint32_t)__shfl(dstar, src) << shift;
+    mask |= 255u << shift;
+    above = __shfl(ab, src);
+  }
+
+  // candidates: every score above kstar; the clusters at kstar are counted and resolved below
+  for (int j = tid; j < M; j += NT) {
+    const uint32_t k = s.skey[j];
+    if (cross && k == kstar) {
+      atomicAdd(&s.misc[3], 1);
+      atomicMin(&s.misc[4], j);
+    } else {
+      const bool sel = !cross || k > kstar;
+      v.in_req[cb + j] = sel;
+      if (sel) {
+        const int pos = atomicAdd(&s.misc[2], 1);
+        if (pos < kCountMax) { ck[pos] = ((unsigned long long)k << 16) | (unsigned)(0xFFFF - j); cw[pos] = DYNAKV_WEIGHT(j); }
+      }
+    }
+  }
+  __syncthreads();
+  int xid = s.misc[4], tie_w = 0;        // xid: the cluster at which the budget is first exceeded
+  if (cross && s.misc[3] > 1) {          // several equal scores at the cut: by ascending id while they fit
+    if (tid < 64) {
+      int cum = above, x = -1;
+      for (int base = 0; base < M && x < 0; base += 64) {
+        const int j = base + lane;
+        const bool tie = j < M && s.skey[j] == kstar;
+        const int w = tie ? DYNAKV_WEIGHT(j) : 0;
+        int inc = w;
+        for (int o = 1; o < 64; o <<= 1) {
+          const int y = __shfl_up(inc, o);
+          if (lane >= o) inc += y;
+        }
+        const unsigned long long ob = __ballot(tie && cum + inc > budget);
+        if (ob) {
+          const int xl = __ffsll((long long)ob) - 1;
+          x = base + xl;
+          cum += __shfl(inc - w, xl);
+        } else {
+          cum += __shfl(inc, 63);
+        }
+      }
+      if (lane == 0) { s.misc[4] = x < 0 ? M : x; s.misc[5] = cum - above; }
+    }
+    __syncthreads();
+    xid = s.misc[4]; tie_w = s.misc[5];
+    for (int j = tid; j < M; j += NT)
+      if (s.skey[j] == kstar) {
+        const bool sel = j < xid;
+        v.in_req[cb + j] = sel;
+        if (sel) {
+          const int pos = atomicAdd(&s.misc[2], 1);
+          if (pos < kCountMax) { ck[pos] = ((unsigned long long)kstar << 16) | (unsigned)(0xFFFF - j); cw[pos] = DYNAKV_WEIGHT(j); }
+        }
+      }
+    __syncthreads();
+  } else if (cross && tid == 0) {
+    v.in_req[cb + xid] = 0;
+  }
+  int cut = s.misc[2], tsel = cross ? above + tie_w : total;
+  if (cut > kCountMax) {
+    __syncthreads();
+    return select_sorted<NT>(v, u, M, budget, s);
+  }
+  if (cross && cut == 0 && budget > 0) {           // the best cluster alone is over budget: its first entries
+    if (tid == 0) {
+      ck[0] = ((unsigned long long)kstar << 16) | (unsigned)(0xFFFF - xid);
+      cw[0] = budget;
+      v.in_req[cb + xid] = 1;
+    }
+    __syncthreads();
+    cut = 1; tsel = budget;
+  }
+
+  // rank and gather offsets of every selected cluster, then its list entries
+  int* plist = v.plist + (size_t)u * v.Lcap;
+  int* poff = v.plist_off + (size_t)u * v.Lcap;
+  int quads = 0;
+  for (int p = tid; p < cut; p += NT) {
+    const unsigned long long my = ck[p];
+    const int myw = cw[p];
+    int rank = 0, t0 = 0, q0 = 0;
+#pragma unroll 4
+    for (int q = 0; q < cut; ++q) {
+      const unsigned long long o = ck[q];
+      const int w = cw[q];
+      if (o > my) { ++rank; t0 += w; q0 += (w + 3) >> 2; }
+    }
+    const int id = 0xFFFF - (int)(my & 0xFFFF);
+    v.sel_ids[cb + rank] = id;
+    emit_cluster(v, u, cb + id, myw, q0, t0, plist, poff, s.list, s.list_cap);
+    quads += (myw + 3) >> 2;
+  }
+  if (quads) atomicAdd(&s.misc[6], quads);
+  __syncthreads();
+  const int nlist = s.misc[6];
+  if (tid == 0) {
+    v.n_sel[u] = cut; v.t_sel[u] = tsel; v.n_list[u] = nlist; v.ticket[u] = 0;
+    v.counters[(size_t)u * kCounters + 4] += tsel;
+    v.counters[(size_t)u * kCounters + 5] += 1;
+    v.counters[(size_t)u * kCounters + 6] += M;
+  }
+#undef DYNAKV_WEIGHT
+  return nlist;
+}
+
 // One workgroup per unit.
 __global__ __launch_bounds__(1024) void select_kernel(View v, int budget) {
   __shared__ uint32_t skey[kMaxClusters];
-  __shared__ uint16_t sid[kMaxClusters];
+  __shared__ __align__(16) unsigned char region[2 * kMaxClusters];
+  __shared__ int hist[1024];
   __shared__ int sm[64];
-  __shared__ int s_cut, s_tsel;
+  __shared__ int misc[8];
+  static_assert(2 * kMaxClusters >= kSelRegion, "candidate arrays must fit the id array");
   const int u = blockIdx.x, tid = threadIdx.x;
   const int M = v.M[u];
   int Mpad = 2;
   while (Mpad < M) Mpad <<= 1;
-  for (int i = tid; i < Mpad; i += 1024) {
-    skey[i] = i < M ? orderable(v.score[(size_t)u * v.Mcap + i]) : 0u;
-    sid[i] = i < M ? (uint16_t)i : (uint16_t)0xFFFF;
-  }
-  select_phase<1024>(v, u, M, budget, skey, sid, sm, &s_cut, &s_tsel, nullptr, 0);
+  for (int i = tid; i < Mpad; i += 1024) skey[i] = i < M ? orderable(v.score[(size_t)u * v.Mcap + i]) : 0u;
+  __syncthreads();
+  const SelectLds s{skey, nullptr, region, hist, sm, misc, nullptr, 0};
+  select_phase<1024>(v, u, M, budget, s);
 }
 
 // ------------------------------------------------------------------------------------------- attention
@@ -178,7 +368,30 @@ typedef short s4 __attribute__((ext_vector_type(4)));
 
 constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
 
-// Fragments of one page and of the query group, per storage type.  qk() returns S^T[token 4*(lane/16)+i]
+// One tile of the attention loop: 16 token slots filled from up to four gather-list entries (quads), which may
+// come from four different pages.  Lane l multiplies token slot l % 16 in QK^T (entry slot / 4, row slot % 4 of
+// that quad) and the four tokens of entry l / 16 in PV, so every lane has its own two page addresses.
+struct Tile {
+  const char* k;     // this lane's first 16 bytes of the K region (further k-steps 1 KB apart)
+  const char* v;     // this lane's first 16 bytes of the V region
+  bool kok;          // the lane's token slot holds a token
+  int nvq;           // valid tokens in the lane's PV quad (0: no entry)
+};
+// eK, eV: list entries of the lane's QK slot and of its PV quad (-1: none); ES = bytes per element.
+template <int ES>
+__device__ inline Tile make_tile(const char* pages, int eK, int eV, int lane) {
+  constexpr size_t kPageBytes = (size_t)kPageElems * ES;
+  Tile t;
+  t.kok = eK >= 0 && (lane & 3) <= (eK & 3);
+  if (eK < 0) eK = 0;
+  t.k = pages + (size_t)(eK >> 4) * kPageBytes + ((lane & 48) + ((eK >> 2) & 3) * 4 + (lane & 3)) * 16;
+  t.nvq = eV >= 0 ? (eV & 3) + 1 : 0;
+  if (eV < 0) eV = 0;
+  t.v = pages + (size_t)(eV >> 4) * kPageBytes + 2048 * ES + (((eV >> 2) & 3) * 16 + (lane & 15)) * 16;
+  return t;
+}
+
+// Fragments of one tile and of the query group, per storage type.  qk() returns S^T[token 4*(lane/16)+i]
 // [head lane%16]; pv() adds P^T-weighted V^T into acc[cb][i] = O^T[column 16*cb + 4*(lane/16) + i][head lane%16].
 template <int DT>
 struct Frag;
@@ -192,14 +405,13 @@ struct Frag<DYNAKV_F32> {
 #pragma unroll
     for (int s = 0; s < 8; ++s) q.b[s] = ok ? *(const f4*)(p + 16 * s) : f4{0, 0, 0, 0};
   }
-  static __device__ void load(KV& f, const char* page, int lane, int nvalid) {
-    const f4* kp = (const f4*)page + lane;
-    const f4* vp = (const f4*)(page + 2048 * 4) + lane;
-    const bool kok = (lane & 15) < nvalid, vok = 4 * (lane >> 4) < nvalid;
+  static __device__ void load(KV& f, const Tile& t) {
+    const f4* kp = (const f4*)t.k;
+    const f4* vp = (const f4*)t.v;
 #pragma unroll
-    for (int s = 0; s < 8; ++s) f.k[s] = kok ? kp[s * 64] : f4{0, 0, 0, 0};
+    for (int s = 0; s < 8; ++s) f.k[s] = t.kok ? kp[s * 64] : f4{0, 0, 0, 0};
 #pragma unroll
-    for (int c = 0; c < 8; ++c) f.v[c] = vok ? vp[c * 64] : f4{0, 0, 0, 0};
+    for (int c = 0; c < 8; ++c) f.v[c] = t.nvq ? vp[c * 64] : f4{0, 0, 0, 0};
   }
   static __device__ f4 qk(const KV& f, const Qf& q) {
     f4 a = {0, 0, 0, 0};
@@ -226,14 +438,13 @@ struct Frag16 {
 #pragma unroll
     for (int s = 0; s < 4; ++s) q.b[s] = ok ? *(const uint4*)(p + 32 * s) : uint4{0, 0, 0, 0};
   }
-  static __device__ void load(KV& f, const char* page, int lane, int nvalid) {
-    const uint4* kp = (const uint4*)page + lane;
-    const uint4* vp = (const uint4*)(page + 2048 * 2) + lane;
-    const bool kok = (lane & 15) < nvalid, vok = 4 * (lane >> 4) < nvalid;
+  static __device__ void load(KV& f, const Tile& t) {
+    const uint4* kp = (const uint4*)t.k;
+    const uint4* vp = (const uint4*)t.v;
 #pragma unroll
-    for (int s = 0; s < 4; ++s) f.k[s] = kok ? kp[s * 64] : uint4{0, 0, 0, 0};
+    for (int s = 0; s < 4; ++s) f.k[s] = t.kok ? kp[s * 64] : uint4{0, 0, 0, 0};
 #pragma unroll
-    for (int c = 0; c < 4; ++c) f.v[c] = vok ? vp[c * 64] : uint4{0, 0, 0, 0};
+    for (int c = 0; c < 4; ++c) f.v[c] = t.nvq ? vp[c * 64] : uint4{0, 0, 0, 0};
   }
   static __device__ f4 qk(const KV& f, const Qf& q) {
     f4 a = {0, 0, 0, 0};
@@ -305,20 +516,19 @@ struct Softmax {
   f4 acc[8];
 };
 
-// One page: S^T = K Q^T on the matrix cores, running max / rescale, O^T += V^T P^T.
+// One tile: S^T = K Q^T on the matrix cores, running max / rescale, O^T += V^T P^T.
 template <class F>
-__device__ inline void consume_page(Softmax& st, const typename F::KV& kv, const typename F::Qf& q, int nvalid, int lg,
-                                    float sc) {
+__device__ inline void consume_page(Softmax& st, const typename F::KV& kv, const typename F::Qf& q, int nvq, float sc) {
   const f4 sacc = F::qk(kv, q);
   float s2[4], mx = -__builtin_inff();
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    s2[i] = (4 * lg + i) < nvalid ? sacc[i] * sc : -__builtin_inff();
+    s2[i] = i < nvq ? sacc[i] * sc : -__builtin_inff();
     mx = fmaxf(mx, s2[i]);
   }
   mx = fmaxf(mx, __shfl_xor(mx, 16));
   mx = fmaxf(mx, __shfl_xor(mx, 32));
-  const float mn = fmaxf(st.m, mx);          // finite: every listed page has a valid token
+  const float mn = fmaxf(st.m, mx);          // finite: every tile has a valid token
   const float alpha = __builtin_amdgcn_exp2f(st.m - mn);
   float pr[4], ps = 0.f;
 #pragma unroll
@@ -330,14 +540,14 @@ __device__ inline void consume_page(Softmax& st, const typename F::KV& kv, const
   F::pv(st.acc, kv, pr);
 }
 
-// grid (S, U); NW wavefronts per workgroup; the unit's gather list is dealt page by page to the S * NW
-// wavefronts.  Each wavefront first fetches its own list entries with one gathered load (lane i holds the
-// entry of its i-th page), so page addresses never wait on a dependent load inside the loop; with PF the
-// next page's loads are issued before the current page is consumed.
+// grid (S, U); NW wavefronts per workgroup; the unit's gather list is dealt tile by tile (four entries) to the
+// S * NW wavefronts.  Each wavefront first fetches the entries of its next 16 tiles with one gathered load
+// (lane l holds entry l % 4 of tile l / 4), so page addresses never wait on a dependent load inside the loop;
+// with PF the next tile's loads are issued before the current tile is consumed.
 template <int DT, int NW, bool PF>
 __global__ __launch_bounds__(NW * 64) void gather_attend_kernel(View v, const void* Q, float* out, float* lse) {
   using F = Frag<DT>;
-  constexpr int kPageBytes = kPageElems * (DT == DYNAKV_F32 ? 4 : 2);
+  constexpr int ES = DT == DYNAKV_F32 ? 4 : 2;
   extern __shared__ float sm_o[];            // [NW][G][130]: accumulators, max, denominator per wave and head
   __shared__ int s_last;
   const int u = blockIdx.y, s = blockIdx.x, S = gridDim.x;
@@ -346,9 +556,9 @@ __global__ __launch_bounds__(NW * 64) void gather_attend_kernel(View v, const vo
 
   typename F::Qf q;
   F::load_q(q, Q, (size_t)u * G + (g < G ? g : 0), lg, g < G);
-  const int nlist = v.n_list[u];
-  const int* plist = v.plist + (size_t)u * v.Pcap;
-  const char* pages = v.pages + (size_t)u * v.Pcap * kPageBytes;
+  const int nlist = v.n_list[u], ntile = (nlist + 3) >> 2;
+  const int* plist = v.plist + (size_t)u * v.Lcap;
+  const char* pages = v.pages + (size_t)u * v.Pcap * kPageElems * ES;
   const float sc = v.scale_f * kLog2e;
 
   Softmax st;
@@ -357,34 +567,36 @@ __global__ __launch_bounds__(NW * 64) void gather_attend_kernel(View v, const vo
   for (int c = 0; c < 8; ++c) st.acc[c] = f4{0, 0, 0, 0};
 
   const int stride = S * NW, p0 = s * NW + wave;
-  const int mine = p0 < nlist ? (nlist - p0 + stride - 1) / stride : 0;   // pages of this wavefront
-  for (int c0 = 0; c0 < mine; c0 += 64) {
-    const int cn = min(64, mine - c0);
-    const int e_l = lane < cn ? plist[p0 + (size_t)(c0 + lane) * stride] : 0;
+  const int mine = p0 < ntile ? (ntile - p0 + stride - 1) / stride : 0;   // tiles of this wavefront
+  const int selK = (lane & 15) >> 2;
+  for (int c0 = 0; c0 < mine; c0 += 16) {
+    const int cn = min(16, mine - c0);
+    const int my_e = 4 * (p0 + (c0 + (lane >> 2)) * stride) + (lane & 3);
+    const int e_l = (lane >> 2) < cn && my_e < nlist ? plist[my_e] : -1;
     if constexpr (PF) {
       typename F::KV a, b;
-      int ea = __builtin_amdgcn_readlane(e_l, 0), eb = 0;
-      F::load(a, pages + (size_t)(ea >> 5) * kPageBytes, lane, ea & 31);
+      Tile ta = make_tile<ES>(pages, __shfl(e_l, selK), __shfl(e_l, lg), lane), tb = ta;
+      F::load(a, ta);
       for (int i = 0; i < cn; i += 2) {
         if (i + 1 < cn) {
-          eb = __builtin_amdgcn_readlane(e_l, i + 1);
-          F::load(b, pages + (size_t)(eb >> 5) * kPageBytes, lane, eb & 31);
+          tb = make_tile<ES>(pages, __shfl(e_l, 4 * (i + 1) + selK), __shfl(e_l, 4 * (i + 1) + lg), lane);
+          F::load(b, tb);
         }
-        consume_page<F>(st, a, q, ea & 31, lg, sc);
+        consume_page<F>(st, a, q, ta.nvq, sc);
         if (i + 1 < cn) {
           if (i + 2 < cn) {
-            ea = __builtin_amdgcn_readlane(e_l, i + 2);
-            F::load(a, pages + (size_t)(ea >> 5) * kPageBytes, lane, ea & 31);
+            ta = make_tile<ES>(pages, __shfl(e_l, 4 * (i + 2) + selK), __shfl(e_l, 4 * (i + 2) + lg), lane);
+            F::load(a, ta);
           }
-          consume_page<F>(st, b, q, eb & 31, lg, sc);
+          consume_page<F>(st, b, q, tb.nvq, sc);
         }
       }
     } else {
       for (int i = 0; i < cn; ++i) {
         typename F::KV a;
-        const int e = __builtin_amdgcn_readlane(e_l, i);
-        F::load(a, pages + (size_t)(e >> 5) * kPageBytes, lane, e & 31);
-        consume_page<F>(st, a, q, e & 31, lg, sc);
+        const Tile ta = make_tile<ES>(pages, __shfl(e_l, 4 * i + selK), __shfl(e_l, 4 * i + lg), lane);
+        F::load(a, ta);
+        consume_page<F>(st, a, q, ta.nvq, sc);
       }
     }
   }
@@ -447,15 +659,20 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
                                                                 float* lse) {
   using F = Frag<DT>;
   constexpr int NT = NW * 64;
-  constexpr int kPageBytes = kPageElems * (DT == DYNAKV_F32 ? 4 : 2);
+  constexpr int ES = DT == DYNAKV_F32 ? 4 : 2;
   constexpr int kMergeBytes = 64 * (kHeadDim + 2) * 4;          // NW * G <= 64 head rows
-  __shared__ __align__(16) unsigned char smem[kMergeBytes];     // sort arrays + list, later the merge buffer
+  constexpr int kKeys = kFusedClusters * 4, kSizes = kFusedClusters * 4, kList = kFusedList * 4;
+  static_assert(kSelRegion >= 2 * kFusedClusters && kKeys + kSizes + kSelRegion + kList >= kMergeBytes, "LDS plan");
+  // scores, sizes, candidates, gather list; after the page loop the front doubles as the merge buffer
+  __shared__ __align__(16) unsigned char smem[kKeys + kSizes + kSelRegion + kList];
   __shared__ double qs[kHeadDim][GP];
   __shared__ int sm[64];
-  __shared__ int s_cut, s_tsel;
-  uint32_t* skey = (uint32_t*)smem;                                   // [4096]
-  uint16_t* sid = (uint16_t*)(smem + kFusedClusters * 4);             // [4096]
-  int* list = (int*)(smem + kFusedClusters * 6);                      // [2048]
+  __shared__ int misc[8];
+  uint32_t* skey = (uint32_t*)smem;
+  int* ssz = (int*)(smem + kKeys);
+  int* list = (int*)(smem + kKeys + kSizes + kSelRegion);
+  int* hist = list;                                   // the histograms are dead before the list is written
+  static_assert(kList >= 1024 * 4, "histograms must fit the list");
   float* sm_o = (float*)smem;
   const int u = blockIdx.x, tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
@@ -470,7 +687,8 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   }
   int Mpad = 2;
   while (Mpad < M) Mpad <<= 1;
-  for (int i = M + tid; i < Mpad; i += NT) { skey[i] = 0u; sid[i] = (uint16_t)0xFFFF; }
+  for (int i = M + tid; i < Mpad; i += NT) skey[i] = 0u;
+  for (int j = tid; j < M; j += NT) ssz[j] = v.cn[(size_t)u * v.Mcap + j] + v.cb[(size_t)u * v.Mcap + j];
   __syncthreads();
   for (int j = tid; (j & ~63) < M; j += NT) {
     f4 row[8];
@@ -489,49 +707,50 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
       const float sc = (float)(red * v.scale_d);
       v.score[(size_t)u * v.Mcap + j] = sc;
       skey[j] = orderable(sc);
-      sid[j] = (uint16_t)j;
     }
   }
   __syncthreads();
 
   // ---- selection
-  const int nlist = select_phase<NT>(v, u, M, budget, skey, sid, sm, &s_cut, &s_tsel, list, kFusedList);
+  const SelectLds sel{skey, ssz, smem + kKeys + kSizes, hist, sm, misc, list, kFusedList};
+  const int nlist = select_phase<NT>(v, u, M, budget, sel);
   __syncthreads();
 
   // ---- gather + attention
   const int g = lane & 15, lg = lane >> 4;
   typename F::Qf q;
   F::load_q(q, Q, (size_t)u * G + (g < G ? g : 0), lg, g < G);
-  const int* plist = v.plist + (size_t)u * v.Pcap;
-  const char* pages = v.pages + (size_t)u * v.Pcap * kPageBytes;
+  const int* plist = v.plist + (size_t)u * v.Lcap;
+  const char* pages = v.pages + (size_t)u * v.Pcap * kPageElems * ES;
   const float sc = v.scale_f * kLog2e;
   Softmax st;
   st.m = -__builtin_inff(); st.l = 0.f;
 #pragma unroll
   for (int c = 0; c < 8; ++c) st.acc[c] = f4{0, 0, 0, 0};
   const int* src = nlist <= kFusedList ? list : plist;
-  {                                                   // two pages in flight per wavefront
+  const int ntile = (nlist + 3) >> 2, selK = (lane & 15) >> 2;
+#define DYNAKV_TILE(T) make_tile<ES>(pages, 4 * (T) + selK < nlist ? src[4 * (T) + selK] : -1, \
+                                     4 * (T) + lg < nlist ? src[4 * (T) + lg] : -1, lane)
+  {                                                   // two tiles in flight per wavefront
     typename F::KV a, b;
-    int ea = 0, eb = 0;
-    if (wave < nlist) {
-      ea = src[wave];
-      F::load(a, pages + (size_t)(ea >> 5) * kPageBytes, lane, ea & 31);
-    }
-    for (int p = wave; p < nlist; p += 2 * NW) {
-      if (p + NW < nlist) {
-        eb = src[p + NW];
-        F::load(b, pages + (size_t)(eb >> 5) * kPageBytes, lane, eb & 31);
+    Tile ta = DYNAKV_TILE(wave), tb = ta;
+    if (wave < ntile) F::load(a, ta);
+    for (int p = wave; p < ntile; p += 2 * NW) {
+      if (p + NW < ntile) {
+        tb = DYNAKV_TILE(p + NW);
+        F::load(b, tb);
       }
-      consume_page<F>(st, a, q, ea & 31, lg, sc);
-      if (p + NW < nlist) {
-        if (p + 2 * NW < nlist) {
-          ea = src[p + 2 * NW];
-          F::load(a, pages + (size_t)(ea >> 5) * kPageBytes, lane, ea & 31);
+      consume_page<F>(st, a, q, ta.nvq, sc);
+      if (p + NW < ntile) {
+        if (p + 2 * NW < ntile) {
+          ta = DYNAKV_TILE(p + 2 * NW);
+          F::load(a, ta);
         }
-        consume_page<F>(st, b, q, eb & 31, lg, sc);
+        consume_page<F>(st, b, q, tb.nvq, sc);
       }
     }
   }
+#undef DYNAKV_TILE
   float l = st.l;
   l += __shfl_xor(l, 16);
   l += __shfl_xor(l, 32);

@@ -184,6 +184,33 @@ def test_budget_edges_and_dense_limit(dtype, G, N0, M0):
         compare_state(ix, o, "edge step %d" % t, full=True)
 
 
+@pytest.mark.parametrize("env", [{}, {"DYNAKV_KV_SPLITS": "1"}])
+def test_selection_with_equal_scores_and_large_active_sets(env, monkeypatch):
+    """The selection's special paths: every score equal (a zero query: ids decide, and the cut falls inside the
+    group of equal scores), some scores equal (duplicated query heads against mirrored values do not tie, so a
+    zeroed half of the coordinates is used), and active sets of more than a thousand clusters."""
+    for k, val in env.items():
+        monkeypatch.setenv(k, val)
+    s = WorkloadSpec("sel", "f16", 2, 4, 4096, 4, 1400, 10 ** 6, 8, 0.05, var_alpha=0.0, size_factor=0.0, seed=31)
+    w = generate(s)
+    ix, o = make_pair(s, 2, kmeans_iters=2)
+    ix.dynakv_build_index(to_dev(w["K0"], "f16"), to_dev(w["V0"], "f16"), torch.from_numpy(w["init_idx"]).to(DEV))
+    o.build_index(w["K0"], w["V0"], w["init_idx"])
+    out = torch.empty(2, 4, 128, device=DEV)
+    lse = torch.empty(2, 4, device=DEV)
+    zero = np.zeros_like(w["Q"][0])
+    cases = [("all equal", zero, B) for B in (0, 1, 7, 100, 2500, 4095, 4096, 10 ** 6)]
+    cases += [("large set", w["Q"][1], B) for B in (3000, 3500, 4096, 10 ** 6)]
+    cases += [("mid set", w["Q"][2], B) for B in (1, 64, 1024, 2048)]
+    for what, Q, B in cases:
+        ix.dynakv_retrieve_attend(to_dev(Q, "f16"), B, out, lse)
+        oo, ol = o.retrieve_attend(Q, B)
+        check_attention(out.cpu().numpy(), lse.cpu().numpy(), oo, ol, "%s budget %d" % (what, B))
+        compare_retrieval(ix, o, "%s budget %d" % (what, B))
+    st = ix.dynakv_export_state(["n_selected"])
+    say("selection paths", env, "last active set:", st["n_selected"].tolist())
+
+
 def test_group_sum_custom_scale_all_resident_and_huge_logits():
     s = WorkloadSpec("opts", "f16", 3, 3, 700, 64, 24, 200, 6, 0.1, var_alpha=1.2, size_factor=0.0, buffer_max=0, seed=99)
     r = run_trajectory(s, range(3), 64, group_reduce=1, softmax_scale=0.05, kmeans_iters=5, full_every=8)
