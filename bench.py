@@ -1,9 +1,10 @@
 """Benchmark of the decode hot path on one MI355X.
 
-A step = dynakv_retrieve_attend + dynakv_append + dynakv_split over all units of the workload, on seeded
+A step = dynakv_decode_step (retrieve + attend, append, split) over all units of the workload, on seeded
 synthetic drifting-mixture inputs already resident in HBM.  Prints one JSON line: decode steps/s, the
-roofline of the dominant kernel (gather + attention, HBM-bound), and the CPU oracle timed on a bounded
-sample of the same workload on this machine's host cores.
+roofline of the dominant kernel (scores + selection + gather + attention + append in one launch when there is
+a unit per compute unit, else gather + attention; HBM-bound), and the CPU oracle timed on a bounded sample of
+the same workload on this machine's host cores.
 """
 from __future__ import annotations
 

@@ -70,6 +70,7 @@ def load():
         lib.dynakv_retrieve_attend.argtypes = [vp, vp, i32, vp, vp, vp]
         lib.dynakv_append.argtypes = [vp, vp, vp, vp]
         lib.dynakv_split.argtypes = [vp, vp]
+        lib.dynakv_decode_step.argtypes = [vp, vp, i32, vp, vp, vp, vp, vp]
         lib.dynakv_export_state.argtypes = [vp, C.POINTER(_State), vp]
         lib.dynakv_profile_enable.argtypes = [vp, i32]
         lib.dynakv_profile_read.argtypes = [vp, C.POINTER(i32), C.POINTER(C.c_double)]
@@ -155,12 +156,21 @@ class Index:
     def dynakv_split(self):
         _check(self._lib.dynakv_split(self._h, _stream()), "dynakv_split")
 
+    def dynakv_decode_step(self, Q: torch.Tensor, token_budget: int, out: torch.Tensor, lse: torch.Tensor | None,
+                           k_new: torch.Tensor, v_new: torch.Tensor):
+        c = self.cfg
+        qp = _dev(Q, self._tdtype, (c.n_units, c.group_size, c.head_dim))
+        op = _dev(out, torch.float32, (c.n_units, c.group_size, c.head_dim))
+        lp = _dev(lse, torch.float32, (c.n_units, c.group_size)) if lse is not None else None
+        kp = _dev(k_new, self._tdtype, (c.n_units, c.head_dim))
+        vp = _dev(v_new, self._tdtype, (c.n_units, c.head_dim))
+        _check(self._lib.dynakv_decode_step(self._h, qp, int(token_budget), op, lp, kp, vp, _stream()),
+               "dynakv_decode_step")
+
     def decode_step_ptrs(self, q_ptr: int, budget: int, out_ptr: int, lse_ptr: int, k_ptr: int, v_ptr: int, stream: int):
-        """One decode step (retrieve_attend, append, split) on raw device addresses: the same three ABI calls
-        without per-call tensor checks, for loops where interpreter time would otherwise dominate."""
-        lib, h = self._lib, self._h
-        rc = lib.dynakv_retrieve_attend(h, q_ptr, budget, out_ptr, lse_ptr, stream) or \
-            lib.dynakv_append(h, k_ptr, v_ptr, stream) or lib.dynakv_split(h, stream)
+        """dynakv_decode_step on raw device addresses, without per-call tensor checks, for loops where
+        interpreter time would otherwise dominate."""
+        rc = self._lib.dynakv_decode_step(self._h, q_ptr, budget, out_ptr, lse_ptr, k_ptr, v_ptr, stream)
         if rc:
             _check(rc, "decode step")
 

@@ -28,7 +28,7 @@ bool config_ok(const dynakv_config_t* c) {
   if (c->n_units < 1 || c->group_size < 1 || c->group_size > 16 || c->head_dim != kHeadDim) return false;
   if (c->dtype != DYNAKV_F32 && c->dtype != DYNAKV_F16 && c->dtype != DYNAKV_BF16) return false;
   if (c->n_clusters_init < 1 || c->max_clusters < c->n_clusters_init || c->max_clusters > kMaxClusters) return false;
-  if (c->max_tokens < c->n_clusters_init || c->max_tokens > (1 << 24)) return false;
+  if (c->max_tokens < c->n_clusters_init || c->max_tokens >= (1 << 24)) return false;
   if (c->kmeans_iters < 1 || c->buffer_max < 0) return false;
   if (c->group_reduce != DYNAKV_GROUP_MAX && c->group_reduce != DYNAKV_GROUP_SUM) return false;
   if (c->softmax_scale < 0.f || c->reserved != 0) return false;
@@ -151,17 +151,16 @@ dynakv_status_t dynakv_build_index(dynakv_index_t* ix, const void* K, const void
   return DYNAKV_OK;
 }
 
-dynakv_status_t dynakv_retrieve_attend(dynakv_index_t* ix, const void* Q, int32_t token_budget, float* out, float* lse,
-                                       void* stream) {
-  if (!ix || !Q || !out || token_budget < 0) return DYNAKV_EINVAL;
-  if (!ix->built) return DYNAKV_ESTATE;
-  hipStream_t st = (hipStream_t)stream;
+// Retrieval, and with kin != null the append as well if one kernel can do both (*appended says whether it did).
+static dynakv_status_t retrieve_impl(dynakv_index_t* ix, const void* Q, int32_t token_budget, float* out, float* lse,
+                                     const void* kin, const void* vin, hipStream_t st, bool* appended) {
   const bool fused = retrieve_is_fused(ix->view);
+  *appended = fused && kin;
   if (!fused && launch_score_select(ix->view, Q, token_budget, st) != hipSuccess) return DYNAKV_EHIP;
   const bool prof = ix->profiling && 2 * (ix->n_prof + 1) <= (int)ix->ev.size();
   if (prof && hipEventRecord(ix->ev[2 * ix->n_prof], st) != hipSuccess) return DYNAKV_EHIP;
   if (fused) {
-    if (launch_retrieve_fused(ix->view, Q, token_budget, out, lse, st) != hipSuccess) return DYNAKV_EHIP;
+    if (launch_retrieve_fused(ix->view, Q, token_budget, out, lse, kin, vin, st) != hipSuccess) return DYNAKV_EHIP;
   } else if (launch_gather_attend(ix->view, Q, out, lse, st) != hipSuccess) {
     return DYNAKV_EHIP;
   }
@@ -170,6 +169,26 @@ dynakv_status_t dynakv_retrieve_attend(dynakv_index_t* ix, const void* Q, int32_
     ++ix->n_prof;
   }
   return DYNAKV_OK;
+}
+
+dynakv_status_t dynakv_retrieve_attend(dynakv_index_t* ix, const void* Q, int32_t token_budget, float* out, float* lse,
+                                       void* stream) {
+  if (!ix || !Q || !out || token_budget < 0) return DYNAKV_EINVAL;
+  if (!ix->built) return DYNAKV_ESTATE;
+  bool appended;
+  return retrieve_impl(ix, Q, token_budget, out, lse, nullptr, nullptr, (hipStream_t)stream, &appended);
+}
+
+dynakv_status_t dynakv_decode_step(dynakv_index_t* ix, const void* Q, int32_t token_budget, float* out, float* lse,
+                                   const void* k_new, const void* v_new, void* stream) {
+  if (!ix || !Q || !out || token_budget < 0 || !k_new || !v_new) return DYNAKV_EINVAL;
+  if (!ix->built) return DYNAKV_ESTATE;
+  hipStream_t st = (hipStream_t)stream;
+  bool appended;
+  const dynakv_status_t rc = retrieve_impl(ix, Q, token_budget, out, lse, k_new, v_new, st, &appended);
+  if (rc != DYNAKV_OK) return rc;
+  if (!appended && launch_append(ix->view, k_new, v_new, st) != hipSuccess) return DYNAKV_EHIP;
+  return launch_split(ix->view, st) == hipSuccess ? DYNAKV_OK : DYNAKV_EHIP;
 }
 
 dynakv_status_t dynakv_append(dynakv_index_t* ix, const void* k_new, const void* v_new, void* stream) {

@@ -1,0 +1,121 @@
+// The part of an append that follows the nearest-cluster search (Algorithm 1, decode block; UpdateVar of
+// Section 4.2): shared by the stand-alone append kernel and by the retrieval kernel that finds the nearest
+// cluster during its own pass over the centroid table.
+#pragma once
+#include "common.hpp"
+
+namespace dynakv {
+
+struct AppendSmem {
+  double kd[kHeadDim];       // the new key, filled (and synchronised) by the caller
+  double delta[kHeadDim], r1[kHeadDim];
+  int ok, commit, page, slot, fresh;
+};
+
+// Cluster j (of M) receives token N of unit u.  Called by all NT >= 256 threads of the unit's workgroup.
+template <int NT>
+__device__ inline void append_commit(const View& v, int u, int j, int M, int N, const void* kin, const void* vin,
+                                     AppendSmem& a) {
+  const int tid = threadIdx.x;
+  const size_t cbase = (size_t)u * v.Mcap;
+  float* R = unit_R(v, u);
+  // UpdateVar, element-wise part: delta_d = k_d - r_d, r'_d = r_d + delta_d / n'
+  const int n1 = v.cn[cbase + j] + 1;
+  if (tid < kHeadDim) {
+    const double r = (double)R[r_index(j, tid)];
+    const double dl = a.kd[tid] - r;
+    a.delta[tid] = dl;
+    a.r1[tid] = r + dl / (double)n1;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    const int sz = v.cn[cbase + j] + v.cb[cbase + j];
+    const int slot = sz % kPageTokens;
+    int page = v.ctail[cbase + j];
+    int ok = 1, fresh = 0;
+    if (slot == 0) {                      // no page yet, or the tail page is full
+      const int np = alloc_page(v, u, &fresh);
+      if (np < 0) {
+        v.err[u] |= DYNAKV_ERR_TOKENS;
+        ok = 0;
+      } else {
+        v.pnext[(size_t)u * v.Pcap + np] = -1;
+        if (sz != 0) v.pnext[(size_t)u * v.Pcap + page] = np;
+        if (sz / kPageTokens < kInlinePages) v.cpg[(cbase + j) * kInlinePages + sz / kPageTokens] = np;
+        v.ctail[cbase + j] = np;
+        page = np;
+      }
+    }
+    int commit = 0;
+    if (ok) {
+      v.last_assign[u] = j;
+      if (v.cflag[cbase + j]) {
+        v.cb[cbase + j] += 1;             // goes to the buffer of a flagged cluster
+      } else {
+        // UpdateVar, the running part: M2' = M2 + sum_d delta_d * (k_d - r'_d)
+        const double M2 = v.cM2[cbase + j] + blocked16([&](int k) __attribute__((always_inline)) {
+          double s = 0.0;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) s = fma(a.delta[k * 8 + e], a.kd[k * 8 + e] - a.r1[k * 8 + e], s);
+          return s;
+        });
+        const double var1 = M2 / (double)n1;
+        bool trig = false;
+        if (n1 >= 2) {
+          if (v.var_alpha > 0.f && var1 > v.tau[u]) trig = true;
+          if (v.size_factor > 0.f && (double)n1 * (double)M > (double)v.size_factor * (double)(N + 1)) trig = true;
+        }
+        if (!trig) {
+          v.cn[cbase + j] = n1;
+          v.cM2[cbase + j] = M2;
+          commit = 1;
+        } else {
+          v.cflag[cbase + j] = 1;
+          v.cb[cbase + j] = 1;
+          v.nflag[u] += 1;
+        }
+      }
+      v.N[u] = N + 1;
+      v.ppos[((size_t)u * v.Pcap + page) * kPageTokens + slot] = N;
+    }
+    a.ok = ok; a.commit = commit; a.page = page; a.slot = slot; a.fresh = fresh;
+  }
+  __syncthreads();
+  if (!a.ok) return;
+  if (a.commit && tid < kHeadDim) R[r_index(j, tid)] = (float)a.r1[tid];
+  char* pg = page_ptr(v, u, a.page);
+  if (a.fresh) {                          // first use of this page: unused slots must hold finite values
+    const int n16 = kPageElems * elem_size(v.dtype) / 16;
+    for (int i = tid; i < n16; i += NT) ((uint4*)pg)[i] = uint4{0, 0, 0, 0};
+    __syncthreads();
+  }
+  if (tid < kHeadDim) copy_elem(pg, k_index(v.dtype, a.slot, tid), kin, (size_t)u * kHeadDim + tid, v.dtype);
+  else if (tid < 2 * kHeadDim)
+    copy_elem(pg, v_index(v.dtype, a.slot, tid - kHeadDim), vin, (size_t)u * kHeadDim + tid - kHeadDim, v.dtype);
+}
+
+// Workgroup-wide arg-min over (value, index) pairs, one per thread (index < 0: none); equal values go to the
+// lowest index.  NT / 64 <= 16 wavefronts; sv / si need 16 entries.  Every thread gets the winning index.
+template <int NT>
+__device__ inline int block_argmin(double val, int idx, double* sv, int* si) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const double ov = __shfl_xor(val, o);
+    const int oi = __shfl_xor(idx, o);
+    if (oi >= 0 && (idx < 0 || ov < val || (ov == val && oi < idx))) { val = ov; idx = oi; }
+  }
+  __syncthreads();
+  if (lane == 0) { sv[w] = val; si[w] = idx; }
+  __syncthreads();
+  val = sv[0]; idx = si[0];
+#pragma unroll
+  for (int k = 1; k < NT / 64; ++k) {
+    const double ov = sv[k];
+    const int oi = si[k];
+    if (oi >= 0 && (idx < 0 || ov < val || (ov == val && oi < idx))) { val = ov; idx = oi; }
+  }
+  return idx;
+}
+
+}  // namespace dynakv

@@ -333,7 +333,8 @@ hipError_t launch_build_index(const View& v, const void* K, const void* V, int n
                               int iters, void* workspace, size_t workspace_bytes, hipStream_t st);
 hipError_t launch_score_select(const View& v, const void* Q, int budget, hipStream_t st);
 bool retrieve_is_fused(const View& v);
-hipError_t launch_retrieve_fused(const View& v, const void* Q, int budget, float* out, float* lse, hipStream_t st);
+hipError_t launch_retrieve_fused(const View& v, const void* Q, int budget, float* out, float* lse, const void* kin,
+                                 const void* vin, hipStream_t st);
 hipError_t launch_gather_attend(const View& v, const void* Q, float* out, float* lse, hipStream_t st);
 hipError_t launch_append(const View& v, const void* k, const void* val, hipStream_t st);
 hipError_t launch_split(const View& v, hipStream_t st);

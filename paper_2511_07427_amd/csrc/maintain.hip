@@ -4,7 +4,7 @@
 //   export_kernel - snapshot of the index for tests
 // One workgroup per unit; each unit's record is touched by that workgroup only.  All decisions are
 // taken on float64 values accumulated left to right, ties to the lowest index.
-#include "common.hpp"
+#include "append.hpp"
 
 namespace dynakv {
 
@@ -12,10 +12,9 @@ namespace {
 
 // ------------------------------------------------------------------------------------------- append
 __global__ __launch_bounds__(256) void append_kernel(View v, const void* kin, const void* vin) {
-  __shared__ double kd[kHeadDim], delta[kHeadDim], r1[kHeadDim];
-  __shared__ double sv[256];
-  __shared__ int si[256];
-  __shared__ int s_ok, s_commit, s_page, s_slot, s_fresh;
+  __shared__ AppendSmem a;
+  __shared__ double sv[16];
+  __shared__ int si[16];
   const int u = blockIdx.x, tid = threadIdx.x;
   float* R = unit_R(v, u);
   f4 row[8];
@@ -25,97 +24,22 @@ __global__ __launch_bounds__(256) void append_kernel(View v, const void* kin, co
     if (tid == 0) v.err[u] |= DYNAKV_ERR_TOKENS;
     return;
   }
-  if (tid < kHeadDim) kd[tid] = (double)load_elem(kin, (size_t)u * kHeadDim + tid, v.dtype);
+  if (tid < kHeadDim) a.kd[tid] = (double)load_elem(kin, (size_t)u * kHeadDim + tid, v.dtype);
   __syncthreads();
-  const size_t cbase = (size_t)u * v.Mcap;
   // nearest centre (squared Euclidean distance); lane = cluster, 16 contiguous bytes per lane and load
   double best = __builtin_inf();
   int arg = -1;
   for (int j = tid; j < M; j += 256) {
     if (j != tid) load_centroid_head(R, j, row);
     double dist[1];
-    centroid_sums<1>(R, j, row, dist, [&](int d, float rv, double (&a)[1]) __attribute__((always_inline)) {
-      const double t = kd[d] - (double)rv;
-      a[0] = fma(t, t, a[0]);
+    centroid_sums<1>(R, j, row, dist, [&](int d, float rv, double (&acc)[1]) __attribute__((always_inline)) {
+      const double t = a.kd[d] - (double)rv;
+      acc[0] = fma(t, t, acc[0]);
     });
-    const double acc = dist[0];
-    if (acc < best || arg < 0) { best = acc; arg = j; }
+    if (dist[0] < best || arg < 0) { best = dist[0]; arg = j; }
   }
-  block_arg_reduce<false>(best, arg, sv, si);
-  const int j = si[0];
-  __syncthreads();
-  // UpdateVar, element-wise part: delta_d = k_d - r_d, r'_d = r_d + delta_d / n'
-  const int n1 = v.cn[cbase + j] + 1;
-  if (tid < kHeadDim) {
-    const double r = (double)R[r_index(j, tid)];
-    const double dl = kd[tid] - r;
-    delta[tid] = dl;
-    r1[tid] = r + dl / (double)n1;
-  }
-  __syncthreads();
-  if (tid == 0) {
-    const int sz = v.cn[cbase + j] + v.cb[cbase + j];
-    const int slot = sz % kPageTokens;
-    int page = v.ctail[cbase + j];
-    int ok = 1, fresh = 0;
-    if (slot == 0) {                      // no page yet, or the tail page is full
-      const int np = alloc_page(v, u, &fresh);
-      if (np < 0) {
-        v.err[u] |= DYNAKV_ERR_TOKENS;
-        ok = 0;
-      } else {
-        v.pnext[(size_t)u * v.Pcap + np] = -1;
-        if (sz != 0) v.pnext[(size_t)u * v.Pcap + page] = np;
-        if (sz / kPageTokens < kInlinePages) v.cpg[(cbase + j) * kInlinePages + sz / kPageTokens] = np;
-        v.ctail[cbase + j] = np;
-        page = np;
-      }
-    }
-    int commit = 0;
-    if (ok) {
-      v.last_assign[u] = j;
-      if (v.cflag[cbase + j]) {
-        v.cb[cbase + j] += 1;             // goes to the buffer of a flagged cluster
-      } else {
-        // UpdateVar, the running part: M2' = M2 + sum_d delta_d * (k_d - r'_d)
-        const double M2 = v.cM2[cbase + j] + blocked16([&](int k) __attribute__((always_inline)) {
-          double a = 0.0;
-#pragma unroll
-          for (int e = 0; e < 8; ++e) a = fma(delta[k * 8 + e], kd[k * 8 + e] - r1[k * 8 + e], a);
-          return a;
-        });
-        const double var1 = M2 / (double)n1;
-        bool trig = false;
-        if (n1 >= 2) {
-          if (v.var_alpha > 0.f && var1 > v.tau[u]) trig = true;
-          if (v.size_factor > 0.f && (double)n1 * (double)M > (double)v.size_factor * (double)(N + 1)) trig = true;
-        }
-        if (!trig) {
-          v.cn[cbase + j] = n1;
-          v.cM2[cbase + j] = M2;
-          commit = 1;
-        } else {
-          v.cflag[cbase + j] = 1;
-          v.cb[cbase + j] = 1;
-          v.nflag[u] += 1;
-        }
-      }
-      v.N[u] = N + 1;
-      v.ppos[((size_t)u * v.Pcap + page) * kPageTokens + slot] = N;
-    }
-    s_ok = ok; s_commit = commit; s_page = page; s_slot = slot; s_fresh = fresh;
-  }
-  __syncthreads();
-  if (!s_ok) return;
-  if (s_commit && tid < kHeadDim) R[r_index(j, tid)] = (float)r1[tid];
-  char* pg = page_ptr(v, u, s_page);
-  if (s_fresh) {                          // first use of this page: unused slots must hold finite values
-    const int n16 = kPageElems * elem_size(v.dtype) / 16;
-    for (int i = tid; i < n16; i += 256) ((uint4*)pg)[i] = uint4{0, 0, 0, 0};
-    __syncthreads();
-  }
-  if (tid < kHeadDim) copy_elem(pg, k_index(v.dtype, s_slot, tid), kin, (size_t)u * kHeadDim + tid, v.dtype);
-  else copy_elem(pg, v_index(v.dtype, s_slot, tid - kHeadDim), vin, (size_t)u * kHeadDim + tid - kHeadDim, v.dtype);
+  const int j = block_argmin<256>(best, arg, sv, si);
+  append_commit<256>(v, u, j, M, N, kin, vin, a);
 }
 
 // ------------------------------------------------------------------------------------------- split

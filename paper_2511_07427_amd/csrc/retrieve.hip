@@ -5,7 +5,7 @@
 //   gather_attend  - streams the selected clusters' pages once; QK^T and PV on matrix cores with an
 //                    online (running-max) softmax, so any gather order is overflow-safe; split over
 //                    several workgroups per unit and merged by the last one to arrive.
-#include "common.hpp"
+#include "append.hpp"
 
 namespace dynakv {
 
@@ -310,24 +310,56 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
     cut = 1; tsel = budget;
   }
 
-  // rank and gather offsets of every selected cluster, then its list entries
+  // rank and gather offsets of every selected cluster, by counting the selected clusters that precede it
+  constexpr int PER = (kCountMax + NT - 1) / NT;
+  unsigned long long packed[PER];
+  int quads = 0;
+#pragma unroll
+  for (int r = 0; r < PER; ++r) {
+    const int p = tid + r * NT;
+    packed[r] = 0;
+    if (p < cut) {
+      const unsigned long long my = ck[p];
+      int rank = 0, t0 = 0, q0 = 0;
+#pragma unroll 4
+      for (int q = 0; q < cut; ++q) {
+        const unsigned long long o = ck[q];
+        const int w = cw[q];
+        if (o > my) { ++rank; t0 += w; q0 += (w + 3) >> 2; }
+      }
+      const int id = 0xFFFF - (int)(my & 0xFFFF);
+      v.sel_ids[cb + rank] = id;
+      packed[r] = ((unsigned long long)id << 48) | ((unsigned long long)t0 << 24) | (unsigned long long)q0;
+      quads += (cw[p] + 3) >> 2;
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int r = 0; r < PER; ++r)
+    if (tid + r * NT < cut) ck[tid + r * NT] = packed[r];      // id, first gather offset, first list entry
+  __syncthreads();
+  // list entries: one work item per inline page of a selected cluster (every page but the last is full, so
+  // its place in the list follows from its index); pages past the inline table are walked by the last item
   int* plist = v.plist + (size_t)u * v.Lcap;
   int* poff = v.plist_off + (size_t)u * v.Lcap;
-  int quads = 0;
-  for (int p = tid; p < cut; p += NT) {
-    const unsigned long long my = ck[p];
-    const int myw = cw[p];
-    int rank = 0, t0 = 0, q0 = 0;
-#pragma unroll 4
-    for (int q = 0; q < cut; ++q) {
-      const unsigned long long o = ck[q];
-      const int w = cw[q];
-      if (o > my) { ++rank; t0 += w; q0 += (w + 3) >> 2; }
+  for (int i = tid; i < cut * kInlinePages; i += NT) {
+    const int p = i / kInlinePages, k = i % kInlinePages;
+    const int take = cw[p], npages = (take + kPageTokens - 1) / kPageTokens;
+    if (k >= npages) continue;
+    const unsigned long long pk = ck[p];
+    const int id = (int)(pk >> 48), t0 = (int)(pk >> 24) & 0xFFFFFF, q0 = (int)pk & 0xFFFFFF;
+    int page = v.cpg[(cb + id) * kInlinePages + k];
+    for (int kk = k; kk < npages && page >= 0; ++kk) {
+      const int nv = min(kPageTokens, take - kk * kPageTokens), w = q0 + 4 * kk;
+      for (int qd = 0; 4 * qd < nv; ++qd) {
+        const int e = page * 16 + qd * 4 + (min(4, nv - 4 * qd) - 1);
+        plist[w + qd] = e;
+        if (w + qd < s.list_cap) s.list[w + qd] = e;
+        poff[w + qd] = t0 + kk * kPageTokens + 4 * qd;
+      }
+      if (k < kInlinePages - 1) break;
+      page = v.pnext[(size_t)u * v.Pcap + page];
     }
-    const int id = 0xFFFF - (int)(my & 0xFFFF);
-    v.sel_ids[cb + rank] = id;
-    emit_cluster(v, u, cb + id, myw, q0, t0, plist, poff, s.list, s.list_cap);
-    quads += (myw + 3) >> 2;
   }
   if (quads) atomicAdd(&s.misc[6], quads);
   __syncthreads();
@@ -654,9 +686,13 @@ __global__ __launch_bounds__(NW * 64) void gather_attend_kernel(View v, const vo
 constexpr int kFusedClusters = 4096;   // clusters per unit the fused kernel can sort
 constexpr int kFusedList = 2048;       // gather-list entries it keeps in LDS (longer lists are read from the workspace)
 
-template <int DT, int NW, int GP>
+//
+// With APPEND the same pass over the centroid table also finds the cluster nearest to the step's new key
+// (one more accumulator per centroid), and the append itself runs at the end of the kernel: a decode step then
+// reads the table once instead of twice.  Scores and selection see the index as it was before the append.
+template <int DT, int NW, int GP, bool APPEND>
 __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const void* Q, int budget, float* out,
-                                                                float* lse) {
+                                                                float* lse, const void* kin, const void* vin) {
   using F = Frag<DT>;
   constexpr int NT = NW * 64;
   constexpr int ES = DT == DYNAKV_F32 ? 4 : 2;
@@ -666,6 +702,9 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   // scores, sizes, candidates, gather list; after the page loop the front doubles as the merge buffer
   __shared__ __align__(16) unsigned char smem[kKeys + kSizes + kSelRegion + kList];
   __shared__ double qs[kHeadDim][GP];
+  __shared__ AppendSmem ap;
+  __shared__ double am_v[16];
+  __shared__ int am_i[16];
   __shared__ int sm[64];
   __shared__ int misc[8];
   uint32_t* skey = (uint32_t*)smem;
@@ -685,20 +724,32 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
     const int g = t / kHeadDim, d = t % kHeadDim;
     qs[d][g] = g < G ? (double)load_elem(Q, ((size_t)u * G + g) * kHeadDim + d, v.dtype) : 0.0;
   }
+  const int N = APPEND ? v.N[u] : 0;
+  const bool room = APPEND && N < v.Ncap;              // otherwise the append is refused, as by the append kernel
+  if (APPEND && tid < kHeadDim) ap.kd[tid] = (double)load_elem(kin, (size_t)u * kHeadDim + tid, v.dtype);
   int Mpad = 2;
   while (Mpad < M) Mpad <<= 1;
   for (int i = M + tid; i < Mpad; i += NT) skey[i] = 0u;
   for (int j = tid; j < M; j += NT) ssz[j] = v.cn[(size_t)u * v.Mcap + j] + v.cb[(size_t)u * v.Mcap + j];
   __syncthreads();
+  double near_d = __builtin_inf();
+  int near_j = -1;
   for (int j = tid; (j & ~63) < M; j += NT) {
     f4 row[8];
     load_centroid_head(R, j, row);
-    double acc[GP];
-    centroid_sums<GP>(R, j, row, acc, [&](int d, float rv, double (&a)[GP]) __attribute__((always_inline)) {
+    constexpr int NA = GP + (APPEND ? 1 : 0);
+    double acc[NA];
+    centroid_sums<NA>(R, j, row, acc, [&](int d, float rv, double (&a)[NA]) __attribute__((always_inline)) {
       const double rd = (double)rv;
 #pragma unroll
       for (int g = 0; g < GP; ++g) a[g] = fma(qs[d][g], rd, a[g]);
+      if constexpr (APPEND) {
+        const double t = ap.kd[d] - rd;
+        a[GP] = fma(t, t, a[GP]);
+      }
     });
+    if constexpr (APPEND)
+      if (j < M && (acc[GP] < near_d || near_j < 0)) { near_d = acc[GP]; near_j = j; }
     if (j < M) {
       double red = acc[0];
 #pragma unroll
@@ -773,6 +824,14 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
     out[((size_t)u * G + gg) * kHeadDim + dc] = L > 0.f ? O / L : 0.f;
     if (lse && dc == 0) lse[(size_t)u * G + gg] = L > 0.f ? (Mx + __builtin_amdgcn_logf(L)) * kLn2 : -__builtin_inff();
   }
+  if constexpr (APPEND) {
+    if (!room) {
+      if (tid == 0) v.err[u] |= DYNAKV_ERR_TOKENS;
+      return;
+    }
+    const int ja = block_argmin<NT>(near_d, near_j, am_v, am_i);
+    append_commit<NT>(v, u, ja, M, N, kin, vin, ap);
+  }
 }
 
 template <int DT, int NW, bool PF>
@@ -796,16 +855,24 @@ bool retrieve_is_fused(const View& v) {
   return v.fuse && v.S == 1 && v.dtype != DYNAKV_F32 && v.Mcap <= kFusedClusters && v.G <= 8;
 }
 
-template <int DT>
-static void launch_fused(const View& v, const void* Q, int budget, float* out, float* lse, hipStream_t st) {
-  // eight wavefronts: 256 registers per lane leave room for float64 scoring and a second page in flight
-  if (v.G <= 4) retrieve_fused_kernel<DT, 8, 4><<<v.U, 512, 0, st>>>(v, Q, budget, out, lse);
-  else retrieve_fused_kernel<DT, 8, 8><<<v.U, 512, 0, st>>>(v, Q, budget, out, lse);
+template <int DT, bool APPEND>
+static void launch_fused(const View& v, const void* Q, int budget, float* out, float* lse, const void* kin,
+                         const void* vin, hipStream_t st) {
+  // eight wavefronts: 256 registers per lane leave room for float64 scoring and a second tile in flight
+  if (v.G <= 4) retrieve_fused_kernel<DT, 8, 4, APPEND><<<v.U, 512, 0, st>>>(v, Q, budget, out, lse, kin, vin);
+  else retrieve_fused_kernel<DT, 8, 8, APPEND><<<v.U, 512, 0, st>>>(v, Q, budget, out, lse, kin, vin);
 }
 
-hipError_t launch_retrieve_fused(const View& v, const void* Q, int budget, float* out, float* lse, hipStream_t st) {
-  if (v.dtype == DYNAKV_F16) launch_fused<DYNAKV_F16>(v, Q, budget, out, lse, st);
-  else launch_fused<DYNAKV_BF16>(v, Q, budget, out, lse, st);
+// kin == nullptr: retrieval only; otherwise retrieval followed by the append of (kin, vin).
+hipError_t launch_retrieve_fused(const View& v, const void* Q, int budget, float* out, float* lse, const void* kin,
+                                 const void* vin, hipStream_t st) {
+  if (v.dtype == DYNAKV_F16) {
+    if (kin) launch_fused<DYNAKV_F16, true>(v, Q, budget, out, lse, kin, vin, st);
+    else launch_fused<DYNAKV_F16, false>(v, Q, budget, out, lse, kin, vin, st);
+  } else {
+    if (kin) launch_fused<DYNAKV_BF16, true>(v, Q, budget, out, lse, kin, vin, st);
+    else launch_fused<DYNAKV_BF16, false>(v, Q, budget, out, lse, kin, vin, st);
+  }
   return hipGetLastError();
 }
 

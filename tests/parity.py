@@ -50,18 +50,20 @@ def check_attention(out_g: np.ndarray, lse_g: np.ndarray, out_o: np.ndarray, lse
     return float(rel.max())
 
 
-def compare_retrieval(ix: binding.Index, o: Oracle, what=""):
+def compare_retrieval(ix: binding.Index, o: Oracle, what="", gather=True):
     """Scores, selected clusters (ordered) and gather indices (ordered) of the last retrieval, bit for bit.
-    Call it before the next append: a later split may recycle the pages the gather list points to."""
-    st = {k: v.numpy() for k, v in
-          ix.dynakv_export_state(["n_selected", "selected", "n_gathered", "gathered", "scores"]).items()}
+    The gather indices can only be read back before the next split (which may recycle the pages the gather
+    list points to): after a whole-step call pass gather=False."""
+    fields = ["n_selected", "selected", "n_gathered", "scores"] + (["gathered"] if gather else [])
+    st = {k: v.numpy() for k, v in ix.dynakv_export_state(fields).items()}
     for u in range(ix.cfg.n_units):
         w = "%s unit %d" % (what, u)
         sel, gat, sc = o.selected(u), o.gather(u), o.scores(u)
         assert st["n_selected"][u] == len(sel), w
         np.testing.assert_array_equal(st["selected"][u, :len(sel)], sel, err_msg=w + " selected clusters")
         assert st["n_gathered"][u] == len(gat), w
-        np.testing.assert_array_equal(st["gathered"][u, :len(gat)], gat, err_msg=w + " gather indices")
+        if gather:
+            np.testing.assert_array_equal(st["gathered"][u, :len(gat)], gat, err_msg=w + " gather indices")
         np.testing.assert_array_equal(st["scores"][u, :len(sc)], sc, err_msg=w + " scores")
 
 
@@ -95,8 +97,9 @@ def compare_state(ix: binding.Index, o: Oracle, what="", full=True):
 
 
 def run_trajectory(spec: WorkloadSpec, units, steps: int, budget: int | None = None, check_every: int = 1,
-                   full_every: int = 64, **over):
-    """Builds both indexes on the given units of the workload and runs `steps` decode steps side by side."""
+                   full_every: int = 64, step_call: str = "three", **over):
+    """Builds both indexes on the given units of the workload and runs `steps` decode steps side by side.
+    step_call: "three" = retrieve_attend, append, split; "one" = dynakv_decode_step; "mixed" = they alternate."""
     units = list(units)
     w = generate(spec, units=units, steps=steps)
     ix, o = make_pair(spec, len(units), max_tokens=spec.prefill + steps, **over)
@@ -112,15 +115,20 @@ def run_trajectory(spec: WorkloadSpec, units, steps: int, budget: int | None = N
     lse = torch.empty(U, G, dtype=torch.float32, device=DEV)
     worst = 0.0
     for t in range(steps):
-        ix.dynakv_retrieve_attend(Qd[t], budget, out, lse)
-        oo, ol = o.retrieve_attend(w["Q"][t], budget)
+        whole = step_call == "one" or (step_call == "mixed" and t % 2 == 1)
         check = t % check_every == 0 or t == steps - 1
+        oo, ol = o.retrieve_attend(w["Q"][t], budget)
+        if whole:
+            ix.dynakv_decode_step(Qd[t], budget, out, lse, Kd[t], Vd[t])
+        else:
+            ix.dynakv_retrieve_attend(Qd[t], budget, out, lse)
         if check:
             worst = max(worst, check_attention(out.cpu().numpy(), lse.cpu().numpy(), oo, ol, "step %d" % t))
-            compare_retrieval(ix, o, "step %d" % t)
-        ix.dynakv_append(Kd[t], Vd[t])
+            compare_retrieval(ix, o, "step %d" % t, gather=not whole)
+        if not whole:
+            ix.dynakv_append(Kd[t], Vd[t])
+            ix.dynakv_split()
         o.append(w["Knew"][t], w["Vnew"][t])
-        ix.dynakv_split()
         o.split()
         if check:
             compare_state(ix, o, "step %d" % t, full=(t % full_every == 0 or t == steps - 1))

@@ -84,8 +84,22 @@ def test_every_launch_shape_of_retrieve_attend(name, units, steps, env, monkeypa
         s = s.scaled(kmeans_iters=2)
     if name == "llama3_8b":
         s = s.scaled(max_cluster_factor=8)
-    r = run_trajectory(s, units, steps, check_every=2, full_every=32)
+    r = run_trajectory(s, units, steps, check_every=1, full_every=32, step_call="mixed")
     say(name, env, {k: r[k] for k in ("worst_rel", "splits", "clusters")})
+
+
+@pytest.mark.parametrize("name,units,steps,env", [
+    ("llama3_8b", [7, 8, 9], 160, {"DYNAKV_KV_SPLITS": "1"}),      # one pass over the centroids per step, G = 4
+    ("qwen25_7b", [5, 6], 256, {"DYNAKV_KV_SPLITS": "1"}),         # the same with G = 7
+    ("batched16", [9], 64, {}),                                    # separate kernels behind the same call
+])
+def test_whole_step_call_matches_the_three_calls(name, units, steps, env, monkeypatch):
+    for k, val in env.items():
+        monkeypatch.setenv(k, val)
+    s = CONFIGS[name]
+    r = run_trajectory(s, units, steps, check_every=1, full_every=32, step_call="one")
+    say(name, env, {k: r[k] for k in ("worst_rel", "splits", "forced", "clusters")})
+    assert r["splits"] > 0 or name == "batched16"
 
 
 # --------------------------------------------------------------------------- hand-worked fixtures, padded to d = 128
@@ -244,6 +258,29 @@ def test_capacity_limits_set_the_error_word_and_keep_state():
     st = ix.dynakv_export_state(["error", "n_tokens", "n_clusters"])
     assert st["n_tokens"][0] == 68 and st["n_clusters"][0] == 4
     assert st["error"][0] & binding.ERR_TOKENS and st["error"][0] & binding.ERR_CLUSTERS
+
+
+@pytest.mark.parametrize("env", [{}, {"DYNAKV_KV_SPLITS": "1"}])
+def test_whole_step_call_at_the_capacity_limits(env, monkeypatch):
+    for k, val in env.items():
+        monkeypatch.setenv(k, val)
+    s = WorkloadSpec("cap", "f16", 1, 2, 64, 8, 4, 32, 4, 0.5, var_alpha=0.5, size_factor=0.0, buffer_max=0,
+                     max_cluster_factor=1, seed=5)
+    w = generate(s)
+    ix, o = make_pair(s, 1, max_tokens=68)
+    ix.dynakv_build_index(to_dev(w["K0"], "f16"), to_dev(w["V0"], "f16"), torch.from_numpy(w["init_idx"]).to(DEV))
+    o.build_index(w["K0"], w["V0"], w["init_idx"])
+    Qd, Kd, Vd = to_dev(w["Q"], "f16"), to_dev(w["Knew"], "f16"), to_dev(w["Vnew"], "f16")
+    out = torch.empty(1, 2, 128, device=DEV)
+    lse = torch.empty(1, 2, device=DEV)
+    for t in range(8):
+        ix.dynakv_decode_step(Qd[t], 32, out, lse, Kd[t], Vd[t])
+        oo, ol = o.retrieve_attend(w["Q"][t], 32)
+        check_attention(out.cpu().numpy(), lse.cpu().numpy(), oo, ol, "cap step %d" % t)
+        o.append(w["Knew"][t], w["Vnew"][t]); o.split()
+        compare_state(ix, o, "cap step %d" % t)
+    st = ix.dynakv_export_state(["error", "n_tokens"])
+    assert st["n_tokens"][0] == 68 and st["error"][0] & binding.ERR_TOKENS
 
 
 def test_rebuild_resets_the_index_and_runs_are_deterministic():
