@@ -9,32 +9,71 @@ namespace dynakv {
 struct AppendSmem {
   double kd[kHeadDim];       // the new key, filled (and synchronised) by the caller
   double delta[kHeadDim], r1[kHeadDim];
+  double bs[16];             // block sums of the M2 increment
+  double m2, tau;
+  int cn, cb, ctail, cflag, nflag, free_top, bump, free_page;
   int ok, commit, page, slot, fresh;
 };
 
 // Cluster j (of M) receives token N of unit u.  Called by all NT >= 256 threads of the unit's workgroup.
+// The record of the cluster and the unit's allocator state are fetched by separate lanes at once, the sum of
+// UpdateVar is formed from 16 block sums computed side by side, and one thread then takes the decisions.
 template <int NT>
 __device__ inline void append_commit(const View& v, int u, int j, int M, int N, const void* kin, const void* vin,
                                      AppendSmem& a) {
   const int tid = threadIdx.x;
   const size_t cbase = (size_t)u * v.Mcap;
   float* R = unit_R(v, u);
+  double r = 0.0;
+  if (tid < kHeadDim) r = (double)R[r_index(j, tid)];
+  switch (tid - kHeadDim) {
+    case 0: a.cn = v.cn[cbase + j]; break;
+    case 1: a.cb = v.cb[cbase + j]; break;
+    case 2: a.ctail = v.ctail[cbase + j]; break;
+    case 3: a.cflag = v.cflag[cbase + j]; break;
+    case 4: a.m2 = v.cM2[cbase + j]; break;
+    case 5: a.tau = v.tau[u]; break;
+    case 6: a.nflag = v.nflag[u]; break;
+    case 7: a.bump = v.bump[u]; break;
+    case 8: {
+      const int top = v.free_top[u];
+      a.free_top = top;
+      a.free_page = top > 0 ? v.freelist[(size_t)u * v.Pcap + top - 1] : -1;
+      break;
+    }
+    default: break;
+  }
+  __syncthreads();
   // UpdateVar, element-wise part: delta_d = k_d - r_d, r'_d = r_d + delta_d / n'
-  const int n1 = v.cn[cbase + j] + 1;
+  const int n1 = a.cn + 1;
   if (tid < kHeadDim) {
-    const double r = (double)R[r_index(j, tid)];
     const double dl = a.kd[tid] - r;
     a.delta[tid] = dl;
     a.r1[tid] = r + dl / (double)n1;
   }
   __syncthreads();
+  if (tid < 16) {                           // block tid of sum_d delta_d * (k_d - r'_d)
+    double s = 0.0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s = fma(a.delta[tid * 8 + e], a.kd[tid * 8 + e] - a.r1[tid * 8 + e], s);
+    a.bs[tid] = s;
+  }
+  __syncthreads();
   if (tid == 0) {
-    const int sz = v.cn[cbase + j] + v.cb[cbase + j];
+    const int sz = a.cn + a.cb;
     const int slot = sz % kPageTokens;
-    int page = v.ctail[cbase + j];
+    int page = a.ctail;
     int ok = 1, fresh = 0;
     if (slot == 0) {                      // no page yet, or the tail page is full
-      const int np = alloc_page(v, u, &fresh);
+      int np = -1;                        // from the free stack, else from the untouched tail of the pool
+      if (a.free_top > 0) {
+        np = a.free_page;
+        v.free_top[u] = a.free_top - 1;
+      } else if (a.bump < v.Pcap) {
+        np = a.bump;
+        v.bump[u] = a.bump + 1;
+        fresh = 1;
+      }
       if (np < 0) {
         v.err[u] |= DYNAKV_ERR_TOKENS;
         ok = 0;
@@ -49,20 +88,15 @@ __device__ inline void append_commit(const View& v, int u, int j, int M, int N, 
     int commit = 0;
     if (ok) {
       v.last_assign[u] = j;
-      if (v.cflag[cbase + j]) {
-        v.cb[cbase + j] += 1;             // goes to the buffer of a flagged cluster
+      if (a.cflag) {
+        v.cb[cbase + j] = a.cb + 1;       // goes to the buffer of a flagged cluster
       } else {
         // UpdateVar, the running part: M2' = M2 + sum_d delta_d * (k_d - r'_d)
-        const double M2 = v.cM2[cbase + j] + blocked16([&](int k) __attribute__((always_inline)) {
-          double s = 0.0;
-#pragma unroll
-          for (int e = 0; e < 8; ++e) s = fma(a.delta[k * 8 + e], a.kd[k * 8 + e] - a.r1[k * 8 + e], s);
-          return s;
-        });
+        const double M2 = a.m2 + blocked16([&](int k) __attribute__((always_inline)) { return a.bs[k]; });
         const double var1 = M2 / (double)n1;
         bool trig = false;
         if (n1 >= 2) {
-          if (v.var_alpha > 0.f && var1 > v.tau[u]) trig = true;
+          if (v.var_alpha > 0.f && var1 > a.tau) trig = true;
           if (v.size_factor > 0.f && (double)n1 * (double)M > (double)v.size_factor * (double)(N + 1)) trig = true;
         }
         if (!trig) {
@@ -72,7 +106,7 @@ __device__ inline void append_commit(const View& v, int u, int j, int M, int N, 
         } else {
           v.cflag[cbase + j] = 1;
           v.cb[cbase + j] = 1;
-          v.nflag[u] += 1;
+          v.nflag[u] = a.nflag + 1;
         }
       }
       v.N[u] = N + 1;

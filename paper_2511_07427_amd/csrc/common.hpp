@@ -278,6 +278,28 @@ __device__ inline int block_excl_scan(int val, int* sm, int& total) {
   return base + x - val;
 }
 
+// The same over 64-bit values (two 32-bit sums side by side); `sm` needs 16 entries.
+__device__ inline unsigned long long block_excl_scan64(unsigned long long val, unsigned long long* sm,
+                                                       unsigned long long& total) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  unsigned long long x = val;
+  for (int o = 1; o < 64; o <<= 1) {
+    const unsigned long long y = __shfl_up(x, o);
+    if (lane >= o) x += y;
+  }
+  __syncthreads();
+  if (lane == 63) sm[w] = x;
+  __syncthreads();
+  unsigned long long base = 0, all = 0;
+  for (int k = 0; k < nw; ++k) {
+    const unsigned long long t = sm[k];
+    if (k < w) base += t;
+    all += t;
+  }
+  total = all;
+  return base + x - val;
+}
+
 // k-th page of the cluster with flat index cj (= u * Mcap + j); `prev` is its page k-1.
 __device__ inline int cluster_page(const View& v, int u, size_t cj, int k, int prev) {
   return k < kInlinePages ? v.cpg[cj * kInlinePages + k] : v.pnext[(size_t)u * v.Pcap + prev];

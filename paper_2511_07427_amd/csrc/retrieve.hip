@@ -62,6 +62,7 @@ struct SelectLds {
   const int* sw;           // [M] stored sizes, or null: they are read from the workspace
   unsigned char* region;
   int* hist;               // [4][256]
+  int* srt;                // [kCountMax] sizes in rank order; may alias sw, must not alias hist or list
   int* sm;                 // [64]
   int* misc;               // [8]
   int* list;
@@ -310,33 +311,56 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
     cut = 1; tsel = budget;
   }
 
-  // rank and gather offsets of every selected cluster, by counting the selected clusters that precede it
+  // rank of every selected cluster = number of selected clusters that precede it
   constexpr int PER = (kCountMax + NT - 1) / NT;
-  unsigned long long packed[PER];
-  int quads = 0;
+  int rk[PER], idw[PER], wt[PER];
 #pragma unroll
   for (int r = 0; r < PER; ++r) {
     const int p = tid + r * NT;
-    packed[r] = 0;
+    rk[r] = -1; idw[r] = 0; wt[r] = 0;
     if (p < cut) {
       const unsigned long long my = ck[p];
-      int rank = 0, t0 = 0, q0 = 0;
-#pragma unroll 4
-      for (int q = 0; q < cut; ++q) {
-        const unsigned long long o = ck[q];
-        const int w = cw[q];
-        if (o > my) { ++rank; t0 += w; q0 += (w + 3) >> 2; }
+      int rank = 0;
+      for (int qb = 0; qb < cut; qb += 8) {           // eight candidates per round trip to LDS
+        unsigned long long o[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) o[i] = ck[min(qb + i, cut - 1)];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) rank += (qb + i < cut && o[i] > my) ? 1 : 0;
       }
-      const int id = 0xFFFF - (int)(my & 0xFFFF);
-      v.sel_ids[cb + rank] = id;
-      packed[r] = ((unsigned long long)id << 48) | ((unsigned long long)t0 << 24) | (unsigned long long)q0;
-      quads += (cw[p] + 3) >> 2;
+      rk[r] = rank; idw[r] = 0xFFFF - (int)(my & 0xFFFF); wt[r] = cw[p];
     }
   }
   __syncthreads();
+  int* by_id = cw;                 // from here on indexed by rank
+  int* by_w = s.srt;
 #pragma unroll
   for (int r = 0; r < PER; ++r)
-    if (tid + r * NT < cut) ck[tid + r * NT] = packed[r];      // id, first gather offset, first list entry
+    if (rk[r] >= 0) {
+      by_id[rk[r]] = idw[r];
+      by_w[rk[r]] = wt[r];
+      v.sel_ids[cb + rk[r]] = idw[r];
+    }
+  __syncthreads();
+  // gather offsets in rank order: running sums of the sizes (low half) and of the list entries (high half)
+  unsigned long long loc[PER], run = 0;
+#pragma unroll
+  for (int k = 0; k < PER; ++k) {
+    const int r = tid * PER + k;
+    const unsigned w = r < cut ? (unsigned)by_w[r] : 0u;
+    loc[k] = (unsigned long long)w | ((unsigned long long)((w + 3) >> 2) << 32);
+    run += loc[k];
+  }
+  unsigned long long total64;
+  unsigned long long pre = block_excl_scan64(run, (unsigned long long*)s.sm, total64);
+#pragma unroll
+  for (int k = 0; k < PER; ++k) {
+    const int r = tid * PER + k;
+    if (r < cut)      // id, first gather offset, first list entry
+      ck[r] = ((unsigned long long)by_id[r] << 48) | ((pre & 0xFFFFFFu) << 24) | ((pre >> 32) & 0xFFFFFFu);
+    pre += loc[k];
+  }
+  const int quads = tid == 0 ? (int)(total64 >> 32) : 0;
   __syncthreads();
   // list entries: one work item per inline page of a selected cluster (every page but the last is full, so
   // its place in the list follows from its index); pages past the inline table are walked by the last item
@@ -344,7 +368,7 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
   int* poff = v.plist_off + (size_t)u * v.Lcap;
   for (int i = tid; i < cut * kInlinePages; i += NT) {
     const int p = i / kInlinePages, k = i % kInlinePages;
-    const int take = cw[p], npages = (take + kPageTokens - 1) / kPageTokens;
+    const int take = by_w[p], npages = (take + kPageTokens - 1) / kPageTokens;
     if (k >= npages) continue;
     const unsigned long long pk = ck[p];
     const int id = (int)(pk >> 48), t0 = (int)(pk >> 24) & 0xFFFFFF, q0 = (int)pk & 0xFFFFFF;
@@ -379,7 +403,7 @@ __global__ __launch_bounds__(1024) void select_kernel(View v, int budget) {
   __shared__ uint32_t skey[kMaxClusters];
   __shared__ __align__(16) unsigned char region[2 * kMaxClusters];
   __shared__ int hist[1024];
-  __shared__ int sm[64];
+  __shared__ __align__(16) int sm[64];
   __shared__ int misc[8];
   static_assert(2 * kMaxClusters >= kSelRegion, "candidate arrays must fit the id array");
   const int u = blockIdx.x, tid = threadIdx.x;
@@ -388,7 +412,8 @@ __global__ __launch_bounds__(1024) void select_kernel(View v, int budget) {
   while (Mpad < M) Mpad <<= 1;
   for (int i = tid; i < Mpad; i += 1024) skey[i] = i < M ? orderable(v.score[(size_t)u * v.Mcap + i]) : 0u;
   __syncthreads();
-  const SelectLds s{skey, nullptr, region, hist, sm, misc, nullptr, 0};
+  __shared__ int srt[kCountMax];
+  const SelectLds s{skey, nullptr, region, hist, srt, sm, misc, nullptr, 0};
   select_phase<1024>(v, u, M, budget, s);
 }
 
@@ -705,7 +730,7 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   __shared__ AppendSmem ap;
   __shared__ double am_v[16];
   __shared__ int am_i[16];
-  __shared__ int sm[64];
+  __shared__ __align__(16) int sm[64];
   __shared__ int misc[8];
   uint32_t* skey = (uint32_t*)smem;
   int* ssz = (int*)(smem + kKeys);
@@ -763,7 +788,7 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   __syncthreads();
 
   // ---- selection
-  const SelectLds sel{skey, ssz, smem + kKeys + kSizes, hist, sm, misc, list, kFusedList};
+  const SelectLds sel{skey, ssz, smem + kKeys + kSizes, hist, ssz, sm, misc, list, kFusedList};
   const int nlist = select_phase<NT>(v, u, M, budget, sel);
   __syncthreads();
 
