@@ -106,6 +106,7 @@ __device__ inline void append_commit(const View& v, int u, int j, int M, int N, 
         } else {
           v.cflag[cbase + j] = 1;
           v.cb[cbase + j] = 1;
+          v.flist[cbase + a.nflag] = j;
           v.nflag[u] = a.nflag + 1;
         }
       }

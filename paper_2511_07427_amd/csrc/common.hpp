@@ -47,6 +47,7 @@ struct View {
   int* cn;           // committed size n_j
   int* cb;           // buffered entries |Buf_j|
   int* cflag;        // f_j
+  int* flist;        // ids of the flagged clusters, first nflag[u] entries, in no particular order
   double* cM2;       // M2_j
   int* cpg;          // [.][8] first pages of the cluster (-1: none); later pages follow pnext
   int* ctail;        // last page

@@ -233,7 +233,7 @@ __device__ inline void children_stats(const View& v, int u, SplitSmem& s, const 
 
 // Splits cluster j of unit u (2-means; Algorithm 1 SplitCluster).  Whole block; all branches uniform.
 template <int DT, bool STAGED>
-__device__ __forceinline__ void split_cluster_impl(const View& v, int u, int j, int m, SplitSmem& s) {
+__device__ __forceinline__ void split_cluster_impl(const View& v, int u, int j, int pos, int m, SplitSmem& s) {
   constexpr int NT = kSplitThreads;
   const int tid = threadIdx.x, grp = tid >> 2, kb = tid & 3;
   const int wave_first = (tid & ~63) >> 2;                    // first member this wavefront would take in a pass
@@ -337,6 +337,7 @@ __device__ __forceinline__ void split_cluster_impl(const View& v, int u, int j, 
     if (tid == 0) {
       v.cn[cbase + j] = m; v.cb[cbase + j] = 0; v.cflag[cbase + j] = 0; v.cM2[cbase + j] = s.m2[0];
       s.nflag -= 1;
+      v.flist[cbase + pos] = v.flist[cbase + s.nflag];     // the last flagged id takes the freed place
       v.counters[(size_t)u * kCounters + 1] += 1;
     }
     __syncthreads();
@@ -418,13 +419,14 @@ __device__ __forceinline__ void split_cluster_impl(const View& v, int u, int j, 
     s.a_top = top - from_free + s.nchain;
     s.a_bump = bump + (need - from_free);
     s.nflag -= 1;
+    v.flist[cbase + pos] = v.flist[cbase + s.nflag];
     v.counters[(size_t)u * kCounters + 0] += 1;
   }
   __syncthreads();
 }
 
 template <int DT>
-__device__ __forceinline__ void split_cluster(const View& v, int u, int j, SplitSmem& s) {
+__device__ __forceinline__ void split_cluster(const View& v, int u, int j, int pos, SplitSmem& s) {
   const int tid = threadIdx.x;
   const size_t cbase = (size_t)u * v.Mcap;
   const int m = v.cn[cbase + j] + v.cb[cbase + j];
@@ -441,8 +443,8 @@ __device__ __forceinline__ void split_cluster(const View& v, int u, int j, Split
     s.nchain = npg;
   }
   __syncthreads();
-  if (m <= (DT == DYNAKV_F32 ? 64 : 128)) split_cluster_impl<DT, true>(v, u, j, m, s);
-  else split_cluster_impl<DT, false>(v, u, j, m, s);
+  if (m <= (DT == DYNAKV_F32 ? 64 : 128)) split_cluster_impl<DT, true>(v, u, j, pos, m, s);
+  else split_cluster_impl<DT, false>(v, u, j, pos, m, s);
 }
 
 template <int DT>
@@ -457,36 +459,40 @@ __global__ __launch_bounds__(kSplitThreads) void split_kernel(View v) {
   const int M0 = v.M[u];
   if (tid == 0) { s.M = M0; s.nflag = v.nflag[u]; s.a_top = v.free_top[u]; s.a_bump = v.bump[u]; }
   // One loop, one call site: first the delayed splits (flagged clusters that the last retrieval selected, in
-  // ascending id), then, once, the forced split of the fullest buffer if the buffers hold B_max entries.
+  // ascending id), then, once, the forced split of the fullest buffer if the buffers hold B_max entries.  Both
+  // searches walk the list of flagged clusters, which holds a handful of ids.
+  __syncthreads();
   int cursor = 0;
   bool forced_done = false;
   while (true) {
-    int j = -1;
+    int j = -1, pos = -1;
+    const int nf = s.nflag;
     if (!forced_done) {
       if (tid == 0) s_min = 0x7FFFFFFF;
       __syncthreads();
-      for (int c = cursor + tid; c < M0; c += NT)
-        if (v.cflag[cbase + c] && (v.Bmax == 0 || v.in_req[cbase + c])) { atomicMin(&s_min, c); break; }
+      for (int i = tid; i < nf; i += NT) {
+        const int c = v.flist[cbase + i];
+        if (c >= cursor && c < M0 && (v.Bmax == 0 || v.in_req[cbase + c])) atomicMin(&s_min, c * kMaxClusters + i);
+      }
       __syncthreads();
-      j = s_min == 0x7FFFFFFF ? -1 : s_min;
+      if (s_min != 0x7FFFFFFF) { j = s_min / kMaxClusters; pos = s_min % kMaxClusters; }
       __syncthreads();
       if (j >= 0) cursor = j + 1;
     }
     if (j < 0) {
       if (forced_done) break;
       forced_done = true;
-      if (!(v.Bmax > 0 && s.nflag > 0)) break;
-      const int M = s.M;
+      if (!(v.Bmax > 0 && nf > 0)) break;
       if (tid == 0) s_tot = 0;
       __syncthreads();
       double bv = -1.0; int bi = -1;
       long long tot = 0;
-      for (int c = tid; c < M; c += NT)
-        if (v.cflag[cbase + c]) {
-          const int b = v.cb[cbase + c];
-          tot += b;
-          if ((double)b > bv) { bv = (double)b; bi = c; }
-        }
+      for (int i = tid; i < nf; i += NT) {
+        const int c = v.flist[cbase + i];
+        const int b = v.cb[cbase + c];
+        tot += b;
+        if ((double)b > bv || ((double)b == bv && c * kMaxClusters + i < bi)) { bv = (double)b; bi = c * kMaxClusters + i; }
+      }
       if (tot) atomicAdd((unsigned long long*)&s_tot, (unsigned long long)tot);
       block_argmax(bv, bi, s.sv, s.si);
       const int arg = s.si[0];
@@ -494,9 +500,9 @@ __global__ __launch_bounds__(kSplitThreads) void split_kernel(View v) {
       __syncthreads();
       if (!(arg >= 0 && total >= v.Bmax)) break;
       if (tid == 0) v.counters[(size_t)u * kCounters + 2] += 1;
-      j = arg;
+      j = arg / kMaxClusters; pos = arg % kMaxClusters;
     }
-    split_cluster<DT>(v, u, j, s);
+    split_cluster<DT>(v, u, j, pos, s);
     __syncthreads();
     if (forced_done) break;
   }
