@@ -447,17 +447,451 @@ __device__ __forceinline__ void split_cluster(const View& v, int u, int j, int p
   else split_cluster_impl<DT, false>(v, u, j, pos, m, s);
 }
 
+// ---- small clusters: one wavefront per split ---------------------------------------------------------
+// Most clusters that get split hold a few dozen entries at most.  Such a split keeps one wavefront busy, so
+// up to four flagged clusters of a unit are split side by side, one per wavefront, with no workgroup barrier
+// inside the 2-means: lane = member for distances and assignments, lane = coordinate (two each) for sums over
+// members.  The arithmetic is the one of split_cluster_impl, term for term.  What depends on the order of the
+// splits (new cluster ids, page allocation) is done by one thread between the two wavefront phases.
+constexpr int kWaveSplits = kSplitThreads / 64;
+constexpr int kWaveStage = 64 * kStageRow16 * 2;                 // 64 rows of a 16-bit type, 32 of float32
+static_assert(32 * kStageRow32 * 4 <= kWaveStage, "float32 rows must fit");
+constexpr int kWavePages = 64 / kPageTokens;                     // pages of the largest such cluster
+
+struct WaveCtx {
+  alignas(16) unsigned char stage[kWaveStage];
+  double cA[kHeadDim], cB[kHeadDim];
+  float rA[kHeadDim], rB[kHeadDim];
+  double dist[64];
+  double m2[2];
+  unsigned char side[64], perm[64];
+  int chain[kWavePages], newpg[kWavePages + 2];
+  int j, m, ok, nS, idM, fresh_from;     // fresh_from: newpg[k] with k >= fresh_from were never used before
+};
+
+__device__ __forceinline__ void wave_sync() {   // LDS written by some lanes of this wavefront, read by others
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_wave_barrier();
+  asm volatile("" ::: "memory");
+}
+
+template <int DT>
+__device__ __forceinline__ float wkey(const WaveCtx& c, int i, int d) {
+  if constexpr (DT == DYNAKV_F32) return ((const float*)c.stage)[i * kStageRow32 + d];
+  else {
+    const uint16_t h = ((const uint16_t*)c.stage)[i * kStageRow16 + d];
+    return DT == DYNAKV_F16 ? f16_to_float(h) : bf16_to_float(h);
+  }
+}
+template <int DT>
+__device__ __forceinline__ void wkey8(const WaveCtx& c, int i, int d8, float (&x)[8]) {
+  if constexpr (DT == DYNAKV_F32) {
+    const f4* p = (const f4*)((const float*)c.stage + i * kStageRow32 + d8 * 8);
+    const f4 a = p[0], b = p[1];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { x[e] = a[e]; x[4 + e] = b[e]; }
+  } else {
+    const uint4 w = *(const uint4*)((const uint16_t*)c.stage + i * kStageRow16 + d8 * 8);
+    const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const uint16_t h = (uint16_t)(ww[e >> 1] >> ((e & 1) * 16));
+      x[e] = DT == DYNAKV_F16 ? f16_to_float(h) : bf16_to_float(h);
+    }
+  }
+}
+
+// Key access in the form quad_sqdist expects.
+template <int DT>
+struct WaveKeys {
+  const WaveCtx& c;
+  __device__ void get8(int i, int d8, float (&x)[8]) const { wkey8<DT>(c, i, d8, x); }
+};
+
+// Wavefront arg-max of (value, index), index < 0 = none, equal values to the lowest index; all lanes get it.
+__device__ __forceinline__ void wave_argmax(double& val, int& idx) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const double ov = __shfl_xor(val, o);
+    const int oi = __shfl_xor(idx, o);
+    if (oi >= 0 && (idx < 0 || ov > val || (ov == val && oi < idx))) { val = ov; idx = oi; }
+  }
+}
+
+// Sums over the members at(q), q = q0..q1-1, of coordinates d and d + 64, each added one by one in that order.
+// With SIDES the members of side 0 go to (a0, a1) and those of side 1 to (b0, b1); otherwise all go to (a0, a1).
+// A member that does not belong to a sum adds +0.0, which leaves a float64 sum unchanged.  Eight loads per
+// round trip to LDS.
+template <int DT, bool SIDES, class At>
+__device__ __forceinline__ void wave_sums(const WaveCtx& c, int q0, int q1, int d, At&& at, double& a0, double& a1,
+                                          double& b0, double& b1) {
+  a0 = 0.0; a1 = 0.0; b0 = 0.0; b1 = 0.0;
+  for (int r0 = q0; r0 < q1; r0 += 8) {
+    float x0[8], x1[8];
+    bool sa[8], sb[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int i = at(min(r0 + k, q1 - 1));
+      const bool in = r0 + k < q1;
+      x0[k] = wkey<DT>(c, i, d);
+      x1[k] = wkey<DT>(c, i, d + 64);
+      const unsigned char sd = SIDES ? c.side[i] : (unsigned char)0;
+      sa[k] = in && sd == 0;
+      sb[k] = in && sd == 1;
+    }
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      a0 += (double)(sa[k] ? x0[k] : 0.f);
+      a1 += (double)(sa[k] ? x1[k] : 0.f);
+      if (SIDES) {
+        b0 += (double)(sb[k] ? x0[k] : 0.f);
+        b1 += (double)(sb[k] ? x1[k] : 0.f);
+      }
+    }
+  }
+}
+
+// First phase, one wavefront: stage the keys, 2-means, stable partition.  Sets c.ok, c.nS, c.perm.
+template <int DT>
+__device__ inline void wave_split_decide(const View& v, int u, WaveCtx& c) {
+  const int lane = threadIdx.x & 63;
+  const size_t cbase = (size_t)u * v.Mcap;
+  constexpr int kEs = DT == DYNAKV_F32 ? 4 : 2;
+  constexpr int kChunks = kHeadDim * kEs / 16;
+  constexpr int kRowBytes = (DT == DYNAKV_F32 ? kStageRow32 : kStageRow16) * kEs;
+  const char* const pool = v.pages + (size_t)u * v.Pcap * ((size_t)kPageElems * kEs);
+  const int m = c.m, j = c.j;
+  const int npg = (m + kPageTokens - 1) / kPageTokens;
+  if (lane < npg) c.chain[lane] = v.cpg[(cbase + j) * kInlinePages + lane];
+  wave_sync();
+  for (int t0 = 0; t0 < m * kChunks; t0 += 4 * 64) {       // four loads in flight per lane
+    uint4 w[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int t = min(t0 + k * 64 + lane, m * kChunks - 1);
+      const int i = t / kChunks, ch = t % kChunks;
+      const size_t off = (size_t)(DT == DYNAKV_F32 ? k_index32(i & 15, 4 * ch) : k_index16(i & 15, 8 * ch)) * kEs;
+      w[k] = *(const uint4*)(pool + (size_t)c.chain[i >> 4] * (kPageElems * kEs) + off);
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int t = t0 + k * 64 + lane;
+      if (t < m * kChunks) *(uint4*)(c.stage + (size_t)(t / kChunks) * kRowBytes + (t % kChunks) * 16) = w[k];
+    }
+  }
+  wave_sync();
+  const WaveKeys<DT> ks{c};
+  const int grp = lane >> 2, kb = lane & 3;      // four lanes per member in the distance passes
+  auto ident = [](int q) { return q; };
+  bool can = m >= 2;
+  if (can) {
+    // seeds: A = member farthest from the mean of all members, B = member farthest from A
+    double s0, s1, u0, u1, dummy;
+    wave_sums<DT, false>(c, 0, m, lane, ident, s0, s1, u0, u1);
+    c.cA[lane] = s0 / (double)m; c.cA[lane + 64] = s1 / (double)m;
+    wave_sync();
+    double bv = -1.0;
+    int a = -1;
+    for (int base = 0; base < m; base += 16) {
+      const int i = base + grp;
+      double t;
+      quad_sqdist<WaveKeys<DT>, double>(ks, min(i, m - 1), kb, c.cA, nullptr, t, dummy);
+      if (kb == 0 && i < m && (a < 0 || t > bv)) { bv = t; a = i; }
+    }
+    wave_argmax(bv, a);
+    c.cB[lane] = (double)wkey<DT>(c, a, lane); c.cB[lane + 64] = (double)wkey<DT>(c, a, lane + 64);
+    wave_sync();
+    bv = -1.0;
+    int b = -1;
+    for (int base = 0; base < m; base += 16) {
+      const int i = base + grp;
+      double t;
+      quad_sqdist<WaveKeys<DT>, double>(ks, min(i, m - 1), kb, c.cB, nullptr, t, dummy);
+      if (kb == 0 && i < m && (b < 0 || t > bv)) { bv = t; b = i; }
+    }
+    wave_argmax(bv, b);
+    can = bv > 0.0;                          // false: all members identical
+    if (can) {
+      c.cA[lane] = c.cB[lane]; c.cA[lane + 64] = c.cB[lane + 64];
+      c.cB[lane] = (double)wkey<DT>(c, b, lane); c.cB[lane + 64] = (double)wkey<DT>(c, b, lane + 64);
+      c.side[lane] = 2;
+      wave_sync();
+      for (int it = 0; it < 16; ++it) {
+        bool moved = false;
+        int nA = 0;
+        for (int base = 0; base < m; base += 16) {
+          const int i = base + grp;
+          double dA, dB;
+          quad_sqdist<WaveKeys<DT>, double>(ks, min(i, m - 1), kb, c.cA, c.cB, dA, dB);
+          const bool own = kb == 0 && i < m;
+          const unsigned char ns = dA <= dB ? 0 : 1;     // tie -> side A
+          moved = moved || __ballot(own && ns != c.side[min(i, 63)]) != 0;
+          nA += __popcll(__ballot(own && ns == 0));
+          if (own) c.side[i] = ns;
+        }
+        wave_sync();
+        if (!moved) break;
+        if (nA == 0 || nA == m) { can = false; break; }
+        double a0, a1, b0, b1;
+        wave_sums<DT, true>(c, 0, m, lane, ident, a0, a1, b0, b1);
+        c.cA[lane] = a0 / (double)nA; c.cA[lane + 64] = a1 / (double)nA;
+        c.cB[lane] = b0 / (double)(m - nA); c.cB[lane + 64] = b1 / (double)(m - nA);
+        wave_sync();
+      }
+    }
+  }
+  int nS = m;
+  if (can) {        // stable partition: the child that holds the earliest entry comes first and keeps the id
+    const unsigned char keep = c.side[0];
+    const unsigned long long mask = __ballot(lane < m && c.side[lane] == keep);
+    const int before = __popcll(mask & ((1ull << lane) - 1ull));
+    nS = __popcll(mask);
+    if (lane < m) c.perm[(mask >> lane) & 1ull ? before : nS + lane - before] = (unsigned char)lane;
+  } else if (lane < m) {
+    c.perm[lane] = (unsigned char)lane;
+  }
+  if (lane == 0) { c.ok = can ? 1 : 0; c.nS = nS; }
+  wave_sync();
+}
+
+// Second phase, one wavefront: children's pages, exact statistics and records.  With c.ok == 0 the cluster is
+// only unflagged, with exact statistics.
+template <int DT>
+__device__ inline void wave_split_commit(const View& v, int u, WaveCtx& c) {
+  const int lane = threadIdx.x & 63;
+  const size_t cbase = (size_t)u * v.Mcap;
+  constexpr int kEs = DT == DYNAKV_F32 ? 4 : 2;
+  constexpr int kChunks = kHeadDim * kEs / 16;
+  constexpr int kRowBytes = (DT == DYNAKV_F32 ? kStageRow32 : kStageRow16) * kEs;
+  constexpr size_t kPageBytes = (size_t)kPageElems * kEs;
+  char* const pool = v.pages + (size_t)u * v.Pcap * kPageBytes;
+  const int m = c.m, j = c.j, nS = c.nS, nM = m - nS, idM = c.ok ? c.idM : -1;
+  const int pS = (nS + kPageTokens - 1) / kPageTokens, pM = (nM + kPageTokens - 1) / kPageTokens, need = pS + pM;
+  if (c.ok) {
+    if (lane < need) v.pnext[(size_t)u * v.Pcap + c.newpg[lane]] = (lane == pS - 1 || lane == need - 1) ? -1 : c.newpg[lane + 1];
+    constexpr int n16 = (int)(kPageBytes / 16);
+    for (int k = c.fresh_from; k < need; ++k)          // pages never used before are zeroed first
+      for (int t = lane; t < n16; t += 64) ((uint4*)(pool + (size_t)c.newpg[k] * kPageBytes))[t] = uint4{0, 0, 0, 0};
+    for (int t = lane; t < m * kChunks; t += 64) {
+      const int q = t / kChunks, ch = t % kChunks;
+      const int i = c.perm[q];
+      const int r = q < nS ? q : q - nS;
+      const int dpage = c.newpg[(q < nS ? 0 : pS) + (r >> 4)];
+      const size_t off = (size_t)(DT == DYNAKV_F32 ? k_index32(r & 15, 4 * ch) : k_index16(r & 15, 8 * ch)) * kEs;
+      *(uint4*)(pool + (size_t)dpage * kPageBytes + off) = *(const uint4*)(c.stage + (size_t)i * kRowBytes + ch * 16);
+    }
+    // values element by element (their page layout interleaves four tokens), eight loads in flight per lane
+    for (int t0 = 0; t0 < m * kHeadDim; t0 += 8 * 64) {
+      uint32_t w[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const int t = min(t0 + k * 64 + lane, m * kHeadDim - 1);
+        const int i = c.perm[t >> 7];
+        const char* src = pool + (size_t)c.chain[i >> 4] * kPageBytes;
+        const int e = v_index(DT, i & 15, t & 127);
+        w[k] = DT == DYNAKV_F32 ? ((const uint32_t*)src)[e] : (uint32_t)((const uint16_t*)src)[e];
+      }
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const int t = t0 + k * 64 + lane;
+        if (t < m * kHeadDim) {
+          const int q = t >> 7;
+          const int r = q < nS ? q : q - nS;
+          char* dst = pool + (size_t)c.newpg[(q < nS ? 0 : pS) + (r >> 4)] * kPageBytes;
+          const int e = v_index(DT, r & 15, t & 127);
+          if (DT == DYNAKV_F32) ((uint32_t*)dst)[e] = w[k];
+          else ((uint16_t*)dst)[e] = (uint16_t)w[k];
+        }
+      }
+    }
+    if (lane < m) {
+      const int i = c.perm[lane];
+      const int r = lane < nS ? lane : lane - nS;
+      const int dpage = c.newpg[(lane < nS ? 0 : pS) + (r >> 4)];
+      v.ppos[((size_t)u * v.Pcap + dpage) * kPageTokens + (r & 15)] =
+          v.ppos[((size_t)u * v.Pcap + c.chain[i >> 4]) * kPageTokens + (i & 15)];
+    }
+  }
+  // exact statistics: float32 means, then M2 about those means, members in their new order
+  auto at = [&](int q) { return (int)c.perm[q]; };
+  double s0, s1, u0, u1;
+  wave_sums<DT, false>(c, 0, nS, lane, at, s0, s1, u0, u1);
+  c.rA[lane] = nS > 0 ? (float)(s0 / (double)nS) : 0.f;
+  c.rA[lane + 64] = nS > 0 ? (float)(s1 / (double)nS) : 0.f;
+  float* R = unit_R(v, u);
+  R[r_index(j, lane)] = c.rA[lane]; R[r_index(j, lane + 64)] = c.rA[lane + 64];
+  if (idM >= 0) {
+    wave_sums<DT, false>(c, nS, m, lane, at, s0, s1, u0, u1);
+    c.rB[lane] = nM > 0 ? (float)(s0 / (double)nM) : 0.f;
+    c.rB[lane + 64] = nM > 0 ? (float)(s1 / (double)nM) : 0.f;
+    R[r_index(idM, lane)] = c.rB[lane]; R[r_index(idM, lane + 64)] = c.rB[lane + 64];
+  }
+  wave_sync();
+  {
+    const WaveKeys<DT> ks{c};
+    const int grp = lane >> 2, kb = lane & 3;
+    for (int base = 0; base < m; base += 16) {
+      const int q = base + grp, qc = min(q, m - 1);
+      double dv, dummy;
+      quad_sqdist<WaveKeys<DT>, float>(ks, c.perm[qc], kb, qc < nS ? c.rA : c.rB, nullptr, dv, dummy);
+      if (kb == 0 && q < m) c.dist[q] = dv;
+    }
+  }
+  wave_sync();
+  if (lane < 2) {
+    const int q0 = lane ? nS : 0, q1 = lane ? m : nS;
+    double acc = 0.0;
+    for (int r0 = q0; r0 < q1; r0 += 8) {
+      double x[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) x[k] = r0 + k < q1 ? c.dist[r0 + k] : 0.0;
+      asm volatile("" ::: "memory");
+#pragma unroll
+      for (int k = 0; k < 8; ++k) acc += x[k];
+    }
+    c.m2[lane] = acc;
+  }
+  wave_sync();
+  if (c.ok && lane < kInlinePages) {
+    v.cpg[(cbase + j) * kInlinePages + lane] = lane < pS ? c.newpg[lane] : -1;
+    v.cpg[(cbase + idM) * kInlinePages + lane] = lane < pM ? c.newpg[pS + lane] : -1;
+  }
+  if (lane == 0) {
+    v.cn[cbase + j] = nS; v.cb[cbase + j] = 0; v.cflag[cbase + j] = 0; v.cM2[cbase + j] = c.m2[0];
+    if (c.ok) {
+      v.ctail[cbase + j] = c.newpg[pS - 1];
+      v.cn[cbase + idM] = nM; v.cb[cbase + idM] = 0; v.cflag[cbase + idM] = 0; v.cM2[cbase + idM] = c.m2[1];
+      v.ctail[cbase + idM] = c.newpg[pS + pM - 1];
+      v.in_req[cbase + idM] = 0;
+    }
+  }
+}
+
+// Plan of one unit's splits, made from the list of its flagged clusters (at most 64 of them).
+struct SplitPlan {
+  int id[64], req[64], cb[64], m[64];   // the flagged clusters
+  int cand[64];                          // positions in the list, in the order of the splits
+  int n_cand, forced, fast;
+  int M, top, bump;                      // the unit's counters while the plan is carried out
+};
+
 template <int DT>
 __global__ __launch_bounds__(kSplitThreads) void split_kernel(View v) {
   constexpr int NT = kSplitThreads;
-  __shared__ SplitSmem s;
+  constexpr size_t kRaw = sizeof(SplitSmem) > kWaveSplits * sizeof(WaveCtx) ? sizeof(SplitSmem) : kWaveSplits * sizeof(WaveCtx);
+  __shared__ __align__(16) unsigned char raw[kRaw];     // either the workgroup-wide split or four wavefront splits
+  __shared__ SplitPlan pl;
   __shared__ int s_min;
   __shared__ long long s_tot;
+  SplitSmem& s = *(SplitSmem*)raw;
+  WaveCtx* const wc = (WaveCtx*)raw;
   const int u = blockIdx.x, tid = threadIdx.x;
-  if (v.nflag[u] == 0) return;
+  const int nf0 = v.nflag[u];
+  if (nf0 == 0) return;
   const size_t cbase = (size_t)u * v.Mcap;
   const int M0 = v.M[u];
-  if (tid == 0) { s.M = M0; s.nflag = v.nflag[u]; s.a_top = v.free_top[u]; s.a_bump = v.bump[u]; }
+
+  // ---- plan: which clusters are split, in which order
+  if (nf0 <= 64) {
+    if (tid < nf0) {
+      const int c = v.flist[cbase + tid];
+      const int b = v.cb[cbase + c];
+      pl.id[tid] = c; pl.req[tid] = v.in_req[cbase + c]; pl.cb[tid] = b; pl.m[tid] = v.cn[cbase + c] + b;
+    }
+    if (tid == 64) { pl.M = M0; pl.top = v.free_top[u]; pl.bump = v.bump[u]; }
+    __syncthreads();
+    if (tid == 0) {
+      // delayed splits: flagged clusters of the active set (all flagged ones if nothing is buffered), ascending id
+      int nc = 0;
+      for (int last = -1;;) {
+        int best = -1;
+        for (int i = 0; i < nf0; ++i)
+          if (pl.id[i] > last && (v.Bmax == 0 || pl.req[i]) && (best < 0 || pl.id[i] < pl.id[best])) best = i;
+        if (best < 0) break;
+        pl.cand[nc++] = best;
+        last = pl.id[best];
+        pl.req[best] = 2;                  // taken
+      }
+      // then, if the remaining buffers hold B_max entries, the fullest of them (lowest id among equals)
+      int forced = 0;
+      if (v.Bmax > 0) {
+        long long total = 0;
+        int best = -1;
+        for (int i = 0; i < nf0; ++i)
+          if (pl.req[i] != 2) {
+            total += pl.cb[i];
+            if (best < 0 || pl.cb[i] > pl.cb[best] || (pl.cb[i] == pl.cb[best] && pl.id[i] < pl.id[best])) best = i;
+          }
+        if (best >= 0 && total >= v.Bmax) { pl.cand[nc++] = best; forced = 1; }
+      }
+      // the wavefront path takes the plan if every cluster is small and no capacity limit can be hit
+      constexpr int kSmall = DT == DYNAKV_F32 ? 32 : 64;
+      long long pages = 0;
+      bool small = true;
+      for (int k = 0; k < nc; ++k) {
+        const int mm = pl.m[pl.cand[k]];
+        small = small && mm <= kSmall;
+        pages += (mm + kPageTokens - 1) / kPageTokens + 1;
+      }
+      pl.n_cand = nc; pl.forced = forced;
+      pl.fast = small && pl.M + nc <= v.Mcap && pages <= (long long)pl.top + (v.Pcap - pl.bump);
+    }
+    __syncthreads();
+    if (pl.fast) {
+      const int wave = tid >> 6, lane = tid & 63;
+      const int nc = pl.n_cand;
+      for (int base = 0; base < nc; base += kWaveSplits) {
+        const bool mine = base + wave < nc;
+        WaveCtx& c = wc[wave];
+        if (mine) {
+          if (lane == 0) { c.j = pl.id[pl.cand[base + wave]]; c.m = pl.m[pl.cand[base + wave]]; }
+          wave_sync();
+          wave_split_decide<DT>(v, u, c);
+        }
+        __syncthreads();
+        if (tid == 0) {                    // ids and pages, in the order of the splits
+          for (int w = 0; w < kWaveSplits && base + w < nc; ++w) {
+            WaveCtx& cw = wc[w];
+            if (!cw.ok) continue;
+            cw.idM = pl.M++;
+            const int need = (cw.nS + kPageTokens - 1) / kPageTokens + (cw.m - cw.nS + kPageTokens - 1) / kPageTokens;
+            const int from_free = min(need, pl.top);
+            for (int k = 0; k < need; ++k)
+              cw.newpg[k] = k < from_free ? v.freelist[(size_t)u * v.Pcap + pl.top - 1 - k] : pl.bump + (k - from_free);
+            cw.fresh_from = from_free;
+            pl.top -= from_free;
+            pl.bump += need - from_free;
+          }
+        }
+        __syncthreads();
+        if (mine) wave_split_commit<DT>(v, u, c);
+        __syncthreads();
+        if (tid == 0) {                    // the parents' pages are recycled only now
+          for (int w = 0; w < kWaveSplits && base + w < nc; ++w) {
+            const WaveCtx& cw = wc[w];
+            v.counters[(size_t)u * kCounters + (cw.ok ? 0 : 1)] += 1;
+            if (!cw.ok) continue;
+            const int npg = (cw.m + kPageTokens - 1) / kPageTokens;
+            for (int k = 0; k < npg; ++k) v.freelist[(size_t)u * v.Pcap + pl.top++] = cw.chain[k];
+          }
+        }
+        __syncthreads();
+      }
+      if (tid == 0) {
+        int n = 0;
+        for (int k = 0; k < nc; ++k) pl.id[pl.cand[k]] = -1;
+        for (int i = 0; i < nf0; ++i)
+          if (pl.id[i] >= 0) v.flist[cbase + n++] = pl.id[i];
+        v.nflag[u] = n; v.M[u] = pl.M; v.free_top[u] = pl.top; v.bump[u] = pl.bump;
+        if (pl.forced) v.counters[(size_t)u * kCounters + 2] += 1;
+      }
+      return;
+    }
+  }
+
+  // ---- general path: one split at a time by the whole workgroup
+  if (tid == 0) { s.M = M0; s.nflag = nf0; s.a_top = v.free_top[u]; s.a_bump = v.bump[u]; }
   // One loop, one call site: first the delayed splits (flagged clusters that the last retrieval selected, in
   // ascending id), then, once, the forced split of the fullest buffer if the buffers hold B_max entries.  Both
   // searches walk the list of flagged clusters, which holds a handful of ids.
