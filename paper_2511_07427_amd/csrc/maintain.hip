@@ -552,19 +552,16 @@ __device__ __forceinline__ void wave_sums(const WaveCtx& c, int q0, int q1, int 
   }
 }
 
-// First phase, one wavefront: stage the keys, 2-means, stable partition.  Sets c.ok, c.nS, c.perm.
+// First phase, one wavefront: stage the keys (c.chain lists their pages), 2-means, stable partition.  Sets
+// c.ok, c.nS, c.perm.
 template <int DT>
 __device__ inline void wave_split_decide(const View& v, int u, WaveCtx& c) {
   const int lane = threadIdx.x & 63;
-  const size_t cbase = (size_t)u * v.Mcap;
   constexpr int kEs = DT == DYNAKV_F32 ? 4 : 2;
   constexpr int kChunks = kHeadDim * kEs / 16;
   constexpr int kRowBytes = (DT == DYNAKV_F32 ? kStageRow32 : kStageRow16) * kEs;
   const char* const pool = v.pages + (size_t)u * v.Pcap * ((size_t)kPageElems * kEs);
-  const int m = c.m, j = c.j;
-  const int npg = (m + kPageTokens - 1) / kPageTokens;
-  if (lane < npg) c.chain[lane] = v.cpg[(cbase + j) * kInlinePages + lane];
-  wave_sync();
+  const int m = c.m;
   for (int t0 = 0; t0 < m * kChunks; t0 += 4 * 64) {       // four loads in flight per lane
     uint4 w[4];
 #pragma unroll
@@ -769,11 +766,14 @@ __device__ inline void wave_split_commit(const View& v, int u, WaveCtx& c) {
 }
 
 // Plan of one unit's splits, made from the list of its flagged clusters (at most 64 of them).
+constexpr int kFreeAhead = 24;
 struct SplitPlan {
   int id[64], req[64], cb[64], m[64];   // the flagged clusters
+  int pg[64][kWavePages];               // their first pages
   int cand[64];                          // positions in the list, in the order of the splits
   int n_cand, forced, fast;
   int M, top, bump;                      // the unit's counters while the plan is carried out
+  int fl[kFreeAhead], fl_base;           // top of the free-page stack, read ahead: fl[k] = entry fl_base - 1 - k
 };
 
 template <int DT>
@@ -797,9 +797,15 @@ __global__ __launch_bounds__(kSplitThreads) void split_kernel(View v) {
     if (tid < nf0) {
       const int c = v.flist[cbase + tid];
       const int b = v.cb[cbase + c];
+      const int4 pg = *(const int4*)&v.cpg[(cbase + c) * kInlinePages];
       pl.id[tid] = c; pl.req[tid] = v.in_req[cbase + c]; pl.cb[tid] = b; pl.m[tid] = v.cn[cbase + c] + b;
+      pl.pg[tid][0] = pg.x; pl.pg[tid][1] = pg.y; pl.pg[tid][2] = pg.z; pl.pg[tid][3] = pg.w;
     }
-    if (tid == 64) { pl.M = M0; pl.top = v.free_top[u]; pl.bump = v.bump[u]; }
+    if (tid >= 64 && tid < 64 + kFreeAhead) {       // everything the page allocation will need, in the same round trips
+      const int top = v.free_top[u], k = tid - 64;
+      if (k < top) pl.fl[k] = v.freelist[(size_t)u * v.Pcap + top - 1 - k];
+      if (k == 0) { pl.M = M0; pl.top = top; pl.bump = v.bump[u]; pl.fl_base = top; }
+    }
     __syncthreads();
     if (tid == 0) {
       // delayed splits: flagged clusters of the active set (all flagged ones if nothing is buffered), ascending id
@@ -845,7 +851,9 @@ __global__ __launch_bounds__(kSplitThreads) void split_kernel(View v) {
         const bool mine = base + wave < nc;
         WaveCtx& c = wc[wave];
         if (mine) {
-          if (lane == 0) { c.j = pl.id[pl.cand[base + wave]]; c.m = pl.m[pl.cand[base + wave]]; }
+          const int at = pl.cand[base + wave];
+          if (lane == 0) { c.j = pl.id[at]; c.m = pl.m[at]; }
+          if (lane < kWavePages) c.chain[lane] = pl.pg[at][lane];
           wave_sync();
           wave_split_decide<DT>(v, u, c);
         }
@@ -857,8 +865,12 @@ __global__ __launch_bounds__(kSplitThreads) void split_kernel(View v) {
             cw.idM = pl.M++;
             const int need = (cw.nS + kPageTokens - 1) / kPageTokens + (cw.m - cw.nS + kPageTokens - 1) / kPageTokens;
             const int from_free = min(need, pl.top);
-            for (int k = 0; k < need; ++k)
-              cw.newpg[k] = k < from_free ? v.freelist[(size_t)u * v.Pcap + pl.top - 1 - k] : pl.bump + (k - from_free);
+            for (int k = 0; k < need; ++k) {
+              const int ahead = pl.fl_base - (pl.top - k);       // pl.fl holds the stack as it was at fl_base
+              cw.newpg[k] = k >= from_free ? pl.bump + (k - from_free)
+                            : (ahead >= 0 && ahead < kFreeAhead) ? pl.fl[ahead]
+                                                                  : v.freelist[(size_t)u * v.Pcap + pl.top - 1 - k];
+            }
             cw.fresh_from = from_free;
             pl.top -= from_free;
             pl.bump += need - from_free;
@@ -874,6 +886,7 @@ __global__ __launch_bounds__(kSplitThreads) void split_kernel(View v) {
             if (!cw.ok) continue;
             const int npg = (cw.m + kPageTokens - 1) / kPageTokens;
             for (int k = 0; k < npg; ++k) v.freelist[(size_t)u * v.Pcap + pl.top++] = cw.chain[k];
+            pl.fl_base = -(1 << 30);         // the stack has changed: what was read ahead no longer applies
           }
         }
         __syncthreads();
