@@ -15,32 +15,56 @@ struct AppendSmem {
   int ok, commit, page, slot, fresh;
 };
 
-// Cluster j (of M) receives token N of unit u.  Called by all NT >= 256 threads of the unit's workgroup.
-// The record of the cluster and the unit's allocator state are fetched by separate lanes at once, the sum of
-// UpdateVar is formed from 16 block sums computed side by side, and one thread then takes the decisions.
+// What one thread fetches for an append: thread d < 128 coordinate d of the centroid, threads 128..136 one field
+// each of the cluster's record or of the unit's allocator state.  All of it in one round trip to memory.
+struct AppendFetch {
+  double x;
+  int i, k;
+};
+__device__ inline AppendFetch append_fetch(const View& v, int u, int j) {
+  const int tid = threadIdx.x;
+  const size_t cbase = (size_t)u * v.Mcap;
+  AppendFetch f{0.0, 0, 0};
+  if (tid < kHeadDim) f.x = (double)unit_R(v, u)[r_index(j, tid)];
+  switch (tid - kHeadDim) {
+    case 0: f.i = v.cn[cbase + j]; break;
+    case 1: f.i = v.cb[cbase + j]; break;
+    case 2: f.i = v.ctail[cbase + j]; break;
+    case 3: f.i = v.cflag[cbase + j]; break;
+    case 4: f.x = v.cM2[cbase + j]; break;
+    case 5: f.x = v.tau[u]; break;
+    case 6: f.i = v.nflag[u]; break;
+    case 7: f.i = v.bump[u]; break;
+    case 8: {
+      f.i = v.free_top[u];
+      f.k = f.i > 0 ? v.freelist[(size_t)u * v.Pcap + f.i - 1] : -1;
+      break;
+    }
+    default: break;
+  }
+  return f;
+}
+
+// Cluster j (of M) receives token N of unit u.  Called by all NT >= 256 threads of the unit's workgroup with
+// what append_fetch returned to each of them (the caller may have issued it long before).  The sum of UpdateVar
+// is formed from 16 block sums computed side by side, and one thread then takes the decisions.
 template <int NT>
 __device__ inline void append_commit(const View& v, int u, int j, int M, int N, const void* kin, const void* vin,
-                                     AppendSmem& a) {
+                                     AppendSmem& a, const AppendFetch& f) {
   const int tid = threadIdx.x;
   const size_t cbase = (size_t)u * v.Mcap;
   float* R = unit_R(v, u);
-  double r = 0.0;
-  if (tid < kHeadDim) r = (double)R[r_index(j, tid)];
+  const double r = f.x;
   switch (tid - kHeadDim) {
-    case 0: a.cn = v.cn[cbase + j]; break;
-    case 1: a.cb = v.cb[cbase + j]; break;
-    case 2: a.ctail = v.ctail[cbase + j]; break;
-    case 3: a.cflag = v.cflag[cbase + j]; break;
-    case 4: a.m2 = v.cM2[cbase + j]; break;
-    case 5: a.tau = v.tau[u]; break;
-    case 6: a.nflag = v.nflag[u]; break;
-    case 7: a.bump = v.bump[u]; break;
-    case 8: {
-      const int top = v.free_top[u];
-      a.free_top = top;
-      a.free_page = top > 0 ? v.freelist[(size_t)u * v.Pcap + top - 1] : -1;
-      break;
-    }
+    case 0: a.cn = f.i; break;
+    case 1: a.cb = f.i; break;
+    case 2: a.ctail = f.i; break;
+    case 3: a.cflag = f.i; break;
+    case 4: a.m2 = f.x; break;
+    case 5: a.tau = f.x; break;
+    case 6: a.nflag = f.i; break;
+    case 7: a.bump = f.i; break;
+    case 8: a.free_top = f.i; a.free_page = f.k; break;
     default: break;
   }
   __syncthreads();

@@ -39,7 +39,8 @@ __global__ __launch_bounds__(256) void append_kernel(View v, const void* kin, co
     if (dist[0] < best || arg < 0) { best = dist[0]; arg = j; }
   }
   const int j = block_argmin<256>(best, arg, sv, si);
-  append_commit<256>(v, u, j, M, N, kin, vin, a);
+  const AppendFetch f = append_fetch(v, u, j);
+  append_commit<256>(v, u, j, M, N, kin, vin, a, f);
 }
 
 // ------------------------------------------------------------------------------------------- split

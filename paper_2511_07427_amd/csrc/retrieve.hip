@@ -69,6 +69,17 @@ struct SelectLds {
   int list_cap;
 };
 
+// List entries of one page holding nv tokens, from list position w and gather offset t0 on.
+__device__ __forceinline__ void emit_page(int page, int nv, int w, int t0, int* plist, int* poff, int* lds_list,
+                                          int lds_cap) {
+  for (int qd = 0; 4 * qd < nv; ++qd) {
+    const int e = page * 16 + qd * 4 + (min(4, nv - 4 * qd) - 1);
+    plist[w + qd] = e;
+    if (w + qd < lds_cap) lds_list[w + qd] = e;
+    poff[w + qd] = t0 + 4 * qd;
+  }
+}
+
 // Gather-list entry: one aligned group of four token slots ("quad") of a page,
 // page * 16 + quad * 4 + (valid tokens - 1); `t0` is the gather offset of its first token.
 __device__ inline int emit_cluster(const View& v, int u, size_t cj, int take, int w, int t0, int* plist, int* poff,
@@ -313,13 +324,25 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
 
   // rank of every selected cluster = number of selected clusters that precede it
   constexpr int PER = (kCountMax + NT - 1) / NT;
-  int rk[PER], idw[PER], wt[PER];
+  int rk[PER], idw[PER], wt[PER], pg[PER][kInlinePages];
 #pragma unroll
   for (int r = 0; r < PER; ++r) {
     const int p = tid + r * NT;
     rk[r] = -1; idw[r] = 0; wt[r] = 0;
+#pragma unroll
+    for (int k = 0; k < kInlinePages; ++k) pg[r][k] = -1;
     if (p < cut) {
       const unsigned long long my = ck[p];
+      {   // the cluster's page table is requested now and used once its place in the list is known
+        const int id = 0xFFFF - (int)(my & 0xFFFF);
+        const int4* row = (const int4*)&v.cpg[(cb + id) * kInlinePages];
+        const int4 a = row[0];
+        pg[r][0] = a.x; pg[r][1] = a.y; pg[r][2] = a.z; pg[r][3] = a.w;
+        if (cw[p] > 4 * kPageTokens) {
+          const int4 b = row[1];
+          pg[r][4] = b.x; pg[r][5] = b.y; pg[r][6] = b.z; pg[r][7] = b.w;
+        }
+      }
       int rank = 0;
       for (int qb = 0; qb < cut; qb += 8) {           // eight candidates per round trip to LDS
         unsigned long long o[8];
@@ -362,27 +385,30 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
   }
   const int quads = tid == 0 ? (int)(total64 >> 32) : 0;
   __syncthreads();
-  // list entries: one work item per inline page of a selected cluster (every page but the last is full, so
-  // its place in the list follows from its index); pages past the inline table are walked by the last item
+  // list entries, by the thread that ranked the cluster (every page but the last is full, so a page's place in
+  // the list follows from its index); pages past the inline table are found by walking the chain
   int* plist = v.plist + (size_t)u * v.Lcap;
   int* poff = v.plist_off + (size_t)u * v.Lcap;
-  for (int i = tid; i < cut * kInlinePages; i += NT) {
-    const int p = i / kInlinePages, k = i % kInlinePages;
-    const int take = by_w[p], npages = (take + kPageTokens - 1) / kPageTokens;
-    if (k >= npages) continue;
-    const unsigned long long pk = ck[p];
-    const int id = (int)(pk >> 48), t0 = (int)(pk >> 24) & 0xFFFFFF, q0 = (int)pk & 0xFFFFFF;
-    int page = v.cpg[(cb + id) * kInlinePages + k];
-    for (int kk = k; kk < npages && page >= 0; ++kk) {
-      const int nv = min(kPageTokens, take - kk * kPageTokens), w = q0 + 4 * kk;
-      for (int qd = 0; 4 * qd < nv; ++qd) {
-        const int e = page * 16 + qd * 4 + (min(4, nv - 4 * qd) - 1);
-        plist[w + qd] = e;
-        if (w + qd < s.list_cap) s.list[w + qd] = e;
-        poff[w + qd] = t0 + kk * kPageTokens + 4 * qd;
+#pragma unroll
+  for (int r = 0; r < PER; ++r) {
+    if (rk[r] < 0) continue;
+    const unsigned long long pk = ck[rk[r]];
+    const int t0 = (int)(pk >> 24) & 0xFFFFFF, q0 = (int)pk & 0xFFFFFF;
+    const int take = wt[r], npages = (take + kPageTokens - 1) / kPageTokens;
+    int page = -1;
+#pragma unroll
+    for (int k = 0; k < kInlinePages; ++k)
+      if (k < npages) {
+        page = pg[r][k];
+        if (page >= 0)
+          emit_page(page, min(kPageTokens, take - k * kPageTokens), q0 + 4 * k, t0 + k * kPageTokens, plist, poff,
+                    s.list, s.list_cap);
       }
-      if (k < kInlinePages - 1) break;
+    for (int kk = kInlinePages; kk < npages && page >= 0; ++kk) {
       page = v.pnext[(size_t)u * v.Pcap + page];
+      if (page >= 0)
+        emit_page(page, min(kPageTokens, take - kk * kPageTokens), q0 + 4 * kk, t0 + kk * kPageTokens, plist, poff,
+                  s.list, s.list_cap);
     }
   }
   if (quads) atomicAdd(&s.misc[6], quads);
@@ -744,6 +770,10 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   const float* R = unit_R(v, u);
 
   // ---- scores (float64, one lane per cluster)
+  // the first centroid rows are requested before anything is waited for (rows up to the table's padded end exist)
+  f4 row0[8];
+  const bool early = (size_t)(tid | 63) * kHeadDim < v.Rstride;
+  if (early) load_centroid_head(R, tid, row0);
   const int M = v.M[u];
   for (int t = tid; t < GP * kHeadDim; t += NT) {
     const int g = t / kHeadDim, d = t % kHeadDim;
@@ -755,13 +785,24 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   int Mpad = 2;
   while (Mpad < M) Mpad <<= 1;
   for (int i = M + tid; i < Mpad; i += NT) skey[i] = 0u;
-  for (int j = tid; j < M; j += NT) ssz[j] = v.cn[(size_t)u * v.Mcap + j] + v.cb[(size_t)u * v.Mcap + j];
+  // stored sizes: requested now, needed by the selection only, so the score loop hides their latency
+  int szr[kFusedClusters / NT];
+#pragma unroll
+  for (int k = 0; k < kFusedClusters / NT; ++k) {
+    const int j = tid + k * NT;
+    szr[k] = j < M ? v.cn[(size_t)u * v.Mcap + j] + v.cb[(size_t)u * v.Mcap + j] : 0;
+  }
   __syncthreads();
   double near_d = __builtin_inf();
   int near_j = -1;
   for (int j = tid; (j & ~63) < M; j += NT) {
     f4 row[8];
-    load_centroid_head(R, j, row);
+    if (j == tid && early) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) row[i] = row0[i];
+    } else {
+      load_centroid_head(R, j, row);
+    }
     constexpr int NA = GP + (APPEND ? 1 : 0);
     double acc[NA];
     centroid_sums<NA>(R, j, row, acc, [&](int d, float rv, double (&a)[NA]) __attribute__((always_inline)) {
@@ -784,6 +825,16 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
       v.score[(size_t)u * v.Mcap + j] = sc;
       skey[j] = orderable(sc);
     }
+  }
+#pragma unroll
+  for (int k = 0; k < kFusedClusters / NT; ++k)
+    if (tid + k * NT < M) ssz[tid + k * NT] = szr[k];
+  // the append's nearest cluster is known now: its record is requested here and used after the attention
+  int ja = -1;
+  AppendFetch apf{0.0, 0, 0};
+  if constexpr (APPEND) {
+    ja = block_argmin<NT>(near_d, near_j, am_v, am_i);
+    if (room) apf = append_fetch(v, u, ja);
   }
   __syncthreads();
 
@@ -854,8 +905,7 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
       if (tid == 0) v.err[u] |= DYNAKV_ERR_TOKENS;
       return;
     }
-    const int ja = block_argmin<NT>(near_d, near_j, am_v, am_i);
-    append_commit<NT>(v, u, ja, M, N, kin, vin, ap);
+    append_commit<NT>(v, u, ja, M, N, kin, vin, ap, apf);
   }
 }
 
