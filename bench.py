@@ -29,7 +29,7 @@ def cpu_baseline(spec, n_units, steps, budget):
     w = generate(spec, units=range(n_units), steps=steps)
     o = Oracle(OracleConfig(n_units, spec.group_size, spec.head_dim, spec.n_clusters_init, spec.max_clusters,
                             spec.prefill + steps, spec.kmeans_iters, spec.buffer_max, 0, spec.var_alpha,
-                            spec.size_factor, 0.0, 0))
+                            spec.size_factor, 0.0, 0, dtype=spec.dtype))
     t0 = time.perf_counter()
     o.build_index(w["K0"], w["V0"], w["init_idx"])
     t1 = time.perf_counter()
@@ -142,7 +142,7 @@ def main():
         assert n == a.steps
         kernel = ix.dynakv_profiled_kernel()
         kv_bytes = gathered / a.steps * 2 * d * esz                    # K and V of every gathered entry, once
-        centroid_bytes = scored / a.steps * d * 4 if kernel == "retrieve_fused_kernel" else 0.0   # float32 table, once
+        centroid_bytes = scored / a.steps * d * esz if kernel == "retrieve_fused_kernel" else 0.0   # search copy in the storage type, once
         bytes_per_launch = kv_bytes + centroid_bytes
         achieved = bytes_per_launch / (ms / n * 1e-3) / 1e9
         roof = dict(bound="hbm", kernel=kernel, achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s",

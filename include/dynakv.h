@@ -95,7 +95,9 @@ dynakv_status_t dynakv_build_index(dynakv_index_t* index, const void* K, const v
 
 /* One retrieval (Algorithm 1 "load top-k clusters by query-centroid similarity"; Section 4.1) followed by
  * softmax attention over the retrieved entries (Section 7, attention over reordered KV):
- * score_j = float32(scale * reduce_g <q_g, r_j>); clusters are taken in (score desc, id asc) order while
+ * score_j = float32(scale * reduce_g <q_g, r~_j>), r~_j = the centroid rounded to cfg.dtype (the copy of the
+ * representatives that searches read is kept in the storage type of the keys; the float32 mean r_j stays the
+ * master for the statistics); clusters are taken in (score desc, id asc) order while
  * their stored sizes n_j + |Buf_j| fit in `token_budget`, stopping at the first that does not fit; if
  * even the best cluster does not fit, its first `token_budget` entries are taken.  The selected set
  * becomes the active set P_req that dynakv_split consults.
@@ -106,7 +108,8 @@ dynakv_status_t dynakv_build_index(dynakv_index_t* index, const void* K, const v
 dynakv_status_t dynakv_retrieve_attend(dynakv_index_t* index, const void* Q, int32_t token_budget, float* out,
                                        float* lse, void* stream);
 
-/* Adds one entry per unit (Algorithm 1: assign to the nearest cluster, UpdateVar, threshold test, then
+/* Adds one entry per unit (Algorithm 1: assign to the nearest cluster (squared distance to r~_j, see
+ * dynakv_retrieve_attend), UpdateVar on the float32 mean, threshold test, then
  * AddEntry + UpdateStats or buffer + flag; Section 4.2).  The entry is always stored at the tail of its
  * cluster's pages; a cluster whose tentative variance exceeds tau (or whose tentative size exceeds the
  * size trigger) is flagged and keeps its statistics frozen, later entries of a flagged cluster count as

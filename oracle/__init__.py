@@ -37,7 +37,8 @@ def build(force: bool = False) -> str:
 class _Cfg(C.Structure):
     _fields_ = [(k, C.c_int32) for k in ("n_units", "group_size", "head_dim", "n_clusters_init", "max_clusters",
                                           "max_tokens", "kmeans_iters", "buffer_max", "group_reduce")] + \
-               [(k, C.c_float) for k in ("var_alpha", "size_factor", "softmax_scale")] + [("seed", C.c_uint64)]
+               [(k, C.c_float) for k in ("var_alpha", "size_factor", "softmax_scale")] + \
+               [("dtype", C.c_int32), ("seed", C.c_uint64)]
 
 
 @dataclass
@@ -55,6 +56,7 @@ class OracleConfig:
     size_factor: float = 0.0
     softmax_scale: float = 0.0
     seed: int = 0
+    dtype: str = "f32"          # storage type of K, V, Q ("f32" | "f16" | "bf16"): fixes the type of the search copy
 
 
 _lib = None
@@ -78,6 +80,8 @@ def _load():
         lib.oracle_tau.argtypes = [C.c_void_p, C.c_int]
         lib.oracle_tau.restype = C.c_double
         lib.oracle_get_clusters.argtypes = [C.c_void_p, C.c_int] + [C.c_void_p] * 5
+        lib.oracle_get_search_copy.argtypes = [C.c_void_p, C.c_int, C.c_void_p]
+        lib.oracle_round_to_storage.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int]
         lib.oracle_get_members.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
         lib.oracle_get_selected.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_int]
         lib.oracle_get_gather.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_int]
@@ -98,7 +102,8 @@ class Oracle:
     def __init__(self, cfg: OracleConfig, threads: int = 0):
         self.cfg = cfg
         self._lib = _load()
-        c = _Cfg(**{k: getattr(cfg, k) for k, _ in _Cfg._fields_})
+        c = _Cfg(**{k: getattr(cfg, k) for k, _ in _Cfg._fields_ if k != "dtype"},
+                 dtype={"f32": 0, "f16": 1, "bf16": 2}[cfg.dtype])
         self._h = self._lib.oracle_create(C.byref(c))
         if threads:
             self._lib.oracle_set_threads(self._h, threads)
@@ -166,6 +171,12 @@ class Oracle:
                                       M2.ctypes.data)
         return dict(centroids=r, n=n, b=b, flag=f, M2=M2)
 
+    def search_copy(self, u):
+        """[M, d] float32: every centroid rounded to the storage type, as the searches read it."""
+        out = np.zeros((self.num_clusters(u), self.cfg.head_dim), dtype=np.float32)
+        self._lib.oracle_get_search_copy(self._h, u, out.ctypes.data)
+        return out
+
     def members(self, u):
         """(offsets [M+1], positions [N]): members of cluster j are positions[offsets[j]:offsets[j+1]]."""
         M, N = self.num_clusters(u), self.num_tokens(u)
@@ -204,3 +215,11 @@ class Oracle:
         return dict(margin_assign=mg[0], margin_trigger=mg[1], margin_select=mg[2],
                     ties=dict(zip(("kmeans", "assign", "trigger", "select", "split_side"), ties.tolist())),
                     splits=int(ev[0]), failed_splits=int(ev[1]), forced_splits=int(ev[2]))
+
+
+def round_to_storage(x, dtype: str):
+    """The oracle's own rounding of float32 values to a storage type (nearest, ties to even), as float32."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    out = np.empty_like(x)
+    _load().oracle_round_to_storage(x.ctypes.data, out.ctypes.data, x.size, {"f32": 0, "f16": 1, "bf16": 2}[dtype])
+    return out

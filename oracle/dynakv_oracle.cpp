@@ -48,6 +48,7 @@ struct Config {
   float var_alpha;          // tau = var_alpha * (k-means objective / N0); <= 0: off
   float size_factor;        // split when n' > size_factor * mean cluster size; <= 0: off
   float softmax_scale;      // 0: 1/sqrt(d)
+  int32_t dtype;            // storage type of K, V, Q: 0 float32, 1 float16, 2 bfloat16
   uint64_t seed;            // k-means seeding when no initial indices are given
 };
 
@@ -57,6 +58,7 @@ struct Cluster {
   int32_t flag = 0;         // f_j = SPLIT
   double M2 = 0.0;          // n_j * sigma_j^2 of the committed members
   std::vector<float> r;     // centroid r_j, float32
+  std::vector<float> rs;    // r_j rounded to the storage type: the copy that searches read (see search_copy)
   std::vector<int32_t> members;  // token positions in storage order
 };
 
@@ -126,6 +128,24 @@ inline double sqdist_fd(const float* x, const double* c, int d) {
   });
 }
 
+// Round to nearest, ties to even, onto the grid of a binary format with `mant` explicit mantissa bits, smallest
+// normal exponent `emin` and largest finite value `fmax` (IEEE-style: gradual underflow, overflow to infinity).
+inline float round_to_format(float x, int mant, int emin, double fmax) {
+  if (x == 0.f || !std::isfinite(x)) return x;
+  int e;
+  std::frexp((double)x, &e);                        // |x| = f * 2^e with f in [0.5, 1): floor(log2|x|) = e - 1
+  const int ex = std::max(e - 1, emin);
+  const double quantum = std::ldexp(1.0, ex - mant);
+  const double y = std::nearbyint((double)x / quantum) * quantum;   // default rounding mode: ties to even
+  if (std::fabs(y) > fmax) return (float)std::copysign(std::numeric_limits<double>::infinity(), y);
+  return (float)y;
+}
+inline float round_to_storage(float x, int dtype) {
+  if (dtype == 1) return round_to_format(x, 10, -14, 65504.0);                                   // float16
+  if (dtype == 2) return round_to_format(x, 7, -126, std::ldexp(2.0 - std::ldexp(1.0, -7), 127));   // bfloat16
+  return x;
+}
+
 inline double norm_margin(double gap, double a, double b) {
   return gap / std::max(1.0, std::max(std::fabs(a), std::fabs(b)));
 }
@@ -138,13 +158,21 @@ inline uint64_t splitmix64(uint64_t& s) {
   return z ^ (z >> 31);
 }
 
+// The representatives that a search reads (query similarity, Section 4.1; nearest cluster of a new entry,
+// Algorithm 1) are kept in the storage type of the keys, like the entries they stand for; the statistics
+// (float32 mean, M2) are not touched by this.  Called whenever r_j changes.
+void search_copy(const Config& c, Cluster& cl) {
+  cl.rs.resize(cl.r.size());
+  for (size_t i = 0; i < cl.r.size(); ++i) cl.rs[i] = round_to_storage(cl.r[i], c.dtype);
+}
+
 // Nearest centre of x among all clusters (Algorithm 1, "assign to nearest cluster";
 // squared Euclidean distance, the k-means metric).  Ties -> lowest id.
 int nearest_cluster(const Unit& u, const float* x, int d, double* best_out, double* second_out) {
   double best = std::numeric_limits<double>::infinity(), second = best;
   int arg = -1;
   for (int j = 0; j < (int)u.clusters.size(); ++j) {
-    const double dj = sqdist_ff(x, u.clusters[j].r.data(), d);
+    const double dj = sqdist_ff(x, u.clusters[j].rs.data(), d);
     if (dj < best) { second = best; best = dj; arg = j; }
     else if (dj < second) second = dj;
   }
@@ -257,6 +285,7 @@ int build_unit(const Config& c, Unit& u, int uid, const float* K, const float* V
     cl.M2 = 0.0;
     for (int32_t p : cl.members) cl.M2 += sqdist_ff(&u.K[(size_t)p * d], cl.r.data(), d);
     Jfinal += cl.M2;
+    search_copy(c, cl);
   }
   // head-specific threshold: a multiple of the unit's own mean squared distance to centre
   u.tau = (double)c.var_alpha * (Jfinal / (double)N0);
@@ -275,7 +304,7 @@ void retrieve_attend_unit(const Config& c, Unit& u, const float* Q, int budget, 
   for (int j = 0; j < M; ++j) {
     double red = 0.0;
     for (int g = 0; g < G; ++g) {
-      const double s = dot_ff(Q + (size_t)g * d, u.clusters[j].r.data(), d);
+      const double s = dot_ff(Q + (size_t)g * d, u.clusters[j].rs.data(), d);
       if (g == 0) red = s;
       else if (c.group_reduce == 0) red = std::max(red, s);
       else red += s;
@@ -388,6 +417,7 @@ void append_unit(const Config& c, Unit& u, const float* k, const float* v) {
     cl.n = n1;
     for (int i = 0; i < d; ++i) cl.r[i] = (float)r1[i];
     cl.M2 = M2;
+    search_copy(c, cl);
   } else {                            // statistics stay frozen; entry buffered, cluster flagged
     cl.flag = 1;
     cl.b = 1;
@@ -405,6 +435,7 @@ int split_cluster(const Config& c, Unit& u, int j) {
   const int m = (int)mem.size();
   auto fail = [&]() {
     exact_stats(u, cl.members, d, cl.r, cl.M2);
+    search_copy(c, cl);
     cl.n = m; cl.b = 0; cl.flag = 0;
     ++u.n_failed_splits;
     return 0;
@@ -455,6 +486,7 @@ int split_cluster(const Config& c, Unit& u, int j) {
   for (int i = 0; i < m; ++i) (side[i] == keep ? stay : moved).members.push_back(mem[i]);
   for (Cluster* ch : {&stay, &moved}) {
     exact_stats(u, ch->members, d, ch->r, ch->M2);
+    search_copy(c, *ch);
     ch->n = (int32_t)ch->members.size();
     ch->b = 0; ch->flag = 0;
   }
@@ -495,6 +527,7 @@ struct oracle_config {
   int32_t n_units, group_size, head_dim, n_clusters_init, max_clusters, max_tokens, kmeans_iters, buffer_max,
       group_reduce;
   float var_alpha, size_factor, softmax_scale;
+  int32_t dtype;
   uint64_t seed;
 };
 
@@ -502,7 +535,7 @@ void* oracle_create(const oracle_config* c) {
   Oracle* o = new Oracle();
   o->cfg = Config{c->n_units, c->group_size, c->head_dim, c->n_clusters_init, c->max_clusters, c->max_tokens,
                   c->kmeans_iters, c->buffer_max, c->group_reduce, c->var_alpha, c->size_factor, c->softmax_scale,
-                  c->seed};
+                  c->dtype, c->seed};
   o->units.resize(c->n_units);
   return o;
 }
@@ -612,6 +645,18 @@ int oracle_get_gather(void* h, int u, int32_t* pos, int cap) {
   for (int i = 0; i < n && i < cap; ++i) pos[i] = un.gather[i];
   return n;
 }
+// search copies [M][d] f32 (the values, exactly representable in the storage type)
+void oracle_get_search_copy(void* h, int u, float* out) {
+  const Oracle* o = (Oracle*)h;
+  const int d = o->cfg.head_dim;
+  const Unit& un = o->units[u];
+  for (size_t j = 0; j < un.clusters.size(); ++j) std::copy(un.clusters[j].rs.begin(), un.clusters[j].rs.end(), out + j * d);
+}
+// out[i] = in[i] rounded to the storage type (0 float32, 1 float16, 2 bfloat16), returned as float32
+void oracle_round_to_storage(const float* in, float* out, int64_t n, int dtype) {
+  for (int64_t i = 0; i < n; ++i) out[i] = round_to_storage(in[i], dtype);
+}
+
 void oracle_get_scores(void* h, int u, float* s) {
   const Unit& un = ((Oracle*)h)->units[u];
   std::copy(un.scores.begin(), un.scores.end(), s);

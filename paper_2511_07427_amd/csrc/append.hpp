@@ -53,7 +53,6 @@ __device__ inline void append_commit(const View& v, int u, int j, int M, int N, 
                                      AppendSmem& a, const AppendFetch& f) {
   const int tid = threadIdx.x;
   const size_t cbase = (size_t)u * v.Mcap;
-  float* R = unit_R(v, u);
   const double r = f.x;
   switch (tid - kHeadDim) {
     case 0: a.cn = f.i; break;
@@ -141,7 +140,7 @@ __device__ inline void append_commit(const View& v, int u, int j, int M, int N, 
   }
   __syncthreads();
   if (!a.ok) return;
-  if (a.commit && tid < kHeadDim) R[r_index(j, tid)] = (float)a.r1[tid];
+  if (a.commit && tid < kHeadDim) store_centroid(v, u, j, tid, (float)a.r1[tid]);
   char* pg = page_ptr(v, u, a.page);
   if (a.fresh) {                          // first use of this page: unused slots must hold finite values
     const int n16 = kPageElems * elem_size(v.dtype) / 16;

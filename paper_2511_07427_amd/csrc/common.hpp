@@ -44,6 +44,8 @@ struct View {
   long long* counters;  // [U][8] splits, failed, forced, (unused), entries gathered, retrievals, clusters scored, -
   // per cluster [U][Mcap]
   float* R;          // [U][Rstride] centroids, lane-interleaved: see r_index()
+  uint16_t* Rq;      // [U][Rstride] the same centroids rounded to the 16-bit storage type (see rq_index()): the
+                     // copy that the searches of a decode step read; unused for float32 storage
   int* cn;           // committed size n_j
   int* cb;           // buffered entries |Buf_j|
   int* cflag;        // f_j
@@ -119,6 +121,26 @@ __host__ __device__ inline size_t r_index(int j, int d) {
 }
 __host__ __device__ inline size_t r_stride(int Mcap) { return (size_t)((Mcap + 63) / 64) * 64 * kHeadDim; }
 __device__ inline float* unit_R(const View& v, int u) { return v.R + (size_t)u * v.Rstride; }
+
+// The representatives that a search reads (query similarity, Section 4.1; nearest cluster of a new entry,
+// Algorithm 1) are kept in the storage type of the keys, like the entries they stand for; the float32 table
+// above stays the master copy for the statistics.  16-bit copy: [tile of 64 clusters][d/8][64][8], 16 bytes per
+// lane and load, one block of the summation order per load.
+__host__ __device__ inline size_t rq_index(int j, int d) {
+  return ((size_t)(j >> 6) * (kHeadDim / 8) + (d >> 3)) * 512 + (size_t)(j & 63) * 8 + (d & 7);
+}
+__device__ inline uint16_t* unit_Rq(const View& v, int u) { return v.Rq + (size_t)u * v.Rstride; }
+// float32 -> 16-bit storage type, round to nearest even; the bits.
+__device__ inline uint16_t round_bits16(float x, int dtype) {
+  if (dtype == DYNAKV_F16) return __builtin_bit_cast(uint16_t, (_Float16)x);
+  const uint32_t u = __float_as_uint(x);
+  return (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);       // bfloat16 (centroids are finite)
+}
+// Writes coordinate d of centroid j: the float32 master and, for 16-bit storage, the search copy.
+__device__ inline void store_centroid(const View& v, int u, int j, int d, float val) {
+  unit_R(v, u)[r_index(j, d)] = val;
+  if (v.dtype != DYNAKV_F32) unit_Rq(v, u)[rq_index(j, d)] = round_bits16(val, v.dtype);
+}
 
 // ---- the fixed summation order ----------------------------------------------------------------------
 // Every float64 sum over the 128 coordinates runs in one order: blocks of 8 consecutive coordinates are
@@ -213,6 +235,79 @@ __device__ __forceinline__ void centroid_sums(const float* R, int j, f4 (&cur)[8
 // ---- element access -----------------------------------------------------------------------------
 __device__ inline float bf16_to_float(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
 __device__ inline float f16_to_float(uint16_t h) { return (float)__builtin_bit_cast(_Float16, h); }
+
+// ---- the same sums over the 16-bit search copy ---------------------------------------------------
+// BF selects bfloat16; NR centroids (1 or 2) of one lane at once, j[r] each: term(d, values, acc) gets the NR
+// coordinate values and adds into acc[r][a].  One 16-byte load is one block of 8 coordinates; the next four
+// blocks are in flight while four are consumed.
+template <int NR>
+__device__ inline void load_search_head(const uint16_t* Rq, const int (&j)[NR], uint4 (&first)[NR][4]) {
+#pragma unroll
+  for (int r = 0; r < NR; ++r) {
+    const uint4* p = (const uint4*)(Rq + rq_index(j[r], 0));
+#pragma unroll
+    for (int i = 0; i < 4; ++i) first[r][i] = p[i * 64];
+  }
+}
+template <bool BF>
+__device__ __forceinline__ float half_at(const uint4& w, int e) {
+  const uint32_t ww = e < 2 ? w.x : e < 4 ? w.y : e < 6 ? w.z : w.w;
+  const uint16_t h = (uint16_t)(ww >> ((e & 1) * 16));
+  return BF ? bf16_to_float(h) : f16_to_float(h);
+}
+template <int NACC, int NR, bool BF, class F>
+__device__ __forceinline__ void search_batch(int b, const uint4 (&cur)[NR][4], double (&out)[NR][NACC], F&& term) {
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    double acc[NR][NACC];
+#pragma unroll
+    for (int r = 0; r < NR; ++r)
+#pragma unroll
+      for (int a = 0; a < NACC; ++a) acc[r][a] = 0.0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float x[NR];
+#pragma unroll
+      for (int r = 0; r < NR; ++r) x[r] = half_at<BF>(cur[r][k], e);
+      term(b * 32 + k * 8 + e, x, acc);
+    }
+#pragma unroll
+    for (int r = 0; r < NR; ++r)
+#pragma unroll
+      for (int a = 0; a < NACC; ++a) out[r][a] += acc[r][a];
+    __builtin_amdgcn_sched_barrier(0);   // keeps the operand loads of later blocks from piling up in registers
+  }
+}
+template <int NACC, int NR, bool BF, class F>
+__device__ __forceinline__ void search_sums(const uint16_t* Rq, const int (&j)[NR], uint4 (&cur)[NR][4],
+                                            double (&out)[NR][NACC], F&& term) {
+  const uint4* p[NR];
+#pragma unroll
+  for (int r = 0; r < NR; ++r) {
+    p[r] = (const uint4*)(Rq + rq_index(j[r], 0));
+#pragma unroll
+    for (int a = 0; a < NACC; ++a) out[r][a] = 0.0;
+  }
+#pragma unroll 1
+  for (int b = 0; b < 3; ++b) {
+    uint4 nxt[NR][4];
+#pragma unroll
+    for (int r = 0; r < NR; ++r)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) nxt[r][i] = p[r][((b + 1) * 4 + i) * 64];
+    search_batch<NACC, NR, BF>(b, cur, out, term);
+#pragma unroll
+    for (int r = 0; r < NR; ++r)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) cur[r][i] = nxt[r][i];
+  }
+  search_batch<NACC, NR, BF>(3, cur, out, term);
+  // the sums are complete here (see centroid_sums)
+#pragma unroll
+  for (int r = 0; r < NR; ++r)
+#pragma unroll
+    for (int a = 0; a < NACC; ++a) asm volatile("" : "+v"(out[r][a]));
+}
 
 // Element `i` of an array of the index's storage type, as float (exact).
 __device__ inline float load_elem(const void* base, size_t i, int dtype) {

@@ -486,6 +486,12 @@ __global__ __launch_bounds__(1024) void finalize_kernel(View v, int N0) {
     }
     v.cb[cb + j] = 0; v.cflag[cb + j] = 0; v.in_req[cb + j] = 0;
   }
+  if (v.dtype != DYNAKV_F32) {               // search copy of the final centroids
+    const float* R = unit_R(v, u);
+    uint16_t* Rq = unit_Rq(v, u);
+    for (int t = tid; t < v.M0 * kHeadDim; t += 1024)
+      Rq[rq_index(t >> 7, t & 127)] = round_bits16(R[r_index(t >> 7, t & 127)], v.dtype);
+  }
   __syncthreads();
   if (tid == 0) {
     double J = 0.0;

@@ -11,14 +11,21 @@ namespace dynakv {
 namespace {
 
 // ------------------------------------------------------------------------------------------- append
+template <int DT>
 __global__ __launch_bounds__(256) void append_kernel(View v, const void* kin, const void* vin) {
   __shared__ AppendSmem a;
   __shared__ double sv[16];
   __shared__ int si[16];
   const int u = blockIdx.x, tid = threadIdx.x;
-  float* R = unit_R(v, u);
+  const float* R = unit_R(v, u);
+  const uint16_t* Rq = unit_Rq(v, u);
   f4 row[8];
-  if ((size_t)(tid | 63) * kHeadDim < v.Rstride) load_centroid_head(R, tid, row);   // requested before anything else
+  uint4 hrow[1][4];
+  if ((size_t)(tid | 63) * kHeadDim < v.Rstride) {    // requested before anything else
+    const int js[1] = {tid};
+    if constexpr (DT == DYNAKV_F32) load_centroid_head(R, tid, row);
+    else load_search_head<1>(Rq, js, hrow);
+  }
   const int M = v.M[u], N = v.N[u];
   if (N >= v.Ncap || M <= 0) {
     if (tid == 0) v.err[u] |= DYNAKV_ERR_TOKENS;
@@ -30,13 +37,23 @@ __global__ __launch_bounds__(256) void append_kernel(View v, const void* kin, co
   double best = __builtin_inf();
   int arg = -1;
   for (int j = tid; j < M; j += 256) {
-    if (j != tid) load_centroid_head(R, j, row);
-    double dist[1];
-    centroid_sums<1>(R, j, row, dist, [&](int d, float rv, double (&acc)[1]) __attribute__((always_inline)) {
-      const double t = a.kd[d] - (double)rv;
-      acc[0] = fma(t, t, acc[0]);
-    });
-    if (dist[0] < best || arg < 0) { best = dist[0]; arg = j; }
+    const int js[1] = {j};
+    double dist[1][1];
+    if constexpr (DT == DYNAKV_F32) {
+      if (j != tid) load_centroid_head(R, j, row);
+      centroid_sums<1>(R, j, row, dist[0], [&](int d, float rv, double (&acc)[1]) __attribute__((always_inline)) {
+        const double t = a.kd[d] - (double)rv;
+        acc[0] = fma(t, t, acc[0]);
+      });
+    } else {
+      if (j != tid) load_search_head<1>(Rq, js, hrow);
+      search_sums<1, 1, DT == DYNAKV_BF16>(Rq, js, hrow, dist,
+          [&](int d, const float (&x)[1], double (&acc)[1][1]) __attribute__((always_inline)) {
+        const double t = a.kd[d] - (double)x[0];
+        acc[0][0] = fma(t, t, acc[0][0]);
+      });
+    }
+    if (dist[0][0] < best || arg < 0) { best = dist[0][0]; arg = j; }
   }
   const int j = block_argmin<256>(best, arg, sv, si);
   const AppendFetch f = append_fetch(v, u, j);
@@ -204,7 +221,7 @@ __device__ inline void children_stats(const View& v, int u, SplitSmem& s, const 
     float* r = c ? s.rB : s.rA;
     const double sum = ordered_sum(q1 - q0, [&](int r) { return ks.get(s.perm[q0 + r], d); }, [](int) { return true; });
     r[d] = q1 > q0 ? (float)(sum / (double)(q1 - q0)) : 0.f;
-    if (id >= 0) unit_R(v, u)[r_index(id, d)] = r[d];
+    if (id >= 0) store_centroid(v, u, id, d, r[d]);
   }
   __syncthreads();
   double* dist = staged ? s.dl : v.dist + (size_t)u * v.Ncap;
@@ -717,13 +734,12 @@ __device__ inline void wave_split_commit(const View& v, int u, WaveCtx& c) {
   wave_sums<DT, false>(c, 0, nS, lane, at, s0, s1, u0, u1);
   c.rA[lane] = nS > 0 ? (float)(s0 / (double)nS) : 0.f;
   c.rA[lane + 64] = nS > 0 ? (float)(s1 / (double)nS) : 0.f;
-  float* R = unit_R(v, u);
-  R[r_index(j, lane)] = c.rA[lane]; R[r_index(j, lane + 64)] = c.rA[lane + 64];
+  store_centroid(v, u, j, lane, c.rA[lane]); store_centroid(v, u, j, lane + 64, c.rA[lane + 64]);
   if (idM >= 0) {
     wave_sums<DT, false>(c, nS, m, lane, at, s0, s1, u0, u1);
     c.rB[lane] = nM > 0 ? (float)(s0 / (double)nM) : 0.f;
     c.rB[lane + 64] = nM > 0 ? (float)(s1 / (double)nM) : 0.f;
-    R[r_index(idM, lane)] = c.rB[lane]; R[r_index(idM, lane + 64)] = c.rB[lane + 64];
+    store_centroid(v, u, idM, lane, c.rB[lane]); store_centroid(v, u, idM, lane + 64, c.rB[lane + 64]);
   }
   wave_sync();
   {
@@ -1036,7 +1052,9 @@ __global__ __launch_bounds__(1024) void export_kernel(View v, dynakv_state_t o) 
 }  // namespace
 
 hipError_t launch_append(const View& v, const void* k, const void* val, hipStream_t st) {
-  append_kernel<<<v.U, 256, 0, st>>>(v, k, val);
+  if (v.dtype == DYNAKV_F32) append_kernel<DYNAKV_F32><<<v.U, 256, 0, st>>>(v, k, val);
+  else if (v.dtype == DYNAKV_F16) append_kernel<DYNAKV_F16><<<v.U, 256, 0, st>>>(v, k, val);
+  else append_kernel<DYNAKV_BF16><<<v.U, 256, 0, st>>>(v, k, val);
   return hipGetLastError();
 }
 hipError_t launch_split(const View& v, hipStream_t st) {

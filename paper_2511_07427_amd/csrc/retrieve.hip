@@ -13,19 +13,28 @@ namespace {
 
 // ------------------------------------------------------------------------------------------- scores
 // Lane = cluster: the centroid table is lane-interleaved, so every load below is 1 KB contiguous per wavefront.
-template <int GP>
+template <int GP, int DT>
 __global__ __launch_bounds__(256) void score_kernel(View v, const void* Q) {
   __shared__ double qs[kHeadDim][GP];
   const int u = blockIdx.y, tid = threadIdx.x;
   const int j = blockIdx.x * 256 + tid;
   const float* R = unit_R(v, u);
+  const uint16_t* Rq = unit_Rq(v, u);
+  const int js[1] = {j};
   // the first quarter of the row is requested before anything else (rows up to the table's padded end exist)
   f4 row[8];
+  uint4 hrow[1][4];
   const bool early = blockIdx.x * 256 < v.M0;        // these rows exist in every state: M never drops below M0
-  if (early) load_centroid_head(R, j, row);
+  if (early) {
+    if constexpr (DT == DYNAKV_F32) load_centroid_head(R, j, row);
+    else load_search_head<1>(Rq, js, hrow);
+  }
   const int M = v.M[u];
   if (blockIdx.x * 256 >= M) return;
-  if (!early && (j & ~63) < M) load_centroid_head(R, j, row);
+  if (!early && (j & ~63) < M) {
+    if constexpr (DT == DYNAKV_F32) load_centroid_head(R, j, row);
+    else load_search_head<1>(Rq, js, hrow);
+  }
   for (int t = tid; t < GP * kHeadDim; t += 256) {
     const int g = t / kHeadDim, d = t % kHeadDim;
     qs[d][g] = g < v.G ? (double)load_elem(Q, ((size_t)u * v.G + g) * kHeadDim + d, v.dtype) : 0.0;
@@ -33,11 +42,23 @@ __global__ __launch_bounds__(256) void score_kernel(View v, const void* Q) {
   __syncthreads();
   if ((j & ~63) >= M) return;                       // whole wavefront past the last cluster
   double acc[GP];
-  centroid_sums<GP>(R, j, row, acc, [&](int d, float rv, double (&a)[GP]) __attribute__((always_inline)) {
-    const double rd = (double)rv;
+  if constexpr (DT == DYNAKV_F32) {
+    centroid_sums<GP>(R, j, row, acc, [&](int d, float rv, double (&a)[GP]) __attribute__((always_inline)) {
+      const double rd = (double)rv;
 #pragma unroll
-    for (int g = 0; g < GP; ++g) a[g] = fma(qs[d][g], rd, a[g]);
-  });
+      for (int g = 0; g < GP; ++g) a[g] = fma(qs[d][g], rd, a[g]);
+    });
+  } else {
+    double acc1[1][GP];
+    search_sums<GP, 1, DT == DYNAKV_BF16>(Rq, js, hrow, acc1,
+        [&](int d, const float (&x)[1], double (&a)[1][GP]) __attribute__((always_inline)) {
+      const double rd = (double)x[0];
+#pragma unroll
+      for (int g = 0; g < GP; ++g) a[0][g] = fma(qs[d][g], rd, a[0][g]);
+    });
+#pragma unroll
+    for (int g = 0; g < GP; ++g) acc[g] = acc1[0][g];
+  }
   if (j >= M) return;
   double red = acc[0];
 #pragma unroll
@@ -767,14 +788,19 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   const int u = blockIdx.x, tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int G = v.G;
-  const float* R = unit_R(v, u);
 
-  // ---- scores (float64, one lane per cluster)
-  // the first centroid rows are requested before anything is waited for (rows up to the table's padded end exist)
-  f4 row0[8];
-  const bool early = (size_t)(tid | 63) * kHeadDim < v.Rstride;
-  if (early) load_centroid_head(R, tid, row0);
+  // ---- scores (float64; every lane takes two clusters per pass, ja and ja + 64, so that the query operands it
+  // reads from LDS serve both)
+  const uint16_t* Rq = unit_Rq(v, u);
+  // the first rows are requested before anything is waited for (rows up to the table's padded end exist)
+  // (with at most one cluster per lane in all, every lane takes one, so that all wavefronts share the work)
+  uint4 row0[2][4];
+  const int span0 = v.M0 > NT ? 128 : 64;            // the guess behind the early request: M has not been read yet
+  const int j0[2] = {wave * span0 + lane, wave * span0 + (span0 - 64) + lane};
+  const bool early = (size_t)(wave * span0 + span0 - 1) * kHeadDim < v.Rstride;
+  if (early) load_search_head<2>(Rq, j0, row0);
   const int M = v.M[u];
+  const int span = M > NT ? 128 : 64;
   for (int t = tid; t < GP * kHeadDim; t += NT) {
     const int g = t / kHeadDim, d = t % kHeadDim;
     qs[d][g] = g < G ? (double)load_elem(Q, ((size_t)u * G + g) * kHeadDim + d, v.dtype) : 0.0;
@@ -795,35 +821,48 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   __syncthreads();
   double near_d = __builtin_inf();
   int near_j = -1;
-  for (int j = tid; (j & ~63) < M; j += NT) {
-    f4 row[8];
-    if (j == tid && early) {
+  for (int base = wave * span; base < M; base += NW * span) {
+    const bool pair = span == 128 && base + 64 < M;  // wavefront-uniform: the second half exists
+    const int js[2] = {base + lane, pair ? base + 64 + lane : base + lane};
+    uint4 row[2][4];
+    if (base == wave * span && early && span == span0) {
 #pragma unroll
-      for (int i = 0; i < 8; ++i) row[i] = row0[i];
+      for (int i = 0; i < 4; ++i) { row[0][i] = row0[0][i]; row[1][i] = pair ? row0[1][i] : row0[0][i]; }
     } else {
-      load_centroid_head(R, j, row);
+      load_search_head<2>(Rq, js, row);
     }
     constexpr int NA = GP + (APPEND ? 1 : 0);
-    double acc[NA];
-    centroid_sums<NA>(R, j, row, acc, [&](int d, float rv, double (&a)[NA]) __attribute__((always_inline)) {
-      const double rd = (double)rv;
+    double acc[2][NA];
+    search_sums<NA, 2, DT == DYNAKV_BF16>(Rq, js, row, acc,
+        [&](int d, const float (&x)[2], double (&a)[2][NA]) __attribute__((always_inline)) {
+      const double r0 = (double)x[0], r1 = (double)x[1];
 #pragma unroll
-      for (int g = 0; g < GP; ++g) a[g] = fma(qs[d][g], rd, a[g]);
+      for (int g = 0; g < GP; ++g) {
+        const double qv = qs[d][g];
+        a[0][g] = fma(qv, r0, a[0][g]);
+        a[1][g] = fma(qv, r1, a[1][g]);
+      }
       if constexpr (APPEND) {
-        const double t = ap.kd[d] - rd;
-        a[GP] = fma(t, t, a[GP]);
+        const double kv = ap.kd[d];
+        const double t0 = kv - r0, t1 = kv - r1;
+        a[0][GP] = fma(t0, t0, a[0][GP]);
+        a[1][GP] = fma(t1, t1, a[1][GP]);
       }
     });
-    if constexpr (APPEND)
-      if (j < M && (acc[GP] < near_d || near_j < 0)) { near_d = acc[GP]; near_j = j; }
-    if (j < M) {
-      double red = acc[0];
 #pragma unroll
-      for (int g = 1; g < GP; ++g)
-        if (g < G) red = v.group_reduce == DYNAKV_GROUP_MAX ? fmax(red, acc[g]) : red + acc[g];
-      const float sc = (float)(red * v.scale_d);
-      v.score[(size_t)u * v.Mcap + j] = sc;
-      skey[j] = orderable(sc);
+    for (int h = 0; h < 2; ++h) {
+      const int j = js[h];
+      if (j < M && (h == 0 || pair)) {
+        if constexpr (APPEND)
+          if (acc[h][GP] < near_d || near_j < 0) { near_d = acc[h][GP]; near_j = j; }
+        double red = acc[h][0];
+#pragma unroll
+        for (int g = 1; g < GP; ++g)
+          if (g < G) red = v.group_reduce == DYNAKV_GROUP_MAX ? fmax(red, acc[h][g]) : red + acc[h][g];
+        const float sc = (float)(red * v.scale_d);
+        v.score[(size_t)u * v.Mcap + j] = sc;
+        skey[j] = orderable(sc);
+      }
     }
   }
 #pragma unroll
@@ -953,9 +992,16 @@ hipError_t launch_retrieve_fused(const View& v, const void* Q, int budget, float
 
 hipError_t launch_score_select(const View& v, const void* Q, int budget, hipStream_t st) {
   const dim3 grid((v.Mcap + 255) / 256, v.U);
-  if (v.G <= 4) score_kernel<4><<<grid, 256, 0, st>>>(v, Q);
-  else if (v.G <= 8) score_kernel<8><<<grid, 256, 0, st>>>(v, Q);
-  else score_kernel<16><<<grid, 256, 0, st>>>(v, Q);
+#define DYNAKV_SCORE(DT)                                                \
+  do {                                                                  \
+    if (v.G <= 4) score_kernel<4, DT><<<grid, 256, 0, st>>>(v, Q);      \
+    else if (v.G <= 8) score_kernel<8, DT><<<grid, 256, 0, st>>>(v, Q); \
+    else score_kernel<16, DT><<<grid, 256, 0, st>>>(v, Q);              \
+  } while (0)
+  if (v.dtype == DYNAKV_F32) DYNAKV_SCORE(DYNAKV_F32);
+  else if (v.dtype == DYNAKV_F16) DYNAKV_SCORE(DYNAKV_F16);
+  else DYNAKV_SCORE(DYNAKV_BF16);
+#undef DYNAKV_SCORE
   select_kernel<<<v.U, 1024, 0, st>>>(v, budget);
   return hipGetLastError();
 }

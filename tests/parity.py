@@ -28,7 +28,7 @@ def make_pair(spec: WorkloadSpec, n_units: int, max_tokens: int | None = None, *
               softmax_scale=0.0)
     kw.update(over)
     ix = binding.Index(binding.Config(dtype=spec.dtype, head_dim=spec.head_dim, **kw), DEV)
-    o = Oracle(OracleConfig(head_dim=spec.head_dim, seed=0, **kw))
+    o = Oracle(OracleConfig(head_dim=spec.head_dim, seed=0, dtype=spec.dtype, **kw))
     return ix, o
 
 

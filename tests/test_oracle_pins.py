@@ -435,3 +435,56 @@ def test_capacity_errors_leave_state_consistent():
     assert o.num_tokens(0) == 7 and o.error(0) == 3
     with pytest.raises(ValueError):
         Oracle(cfg(maxt=4)).build_index(K, K, np.array([[0, 4]], np.int32))
+
+
+# ---------------------------------------------------------------- search copies in the storage type
+
+def _bf16(x):
+    u = np.asarray(x, np.float32).view(np.uint32)
+    return ((u + (((u >> 16) & 1) + 0x7FFF)) & np.uint32(0xFFFF0000)).view(np.float32)
+
+
+def test_storage_rounding_is_ieee_round_to_nearest_even():
+    from oracle import round_to_storage
+    rng = np.random.default_rng(7)
+    x = (rng.standard_normal(100000) * 10.0 ** rng.integers(-9, 5, 100000)).astype(np.float32)
+    x = np.concatenate([x, np.array([0, -0.0, 65504, 65519.99, 65520, 7e4, 1e-8, 2 ** -25, 2 ** -24, 3e-8, -6.1e-5,
+                                     2049, 2051, 1 + 2 ** -11, 1 + 3 * 2 ** -11], np.float32)])
+    with np.errstate(over="ignore"):
+        np.testing.assert_array_equal(round_to_storage(x, "f16"), x.astype(np.float16).astype(np.float32))
+    np.testing.assert_array_equal(round_to_storage(x, "bf16"), _bf16(x))
+    np.testing.assert_array_equal(round_to_storage(x, "f32"), x)
+    assert round_to_storage(np.float32([2049.0]), "f16")[0] == 2048.0      # tie -> even
+    assert round_to_storage(np.float32([2051.0]), "f16")[0] == 2052.0
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_searches_read_the_centroids_in_the_storage_type(dtype):
+    """Scores and nearest-cluster assignment use r_j rounded to the storage type; the float32 mean itself and the
+    statistics do not change.  Checked against numpy on a drifting trajectory with appends and splits."""
+    s = CONFIGS["tiny"].scaled(dtype=dtype, var_alpha=1.2, size_factor=0.0, buffer_max=4)
+    w = generate(s, steps=96)
+    o = Oracle(OracleConfig(1, 4, 128, 32, 128, s.max_tokens, 5, 4, 0, s.var_alpha, 0.0, 0.0, 0, dtype=dtype))
+    o.build_index(w["K0"], w["V0"], w["init_idx"])
+    conv = (lambda a: a.astype(np.float16).astype(np.float32)) if dtype == "f16" else _bf16
+    differ = 0
+    for t in range(96):
+        c = o.clusters(0)
+        rs = o.search_copy(0)
+        np.testing.assert_array_equal(rs, conv(c["centroids"]))
+        q = w["Q"][t, 0].astype(np.float64)
+        o.retrieve_attend(w["Q"][t], 256)
+        want = (q @ rs.astype(np.float64).T).max(0) / np.sqrt(128)
+        got = o.scores(0)
+        np.testing.assert_allclose(got, want, rtol=2e-7, atol=1e-30)
+        plain = ((q @ c["centroids"].astype(np.float64).T).max(0) / np.sqrt(128)).astype(np.float32)
+        differ += int((got != plain).sum())
+        k = w["Knew"][t, 0].astype(np.float64)
+        d2 = ((k[None, :] - rs.astype(np.float64)) ** 2).sum(1)
+        o.append(w["Knew"][t], w["Vnew"][t])
+        order = np.argsort(d2, kind="stable")
+        if len(order) == 1 or d2[order[1]] - d2[order[0]] > 1e-9 * d2[order[0]]:
+            assert o.last_assign(0) == order[0]
+        o.split()
+    assert differ > 0          # the rounding is visible: scores are not those of the unrounded means
+    assert o.diagnostics(0)["splits"] > 0
