@@ -20,6 +20,14 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_PEAK_TFLOPS = 2500.0      # dense fp16/bf16, published
 
+# HBM bytes per launch of the dominant kernel from two `rocprofv3 --pmc` runs of this file with its default
+# arguments (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch averaged over the timed launches), each scaled by what
+# the same counter reads for the float32 -> float16 copy of the 134 217 728-element prefill keys (512 MiB read,
+# 256 MiB written): FETCH_SIZE reads 262 167 KiB for it (factor 2.000), WRITE_SIZE 262 144 KiB (factor 1.000).
+# Only valid for exactly that workload; any other arguments report null.
+PMC_TRAFFIC = {("llama3_8b", 8192, 64, 0): {"fetch_kib": 130302.6, "fetch_scale": 524288.0 / 262166.6,
+                                            "write_kib": 3390.4, "write_scale": 1.0}}
+
 
 def cpu_baseline(spec, n_units, steps, budget):
     """The oracle as it stands, on a bounded sample: `n_units` units, k-means prefill plus `steps` decode steps."""
@@ -145,8 +153,10 @@ def main():
         centroid_bytes = scored / a.steps * d * esz if kernel == "retrieve_fused_kernel" else 0.0   # search copy in the storage type, once
         bytes_per_launch = kv_bytes + centroid_bytes
         achieved = bytes_per_launch / (ms / n * 1e-3) / 1e9
+        pmc = PMC_TRAFFIC.get((a.config, a.steps, a.warmup, a.units)) if kernel == "retrieve_fused_kernel" else None
+        traffic = (pmc["fetch_kib"] * pmc["fetch_scale"] + pmc["write_kib"] * pmc["write_scale"]) * 1024.0 if pmc else None
         roof = dict(bound="hbm", kernel=kernel, achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=achieved / HBM_PEAK_GBS, traffic=None, avg_launch_us=ms / n * 1e3,
+                    frac=achieved / HBM_PEAK_GBS, traffic=traffic, avg_launch_us=ms / n * 1e3,
                     algorithmic_bytes_per_launch=bytes_per_launch, kv_bytes_per_launch=kv_bytes,
                     centroid_bytes_per_launch=centroid_bytes, gathered_entries_per_unit=gathered / retrievals,
                     clusters_per_unit=scored / retrievals)

@@ -475,6 +475,9 @@ constexpr int kWaveSplits = kSplitThreads / 64;
 constexpr int kWaveStage = 64 * kStageRow16 * 2;                 // 64 rows of a 16-bit type, 32 of float32
 static_assert(32 * kStageRow32 * 4 <= kWaveStage, "float32 rows must fit");
 constexpr int kWavePages = 64 / kPageTokens;                     // pages of the largest such cluster
+// Values of the first 16 members (element t = 64k + lane of the member-major [m][128] array, k < 32) are
+// requested together with the keys and wait in registers until the children's pages are known.
+constexpr int kVAhead = 32, kVAheadMembers = kVAhead * 64 / kHeadDim;
 
 struct WaveCtx {
   alignas(16) unsigned char stage[kWaveStage];
@@ -482,7 +485,7 @@ struct WaveCtx {
   float rA[kHeadDim], rB[kHeadDim];
   double dist[64];
   double m2[2];
-  unsigned char side[64], perm[64];
+  unsigned char side[64], perm[64], inv[64];     // inv[member] = its place in perm
   int chain[kWavePages], newpg[kWavePages + 2];
   int j, m, ok, nS, idM, fresh_from;     // fresh_from: newpg[k] with k >= fresh_from were never used before
 };
@@ -573,7 +576,7 @@ __device__ __forceinline__ void wave_sums(const WaveCtx& c, int q0, int q1, int 
 // First phase, one wavefront: stage the keys (c.chain lists their pages), 2-means, stable partition.  Sets
 // c.ok, c.nS, c.perm.
 template <int DT>
-__device__ inline void wave_split_decide(const View& v, int u, WaveCtx& c) {
+__device__ inline void wave_split_decide(const View& v, int u, WaveCtx& c, uint32_t (&vahead)[kVAhead], int& pos_ahead) {
   const int lane = threadIdx.x & 63;
   constexpr int kEs = DT == DYNAKV_F32 ? 4 : 2;
   constexpr int kChunks = kHeadDim * kEs / 16;
@@ -595,6 +598,17 @@ __device__ inline void wave_split_decide(const View& v, int u, WaveCtx& c) {
       if (t < m * kChunks) *(uint4*)(c.stage + (size_t)(t / kChunks) * kRowBytes + (t % kChunks) * 16) = w[k];
     }
   }
+#pragma unroll
+  for (int k = 0; k < kVAhead; ++k) {
+    const int t = k * 64 + lane, i = t >> 7;
+    vahead[k] = 0;
+    if (i < m) {
+      const char* src = pool + (size_t)c.chain[i >> 4] * (kPageElems * kEs);
+      const int e = v_index(DT, i & 15, t & 127);
+      vahead[k] = DT == DYNAKV_F32 ? ((const uint32_t*)src)[e] : (uint32_t)((const uint16_t*)src)[e];
+    }
+  }
+  pos_ahead = lane < m ? v.ppos[((size_t)u * v.Pcap + c.chain[lane >> 4]) * kPageTokens + (lane & 15)] : 0;
   wave_sync();
   const WaveKeys<DT> ks{c};
   const int grp = lane >> 2, kb = lane & 3;      // four lanes per member in the distance passes
@@ -662,9 +676,14 @@ __device__ inline void wave_split_decide(const View& v, int u, WaveCtx& c) {
     const unsigned long long mask = __ballot(lane < m && c.side[lane] == keep);
     const int before = __popcll(mask & ((1ull << lane) - 1ull));
     nS = __popcll(mask);
-    if (lane < m) c.perm[(mask >> lane) & 1ull ? before : nS + lane - before] = (unsigned char)lane;
+    if (lane < m) {
+      const int q = (mask >> lane) & 1ull ? before : nS + lane - before;
+      c.perm[q] = (unsigned char)lane;
+      c.inv[lane] = (unsigned char)q;
+    }
   } else if (lane < m) {
     c.perm[lane] = (unsigned char)lane;
+    c.inv[lane] = (unsigned char)lane;
   }
   if (lane == 0) { c.ok = can ? 1 : 0; c.nS = nS; }
   wave_sync();
@@ -673,7 +692,8 @@ __device__ inline void wave_split_decide(const View& v, int u, WaveCtx& c) {
 // Second phase, one wavefront: children's pages, exact statistics and records.  With c.ok == 0 the cluster is
 // only unflagged, with exact statistics.
 template <int DT>
-__device__ inline void wave_split_commit(const View& v, int u, WaveCtx& c) {
+__device__ inline void wave_split_commit(const View& v, int u, WaveCtx& c, const uint32_t (&vahead)[kVAhead],
+                                         int pos_ahead) {
   const int lane = threadIdx.x & 63;
   const size_t cbase = (size_t)u * v.Mcap;
   constexpr int kEs = DT == DYNAKV_F32 ? 4 : 2;
@@ -696,13 +716,25 @@ __device__ inline void wave_split_commit(const View& v, int u, WaveCtx& c) {
       const size_t off = (size_t)(DT == DYNAKV_F32 ? k_index32(r & 15, 4 * ch) : k_index16(r & 15, 8 * ch)) * kEs;
       *(uint4*)(pool + (size_t)dpage * kPageBytes + off) = *(const uint4*)(c.stage + (size_t)i * kRowBytes + ch * 16);
     }
-    // values element by element (their page layout interleaves four tokens), eight loads in flight per lane
-    for (int t0 = 0; t0 < m * kHeadDim; t0 += 8 * 64) {
+    // values element by element (their page layout interleaves four tokens): first those requested ahead
+#pragma unroll
+    for (int k = 0; k < kVAhead; ++k) {
+      const int t = k * 64 + lane, i = t >> 7;
+      if (i < m) {
+        const int q = c.inv[i];
+        const int r = q < nS ? q : q - nS;
+        char* dst = pool + (size_t)c.newpg[(q < nS ? 0 : pS) + (r >> 4)] * kPageBytes;
+        const int e = v_index(DT, r & 15, t & 127);
+        if (DT == DYNAKV_F32) ((uint32_t*)dst)[e] = vahead[k];
+        else ((uint16_t*)dst)[e] = (uint16_t)vahead[k];
+      }
+    }
+    // then the members past those, eight loads in flight per lane
+    for (int t0 = kVAheadMembers * kHeadDim; t0 < m * kHeadDim; t0 += 8 * 64) {
       uint32_t w[8];
 #pragma unroll
       for (int k = 0; k < 8; ++k) {
-        const int t = min(t0 + k * 64 + lane, m * kHeadDim - 1);
-        const int i = c.perm[t >> 7];
+        const int t = min(t0 + k * 64 + lane, m * kHeadDim - 1), i = t >> 7;
         const char* src = pool + (size_t)c.chain[i >> 4] * kPageBytes;
         const int e = v_index(DT, i & 15, t & 127);
         w[k] = DT == DYNAKV_F32 ? ((const uint32_t*)src)[e] : (uint32_t)((const uint16_t*)src)[e];
@@ -711,7 +743,7 @@ __device__ inline void wave_split_commit(const View& v, int u, WaveCtx& c) {
       for (int k = 0; k < 8; ++k) {
         const int t = t0 + k * 64 + lane;
         if (t < m * kHeadDim) {
-          const int q = t >> 7;
+          const int q = c.inv[t >> 7];
           const int r = q < nS ? q : q - nS;
           char* dst = pool + (size_t)c.newpg[(q < nS ? 0 : pS) + (r >> 4)] * kPageBytes;
           const int e = v_index(DT, r & 15, t & 127);
@@ -721,11 +753,10 @@ __device__ inline void wave_split_commit(const View& v, int u, WaveCtx& c) {
       }
     }
     if (lane < m) {
-      const int i = c.perm[lane];
-      const int r = lane < nS ? lane : lane - nS;
-      const int dpage = c.newpg[(lane < nS ? 0 : pS) + (r >> 4)];
-      v.ppos[((size_t)u * v.Pcap + dpage) * kPageTokens + (r & 15)] =
-          v.ppos[((size_t)u * v.Pcap + c.chain[i >> 4]) * kPageTokens + (i & 15)];
+      const int q = c.inv[lane];
+      const int r = q < nS ? q : q - nS;
+      const int dpage = c.newpg[(q < nS ? 0 : pS) + (r >> 4)];
+      v.ppos[((size_t)u * v.Pcap + dpage) * kPageTokens + (r & 15)] = pos_ahead;
     }
   }
   // exact statistics: float32 means, then M2 about those means, members in their new order
@@ -804,22 +835,25 @@ __global__ __launch_bounds__(kSplitThreads) void split_kernel(View v) {
   SplitSmem& s = *(SplitSmem*)raw;
   WaveCtx* const wc = (WaveCtx*)raw;
   const int u = blockIdx.x, tid = threadIdx.x;
+  const size_t cbase = (size_t)u * v.Mcap;
+  // requested together with the flag count, so that the plan below starts one round trip earlier
+  const int c_ahead = tid < min(64, v.Mcap) ? v.flist[cbase + tid] : 0;
+  const int top_ahead = v.free_top[u];
+  const int M0 = v.M[u];
   const int nf0 = v.nflag[u];
   if (nf0 == 0) return;
-  const size_t cbase = (size_t)u * v.Mcap;
-  const int M0 = v.M[u];
 
   // ---- plan: which clusters are split, in which order
   if (nf0 <= 64) {
     if (tid < nf0) {
-      const int c = v.flist[cbase + tid];
+      const int c = c_ahead;
       const int b = v.cb[cbase + c];
       const int4 pg = *(const int4*)&v.cpg[(cbase + c) * kInlinePages];
       pl.id[tid] = c; pl.req[tid] = v.in_req[cbase + c]; pl.cb[tid] = b; pl.m[tid] = v.cn[cbase + c] + b;
       pl.pg[tid][0] = pg.x; pl.pg[tid][1] = pg.y; pl.pg[tid][2] = pg.z; pl.pg[tid][3] = pg.w;
     }
     if (tid >= 64 && tid < 64 + kFreeAhead) {       // everything the page allocation will need, in the same round trips
-      const int top = v.free_top[u], k = tid - 64;
+      const int top = top_ahead, k = tid - 64;
       if (k < top) pl.fl[k] = v.freelist[(size_t)u * v.Pcap + top - 1 - k];
       if (k == 0) { pl.M = M0; pl.top = top; pl.bump = v.bump[u]; pl.fl_base = top; }
     }
@@ -866,13 +900,15 @@ __global__ __launch_bounds__(kSplitThreads) void split_kernel(View v) {
       const int nc = pl.n_cand;
       for (int base = 0; base < nc; base += kWaveSplits) {
         const bool mine = base + wave < nc;
+        uint32_t vahead[kVAhead];
+        int pos_ahead = 0;
         WaveCtx& c = wc[wave];
         if (mine) {
           const int at = pl.cand[base + wave];
           if (lane == 0) { c.j = pl.id[at]; c.m = pl.m[at]; }
           if (lane < kWavePages) c.chain[lane] = pl.pg[at][lane];
           wave_sync();
-          wave_split_decide<DT>(v, u, c);
+          wave_split_decide<DT>(v, u, c, vahead, pos_ahead);
         }
         __syncthreads();
         if (tid == 0) {                    // ids and pages, in the order of the splits
@@ -894,7 +930,7 @@ __global__ __launch_bounds__(kSplitThreads) void split_kernel(View v) {
           }
         }
         __syncthreads();
-        if (mine) wave_split_commit<DT>(v, u, c);
+        if (mine) wave_split_commit<DT>(v, u, c, vahead, pos_ahead);
         __syncthreads();
         if (tid == 0) {                    // the parents' pages are recycled only now
           for (int w = 0; w < kWaveSplits && base + w < nc; ++w) {
