@@ -103,7 +103,7 @@ size_t carve(const dynakv_config_t& c, char* base, View* out) {
   v.kmA_stride = mpad * kHeadDim * 3;                    // up to three 16-bit terms per coordinate
   v.kmA = (uint16_t*)take(U * v.kmA_stride * 2);
   v.hn = (float*)take(U * mpad * 4); v.rmax = (float*)take(U * 4);
-  v.nflagged = (int*)take(U * 4); v.has_empty = (int*)take(U * 4);
+  v.nflagged = (int*)take(U * 4); v.has_empty = (int*)take(U * 4); v.xrange = (int*)take(U * 8);
   if (out) *out = v;
   return off;
 }

@@ -80,6 +80,7 @@ struct View {
   float* rmax;       // [U] max_j |r_j|
   int* nflagged;     // [U] points whose filter gap is below the rounding bound (listed in `order`)
   int* has_empty;    // [U] some cluster got no point in the last assignment
+  int* xrange;       // [U][2] smallest and largest binary exponent among the unit's non-zero prefill keys
 };
 
 __host__ __device__ inline int elem_size(int dtype) { return dtype == DYNAKV_F32 ? 4 : 2; }

@@ -27,6 +27,92 @@ __global__ __launch_bounds__(128) void kmeans_init_kernel(View v, const void* X,
   int p = init_idx[(size_t)u * v.M0 + j];
   p = min(max(p, 0), N0 - 1);
   unit_R(v, u)[r_index(j, d)] = load_elem(X, ((size_t)u * N0 + p) * kHeadDim + d, v.dtype);
+  if (j == 0 && d == 0) { v.xrange[2 * u] = 0x7FFFFFFF; v.xrange[2 * u + 1] = -0x7FFFFFFF; }
+}
+
+// ---- order-free centre sums -----------------------------------------------------------------------------
+// The centre of a cluster is the float64 sum of its members in ascending position, divided by the count.  Every
+// key of a 16-bit type is an integer multiple of 2^q, q = (smallest exponent in the unit) - (mantissa bits), and
+// smaller than 2^(emax+1); if (emax + 1 + ceil(log2 N0)) - q <= 53, every partial sum of any subset in any order
+// is exactly representable, so the sum does not depend on the order at all and the members need not be sorted
+// first: a counting sort that leaves them in arbitrary order is enough.  Units whose keys span too wide a range
+// (and float32 keys, and more than 2048 centres) keep the sorted path.
+constexpr int kAtomicCentres = 2048;
+__global__ __launch_bounds__(256) void kmeans_range_kernel(View v, const void* X, int N0) {
+  const int u = blockIdx.y;
+  if (v.dtype == DYNAKV_F32) return;
+  const uint4* x = (const uint4*)((const uint16_t*)X + (size_t)u * N0 * kHeadDim);
+  const int n16 = N0 * kHeadDim / 8;
+  const int ebits = v.dtype == DYNAKV_F16 ? 5 : 8, mbits = v.dtype == DYNAKV_F16 ? 10 : 7;
+  const int bias = v.dtype == DYNAKV_F16 ? 15 : 127, emask = (1 << ebits) - 1;
+  int lo = 0x7FFFFFFF, hi = -0x7FFFFFFF;
+  for (int i = blockIdx.x * 256 + threadIdx.x; i < n16; i += gridDim.x * 256) {
+    const uint4 w = x[i];
+    const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const uint32_t h = (ww[e >> 1] >> ((e & 1) * 16)) & 0x7FFFu;
+      if (h == 0) continue;
+      const int eb = (int)(h >> mbits) & emask;
+      // subnormals share the grid of the smallest normal exponent; infinities and NaNs make the range unusable
+      const int ex = eb == emask ? 0x3FFFFFFF : (eb == 0 ? 1 : eb) - bias;
+      lo = min(lo, ex); hi = max(hi, ex);
+    }
+  }
+  for (int o = 32; o > 0; o >>= 1) { lo = min(lo, __shfl_xor(lo, o)); hi = max(hi, __shfl_xor(hi, o)); }
+  if ((threadIdx.x & 63) == 0 && hi >= lo) { atomicMin(&v.xrange[2 * u], lo); atomicMax(&v.xrange[2 * u + 1], hi); }
+}
+// Whether unit u qualifies (see above); q receives the grid exponent.
+__device__ inline bool sums_order_free(const View& v, int u, int N0, int* q) {
+  if (v.dtype == DYNAKV_F32 || v.M0 > kAtomicCentres) return false;
+  const int lo = v.xrange[2 * u], hi = v.xrange[2 * u + 1];
+  const int mbits = v.dtype == DYNAKV_F16 ? 10 : 7;
+  if (hi < lo) { *q = 0; return true; }               // all keys zero
+  int L = 0;
+  while ((1 << L) < N0) ++L;
+  *q = lo - mbits;
+  return hi < 0x3FFFFFFF && (hi + 1 + L) - (lo - mbits) <= 53;
+}
+
+// Members of every cluster of the last assignment, in no particular order, for the units whose sums are
+// order-free: a counting sort by label (sizes, their prefix, then one LDS counter per cluster hands out the
+// places).  One workgroup per unit.  Also the cluster sizes and whether any cluster is empty.
+__global__ __launch_bounds__(1024) void kmeans_bucket_kernel(View v, int N0) {
+  __shared__ int cnt[kAtomicCentres], off[kAtomicCentres];
+  __shared__ int sm[64];
+  const int u = blockIdx.x, tid = threadIdx.x;
+  int q;
+  if (!sums_order_free(v, u, N0, &q)) return;
+  for (int j = tid; j < kAtomicCentres; j += 1024) cnt[j] = 0;
+  __syncthreads();
+  const int* lab = v.labels + (size_t)u * v.Ncap;
+  for (int i = tid; i < N0; i += 1024) atomicAdd(&cnt[lab[i]], 1);
+  __syncthreads();
+  int c2[2], tot = 0, empty = 0;
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    const int j = tid * 2 + k;
+    c2[k] = j < v.M0 ? cnt[j] : 0;
+    tot += c2[k];
+    empty |= j < v.M0 && c2[k] == 0;
+  }
+  int total;
+  int run = block_excl_scan(tot, sm, total);
+  int* koff = v.koff + (size_t)u * (v.Mcap + 1);
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    const int j = tid * 2 + k;
+    if (j < v.M0) { off[j] = run; koff[j] = run; v.cn[(size_t)u * v.Mcap + j] = c2[k]; cnt[j] = 0; }
+    run += c2[k];
+  }
+  if (tid == 0) { koff[v.M0] = N0; v.has_empty[u] = 0; }
+  __syncthreads();
+  if (empty) v.has_empty[u] = 1;
+  int* order = v.order + (size_t)u * v.Ncap;
+  for (int i = tid; i < N0; i += 1024) {
+    const int j = lab[i];
+    order[off[j] + atomicAdd(&cnt[j], 1)] = i;
+  }
 }
 
 // One thread per point: nearest centre in exact float64, centres staged through LDS in tiles.
@@ -81,9 +167,11 @@ __global__ __launch_bounds__(256) void kmeans_assign_f64_kernel(View v, const vo
 
 // One workgroup per unit: bitonic sort of (label, position) keys in LDS -> members of every cluster in
 // ascending position, and the start of every cluster in that order.
-__global__ __launch_bounds__(1024) void kmeans_sort_kernel(View v, int N0, int Npad, int pos_bits) {
+__global__ __launch_bounds__(1024) void kmeans_sort_kernel(View v, int N0, int Npad, int pos_bits, int always) {
   __shared__ uint32_t key[kMaxPrefill];
   const int u = blockIdx.x, tid = threadIdx.x;
+  int qx;
+  if (!always && sums_order_free(v, u, N0, &qx)) return;       // the order is only needed for the layout
   const int* lab = v.labels + (size_t)u * v.Ncap;
   for (int i = tid; i < Npad; i += 1024) key[i] = i < N0 ? ((uint32_t)lab[i] << pos_bits) | (uint32_t)i : 0xFFFFFFFFu;
   __syncthreads();
@@ -118,43 +206,48 @@ __global__ __launch_bounds__(1024) void kmeans_sort_kernel(View v, int N0, int N
   }
 }
 
-// Wavefront per cluster, two coordinates per lane: centre = mean of the members, summed in ascending
-// position (Eq. 4).  The wavefront first fetches up to 64 member positions with one load, so the row loads
-// that follow do not wait on each other.  grid (ceil(M0/4), U).
+// Sixteen lanes per cluster, eight coordinates per lane (one 16-byte load per member of a 16-bit type): centre
+// = mean of the members, added one by one in the order of `order` (ascending position after the sort: Eq. 4
+// in the fixed order; any order for the units whose sums are order-free).  The 16 lanes fetch the next 16
+// member positions with one load while the current 16 rows, all in flight at once, are added.
+// grid (ceil(M0/16), U), 256 threads.
+template <int DT>
 __global__ __launch_bounds__(256) void kmeans_update_kernel(View v, const void* X, int N0) {
-  const int u = blockIdx.y, j = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  constexpr int RB = DT == DYNAKV_F32 ? 8 : 16;        // rows in flight per lane
+  const int u = blockIdx.y, j = blockIdx.x * 16 + (threadIdx.x >> 4), c = threadIdx.x & 15;
   if (j >= v.M0) return;
   const int* koff = v.koff + (size_t)u * (v.Mcap + 1);
   const int* order = v.order + (size_t)u * v.Ncap;
   const int b = koff[j], e = koff[j + 1];
+  if (c == 0) v.cn[(size_t)u * v.Mcap + j] = e - b;
   if (e == b) return;
-  double s0 = 0.0, s1 = 0.0;
-  for (int c0 = b; c0 < e; c0 += 64) {
-    const int cn = min(64, e - c0);
-    const int my = lane < cn ? order[c0 + lane] : 0;
-    for (int k0 = 0; k0 < cn; k0 += 8) {   // eight row loads in flight, then added in member order
-      float x0[8], x1[8];
+  double s[8];
 #pragma unroll
-      for (int k = 0; k < 8; ++k) {
-        const int pos = __builtin_amdgcn_readlane(my, min(k0 + k, 63));
-        const size_t i = ((size_t)u * N0 + pos) * kHeadDim + lane * 2;
-        if (k0 + k >= cn) { x0[k] = 0.f; x1[k] = 0.f; }    // +0.0 leaves the sums unchanged
-        else if (v.dtype == DYNAKV_F32) {
-          const float2 t = *(const float2*)((const float*)X + i);
-          x0[k] = t.x; x1[k] = t.y;
-        } else {
-          const uint32_t w = *(const uint32_t*)((const uint16_t*)X + i);
-          x0[k] = v.dtype == DYNAKV_F16 ? f16_to_float((uint16_t)w) : bf16_to_float((uint16_t)w);
-          x1[k] = v.dtype == DYNAKV_F16 ? f16_to_float((uint16_t)(w >> 16)) : bf16_to_float((uint16_t)(w >> 16));
-        }
+  for (int k = 0; k < 8; ++k) s[k] = 0.0;
+  int mine = b + c < e ? order[b + c] : 0;              // lane c holds member c of the current 16
+  for (int q0 = b; q0 < e; q0 += 16) {
+    const int next = q0 + 16 + c < e ? order[q0 + 16 + c] : 0;
+#pragma unroll
+    for (int h = 0; h < 16; h += RB) {
+      if (q0 + h >= e) break;
+      float x[RB][8];
+#pragma unroll
+      for (int k = 0; k < RB; ++k) {
+        const int pos = __shfl(mine, h + k, 16);
+        load8(X, ((size_t)u * N0 + pos) * kHeadDim + c * 8, DT, x[k]);
       }
 #pragma unroll
-      for (int k = 0; k < 8; ++k) { s0 += (double)x0[k]; s1 += (double)x1[k]; }
+      for (int k = 0; k < RB; ++k)
+        if (q0 + h + k < e) {
+#pragma unroll
+          for (int d = 0; d < 8; ++d) s[d] += (double)x[k][d];
+        }
     }
+    mine = next;
   }
   float* R = unit_R(v, u);
-  R[r_index(j, lane * 2)] = (float)(s0 / (double)(e - b));
-  R[r_index(j, lane * 2 + 1)] = (float)(s1 / (double)(e - b));
+#pragma unroll
+  for (int d = 0; d < 8; ++d) R[r_index(j, c * 8 + d)] = (float)(s[d] / (double)(e - b));
 }
 
 // One workgroup per unit: every empty cluster, in ascending id, takes the not-yet-taken point that is
@@ -164,12 +257,11 @@ __global__ __launch_bounds__(256) void kmeans_reseed_kernel(View v, const void* 
   __shared__ int si[256];
   __shared__ int any_empty;
   const int u = blockIdx.x, tid = threadIdx.x;
-  const int* koff = v.koff + (size_t)u * (v.Mcap + 1);
   double* dist = v.dist + (size_t)u * v.Ncap;
   if (!v.has_empty[u]) return;
   (void)any_empty;
   for (int j = 0; j < v.M0; ++j) {
-    if (koff[j + 1] != koff[j]) continue;   // uniform across the block
+    if (v.cn[(size_t)u * v.Mcap + j] != 0) continue;   // uniform across the block
     double bv = -1.0;
     int bi = -1;
     for (int i = tid; i < N0; i += 256) {
@@ -538,10 +630,12 @@ hipError_t launch_build_index(const View& v, const void* K, const void* V, int N
                               void* ws, size_t ws_bytes, hipStream_t st) {
   (void)ws; (void)ws_bytes;
   kmeans_init_kernel<<<dim3(v.M0, v.U), 128, 0, st>>>(v, K, N0, init_idx);
+  kmeans_range_kernel<<<dim3(16, v.U), 256, 0, st>>>(v, K, N0);
   int Npad = 2, pos_bits = 1;
   while (Npad < N0) { Npad <<= 1; ++pos_bits; }
   const dim3 gpts((N0 + 255) / 256, v.U);
   const bool mfma = v.dtype != DYNAKV_F32;     // float32 keys keep the plain float64 scan
+  const bool atomic_path = mfma && v.M0 <= kAtomicCentres;   // per unit, the kernels decide by the keys' range
   const dim3 gprep(((v.M0 + 31) / 32 * 32 + 255) / 256, v.U);
   for (int it = 0; it < iters; ++it) {
     if (mfma) {
@@ -558,9 +652,13 @@ hipError_t launch_build_index(const View& v, const void* K, const void* V, int N
     } else {
       kmeans_assign_f64_kernel<<<gpts, 256, 0, st>>>(v, K, N0);
     }
-    kmeans_sort_kernel<<<v.U, 1024, 0, st>>>(v, N0, Npad, pos_bits);
+    kmeans_sort_kernel<<<v.U, 1024, 0, st>>>(v, N0, Npad, pos_bits, it + 1 == iters);
+    if (atomic_path && it + 1 < iters) kmeans_bucket_kernel<<<v.U, 1024, 0, st>>>(v, N0);
     if (it + 1 < iters) kmeans_dist_kernel<<<gpts, 256, 0, st>>>(v, K, N0);
-    kmeans_update_kernel<<<dim3((v.M0 + 3) / 4, v.U), 256, 0, st>>>(v, K, N0);
+    const dim3 gupd((v.M0 + 15) / 16, v.U);
+    if (v.dtype == DYNAKV_F32) kmeans_update_kernel<DYNAKV_F32><<<gupd, 256, 0, st>>>(v, K, N0);
+    else if (v.dtype == DYNAKV_F16) kmeans_update_kernel<DYNAKV_F16><<<gupd, 256, 0, st>>>(v, K, N0);
+    else kmeans_update_kernel<DYNAKV_BF16><<<gupd, 256, 0, st>>>(v, K, N0);
     if (it + 1 < iters) kmeans_reseed_kernel<<<v.U, 256, 0, st>>>(v, K, N0);
   }
   point_dist_kernel<<<gpts, 256, 0, st>>>(v, K, N0);
