@@ -576,7 +576,7 @@ __global__ __launch_bounds__(1024) void finalize_kernel(View v, int N0) {
       v.cn[cb + j] = 0; v.cM2[cb + j] = 0.0; v.ctail[cb + j] = -1;
       for (int p = 0; p < kInlinePages; ++p) v.cpg[(cb + j) * kInlinePages + p] = -1;
     }
-    v.cb[cb + j] = 0; v.cflag[cb + j] = 0; v.in_req[cb + j] = 0;
+    v.cb[cb + j] = 0; v.cflag[cb + j] = 0; v.in_req[cb + j] = 0; v.score[cb + j] = 0.f;
   }
   if (v.dtype != DYNAKV_F32) {               // search copy of the final centroids
     const float* R = unit_R(v, u);

@@ -283,6 +283,21 @@ def test_whole_step_call_at_the_capacity_limits(env, monkeypatch):
     assert st["n_tokens"][0] == 68 and st["error"][0] & binding.ERR_TOKENS
 
 
+def test_prefill_with_a_wide_key_range_sums_in_storage_order():
+    """Keys whose exponents span too many bits for order-free centre sums: the k-means update must add the
+    members in ascending position, like the oracle (bfloat16, a few keys scaled far up and far down)."""
+    s = WorkloadSpec("wide", "bf16", 2, 2, 1500, 4, 24, 256, 6, 0.05, var_alpha=0.0, size_factor=0.0, seed=123)
+    w = generate(s)
+    K0 = w["K0"].copy()
+    K0[:, 5] *= 2.0 ** 30
+    K0[:, 77] *= 2.0 ** 30
+    K0[:, 300:303] *= 2.0 ** -40
+    ix, o = make_pair(s, 2, kmeans_iters=5)
+    ix.dynakv_build_index(to_dev(K0, "bf16"), to_dev(w["V0"], "bf16"), torch.from_numpy(w["init_idx"]).to(DEV))
+    o.build_index(K0, w["V0"], w["init_idx"])
+    compare_state(ix, o, "wide-range build")
+
+
 def test_rebuild_resets_the_index_and_runs_are_deterministic():
     s = CONFIGS["tiny"].scaled(prefill=777, n_clusters_init=19)
     w = generate(s, steps=8)
