@@ -130,7 +130,7 @@ dynakv_status_t dynakv_split(dynakv_index_t* index, void* stream);
  * v_new) and dynakv_split(), in that order and with the same results bit for bit, so the three calls and
  * this one can be mixed freely.  It exists because the step's two passes over the centroid table (query
  * similarity, Section 4.1; nearest cluster of the new key, Section 4.2) read the same data: with at least
- * 256 units one kernel makes both in a single pass.  Arguments as in the three calls. */
+ * 32 units one kernel makes both in a single pass.  Arguments as in the three calls. */
 dynakv_status_t dynakv_decode_step(dynakv_index_t* index, const void* Q, int32_t token_budget, float* out,
                                    float* lse, const void* k_new, const void* v_new, void* stream);
 
@@ -162,7 +162,7 @@ typedef struct {
 dynakv_status_t dynakv_export_state(dynakv_index_t* index, const dynakv_state_t* dst, void* stream);
 
 /* Timing aid: when enabled, the dominant kernel of dynakv_retrieve_attend / dynakv_decode_step (gather +
- * attention; with at least 256 units the single kernel that also scores and selects and, in a decode step,
+ * attention; with at least 32 units the single kernel that also scores and selects and, in a decode step,
  * appends) is bracketed by HIP events on its own stream.  dynakv_profile_read synchronises those events and
  * returns the number of launches and their summed duration in milliseconds since the last enable. */
 dynakv_status_t dynakv_profile_enable(dynakv_index_t* index, int32_t max_launches);

@@ -41,11 +41,14 @@ int pow2_floor(int x) {
   return p;
 }
 
-// Shape of the gather + attention launch: S workgroups per unit (at least one workgroup per compute unit
-// of the chip) of NW wavefronts each (about 4096 wavefronts in all; the workgroup merge needs
-// NW * G * 130 floats of LDS).  DYNAKV_KV_SPLITS / DYNAKV_ATT_WAVES override for tuning runs.
+// Shape of the gather + attention launch: S workgroups per unit of NW wavefronts each (the workgroup merge
+// needs NW * G * 130 floats of LDS).  One workgroup per unit from 32 units on: the step is bound by dependent
+// round trips to memory rather than by the number of busy compute units, and every further workgroup per unit
+// adds partial results, a ticket and a merge (measured on the 8-unit configuration: 4 workgroups per unit
+// beat 1, 2, 8, 16 and 32; with 112 and 128 units 1 beats 2 and 3).  With S = 1 the single-kernel retrieval
+// runs.  DYNAKV_KV_SPLITS / DYNAKV_ATT_WAVES override for tuning runs.
 void plan_attention(const dynakv_config_t& c, int* S, int* NW) {
-  int s = (256 + c.n_units - 1) / c.n_units;
+  int s = (32 + c.n_units - 1) / c.n_units;
   int nw = pow2_floor(4096 / (c.n_units * s) > 0 ? 4096 / (c.n_units * s) : 1);
   if (const char* e = std::getenv("DYNAKV_KV_SPLITS")) s = std::atoi(e);
   if (const char* e = std::getenv("DYNAKV_ATT_WAVES")) nw = std::atoi(e);

@@ -599,20 +599,28 @@ template <> struct Frag<DYNAKV_F16> : Frag16<false> {};
 template <> struct Frag<DYNAKV_BF16> : Frag16<true> {};
 
 // Merges `n` partial results (running max in the log2 domain, denominator, one accumulator) that sit
-// `stride` floats apart.
+// `stride` floats apart.  DEVICE: the partial results were written by other workgroups (see st_device).
+template <bool DEVICE = false>
 __device__ inline void merge_partials(const float* mx, const float* den, const float* acc, int n, int stride,
                                       float& M, float& L, float& O) {
+  auto ld = [](const float* p) {
+    return DEVICE ? __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : *p;
+  };
   M = -__builtin_inff();
-  for (int w = 0; w < n; ++w) M = fmaxf(M, mx[(size_t)w * stride]);
+  for (int w = 0; w < n; ++w) M = fmaxf(M, ld(mx + (size_t)w * stride));
   L = 0.f; O = 0.f;
   for (int w = 0; w < n; ++w) {
-    const float mw = mx[(size_t)w * stride];
+    const float mw = ld(mx + (size_t)w * stride);
     if (mw == -__builtin_inff()) continue;
     const float sc = __builtin_amdgcn_exp2f(mw - M);
-    L += sc * den[(size_t)w * stride];
-    O += sc * acc[(size_t)w * stride];
+    L += sc * ld(den + (size_t)w * stride);
+    O += sc * ld(acc + (size_t)w * stride);
   }
 }
+// Store that other workgroups of the device can read back (with the matching load above) once it has completed,
+// without any cache-wide write-back or invalidation: both go past the caches that are not coherent across the
+// chip.  A device-scope fence would do the same for all memory at a cost that grows with every workgroup.
+__device__ inline void st_device(float* p, float x) { __hip_atomic_store(p, x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 
 // Per-wavefront running state of the online softmax.
 struct Softmax {
@@ -729,24 +737,24 @@ __global__ __launch_bounds__(NW * 64) void gather_attend_kernel(View v, const vo
       out[((size_t)u * G + gg) * kHeadDim + dc] = L > 0.f ? O / L : 0.f;
       if (lse && dc == 0) lse[(size_t)u * G + gg] = L > 0.f ? (M + __builtin_amdgcn_logf(L)) * kLn2 : -__builtin_inff();
     } else {
-      part[gg * hs + dc] = O;
-      if (dc == 0) { part[gg * hs + kHeadDim] = M; part[gg * hs + kHeadDim + 1] = L; }
+      st_device(&part[gg * hs + dc], O);
+      if (dc == 0) { st_device(&part[gg * hs + kHeadDim], M); st_device(&part[gg * hs + kHeadDim + 1], L); }
     }
   }
   if (S == 1) return;
-  // the last workgroup of the unit to arrive merges all partial results
-  __threadfence();
+  // the last workgroup of the unit to arrive merges all partial results: every thread waits for its own stores
+  // to complete, the barrier collects the workgroup, then one thread takes the ticket
+  __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
   if (threadIdx.x == 0) s_last = atomicAdd(&v.ticket[u], 1) == S - 1;
   __syncthreads();
   if (!s_last) return;
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
   const float* all = v.part + (size_t)u * S * ws;
   for (int t = threadIdx.x; t < G * kHeadDim; t += NW * 64) {
     const int gg = t / kHeadDim, dc = t % kHeadDim;
     const float* b = all + gg * hs;
     float M, L, O;
-    merge_partials(b + kHeadDim, b + kHeadDim + 1, b + dc, S, ws, M, L, O);
+    merge_partials<true>(b + kHeadDim, b + kHeadDim + 1, b + dc, S, ws, M, L, O);
     out[((size_t)u * G + gg) * kHeadDim + dc] = L > 0.f ? O / L : 0.f;
     if (lse && dc == 0) lse[(size_t)u * G + gg] = L > 0.f ? (M + __builtin_amdgcn_logf(L)) * kLn2 : -__builtin_inff();
   }
