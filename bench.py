@@ -64,8 +64,8 @@ def main():
     ap.add_argument("--no-kernel-events", action="store_true", help="skip the HIP events around the dominant kernel")
     a = ap.parse_args()
     if a.gpus != 1:
-        sys.exit("bench.py: this path runs on one GPU; units are independent and shard without communication "
-                 "(see DESIGN.md), but no multi-GPU run exists here. Use --gpus 1.")
+        sys.exit("bench.py: this path runs on one GPU; units (layer, sequence, KV head) are independent and would "
+                 "shard over GPUs without communication, but no multi-GPU run exists here. Use --gpus 1.")
 
     import numpy as np
     import torch
