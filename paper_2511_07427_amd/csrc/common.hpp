@@ -86,24 +86,23 @@ struct View {
 __host__ __device__ inline int elem_size(int dtype) { return dtype == DYNAKV_F32 ? 4 : 2; }
 
 // ---- page layout -----------------------------------------------------------------------------
-// A page stores 16 tokens in the register order of the matrix instructions that consume it, so
-// that one wavefront load of 16 bytes per lane is fully contiguous.
-//   16-bit types: K region [4 k-steps][64 lanes][8]: lane = (d%32)/8*16 + slot holds dims 32*ks + 8*(lane/16) + e
-//                 V region [4][64 lanes][2][4]:      lane = slot/4*16 + d%16 holds tokens 4*(lane/16) + i of
-//                                                    columns 16*(2*c + h) + lane%16
-//   float32:      K region [8][64 lanes][4]:         dims 16*s + 4*(lane/16) + i
-//                 V region [8][64 lanes][4]:         tokens 4*(lane/16) + kk of column 16*cb + lane%16
+// A page stores 16 tokens so that the matrix instructions that consume it load 16 bytes per lane and that
+// the bytes fetched follow the valid tokens as closely as 64-byte memory sectors allow.
+//   K region [16 slots][128]: one row per token.  In QK^T lane l holds token slot l%16 and, per k-step s, the
+//                 16 bytes at row offset 64*s + 16*(l/16) (dims 32s + 8*(l/16) + e for 16-bit types, 16s +
+//                 4*(l/16) + i for float32): four lanes cover one 64-byte sector of one token, so a page with
+//                 n valid tokens costs exactly n rows.
+//   V region, 16-bit types [4][64 lanes][2][4]: lane = slot/4*16 + d%16 holds tokens 4*(lane/16) + i of
+//                 columns 16*(2*c + h) + lane%16 (the PV instruction wants the tokens of one column together,
+//                 so V is fetched in groups of four token slots);
+//             float32 [8][64 lanes][4]: tokens 4*(lane/16) + kk of column 16*cb + lane%16.
 // Offsets are in elements from the start of the page; the V region starts at 2048.
-__host__ __device__ inline int k_index16(int slot, int d) {
-  return (d >> 5) * 512 + ((((d & 31) >> 3) << 4) + slot) * 8 + (d & 7);
-}
+__host__ __device__ inline int k_index16(int slot, int d) { return slot * kHeadDim + d; }
 __host__ __device__ inline int v_index16(int slot, int d) {
   const int cb = d >> 4;
   return 2048 + (cb >> 1) * 512 + (((slot >> 2) << 4) + (d & 15)) * 8 + (cb & 1) * 4 + (slot & 3);
 }
-__host__ __device__ inline int k_index32(int slot, int d) {
-  return (d >> 4) * 256 + ((((d & 15) >> 2) << 4) + slot) * 4 + (d & 3);
-}
+__host__ __device__ inline int k_index32(int slot, int d) { return slot * kHeadDim + d; }
 __host__ __device__ inline int v_index32(int slot, int d) {
   return 2048 + (d >> 4) * 256 + (((slot >> 2) << 4) + (d & 15)) * 4 + (slot & 3);
 }

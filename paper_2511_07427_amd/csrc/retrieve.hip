@@ -476,7 +476,7 @@ constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
 // come from four different pages.  Lane l multiplies token slot l % 16 in QK^T (entry slot / 4, row slot % 4 of
 // that quad) and the four tokens of entry l / 16 in PV, so every lane has its own two page addresses.
 struct Tile {
-  const char* k;     // this lane's first 16 bytes of the K region (further k-steps 1 KB apart)
+  const char* k;     // this lane's first 16 bytes of its token's K row (further k-steps 64 bytes apart)
   const char* v;     // this lane's first 16 bytes of the V region
   bool kok;          // the lane's token slot holds a token
   int nvq;           // valid tokens in the lane's PV quad (0: no entry)
@@ -488,7 +488,7 @@ __device__ inline Tile make_tile(const char* pages, int eK, int eV, int lane) {
   Tile t;
   t.kok = eK >= 0 && (lane & 3) <= (eK & 3);
   if (eK < 0) eK = 0;
-  t.k = pages + (size_t)(eK >> 4) * kPageBytes + ((lane & 48) + ((eK >> 2) & 3) * 4 + (lane & 3)) * 16;
+  t.k = pages + (size_t)(eK >> 4) * kPageBytes + (((eK >> 2) & 3) * 4 + (lane & 3)) * (kHeadDim * ES) + (lane >> 4) * 16;
   t.nvq = eV >= 0 ? (eV & 3) + 1 : 0;
   if (eV < 0) eV = 0;
   t.v = pages + (size_t)(eV >> 4) * kPageBytes + 2048 * ES + (((eV >> 2) & 3) * 16 + (lane & 15)) * 16;
@@ -513,7 +513,7 @@ struct Frag<DYNAKV_F32> {
     const f4* kp = (const f4*)t.k;
     const f4* vp = (const f4*)t.v;
 #pragma unroll
-    for (int s = 0; s < 8; ++s) f.k[s] = t.kok ? kp[s * 64] : f4{0, 0, 0, 0};
+    for (int s = 0; s < 8; ++s) f.k[s] = t.kok ? kp[s * 4] : f4{0, 0, 0, 0};
 #pragma unroll
     for (int c = 0; c < 8; ++c) f.v[c] = t.nvq ? vp[c * 64] : f4{0, 0, 0, 0};
   }
@@ -546,7 +546,7 @@ struct Frag16 {
     const uint4* kp = (const uint4*)t.k;
     const uint4* vp = (const uint4*)t.v;
 #pragma unroll
-    for (int s = 0; s < 4; ++s) f.k[s] = t.kok ? kp[s * 64] : uint4{0, 0, 0, 0};
+    for (int s = 0; s < 4; ++s) f.k[s] = t.kok ? kp[s * 4] : uint4{0, 0, 0, 0};
 #pragma unroll
     for (int c = 0; c < 4; ++c) f.v[c] = t.nvq ? vp[c * 64] : uint4{0, 0, 0, 0};
   }
