@@ -12,7 +12,7 @@ struct AppendSmem {
   double bs[16];             // block sums of the M2 increment
   double m2, tau;
   int cn, cb, ctail, cflag, nflag, free_top, bump, free_page;
-  int ok, commit, page, slot, fresh;
+  int ok, commit, page, slot;
 };
 
 // What one thread fetches for an append: thread d < 128 coordinate d of the centroid, threads 128..136 one field
@@ -86,7 +86,7 @@ __device__ inline void append_commit(const View& v, int u, int j, int M, int N, 
     const int sz = a.cn + a.cb;
     const int slot = sz % kPageTokens;
     int page = a.ctail;
-    int ok = 1, fresh = 0;
+    int ok = 1;
     if (slot == 0) {                      // no page yet, or the tail page is full
       int np = -1;                        // from the free stack, else from the untouched tail of the pool
       if (a.free_top > 0) {
@@ -95,7 +95,6 @@ __device__ inline void append_commit(const View& v, int u, int j, int M, int N, 
       } else if (a.bump < v.Pcap) {
         np = a.bump;
         v.bump[u] = a.bump + 1;
-        fresh = 1;
       }
       if (np < 0) {
         v.err[u] |= DYNAKV_ERR_TOKENS;
@@ -136,17 +135,12 @@ __device__ inline void append_commit(const View& v, int u, int j, int M, int N, 
       v.N[u] = N + 1;
       v.ppos[((size_t)u * v.Pcap + page) * kPageTokens + slot] = N;
     }
-    a.ok = ok; a.commit = commit; a.page = page; a.slot = slot; a.fresh = fresh;
+    a.ok = ok; a.commit = commit; a.page = page; a.slot = slot;
   }
   __syncthreads();
   if (!a.ok) return;
   if (a.commit && tid < kHeadDim) store_centroid(v, u, j, tid, (float)a.r1[tid]);
   char* pg = page_ptr(v, u, a.page);
-  if (a.fresh) {                          // first use of this page: unused slots must hold finite values
-    const int n16 = kPageElems * elem_size(v.dtype) / 16;
-    for (int i = tid; i < n16; i += NT) ((uint4*)pg)[i] = uint4{0, 0, 0, 0};
-    __syncthreads();
-  }
   if (tid < kHeadDim) copy_elem(pg, k_index(v.dtype, a.slot, tid), kin, (size_t)u * kHeadDim + tid, v.dtype);
   else if (tid < 2 * kHeadDim)
     copy_elem(pg, v_index(v.dtype, a.slot, tid - kHeadDim), vin, (size_t)u * kHeadDim + tid - kHeadDim, v.dtype);

@@ -86,26 +86,19 @@ struct View {
 __host__ __device__ inline int elem_size(int dtype) { return dtype == DYNAKV_F32 ? 4 : 2; }
 
 // ---- page layout -----------------------------------------------------------------------------
-// A page stores 16 tokens so that the matrix instructions that consume it load 16 bytes per lane and that
-// the bytes fetched follow the valid tokens as closely as 64-byte memory sectors allow.
-//   K region [16 slots][128]: one row per token.  In QK^T lane l holds token slot l%16 and, per k-step s, the
-//                 16 bytes at row offset 64*s + 16*(l/16) (dims 32s + 8*(l/16) + e for 16-bit types, 16s +
-//                 4*(l/16) + i for float32): four lanes cover one 64-byte sector of one token, so a page with
-//                 n valid tokens costs exactly n rows.
-//   V region, 16-bit types [4][64 lanes][2][4]: lane = slot/4*16 + d%16 holds tokens 4*(lane/16) + i of
-//                 columns 16*(2*c + h) + lane%16 (the PV instruction wants the tokens of one column together,
-//                 so V is fetched in groups of four token slots);
-//             float32 [8][64 lanes][4]: tokens 4*(lane/16) + kk of column 16*cb + lane%16.
+// A page stores 16 tokens: a K region and a V region, each [16 slots][128], one row per token, so that the
+// bytes fetched follow the valid tokens exactly: a page with n valid tokens costs n K rows and n V rows.
+// In the attention kernels lane l holds token slot l%16 and, per piece s, the 16 bytes at row offset
+// 64*s + 16*(l/16) of that token's K row and of its V row (dims 32s + 8*(l/16) + e for 16-bit types, 16s +
+// 4*(l/16) + i for float32): four lanes cover one 64-byte sector of one token.  QK^T consumes the K pieces as
+// loaded; PV wants the four tokens of one column together, so the V pieces are transposed on chip.
+// Every load of a slot is masked by the cluster's size, so slots that hold no token are never read and pages
+// need no initialisation.
 // Offsets are in elements from the start of the page; the V region starts at 2048.
 __host__ __device__ inline int k_index16(int slot, int d) { return slot * kHeadDim + d; }
-__host__ __device__ inline int v_index16(int slot, int d) {
-  const int cb = d >> 4;
-  return 2048 + (cb >> 1) * 512 + (((slot >> 2) << 4) + (d & 15)) * 8 + (cb & 1) * 4 + (slot & 3);
-}
+__host__ __device__ inline int v_index16(int slot, int d) { return 2048 + slot * kHeadDim + d; }
 __host__ __device__ inline int k_index32(int slot, int d) { return slot * kHeadDim + d; }
-__host__ __device__ inline int v_index32(int slot, int d) {
-  return 2048 + (d >> 4) * 256 + (((slot >> 2) << 4) + (d & 15)) * 4 + (slot & 3);
-}
+__host__ __device__ inline int v_index32(int slot, int d) { return 2048 + slot * kHeadDim + d; }
 __host__ __device__ inline int k_index(int dtype, int slot, int d) {
   return dtype == DYNAKV_F32 ? k_index32(slot, d) : k_index16(slot, d);
 }
@@ -421,24 +414,6 @@ __device__ inline void block_arg_reduce(double val, int idx, double* sv, int* si
   }
 }
 
-// Takes a page from the unit's free stack, else from the untouched tail of its pool (then *fresh = 1: the
-// caller must zero it before use); -1 if none is left.  One thread per unit calls this at a time.
-__device__ inline int alloc_page(const View& v, int u, int* fresh) {
-  int top = v.free_top[u];
-  *fresh = 0;
-  if (top > 0) {
-    --top;
-    v.free_top[u] = top;
-    return v.freelist[(size_t)u * v.Pcap + top];
-  }
-  const int b = v.bump[u];
-  if (b < v.Pcap) {
-    v.bump[u] = b + 1;
-    *fresh = 1;
-    return b;
-  }
-  return -1;
-}
 __device__ inline int pages_available(const View& v, int u) { return v.free_top[u] + (v.Pcap - v.bump[u]); }
 __device__ inline void free_page(const View& v, int u, int page) {
   const int top = v.free_top[u];

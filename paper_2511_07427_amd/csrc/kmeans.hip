@@ -12,15 +12,6 @@ namespace dynakv {
 
 namespace {
 
-// Zeroes the pages the layout is about to use (unused slots of a page must hold finite values: masked
-// tokens are multiplied by P = 0).  Pages handed out later are zeroed when they leave the untouched pool.
-__global__ __launch_bounds__(256) void zero_pages_kernel(View v) {
-  const int u = blockIdx.y;
-  const size_t n16 = (size_t)v.bump[u] * kPageElems * elem_size(v.dtype) / 16;
-  uint4* p = (uint4*)page_ptr(v, u, 0);
-  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) p[i] = uint4{0, 0, 0, 0};
-}
-
 // R[u][j] = key at position init_idx[u][j]
 __global__ __launch_bounds__(128) void kmeans_init_kernel(View v, const void* X, int N0, const int* init_idx) {
   const int u = blockIdx.y, j = blockIdx.x, d = threadIdx.x;
@@ -596,7 +587,7 @@ __global__ __launch_bounds__(1024) void finalize_kernel(View v, int N0) {
 }
 
 // 16 consecutive entries of the sorted order per workgroup, 16 threads per entry, 8 coordinates per thread:
-// keys move as whole 16-byte operand chunks, values are scattered into the token-interleaved V layout.
+// keys and values move as whole 16-byte chunks of their token's rows.
 __global__ __launch_bounds__(256) void layout_copy_kernel(View v, const void* K, const void* V, int N0) {
   const int u = blockIdx.y, q = blockIdx.x * 16 + (threadIdx.x >> 4), c = threadIdx.x & 15;
   if (q >= N0) return;
@@ -611,15 +602,11 @@ __global__ __launch_bounds__(256) void layout_copy_kernel(View v, const void* K,
     const f4* vs = (const f4*)((const float*)V + src);
     *(f4*)((float*)pg + k_index32(slot, c * 8)) = ks[0];
     *(f4*)((float*)pg + k_index32(slot, c * 8 + 4)) = ks[1];
-    const f4 a = vs[0], b = vs[1];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) ((float*)pg)[v_index32(slot, c * 8 + e)] = e < 4 ? a[e] : b[e - 4];
+    *(f4*)((float*)pg + v_index32(slot, c * 8)) = vs[0];
+    *(f4*)((float*)pg + v_index32(slot, c * 8 + 4)) = vs[1];
   } else {
     *(uint4*)((uint16_t*)pg + k_index16(slot, c * 8)) = *(const uint4*)((const uint16_t*)K + src);
-    const uint4 w = *(const uint4*)((const uint16_t*)V + src);
-    const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
-#pragma unroll
-    for (int e = 0; e < 8; ++e) ((uint16_t*)pg)[v_index16(slot, c * 8 + e)] = (uint16_t)(ww[e >> 1] >> ((e & 1) * 16));
+    *(uint4*)((uint16_t*)pg + v_index16(slot, c * 8)) = *(const uint4*)((const uint16_t*)V + src);
   }
   if (c == 0) v.ppos[((size_t)u * v.Pcap + page) * kPageTokens + slot] = pos;
 }
@@ -663,7 +650,6 @@ hipError_t launch_build_index(const View& v, const void* K, const void* V, int N
   }
   point_dist_kernel<<<gpts, 256, 0, st>>>(v, K, N0);
   finalize_kernel<<<v.U, 1024, 0, st>>>(v, N0);
-  zero_pages_kernel<<<dim3(16, v.U), 256, 0, st>>>(v);
   layout_copy_kernel<<<dim3((N0 + 15) / 16, v.U), 256, 0, st>>>(v, K, V, N0);
   return hipGetLastError();
 }

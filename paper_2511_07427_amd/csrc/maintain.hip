@@ -392,32 +392,23 @@ __device__ __forceinline__ void split_cluster_impl(const View& v, int u, int j, 
     const bool last = k == pS - 1 || k == need - 1;
     v.pnext[(size_t)u * v.Pcap + s.newpg[k]] = last ? -1 : s.newpg[k + 1];
   }
-  if (need > from_free) {                 // pages never used before are zeroed first
-    constexpr int n16 = kPageElems * kEs / 16;
-    for (int t = tid; t < (need - from_free) * n16; t += NT)
-      ((uint4*)(pool + (size_t)s.newpg[from_free + t / n16] * (kPageElems * kEs)))[t % n16] = uint4{0, 0, 0, 0};
-    __syncthreads();
-  }
-  // keys in 16-byte chunks, values element by element (their page layout interleaves four tokens)
+  // keys and values in 16-byte chunks of their rows (the V row of a slot lies one K region after its K row)
+  constexpr size_t kVRegion = (size_t)kPageTokens * kHeadDim * kEs;
+#pragma unroll 2
   for (int t = tid; t < m * kChunks; t += NT) {
     const int q = t / kChunks, c = t % kChunks;
     const int i = s.perm[q];
     const int r = q < nS ? q : q - nS;
     const int dpage = s.newpg[(q < nS ? 0 : pS) + (r >> 4)];
+    const char* src = pool + (size_t)s.chain[i >> 4] * (kPageElems * kEs) + kchunk(i & 15, c);
+    char* dst = pool + (size_t)dpage * (kPageElems * kEs) + kchunk(r & 15, c);
     uint4 w;
     if constexpr (STAGED) w = *(const uint4*)(s.stage + (size_t)i * kRowBytes + c * 16);
-    else w = *(const uint4*)(pool + (size_t)s.chain[i >> 4] * (kPageElems * kEs) + kchunk(i & 15, c));
-    *(uint4*)(pool + (size_t)dpage * (kPageElems * kEs) + kchunk(r & 15, c)) = w;
-  }
-#pragma unroll 4
-  for (int t = tid; t < m * kHeadDim; t += NT) {
-    const int q = t >> 7, d = t & 127;
-    const int i = s.perm[q];
-    const int r = q < nS ? q : q - nS;
-    const int dpage = s.newpg[(q < nS ? 0 : pS) + (r >> 4)];
-    copy_elem(pool + (size_t)dpage * (kPageElems * kEs), v_index(DT, r & 15, d),
-              pool + (size_t)s.chain[i >> 4] * (kPageElems * kEs), v_index(DT, i & 15, d), DT);
-    if (d == 0)
+    else w = *(const uint4*)src;
+    const uint4 x = *(const uint4*)(src + kVRegion);
+    *(uint4*)dst = w;
+    *(uint4*)(dst + kVRegion) = x;
+    if (c == 0)
       v.ppos[((size_t)u * v.Pcap + dpage) * kPageTokens + (r & 15)] =
           v.ppos[((size_t)u * v.Pcap + s.chain[i >> 4]) * kPageTokens + (i & 15)];
   }
@@ -475,9 +466,10 @@ constexpr int kWaveSplits = kSplitThreads / 64;
 constexpr int kWaveStage = 64 * kStageRow16 * 2;                 // 64 rows of a 16-bit type, 32 of float32
 static_assert(32 * kStageRow32 * 4 <= kWaveStage, "float32 rows must fit");
 constexpr int kWavePages = 64 / kPageTokens;                     // pages of the largest such cluster
-// Values of the first 16 members (element t = 64k + lane of the member-major [m][128] array, k < 32) are
-// requested together with the keys and wait in registers until the children's pages are known.
-constexpr int kVAhead = 32, kVAheadMembers = kVAhead * 64 / kHeadDim;
+// Values of the first members (16-byte chunk t = 64k + lane of the member-major array of V rows, k < kVAhead:
+// 16 members of a 16-bit type, 8 of float32) are requested together with the keys and wait in registers until
+// the children's pages are known.
+constexpr int kVAhead = 4;
 
 struct WaveCtx {
   alignas(16) unsigned char stage[kWaveStage];
@@ -487,7 +479,7 @@ struct WaveCtx {
   double m2[2];
   unsigned char side[64], perm[64], inv[64];     // inv[member] = its place in perm
   int chain[kWavePages], newpg[kWavePages + 2];
-  int j, m, ok, nS, idM, fresh_from;     // fresh_from: newpg[k] with k >= fresh_from were never used before
+  int j, m, ok, nS, idM;
 };
 
 __device__ __forceinline__ void wave_sync() {   // LDS written by some lanes of this wavefront, read by others
@@ -576,7 +568,7 @@ __device__ __forceinline__ void wave_sums(const WaveCtx& c, int q0, int q1, int 
 // First phase, one wavefront: stage the keys (c.chain lists their pages), 2-means, stable partition.  Sets
 // c.ok, c.nS, c.perm.
 template <int DT>
-__device__ inline void wave_split_decide(const View& v, int u, WaveCtx& c, uint32_t (&vahead)[kVAhead], int& pos_ahead) {
+__device__ inline void wave_split_decide(const View& v, int u, WaveCtx& c, uint4 (&vahead)[kVAhead], int& pos_ahead) {
   const int lane = threadIdx.x & 63;
   constexpr int kEs = DT == DYNAKV_F32 ? 4 : 2;
   constexpr int kChunks = kHeadDim * kEs / 16;
@@ -600,12 +592,11 @@ __device__ inline void wave_split_decide(const View& v, int u, WaveCtx& c, uint3
   }
 #pragma unroll
   for (int k = 0; k < kVAhead; ++k) {
-    const int t = k * 64 + lane, i = t >> 7;
-    vahead[k] = 0;
+    const int t = k * 64 + lane, i = t / kChunks, ch = t % kChunks;
+    vahead[k] = uint4{0, 0, 0, 0};
     if (i < m) {
-      const char* src = pool + (size_t)c.chain[i >> 4] * (kPageElems * kEs);
-      const int e = v_index(DT, i & 15, t & 127);
-      vahead[k] = DT == DYNAKV_F32 ? ((const uint32_t*)src)[e] : (uint32_t)((const uint16_t*)src)[e];
+      const size_t off = (size_t)(DT == DYNAKV_F32 ? v_index32(i & 15, 4 * ch) : v_index16(i & 15, 8 * ch)) * kEs;
+      vahead[k] = *(const uint4*)(pool + (size_t)c.chain[i >> 4] * (kPageElems * kEs) + off);
     }
   }
   pos_ahead = lane < m ? v.ppos[((size_t)u * v.Pcap + c.chain[lane >> 4]) * kPageTokens + (lane & 15)] : 0;
@@ -692,7 +683,7 @@ __device__ inline void wave_split_decide(const View& v, int u, WaveCtx& c, uint3
 // Second phase, one wavefront: children's pages, exact statistics and records.  With c.ok == 0 the cluster is
 // only unflagged, with exact statistics.
 template <int DT>
-__device__ inline void wave_split_commit(const View& v, int u, WaveCtx& c, const uint32_t (&vahead)[kVAhead],
+__device__ inline void wave_split_commit(const View& v, int u, WaveCtx& c, const uint4 (&vahead)[kVAhead],
                                          int pos_ahead) {
   const int lane = threadIdx.x & 63;
   const size_t cbase = (size_t)u * v.Mcap;
@@ -705,9 +696,6 @@ __device__ inline void wave_split_commit(const View& v, int u, WaveCtx& c, const
   const int pS = (nS + kPageTokens - 1) / kPageTokens, pM = (nM + kPageTokens - 1) / kPageTokens, need = pS + pM;
   if (c.ok) {
     if (lane < need) v.pnext[(size_t)u * v.Pcap + c.newpg[lane]] = (lane == pS - 1 || lane == need - 1) ? -1 : c.newpg[lane + 1];
-    constexpr int n16 = (int)(kPageBytes / 16);
-    for (int k = c.fresh_from; k < need; ++k)          // pages never used before are zeroed first
-      for (int t = lane; t < n16; t += 64) ((uint4*)(pool + (size_t)c.newpg[k] * kPageBytes))[t] = uint4{0, 0, 0, 0};
     for (int t = lane; t < m * kChunks; t += 64) {
       const int q = t / kChunks, ch = t % kChunks;
       const int i = c.perm[q];
@@ -716,40 +704,32 @@ __device__ inline void wave_split_commit(const View& v, int u, WaveCtx& c, const
       const size_t off = (size_t)(DT == DYNAKV_F32 ? k_index32(r & 15, 4 * ch) : k_index16(r & 15, 8 * ch)) * kEs;
       *(uint4*)(pool + (size_t)dpage * kPageBytes + off) = *(const uint4*)(c.stage + (size_t)i * kRowBytes + ch * 16);
     }
-    // values element by element (their page layout interleaves four tokens): first those requested ahead
+    // values chunk by chunk like the keys, straight from their old pages: first the chunks requested ahead
+    auto vchunk = [](int slot, int ch) -> size_t {
+      return (size_t)(DT == DYNAKV_F32 ? v_index32(slot, 4 * ch) : v_index16(slot, 8 * ch)) * kEs;
+    };
+    auto vdest = [&](int i, int ch) -> char* {
+      const int q = c.inv[i];
+      const int r = q < nS ? q : q - nS;
+      return (char*)pool + (size_t)c.newpg[(q < nS ? 0 : pS) + (r >> 4)] * kPageBytes + vchunk(r & 15, ch);
+    };
 #pragma unroll
     for (int k = 0; k < kVAhead; ++k) {
-      const int t = k * 64 + lane, i = t >> 7;
-      if (i < m) {
-        const int q = c.inv[i];
-        const int r = q < nS ? q : q - nS;
-        char* dst = pool + (size_t)c.newpg[(q < nS ? 0 : pS) + (r >> 4)] * kPageBytes;
-        const int e = v_index(DT, r & 15, t & 127);
-        if (DT == DYNAKV_F32) ((uint32_t*)dst)[e] = vahead[k];
-        else ((uint16_t*)dst)[e] = (uint16_t)vahead[k];
-      }
+      const int t = k * 64 + lane, i = t / kChunks;
+      if (i < m) *(uint4*)vdest(i, t % kChunks) = vahead[k];
     }
-    // then the members past those, eight loads in flight per lane
-    for (int t0 = kVAheadMembers * kHeadDim; t0 < m * kHeadDim; t0 += 8 * 64) {
-      uint32_t w[8];
+    // then the members past those, four loads in flight per lane
+    for (int t0 = kVAhead * 64; t0 < m * kChunks; t0 += 4 * 64) {
+      uint4 w[4];
 #pragma unroll
-      for (int k = 0; k < 8; ++k) {
-        const int t = min(t0 + k * 64 + lane, m * kHeadDim - 1), i = t >> 7;
-        const char* src = pool + (size_t)c.chain[i >> 4] * kPageBytes;
-        const int e = v_index(DT, i & 15, t & 127);
-        w[k] = DT == DYNAKV_F32 ? ((const uint32_t*)src)[e] : (uint32_t)((const uint16_t*)src)[e];
+      for (int k = 0; k < 4; ++k) {
+        const int t = min(t0 + k * 64 + lane, m * kChunks - 1), i = t / kChunks;
+        w[k] = *(const uint4*)(pool + (size_t)c.chain[i >> 4] * kPageBytes + vchunk(i & 15, t % kChunks));
       }
 #pragma unroll
-      for (int k = 0; k < 8; ++k) {
+      for (int k = 0; k < 4; ++k) {
         const int t = t0 + k * 64 + lane;
-        if (t < m * kHeadDim) {
-          const int q = c.inv[t >> 7];
-          const int r = q < nS ? q : q - nS;
-          char* dst = pool + (size_t)c.newpg[(q < nS ? 0 : pS) + (r >> 4)] * kPageBytes;
-          const int e = v_index(DT, r & 15, t & 127);
-          if (DT == DYNAKV_F32) ((uint32_t*)dst)[e] = w[k];
-          else ((uint16_t*)dst)[e] = (uint16_t)w[k];
-        }
+        if (t < m * kChunks) *(uint4*)vdest(t / kChunks, t % kChunks) = w[k];
       }
     }
     if (lane < m) {
@@ -900,7 +880,7 @@ __global__ __launch_bounds__(kSplitThreads) void split_kernel(View v) {
       const int nc = pl.n_cand;
       for (int base = 0; base < nc; base += kWaveSplits) {
         const bool mine = base + wave < nc;
-        uint32_t vahead[kVAhead];
+        uint4 vahead[kVAhead];
         int pos_ahead = 0;
         WaveCtx& c = wc[wave];
         if (mine) {
@@ -924,7 +904,6 @@ __global__ __launch_bounds__(kSplitThreads) void split_kernel(View v) {
                             : (ahead >= 0 && ahead < kFreeAhead) ? pl.fl[ahead]
                                                                   : v.freelist[(size_t)u * v.Pcap + pl.top - 1 - k];
             }
-            cw.fresh_from = from_free;
             pl.top -= from_free;
             pl.bump += need - from_free;
           }

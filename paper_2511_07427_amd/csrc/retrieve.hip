@@ -473,11 +473,15 @@ typedef short s4 __attribute__((ext_vector_type(4)));
 constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
 
 // One tile of the attention loop: 16 token slots filled from up to four gather-list entries (quads), which may
-// come from four different pages.  Lane l multiplies token slot l % 16 in QK^T (entry slot / 4, row slot % 4 of
-// that quad) and the four tokens of entry l / 16 in PV, so every lane has its own two page addresses.
+// come from four different pages.  Lane l loads pieces of the K row and of the V row of token slot l % 16
+// (entry slot / 4, row slot % 4 of that quad): K feeds QK^T as loaded; PV wants the four tokens of quad l / 16 of
+// one column in a lane, so the V rows go through a per-wavefront LDS tile (rows padded to kVRow bytes) and come
+// back transposed.  Both K and V traffic therefore follow the valid tokens exactly.
+constexpr int kVRow16 = kHeadDim * 2 + 16, kVRow32 = kHeadDim * 4 + 16;   // bytes; the pad spreads the quads over the banks
+constexpr int kVTile16 = kPageTokens * kVRow16, kVTile32 = kPageTokens * kVRow32;
 struct Tile {
-  const char* k;     // this lane's first 16 bytes of its token's K row (further k-steps 64 bytes apart)
-  const char* v;     // this lane's first 16 bytes of the V region
+  const char* k;     // this lane's first 16 bytes of its token's K row (further pieces 64 bytes apart); the V row
+                     // of the same token lies one K region further
   bool kok;          // the lane's token slot holds a token
   int nvq;           // valid tokens in the lane's PV quad (0: no entry)
 };
@@ -490,20 +494,20 @@ __device__ inline Tile make_tile(const char* pages, int eK, int eV, int lane) {
   if (eK < 0) eK = 0;
   t.k = pages + (size_t)(eK >> 4) * kPageBytes + (((eK >> 2) & 3) * 4 + (lane & 3)) * (kHeadDim * ES) + (lane >> 4) * 16;
   t.nvq = eV >= 0 ? (eV & 3) + 1 : 0;
-  if (eV < 0) eV = 0;
-  t.v = pages + (size_t)(eV >> 4) * kPageBytes + 2048 * ES + (((eV >> 2) & 3) * 16 + (lane & 15)) * 16;
   return t;
 }
 
 // Fragments of one tile and of the query group, per storage type.  qk() returns S^T[token 4*(lane/16)+i]
-// [head lane%16]; pv() adds P^T-weighted V^T into acc[cb][i] = O^T[column 16*cb + 4*(lane/16) + i][head lane%16].
+// [head lane%16]; pv() adds P^T-weighted V^T into acc[cb][i] = O^T[column out_col(cb, 4*(lane/16) + i)][head lane%16].
 template <int DT>
 struct Frag;
 
 template <>
 struct Frag<DYNAKV_F32> {
-  struct KV { f4 k[8]; f4 v[8]; };
+  struct KV { f4 k[8]; f4 v[8]; };     // v: this lane's pieces of its token's V row, as loaded
+  struct VT { f4 c[8]; };              // c[cb][kk] = V[token 4*(lane/16) + kk][column out_col(cb, lane%16)]
   struct Qf { f4 b[8]; };
+  static constexpr int kVTile = kVTile32;
   static __device__ void load_q(Qf& q, const void* Q, size_t row, int lg, bool ok) {
     const float* p = (const float*)Q + row * kHeadDim + 4 * lg;
 #pragma unroll
@@ -511,11 +515,25 @@ struct Frag<DYNAKV_F32> {
   }
   static __device__ void load(KV& f, const Tile& t) {
     const f4* kp = (const f4*)t.k;
-    const f4* vp = (const f4*)t.v;
+    const f4* vp = (const f4*)(t.k + 2048 * 4);
 #pragma unroll
     for (int s = 0; s < 8; ++s) f.k[s] = t.kok ? kp[s * 4] : f4{0, 0, 0, 0};
 #pragma unroll
-    for (int c = 0; c < 8; ++c) f.v[c] = t.nvq ? vp[c * 64] : f4{0, 0, 0, 0};
+    for (int s = 0; s < 8; ++s) f.v[s] = t.kok ? vp[s * 4] : f4{0, 0, 0, 0};
+  }
+  // V rows -> LDS tile of this wavefront (zeros for empty slots), then back with tokens innermost
+  static __device__ void stage(const KV& f, char* tile, int lane) {
+    char* row = tile + (lane & 15) * kVRow32 + (lane >> 4) * 16;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) *(f4*)(row + s * 64) = f.v[s];
+  }
+  static __device__ int out_col(int cb, int a) { return 16 * cb + a; }   // row a of accumulator block cb
+  static __device__ void unstage(VT& t, const char* tile, int lane) {
+    const char* p = tile + (lane >> 4) * 4 * kVRow32 + (lane & 15) * 4;
+#pragma unroll
+    for (int cb = 0; cb < 8; ++cb)
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) t.c[cb][kk] = *(const float*)(p + kk * kVRow32 + cb * 64);
   }
   static __device__ f4 qk(const KV& f, const Qf& q) {
     f4 a = {0, 0, 0, 0};
@@ -525,18 +543,20 @@ struct Frag<DYNAKV_F32> {
       for (int i = 0; i < 4; ++i) a = __builtin_amdgcn_mfma_f32_16x16x4f32(f.k[s][i], q.b[s][i], a, 0, 0, 0);
     return a;
   }
-  static __device__ void pv(f4 (&acc)[8], const KV& f, const float (&p)[4]) {
+  static __device__ void pv(f4 (&acc)[8], const VT& f, const float (&p)[4]) {
 #pragma unroll
     for (int c = 0; c < 8; ++c)
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(f.v[c][kk], p[kk], acc[c], 0, 0, 0);
+      for (int kk = 0; kk < 4; ++kk) acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(f.c[c][kk], p[kk], acc[c], 0, 0, 0);
   }
 };
 
 template <bool BF>
 struct Frag16 {
-  struct KV { uint4 k[4]; uint4 v[4]; };
+  struct KV { uint4 k[4]; uint4 v[4]; };   // v: this lane's pieces of its token's V row, as loaded
+  struct VT { uint2 c[8]; };               // c[cb] = V[tokens 4*(lane/16) .. +3][column out_col(cb, lane%16)]
   struct Qf { uint4 b[4]; };
+  static constexpr int kVTile = kVTile16;
   static __device__ void load_q(Qf& q, const void* Q, size_t row, int lg, bool ok) {
     const uint16_t* p = (const uint16_t*)Q + row * kHeadDim + 8 * lg;
 #pragma unroll
@@ -544,11 +564,30 @@ struct Frag16 {
   }
   static __device__ void load(KV& f, const Tile& t) {
     const uint4* kp = (const uint4*)t.k;
-    const uint4* vp = (const uint4*)t.v;
+    const uint4* vp = (const uint4*)(t.k + 2048 * 2);
 #pragma unroll
     for (int s = 0; s < 4; ++s) f.k[s] = t.kok ? kp[s * 4] : uint4{0, 0, 0, 0};
 #pragma unroll
-    for (int c = 0; c < 4; ++c) f.v[c] = t.nvq ? vp[c * 64] : uint4{0, 0, 0, 0};
+    for (int s = 0; s < 4; ++s) f.v[s] = t.kok ? vp[s * 4] : uint4{0, 0, 0, 0};
+  }
+  // V rows -> LDS tile of this wavefront (zeros for empty slots), then back with tokens innermost
+  static __device__ void stage(const KV& f, char* tile, int lane) {
+    char* row = tile + (lane & 15) * kVRow16 + (lane >> 4) * 16;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) *(uint4*)(row + s * 64) = f.v[s];
+  }
+  // row a of accumulator block cb is this output column: a lane reads column pairs (one 32-bit word per token)
+  static __device__ int out_col(int cb, int a) { return 32 * (cb >> 1) + 2 * a + (cb & 1); }
+  static __device__ void unstage(VT& t, const char* tile, int lane) {
+    const char* p = tile + (lane >> 4) * 4 * kVRow16 + (lane & 15) * 4;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      uint32_t w[4];
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) w[kk] = *(const uint32_t*)(p + kk * kVRow16 + s * 64);
+      t.c[2 * s] = uint2{(w[0] & 0xffffu) | (w[1] << 16), (w[2] & 0xffffu) | (w[3] << 16)};
+      t.c[2 * s + 1] = uint2{(w[0] >> 16) | (w[1] & 0xffff0000u), (w[2] >> 16) | (w[3] & 0xffff0000u)};
+    }
   }
   static __device__ f4 qk(const KV& f, const Qf& q) {
     f4 a = {0, 0, 0, 0};
@@ -568,7 +607,7 @@ struct Frag16 {
       return __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(h4, a), __builtin_bit_cast(h4, b), c, 0, 0, 0);
   }
   // p is split into a rounded part and its remainder so that the product keeps float32-like accuracy
-  static __device__ void pv(f4 (&acc)[8], const KV& f, const float (&p)[4]) {
+  static __device__ void pv(f4 (&acc)[8], const VT& f, const float (&p)[4]) {
     uint16_t hi[4], lo[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -588,10 +627,8 @@ struct Frag16 {
     const uint2 pl = {(uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16)};
 #pragma unroll
     for (int c = 0; c < 8; ++c) {
-      const uint4 w = f.v[c >> 1];
-      const uint2 vf = (c & 1) ? uint2{w.z, w.w} : uint2{w.x, w.y};
-      acc[c] = mma4(vf, ph, acc[c]);
-      acc[c] = mma4(vf, pl, acc[c]);
+      acc[c] = mma4(f.c[c], ph, acc[c]);
+      acc[c] = mma4(f.c[c], pl, acc[c]);
     }
   }
 };
@@ -630,7 +667,9 @@ struct Softmax {
 
 // One tile: S^T = K Q^T on the matrix cores, running max / rescale, O^T += V^T P^T.
 template <class F>
-__device__ inline void consume_page(Softmax& st, const typename F::KV& kv, const typename F::Qf& q, int nvq, float sc) {
+__device__ inline void consume_page(Softmax& st, const typename F::KV& kv, const typename F::Qf& q, int nvq, float sc,
+                                    char* vtile, int lane) {
+  F::stage(kv, vtile, lane);              // the scores are computed while the V rows settle in LDS
   const f4 sacc = F::qk(kv, q);
   float s2[4], mx = -__builtin_inff();
 #pragma unroll
@@ -649,7 +688,11 @@ __device__ inline void consume_page(Softmax& st, const typename F::KV& kv, const
   st.m = mn;
 #pragma unroll
   for (int c = 0; c < 8; ++c) st.acc[c] *= alpha;
-  F::pv(st.acc, kv, pr);
+  asm volatile("" ::: "memory");          // same wavefront: LDS keeps program order, the compiler must too
+  typename F::VT vt;
+  F::unstage(vt, vtile, lane);
+  asm volatile("" ::: "memory");
+  F::pv(st.acc, vt, pr);
 }
 
 // grid (S, U); NW wavefronts per workgroup; the unit's gather list is dealt tile by tile (four entries) to the
@@ -660,7 +703,8 @@ template <int DT, int NW, bool PF>
 __global__ __launch_bounds__(NW * 64) void gather_attend_kernel(View v, const void* Q, float* out, float* lse) {
   using F = Frag<DT>;
   constexpr int ES = DT == DYNAKV_F32 ? 4 : 2;
-  extern __shared__ float sm_o[];            // [NW][G][130]: accumulators, max, denominator per wave and head
+  // one V tile per wavefront during the loop, then [NW][G][130]: accumulators, max, denominator per wave and head
+  extern __shared__ __align__(16) float sm_o[];
   __shared__ int s_last;
   const int u = blockIdx.y, s = blockIdx.x, S = gridDim.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -681,6 +725,7 @@ __global__ __launch_bounds__(NW * 64) void gather_attend_kernel(View v, const vo
   const int stride = S * NW, p0 = s * NW + wave;
   const int mine = p0 < ntile ? (ntile - p0 + stride - 1) / stride : 0;   // tiles of this wavefront
   const int selK = (lane & 15) >> 2;
+  char* vtile = (char*)sm_o + wave * F::kVTile;
   for (int c0 = 0; c0 < mine; c0 += 16) {
     const int cn = min(16, mine - c0);
     const int my_e = 4 * (p0 + (c0 + (lane >> 2)) * stride) + (lane & 3);
@@ -694,13 +739,13 @@ __global__ __launch_bounds__(NW * 64) void gather_attend_kernel(View v, const vo
           tb = make_tile<ES>(pages, __shfl(e_l, 4 * (i + 1) + selK), __shfl(e_l, 4 * (i + 1) + lg), lane);
           F::load(b, tb);
         }
-        consume_page<F>(st, a, q, ta.nvq, sc);
+        consume_page<F>(st, a, q, ta.nvq, sc, vtile, lane);
         if (i + 1 < cn) {
           if (i + 2 < cn) {
             ta = make_tile<ES>(pages, __shfl(e_l, 4 * (i + 2) + selK), __shfl(e_l, 4 * (i + 2) + lg), lane);
             F::load(a, ta);
           }
-          consume_page<F>(st, b, q, tb.nvq, sc);
+          consume_page<F>(st, b, q, tb.nvq, sc, vtile, lane);
         }
       }
     } else {
@@ -708,7 +753,7 @@ __global__ __launch_bounds__(NW * 64) void gather_attend_kernel(View v, const vo
         typename F::KV a;
         const Tile ta = make_tile<ES>(pages, __shfl(e_l, 4 * i + selK), __shfl(e_l, 4 * i + lg), lane);
         F::load(a, ta);
-        consume_page<F>(st, a, q, ta.nvq, sc);
+        consume_page<F>(st, a, q, ta.nvq, sc, vtile, lane);
       }
     }
   }
@@ -717,13 +762,14 @@ __global__ __launch_bounds__(NW * 64) void gather_attend_kernel(View v, const vo
   l += __shfl_xor(l, 32);
 
   // workgroup merge
+  __syncthreads();                                    // the V tiles are dead: their space becomes the merge buffer
   const int hs = kHeadDim + 2, ws = G * hs;
   if (g < G) {
     float* o = sm_o + wave * ws + g * hs;
 #pragma unroll
     for (int c = 0; c < 8; ++c)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) o[16 * c + 4 * lg + i] = st.acc[c][i];
+      for (int i = 0; i < 4; ++i) o[F::out_col(c, 4 * lg + i)] = st.acc[c][i];
     if (lg == 0) { o[kHeadDim] = st.m; o[kHeadDim + 1] = l; }
   }
   __syncthreads();
@@ -779,6 +825,7 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   constexpr int kMergeBytes = 64 * (kHeadDim + 2) * 4;          // NW * G <= 64 head rows
   constexpr int kKeys = kFusedClusters * 4, kSizes = kFusedClusters * 4, kList = kFusedList * 4;
   static_assert(kSelRegion >= 2 * kFusedClusters && kKeys + kSizes + kSelRegion + kList >= kMergeBytes, "LDS plan");
+  static_assert(NW * F::kVTile <= kKeys + kSizes + kSelRegion, "the V tiles take the space of the selection's tables");
   // scores, sizes, candidates, gather list; after the page loop the front doubles as the merge buffer
   __shared__ __align__(16) unsigned char smem[kKeys + kSizes + kSelRegion + kList];
   __shared__ double qs[kHeadDim][GP];
@@ -903,6 +950,7 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   for (int c = 0; c < 8; ++c) st.acc[c] = f4{0, 0, 0, 0};
   const int* src = nlist <= kFusedList ? list : plist;
   const int ntile = (nlist + 3) >> 2, selK = (lane & 15) >> 2;
+  char* vtile = (char*)smem + wave * F::kVTile;      // scores, sizes and candidates are dead
 #define DYNAKV_TILE(T) make_tile<ES>(pages, 4 * (T) + selK < nlist ? src[4 * (T) + selK] : -1, \
                                      4 * (T) + lg < nlist ? src[4 * (T) + lg] : -1, lane)
   {                                                   // two tiles in flight per wavefront
@@ -914,13 +962,13 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
         tb = DYNAKV_TILE(p + NW);
         F::load(b, tb);
       }
-      consume_page<F>(st, a, q, ta.nvq, sc);
+      consume_page<F>(st, a, q, ta.nvq, sc, vtile, lane);
       if (p + NW < ntile) {
         if (p + 2 * NW < ntile) {
           ta = DYNAKV_TILE(p + 2 * NW);
           F::load(a, ta);
         }
-        consume_page<F>(st, b, q, tb.nvq, sc);
+        consume_page<F>(st, b, q, tb.nvq, sc, vtile, lane);
       }
     }
   }
@@ -935,7 +983,7 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
 #pragma unroll
     for (int c = 0; c < 8; ++c)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) o[16 * c + 4 * lg + i] = st.acc[c][i];
+      for (int i = 0; i < 4; ++i) o[F::out_col(c, 4 * lg + i)] = st.acc[c][i];
     if (lg == 0) { o[kHeadDim] = st.m; o[kHeadDim + 1] = l; }
   }
   __syncthreads();
@@ -958,7 +1006,7 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
 
 template <int DT, int NW, bool PF>
 void launch_ga(const View& v, const void* Q, float* out, float* lse, hipStream_t st) {
-  const size_t lds = (size_t)NW * v.G * (kHeadDim + 2) * sizeof(float);
+  const size_t lds = std::max((size_t)NW * v.G * (kHeadDim + 2) * sizeof(float), (size_t)NW * Frag<DT>::kVTile);
   gather_attend_kernel<DT, NW, PF><<<dim3(v.S, v.U), NW * 64, lds, st>>>(v, Q, out, lse);
 }
 template <int DT>
