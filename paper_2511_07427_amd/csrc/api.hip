@@ -74,7 +74,7 @@ size_t carve(const dynakv_config_t& c, char* base, View* out) {
   v.U = c.n_units; v.G = c.group_size; v.dtype = c.dtype; v.M0 = c.n_clusters_init; v.Mcap = c.max_clusters;
   v.Ncap = c.max_tokens; v.Pcap = pages_per_unit(c); v.Lcap = (c.max_tokens + 3) & ~3; v.Bmax = c.buffer_max; v.group_reduce = c.group_reduce;
   plan_attention(c, &v.S, &v.NW);
-  v.fuse = std::getenv("DYNAKV_NO_FUSE") ? 0 : 1;       // tuning / test switch
+  v.fuse = std::getenv("DYNAKV_NO_FUSE") ? 0 : std::getenv("DYNAKV_SPLIT_KERNEL") ? 1 : 2;   // tuning / test switches
   v.var_alpha = c.var_alpha; v.size_factor = c.size_factor;
   v.scale_d = c.softmax_scale > 0.f ? (double)c.softmax_scale : 1.0 / std::sqrt((double)c.head_dim);
   v.scale_f = (float)v.scale_d;
@@ -155,16 +155,17 @@ dynakv_status_t dynakv_build_index(dynakv_index_t* ix, const void* K, const void
   return DYNAKV_OK;
 }
 
-// Retrieval, and with kin != null the append as well if one kernel can do both (*appended says whether it did).
+// Retrieval, and with kin != null the append as well if one kernel can do both (*appended says whether it did),
+// and with `split` the due splits too (*appended then covers them).
 static dynakv_status_t retrieve_impl(dynakv_index_t* ix, const void* Q, int32_t token_budget, float* out, float* lse,
-                                     const void* kin, const void* vin, hipStream_t st, bool* appended) {
+                                     const void* kin, const void* vin, bool split, hipStream_t st, bool* appended) {
   const bool fused = retrieve_is_fused(ix->view);
   *appended = fused && kin;
   if (!fused && launch_score_select(ix->view, Q, token_budget, st) != hipSuccess) return DYNAKV_EHIP;
   const bool prof = ix->profiling && 2 * (ix->n_prof + 1) <= (int)ix->ev.size();
   if (prof && hipEventRecord(ix->ev[2 * ix->n_prof], st) != hipSuccess) return DYNAKV_EHIP;
   if (fused) {
-    if (launch_retrieve_fused(ix->view, Q, token_budget, out, lse, kin, vin, st) != hipSuccess) return DYNAKV_EHIP;
+    if (launch_retrieve_fused(ix->view, Q, token_budget, out, lse, kin, vin, split, st) != hipSuccess) return DYNAKV_EHIP;
   } else if (launch_gather_attend(ix->view, Q, out, lse, st) != hipSuccess) {
     return DYNAKV_EHIP;
   }
@@ -180,7 +181,7 @@ dynakv_status_t dynakv_retrieve_attend(dynakv_index_t* ix, const void* Q, int32_
   if (!ix || !Q || !out || token_budget < 0) return DYNAKV_EINVAL;
   if (!ix->built) return DYNAKV_ESTATE;
   bool appended;
-  return retrieve_impl(ix, Q, token_budget, out, lse, nullptr, nullptr, (hipStream_t)stream, &appended);
+  return retrieve_impl(ix, Q, token_budget, out, lse, nullptr, nullptr, false, (hipStream_t)stream, &appended);
 }
 
 dynakv_status_t dynakv_decode_step(dynakv_index_t* ix, const void* Q, int32_t token_budget, float* out, float* lse,
@@ -189,8 +190,10 @@ dynakv_status_t dynakv_decode_step(dynakv_index_t* ix, const void* Q, int32_t to
   if (!ix->built) return DYNAKV_ESTATE;
   hipStream_t st = (hipStream_t)stream;
   bool appended;
-  const dynakv_status_t rc = retrieve_impl(ix, Q, token_budget, out, lse, k_new, v_new, st, &appended);
+  const bool one_kernel = ix->view.fuse == 2;        // the splits too, where the retrieval kernel takes the append
+  const dynakv_status_t rc = retrieve_impl(ix, Q, token_budget, out, lse, k_new, v_new, one_kernel, st, &appended);
   if (rc != DYNAKV_OK) return rc;
+  if (appended && one_kernel) return DYNAKV_OK;
   if (!appended && launch_append(ix->view, k_new, v_new, st) != hipSuccess) return DYNAKV_EHIP;
   return launch_split(ix->view, st) == hipSuccess ? DYNAKV_OK : DYNAKV_EHIP;
 }

@@ -341,10 +341,12 @@ __device__ inline float page_key(const View& v, int u, int page, int slot, int d
 }
 
 // ---- block helpers ------------------------------------------------------------------------------
-// Exclusive prefix sum over the threads of a block (blockDim.x a multiple of 64, at most 1024).
+// Exclusive prefix sum over the threads of a block (blockDim.x a multiple of 64, at most 1024), or over its
+// first 64 * nw threads if nw > 0 (then only those may call).
 // `sm` needs 64 ints.  Returns the prefix of this thread; `total` receives the block sum.
-__device__ inline int block_excl_scan(int val, int* sm, int& total) {
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+__device__ inline int block_excl_scan(int val, int* sm, int& total, int nw = 0) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  if (nw == 0) nw = blockDim.x >> 6;
   int x = val;
   for (int o = 1; o < 64; o <<= 1) {
     const int y = __shfl_up(x, o);
@@ -427,7 +429,7 @@ hipError_t launch_build_index(const View& v, const void* K, const void* V, int n
 hipError_t launch_score_select(const View& v, const void* Q, int budget, hipStream_t st);
 bool retrieve_is_fused(const View& v);
 hipError_t launch_retrieve_fused(const View& v, const void* Q, int budget, float* out, float* lse, const void* kin,
-                                 const void* vin, hipStream_t st);
+                                 const void* vin, bool split, hipStream_t st);
 hipError_t launch_gather_attend(const View& v, const void* Q, float* out, float* lse, hipStream_t st);
 hipError_t launch_append(const View& v, const void* k, const void* val, hipStream_t st);
 hipError_t launch_split(const View& v, hipStream_t st);

@@ -4,7 +4,7 @@
 //   export_kernel - snapshot of the index for tests
 // One workgroup per unit; each unit's record is touched by that workgroup only.  All decisions are
 // taken on float64 values accumulated left to right, ties to the lowest index.
-#include "append.hpp"
+#include "split.hpp"
 
 namespace dynakv {
 
@@ -61,932 +61,11 @@ __global__ __launch_bounds__(256) void append_kernel(View v, const void* kin, co
 }
 
 // ------------------------------------------------------------------------------------------- split
-// Keys of the cluster being split are staged once in LDS (up to 128 members of a 16-bit type, 64 of
-// float32; rows padded so that "lane = member" and "lane = coordinate" reads are both conflict-free);
-// larger clusters fall back to reading their pages.
-constexpr int kStageRow16 = kHeadDim + 8, kStageRow32 = kHeadDim + 4;
-constexpr int kStageBytes = 128 * kStageRow16 * 2;
-
-struct SplitSmem {
-  int chain[kMaxSplitMembers / kPageTokens];      // pages of the cluster being split
-  int newpg[kMaxSplitMembers / kPageTokens + 2];  // pages of the two children
-  unsigned char side[kMaxSplitMembers];
-  unsigned short perm[kMaxSplitMembers];           // members of the staying child in order, then of the moved one
-  double cA[kHeadDim], cB[kHeadDim];
-  float rA[kHeadDim], rB[kHeadDim];
-  double sv[16];
-  int si[16];
-  double dl[128];                                  // member distances of a staged cluster
-  int scan[64];
-  int flag, count, nchain;
-  int M, nflag, a_top, a_bump;                     // the unit's counters, held here for the whole kernel
-  double m2[2];
-  alignas(16) unsigned char stage[kStageBytes];
-};
-
-// Access to the keys of the members, by member index: 8 consecutive coordinates at a time, or one.
-template <int DT, bool STAGED>
-struct Keys {
-  const View& v; const SplitSmem& s; int u;
-  __device__ void get8(int i, int d8, float (&x)[8]) const {
-    if constexpr (STAGED && DT == DYNAKV_F32) {
-      const f4* p = (const f4*)((const float*)s.stage + i * kStageRow32 + d8 * 8);
-      const f4 a = p[0], b = p[1];
-#pragma unroll
-      for (int e = 0; e < 4; ++e) { x[e] = a[e]; x[4 + e] = b[e]; }
-    } else if constexpr (STAGED) {
-      const uint4 w = *(const uint4*)((const uint16_t*)s.stage + i * kStageRow16 + d8 * 8);
-      const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const uint16_t h = (uint16_t)(ww[e >> 1] >> ((e & 1) * 16));
-        x[e] = DT == DYNAKV_F16 ? f16_to_float(h) : bf16_to_float(h);
-      }
-    } else {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) x[e] = page_key(v, u, s.chain[i >> 4], i & 15, d8 * 8 + e);
-    }
-  }
-  __device__ float get(int i, int d) const {
-    if constexpr (STAGED && DT == DYNAKV_F32) return ((const float*)s.stage)[i * kStageRow32 + d];
-    else if constexpr (STAGED) {
-      const uint16_t h = ((const uint16_t*)s.stage)[i * kStageRow16 + d];
-      return DT == DYNAKV_F16 ? f16_to_float(h) : bf16_to_float(h);
-    } else return page_key(v, u, s.chain[i >> 4], i & 15, d);
-  }
-};
-
-constexpr int kSplitThreads = 256;
-
-// Arg-max over (value, index) pairs held one per thread of the whole block; ties go to the lowest index;
-// index < 0 means "no candidate".  Wavefront shuffles first, then the 16 wavefront winners through LDS.
-__device__ inline void block_argmax(double val, int idx, double* sv, int* si) {
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  for (int o = 32; o > 0; o >>= 1) {
-    const double ov = __shfl_xor(val, o);
-    const int oi = __shfl_xor(idx, o);
-    if (oi >= 0 && (idx < 0 || ov > val || (ov == val && oi < idx))) { val = ov; idx = oi; }
-  }
-  __syncthreads();
-  if (lane == 0) { sv[w] = val; si[w] = idx; }
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    for (int k = 1; k < kSplitThreads / 64; ++k)
-      if (si[k] >= 0 && (si[0] < 0 || sv[k] > sv[0] || (sv[k] == sv[0] && si[k] < si[0]))) { sv[0] = sv[k]; si[0] = si[k]; }
-  }
-  __syncthreads();
-}
-
-// Squared distances of member i to one or two centres (C = double or float) in the fixed summation order.
-// Called by the four lanes of a quad at once: lane q accumulates blocks 4q..4q+3 (coordinates 32q..32q+31),
-// the block sums are then added left to right across the quad; every lane returns the totals.
-template <class K, class C>
-__device__ inline void quad_sqdist(const K& ks, int i, int q, const C* cA, const C* cB, double& dA, double& dB) {
-  double sa[4], sb[4];
-#pragma unroll
-  for (int k = 0; k < 4; ++k) {
-    // every operand of the block is requested before the first use, so the LDS latency is paid once per block
-    float x[8];
-    C ca[8], cb[8];
-    ks.get8(i, q * 4 + k, x);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) { ca[e] = cA[(q * 4 + k) * 8 + e]; cb[e] = cB ? cB[(q * 4 + k) * 8 + e] : C(0); }
-    asm volatile("" ::: "memory");
-    double a = 0.0, b = 0.0;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const double xd = (double)x[e];
-      const double ta = xd - (double)ca[e];
-      a = fma(ta, ta, a);
-      if (cB) {
-        const double tb = xd - (double)cb[e];
-        b = fma(tb, tb, b);
-      }
-    }
-    sa[k] = a; sb[k] = b;
-  }
-  dA = blocked16_quad(sa);
-  dB = cB ? blocked16_quad(sb) : 0.0;
-}
-
-// Sum over r = 0..n-1, in that order, of key(r) for the r that use(r) accepts: eight operands are requested
-// at a time (clamped, so the loads do not depend on the test), then added one by one; a rejected or
-// out-of-range term adds +0.0, which leaves the float64 sum unchanged.
-template <class Key, class Use>
-__device__ inline double ordered_sum(int n, Key&& key, Use&& use) {
-  double sum = 0.0;
-  for (int r0 = 0; r0 < n; r0 += 8) {
-    float x[8];
-#pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      const int r = min(r0 + k, n - 1);
-      const float kv = key(r);
-      x[k] = (r0 + k < n && use(r)) ? kv : 0.f;
-    }
-    asm volatile("" ::: "memory");
-#pragma unroll
-    for (int k = 0; k < 8; ++k) sum += (double)x[k];
-  }
-  return sum;
-}
-
-// Arg-max of dist[0..n) (ties to the lowest index) by one thread, eight loads at a time; result in sv[0], si[0].
-__device__ inline void serial_argmax(const double* dist, int n, double* sv, int* si) {
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    double bv = -1.0; int bi = -1;
-    for (int r0 = 0; r0 < n; r0 += 8) {
-      double x[8];
-#pragma unroll
-      for (int k = 0; k < 8; ++k) x[k] = dist[min(r0 + k, n - 1)];
-      asm volatile("" ::: "memory");
-#pragma unroll
-      for (int k = 0; k < 8; ++k)
-        if (r0 + k < n && x[k] > bv) { bv = x[k]; bi = r0 + k; }
-    }
-    sv[0] = bv; si[0] = bi;
-  }
-  __syncthreads();
-}
-
-// Exact statistics of both children at once: members perm[0 .. nS) form cluster idS, perm[nS .. m) cluster idM
-// (idM < 0: there is no second child).  Threads 0..127 own the coordinates of the first, 128..255 of the
-// second.  float32 means go to rA / rB (LDS) and to the centroid table, M2 about those means to s.m2[].
-template <class K>
-__device__ inline void children_stats(const View& v, int u, SplitSmem& s, const K& ks, bool staged, int nS, int m,
-                                      int idS, int idM) {
-  const int tid = threadIdx.x, d = tid & (kHeadDim - 1), c = (tid >> 7) & 1;
-  const int q0 = c ? nS : 0, q1 = c ? m : nS, id = c ? idM : idS;
-  if (tid < 2 * kHeadDim) {
-    float* r = c ? s.rB : s.rA;
-    const double sum = ordered_sum(q1 - q0, [&](int r) { return ks.get(s.perm[q0 + r], d); }, [](int) { return true; });
-    r[d] = q1 > q0 ? (float)(sum / (double)(q1 - q0)) : 0.f;
-    if (id >= 0) store_centroid(v, u, id, d, r[d]);
-  }
-  __syncthreads();
-  double* dist = staged ? s.dl : v.dist + (size_t)u * v.Ncap;
-  const int grp = tid >> 2, k = tid & 3;
-  for (int base = 0; base < m; base += kSplitThreads / 4) {
-    if (base + (int)((tid & ~63) >> 2) >= m) continue;      // this wavefront has no member
-    const int q = base + grp, qc = min(q, m - 1);
-    double da, db;
-    quad_sqdist<K, float>(ks, s.perm[qc], k, qc < nS ? s.rA : s.rB, nullptr, da, db);
-    if (k == 0 && q < m) dist[q] = da;
-  }
-  __syncthreads();
-  if (d == 0 && tid < 2 * kHeadDim) {
-    double acc = 0.0;
-    for (int r0 = q0; r0 < q1; r0 += 8) {
-      double x[8];
-#pragma unroll
-      for (int k = 0; k < 8; ++k) x[k] = r0 + k < q1 ? dist[r0 + k] : 0.0;
-      asm volatile("" ::: "memory");
-#pragma unroll
-      for (int k = 0; k < 8; ++k) acc += x[k];
-    }
-    s.m2[c] = acc;
-  }
-  __syncthreads();
-}
-
-// Splits cluster j of unit u (2-means; Algorithm 1 SplitCluster).  Whole block; all branches uniform.
-template <int DT, bool STAGED>
-__device__ __forceinline__ void split_cluster_impl(const View& v, int u, int j, int pos, int m, SplitSmem& s) {
-  constexpr int NT = kSplitThreads;
-  const int tid = threadIdx.x, grp = tid >> 2, kb = tid & 3;
-  const int wave_first = (tid & ~63) >> 2;                    // first member this wavefront would take in a pass
-  const size_t cbase = (size_t)u * v.Mcap;
-  constexpr int kEs = DT == DYNAKV_F32 ? 4 : 2;
-  constexpr int kChunks = kHeadDim * kEs / 16;                      // 16-byte chunks per key
-  constexpr int kRowBytes = (DT == DYNAKV_F32 ? kStageRow32 : kStageRow16) * kEs;
-  char* const pool = v.pages + (size_t)u * v.Pcap * ((size_t)kPageElems * kEs);
-  const Keys<DT, STAGED> ks{v, s, u};
-  // byte offset of 16-byte chunk c of the key in `slot` inside its page
-  auto kchunk = [](int slot, int c) -> size_t {
-    return (size_t)(DT == DYNAKV_F32 ? k_index32(slot, 4 * c) : k_index16(slot, 8 * c)) * kEs;
-  };
-  if constexpr (STAGED) {                  // one pass over the cluster's keys; every later pass reads LDS
-    for (int t = tid; t < m * kChunks; t += NT) {
-      const int i = t / kChunks, c = t % kChunks;
-      *(uint4*)(s.stage + (size_t)i * kRowBytes + c * 16) =
-          *(const uint4*)(pool + (size_t)s.chain[i >> 4] * (kPageElems * kEs) + kchunk(i & 15, c));
-    }
-    __syncthreads();
-  }
-  bool can_split = m >= 2;
-  if (can_split) {
-    // seeds: A = member farthest from the mean of all members, B = member farthest from A
-    if (tid < kHeadDim) {
-      const double sum = ordered_sum(m, [&](int i) { return ks.get(i, tid); }, [](int) { return true; });
-      s.cA[tid] = sum / (double)m;
-    }
-    __syncthreads();
-    double dummy;
-    double* const seed_dist = STAGED ? s.dl : v.dist + (size_t)u * v.Ncap;
-    for (int base = 0; base < m; base += NT / 4) {
-      if (base + wave_first >= m) continue;
-      const int i = base + grp;
-      double t;
-      quad_sqdist<decltype(ks), double>(ks, min(i, m - 1), kb, s.cA, nullptr, t, dummy);
-      if (kb == 0 && i < m) seed_dist[i] = t;
-    }
-    serial_argmax(seed_dist, m, s.sv, s.si);
-    const int a = s.si[0];
-    __syncthreads();
-    if (tid < kHeadDim) s.cB[tid] = (double)ks.get(a, tid);
-    __syncthreads();
-    for (int base = 0; base < m; base += NT / 4) {
-      if (base + wave_first >= m) continue;
-      const int i = base + grp;
-      double t;
-      quad_sqdist<decltype(ks), double>(ks, min(i, m - 1), kb, s.cB, nullptr, t, dummy);
-      if (kb == 0 && i < m) seed_dist[i] = t;
-    }
-    serial_argmax(seed_dist, m, s.sv, s.si);
-    const int b = s.si[0];
-    const double db = s.sv[0];
-    __syncthreads();
-    can_split = db > 0.0;                 // false: all members identical
-    if (can_split) {
-      if (tid < kHeadDim) { s.cA[tid] = s.cB[tid]; }
-      __syncthreads();
-      if (tid < kHeadDim) s.cB[tid] = (double)ks.get(b, tid);
-      for (int i = tid; i < m; i += NT) s.side[i] = 2;
-      if (tid == 0) { s.flag = 0; s.count = 0; }
-      __syncthreads();
-      for (int it = 0; it < 16; ++it) {
-        int changed = 0, na = 0;
-        for (int base = 0; base < m; base += NT / 4) {
-          if (base + wave_first >= m) continue;
-          const int i = base + grp;
-          double dA, dB;
-          quad_sqdist<decltype(ks), double>(ks, min(i, m - 1), kb, s.cA, s.cB, dA, dB);
-          if (kb == 0 && i < m) {
-            const unsigned char ns = dA <= dB ? 0 : 1;   // tie -> side A
-            changed |= ns != s.side[i];
-            s.side[i] = ns;
-            na += ns == 0;
-          }
-        }
-        if (changed) s.flag = 1;
-        if (na) atomicAdd(&s.count, na);
-        __syncthreads();
-        const int nA = s.count;
-        const bool moved = s.flag != 0;
-        __syncthreads();
-        if (!moved) break;
-        if (nA == 0 || nA == m) { can_split = false; break; }
-        if (tid < 2 * kHeadDim) {
-          const int d = tid & (kHeadDim - 1);
-          const unsigned char mine = tid < kHeadDim ? 0 : 1;
-          const double sum = ordered_sum(m, [&](int i) { return ks.get(i, d); }, [&](int i) { return s.side[i] == mine; });
-          if (mine == 0) s.cA[d] = sum / (double)nA;
-          else s.cB[d] = sum / (double)(m - nA);
-        }
-        if (tid == 0) { s.flag = 0; s.count = 0; }
-        __syncthreads();
-      }
-    }
-  }
-  if (!can_split) {                       // unflag with exact statistics of the whole cluster
-    for (int i = tid; i < m; i += NT) s.perm[i] = (unsigned short)i;
-    __syncthreads();
-    children_stats(v, u, s, ks, STAGED, m, m, j, -1);
-    if (tid == 0) {
-      v.cn[cbase + j] = m; v.cb[cbase + j] = 0; v.cflag[cbase + j] = 0; v.cM2[cbase + j] = s.m2[0];
-      s.nflag -= 1;
-      v.flist[cbase + pos] = v.flist[cbase + s.nflag];     // the last flagged id takes the freed place
-      v.counters[(size_t)u * kCounters + 1] += 1;
-    }
-    __syncthreads();
-    return;
-  }
-  const int M = s.M;
-  if (M >= v.Mcap) {
-    if (tid == 0) v.err[u] |= DYNAKV_ERR_CLUSTERS;
-    return;
-  }
-  // stable partition: the child that holds the earliest entry keeps id j
-  const unsigned char keep = s.side[0];
-  const int chunk = (m + NT - 1) / NT;
-  const int lo = min(m, tid * chunk), hi = min(m, lo + chunk);
-  int mine = 0;
-  for (int i = lo; i < hi; ++i) mine += s.side[i] == keep;
-  int nS;
-  int rs = block_excl_scan(mine, s.scan, nS);
-  int rm = nS + lo - rs;
-  for (int i = lo; i < hi; ++i) s.perm[s.side[i] == keep ? rs++ : rm++] = (unsigned short)i;
-  const int nM = m - nS;
-  const int pS = (nS + kPageTokens - 1) / kPageTokens, pM = (nM + kPageTokens - 1) / kPageTokens;
-  const int need = pS + pM, top = s.a_top, bump = s.a_bump;
-  if (top + (v.Pcap - bump) < need) {
-    if (tid == 0) v.err[u] |= DYNAKV_ERR_TOKENS;
-    return;
-  }
-  // fresh pages for both children (recycled pages first); the parent's pages are recycled afterwards
-  const int from_free = min(need, top);
-  for (int k = tid; k < need; k += NT)
-    s.newpg[k] = k < from_free ? v.freelist[(size_t)u * v.Pcap + top - 1 - k] : bump + (k - from_free);
-  __syncthreads();
-  for (int k = tid; k < need; k += NT) {
-    const bool last = k == pS - 1 || k == need - 1;
-    v.pnext[(size_t)u * v.Pcap + s.newpg[k]] = last ? -1 : s.newpg[k + 1];
-  }
-  // keys and values in 16-byte chunks of their rows (the V row of a slot lies one K region after its K row)
-  constexpr size_t kVRegion = (size_t)kPageTokens * kHeadDim * kEs;
-#pragma unroll 2
-  for (int t = tid; t < m * kChunks; t += NT) {
-    const int q = t / kChunks, c = t % kChunks;
-    const int i = s.perm[q];
-    const int r = q < nS ? q : q - nS;
-    const int dpage = s.newpg[(q < nS ? 0 : pS) + (r >> 4)];
-    const char* src = pool + (size_t)s.chain[i >> 4] * (kPageElems * kEs) + kchunk(i & 15, c);
-    char* dst = pool + (size_t)dpage * (kPageElems * kEs) + kchunk(r & 15, c);
-    uint4 w;
-    if constexpr (STAGED) w = *(const uint4*)(s.stage + (size_t)i * kRowBytes + c * 16);
-    else w = *(const uint4*)src;
-    const uint4 x = *(const uint4*)(src + kVRegion);
-    *(uint4*)dst = w;
-    *(uint4*)(dst + kVRegion) = x;
-    if (c == 0)
-      v.ppos[((size_t)u * v.Pcap + dpage) * kPageTokens + (r & 15)] =
-          v.ppos[((size_t)u * v.Pcap + s.chain[i >> 4]) * kPageTokens + (i & 15)];
-  }
-  children_stats(v, u, s, ks, STAGED, nS, m, j, M);
-  for (int k = tid; k < s.nchain; k += NT) v.freelist[(size_t)u * v.Pcap + (top - from_free) + k] = s.chain[k];
-  if (tid < kInlinePages) {
-    v.cpg[(cbase + j) * kInlinePages + tid] = tid < pS ? s.newpg[tid] : -1;
-    v.cpg[(cbase + M) * kInlinePages + tid] = tid < pM ? s.newpg[pS + tid] : -1;
-  }
-  if (tid == 0) {
-    v.cn[cbase + j] = nS; v.cb[cbase + j] = 0; v.cflag[cbase + j] = 0; v.cM2[cbase + j] = s.m2[0];
-    v.ctail[cbase + j] = s.newpg[pS - 1];
-    v.cn[cbase + M] = nM; v.cb[cbase + M] = 0; v.cflag[cbase + M] = 0; v.cM2[cbase + M] = s.m2[1];
-    v.ctail[cbase + M] = s.newpg[pS + pM - 1];
-    v.in_req[cbase + M] = 0;
-    s.M = M + 1;
-    s.a_top = top - from_free + s.nchain;
-    s.a_bump = bump + (need - from_free);
-    s.nflag -= 1;
-    v.flist[cbase + pos] = v.flist[cbase + s.nflag];
-    v.counters[(size_t)u * kCounters + 0] += 1;
-  }
-  __syncthreads();
-}
-
-template <int DT>
-__device__ __forceinline__ void split_cluster(const View& v, int u, int j, int pos, SplitSmem& s) {
-  const int tid = threadIdx.x;
-  const size_t cbase = (size_t)u * v.Mcap;
-  const int m = v.cn[cbase + j] + v.cb[cbase + j];
-  if (m > kMaxSplitMembers) {
-    if (tid == 0) v.err[u] |= DYNAKV_ERR_SPLIT_SIZE;
-    return;
-  }
-  __syncthreads();
-  const int npg = (m + kPageTokens - 1) / kPageTokens;
-  if (tid < kInlinePages && tid < npg) s.chain[tid] = v.cpg[(cbase + j) * kInlinePages + tid];
-  __syncthreads();
-  if (tid == 0) {
-    for (int k = kInlinePages; k < npg; ++k) s.chain[k] = v.pnext[(size_t)u * v.Pcap + s.chain[k - 1]];
-    s.nchain = npg;
-  }
-  __syncthreads();
-  if (m <= (DT == DYNAKV_F32 ? 64 : 128)) split_cluster_impl<DT, true>(v, u, j, pos, m, s);
-  else split_cluster_impl<DT, false>(v, u, j, pos, m, s);
-}
-
-// ---- small clusters: one wavefront per split ---------------------------------------------------------
-// Most clusters that get split hold a few dozen entries at most.  Such a split keeps one wavefront busy, so
-// up to four flagged clusters of a unit are split side by side, one per wavefront, with no workgroup barrier
-// inside the 2-means: lane = member for distances and assignments, lane = coordinate (two each) for sums over
-// members.  The arithmetic is the one of split_cluster_impl, term for term.  What depends on the order of the
-// splits (new cluster ids, page allocation) is done by one thread between the two wavefront phases.
-constexpr int kWaveSplits = kSplitThreads / 64;
-constexpr int kWaveStage = 64 * kStageRow16 * 2;                 // 64 rows of a 16-bit type, 32 of float32
-static_assert(32 * kStageRow32 * 4 <= kWaveStage, "float32 rows must fit");
-constexpr int kWavePages = 64 / kPageTokens;                     // pages of the largest such cluster
-// Values of the first members (16-byte chunk t = 64k + lane of the member-major array of V rows, k < kVAhead:
-// 16 members of a 16-bit type, 8 of float32) are requested together with the keys and wait in registers until
-// the children's pages are known.
-constexpr int kVAhead = 4;
-
-struct WaveCtx {
-  alignas(16) unsigned char stage[kWaveStage];
-  double cA[kHeadDim], cB[kHeadDim];
-  float rA[kHeadDim], rB[kHeadDim];
-  double dist[64];
-  double m2[2];
-  unsigned char side[64], perm[64], inv[64];     // inv[member] = its place in perm
-  int chain[kWavePages], newpg[kWavePages + 2];
-  int j, m, ok, nS, idM;
-};
-
-__device__ __forceinline__ void wave_sync() {   // LDS written by some lanes of this wavefront, read by others
-  asm volatile("" ::: "memory");
-  __builtin_amdgcn_wave_barrier();
-  asm volatile("" ::: "memory");
-}
-
-template <int DT>
-__device__ __forceinline__ float wkey(const WaveCtx& c, int i, int d) {
-  if constexpr (DT == DYNAKV_F32) return ((const float*)c.stage)[i * kStageRow32 + d];
-  else {
-    const uint16_t h = ((const uint16_t*)c.stage)[i * kStageRow16 + d];
-    return DT == DYNAKV_F16 ? f16_to_float(h) : bf16_to_float(h);
-  }
-}
-template <int DT>
-__device__ __forceinline__ void wkey8(const WaveCtx& c, int i, int d8, float (&x)[8]) {
-  if constexpr (DT == DYNAKV_F32) {
-    const f4* p = (const f4*)((const float*)c.stage + i * kStageRow32 + d8 * 8);
-    const f4 a = p[0], b = p[1];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) { x[e] = a[e]; x[4 + e] = b[e]; }
-  } else {
-    const uint4 w = *(const uint4*)((const uint16_t*)c.stage + i * kStageRow16 + d8 * 8);
-    const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const uint16_t h = (uint16_t)(ww[e >> 1] >> ((e & 1) * 16));
-      x[e] = DT == DYNAKV_F16 ? f16_to_float(h) : bf16_to_float(h);
-    }
-  }
-}
-
-// Key access in the form quad_sqdist expects.
-template <int DT>
-struct WaveKeys {
-  const WaveCtx& c;
-  __device__ void get8(int i, int d8, float (&x)[8]) const { wkey8<DT>(c, i, d8, x); }
-};
-
-// Wavefront arg-max of (value, index), index < 0 = none, equal values to the lowest index; all lanes get it.
-__device__ __forceinline__ void wave_argmax(double& val, int& idx) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    const double ov = __shfl_xor(val, o);
-    const int oi = __shfl_xor(idx, o);
-    if (oi >= 0 && (idx < 0 || ov > val || (ov == val && oi < idx))) { val = ov; idx = oi; }
-  }
-}
-
-// Sums over the members at(q), q = q0..q1-1, of coordinates d and d + 64, each added one by one in that order.
-// With SIDES the members of side 0 go to (a0, a1) and those of side 1 to (b0, b1); otherwise all go to (a0, a1).
-// A member that does not belong to a sum adds +0.0, which leaves a float64 sum unchanged.  Eight loads per
-// round trip to LDS.
-template <int DT, bool SIDES, class At>
-__device__ __forceinline__ void wave_sums(const WaveCtx& c, int q0, int q1, int d, At&& at, double& a0, double& a1,
-                                          double& b0, double& b1) {
-  a0 = 0.0; a1 = 0.0; b0 = 0.0; b1 = 0.0;
-  for (int r0 = q0; r0 < q1; r0 += 8) {
-    float x0[8], x1[8];
-    bool sa[8], sb[8];
-#pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      const int i = at(min(r0 + k, q1 - 1));
-      const bool in = r0 + k < q1;
-      x0[k] = wkey<DT>(c, i, d);
-      x1[k] = wkey<DT>(c, i, d + 64);
-      const unsigned char sd = SIDES ? c.side[i] : (unsigned char)0;
-      sa[k] = in && sd == 0;
-      sb[k] = in && sd == 1;
-    }
-    asm volatile("" ::: "memory");
-#pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      a0 += (double)(sa[k] ? x0[k] : 0.f);
-      a1 += (double)(sa[k] ? x1[k] : 0.f);
-      if (SIDES) {
-        b0 += (double)(sb[k] ? x0[k] : 0.f);
-        b1 += (double)(sb[k] ? x1[k] : 0.f);
-      }
-    }
-  }
-}
-
-// First phase, one wavefront: stage the keys (c.chain lists their pages), 2-means, stable partition.  Sets
-// c.ok, c.nS, c.perm.
-template <int DT>
-__device__ inline void wave_split_decide(const View& v, int u, WaveCtx& c, uint4 (&vahead)[kVAhead], int& pos_ahead) {
-  const int lane = threadIdx.x & 63;
-  constexpr int kEs = DT == DYNAKV_F32 ? 4 : 2;
-  constexpr int kChunks = kHeadDim * kEs / 16;
-  constexpr int kRowBytes = (DT == DYNAKV_F32 ? kStageRow32 : kStageRow16) * kEs;
-  const char* const pool = v.pages + (size_t)u * v.Pcap * ((size_t)kPageElems * kEs);
-  const int m = c.m;
-  for (int t0 = 0; t0 < m * kChunks; t0 += 4 * 64) {       // four loads in flight per lane
-    uint4 w[4];
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      const int t = min(t0 + k * 64 + lane, m * kChunks - 1);
-      const int i = t / kChunks, ch = t % kChunks;
-      const size_t off = (size_t)(DT == DYNAKV_F32 ? k_index32(i & 15, 4 * ch) : k_index16(i & 15, 8 * ch)) * kEs;
-      w[k] = *(const uint4*)(pool + (size_t)c.chain[i >> 4] * (kPageElems * kEs) + off);
-    }
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      const int t = t0 + k * 64 + lane;
-      if (t < m * kChunks) *(uint4*)(c.stage + (size_t)(t / kChunks) * kRowBytes + (t % kChunks) * 16) = w[k];
-    }
-  }
-#pragma unroll
-  for (int k = 0; k < kVAhead; ++k) {
-    const int t = k * 64 + lane, i = t / kChunks, ch = t % kChunks;
-    vahead[k] = uint4{0, 0, 0, 0};
-    if (i < m) {
-      const size_t off = (size_t)(DT == DYNAKV_F32 ? v_index32(i & 15, 4 * ch) : v_index16(i & 15, 8 * ch)) * kEs;
-      vahead[k] = *(const uint4*)(pool + (size_t)c.chain[i >> 4] * (kPageElems * kEs) + off);
-    }
-  }
-  pos_ahead = lane < m ? v.ppos[((size_t)u * v.Pcap + c.chain[lane >> 4]) * kPageTokens + (lane & 15)] : 0;
-  wave_sync();
-  const WaveKeys<DT> ks{c};
-  const int grp = lane >> 2, kb = lane & 3;      // four lanes per member in the distance passes
-  auto ident = [](int q) { return q; };
-  bool can = m >= 2;
-  if (can) {
-    // seeds: A = member farthest from the mean of all members, B = member farthest from A
-    double s0, s1, u0, u1, dummy;
-    wave_sums<DT, false>(c, 0, m, lane, ident, s0, s1, u0, u1);
-    c.cA[lane] = s0 / (double)m; c.cA[lane + 64] = s1 / (double)m;
-    wave_sync();
-    double bv = -1.0;
-    int a = -1;
-    for (int base = 0; base < m; base += 16) {
-      const int i = base + grp;
-      double t;
-      quad_sqdist<WaveKeys<DT>, double>(ks, min(i, m - 1), kb, c.cA, nullptr, t, dummy);
-      if (kb == 0 && i < m && (a < 0 || t > bv)) { bv = t; a = i; }
-    }
-    wave_argmax(bv, a);
-    c.cB[lane] = (double)wkey<DT>(c, a, lane); c.cB[lane + 64] = (double)wkey<DT>(c, a, lane + 64);
-    wave_sync();
-    bv = -1.0;
-    int b = -1;
-    for (int base = 0; base < m; base += 16) {
-      const int i = base + grp;
-      double t;
-      quad_sqdist<WaveKeys<DT>, double>(ks, min(i, m - 1), kb, c.cB, nullptr, t, dummy);
-      if (kb == 0 && i < m && (b < 0 || t > bv)) { bv = t; b = i; }
-    }
-    wave_argmax(bv, b);
-    can = bv > 0.0;                          // false: all members identical
-    if (can) {
-      c.cA[lane] = c.cB[lane]; c.cA[lane + 64] = c.cB[lane + 64];
-      c.cB[lane] = (double)wkey<DT>(c, b, lane); c.cB[lane + 64] = (double)wkey<DT>(c, b, lane + 64);
-      c.side[lane] = 2;
-      wave_sync();
-      for (int it = 0; it < 16; ++it) {
-        bool moved = false;
-        int nA = 0;
-        for (int base = 0; base < m; base += 16) {
-          const int i = base + grp;
-          double dA, dB;
-          quad_sqdist<WaveKeys<DT>, double>(ks, min(i, m - 1), kb, c.cA, c.cB, dA, dB);
-          const bool own = kb == 0 && i < m;
-          const unsigned char ns = dA <= dB ? 0 : 1;     // tie -> side A
-          moved = moved || __ballot(own && ns != c.side[min(i, 63)]) != 0;
-          nA += __popcll(__ballot(own && ns == 0));
-          if (own) c.side[i] = ns;
-        }
-        wave_sync();
-        if (!moved) break;
-        if (nA == 0 || nA == m) { can = false; break; }
-        double a0, a1, b0, b1;
-        wave_sums<DT, true>(c, 0, m, lane, ident, a0, a1, b0, b1);
-        c.cA[lane] = a0 / (double)nA; c.cA[lane + 64] = a1 / (double)nA;
-        c.cB[lane] = b0 / (double)(m - nA); c.cB[lane + 64] = b1 / (double)(m - nA);
-        wave_sync();
-      }
-    }
-  }
-  int nS = m;
-  if (can) {        // stable partition: the child that holds the earliest entry comes first and keeps the id
-    const unsigned char keep = c.side[0];
-    const unsigned long long mask = __ballot(lane < m && c.side[lane] == keep);
-    const int before = __popcll(mask & ((1ull << lane) - 1ull));
-    nS = __popcll(mask);
-    if (lane < m) {
-      const int q = (mask >> lane) & 1ull ? before : nS + lane - before;
-      c.perm[q] = (unsigned char)lane;
-      c.inv[lane] = (unsigned char)q;
-    }
-  } else if (lane < m) {
-    c.perm[lane] = (unsigned char)lane;
-    c.inv[lane] = (unsigned char)lane;
-  }
-  if (lane == 0) { c.ok = can ? 1 : 0; c.nS = nS; }
-  wave_sync();
-}
-
-// Second phase, one wavefront: children's pages, exact statistics and records.  With c.ok == 0 the cluster is
-// only unflagged, with exact statistics.
-template <int DT>
-__device__ inline void wave_split_commit(const View& v, int u, WaveCtx& c, const uint4 (&vahead)[kVAhead],
-                                         int pos_ahead) {
-  const int lane = threadIdx.x & 63;
-  const size_t cbase = (size_t)u * v.Mcap;
-  constexpr int kEs = DT == DYNAKV_F32 ? 4 : 2;
-  constexpr int kChunks = kHeadDim * kEs / 16;
-  constexpr int kRowBytes = (DT == DYNAKV_F32 ? kStageRow32 : kStageRow16) * kEs;
-  constexpr size_t kPageBytes = (size_t)kPageElems * kEs;
-  char* const pool = v.pages + (size_t)u * v.Pcap * kPageBytes;
-  const int m = c.m, j = c.j, nS = c.nS, nM = m - nS, idM = c.ok ? c.idM : -1;
-  const int pS = (nS + kPageTokens - 1) / kPageTokens, pM = (nM + kPageTokens - 1) / kPageTokens, need = pS + pM;
-  if (c.ok) {
-    if (lane < need) v.pnext[(size_t)u * v.Pcap + c.newpg[lane]] = (lane == pS - 1 || lane == need - 1) ? -1 : c.newpg[lane + 1];
-    for (int t = lane; t < m * kChunks; t += 64) {
-      const int q = t / kChunks, ch = t % kChunks;
-      const int i = c.perm[q];
-      const int r = q < nS ? q : q - nS;
-      const int dpage = c.newpg[(q < nS ? 0 : pS) + (r >> 4)];
-      const size_t off = (size_t)(DT == DYNAKV_F32 ? k_index32(r & 15, 4 * ch) : k_index16(r & 15, 8 * ch)) * kEs;
-      *(uint4*)(pool + (size_t)dpage * kPageBytes + off) = *(const uint4*)(c.stage + (size_t)i * kRowBytes + ch * 16);
-    }
-    // values chunk by chunk like the keys, straight from their old pages: first the chunks requested ahead
-    auto vchunk = [](int slot, int ch) -> size_t {
-      return (size_t)(DT == DYNAKV_F32 ? v_index32(slot, 4 * ch) : v_index16(slot, 8 * ch)) * kEs;
-    };
-    auto vdest = [&](int i, int ch) -> char* {
-      const int q = c.inv[i];
-      const int r = q < nS ? q : q - nS;
-      return (char*)pool + (size_t)c.newpg[(q < nS ? 0 : pS) + (r >> 4)] * kPageBytes + vchunk(r & 15, ch);
-    };
-#pragma unroll
-    for (int k = 0; k < kVAhead; ++k) {
-      const int t = k * 64 + lane, i = t / kChunks;
-      if (i < m) *(uint4*)vdest(i, t % kChunks) = vahead[k];
-    }
-    // then the members past those, four loads in flight per lane
-    for (int t0 = kVAhead * 64; t0 < m * kChunks; t0 += 4 * 64) {
-      uint4 w[4];
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const int t = min(t0 + k * 64 + lane, m * kChunks - 1), i = t / kChunks;
-        w[k] = *(const uint4*)(pool + (size_t)c.chain[i >> 4] * kPageBytes + vchunk(i & 15, t % kChunks));
-      }
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const int t = t0 + k * 64 + lane;
-        if (t < m * kChunks) *(uint4*)vdest(t / kChunks, t % kChunks) = w[k];
-      }
-    }
-    if (lane < m) {
-      const int q = c.inv[lane];
-      const int r = q < nS ? q : q - nS;
-      const int dpage = c.newpg[(q < nS ? 0 : pS) + (r >> 4)];
-      v.ppos[((size_t)u * v.Pcap + dpage) * kPageTokens + (r & 15)] = pos_ahead;
-    }
-  }
-  // exact statistics: float32 means, then M2 about those means, members in their new order
-  auto at = [&](int q) { return (int)c.perm[q]; };
-  double s0, s1, u0, u1;
-  wave_sums<DT, false>(c, 0, nS, lane, at, s0, s1, u0, u1);
-  c.rA[lane] = nS > 0 ? (float)(s0 / (double)nS) : 0.f;
-  c.rA[lane + 64] = nS > 0 ? (float)(s1 / (double)nS) : 0.f;
-  store_centroid(v, u, j, lane, c.rA[lane]); store_centroid(v, u, j, lane + 64, c.rA[lane + 64]);
-  if (idM >= 0) {
-    wave_sums<DT, false>(c, nS, m, lane, at, s0, s1, u0, u1);
-    c.rB[lane] = nM > 0 ? (float)(s0 / (double)nM) : 0.f;
-    c.rB[lane + 64] = nM > 0 ? (float)(s1 / (double)nM) : 0.f;
-    store_centroid(v, u, idM, lane, c.rB[lane]); store_centroid(v, u, idM, lane + 64, c.rB[lane + 64]);
-  }
-  wave_sync();
-  {
-    const WaveKeys<DT> ks{c};
-    const int grp = lane >> 2, kb = lane & 3;
-    for (int base = 0; base < m; base += 16) {
-      const int q = base + grp, qc = min(q, m - 1);
-      double dv, dummy;
-      quad_sqdist<WaveKeys<DT>, float>(ks, c.perm[qc], kb, qc < nS ? c.rA : c.rB, nullptr, dv, dummy);
-      if (kb == 0 && q < m) c.dist[q] = dv;
-    }
-  }
-  wave_sync();
-  if (lane < 2) {
-    const int q0 = lane ? nS : 0, q1 = lane ? m : nS;
-    double acc = 0.0;
-    for (int r0 = q0; r0 < q1; r0 += 8) {
-      double x[8];
-#pragma unroll
-      for (int k = 0; k < 8; ++k) x[k] = r0 + k < q1 ? c.dist[r0 + k] : 0.0;
-      asm volatile("" ::: "memory");
-#pragma unroll
-      for (int k = 0; k < 8; ++k) acc += x[k];
-    }
-    c.m2[lane] = acc;
-  }
-  wave_sync();
-  if (c.ok && lane < kInlinePages) {
-    v.cpg[(cbase + j) * kInlinePages + lane] = lane < pS ? c.newpg[lane] : -1;
-    v.cpg[(cbase + idM) * kInlinePages + lane] = lane < pM ? c.newpg[pS + lane] : -1;
-  }
-  if (lane == 0) {
-    v.cn[cbase + j] = nS; v.cb[cbase + j] = 0; v.cflag[cbase + j] = 0; v.cM2[cbase + j] = c.m2[0];
-    if (c.ok) {
-      v.ctail[cbase + j] = c.newpg[pS - 1];
-      v.cn[cbase + idM] = nM; v.cb[cbase + idM] = 0; v.cflag[cbase + idM] = 0; v.cM2[cbase + idM] = c.m2[1];
-      v.ctail[cbase + idM] = c.newpg[pS + pM - 1];
-      v.in_req[cbase + idM] = 0;
-    }
-  }
-}
-
-// Plan of one unit's splits, made from the list of its flagged clusters (at most 64 of them).
-constexpr int kFreeAhead = 24;
-struct SplitPlan {
-  int id[64], req[64], cb[64], m[64];   // the flagged clusters
-  int pg[64][kWavePages];               // their first pages
-  int cand[64];                          // positions in the list, in the order of the splits
-  int n_cand, forced, fast;
-  int M, top, bump;                      // the unit's counters while the plan is carried out
-  int fl[kFreeAhead], fl_base;           // top of the free-page stack, read ahead: fl[k] = entry fl_base - 1 - k
-};
-
 template <int DT>
 __global__ __launch_bounds__(kSplitThreads) void split_kernel(View v) {
-  constexpr int NT = kSplitThreads;
-  constexpr size_t kRaw = sizeof(SplitSmem) > kWaveSplits * sizeof(WaveCtx) ? sizeof(SplitSmem) : kWaveSplits * sizeof(WaveCtx);
-  __shared__ __align__(16) unsigned char raw[kRaw];     // either the workgroup-wide split or four wavefront splits
-  __shared__ SplitPlan pl;
-  __shared__ int s_min;
-  __shared__ long long s_tot;
-  SplitSmem& s = *(SplitSmem*)raw;
-  WaveCtx* const wc = (WaveCtx*)raw;
-  const int u = blockIdx.x, tid = threadIdx.x;
-  const size_t cbase = (size_t)u * v.Mcap;
-  // requested together with the flag count, so that the plan below starts one round trip earlier
-  const int c_ahead = tid < min(64, v.Mcap) ? v.flist[cbase + tid] : 0;
-  const int top_ahead = v.free_top[u];
-  const int M0 = v.M[u];
-  const int nf0 = v.nflag[u];
-  if (nf0 == 0) return;
-
-  // ---- plan: which clusters are split, in which order
-  if (nf0 <= 64) {
-    if (tid < nf0) {
-      const int c = c_ahead;
-      const int b = v.cb[cbase + c];
-      const int4 pg = *(const int4*)&v.cpg[(cbase + c) * kInlinePages];
-      pl.id[tid] = c; pl.req[tid] = v.in_req[cbase + c]; pl.cb[tid] = b; pl.m[tid] = v.cn[cbase + c] + b;
-      pl.pg[tid][0] = pg.x; pl.pg[tid][1] = pg.y; pl.pg[tid][2] = pg.z; pl.pg[tid][3] = pg.w;
-    }
-    if (tid >= 64 && tid < 64 + kFreeAhead) {       // everything the page allocation will need, in the same round trips
-      const int top = top_ahead, k = tid - 64;
-      if (k < top) pl.fl[k] = v.freelist[(size_t)u * v.Pcap + top - 1 - k];
-      if (k == 0) { pl.M = M0; pl.top = top; pl.bump = v.bump[u]; pl.fl_base = top; }
-    }
-    __syncthreads();
-    if (tid == 0) {
-      // delayed splits: flagged clusters of the active set (all flagged ones if nothing is buffered), ascending id
-      int nc = 0;
-      for (int last = -1;;) {
-        int best = -1;
-        for (int i = 0; i < nf0; ++i)
-          if (pl.id[i] > last && (v.Bmax == 0 || pl.req[i]) && (best < 0 || pl.id[i] < pl.id[best])) best = i;
-        if (best < 0) break;
-        pl.cand[nc++] = best;
-        last = pl.id[best];
-        pl.req[best] = 2;                  // taken
-      }
-      // then, if the remaining buffers hold B_max entries, the fullest of them (lowest id among equals)
-      int forced = 0;
-      if (v.Bmax > 0) {
-        long long total = 0;
-        int best = -1;
-        for (int i = 0; i < nf0; ++i)
-          if (pl.req[i] != 2) {
-            total += pl.cb[i];
-            if (best < 0 || pl.cb[i] > pl.cb[best] || (pl.cb[i] == pl.cb[best] && pl.id[i] < pl.id[best])) best = i;
-          }
-        if (best >= 0 && total >= v.Bmax) { pl.cand[nc++] = best; forced = 1; }
-      }
-      // the wavefront path takes the plan if every cluster is small and no capacity limit can be hit
-      constexpr int kSmall = DT == DYNAKV_F32 ? 32 : 64;
-      long long pages = 0;
-      bool small = true;
-      for (int k = 0; k < nc; ++k) {
-        const int mm = pl.m[pl.cand[k]];
-        small = small && mm <= kSmall;
-        pages += (mm + kPageTokens - 1) / kPageTokens + 1;
-      }
-      pl.n_cand = nc; pl.forced = forced;
-      pl.fast = small && pl.M + nc <= v.Mcap && pages <= (long long)pl.top + (v.Pcap - pl.bump);
-    }
-    __syncthreads();
-    if (pl.fast) {
-      const int wave = tid >> 6, lane = tid & 63;
-      const int nc = pl.n_cand;
-      for (int base = 0; base < nc; base += kWaveSplits) {
-        const bool mine = base + wave < nc;
-        uint4 vahead[kVAhead];
-        int pos_ahead = 0;
-        WaveCtx& c = wc[wave];
-        if (mine) {
-          const int at = pl.cand[base + wave];
-          if (lane == 0) { c.j = pl.id[at]; c.m = pl.m[at]; }
-          if (lane < kWavePages) c.chain[lane] = pl.pg[at][lane];
-          wave_sync();
-          wave_split_decide<DT>(v, u, c, vahead, pos_ahead);
-        }
-        __syncthreads();
-        if (tid == 0) {                    // ids and pages, in the order of the splits
-          for (int w = 0; w < kWaveSplits && base + w < nc; ++w) {
-            WaveCtx& cw = wc[w];
-            if (!cw.ok) continue;
-            cw.idM = pl.M++;
-            const int need = (cw.nS + kPageTokens - 1) / kPageTokens + (cw.m - cw.nS + kPageTokens - 1) / kPageTokens;
-            const int from_free = min(need, pl.top);
-            for (int k = 0; k < need; ++k) {
-              const int ahead = pl.fl_base - (pl.top - k);       // pl.fl holds the stack as it was at fl_base
-              cw.newpg[k] = k >= from_free ? pl.bump + (k - from_free)
-                            : (ahead >= 0 && ahead < kFreeAhead) ? pl.fl[ahead]
-                                                                  : v.freelist[(size_t)u * v.Pcap + pl.top - 1 - k];
-            }
-            pl.top -= from_free;
-            pl.bump += need - from_free;
-          }
-        }
-        __syncthreads();
-        if (mine) wave_split_commit<DT>(v, u, c, vahead, pos_ahead);
-        __syncthreads();
-        if (tid == 0) {                    // the parents' pages are recycled only now
-          for (int w = 0; w < kWaveSplits && base + w < nc; ++w) {
-            const WaveCtx& cw = wc[w];
-            v.counters[(size_t)u * kCounters + (cw.ok ? 0 : 1)] += 1;
-            if (!cw.ok) continue;
-            const int npg = (cw.m + kPageTokens - 1) / kPageTokens;
-            for (int k = 0; k < npg; ++k) v.freelist[(size_t)u * v.Pcap + pl.top++] = cw.chain[k];
-            pl.fl_base = -(1 << 30);         // the stack has changed: what was read ahead no longer applies
-          }
-        }
-        __syncthreads();
-      }
-      if (tid == 0) {
-        int n = 0;
-        for (int k = 0; k < nc; ++k) pl.id[pl.cand[k]] = -1;
-        for (int i = 0; i < nf0; ++i)
-          if (pl.id[i] >= 0) v.flist[cbase + n++] = pl.id[i];
-        v.nflag[u] = n; v.M[u] = pl.M; v.free_top[u] = pl.top; v.bump[u] = pl.bump;
-        if (pl.forced) v.counters[(size_t)u * kCounters + 2] += 1;
-      }
-      return;
-    }
-  }
-
-  // ---- general path: one split at a time by the whole workgroup
-  if (tid == 0) { s.M = M0; s.nflag = nf0; s.a_top = v.free_top[u]; s.a_bump = v.bump[u]; }
-  // One loop, one call site: first the delayed splits (flagged clusters that the last retrieval selected, in
-  // ascending id), then, once, the forced split of the fullest buffer if the buffers hold B_max entries.  Both
-  // searches walk the list of flagged clusters, which holds a handful of ids.
-  __syncthreads();
-  int cursor = 0;
-  bool forced_done = false;
-  while (true) {
-    int j = -1, pos = -1;
-    const int nf = s.nflag;
-    if (!forced_done) {
-      if (tid == 0) s_min = 0x7FFFFFFF;
-      __syncthreads();
-      for (int i = tid; i < nf; i += NT) {
-        const int c = v.flist[cbase + i];
-        if (c >= cursor && c < M0 && (v.Bmax == 0 || v.in_req[cbase + c])) atomicMin(&s_min, c * kMaxClusters + i);
-      }
-      __syncthreads();
-      if (s_min != 0x7FFFFFFF) { j = s_min / kMaxClusters; pos = s_min % kMaxClusters; }
-      __syncthreads();
-      if (j >= 0) cursor = j + 1;
-    }
-    if (j < 0) {
-      if (forced_done) break;
-      forced_done = true;
-      if (!(v.Bmax > 0 && nf > 0)) break;
-      if (tid == 0) s_tot = 0;
-      __syncthreads();
-      double bv = -1.0; int bi = -1;
-      long long tot = 0;
-      for (int i = tid; i < nf; i += NT) {
-        const int c = v.flist[cbase + i];
-        const int b = v.cb[cbase + c];
-        tot += b;
-        if ((double)b > bv || ((double)b == bv && c * kMaxClusters + i < bi)) { bv = (double)b; bi = c * kMaxClusters + i; }
-      }
-      if (tot) atomicAdd((unsigned long long*)&s_tot, (unsigned long long)tot);
-      block_argmax(bv, bi, s.sv, s.si);
-      const int arg = s.si[0];
-      const long long total = s_tot;
-      __syncthreads();
-      if (!(arg >= 0 && total >= v.Bmax)) break;
-      if (tid == 0) v.counters[(size_t)u * kCounters + 2] += 1;
-      j = arg / kMaxClusters; pos = arg % kMaxClusters;
-    }
-    split_cluster<DT>(v, u, j, pos, s);
-    __syncthreads();
-    if (forced_done) break;
-  }
-  __syncthreads();
-  if (tid == 0) { v.M[u] = s.M; v.nflag[u] = s.nflag; v.free_top[u] = s.a_top; v.bump[u] = s.a_bump; }
+  __shared__ __align__(16) unsigned char raw[kSplitRaw];
+  __shared__ SplitWork wk;
+  split_unit<DT>(v, blockIdx.x, raw, wk);
 }
 
 // ------------------------------------------------------------------------------------------- export

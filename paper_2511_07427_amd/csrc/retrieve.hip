@@ -5,7 +5,9 @@
 //   gather_attend  - streams the selected clusters' pages once; QK^T and PV on matrix cores with an
 //                    online (running-max) softmax, so any gather order is overflow-safe; split over
 //                    several workgroups per unit and merged by the last one to arrive.
-#include "append.hpp"
+#include <type_traits>
+
+#include "split.hpp"
 
 namespace dynakv {
 
@@ -487,7 +489,7 @@ struct Tile {
 };
 // eK, eV: list entries of the lane's QK slot and of its PV quad (-1: none); ES = bytes per element.
 template <int ES>
-__device__ inline Tile make_tile(const char* pages, int eK, int eV, int lane) {
+__device__ __forceinline__ Tile make_tile(const char* pages, int eK, int eV, int lane) {
   constexpr size_t kPageBytes = (size_t)kPageElems * ES;
   Tile t;
   t.kok = eK >= 0 && (lane & 3) <= (eK & 3);
@@ -508,12 +510,12 @@ struct Frag<DYNAKV_F32> {
   struct VT { f4 c[8]; };              // c[cb][kk] = V[token 4*(lane/16) + kk][column out_col(cb, lane%16)]
   struct Qf { f4 b[8]; };
   static constexpr int kVTile = kVTile32;
-  static __device__ void load_q(Qf& q, const void* Q, size_t row, int lg, bool ok) {
+  static __device__ __forceinline__ void load_q(Qf& q, const void* Q, size_t row, int lg, bool ok) {
     const float* p = (const float*)Q + row * kHeadDim + 4 * lg;
 #pragma unroll
     for (int s = 0; s < 8; ++s) q.b[s] = ok ? *(const f4*)(p + 16 * s) : f4{0, 0, 0, 0};
   }
-  static __device__ void load(KV& f, const Tile& t) {
+  static __device__ __forceinline__ void load(KV& f, const Tile& t) {
     const f4* kp = (const f4*)t.k;
     const f4* vp = (const f4*)(t.k + 2048 * 4);
 #pragma unroll
@@ -522,20 +524,20 @@ struct Frag<DYNAKV_F32> {
     for (int s = 0; s < 8; ++s) f.v[s] = t.kok ? vp[s * 4] : f4{0, 0, 0, 0};
   }
   // V rows -> LDS tile of this wavefront (zeros for empty slots), then back with tokens innermost
-  static __device__ void stage(const KV& f, char* tile, int lane) {
+  static __device__ __forceinline__ void stage(const KV& f, char* tile, int lane) {
     char* row = tile + (lane & 15) * kVRow32 + (lane >> 4) * 16;
 #pragma unroll
     for (int s = 0; s < 8; ++s) *(f4*)(row + s * 64) = f.v[s];
   }
-  static __device__ int out_col(int cb, int a) { return 16 * cb + a; }   // row a of accumulator block cb
-  static __device__ void unstage(VT& t, const char* tile, int lane) {
+  static __device__ __forceinline__ int out_col(int cb, int a) { return 16 * cb + a; }   // row a of accumulator block cb
+  static __device__ __forceinline__ void unstage(VT& t, const char* tile, int lane) {
     const char* p = tile + (lane >> 4) * 4 * kVRow32 + (lane & 15) * 4;
 #pragma unroll
     for (int cb = 0; cb < 8; ++cb)
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) t.c[cb][kk] = *(const float*)(p + kk * kVRow32 + cb * 64);
   }
-  static __device__ f4 qk(const KV& f, const Qf& q) {
+  static __device__ __forceinline__ f4 qk(const KV& f, const Qf& q) {
     f4 a = {0, 0, 0, 0};
 #pragma unroll
     for (int s = 0; s < 8; ++s)
@@ -543,7 +545,7 @@ struct Frag<DYNAKV_F32> {
       for (int i = 0; i < 4; ++i) a = __builtin_amdgcn_mfma_f32_16x16x4f32(f.k[s][i], q.b[s][i], a, 0, 0, 0);
     return a;
   }
-  static __device__ void pv(f4 (&acc)[8], const VT& f, const float (&p)[4]) {
+  static __device__ __forceinline__ void pv(f4 (&acc)[8], const VT& f, const float (&p)[4]) {
 #pragma unroll
     for (int c = 0; c < 8; ++c)
 #pragma unroll
@@ -557,12 +559,12 @@ struct Frag16 {
   struct VT { uint2 c[8]; };               // c[cb] = V[tokens 4*(lane/16) .. +3][column out_col(cb, lane%16)]
   struct Qf { uint4 b[4]; };
   static constexpr int kVTile = kVTile16;
-  static __device__ void load_q(Qf& q, const void* Q, size_t row, int lg, bool ok) {
+  static __device__ __forceinline__ void load_q(Qf& q, const void* Q, size_t row, int lg, bool ok) {
     const uint16_t* p = (const uint16_t*)Q + row * kHeadDim + 8 * lg;
 #pragma unroll
     for (int s = 0; s < 4; ++s) q.b[s] = ok ? *(const uint4*)(p + 32 * s) : uint4{0, 0, 0, 0};
   }
-  static __device__ void load(KV& f, const Tile& t) {
+  static __device__ __forceinline__ void load(KV& f, const Tile& t) {
     const uint4* kp = (const uint4*)t.k;
     const uint4* vp = (const uint4*)(t.k + 2048 * 2);
 #pragma unroll
@@ -571,14 +573,14 @@ struct Frag16 {
     for (int s = 0; s < 4; ++s) f.v[s] = t.kok ? vp[s * 4] : uint4{0, 0, 0, 0};
   }
   // V rows -> LDS tile of this wavefront (zeros for empty slots), then back with tokens innermost
-  static __device__ void stage(const KV& f, char* tile, int lane) {
+  static __device__ __forceinline__ void stage(const KV& f, char* tile, int lane) {
     char* row = tile + (lane & 15) * kVRow16 + (lane >> 4) * 16;
 #pragma unroll
     for (int s = 0; s < 4; ++s) *(uint4*)(row + s * 64) = f.v[s];
   }
   // row a of accumulator block cb is this output column: a lane reads column pairs (one 32-bit word per token)
-  static __device__ int out_col(int cb, int a) { return 32 * (cb >> 1) + 2 * a + (cb & 1); }
-  static __device__ void unstage(VT& t, const char* tile, int lane) {
+  static __device__ __forceinline__ int out_col(int cb, int a) { return 32 * (cb >> 1) + 2 * a + (cb & 1); }
+  static __device__ __forceinline__ void unstage(VT& t, const char* tile, int lane) {
     const char* p = tile + (lane >> 4) * 4 * kVRow16 + (lane & 15) * 4;
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
@@ -589,7 +591,7 @@ struct Frag16 {
       t.c[2 * s + 1] = uint2{(w[0] >> 16) | (w[1] & 0xffff0000u), (w[2] >> 16) | (w[3] & 0xffff0000u)};
     }
   }
-  static __device__ f4 qk(const KV& f, const Qf& q) {
+  static __device__ __forceinline__ f4 qk(const KV& f, const Qf& q) {
     f4 a = {0, 0, 0, 0};
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
@@ -600,14 +602,14 @@ struct Frag16 {
     }
     return a;
   }
-  static __device__ f4 mma4(uint2 a, uint2 b, f4 c) {
+  static __device__ __forceinline__ f4 mma4(uint2 a, uint2 b, f4 c) {
     if constexpr (BF)
       return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s4, a), __builtin_bit_cast(s4, b), c, 0, 0, 0);
     else
       return __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(h4, a), __builtin_bit_cast(h4, b), c, 0, 0, 0);
   }
   // p is split into a rounded part and its remainder so that the product keeps float32-like accuracy
-  static __device__ void pv(f4 (&acc)[8], const VT& f, const float (&p)[4]) {
+  static __device__ __forceinline__ void pv(f4 (&acc)[8], const VT& f, const float (&p)[4]) {
     uint16_t hi[4], lo[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -667,7 +669,7 @@ struct Softmax {
 
 // One tile: S^T = K Q^T on the matrix cores, running max / rescale, O^T += V^T P^T.
 template <class F>
-__device__ inline void consume_page(Softmax& st, const typename F::KV& kv, const typename F::Qf& q, int nvq, float sc,
+__device__ __forceinline__ void consume_page(Softmax& st, const typename F::KV& kv, const typename F::Qf& q, int nvq, float sc,
                                     char* vtile, int lane) {
   F::stage(kv, vtile, lane);              // the scores are computed while the V rows settle in LDS
   const f4 sacc = F::qk(kv, q);
@@ -816,7 +818,9 @@ constexpr int kFusedList = 2048;       // gather-list entries it keeps in LDS (l
 // With APPEND the same pass over the centroid table also finds the cluster nearest to the step's new key
 // (one more accumulator per centroid), and the append itself runs at the end of the kernel: a decode step then
 // reads the table once instead of twice.  Scores and selection see the index as it was before the append.
-template <int DT, int NW, int GP, bool APPEND>
+// With SPLIT (only with APPEND) the unit's due splits follow the append in the same launch, carried out by the
+// first kSplitThreads threads after the others have left: a whole decode step is then one kernel.
+template <int DT, int NW, int GP, bool APPEND, bool SPLIT>
 __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const void* Q, int budget, float* out,
                                                                 float* lse, const void* kin, const void* vin) {
   using F = Frag<DT>;
@@ -827,7 +831,9 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   static_assert(kSelRegion >= 2 * kFusedClusters && kKeys + kSizes + kSelRegion + kList >= kMergeBytes, "LDS plan");
   static_assert(NW * F::kVTile <= kKeys + kSizes + kSelRegion, "the V tiles take the space of the selection's tables");
   // scores, sizes, candidates, gather list; after the page loop the front doubles as the merge buffer
-  __shared__ __align__(16) unsigned char smem[kKeys + kSizes + kSelRegion + kList];
+  constexpr size_t kPhases = kKeys + kSizes + kSelRegion + kList;
+  static_assert(!SPLIT || (APPEND && NW * 64 >= kSplitThreads), "splits follow an append");
+  __shared__ __align__(16) unsigned char smem[SPLIT && kSplitRaw > kPhases ? kSplitRaw : kPhases];
   __shared__ double qs[kHeadDim][GP];
   __shared__ AppendSmem ap;
   __shared__ double am_v[16];
@@ -844,18 +850,20 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   const int lane = tid & 63, wave = tid >> 6;
   const int G = v.G;
 
-  // ---- scores (float64; every lane takes two clusters per pass, ja and ja + 64, so that the query operands it
-  // reads from LDS serve both)
+  // ---- scores (float64).  The clusters are dealt in groups of 64 (one per lane): wavefront w takes the groups
+  // w, w + NW, w + 2 NW, ... and works on up to kAtOnce of them at once, so that the query operands it reads from
+  // LDS serve all of them and every wavefront gets the same number of groups to within one.
+  constexpr int kAtOnce = GP <= 4 ? 3 : 2;           // register budget: accumulators and rows in flight per lane
+  constexpr int NA = GP + (APPEND ? 1 : 0);
   const uint16_t* Rq = unit_Rq(v, u);
   // the first rows are requested before anything is waited for (rows up to the table's padded end exist)
-  // (with at most one cluster per lane in all, every lane takes one, so that all wavefronts share the work)
-  uint4 row0[2][4];
-  const int span0 = v.M0 > NT ? 128 : 64;            // the guess behind the early request: M has not been read yet
-  const int j0[2] = {wave * span0 + lane, wave * span0 + (span0 - 64) + lane};
-  const bool early = (size_t)(wave * span0 + span0 - 1) * kHeadDim < v.Rstride;
-  if (early) load_search_head<2>(Rq, j0, row0);
+  uint4 e0 = {}, e1 = {}, e2 = {}, e3 = {};
+  const bool early = (size_t)(wave * 64 + 63) * kHeadDim < v.Rstride;
+  if (early) {
+    const uint4* p = (const uint4*)(Rq + rq_index(wave * 64 + lane, 0));
+    e0 = p[0]; e1 = p[64]; e2 = p[128]; e3 = p[192];
+  }
   const int M = v.M[u];
-  const int span = M > NT ? 128 : 64;
   for (int t = tid; t < GP * kHeadDim; t += NT) {
     const int g = t / kHeadDim, d = t % kHeadDim;
     qs[d][g] = g < G ? (double)load_elem(Q, ((size_t)u * G + g) * kHeadDim + d, v.dtype) : 0.0;
@@ -876,49 +884,66 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   __syncthreads();
   double near_d = __builtin_inf();
   int near_j = -1;
-  for (int base = wave * span; base < M; base += NW * span) {
-    const bool pair = span == 128 && base + 64 < M;  // wavefront-uniform: the second half exists
-    const int js[2] = {base + lane, pair ? base + 64 + lane : base + lane};
-    uint4 row[2][4];
-    if (base == wave * span && early && span == span0) {
+  // NR groups of this wavefront from group g0 on, NW groups apart
+  auto score_groups = [&](auto nr_tag, int g0, bool first) __attribute__((always_inline)) {
+    constexpr int NR = decltype(nr_tag)::value;
+    int js[NR];
+    uint4 row[NR][4];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) { row[0][i] = row0[0][i]; row[1][i] = pair ? row0[1][i] : row0[0][i]; }
-    } else {
-      load_search_head<2>(Rq, js, row);
+    for (int r = 0; r < NR; ++r) {
+      js[r] = (g0 + r * NW) * 64 + lane;
+      if (r == 0 && first && early) {
+        row[0][0] = e0; row[0][1] = e1; row[0][2] = e2; row[0][3] = e3;
+      } else {
+        const uint4* p = (const uint4*)(Rq + rq_index(js[r], 0));
+#pragma unroll
+        for (int i = 0; i < 4; ++i) row[r][i] = p[i * 64];
+      }
     }
-    constexpr int NA = GP + (APPEND ? 1 : 0);
-    double acc[2][NA];
-    search_sums<NA, 2, DT == DYNAKV_BF16>(Rq, js, row, acc,
-        [&](int d, const float (&x)[2], double (&a)[2][NA]) __attribute__((always_inline)) {
-      const double r0 = (double)x[0], r1 = (double)x[1];
+    double acc[NR][NA];
+    search_sums<NA, NR, DT == DYNAKV_BF16>(Rq, js, row, acc,
+        [&](int d, const float (&x)[NR], double (&a)[NR][NA]) __attribute__((always_inline)) {
+      double r64[NR];
+#pragma unroll
+      for (int r = 0; r < NR; ++r) r64[r] = (double)x[r];
 #pragma unroll
       for (int g = 0; g < GP; ++g) {
         const double qv = qs[d][g];
-        a[0][g] = fma(qv, r0, a[0][g]);
-        a[1][g] = fma(qv, r1, a[1][g]);
+#pragma unroll
+        for (int r = 0; r < NR; ++r) a[r][g] = fma(qv, r64[r], a[r][g]);
       }
       if constexpr (APPEND) {
         const double kv = ap.kd[d];
-        const double t0 = kv - r0, t1 = kv - r1;
-        a[0][GP] = fma(t0, t0, a[0][GP]);
-        a[1][GP] = fma(t1, t1, a[1][GP]);
+#pragma unroll
+        for (int r = 0; r < NR; ++r) {
+          const double t = kv - r64[r];
+          a[r][GP] = fma(t, t, a[r][GP]);
+        }
       }
     });
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const int j = js[h];
-      if (j < M && (h == 0 || pair)) {
+    for (int r = 0; r < NR; ++r) {
+      const int j = js[r];
+      if (j < M) {
         if constexpr (APPEND)
-          if (acc[h][GP] < near_d || near_j < 0) { near_d = acc[h][GP]; near_j = j; }
-        double red = acc[h][0];
+          if (acc[r][GP] < near_d || near_j < 0) { near_d = acc[r][GP]; near_j = j; }
+        double red = acc[r][0];
 #pragma unroll
         for (int g = 1; g < GP; ++g)
-          if (g < G) red = v.group_reduce == DYNAKV_GROUP_MAX ? fmax(red, acc[h][g]) : red + acc[h][g];
+          if (g < G) red = v.group_reduce == DYNAKV_GROUP_MAX ? fmax(red, acc[r][g]) : red + acc[r][g];
         const float sc = (float)(red * v.scale_d);
         v.score[(size_t)u * v.Mcap + j] = sc;
         skey[j] = orderable(sc);
       }
     }
+  };
+  const int ngroup = (M + 63) >> 6;
+  for (int g0 = wave; g0 < ngroup; g0 += kAtOnce * NW) {
+    const int cnt = min(kAtOnce, (ngroup - g0 + NW - 1) / NW);      // wavefront-uniform
+    const bool first = g0 == wave;
+    if (cnt == 1) score_groups(std::integral_constant<int, 1>{}, g0, first);
+    else if (cnt == 2) score_groups(std::integral_constant<int, 2>{}, g0, first);
+    else if constexpr (kAtOnce == 3) score_groups(std::integral_constant<int, 3>{}, g0, first);
   }
 #pragma unroll
   for (int k = 0; k < kFusedClusters / NT; ++k)
@@ -998,9 +1023,16 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   if constexpr (APPEND) {
     if (!room) {
       if (tid == 0) v.err[u] |= DYNAKV_ERR_TOKENS;
-      return;
+      if constexpr (!SPLIT) return;
+    } else {
+      append_commit<NT>(v, u, ja, M, N, kin, vin, ap, apf);
     }
-    append_commit<NT>(v, u, ja, M, N, kin, vin, ap, apf);
+    if constexpr (SPLIT) {
+      __shared__ SplitWork wk;
+      __syncthreads();                               // the append's flag and every use of smem lie behind
+      if (tid >= kSplitThreads) return;              // barriers from here on count the remaining wavefronts only
+      split_unit<DT>(v, u, smem, wk);
+    }
   }
 }
 
@@ -1025,23 +1057,26 @@ bool retrieve_is_fused(const View& v) {
   return v.fuse && v.S == 1 && v.dtype != DYNAKV_F32 && v.Mcap <= kFusedClusters && v.G <= 8;
 }
 
-template <int DT, bool APPEND>
+template <int DT, bool APPEND, bool SPLIT>
 static void launch_fused(const View& v, const void* Q, int budget, float* out, float* lse, const void* kin,
                          const void* vin, hipStream_t st) {
   // eight wavefronts: 256 registers per lane leave room for float64 scoring and a second tile in flight
-  if (v.G <= 4) retrieve_fused_kernel<DT, 8, 4, APPEND><<<v.U, 512, 0, st>>>(v, Q, budget, out, lse, kin, vin);
-  else retrieve_fused_kernel<DT, 8, 8, APPEND><<<v.U, 512, 0, st>>>(v, Q, budget, out, lse, kin, vin);
+  if (v.G <= 4) retrieve_fused_kernel<DT, 8, 4, APPEND, SPLIT><<<v.U, 512, 0, st>>>(v, Q, budget, out, lse, kin, vin);
+  else retrieve_fused_kernel<DT, 8, 8, APPEND, SPLIT><<<v.U, 512, 0, st>>>(v, Q, budget, out, lse, kin, vin);
 }
 
-// kin == nullptr: retrieval only; otherwise retrieval followed by the append of (kin, vin).
+// kin == nullptr: retrieval only; otherwise retrieval followed by the append of (kin, vin) and, with `split`,
+// by the splits that are due.
 hipError_t launch_retrieve_fused(const View& v, const void* Q, int budget, float* out, float* lse, const void* kin,
-                                 const void* vin, hipStream_t st) {
+                                 const void* vin, bool split, hipStream_t st) {
   if (v.dtype == DYNAKV_F16) {
-    if (kin) launch_fused<DYNAKV_F16, true>(v, Q, budget, out, lse, kin, vin, st);
-    else launch_fused<DYNAKV_F16, false>(v, Q, budget, out, lse, kin, vin, st);
+    if (kin && split) launch_fused<DYNAKV_F16, true, true>(v, Q, budget, out, lse, kin, vin, st);
+    else if (kin) launch_fused<DYNAKV_F16, true, false>(v, Q, budget, out, lse, kin, vin, st);
+    else launch_fused<DYNAKV_F16, false, false>(v, Q, budget, out, lse, kin, vin, st);
   } else {
-    if (kin) launch_fused<DYNAKV_BF16, true>(v, Q, budget, out, lse, kin, vin, st);
-    else launch_fused<DYNAKV_BF16, false>(v, Q, budget, out, lse, kin, vin, st);
+    if (kin && split) launch_fused<DYNAKV_BF16, true, true>(v, Q, budget, out, lse, kin, vin, st);
+    else if (kin) launch_fused<DYNAKV_BF16, true, false>(v, Q, budget, out, lse, kin, vin, st);
+    else launch_fused<DYNAKV_BF16, false, false>(v, Q, budget, out, lse, kin, vin, st);
   }
   return hipGetLastError();
 }
