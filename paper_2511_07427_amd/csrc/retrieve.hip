@@ -818,8 +818,11 @@ constexpr int kFusedList = 2048;       // gather-list entries it keeps in LDS (l
 // With APPEND the same pass over the centroid table also finds the cluster nearest to the step's new key
 // (one more accumulator per centroid), and the append itself runs at the end of the kernel: a decode step then
 // reads the table once instead of twice.  Scores and selection see the index as it was before the append.
-// With SPLIT (only with APPEND) the unit's due splits follow the append in the same launch, carried out by the
-// first kSplitThreads threads after the others have left: a whole decode step is then one kernel.
+// With SPLIT (only with APPEND) the unit's due splits are part of the same launch: a whole decode step is then
+// one kernel.  The append is committed before the pages are streamed (the gather list is fixed by then and the
+// append touches nothing it names); while the other wavefronts stream, the first one plans the splits and takes
+// the decisions of the first of them, which only read the index; the splits are then carried out after the
+// attention by the first kSplitThreads threads, once the other threads have left.
 template <int DT, int NW, int GP, bool APPEND, bool SPLIT>
 __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const void* Q, int budget, float* out,
                                                                 float* lse, const void* kin, const void* vin) {
@@ -833,7 +836,13 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   // scores, sizes, candidates, gather list; after the page loop the front doubles as the merge buffer
   constexpr size_t kPhases = kKeys + kSizes + kSelRegion + kList;
   static_assert(!SPLIT || (APPEND && NW * 64 >= kSplitThreads), "splits follow an append");
-  __shared__ __align__(16) unsigned char smem[SPLIT && kSplitRaw > kPhases ? kSplitRaw : kPhases];
+  // the split's LDS starts where its last kPreSplits contexts, which are filled while pages are streamed, clear
+  // everything the streaming uses
+  constexpr size_t kPreCtx = (kWaveSplits - kPreSplits) * sizeof(WaveCtx);
+  constexpr size_t kRawOff = !SPLIT || kPreCtx >= kPhases ? 0 : (kPhases - kPreCtx + 15) / 16 * 16;
+  static_assert(sizeof(WaveCtx) % 16 == 0 && kWaveSplits * sizeof(WaveCtx) <= kSplitRaw, "split contexts");
+  __shared__ __align__(16) unsigned char smem[SPLIT && kRawOff + kSplitRaw > kPhases ? kRawOff + kSplitRaw : kPhases];
+  __shared__ SplitWork wk;
   __shared__ double qs[kHeadDim][GP];
   __shared__ AppendSmem ap;
   __shared__ double am_v[16];
@@ -948,7 +957,7 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
 #pragma unroll
   for (int k = 0; k < kFusedClusters / NT; ++k)
     if (tid + k * NT < M) ssz[tid + k * NT] = szr[k];
-  // the append's nearest cluster is known now: its record is requested here and used after the attention
+  // the append's nearest cluster is known now: its record is requested here and used after the selection
   int ja = -1;
   AppendFetch apf{0.0, 0, 0};
   if constexpr (APPEND) {
@@ -962,7 +971,18 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   const int nlist = select_phase<NT>(v, u, M, budget, sel);
   __syncthreads();
 
-  // ---- gather + attention
+  // ---- the append (scores and selection saw the index as it was before)
+  if constexpr (APPEND) {
+    if (room) append_commit<NT>(v, u, ja, M, N, kin, vin, ap, apf);
+    else if (tid == 0) v.err[u] |= DYNAKV_ERR_TOKENS;
+    __syncthreads();
+  }
+
+  // ---- gather + attention (with SPLIT by all wavefronts but the first, which prepares the splits meanwhile)
+  constexpr int GW = SPLIT ? NW - 1 : NW;
+  const int gw = SPLIT ? wave - 1 : wave;
+  if constexpr (SPLIT)
+    if (wave == 0) split_prepare<DT>(v, u, smem + kRawOff, wk);
   const int g = lane & 15, lg = lane >> 4;
   typename F::Qf q;
   F::load_q(q, Q, (size_t)u * G + (g < G ? g : 0), lg, g < G);
@@ -975,22 +995,22 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   for (int c = 0; c < 8; ++c) st.acc[c] = f4{0, 0, 0, 0};
   const int* src = nlist <= kFusedList ? list : plist;
   const int ntile = (nlist + 3) >> 2, selK = (lane & 15) >> 2;
-  char* vtile = (char*)smem + wave * F::kVTile;      // scores, sizes and candidates are dead
+  char* vtile = (char*)smem + max(gw, 0) * F::kVTile;      // scores, sizes and candidates are dead
 #define DYNAKV_TILE(T) make_tile<ES>(pages, 4 * (T) + selK < nlist ? src[4 * (T) + selK] : -1, \
                                      4 * (T) + lg < nlist ? src[4 * (T) + lg] : -1, lane)
-  {                                                   // two tiles in flight per wavefront
+  if (gw >= 0) {                                      // two tiles in flight per wavefront
     typename F::KV a, b;
-    Tile ta = DYNAKV_TILE(wave), tb = ta;
-    if (wave < ntile) F::load(a, ta);
-    for (int p = wave; p < ntile; p += 2 * NW) {
-      if (p + NW < ntile) {
-        tb = DYNAKV_TILE(p + NW);
+    Tile ta = DYNAKV_TILE(gw), tb = ta;
+    if (gw < ntile) F::load(a, ta);
+    for (int p = gw; p < ntile; p += 2 * GW) {
+      if (p + GW < ntile) {
+        tb = DYNAKV_TILE(p + GW);
         F::load(b, tb);
       }
       consume_page<F>(st, a, q, ta.nvq, sc, vtile, lane);
-      if (p + NW < ntile) {
-        if (p + 2 * NW < ntile) {
-          ta = DYNAKV_TILE(p + 2 * NW);
+      if (p + GW < ntile) {
+        if (p + 2 * GW < ntile) {
+          ta = DYNAKV_TILE(p + 2 * GW);
           F::load(a, ta);
         }
         consume_page<F>(st, b, q, tb.nvq, sc, vtile, lane);
@@ -1020,19 +1040,10 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
     out[((size_t)u * G + gg) * kHeadDim + dc] = L > 0.f ? O / L : 0.f;
     if (lse && dc == 0) lse[(size_t)u * G + gg] = L > 0.f ? (Mx + __builtin_amdgcn_logf(L)) * kLn2 : -__builtin_inff();
   }
-  if constexpr (APPEND) {
-    if (!room) {
-      if (tid == 0) v.err[u] |= DYNAKV_ERR_TOKENS;
-      if constexpr (!SPLIT) return;
-    } else {
-      append_commit<NT>(v, u, ja, M, N, kin, vin, ap, apf);
-    }
-    if constexpr (SPLIT) {
-      __shared__ SplitWork wk;
-      __syncthreads();                               // the append's flag and every use of smem lie behind
-      if (tid >= kSplitThreads) return;              // barriers from here on count the remaining wavefronts only
-      split_unit<DT>(v, u, smem, wk);
-    }
+  if constexpr (SPLIT) {
+    __syncthreads();                                 // every use of smem lies behind
+    if (tid >= kSplitThreads) return;                // barriers from here on count the remaining wavefronts only
+    split_unit<DT>(v, u, smem + kRawOff, wk, true);
   }
 }
 

@@ -426,6 +426,7 @@ struct WaveCtx {
   double m2[2];
   unsigned char side[64], perm[64], inv[64];     // inv[member] = its place in perm
   int chain[kWavePages], newpg[kWavePages + 2];
+  int pos[64];                                   // sequence positions of the members
   int j, m, ok, nS, idM;
 };
 
@@ -514,8 +515,8 @@ __device__ __forceinline__ void wave_sums(const WaveCtx& c, int q0, int q1, int 
 
 // First phase, one wavefront: stage the keys (c.chain lists their pages), 2-means, stable partition.  Sets
 // c.ok, c.nS, c.perm.
-template <int DT>
-__device__ inline void wave_split_decide(const View& v, int u, WaveCtx& c, uint4 (&vahead)[kVAhead], int& pos_ahead) {
+template <int DT, bool AHEAD>
+__device__ inline void wave_split_decide(const View& v, int u, WaveCtx& c, uint4 (&vahead)[kVAhead]) {
   const int lane = threadIdx.x & 63;
   constexpr int kEs = DT == DYNAKV_F32 ? 4 : 2;
   constexpr int kChunks = kHeadDim * kEs / 16;
@@ -541,12 +542,12 @@ __device__ inline void wave_split_decide(const View& v, int u, WaveCtx& c, uint4
   for (int k = 0; k < kVAhead; ++k) {
     const int t = k * 64 + lane, i = t / kChunks, ch = t % kChunks;
     vahead[k] = uint4{0, 0, 0, 0};
-    if (i < m) {
+    if (AHEAD && i < m) {
       const size_t off = (size_t)(DT == DYNAKV_F32 ? v_index32(i & 15, 4 * ch) : v_index16(i & 15, 8 * ch)) * kEs;
       vahead[k] = *(const uint4*)(pool + (size_t)c.chain[i >> 4] * (kPageElems * kEs) + off);
     }
   }
-  pos_ahead = lane < m ? v.ppos[((size_t)u * v.Pcap + c.chain[lane >> 4]) * kPageTokens + (lane & 15)] : 0;
+  if (lane < m) c.pos[lane] = v.ppos[((size_t)u * v.Pcap + c.chain[lane >> 4]) * kPageTokens + (lane & 15)];
   wave_sync();
   const WaveKeys<DT> ks{c};
   const int grp = lane >> 2, kb = lane & 3;      // four lanes per member in the distance passes
@@ -631,7 +632,7 @@ __device__ inline void wave_split_decide(const View& v, int u, WaveCtx& c, uint4
 // only unflagged, with exact statistics.
 template <int DT>
 __device__ inline void wave_split_commit(const View& v, int u, WaveCtx& c, const uint4 (&vahead)[kVAhead],
-                                         int pos_ahead) {
+                                         bool ahead) {
   const int lane = threadIdx.x & 63;
   const size_t cbase = (size_t)u * v.Mcap;
   constexpr int kEs = DT == DYNAKV_F32 ? 4 : 2;
@@ -660,13 +661,15 @@ __device__ inline void wave_split_commit(const View& v, int u, WaveCtx& c, const
       const int r = q < nS ? q : q - nS;
       return (char*)pool + (size_t)c.newpg[(q < nS ? 0 : pS) + (r >> 4)] * kPageBytes + vchunk(r & 15, ch);
     };
+    if (ahead) {
 #pragma unroll
-    for (int k = 0; k < kVAhead; ++k) {
-      const int t = k * 64 + lane, i = t / kChunks;
-      if (i < m) *(uint4*)vdest(i, t % kChunks) = vahead[k];
+      for (int k = 0; k < kVAhead; ++k) {
+        const int t = k * 64 + lane, i = t / kChunks;
+        if (i < m) *(uint4*)vdest(i, t % kChunks) = vahead[k];
+      }
     }
-    // then the members past those, four loads in flight per lane
-    for (int t0 = kVAhead * 64; t0 < m * kChunks; t0 += 4 * 64) {
+    // then the members past those (all, if nothing was requested ahead), four loads in flight per lane
+    for (int t0 = ahead ? kVAhead * 64 : 0; t0 < m * kChunks; t0 += 4 * 64) {
       uint4 w[4];
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
@@ -683,7 +686,7 @@ __device__ inline void wave_split_commit(const View& v, int u, WaveCtx& c, const
       const int q = c.inv[lane];
       const int r = q < nS ? q : q - nS;
       const int dpage = c.newpg[(q < nS ? 0 : pS) + (r >> 4)];
-      v.ppos[((size_t)u * v.Pcap + dpage) * kPageTokens + (r & 15)] = pos_ahead;
+      v.ppos[((size_t)u * v.Pcap + dpage) * kPageTokens + (r & 15)] = c.pos[lane];
     }
   }
   // exact statistics: float32 means, then M2 about those means, members in their new order
@@ -753,17 +756,112 @@ struct SplitPlan {
 
 // LDS of one unit's splits: `raw` holds either the workgroup-wide split or four wavefront splits.
 constexpr size_t kSplitRaw = sizeof(SplitSmem) > kWaveSplits * sizeof(WaveCtx) ? sizeof(SplitSmem) : kWaveSplits * sizeof(WaveCtx);
+constexpr int kPreSplits = 2;            // splits that split_prepare decides ahead
 struct SplitWork {
   SplitPlan pl;
   long long s_tot;
   int s_min;
+  int nf0, M0, npre;                     // left by split_prepare: flagged clusters, clusters, splits already decided
 };
+// Candidate k of a round of wavefront splits is held in context ctx_of(k) and handled by that wavefront: the
+// contexts of the first candidates lie at the far end of `raw`.
+__device__ __forceinline__ int ctx_of(int k) { return kWaveSplits - 1 - k; }
+
+// Fetches what the plan needs about flagged cluster `c` (slot i of the plan).
+__device__ __forceinline__ void plan_fetch(const View& v, size_t cbase, SplitPlan& pl, int i, int c) {
+  const int b = v.cb[cbase + c];
+  const int4 pg = *(const int4*)&v.cpg[(cbase + c) * kInlinePages];
+  pl.id[i] = c; pl.req[i] = v.in_req[cbase + c]; pl.cb[i] = b; pl.m[i] = v.cn[cbase + c] + b;
+  pl.pg[i][0] = pg.x; pl.pg[i][1] = pg.y; pl.pg[i][2] = pg.z; pl.pg[i][3] = pg.w;
+}
+// Everything the page allocation will need, requested in the same round trip: entry k of the read-ahead.
+__device__ __forceinline__ void plan_fetch_pages(const View& v, int u, SplitPlan& pl, int k, int top, int M0) {
+  if (k < top) pl.fl[k] = v.freelist[(size_t)u * v.Pcap + top - 1 - k];
+  if (k == 0) { pl.M = M0; pl.top = top; pl.bump = v.bump[u]; pl.fl_base = top; }
+}
+
+// The order of the unit's splits, by one thread, from the fetched list of its nf0 <= 64 flagged clusters.
+template <int DT>
+__device__ inline void plan_splits(const View& v, SplitPlan& pl, int nf0) {
+  // delayed splits: flagged clusters of the active set (all flagged ones if nothing is buffered), ascending id
+  int nc = 0;
+  for (int last = -1;;) {
+    int best = -1;
+    for (int i = 0; i < nf0; ++i)
+      if (pl.id[i] > last && (v.Bmax == 0 || pl.req[i]) && (best < 0 || pl.id[i] < pl.id[best])) best = i;
+    if (best < 0) break;
+    pl.cand[nc++] = best;
+    last = pl.id[best];
+    pl.req[best] = 2;                  // taken
+  }
+  // then, if the remaining buffers hold B_max entries, the fullest of them (lowest id among equals)
+  int forced = 0;
+  if (v.Bmax > 0) {
+    long long total = 0;
+    int best = -1;
+    for (int i = 0; i < nf0; ++i)
+      if (pl.req[i] != 2) {
+        total += pl.cb[i];
+        if (best < 0 || pl.cb[i] > pl.cb[best] || (pl.cb[i] == pl.cb[best] && pl.id[i] < pl.id[best])) best = i;
+      }
+    if (best >= 0 && total >= v.Bmax) { pl.cand[nc++] = best; forced = 1; }
+  }
+  // the wavefront path takes the plan if every cluster is small and no capacity limit can be hit
+  constexpr int kSmall = DT == DYNAKV_F32 ? 32 : 64;
+  long long pages = 0;
+  bool small = true;
+  for (int k = 0; k < nc; ++k) {
+    const int mm = pl.m[pl.cand[k]];
+    small = small && mm <= kSmall;
+    pages += (mm + kPageTokens - 1) / kPageTokens + 1;
+  }
+  pl.n_cand = nc; pl.forced = forced;
+  pl.fast = small && pl.M + nc <= v.Mcap && pages <= (long long)pl.top + (v.Pcap - pl.bump);
+}
+
+// Hands candidate `at` of the plan to context c (one wavefront).
+__device__ __forceinline__ void wave_take(const SplitPlan& pl, int at, WaveCtx& c, int lane) {
+  if (lane == 0) { c.j = pl.id[at]; c.m = pl.m[at]; }
+  if (lane < kWavePages) c.chain[lane] = pl.pg[at][lane];
+  wave_sync();
+}
+
+// Head start for split_unit, by ONE wavefront (the first of the workgroup) while the others are busy elsewhere:
+// the plan and, if the wavefront path takes it, the decisions of its first kPreSplits splits.  Reads the index
+// only; writes `wk` and the last kPreSplits contexts of `raw`.  split_unit(..., true) continues from there.
+template <int DT>
+__device__ inline void split_prepare(const View& v, int u, unsigned char* raw, SplitWork& wk) {
+  SplitPlan& pl = wk.pl;
+  WaveCtx* const wc = (WaveCtx*)raw;
+  const int lane = threadIdx.x & 63;
+  const size_t cbase = (size_t)u * v.Mcap;
+  const int c_ahead = lane < min(64, v.Mcap) ? v.flist[cbase + lane] : 0;
+  const int top = v.free_top[u];
+  const int M0 = v.M[u];
+  const int nf0 = v.nflag[u];
+  if (lane == 0) { wk.nf0 = nf0; wk.M0 = M0; wk.npre = 0; pl.fast = 0; }
+  if (nf0 == 0 || nf0 > 64) return;
+  if (lane < nf0) plan_fetch(v, cbase, pl, lane, c_ahead);
+  if (lane < kFreeAhead) plan_fetch_pages(v, u, pl, lane, top, M0);
+  wave_sync();
+  if (lane == 0) plan_splits<DT>(v, pl, nf0);
+  wave_sync();
+  if (!pl.fast) return;
+  const int npre = min(pl.n_cand, kPreSplits);
+  for (int k = 0; k < npre; ++k) {
+    WaveCtx& c = wc[ctx_of(k)];
+    uint4 none[kVAhead];
+    wave_take(pl, pl.cand[k], c, lane);
+    wave_split_decide<DT, false>(v, u, c, none);
+  }
+  if (lane == 0) wk.npre = npre;
+}
 
 // All splits of unit u that are due (Algorithm 1, decode block: delayed splits, then the forced one), by the
 // first kSplitThreads threads of the workgroup; no other thread of the workgroup may still be running.
-// raw: kSplitRaw bytes of LDS, 16-byte aligned.
+// raw: kSplitRaw bytes of LDS, 16-byte aligned.  prepared: split_prepare has run (and a barrier since).
 template <int DT>
-__device__ __forceinline__ void split_unit(const View& v, int u, unsigned char* raw, SplitWork& wk) {
+__device__ __forceinline__ void split_unit(const View& v, int u, unsigned char* raw, SplitWork& wk, bool prepared) {
   constexpr int NT = kSplitThreads;
   SplitPlan& pl = wk.pl;
   int& s_min = wk.s_min;
@@ -772,92 +870,53 @@ __device__ __forceinline__ void split_unit(const View& v, int u, unsigned char* 
   WaveCtx* const wc = (WaveCtx*)raw;
   const int tid = threadIdx.x;
   const size_t cbase = (size_t)u * v.Mcap;
-  // requested together with the flag count, so that the plan below starts one round trip earlier
-  const int c_ahead = tid < min(64, v.Mcap) ? v.flist[cbase + tid] : 0;
-  const int top_ahead = v.free_top[u];
-  const int M0 = v.M[u];
-  const int nf0 = v.nflag[u];
-  if (nf0 == 0) return;
+  int M0, nf0, npre = 0;
+  if (prepared) {
+    M0 = wk.M0; nf0 = wk.nf0; npre = wk.npre;
+    if (nf0 == 0) return;
+  } else {
+    // requested together with the flag count, so that the plan below starts one round trip earlier
+    const int c_ahead = tid < min(64, v.Mcap) ? v.flist[cbase + tid] : 0;
+    const int top_ahead = v.free_top[u];
+    M0 = v.M[u];
+    nf0 = v.nflag[u];
+    if (nf0 == 0) return;
+    if (nf0 <= 64) {
+      if (tid < nf0) plan_fetch(v, cbase, pl, tid, c_ahead);
+      if (tid >= 64 && tid < 64 + kFreeAhead) plan_fetch_pages(v, u, pl, tid - 64, top_ahead, M0);
+      __syncthreads();
+      if (tid == 0) plan_splits<DT>(v, pl, nf0);
+      __syncthreads();
+    }
+  }
 
-  // ---- plan: which clusters are split, in which order
+  // ---- the plan's splits, up to four side by side, one per wavefront
   if (nf0 <= 64) {
-    if (tid < nf0) {
-      const int c = c_ahead;
-      const int b = v.cb[cbase + c];
-      const int4 pg = *(const int4*)&v.cpg[(cbase + c) * kInlinePages];
-      pl.id[tid] = c; pl.req[tid] = v.in_req[cbase + c]; pl.cb[tid] = b; pl.m[tid] = v.cn[cbase + c] + b;
-      pl.pg[tid][0] = pg.x; pl.pg[tid][1] = pg.y; pl.pg[tid][2] = pg.z; pl.pg[tid][3] = pg.w;
-    }
-    if (tid >= 64 && tid < 64 + kFreeAhead) {       // everything the page allocation will need, in the same round trips
-      const int top = top_ahead, k = tid - 64;
-      if (k < top) pl.fl[k] = v.freelist[(size_t)u * v.Pcap + top - 1 - k];
-      if (k == 0) { pl.M = M0; pl.top = top; pl.bump = v.bump[u]; pl.fl_base = top; }
-    }
-    __syncthreads();
-    if (tid == 0) {
-      // delayed splits: flagged clusters of the active set (all flagged ones if nothing is buffered), ascending id
-      int nc = 0;
-      for (int last = -1;;) {
-        int best = -1;
-        for (int i = 0; i < nf0; ++i)
-          if (pl.id[i] > last && (v.Bmax == 0 || pl.req[i]) && (best < 0 || pl.id[i] < pl.id[best])) best = i;
-        if (best < 0) break;
-        pl.cand[nc++] = best;
-        last = pl.id[best];
-        pl.req[best] = 2;                  // taken
-      }
-      // then, if the remaining buffers hold B_max entries, the fullest of them (lowest id among equals)
-      int forced = 0;
-      if (v.Bmax > 0) {
-        long long total = 0;
-        int best = -1;
-        for (int i = 0; i < nf0; ++i)
-          if (pl.req[i] != 2) {
-            total += pl.cb[i];
-            if (best < 0 || pl.cb[i] > pl.cb[best] || (pl.cb[i] == pl.cb[best] && pl.id[i] < pl.id[best])) best = i;
-          }
-        if (best >= 0 && total >= v.Bmax) { pl.cand[nc++] = best; forced = 1; }
-      }
-      // the wavefront path takes the plan if every cluster is small and no capacity limit can be hit
-      constexpr int kSmall = DT == DYNAKV_F32 ? 32 : 64;
-      long long pages = 0;
-      bool small = true;
-      for (int k = 0; k < nc; ++k) {
-        const int mm = pl.m[pl.cand[k]];
-        small = small && mm <= kSmall;
-        pages += (mm + kPageTokens - 1) / kPageTokens + 1;
-      }
-      pl.n_cand = nc; pl.forced = forced;
-      pl.fast = small && pl.M + nc <= v.Mcap && pages <= (long long)pl.top + (v.Pcap - pl.bump);
-    }
-    __syncthreads();
     if (pl.fast) {
       const int wave = tid >> 6, lane = tid & 63;
       const int nc = pl.n_cand;
       for (int base = 0; base < nc; base += kWaveSplits) {
-        const bool mine = base + wave < nc;
+        const int mk = base + ctx_of(wave);            // this wavefront's candidate
+        const bool mine = mk < nc;
+        const bool ahead = mine && mk >= npre;         // the first npre candidates are decided already
         uint4 vahead[kVAhead];
-        int pos_ahead = 0;
         WaveCtx& c = wc[wave];
-        if (mine) {
-          const int at = pl.cand[base + wave];
-          if (lane == 0) { c.j = pl.id[at]; c.m = pl.m[at]; }
-          if (lane < kWavePages) c.chain[lane] = pl.pg[at][lane];
-          wave_sync();
-          wave_split_decide<DT>(v, u, c, vahead, pos_ahead);
+        if (ahead) {
+          wave_take(pl, pl.cand[mk], c, lane);
+          wave_split_decide<DT, true>(v, u, c, vahead);
         }
         __syncthreads();
         if (tid == 0) {                    // ids and pages, in the order of the splits
           for (int w = 0; w < kWaveSplits && base + w < nc; ++w) {
-            WaveCtx& cw = wc[w];
+            WaveCtx& cw = wc[ctx_of(w)];
             if (!cw.ok) continue;
             cw.idM = pl.M++;
             const int need = (cw.nS + kPageTokens - 1) / kPageTokens + (cw.m - cw.nS + kPageTokens - 1) / kPageTokens;
             const int from_free = min(need, pl.top);
             for (int k = 0; k < need; ++k) {
-              const int ahead = pl.fl_base - (pl.top - k);       // pl.fl holds the stack as it was at fl_base
+              const int ra = pl.fl_base - (pl.top - k);          // pl.fl holds the stack as it was at fl_base
               cw.newpg[k] = k >= from_free ? pl.bump + (k - from_free)
-                            : (ahead >= 0 && ahead < kFreeAhead) ? pl.fl[ahead]
+                            : (ra >= 0 && ra < kFreeAhead) ? pl.fl[ra]
                                                                   : v.freelist[(size_t)u * v.Pcap + pl.top - 1 - k];
             }
             pl.top -= from_free;
@@ -865,11 +924,11 @@ __device__ __forceinline__ void split_unit(const View& v, int u, unsigned char* 
           }
         }
         __syncthreads();
-        if (mine) wave_split_commit<DT>(v, u, c, vahead, pos_ahead);
+        if (mine) wave_split_commit<DT>(v, u, c, vahead, ahead);
         __syncthreads();
         if (tid == 0) {                    // the parents' pages are recycled only now
           for (int w = 0; w < kWaveSplits && base + w < nc; ++w) {
-            const WaveCtx& cw = wc[w];
+            const WaveCtx& cw = wc[ctx_of(w)];
             v.counters[(size_t)u * kCounters + (cw.ok ? 0 : 1)] += 1;
             if (!cw.ok) continue;
             const int npg = (cw.m + kPageTokens - 1) / kPageTokens;
