@@ -2,9 +2,9 @@
 
 A step = dynakv_decode_step (retrieve + attend, append, split) over all units of the workload, on seeded
 synthetic drifting-mixture inputs already resident in HBM.  Prints one JSON line: decode steps/s, the
-roofline of the dominant kernel (scores + selection + gather + attention + append in one launch when there is
-a unit per compute unit, else gather + attention; HBM-bound), and the CPU oracle timed on a bounded sample of
-the same workload on this machine's host cores.
+roofline of the dominant kernel (the whole step in one launch from 32 units on: scores, selection, append,
+gather + attention, splits; else gather + attention; HBM-bound), and the CPU oracle timed on a bounded sample
+of the same workload on this machine's host cores.
 """
 from __future__ import annotations
 
@@ -23,10 +23,10 @@ MFMA_PEAK_TFLOPS = 2500.0      # dense fp16/bf16, published
 # HBM bytes per launch of the dominant kernel from two `rocprofv3 --pmc` runs of this file with its default
 # arguments (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch averaged over the timed launches), each scaled by what
 # the same counter reads for the float32 -> float16 copy of the 134 217 728-element prefill keys (512 MiB read,
-# 256 MiB written): FETCH_SIZE reads 262 167 KiB for it (factor 2.000), WRITE_SIZE 262 144 KiB (factor 1.000).
+# 256 MiB written): FETCH_SIZE reads 262 169 KiB for it (factor 2.000), WRITE_SIZE 262 144 KiB (factor 1.000).
 # Only valid for exactly that workload; any other arguments report null.
-PMC_TRAFFIC = {("llama3_8b", 8192, 64, 0): {"fetch_kib": 111603.7, "fetch_scale": 524288.0 / 262166.4,
-                                            "write_kib": 3326.4, "write_scale": 1.0}}
+PMC_TRAFFIC = {("llama3_8b", 8192, 64, 0): {"fetch_kib": 108795.7, "fetch_scale": 524288.0 / 262168.6,
+                                            "write_kib": 12095.4, "write_scale": 1.0}}
 
 
 def cpu_baseline(spec, n_units, steps, budget):
