@@ -13,6 +13,7 @@ struct AppendSmem {
   double m2, tau;
   int cn, cb, ctail, cflag, nflag, free_top, bump, free_page;
   int ok, commit, page, slot;
+  int nflag1, top1, bump1;   // the unit's flag count and allocator state as the append leaves them
 };
 
 // What one thread fetches for an append: thread d < 128 coordinate d of the centroid, threads 128..136 one field
@@ -87,14 +88,17 @@ __device__ inline void append_commit(const View& v, int u, int j, int M, int N, 
     const int slot = sz % kPageTokens;
     int page = a.ctail;
     int ok = 1;
+    a.nflag1 = a.nflag; a.top1 = a.free_top; a.bump1 = a.bump;
     if (slot == 0) {                      // no page yet, or the tail page is full
       int np = -1;                        // from the free stack, else from the untouched tail of the pool
       if (a.free_top > 0) {
         np = a.free_page;
         v.free_top[u] = a.free_top - 1;
+        a.top1 = a.free_top - 1;
       } else if (a.bump < v.Pcap) {
         np = a.bump;
         v.bump[u] = a.bump + 1;
+        a.bump1 = a.bump + 1;
       }
       if (np < 0) {
         v.err[u] |= DYNAKV_ERR_TOKENS;
@@ -130,6 +134,7 @@ __device__ inline void append_commit(const View& v, int u, int j, int M, int N, 
           v.cb[cbase + j] = 1;
           v.flist[cbase + a.nflag] = j;
           v.nflag[u] = a.nflag + 1;
+          a.nflag1 = a.nflag + 1;
         }
       }
       v.N[u] = N + 1;

@@ -65,7 +65,8 @@ template <int DT>
 __global__ __launch_bounds__(kSplitThreads) void split_kernel(View v) {
   __shared__ __align__(16) unsigned char raw[kSplitRaw];
   __shared__ SplitWork wk;
-  split_unit<DT>(v, blockIdx.x, raw, wk, false);
+  const uint4 none[kVAhead] = {};
+  split_unit<DT>(v, blockIdx.x, raw, wk, false, none);
 }
 
 // ------------------------------------------------------------------------------------------- export

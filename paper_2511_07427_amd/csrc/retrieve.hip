@@ -872,6 +872,15 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
     const uint4* p = (const uint4*)(Rq + rq_index(wave * 64 + lane, 0));
     e0 = p[0]; e1 = p[64]; e2 = p[128]; e3 = p[192];
   }
+  // the flagged list and the free-page stack as they are before this step's append: the plan of the splits
+  // starts from them
+  int flagged0 = 0, nflag0 = 0, top0 = 0;
+  if constexpr (SPLIT)
+    if (wave == 0) {
+      if (lane < v.Mcap) flagged0 = v.flist[(size_t)u * v.Mcap + lane];
+      nflag0 = v.nflag[u];
+      top0 = v.free_top[u];
+    }
   const int M = v.M[u];
   for (int t = tid; t < GP * kHeadDim; t += NT) {
     const int g = t / kHeadDim, d = t % kHeadDim;
@@ -971,18 +980,28 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   const int nlist = select_phase<NT>(v, u, M, budget, sel);
   __syncthreads();
 
-  // ---- the append (scores and selection saw the index as it was before)
+  // ---- the append (scores and selection saw the index as it was before); with SPLIT the first wavefront
+  // requests what the plan of the splits needs beforehand and makes the plan right after
+  PlanEarly pe{};
+  if constexpr (SPLIT)
+    if (wave == 0) pe = plan_fetch_early(v, u, flagged0, nflag0, top0, room ? ja : -1, lane);
   if constexpr (APPEND) {
     if (room) append_commit<NT>(v, u, ja, M, N, kin, vin, ap, apf);
     else if (tid == 0) v.err[u] |= DYNAKV_ERR_TOKENS;
     __syncthreads();
   }
+  int nprep = 0;
+  if constexpr (SPLIT) {
+    if (wave == 0) plan_finish<DT>(v, wk, pe, nflag0, top0, M, ja, room ? &ap : nullptr);
+    __syncthreads();
+    nprep = wk.npre;
+  }
 
-  // ---- gather + attention (with SPLIT by all wavefronts but the first, which prepares the splits meanwhile)
-  constexpr int GW = SPLIT ? NW - 1 : NW;
-  const int gw = SPLIT ? wave - 1 : wave;
+  // ---- gather + attention (with SPLIT the first nprep wavefronts decide the first splits of the plan meanwhile)
+  const int GW = NW - nprep, gw = wave - nprep;
+  uint4 pre_v[kVAhead] = {};
   if constexpr (SPLIT)
-    if (wave == 0) split_prepare<DT>(v, u, smem + kRawOff, wk);
+    if (wave < nprep) split_predecide<DT>(v, u, smem + kRawOff, wk, wave, pre_v);
   const int g = lane & 15, lg = lane >> 4;
   typename F::Qf q;
   F::load_q(q, Q, (size_t)u * G + (g < G ? g : 0), lg, g < G);
@@ -1043,7 +1062,7 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   if constexpr (SPLIT) {
     __syncthreads();                                 // every use of smem lies behind
     if (tid >= kSplitThreads) return;                // barriers from here on count the remaining wavefronts only
-    split_unit<DT>(v, u, smem + kRawOff, wk, true);
+    split_unit<DT>(v, u, smem + kRawOff, wk, true, pre_v);
   }
 }
 

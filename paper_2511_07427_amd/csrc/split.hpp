@@ -628,8 +628,52 @@ __device__ inline void wave_split_decide(const View& v, int u, WaveCtx& c, uint4
   wave_sync();
 }
 
-// Second phase, one wavefront: children's pages, exact statistics and records.  With c.ok == 0 the cluster is
-// only unflagged, with exact statistics.
+// Exact statistics of the children (of the unsplit cluster if c.ok == 0), one wavefront, LDS only: float32
+// means into c.rA / c.rB, then M2 about those means into c.m2, members in their new order.
+template <int DT>
+__device__ inline void wave_split_stats(WaveCtx& c) {
+  const int lane = threadIdx.x & 63;
+  const int m = c.m, nS = c.nS, nM = m - nS;
+  auto at = [&](int q) { return (int)c.perm[q]; };
+  double s0, s1, u0, u1;
+  wave_sums<DT, false>(c, 0, nS, lane, at, s0, s1, u0, u1);
+  c.rA[lane] = nS > 0 ? (float)(s0 / (double)nS) : 0.f;
+  c.rA[lane + 64] = nS > 0 ? (float)(s1 / (double)nS) : 0.f;
+  if (c.ok) {
+    wave_sums<DT, false>(c, nS, m, lane, at, s0, s1, u0, u1);
+    c.rB[lane] = nM > 0 ? (float)(s0 / (double)nM) : 0.f;
+    c.rB[lane + 64] = nM > 0 ? (float)(s1 / (double)nM) : 0.f;
+  }
+  wave_sync();
+  {
+    const WaveKeys<DT> ks{c};
+    const int grp = lane >> 2, kb = lane & 3;
+    for (int base = 0; base < m; base += 16) {
+      const int q = base + grp, qc = min(q, m - 1);
+      double dv, dummy;
+      quad_sqdist<WaveKeys<DT>, float>(ks, c.perm[qc], kb, qc < nS ? c.rA : c.rB, nullptr, dv, dummy);
+      if (kb == 0 && q < m) c.dist[q] = dv;
+    }
+  }
+  wave_sync();
+  if (lane < 2) {
+    const int q0 = lane ? nS : 0, q1 = lane ? m : nS;
+    double acc = 0.0;
+    for (int r0 = q0; r0 < q1; r0 += 8) {
+      double x[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) x[k] = r0 + k < q1 ? c.dist[r0 + k] : 0.0;
+      asm volatile("" ::: "memory");
+#pragma unroll
+      for (int k = 0; k < 8; ++k) acc += x[k];
+    }
+    c.m2[lane] = acc;
+  }
+  wave_sync();
+}
+
+// Last phase, one wavefront, once the children's id and pages are assigned: pages, centroids and records.  With
+// c.ok == 0 the cluster is only unflagged, with exact statistics.  wave_split_stats has run on c.
 template <int DT>
 __device__ inline void wave_split_commit(const View& v, int u, WaveCtx& c, const uint4 (&vahead)[kVAhead],
                                          bool ahead) {
@@ -689,45 +733,8 @@ __device__ inline void wave_split_commit(const View& v, int u, WaveCtx& c, const
       v.ppos[((size_t)u * v.Pcap + dpage) * kPageTokens + (r & 15)] = c.pos[lane];
     }
   }
-  // exact statistics: float32 means, then M2 about those means, members in their new order
-  auto at = [&](int q) { return (int)c.perm[q]; };
-  double s0, s1, u0, u1;
-  wave_sums<DT, false>(c, 0, nS, lane, at, s0, s1, u0, u1);
-  c.rA[lane] = nS > 0 ? (float)(s0 / (double)nS) : 0.f;
-  c.rA[lane + 64] = nS > 0 ? (float)(s1 / (double)nS) : 0.f;
   store_centroid(v, u, j, lane, c.rA[lane]); store_centroid(v, u, j, lane + 64, c.rA[lane + 64]);
-  if (idM >= 0) {
-    wave_sums<DT, false>(c, nS, m, lane, at, s0, s1, u0, u1);
-    c.rB[lane] = nM > 0 ? (float)(s0 / (double)nM) : 0.f;
-    c.rB[lane + 64] = nM > 0 ? (float)(s1 / (double)nM) : 0.f;
-    store_centroid(v, u, idM, lane, c.rB[lane]); store_centroid(v, u, idM, lane + 64, c.rB[lane + 64]);
-  }
-  wave_sync();
-  {
-    const WaveKeys<DT> ks{c};
-    const int grp = lane >> 2, kb = lane & 3;
-    for (int base = 0; base < m; base += 16) {
-      const int q = base + grp, qc = min(q, m - 1);
-      double dv, dummy;
-      quad_sqdist<WaveKeys<DT>, float>(ks, c.perm[qc], kb, qc < nS ? c.rA : c.rB, nullptr, dv, dummy);
-      if (kb == 0 && q < m) c.dist[q] = dv;
-    }
-  }
-  wave_sync();
-  if (lane < 2) {
-    const int q0 = lane ? nS : 0, q1 = lane ? m : nS;
-    double acc = 0.0;
-    for (int r0 = q0; r0 < q1; r0 += 8) {
-      double x[8];
-#pragma unroll
-      for (int k = 0; k < 8; ++k) x[k] = r0 + k < q1 ? c.dist[r0 + k] : 0.0;
-      asm volatile("" ::: "memory");
-#pragma unroll
-      for (int k = 0; k < 8; ++k) acc += x[k];
-    }
-    c.m2[lane] = acc;
-  }
-  wave_sync();
+  if (idM >= 0) { store_centroid(v, u, idM, lane, c.rB[lane]); store_centroid(v, u, idM, lane + 64, c.rB[lane + 64]); }
   if (c.ok && lane < kInlinePages) {
     v.cpg[(cbase + j) * kInlinePages + lane] = lane < pS ? c.newpg[lane] : -1;
     v.cpg[(cbase + idM) * kInlinePages + lane] = lane < pM ? c.newpg[pS + lane] : -1;
@@ -756,23 +763,30 @@ struct SplitPlan {
 
 // LDS of one unit's splits: `raw` holds either the workgroup-wide split or four wavefront splits.
 constexpr size_t kSplitRaw = sizeof(SplitSmem) > kWaveSplits * sizeof(WaveCtx) ? sizeof(SplitSmem) : kWaveSplits * sizeof(WaveCtx);
-constexpr int kPreSplits = 2;            // splits that split_prepare decides ahead
+constexpr int kPreSplits = 2;            // splits that split_predecide decides ahead
 struct SplitWork {
   SplitPlan pl;
   long long s_tot;
   int s_min;
-  int nf0, M0, npre;                     // left by split_prepare: flagged clusters, clusters, splits already decided
+  int nf0, M0, npre;                     // left by plan_finish: flagged clusters, clusters, splits decided ahead
 };
-// Candidate k of a round of wavefront splits is held in context ctx_of(k) and handled by that wavefront: the
-// contexts of the first candidates lie at the far end of `raw`.
+// Candidate k of a round of wavefront splits is handled by wavefront k and held in context ctx_of(k): the
+// contexts of the first candidates lie at the far end of `raw`, clear of what a caller of split_predecide may
+// still be using at the front.
 __device__ __forceinline__ int ctx_of(int k) { return kWaveSplits - 1 - k; }
 
-// Fetches what the plan needs about flagged cluster `c` (slot i of the plan).
-__device__ __forceinline__ void plan_fetch(const View& v, size_t cbase, SplitPlan& pl, int i, int c) {
+// What the plan needs about one flagged cluster; id < 0: no cluster.
+struct PlanEntry {
+  int id, req, cb, m;
+};
+// Fetches it for flagged cluster `c` (slot i of the plan), into the plan and for the calling lane.
+__device__ __forceinline__ PlanEntry plan_fetch(const View& v, size_t cbase, SplitPlan& pl, int i, int c) {
   const int b = v.cb[cbase + c];
   const int4 pg = *(const int4*)&v.cpg[(cbase + c) * kInlinePages];
-  pl.id[i] = c; pl.req[i] = v.in_req[cbase + c]; pl.cb[i] = b; pl.m[i] = v.cn[cbase + c] + b;
+  const PlanEntry e{c, v.in_req[cbase + c], b, v.cn[cbase + c] + b};
+  pl.id[i] = e.id; pl.req[i] = e.req; pl.cb[i] = e.cb; pl.m[i] = e.m;
   pl.pg[i][0] = pg.x; pl.pg[i][1] = pg.y; pl.pg[i][2] = pg.z; pl.pg[i][3] = pg.w;
+  return e;
 }
 // Everything the page allocation will need, requested in the same round trip: entry k of the read-ahead.
 __device__ __forceinline__ void plan_fetch_pages(const View& v, int u, SplitPlan& pl, int k, int top, int M0) {
@@ -780,43 +794,49 @@ __device__ __forceinline__ void plan_fetch_pages(const View& v, int u, SplitPlan
   if (k == 0) { pl.M = M0; pl.top = top; pl.bump = v.bump[u]; pl.fl_base = top; }
 }
 
-// The order of the unit's splits, by one thread, from the fetched list of its nf0 <= 64 flagged clusters.
+// The order of the unit's splits, by one whole wavefront: lane i < nf0 <= 64 brings flagged cluster i (e.id < 0 in
+// the other lanes); pl.M, pl.top and pl.bump are in place.  Delayed splits first: flagged clusters of the active
+// set (all flagged ones if nothing is buffered) in ascending id; then, if the remaining buffers hold B_max
+// entries, the fullest of them (lowest id among equals).
 template <int DT>
-__device__ inline void plan_splits(const View& v, SplitPlan& pl, int nf0) {
-  // delayed splits: flagged clusters of the active set (all flagged ones if nothing is buffered), ascending id
-  int nc = 0;
-  for (int last = -1;;) {
-    int best = -1;
-    for (int i = 0; i < nf0; ++i)
-      if (pl.id[i] > last && (v.Bmax == 0 || pl.req[i]) && (best < 0 || pl.id[i] < pl.id[best])) best = i;
-    if (best < 0) break;
-    pl.cand[nc++] = best;
-    last = pl.id[best];
-    pl.req[best] = 2;                  // taken
+__device__ inline void plan_splits(const View& v, SplitPlan& pl, const PlanEntry& e) {
+  const int lane = threadIdx.x & 63;
+  const bool have = e.id >= 0;
+  const bool delayed = have && (v.Bmax == 0 || e.req != 0);
+  const unsigned long long dmask = __ballot(delayed);
+  int rank = 0;
+  for (unsigned long long mm = dmask; mm; mm &= mm - 1) {          // ids are distinct: rank = smaller ids
+    const int other = __shfl(e.id, __ffsll((long long)mm) - 1);
+    rank += other < e.id ? 1 : 0;
   }
-  // then, if the remaining buffers hold B_max entries, the fullest of them (lowest id among equals)
-  int forced = 0;
+  if (delayed) pl.cand[rank] = lane;
+  int nc = __popcll(dmask), forced = 0, fl = -1;
   if (v.Bmax > 0) {
-    long long total = 0;
-    int best = -1;
-    for (int i = 0; i < nf0; ++i)
-      if (pl.req[i] != 2) {
-        total += pl.cb[i];
-        if (best < 0 || pl.cb[i] > pl.cb[best] || (pl.cb[i] == pl.cb[best] && pl.id[i] < pl.id[best])) best = i;
-      }
-    if (best >= 0 && total >= v.Bmax) { pl.cand[nc++] = best; forced = 1; }
+    const bool rest = have && !delayed;
+    int total = rest ? e.cb : 0;
+    int bcb = rest ? e.cb : -1, bid = rest ? e.id : 0x7fffffff, bl = lane;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      total += __shfl_xor(total, o);
+      const int ocb = __shfl_xor(bcb, o), oid = __shfl_xor(bid, o), ol = __shfl_xor(bl, o);
+      if (ocb > bcb || (ocb == bcb && oid < bid)) { bcb = ocb; bid = oid; bl = ol; }
+    }
+    if (bcb >= 0 && total >= v.Bmax) {
+      if (lane == 0) pl.cand[nc] = bl;
+      fl = bl; ++nc; forced = 1;
+    }
   }
   // the wavefront path takes the plan if every cluster is small and no capacity limit can be hit
   constexpr int kSmall = DT == DYNAKV_F32 ? 32 : 64;
-  long long pages = 0;
-  bool small = true;
-  for (int k = 0; k < nc; ++k) {
-    const int mm = pl.m[pl.cand[k]];
-    small = small && mm <= kSmall;
-    pages += (mm + kPageTokens - 1) / kPageTokens + 1;
+  const bool isc = delayed || lane == fl;
+  const bool small = __ballot(isc && e.m > kSmall) == 0;
+  int pages = isc ? (e.m + kPageTokens - 1) / kPageTokens + 1 : 0;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) pages += __shfl_xor(pages, o);
+  if (lane == 0) {
+    pl.n_cand = nc; pl.forced = forced;
+    pl.fast = small && pl.M + nc <= v.Mcap && pages <= pl.top + (v.Pcap - pl.bump);
   }
-  pl.n_cand = nc; pl.forced = forced;
-  pl.fast = small && pl.M + nc <= v.Mcap && pages <= (long long)pl.top + (v.Pcap - pl.bump);
 }
 
 // Hands candidate `at` of the plan to context c (one wavefront).
@@ -826,42 +846,89 @@ __device__ __forceinline__ void wave_take(const SplitPlan& pl, int at, WaveCtx& 
   wave_sync();
 }
 
-// Head start for split_unit, by ONE wavefront (the first of the workgroup) while the others are busy elsewhere:
-// the plan and, if the wavefront path takes it, the decisions of its first kPreSplits splits.  Reads the index
-// only; writes `wk` and the last kPreSplits contexts of `raw`.  split_unit(..., true) continues from there.
-template <int DT>
-__device__ inline void split_prepare(const View& v, int u, unsigned char* raw, SplitWork& wk) {
-  SplitPlan& pl = wk.pl;
-  WaveCtx* const wc = (WaveCtx*)raw;
-  const int lane = threadIdx.x & 63;
+// ---- head start for split_unit inside a kernel that has just selected the active set and appended a token ----
+// The plan's inputs are requested before the append is committed (plan_fetch_early, first wavefront, after the
+// selection), corrected for what the append changed and turned into the plan right after it (plan_finish); the
+// first kPreSplits splits of the plan can then be decided (split_predecide, one wavefront each) while the rest
+// of the workgroup is busy elsewhere: deciding only reads the index.
+struct PlanEarly {
+  int id, req, cb, cn;     // lane i < nflag0: flagged cluster i; lane nflag0: the cluster the append may flag
+  int fl0, bump0;          // free-page stack entry top0 - 1 - lane; bump pointer
+  int4 pg;
+};
+// flagged0: entry `lane` of the flagged list, nflag0 its length, top0 the height of the free-page stack, all as
+// they are before the append; ja: the cluster the append goes to (< 0: no append).
+__device__ __forceinline__ PlanEarly plan_fetch_early(const View& v, int u, int flagged0, int nflag0, int top0, int ja,
+                                                      int lane) {
   const size_t cbase = (size_t)u * v.Mcap;
-  const int c_ahead = lane < min(64, v.Mcap) ? v.flist[cbase + lane] : 0;
-  const int top = v.free_top[u];
-  const int M0 = v.M[u];
-  const int nf0 = v.nflag[u];
-  if (lane == 0) { wk.nf0 = nf0; wk.M0 = M0; wk.npre = 0; pl.fast = 0; }
-  if (nf0 == 0 || nf0 > 64) return;
-  if (lane < nf0) plan_fetch(v, cbase, pl, lane, c_ahead);
-  if (lane < kFreeAhead) plan_fetch_pages(v, u, pl, lane, top, M0);
-  wave_sync();
-  if (lane == 0) plan_splits<DT>(v, pl, nf0);
-  wave_sync();
-  if (!pl.fast) return;
-  const int npre = min(pl.n_cand, kPreSplits);
-  for (int k = 0; k < npre; ++k) {
-    WaveCtx& c = wc[ctx_of(k)];
-    uint4 none[kVAhead];
-    wave_take(pl, pl.cand[k], c, lane);
-    wave_split_decide<DT, false>(v, u, c, none);
+  PlanEarly e{-1, 0, 0, 0, 0, 0, int4{-1, -1, -1, -1}};
+  const int c = lane < nflag0 ? flagged0 : lane == nflag0 ? ja : -1;
+  if (c >= 0 && nflag0 <= 64) {
+    e.id = c; e.req = v.in_req[cbase + c]; e.cb = v.cb[cbase + c]; e.cn = v.cn[cbase + c];
+    e.pg = *(const int4*)&v.cpg[(cbase + c) * kInlinePages];
   }
-  if (lane == 0) wk.npre = npre;
+  if (lane <= kFreeAhead && lane < top0) e.fl0 = v.freelist[(size_t)u * v.Pcap + top0 - 1 - lane];
+  e.bump0 = v.bump[u];
+  return e;
+}
+// First wavefront, after the append (a: its record, null if there was none) and a barrier.  Leaves the plan in
+// wk.pl and wk.nf0 / M0 / npre (npre = splits to decide ahead).
+template <int DT>
+__device__ inline void plan_finish(const View& v, SplitWork& wk, PlanEarly e, int nflag0, int top0, int M, int ja,
+                                   const AppendSmem* a) {
+  SplitPlan& pl = wk.pl;
+  const int lane = threadIdx.x & 63;
+  int nf = nflag0, top = top0, bump = e.bump0;
+  if (a && a->ok) {
+    nf = a->nflag1; top = a->top1; bump = a->bump1;
+    const int sz = a->cn + a->cb;                        // entries of cluster ja before the append
+    const bool newflag = nf > nflag0;
+    if (newflag ? lane == nflag0 : (lane < nflag0 && e.id == ja)) {
+      e.cb = newflag ? 1 : e.cb + 1;                     // the token went to the buffer of a flagged cluster
+      if (a->slot == 0) {                                // and opened a page
+        const int k = sz / kPageTokens;
+        if (k == 0) e.pg.x = a->page;
+        else if (k == 1) e.pg.y = a->page;
+        else if (k == 2) e.pg.z = a->page;
+        else if (k == 3) e.pg.w = a->page;
+      }
+    }
+  }
+  if (lane >= nf) e.id = -1;
+  const int fl = __shfl(e.fl0, min(lane + (top0 - top), 63));     // the append took at most the top page
+  if (lane == 0) {
+    wk.nf0 = nf; wk.M0 = M; wk.npre = 0;
+    pl.fast = 0; pl.M = M; pl.top = top; pl.bump = bump; pl.fl_base = top;
+  }
+  if (nf == 0 || nf > 64) return;
+  if (lane < kFreeAhead && lane < top) pl.fl[lane] = fl;
+  if (e.id >= 0) {
+    pl.id[lane] = e.id; pl.req[lane] = e.req; pl.cb[lane] = e.cb; pl.m[lane] = e.cn + e.cb;
+    pl.pg[lane][0] = e.pg.x; pl.pg[lane][1] = e.pg.y; pl.pg[lane][2] = e.pg.z; pl.pg[lane][3] = e.pg.w;
+  }
+  wave_sync();
+  plan_splits<DT>(v, pl, PlanEntry{e.id, e.req, e.cb, e.cn + e.cb});
+  wave_sync();
+  if (lane == 0) wk.npre = pl.fast ? min(pl.n_cand, kPreSplits) : 0;
+}
+// Wavefront k < wk.npre decides split k of the plan and computes the children's statistics, into context
+// ctx_of(k) of `raw`; pre_v: the values requested ahead, for the same wavefront to hand to split_unit.
+template <int DT>
+__device__ inline void split_predecide(const View& v, int u, unsigned char* raw, const SplitWork& wk, int k,
+                                       uint4 (&pre_v)[kVAhead]) {
+  WaveCtx& c = ((WaveCtx*)raw)[ctx_of(k)];
+  wave_take(wk.pl, wk.pl.cand[k], c, threadIdx.x & 63);
+  wave_split_decide<DT, true>(v, u, c, pre_v);
+  wave_split_stats<DT>(c);
 }
 
 // All splits of unit u that are due (Algorithm 1, decode block: delayed splits, then the forced one), by the
 // first kSplitThreads threads of the workgroup; no other thread of the workgroup may still be running.
-// raw: kSplitRaw bytes of LDS, 16-byte aligned.  prepared: split_prepare has run (and a barrier since).
+// raw: kSplitRaw bytes of LDS, 16-byte aligned.  prepared: plan_finish and split_predecide have run (and a barrier
+// since), pre_v is what split_predecide left in each of the first wk.npre wavefronts.
 template <int DT>
-__device__ __forceinline__ void split_unit(const View& v, int u, unsigned char* raw, SplitWork& wk, bool prepared) {
+__device__ __forceinline__ void split_unit(const View& v, int u, unsigned char* raw, SplitWork& wk, bool prepared,
+                                           const uint4 (&pre_v)[kVAhead]) {
   constexpr int NT = kSplitThreads;
   SplitPlan& pl = wk.pl;
   int& s_min = wk.s_min;
@@ -882,10 +949,11 @@ __device__ __forceinline__ void split_unit(const View& v, int u, unsigned char* 
     nf0 = v.nflag[u];
     if (nf0 == 0) return;
     if (nf0 <= 64) {
-      if (tid < nf0) plan_fetch(v, cbase, pl, tid, c_ahead);
+      PlanEntry e{-1, 0, 0, 0};
+      if (tid < nf0) e = plan_fetch(v, cbase, pl, tid, c_ahead);
       if (tid >= 64 && tid < 64 + kFreeAhead) plan_fetch_pages(v, u, pl, tid - 64, top_ahead, M0);
       __syncthreads();
-      if (tid == 0) plan_splits<DT>(v, pl, nf0);
+      if (tid < 64) plan_splits<DT>(v, pl, e);
       __syncthreads();
     }
   }
@@ -896,14 +964,18 @@ __device__ __forceinline__ void split_unit(const View& v, int u, unsigned char* 
       const int wave = tid >> 6, lane = tid & 63;
       const int nc = pl.n_cand;
       for (int base = 0; base < nc; base += kWaveSplits) {
-        const int mk = base + ctx_of(wave);            // this wavefront's candidate
+        const int mk = base + wave;                    // this wavefront's candidate
         const bool mine = mk < nc;
-        const bool ahead = mine && mk >= npre;         // the first npre candidates are decided already
+        const bool decide = mine && mk >= npre;        // the first npre candidates are decided already
+        const bool ahead = mine;                       // values requested ahead: here, or by split_predecide
         uint4 vahead[kVAhead];
-        WaveCtx& c = wc[wave];
-        if (ahead) {
+#pragma unroll
+        for (int k = 0; k < kVAhead; ++k) vahead[k] = pre_v[k];
+        WaveCtx& c = wc[ctx_of(wave)];
+        if (decide) {
           wave_take(pl, pl.cand[mk], c, lane);
           wave_split_decide<DT, true>(v, u, c, vahead);
+          wave_split_stats<DT>(c);
         }
         __syncthreads();
         if (tid == 0) {                    // ids and pages, in the order of the splits
