@@ -763,7 +763,6 @@ struct SplitPlan {
 
 // LDS of one unit's splits: `raw` holds either the workgroup-wide split or four wavefront splits.
 constexpr size_t kSplitRaw = sizeof(SplitSmem) > kWaveSplits * sizeof(WaveCtx) ? sizeof(SplitSmem) : kWaveSplits * sizeof(WaveCtx);
-constexpr int kPreSplits = 2;            // splits that split_predecide decides ahead
 struct SplitWork {
   SplitPlan pl;
   long long s_tot;
@@ -849,7 +848,7 @@ __device__ __forceinline__ void wave_take(const SplitPlan& pl, int at, WaveCtx& 
 // ---- head start for split_unit inside a kernel that has just selected the active set and appended a token ----
 // The plan's inputs are requested before the append is committed (plan_fetch_early, first wavefront, after the
 // selection), corrected for what the append changed and turned into the plan right after it (plan_finish); the
-// first kPreSplits splits of the plan can then be decided (split_predecide, one wavefront each) while the rest
+// first splits of the plan can then be decided (split_predecide, one wavefront each) while the rest
 // of the workgroup is busy elsewhere: deciding only reads the index.
 struct PlanEarly {
   int id, req, cb, cn;     // lane i < nflag0: flagged cluster i; lane nflag0: the cluster the append may flag
@@ -872,10 +871,10 @@ __device__ __forceinline__ PlanEarly plan_fetch_early(const View& v, int u, int 
   return e;
 }
 // First wavefront, after the append (a: its record, null if there was none) and a barrier.  Leaves the plan in
-// wk.pl and wk.nf0 / M0 / npre (npre = splits to decide ahead).
+// wk.pl and wk.nf0 / M0 / npre (npre <= max_pre = splits to decide ahead).
 template <int DT>
 __device__ inline void plan_finish(const View& v, SplitWork& wk, PlanEarly e, int nflag0, int top0, int M, int ja,
-                                   const AppendSmem* a) {
+                                   const AppendSmem* a, int max_pre) {
   SplitPlan& pl = wk.pl;
   const int lane = threadIdx.x & 63;
   int nf = nflag0, top = top0, bump = e.bump0;
@@ -909,7 +908,7 @@ __device__ inline void plan_finish(const View& v, SplitWork& wk, PlanEarly e, in
   wave_sync();
   plan_splits<DT>(v, pl, PlanEntry{e.id, e.req, e.cb, e.cn + e.cb});
   wave_sync();
-  if (lane == 0) wk.npre = pl.fast ? min(pl.n_cand, kPreSplits) : 0;
+  if (lane == 0) wk.npre = pl.fast ? min(pl.n_cand, max_pre) : 0;
 }
 // Wavefront k < wk.npre decides split k of the plan and computes the children's statistics, into context
 // ctx_of(k) of `raw`; pre_v: the values requested ahead, for the same wavefront to hand to split_unit.
