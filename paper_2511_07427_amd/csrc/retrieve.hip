@@ -345,16 +345,22 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
     cut = 1; tsel = budget;
   }
 
-  // rank of every selected cluster = number of selected clusters that precede it
+  // rank of every selected cluster = number of selected clusters that precede it.  While the workgroup has
+  // several threads per selected cluster, `tpc` adjacent lanes share one cluster's count (and the first of them
+  // goes on as its owner).
   constexpr int PER = (kCountMax + NT - 1) / NT;
+  int tpc = 1, tsh = 0;
+  while (tpc < 8 && cut * tpc * 2 <= NT) { tpc <<= 1; ++tsh; }
+  const int sub = tid & (tpc - 1);
+  const int chunk = ((cut + tpc - 1) / tpc + 7) & ~7;
   int rk[PER], idw[PER], wt[PER], pg[PER][kInlinePages];
 #pragma unroll
   for (int r = 0; r < PER; ++r) {
-    const int p = tid + r * NT;
+    const int p = r == 0 ? tid >> tsh : tid + r * NT;
     rk[r] = -1; idw[r] = 0; wt[r] = 0;
 #pragma unroll
     for (int k = 0; k < kInlinePages; ++k) pg[r][k] = -1;
-    if (p < cut) {
+    if (p < cut && (r == 0 || tpc == 1)) {              // wavefront-uniform per group of tpc lanes
       const unsigned long long my = ck[p];
       {   // the cluster's page table is requested now and used once its place in the list is known
         const int id = 0xFFFF - (int)(my & 0xFFFF);
@@ -367,14 +373,17 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
         }
       }
       int rank = 0;
-      for (int qb = 0; qb < cut; qb += 8) {           // eight candidates per round trip to LDS
+      const int q0 = r == 0 ? sub * chunk : 0, q1 = r == 0 ? min(cut, q0 + chunk) : cut;
+      for (int qb = q0; qb < q1; qb += 8) {           // eight candidates per round trip to LDS
         unsigned long long o[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) o[i] = ck[min(qb + i, cut - 1)];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) rank += (qb + i < cut && o[i] > my) ? 1 : 0;
+        for (int i = 0; i < 8; ++i) rank += (qb + i < q1 && o[i] > my) ? 1 : 0;
       }
-      rk[r] = rank; idw[r] = 0xFFFF - (int)(my & 0xFFFF); wt[r] = cw[p];
+      if (r == 0)
+        for (int o = 1; o < tpc; o <<= 1) rank += __shfl_xor(rank, o);
+      if (r != 0 || sub == 0) { rk[r] = rank; idw[r] = 0xFFFF - (int)(my & 0xFFFF); wt[r] = cw[p]; }
     }
   }
   __syncthreads();
