@@ -223,16 +223,20 @@ __device__ inline int select_sorted(const View& v, int u, int M, int budget, con
 // found by a radix search over the 32-bit orderable scores (four passes of size-weighted 256-bin histograms);
 // everything above it is selected, equal scores are taken by ascending id while they fit.  Each selected
 // cluster then finds its rank and its gather offsets by counting the selected clusters that precede it.
+// first_ready: the caller has zeroed s.hist and set s.misc (entry 4 = 0x7fffffff, the others 0), has added every
+// cluster's size to bin (key >> 24) of the first histogram, and a barrier lies behind all of that.
 template <int NT>
-__device__ inline int select_phase(const View& v, int u, int M, int budget, const SelectLds& s) {
+__device__ inline int select_phase(const View& v, int u, int M, int budget, const SelectLds& s, bool first_ready = false) {
   const int tid = threadIdx.x, lane = tid & 63;
   const size_t cb = (size_t)u * v.Mcap;
   unsigned long long* ck = (unsigned long long*)s.region;       // (score << 16) | (0xFFFF - id): larger goes first
   int* cw = (int*)(s.region + kCountMax * 8);
 #define DYNAKV_WEIGHT(j) (s.sw ? s.sw[j] : v.cn[cb + (j)] + v.cb[cb + (j)])
-  for (int i = tid; i < 1024; i += NT) s.hist[i] = 0;
-  if (tid < 8) s.misc[tid] = tid == 4 ? 0x7fffffff : 0;
-  __syncthreads();
+  if (!first_ready) {
+    for (int i = tid; i < 1024; i += NT) s.hist[i] = 0;
+    if (tid < 8) s.misc[tid] = tid == 4 ? 0x7fffffff : 0;
+    __syncthreads();
+  }
 
   uint32_t kstar = 0, mask = 0;
   int above = 0, total = 0;
@@ -240,14 +244,16 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
   for (int pass = 0; pass < 4; ++pass) {
     const int shift = 24 - 8 * pass;
     int* h = s.hist + 256 * pass;
-    for (int j = tid; j < M; j += NT) {
-      const uint32_t k = s.skey[j];
-      if ((k & mask) == kstar) {
-        const int w = DYNAKV_WEIGHT(j);
-        if (w) atomicAdd(&h[(k >> shift) & 255], w);
+    if (pass > 0 || !first_ready) {
+      for (int j = tid; j < M; j += NT) {
+        const uint32_t k = s.skey[j];
+        if ((k & mask) == kstar) {
+          const int w = DYNAKV_WEIGHT(j);
+          if (w) atomicAdd(&h[(k >> shift) & 255], w);
+        }
       }
+      __syncthreads();
     }
-    __syncthreads();
     // every wavefront: lane l owns the digits 255 - 4l .. 252 - 4l, highest first
     int hv[4], t = 0;
 #pragma unroll
@@ -902,13 +908,16 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   int Mpad = 2;
   while (Mpad < M) Mpad <<= 1;
   for (int i = M + tid; i < Mpad; i += NT) skey[i] = 0u;
-  // stored sizes: requested now, needed by the selection only, so the score loop hides their latency
-  int szr[kFusedClusters / NT];
+  for (int i = tid; i < 1024; i += NT) hist[i] = 0;
+  if (tid < 8) misc[tid] = tid == 4 ? 0x7fffffff : 0;
+  // stored sizes: a thread scores exactly the clusters tid + k * NT, so each size goes through LDS from the thread
+  // that requested it to itself (and is there for the selection afterwards)
 #pragma unroll
   for (int k = 0; k < kFusedClusters / NT; ++k) {
     const int j = tid + k * NT;
-    szr[k] = j < M ? v.cn[(size_t)u * v.Mcap + j] + v.cb[(size_t)u * v.Mcap + j] : 0;
+    if (j < M) ssz[j] = v.cn[(size_t)u * v.Mcap + j] + v.cb[(size_t)u * v.Mcap + j];
   }
+  static_assert(NW * 64 == NT, "group g of wavefront w holds the clusters tid + (g / NW) * NT");
   __syncthreads();
   double near_d = __builtin_inf();
   int near_j = -1;
@@ -961,7 +970,10 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
           if (g < G) red = v.group_reduce == DYNAKV_GROUP_MAX ? fmax(red, acc[r][g]) : red + acc[r][g];
         const float sc = (float)(red * v.scale_d);
         v.score[(size_t)u * v.Mcap + j] = sc;
-        skey[j] = orderable(sc);
+        const uint32_t key = orderable(sc);
+        skey[j] = key;
+        const int w = ssz[j];                          // first pass of the selection's radix search
+        if (w) atomicAdd(&hist[key >> 24], w);
       }
     }
   };
@@ -973,9 +985,6 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
     else if (cnt == 2) score_groups(std::integral_constant<int, 2>{}, g0, first);
     else if constexpr (kAtOnce == 3) score_groups(std::integral_constant<int, 3>{}, g0, first);
   }
-#pragma unroll
-  for (int k = 0; k < kFusedClusters / NT; ++k)
-    if (tid + k * NT < M) ssz[tid + k * NT] = szr[k];
   // the append's nearest cluster is known now: its record is requested here and used after the selection
   int ja = -1;
   AppendFetch apf{0.0, 0, 0};
@@ -987,7 +996,7 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
 
   // ---- selection
   const SelectLds sel{skey, ssz, smem + kKeys + kSizes, hist, ssz, sm, misc, list, kFusedList};
-  const int nlist = select_phase<NT>(v, u, M, budget, sel);
+  const int nlist = select_phase<NT>(v, u, M, budget, sel, true);
   __syncthreads();
 
   // ---- the append (scores and selection saw the index as it was before); with SPLIT the first wavefront
