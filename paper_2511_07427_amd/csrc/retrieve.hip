@@ -890,7 +890,7 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   }
   // the flagged list and the free-page stack as they are before this step's append: the plan of the splits
   // starts from them
-  int flagged0 = 0, nflag0 = 0, top0 = 0;
+  int flagged0 = 0, nflag0 = 0, top0 = 0;            // kept in LDS (wk) until the selection is done
   if constexpr (SPLIT)
     if (wave == 0) {
       if (lane < v.Mcap) flagged0 = v.flist[(size_t)u * v.Mcap + lane];
@@ -918,6 +918,11 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
     if (j < M) ssz[j] = v.cn[(size_t)u * v.Mcap + j] + v.cb[(size_t)u * v.Mcap + j];
   }
   static_assert(NW * 64 == NT, "group g of wavefront w holds the clusters tid + (g / NW) * NT");
+  if constexpr (SPLIT)
+    if (wave == 0) {
+      wk.flagged0[lane] = flagged0;
+      if (lane == 0) { wk.nflag0 = nflag0; wk.top0 = top0; }
+    }
   __syncthreads();
   double near_d = __builtin_inf();
   int near_j = -1;
@@ -1003,7 +1008,10 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   // requests what the plan of the splits needs beforehand and makes the plan right after
   PlanEarly pe{};
   if constexpr (SPLIT)
-    if (wave == 0) pe = plan_fetch_early(v, u, flagged0, nflag0, top0, room ? ja : -1, lane);
+    if (wave == 0) {
+      flagged0 = wk.flagged0[lane]; nflag0 = wk.nflag0; top0 = wk.top0;
+      pe = plan_fetch_early(v, u, flagged0, nflag0, top0, room ? ja : -1, lane);
+    }
   if constexpr (APPEND) {
     if (room) append_commit<NT>(v, u, ja, M, N, kin, vin, ap, apf);
     else if (tid == 0) v.err[u] |= DYNAKV_ERR_TOKENS;

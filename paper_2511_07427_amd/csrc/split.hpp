@@ -768,6 +768,7 @@ struct SplitWork {
   long long s_tot;
   int s_min;
   int nf0, M0, npre;                     // left by plan_finish: flagged clusters, clusters, splits decided ahead
+  int flagged0[64], nflag0, top0;        // for plan_fetch_early: the flagged list and the free stack before the append
 };
 // Candidate k of a round of wavefront splits is handled by wavefront k and held in context ctx_of(k): the
 // contexts of the first candidates lie at the far end of `raw`, clear of what a caller of split_predecide may
