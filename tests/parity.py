@@ -114,7 +114,9 @@ def run_trajectory(spec: WorkloadSpec, units, steps: int, budget: int | None = N
     out = torch.empty(U, G, d, dtype=torch.float32, device=DEV)
     lse = torch.empty(U, G, dtype=torch.float32, device=DEV)
     worst = 0.0
+    most_splits = 0                    # largest number of splits of one unit in one step
     for t in range(steps):
+        m_before = [o.num_clusters(u) for u in range(U)]
         whole = step_call == "one" or (step_call == "mixed" and t % 2 == 1)
         check = t % check_every == 0 or t == steps - 1
         oo, ol = o.retrieve_attend(w["Q"][t], budget)
@@ -130,9 +132,11 @@ def run_trajectory(spec: WorkloadSpec, units, steps: int, budget: int | None = N
             ix.dynakv_split()
         o.append(w["Knew"][t], w["Vnew"][t])
         o.split()
+        most_splits = max(most_splits, max(o.num_clusters(u) - m_before[u] for u in range(U)))
         if check:
             compare_state(ix, o, "step %d" % t, full=(t % full_every == 0 or t == steps - 1))
     diag = [o.diagnostics(u) for u in range(U)]
     return dict(worst_rel=worst, ties={k: sum(dd["ties"][k] for dd in diag) for k in diag[0]["ties"]},
                 splits=sum(dd["splits"] for dd in diag), forced=sum(dd["forced_splits"] for dd in diag),
-                clusters=[o.num_clusters(u) for u in range(U)], index=ix, oracle=o, workload=w)
+                clusters=[o.num_clusters(u) for u in range(U)], most_splits_in_a_step=most_splits,
+                index=ix, oracle=o, workload=w)

@@ -102,6 +102,17 @@ def test_whole_step_call_matches_the_three_calls(name, units, steps, env, monkey
     assert r["splits"] > 0 or name == "batched16"
 
 
+def test_long_run_through_the_whole_step_call_with_several_splits_per_step(monkeypatch):
+    # the steady state of the benchmark configuration in its launch shape (one workgroup per unit, the whole
+    # step in one kernel): small clusters, several due splits of one unit in one step (decided by separate
+    # wavefronts while the pages are streamed, the fourth after the attention)
+    monkeypatch.setenv("DYNAKV_KV_SPLITS", "1")
+    s = CONFIGS["llama3_8b"]
+    r = run_trajectory(s, [16, 17, 18, 19, 20, 21, 22, 23], 2560, check_every=32, full_every=640, step_call="one")
+    say("long:", {k: r[k] for k in ("worst_rel", "splits", "forced", "clusters", "most_splits_in_a_step")})
+    assert r["splits"] > 2000 and r["most_splits_in_a_step"] >= 3
+
+
 # --------------------------------------------------------------------------- hand-worked fixtures, padded to d = 128
 
 def _pad(a):
