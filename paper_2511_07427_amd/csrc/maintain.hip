@@ -65,8 +65,7 @@ template <int DT>
 __global__ __launch_bounds__(kSplitThreads) void split_kernel(View v) {
   __shared__ __align__(16) unsigned char raw[kSplitRaw];
   __shared__ SplitWork wk;
-  const uint4 none[kVAhead] = {};
-  split_unit<DT>(v, blockIdx.x, raw, wk, false, none);
+  split_unit<DT>(v, blockIdx.x, raw, wk, false);
 }
 
 // ------------------------------------------------------------------------------------------- export

@@ -836,8 +836,8 @@ constexpr int kFusedList = 2048;       // gather-list entries it keeps in LDS (l
 // With SPLIT (only with APPEND) the unit's due splits are part of the same launch: a whole decode step is then
 // one kernel.  The append is committed before the pages are streamed (the gather list is fixed by then and the
 // append touches nothing it names); while the other wavefronts stream, the first one plans the splits and takes
-// the decisions of the first of them, which only read the index; the splits are then carried out after the
-// attention by the first kSplitThreads threads, once the other threads have left.
+// the decisions of the first of them, which only read the index; these splits are written while the attention
+// output is merged, and the rest is carried out by the first kSplitThreads threads, once the others have left.
 template <int DT, int NW, int GP, bool APPEND, bool SPLIT>
 __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const void* Q, int budget, float* out,
                                                                 float* lse, const void* kin, const void* vin) {
@@ -1077,19 +1077,27 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
       for (int i = 0; i < 4; ++i) o[F::out_col(c, 4 * lg + i)] = st.acc[c][i];
     if (lg == 0) { o[kHeadDim] = st.m; o[kHeadDim + 1] = l; }
   }
+  // the splits decided meanwhile get their ids and pages in plan order (one thread) ...
+  if constexpr (SPLIT)
+    if (tid == 0 && nprep > 0) split_assign(v, u, (WaveCtx*)(smem + kRawOff), wk.pl, nprep);
   __syncthreads();
-  for (int t = tid; t < G * kHeadDim; t += NT) {
-    const int gg = t / kHeadDim, dc = t % kHeadDim;
-    const float* b = sm_o + gg * hs;
-    float Mx, L, O;
-    merge_partials(b + kHeadDim, b + kHeadDim + 1, b + dc, NW, ws, Mx, L, O);
-    out[((size_t)u * G + gg) * kHeadDim + dc] = L > 0.f ? O / L : 0.f;
-    if (lse && dc == 0) lse[(size_t)u * G + gg] = L > 0.f ? (Mx + __builtin_amdgcn_logf(L)) * kLn2 : -__builtin_inff();
+  if (SPLIT && wave < nprep) {
+    // ... and are written by the wavefronts that decided them, while the others merge the attention output
+    wave_split_commit<DT>(v, u, ((WaveCtx*)(smem + kRawOff))[ctx_of(wave)], pre_v, true);
+  } else {
+    for (int t = tid - nprep * 64; t < G * kHeadDim; t += NT - nprep * 64) {
+      const int gg = t / kHeadDim, dc = t % kHeadDim;
+      const float* b = sm_o + gg * hs;
+      float Mx, L, O;
+      merge_partials(b + kHeadDim, b + kHeadDim + 1, b + dc, NW, ws, Mx, L, O);
+      out[((size_t)u * G + gg) * kHeadDim + dc] = L > 0.f ? O / L : 0.f;
+      if (lse && dc == 0) lse[(size_t)u * G + gg] = L > 0.f ? (Mx + __builtin_amdgcn_logf(L)) * kLn2 : -__builtin_inff();
+    }
   }
   if constexpr (SPLIT) {
     __syncthreads();                                 // every use of smem lies behind
     if (tid >= kSplitThreads) return;                // barriers from here on count the remaining wavefronts only
-    split_unit<DT>(v, u, smem + kRawOff, wk, true, pre_v);
+    split_unit<DT>(v, u, smem + kRawOff, wk, true);
   }
 }
 

@@ -922,13 +922,44 @@ __device__ inline void split_predecide(const View& v, int u, unsigned char* raw,
   wave_split_stats<DT>(c);
 }
 
+// One thread: ids and pages for the decided splits base .. base + n - 1 of the plan (contexts ctx_of(0 .. n-1)),
+// in the order of the plan.
+__device__ inline void split_assign(const View& v, int u, WaveCtx* wc, SplitPlan& pl, int n) {
+  for (int w = 0; w < n; ++w) {
+    WaveCtx& cw = wc[ctx_of(w)];
+    if (!cw.ok) continue;
+    cw.idM = pl.M++;
+    const int need = (cw.nS + kPageTokens - 1) / kPageTokens + (cw.m - cw.nS + kPageTokens - 1) / kPageTokens;
+    const int from_free = min(need, pl.top);
+    for (int k = 0; k < need; ++k) {
+      const int ra = pl.fl_base - (pl.top - k);          // pl.fl holds the stack as it was at fl_base
+      cw.newpg[k] = k >= from_free ? pl.bump + (k - from_free)
+                    : (ra >= 0 && ra < kFreeAhead) ? pl.fl[ra]
+                                                    : v.freelist[(size_t)u * v.Pcap + pl.top - 1 - k];
+    }
+    pl.top -= from_free;
+    pl.bump += need - from_free;
+  }
+}
+// One thread, once the n splits are committed and nothing reads the parents' pages any more: recycles them.
+__device__ inline void split_recycle(const View& v, int u, const WaveCtx* wc, SplitPlan& pl, int n) {
+  for (int w = 0; w < n; ++w) {
+    const WaveCtx& cw = wc[ctx_of(w)];
+    v.counters[(size_t)u * kCounters + (cw.ok ? 0 : 1)] += 1;
+    if (!cw.ok) continue;
+    const int npg = (cw.m + kPageTokens - 1) / kPageTokens;
+    for (int k = 0; k < npg; ++k) v.freelist[(size_t)u * v.Pcap + pl.top++] = cw.chain[k];
+    pl.fl_base = -(1 << 30);         // the stack has changed: what was read ahead no longer applies
+  }
+}
+
 // All splits of unit u that are due (Algorithm 1, decode block: delayed splits, then the forced one), by the
 // first kSplitThreads threads of the workgroup; no other thread of the workgroup may still be running.
-// raw: kSplitRaw bytes of LDS, 16-byte aligned.  prepared: plan_finish and split_predecide have run (and a barrier
-// since), pre_v is what split_predecide left in each of the first wk.npre wavefronts.
+// raw: kSplitRaw bytes of LDS, 16-byte aligned.  prepared: plan_finish and split_predecide have run and the
+// caller has assigned (split_assign) and committed (wave_split_commit) the wk.npre splits decided ahead, with a
+// barrier since; their parents' pages are still to be recycled.
 template <int DT>
-__device__ __forceinline__ void split_unit(const View& v, int u, unsigned char* raw, SplitWork& wk, bool prepared,
-                                           const uint4 (&pre_v)[kVAhead]) {
+__device__ __forceinline__ void split_unit(const View& v, int u, unsigned char* raw, SplitWork& wk, bool prepared) {
   constexpr int NT = kSplitThreads;
   SplitPlan& pl = wk.pl;
   int& s_min = wk.s_min;
@@ -963,51 +994,27 @@ __device__ __forceinline__ void split_unit(const View& v, int u, unsigned char* 
     if (pl.fast) {
       const int wave = tid >> 6, lane = tid & 63;
       const int nc = pl.n_cand;
-      for (int base = 0; base < nc; base += kWaveSplits) {
+      if (npre > 0) {                      // committed by the caller
+        if (tid == 0) split_recycle(v, u, wc, pl, npre);
+        __syncthreads();
+      }
+      for (int base = npre; base < nc; base += kWaveSplits) {
         const int mk = base + wave;                    // this wavefront's candidate
         const bool mine = mk < nc;
-        const bool decide = mine && mk >= npre;        // the first npre candidates are decided already
-        const bool ahead = mine;                       // values requested ahead: here, or by split_predecide
+        const int n = min(kWaveSplits, nc - base);
         uint4 vahead[kVAhead];
-#pragma unroll
-        for (int k = 0; k < kVAhead; ++k) vahead[k] = pre_v[k];
         WaveCtx& c = wc[ctx_of(wave)];
-        if (decide) {
+        if (mine) {
           wave_take(pl, pl.cand[mk], c, lane);
           wave_split_decide<DT, true>(v, u, c, vahead);
           wave_split_stats<DT>(c);
         }
         __syncthreads();
-        if (tid == 0) {                    // ids and pages, in the order of the splits
-          for (int w = 0; w < kWaveSplits && base + w < nc; ++w) {
-            WaveCtx& cw = wc[ctx_of(w)];
-            if (!cw.ok) continue;
-            cw.idM = pl.M++;
-            const int need = (cw.nS + kPageTokens - 1) / kPageTokens + (cw.m - cw.nS + kPageTokens - 1) / kPageTokens;
-            const int from_free = min(need, pl.top);
-            for (int k = 0; k < need; ++k) {
-              const int ra = pl.fl_base - (pl.top - k);          // pl.fl holds the stack as it was at fl_base
-              cw.newpg[k] = k >= from_free ? pl.bump + (k - from_free)
-                            : (ra >= 0 && ra < kFreeAhead) ? pl.fl[ra]
-                                                                  : v.freelist[(size_t)u * v.Pcap + pl.top - 1 - k];
-            }
-            pl.top -= from_free;
-            pl.bump += need - from_free;
-          }
-        }
+        if (tid == 0) split_assign(v, u, wc, pl, n);             // ids and pages, in the order of the splits
         __syncthreads();
-        if (mine) wave_split_commit<DT>(v, u, c, vahead, ahead);
+        if (mine) wave_split_commit<DT>(v, u, c, vahead, true);
         __syncthreads();
-        if (tid == 0) {                    // the parents' pages are recycled only now
-          for (int w = 0; w < kWaveSplits && base + w < nc; ++w) {
-            const WaveCtx& cw = wc[ctx_of(w)];
-            v.counters[(size_t)u * kCounters + (cw.ok ? 0 : 1)] += 1;
-            if (!cw.ok) continue;
-            const int npg = (cw.m + kPageTokens - 1) / kPageTokens;
-            for (int k = 0; k < npg; ++k) v.freelist[(size_t)u * v.Pcap + pl.top++] = cw.chain[k];
-            pl.fl_base = -(1 << 30);         // the stack has changed: what was read ahead no longer applies
-          }
-        }
+        if (tid == 0) split_recycle(v, u, wc, pl, n);            // the parents' pages are recycled only now
         __syncthreads();
       }
       if (tid == 0) {
