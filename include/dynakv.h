@@ -129,8 +129,11 @@ dynakv_status_t dynakv_split(dynakv_index_t* index, void* stream);
 /* One whole decode step of Algorithm 1 (decode block): dynakv_retrieve_attend(Q), dynakv_append(k_new,
  * v_new) and dynakv_split(), in that order and with the same results bit for bit, so the three calls and
  * this one can be mixed freely.  It exists because the step's two passes over the centroid table (query
- * similarity, Section 4.1; nearest cluster of the new key, Section 4.2) read the same data: with at least
- * 32 units one kernel makes both in a single pass.  Arguments as in the three calls. */
+ * similarity, Section 4.1; nearest cluster of the new key, Section 4.2) read the same data, and because a
+ * step is a chain of short dependent phases: with at least 32 units (16-bit storage, at most 4096 clusters
+ * and 8 query heads per unit) the whole step is ONE kernel launch that reads the table once, commits the
+ * append before it streams the selected pages, and prepares the due splits while it streams them.
+ * Arguments as in the three calls. */
 dynakv_status_t dynakv_decode_step(dynakv_index_t* index, const void* Q, int32_t token_budget, float* out,
                                    float* lse, const void* k_new, const void* v_new, void* stream);
 
@@ -163,12 +166,12 @@ dynakv_status_t dynakv_export_state(dynakv_index_t* index, const dynakv_state_t*
 
 /* Timing aid: when enabled, the dominant kernel of dynakv_retrieve_attend / dynakv_decode_step (gather +
  * attention; with at least 32 units the single kernel that also scores and selects and, in a decode step,
- * appends) is bracketed by HIP events on its own stream.  dynakv_profile_read synchronises those events and
+ * appends and splits) is bracketed by HIP events on its own stream.  dynakv_profile_read synchronises those events and
  * returns the number of launches and their summed duration in milliseconds since the last enable. */
 dynakv_status_t dynakv_profile_enable(dynakv_index_t* index, int32_t max_launches);
 dynakv_status_t dynakv_profile_read(dynakv_index_t* index, int32_t* n_launches, double* total_ms);
 /* Name of the kernel those events bracket: "retrieve_fused_kernel" (scores + selection + gather + attention in
- * one launch) or "gather_attend_kernel". */
+ * one launch; in dynakv_decode_step the append and the splits as well) or "gather_attend_kernel". */
 const char* dynakv_profiled_kernel(dynakv_index_t* index);
 
 const char* dynakv_strerror(dynakv_status_t status);

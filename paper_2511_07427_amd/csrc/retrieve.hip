@@ -5,6 +5,8 @@
 //   gather_attend  - streams the selected clusters' pages once; QK^T and PV on matrix cores with an
 //                    online (running-max) softmax, so any gather order is overflow-safe; split over
 //                    several workgroups per unit and merged by the last one to arrive.
+//   retrieve_fused - all of the above for one unit in one workgroup and, in a whole decode step, the append
+//                    (Section 4.2) and the due splits as well: the step is one launch.
 #include <type_traits>
 
 #include "split.hpp"
