@@ -511,30 +511,35 @@ __global__ __launch_bounds__(256) void kmeans_dist_kernel(View v, const void* X,
   });
 }
 
-// dist[i] = squared distance of point i to the (updated) centre of its own cluster
+// dist[i] = squared distance of point i to the (updated) centre of its own cluster.  Sixteen lanes per point, one
+// block of 8 coordinates each (so a wavefront reads 1 KB of consecutive keys at a time); the 16 block sums are
+// then added left to right by one thread per point.
 __global__ __launch_bounds__(256) void point_dist_kernel(View v, const void* X, int N0) {
-  const int u = blockIdx.y, i = blockIdx.x * 256 + threadIdx.x;
-  if (i >= N0) return;
+  __shared__ double bs[16][17];
+  const int u = blockIdx.y, p = threadIdx.x >> 4, k = threadIdx.x & 15;
+  const int i = min(blockIdx.x * 16 + p, N0 - 1);
   const int j = v.labels[(size_t)u * v.Ncap + i];
   const float* R = unit_R(v, u);
-  const size_t base = ((size_t)u * N0 + i) * kHeadDim;
-  v.dist[(size_t)u * v.Ncap + i] = blocked16([&](int k) __attribute__((always_inline)) {
-    float x[8];
-    load8(X, base + k * 8, v.dtype, x);
-    const f4 ra = *(const f4*)(R + r_index(j, k * 8)), rb = *(const f4*)(R + r_index(j, k * 8 + 4));
-    double acc = 0.0;
+  float x[8];
+  load8(X, ((size_t)u * N0 + i) * kHeadDim + k * 8, v.dtype, x);
+  const f4 ra = *(const f4*)(R + r_index(j, k * 8)), rb = *(const f4*)(R + r_index(j, k * 8 + 4));
+  double acc = 0.0;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const double t = (double)x[e] - (double)(e < 4 ? ra[e] : rb[e - 4]);
-      acc = fma(t, t, acc);
-    }
-    return acc;
-  });
+  for (int e = 0; e < 8; ++e) {
+    const double t = (double)x[e] - (double)(e < 4 ? ra[e] : rb[e - 4]);
+    acc = fma(t, t, acc);
+  }
+  bs[p][k] = acc;
+  __syncthreads();
+  if (threadIdx.x < 16 && blockIdx.x * 16 + threadIdx.x < N0)
+    v.dist[(size_t)u * v.Ncap + blockIdx.x * 16 + threadIdx.x] =
+        blocked16([&](int kk) __attribute__((always_inline)) { return bs[threadIdx.x][kk]; });
 }
 
 // One workgroup per unit: per-cluster n, M2 (members in order), page chains, tau, counters.
 __global__ __launch_bounds__(1024) void finalize_kernel(View v, int N0) {
   __shared__ int sm[64];
+  __shared__ double m2s[kMaxClusters];          // M2 of every cluster, for the sum that gives tau
   const int u = blockIdx.x, tid = threadIdx.x;
   const int* koff = v.koff + (size_t)u * (v.Mcap + 1);
   const int* order = v.order + (size_t)u * v.Ncap;
@@ -553,11 +558,7 @@ __global__ __launch_bounds__(1024) void finalize_kernel(View v, int N0) {
     const int j = tid * 8 + k;
     if (j >= v.Mcap) break;
     if (j < v.M0) {
-      const int b = koff[j], e = koff[j + 1];
-      double m2 = 0.0;
-      for (int q = b; q < e; ++q) m2 += dist[order[q]];
-      v.cn[cb + j] = e - b;
-      v.cM2[cb + j] = m2;
+      v.cn[cb + j] = koff[j + 1] - koff[j];
       v.pg_off[cb + j] = base;
       for (int p = 0; p < kInlinePages; ++p) v.cpg[(cb + j) * kInlinePages + p] = p < np[k] ? base + p : -1;
       v.ctail[cb + j] = np[k] ? base + np[k] - 1 : -1;
@@ -569,6 +570,25 @@ __global__ __launch_bounds__(1024) void finalize_kernel(View v, int N0) {
     }
     v.cb[cb + j] = 0; v.cflag[cb + j] = 0; v.in_req[cb + j] = 0; v.score[cb + j] = 0.f;
   }
+  // M2 of cluster j = sum of its members' distances in storage order: one thread per cluster, eight members
+  // requested at a time, added one by one
+  for (int j = tid; j < v.M0; j += 1024) {
+    const int b = koff[j], e = koff[j + 1];
+    double m2 = 0.0;
+    for (int q0 = b; q0 < e; q0 += 8) {
+      int o[8];
+      double x[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) o[k] = order[min(q0 + k, e - 1)];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) x[k] = dist[o[k]];
+#pragma unroll
+      for (int k = 0; k < 8; ++k)
+        if (q0 + k < e) m2 += x[k];
+    }
+    v.cM2[cb + j] = m2;
+    m2s[j] = m2;
+  }
   if (v.dtype != DYNAKV_F32) {               // search copy of the final centroids
     const float* R = unit_R(v, u);
     uint16_t* Rq = unit_Rq(v, u);
@@ -578,7 +598,7 @@ __global__ __launch_bounds__(1024) void finalize_kernel(View v, int N0) {
   __syncthreads();
   if (tid == 0) {
     double J = 0.0;
-    for (int j = 0; j < v.M0; ++j) J += v.cM2[cb + j];
+    for (int j = 0; j < v.M0; ++j) J += m2s[j];
     v.tau[u] = (double)v.var_alpha * (J / (double)N0);
     v.M[u] = v.M0; v.N[u] = N0; v.err[u] = 0; v.nflag[u] = 0; v.n_sel[u] = 0; v.t_sel[u] = 0; v.n_list[u] = 0;
     v.ticket[u] = 0; v.bump[u] = total; v.free_top[u] = 0; v.last_assign[u] = -1;
@@ -648,7 +668,7 @@ hipError_t launch_build_index(const View& v, const void* K, const void* V, int N
     else kmeans_update_kernel<DYNAKV_BF16><<<gupd, 256, 0, st>>>(v, K, N0);
     if (it + 1 < iters) kmeans_reseed_kernel<<<v.U, 256, 0, st>>>(v, K, N0);
   }
-  point_dist_kernel<<<gpts, 256, 0, st>>>(v, K, N0);
+  point_dist_kernel<<<dim3((N0 + 15) / 16, v.U), 256, 0, st>>>(v, K, N0);
   finalize_kernel<<<v.U, 1024, 0, st>>>(v, N0);
   layout_copy_kernel<<<dim3((N0 + 15) / 16, v.U), 256, 0, st>>>(v, K, V, N0);
   return hipGetLastError();
