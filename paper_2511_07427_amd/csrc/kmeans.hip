@@ -512,12 +512,13 @@ __global__ __launch_bounds__(256) void kmeans_dist_kernel(View v, const void* X,
 }
 
 // dist[i] = squared distance of point i to the (updated) centre of its own cluster.  Sixteen lanes per point, one
-// block of 8 coordinates each (so a wavefront reads 1 KB of consecutive keys at a time); the 16 block sums are
-// then added left to right by one thread per point.
+// block of 8 coordinates each; the 16 block sums are then added left to right by one thread per point.  Points
+// are taken in the sorted order (by cluster), so the 16 points of a workgroup mostly share one centre and its
+// lines of the lane-interleaved table are fetched once.
 __global__ __launch_bounds__(256) void point_dist_kernel(View v, const void* X, int N0) {
   __shared__ double bs[16][17];
   const int u = blockIdx.y, p = threadIdx.x >> 4, k = threadIdx.x & 15;
-  const int i = min(blockIdx.x * 16 + p, N0 - 1);
+  const int i = v.order[(size_t)u * v.Ncap + min((int)blockIdx.x * 16 + p, N0 - 1)];
   const int j = v.labels[(size_t)u * v.Ncap + i];
   const float* R = unit_R(v, u);
   float x[8];
@@ -531,9 +532,9 @@ __global__ __launch_bounds__(256) void point_dist_kernel(View v, const void* X, 
   }
   bs[p][k] = acc;
   __syncthreads();
-  if (threadIdx.x < 16 && blockIdx.x * 16 + threadIdx.x < N0)
-    v.dist[(size_t)u * v.Ncap + blockIdx.x * 16 + threadIdx.x] =
-        blocked16([&](int kk) __attribute__((always_inline)) { return bs[threadIdx.x][kk]; });
+  // (thread 16 t holds the index of point t of the workgroup)
+  if ((threadIdx.x & 15) == 0 && blockIdx.x * 16 + p < N0)
+    v.dist[(size_t)u * v.Ncap + i] = blocked16([&](int kk) __attribute__((always_inline)) { return bs[p][kk]; });
 }
 
 // One workgroup per unit: per-cluster n, M2 (members in order), page chains, tau, counters.
