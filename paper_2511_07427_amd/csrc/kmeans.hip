@@ -433,8 +433,9 @@ __global__ __launch_bounds__(256) void kmeans_assign_mfma_kernel(View v, const v
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
         const float val = acc[t][i];
-        second[t] = fmaxf(second[t], fminf(best[t], val));
-        if (val > best[t]) { best[t] = val; bidx[t] = tile * 32 + 8 * (i >> 2) + 4 * h + (i & 3); }
+        second[t] = __builtin_amdgcn_fmed3f(best[t], second[t], val);      // second <= best: the median is the runner-up
+        if (val > best[t]) bidx[t] = tile * 32 + 8 * (i >> 2) + 4 * h + (i & 3);
+        best[t] = fmaxf(best[t], val);
       }
     if (tile + 1 < ntiles) KM_COMMIT(cur ^ 1);
     __syncthreads();
