@@ -854,8 +854,8 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   constexpr size_t kPhases = kKeys + kSizes + kSelRegion + kList;
   static_assert(!SPLIT || (APPEND && NW * 64 >= kSplitThreads), "splits follow an append");
   // the split's LDS starts where its last kPreSplits contexts, which are filled while pages are streamed, clear
-  // everything the streaming uses (three of them where the 160 KB of LDS allow)
-  constexpr int kPreSplits = GP <= 4 ? 3 : 2;
+  // everything the streaming uses (all four: the 160 KB of LDS allow it)
+  constexpr int kPreSplits = kWaveSplits;
   constexpr size_t kPreCtx = (kWaveSplits - kPreSplits) * sizeof(WaveCtx);
   constexpr size_t kRawOff = !SPLIT || kPreCtx >= kPhases ? 0 : (kPhases - kPreCtx + 15) / 16 * 16;
   static_assert(sizeof(WaveCtx) % 16 == 0 && kWaveSplits * sizeof(WaveCtx) <= kSplitRaw, "split contexts");

@@ -524,18 +524,18 @@ __device__ inline void wave_split_decide(const View& v, int u, WaveCtx& c, uint4
   const char* const pool = v.pages + (size_t)u * v.Pcap * ((size_t)kPageElems * kEs);
   const int m = c.m;
   for (int t0 = 0; t0 < m * kChunks; t0 += 4 * 64) {       // four loads in flight per lane
-    uint4 w[4];
+    f4 w[4];                                               // (a plain vector type: these stay in registers)
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
       const int t = min(t0 + k * 64 + lane, m * kChunks - 1);
       const int i = t / kChunks, ch = t % kChunks;
       const size_t off = (size_t)(DT == DYNAKV_F32 ? k_index32(i & 15, 4 * ch) : k_index16(i & 15, 8 * ch)) * kEs;
-      w[k] = *(const uint4*)(pool + (size_t)c.chain[i >> 4] * (kPageElems * kEs) + off);
+      w[k] = *(const f4*)(pool + (size_t)c.chain[i >> 4] * (kPageElems * kEs) + off);
     }
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
       const int t = t0 + k * 64 + lane;
-      if (t < m * kChunks) *(uint4*)(c.stage + (size_t)(t / kChunks) * kRowBytes + (t % kChunks) * 16) = w[k];
+      if (t < m * kChunks) *(f4*)(c.stage + (size_t)(t / kChunks) * kRowBytes + (t % kChunks) * 16) = w[k];
     }
   }
 #pragma unroll
@@ -631,7 +631,7 @@ __device__ inline void wave_split_decide(const View& v, int u, WaveCtx& c, uint4
 // Exact statistics of the children (of the unsplit cluster if c.ok == 0), one wavefront, LDS only: float32
 // means into c.rA / c.rB, then M2 about those means into c.m2, members in their new order.
 template <int DT>
-__device__ inline void wave_split_stats(WaveCtx& c) {
+__device__ __forceinline__ void wave_split_stats(WaveCtx& c) {
   const int lane = threadIdx.x & 63;
   const int m = c.m, nS = c.nS, nM = m - nS;
   auto at = [&](int q) { return (int)c.perm[q]; };
@@ -714,16 +714,16 @@ __device__ inline void wave_split_commit(const View& v, int u, WaveCtx& c, const
     }
     // then the members past those (all, if nothing was requested ahead), four loads in flight per lane
     for (int t0 = ahead ? kVAhead * 64 : 0; t0 < m * kChunks; t0 += 4 * 64) {
-      uint4 w[4];
+      f4 w[4];
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
         const int t = min(t0 + k * 64 + lane, m * kChunks - 1), i = t / kChunks;
-        w[k] = *(const uint4*)(pool + (size_t)c.chain[i >> 4] * kPageBytes + vchunk(i & 15, t % kChunks));
+        w[k] = *(const f4*)(pool + (size_t)c.chain[i >> 4] * kPageBytes + vchunk(i & 15, t % kChunks));
       }
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
         const int t = t0 + k * 64 + lane;
-        if (t < m * kChunks) *(uint4*)vdest(t / kChunks, t % kChunks) = w[k];
+        if (t < m * kChunks) *(f4*)vdest(t / kChunks, t % kChunks) = w[k];
       }
     }
     if (lane < m) {
