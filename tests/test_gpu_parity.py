@@ -89,8 +89,9 @@ def test_every_launch_shape_of_retrieve_attend(name, units, steps, env, monkeypa
 
 
 @pytest.mark.parametrize("name,units,steps,env", [
-    ("llama3_8b", [7, 8, 9], 160, {"DYNAKV_KV_SPLITS": "1"}),      # one pass over the centroids per step, G = 4
+    ("llama3_8b", [7, 8, 9], 160, {"DYNAKV_KV_SPLITS": "1"}),      # the whole step in one kernel, G = 4
     ("qwen25_7b", [5, 6], 256, {"DYNAKV_KV_SPLITS": "1"}),         # the same with G = 7
+    ("llama3_8b", [7, 8, 9], 160, {"DYNAKV_KV_SPLITS": "1", "DYNAKV_SPLIT_KERNEL": "1"}),   # retrieval + append in one kernel, splits in their own
     ("batched16", [9], 64, {}),                                    # separate kernels behind the same call
 ])
 def test_whole_step_call_matches_the_three_calls(name, units, steps, env, monkeypatch):
