@@ -25,8 +25,8 @@ MFMA_PEAK_TFLOPS = 2500.0      # dense fp16/bf16, published
 # the same counter reads for the float32 -> float16 copy of the 134 217 728-element prefill keys (512 MiB read,
 # 256 MiB written): FETCH_SIZE reads 262 169 KiB for it (factor 2.000), WRITE_SIZE 262 144 KiB (factor 1.000).
 # Only valid for exactly that workload; any other arguments report null.
-PMC_TRAFFIC = {("llama3_8b", 8192, 64, 0): {"fetch_kib": 107011.3, "fetch_scale": 524288.0 / 262169.0,
-                                            "write_kib": 9077.2, "write_scale": 1.0}}
+PMC_TRAFFIC = {("llama3_8b", 8192, 64, 0): {"fetch_kib": 106706.7, "fetch_scale": 524288.0 / 262168.9,
+                                            "write_kib": 8687.5, "write_scale": 1.0}}
 
 
 def cpu_baseline(spec, n_units, steps, budget):
