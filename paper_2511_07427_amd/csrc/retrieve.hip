@@ -833,13 +833,15 @@ constexpr int kFusedList = 2048;       // gather-list entries it keeps in LDS (l
 
 //
 // With APPEND the same pass over the centroid table also finds the cluster nearest to the step's new key
-// (one more accumulator per centroid), and the append itself runs at the end of the kernel: a decode step then
-// reads the table once instead of twice.  Scores and selection see the index as it was before the append.
+// (one more accumulator per centroid), and the append itself is committed after the selection (the gather list is
+// fixed by then and the append touches nothing it names): a decode step then reads the table once instead of
+// twice.  Scores and selection see the index as it was before the append.
 // With SPLIT (only with APPEND) the unit's due splits are part of the same launch: a whole decode step is then
-// one kernel.  The append is committed before the pages are streamed (the gather list is fixed by then and the
-// append touches nothing it names); while the other wavefronts stream, the first one plans the splits and takes
-// the decisions of the first of them, which only read the index; these splits are written while the attention
-// output is merged, and the rest is carried out by the first kSplitThreads threads, once the others have left.
+// one kernel.  The splits are planned right after the append; while the pages are streamed, the first wavefronts,
+// one per due split (up to kWaveSplits), decide their split instead of streaming, which only reads the index;
+// these splits are written while the attention output is merged, and whatever is left (recycling the parents'
+// pages, further splits, the workgroup-wide path for large clusters) is carried out by the first kSplitThreads
+// threads, once the others have left.
 template <int DT, int NW, int GP, bool APPEND, bool SPLIT>
 __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const void* Q, int budget, float* out,
                                                                 float* lse, const void* kin, const void* vin) {
@@ -853,13 +855,12 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   // scores, sizes, candidates, gather list; after the page loop the front doubles as the merge buffer
   constexpr size_t kPhases = kKeys + kSizes + kSelRegion + kList;
   static_assert(!SPLIT || (APPEND && NW * 64 >= kSplitThreads), "splits follow an append");
-  // the split's LDS starts where its last kPreSplits contexts, which are filled while pages are streamed, clear
-  // everything the streaming uses (all four: the 160 KB of LDS allow it)
-  constexpr int kPreSplits = kWaveSplits;
-  constexpr size_t kPreCtx = (kWaveSplits - kPreSplits) * sizeof(WaveCtx);
-  constexpr size_t kRawOff = !SPLIT || kPreCtx >= kPhases ? 0 : (kPhases - kPreCtx + 15) / 16 * 16;
+  // the split's LDS follows everything the streaming uses: its wavefront contexts are filled meanwhile
+  constexpr int kPreSplits = kWaveSplits;              // splits decided while the pages are streamed
+  constexpr size_t kRawOff = SPLIT ? (kPhases + 15) / 16 * 16 : 0;
   static_assert(sizeof(WaveCtx) % 16 == 0 && kWaveSplits * sizeof(WaveCtx) <= kSplitRaw, "split contexts");
-  __shared__ __align__(16) unsigned char smem[SPLIT && kRawOff + kSplitRaw > kPhases ? kRawOff + kSplitRaw : kPhases];
+  static_assert(!SPLIT || kRawOff + kSplitRaw + 16 * 1024 <= 160 * 1024, "LDS of one compute unit");
+  __shared__ __align__(16) unsigned char smem[SPLIT ? kRawOff + kSplitRaw : kPhases];
   __shared__ SplitWork wk;
   __shared__ double qs[kHeadDim][GP];
   __shared__ AppendSmem ap;
