@@ -114,6 +114,15 @@ def test_long_run_through_the_whole_step_call_with_several_splits_per_step(monke
     assert r["splits"] > 2000 and r["most_splits_in_a_step"] >= 3
 
 
+def test_long_run_through_the_whole_step_call_group_of_7(monkeypatch):
+    # the same for the kernel variant that holds up to 8 query heads per KV head (bf16, G = 7)
+    monkeypatch.setenv("DYNAKV_KV_SPLITS", "1")
+    s = CONFIGS["qwen25_7b"]
+    r = run_trajectory(s, [30, 31, 32, 33], 2048, check_every=32, full_every=512, step_call="one")
+    say("long, G = 7:", {k: r[k] for k in ("worst_rel", "splits", "forced", "clusters", "most_splits_in_a_step")})
+    assert r["splits"] > 500 and r["most_splits_in_a_step"] >= 2
+
+
 # --------------------------------------------------------------------------- hand-worked fixtures, padded to d = 128
 
 def _pad(a):
