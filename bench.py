@@ -2,7 +2,7 @@
 
 A step = dynakv_decode_step (retrieve + attend, append, split) over all units of the workload, on seeded
 synthetic drifting-mixture inputs already resident in HBM.  Prints one JSON line: decode steps/s, the
-roofline of the dominant kernel (the whole step in one launch from 32 units on: scores, selection, append,
+roofline of the dominant kernel (the whole step in one launch where the shape allows: scores, selection, append,
 gather + attention, splits; else gather + attention; HBM-bound), and the CPU oracle timed on a bounded sample
 of the same workload on this machine's host cores.
 """

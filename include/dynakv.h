@@ -130,8 +130,8 @@ dynakv_status_t dynakv_split(dynakv_index_t* index, void* stream);
  * v_new) and dynakv_split(), in that order and with the same results bit for bit, so the three calls and
  * this one can be mixed freely.  It exists because the step's two passes over the centroid table (query
  * similarity, Section 4.1; nearest cluster of the new key, Section 4.2) read the same data, and because a
- * step is a chain of short dependent phases: with at least 32 units (16-bit storage, at most 4096 clusters
- * and 8 query heads per unit) the whole step is ONE kernel launch that reads the table once, commits the
+ * step is a chain of short dependent phases: with 16-bit storage, at most 4096 clusters and at most 8 query
+ * heads per unit the whole step is ONE kernel launch that reads the table once, commits the
  * append before it streams the selected pages, and prepares the due splits while it streams them.
  * Arguments as in the three calls. */
 dynakv_status_t dynakv_decode_step(dynakv_index_t* index, const void* Q, int32_t token_budget, float* out,
@@ -165,7 +165,7 @@ typedef struct {
 dynakv_status_t dynakv_export_state(dynakv_index_t* index, const dynakv_state_t* dst, void* stream);
 
 /* Timing aid: when enabled, the dominant kernel of dynakv_retrieve_attend / dynakv_decode_step (gather +
- * attention; with at least 32 units the single kernel that also scores and selects and, in a decode step,
+ * attention; where it can run, the single kernel that also scores and selects and, in a decode step,
  * appends and splits) is bracketed by HIP events on its own stream.  dynakv_profile_read synchronises those events and
  * returns the number of launches and their summed duration in milliseconds since the last enable. */
 dynakv_status_t dynakv_profile_enable(dynakv_index_t* index, int32_t max_launches);

@@ -42,13 +42,17 @@ int pow2_floor(int x) {
 }
 
 // Shape of the gather + attention launch: S workgroups per unit of NW wavefronts each (the workgroup merge
-// needs NW * G * 130 floats of LDS).  One workgroup per unit from 32 units on: the step is bound by dependent
-// round trips to memory rather than by the number of busy compute units, and every further workgroup per unit
-// adds partial results, a ticket and a merge (measured on the 8-unit configuration: 4 workgroups per unit
-// beat 1, 2, 8, 16 and 32; with 112 and 128 units 1 beats 2 and 3).  With S = 1 the single-kernel retrieval
-// runs.  DYNAKV_KV_SPLITS / DYNAKV_ATT_WAVES override for tuning runs.
+// needs NW * G * 130 floats of LDS).  With S = 1 the single-kernel retrieval runs where it can.  Where it cannot
+// (float32, more than kFusedClusters clusters or more than 8 query heads per unit) the separate kernels use one
+// workgroup per unit from 32 units on: the step is bound by dependent round trips to memory rather than by the
+// number of busy compute units, and every further workgroup per unit adds partial results, a ticket and a merge
+// (measured on the 8-unit configuration: 4 workgroups per unit beat 1, 2, 8, 16 and 32; with 112 and 128 units
+// 1 beats 2 and 3).  DYNAKV_KV_SPLITS / DYNAKV_ATT_WAVES override for tuning runs.
 void plan_attention(const dynakv_config_t& c, int* S, int* NW) {
   int s = (32 + c.n_units - 1) / c.n_units;
+  // where the single-kernel retrieval can run (see retrieve_is_fused) it beats split-KV at every unit count:
+  // measured 16.5k against 15.5k steps/s with 8 units, 15.1k against 13.1k with 24 (configuration 2's shape)
+  if (c.dtype != DYNAKV_F32 && c.max_clusters <= kFusedClusters && c.group_size <= 8) s = 1;
   int nw = pow2_floor(4096 / (c.n_units * s) > 0 ? 4096 / (c.n_units * s) : 1);
   if (const char* e = std::getenv("DYNAKV_KV_SPLITS")) s = std::atoi(e);
   if (const char* e = std::getenv("DYNAKV_ATT_WAVES")) nw = std::atoi(e);

@@ -14,6 +14,7 @@ constexpr int kPageTokens = 16;                 // tokens per page = one MFMA ti
 constexpr int kPageElems = 2 * kPageTokens * kHeadDim;  // K region then V region
 constexpr int kMaxClusters = 8192;              // selection sorts one unit's clusters in LDS
 constexpr int kMaxPrefill = 16384;              // k-means sorts one unit's labels in LDS
+constexpr int kFusedClusters = 4096;            // clusters per unit the single-kernel retrieval can hold in LDS
 constexpr int kMaxSplitMembers = 4096;          // largest cluster the split kernel handles
 constexpr int kMaxKvSplits = 64;
 constexpr int kCounters = 8;

@@ -828,7 +828,6 @@ __global__ __launch_bounds__(NW * 64) void gather_attend_kernel(View v, const vo
 // Whole retrieval of one unit in one workgroup (used when there is at least one unit per compute unit):
 // scores -> LDS, sort and budget cut in LDS, gather list in LDS, then the same page loop and merge as
 // gather_attend_kernel.  Saves two launches and every trip through the workspace between the phases.
-constexpr int kFusedClusters = 4096;   // clusters per unit the fused kernel can sort
 constexpr int kFusedList = 2048;       // gather-list entries it keeps in LDS (longer lists are read from the workspace)
 
 //
