@@ -96,7 +96,7 @@ size_t carve(const dynakv_config_t& c, char* base, View* out) {
   v.Rstride = r_stride(v.Mcap);
   v.R = (float*)take(U * v.Rstride * 4);
   v.Rq = (uint16_t*)take(c.dtype == DYNAKV_F32 ? 0 : U * v.Rstride * 2);
-  v.cn = (int*)take(UM * 4); v.cb = (int*)take(UM * 4); v.cflag = (int*)take(UM * 4); v.flist = (int*)take(UM * 4); v.cM2 = (double*)take(UM * 8);
+  v.cn = (int*)take(UM * 4); v.cb = (int*)take(UM * 4); v.csz = (int*)take(UM * 4); v.cflag = (int*)take(UM * 4); v.flist = (int*)take(UM * 4); v.cM2 = (double*)take(UM * 8);
   v.cpg = (int*)take(UM * kInlinePages * 4); v.ctail = (int*)take(UM * 4); v.score = (float*)take(UM * 4);
   v.sel_ids = (int*)take(UM * 4); v.in_req = (unsigned char*)take(UM); v.tok_off = (int*)take(UM * 4);
   v.pg_off = (int*)take(UM * 4);

@@ -116,6 +116,7 @@ __device__ inline void append_commit(const View& v, int u, int j, int M, int N, 
       v.last_assign[u] = j;
       if (a.cflag) {
         v.cb[cbase + j] = a.cb + 1;       // goes to the buffer of a flagged cluster
+        v.csz[cbase + j] = a.cn + a.cb + 1;
       } else {
         // UpdateVar, the running part: M2' = M2 + sum_d delta_d * (k_d - r'_d)
         const double M2 = a.m2 + blocked16([&](int k) __attribute__((always_inline)) { return a.bs[k]; });
@@ -127,11 +128,13 @@ __device__ inline void append_commit(const View& v, int u, int j, int M, int N, 
         }
         if (!trig) {
           v.cn[cbase + j] = n1;
+          v.csz[cbase + j] = n1 + a.cb;
           v.cM2[cbase + j] = M2;
           commit = 1;
         } else {
           v.cflag[cbase + j] = 1;
           v.cb[cbase + j] = 1;
+          v.csz[cbase + j] = a.cn + 1;
           v.flist[cbase + a.nflag] = j;
           v.nflag[u] = a.nflag + 1;
           a.nflag1 = a.nflag + 1;

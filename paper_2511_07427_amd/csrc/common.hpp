@@ -48,6 +48,7 @@ struct View {
   uint16_t* Rq;      // [U][Rstride] the same centroids rounded to the 16-bit storage type (see rq_index()): the
                      // copy that the searches of a decode step read; unused for float32 storage
   int* cn;           // committed size n_j
+  int* csz;          // stored entries n_j + |Buf_j| (kept beside the two so that the selection reads one array)
   int* cb;           // buffered entries |Buf_j|
   int* cflag;        // f_j
   int* flist;        // ids of the flagged clusters, first nflag[u] entries, in no particular order

@@ -561,13 +561,14 @@ __global__ __launch_bounds__(1024) void finalize_kernel(View v, int N0) {
     if (j >= v.Mcap) break;
     if (j < v.M0) {
       v.cn[cb + j] = koff[j + 1] - koff[j];
+      v.csz[cb + j] = koff[j + 1] - koff[j];
       v.pg_off[cb + j] = base;
       for (int p = 0; p < kInlinePages; ++p) v.cpg[(cb + j) * kInlinePages + p] = p < np[k] ? base + p : -1;
       v.ctail[cb + j] = np[k] ? base + np[k] - 1 : -1;
       for (int p = 0; p < np[k]; ++p) v.pnext[(size_t)u * v.Pcap + base + p] = p + 1 < np[k] ? base + p + 1 : -1;
       base += np[k];
     } else {
-      v.cn[cb + j] = 0; v.cM2[cb + j] = 0.0; v.ctail[cb + j] = -1;
+      v.cn[cb + j] = 0; v.csz[cb + j] = 0; v.cM2[cb + j] = 0.0; v.ctail[cb + j] = -1;
       for (int p = 0; p < kInlinePages; ++p) v.cpg[(cb + j) * kInlinePages + p] = -1;
     }
     v.cb[cb + j] = 0; v.cflag[cb + j] = 0; v.in_req[cb + j] = 0; v.score[cb + j] = 0.f;

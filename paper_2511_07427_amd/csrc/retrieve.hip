@@ -900,6 +900,13 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
       top0 = v.free_top[u];
     }
   const int M = v.M[u];
+  // stored sizes, requested for every cluster slot of the unit so that the requests do not wait for M
+  int szr[kFusedClusters / NT];
+#pragma unroll
+  for (int k = 0; k < kFusedClusters / NT; ++k) {
+    const int j = tid + k * NT;
+    szr[k] = j < v.Mcap ? v.csz[(size_t)u * v.Mcap + j] : 0;
+  }
   for (int t = tid; t < GP * kHeadDim; t += NT) {
     const int g = t / kHeadDim, d = t % kHeadDim;
     qs[d][g] = g < G ? (double)load_elem(Q, ((size_t)u * G + g) * kHeadDim + d, v.dtype) : 0.0;
@@ -915,10 +922,8 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   // stored sizes: a thread scores exactly the clusters tid + k * NT, so each size goes through LDS from the thread
   // that requested it to itself (and is there for the selection afterwards)
 #pragma unroll
-  for (int k = 0; k < kFusedClusters / NT; ++k) {
-    const int j = tid + k * NT;
-    if (j < M) ssz[j] = v.cn[(size_t)u * v.Mcap + j] + v.cb[(size_t)u * v.Mcap + j];
-  }
+  for (int k = 0; k < kFusedClusters / NT; ++k)
+    if (tid + k * NT < M) ssz[tid + k * NT] = szr[k];
   static_assert(NW * 64 == NT, "group g of wavefront w holds the clusters tid + (g / NW) * NT");
   if constexpr (SPLIT)
     if (wave == 0) {

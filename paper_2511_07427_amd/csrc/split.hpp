@@ -300,7 +300,7 @@ __device__ __forceinline__ void split_cluster_impl(const View& v, int u, int j, 
     __syncthreads();
     children_stats(v, u, s, ks, STAGED, m, m, j, -1);
     if (tid == 0) {
-      v.cn[cbase + j] = m; v.cb[cbase + j] = 0; v.cflag[cbase + j] = 0; v.cM2[cbase + j] = s.m2[0];
+      v.cn[cbase + j] = m; v.csz[cbase + j] = m; v.cb[cbase + j] = 0; v.cflag[cbase + j] = 0; v.cM2[cbase + j] = s.m2[0];
       s.nflag -= 1;
       v.flist[cbase + pos] = v.flist[cbase + s.nflag];     // the last flagged id takes the freed place
       v.counters[(size_t)u * kCounters + 1] += 1;
@@ -366,9 +366,9 @@ __device__ __forceinline__ void split_cluster_impl(const View& v, int u, int j, 
     v.cpg[(cbase + M) * kInlinePages + tid] = tid < pM ? s.newpg[pS + tid] : -1;
   }
   if (tid == 0) {
-    v.cn[cbase + j] = nS; v.cb[cbase + j] = 0; v.cflag[cbase + j] = 0; v.cM2[cbase + j] = s.m2[0];
+    v.cn[cbase + j] = nS; v.csz[cbase + j] = nS; v.cb[cbase + j] = 0; v.cflag[cbase + j] = 0; v.cM2[cbase + j] = s.m2[0];
     v.ctail[cbase + j] = s.newpg[pS - 1];
-    v.cn[cbase + M] = nM; v.cb[cbase + M] = 0; v.cflag[cbase + M] = 0; v.cM2[cbase + M] = s.m2[1];
+    v.cn[cbase + M] = nM; v.csz[cbase + M] = nM; v.cb[cbase + M] = 0; v.cflag[cbase + M] = 0; v.cM2[cbase + M] = s.m2[1];
     v.ctail[cbase + M] = s.newpg[pS + pM - 1];
     v.in_req[cbase + M] = 0;
     s.M = M + 1;
@@ -740,10 +740,10 @@ __device__ inline void wave_split_commit(const View& v, int u, WaveCtx& c, const
     v.cpg[(cbase + idM) * kInlinePages + lane] = lane < pM ? c.newpg[pS + lane] : -1;
   }
   if (lane == 0) {
-    v.cn[cbase + j] = nS; v.cb[cbase + j] = 0; v.cflag[cbase + j] = 0; v.cM2[cbase + j] = c.m2[0];
+    v.cn[cbase + j] = nS; v.csz[cbase + j] = nS; v.cb[cbase + j] = 0; v.cflag[cbase + j] = 0; v.cM2[cbase + j] = c.m2[0];
     if (c.ok) {
       v.ctail[cbase + j] = c.newpg[pS - 1];
-      v.cn[cbase + idM] = nM; v.cb[cbase + idM] = 0; v.cflag[cbase + idM] = 0; v.cM2[cbase + idM] = c.m2[1];
+      v.cn[cbase + idM] = nM; v.csz[cbase + idM] = nM; v.cb[cbase + idM] = 0; v.cflag[cbase + idM] = 0; v.cM2[cbase + idM] = c.m2[1];
       v.ctail[cbase + idM] = c.newpg[pS + pM - 1];
       v.in_req[cbase + idM] = 0;
     }
