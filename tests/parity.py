@@ -50,15 +50,20 @@ def check_attention(out_g: np.ndarray, lse_g: np.ndarray, out_o: np.ndarray, lse
     return float(rel.max())
 
 
-def compare_retrieval(ix: binding.Index, o: Oracle, what="", gather=True):
+def _pairs(ix: binding.Index, units):
+    """(unit of the library's index, unit of the oracle's): the oracle holds either all units or the sample `units`."""
+    return list(enumerate(range(ix.cfg.n_units) if units is None else units))
+
+
+def compare_retrieval(ix: binding.Index, o: Oracle, what="", gather=True, units=None):
     """Scores, selected clusters (ordered) and gather indices (ordered) of the last retrieval, bit for bit.
     The gather indices can only be read back before the next split (which may recycle the pages the gather
     list points to): after a whole-step call pass gather=False."""
     fields = ["n_selected", "selected", "n_gathered", "scores"] + (["gathered"] if gather else [])
     st = {k: v.numpy() for k, v in ix.dynakv_export_state(fields).items()}
-    for u in range(ix.cfg.n_units):
+    for ou, u in _pairs(ix, units):
         w = "%s unit %d" % (what, u)
-        sel, gat, sc = o.selected(u), o.gather(u), o.scores(u)
+        sel, gat, sc = o.selected(ou), o.gather(ou), o.scores(ou)
         assert st["n_selected"][u] == len(sel), w
         np.testing.assert_array_equal(st["selected"][u, :len(sel)], sel, err_msg=w + " selected clusters")
         assert st["n_gathered"][u] == len(gat), w
@@ -67,30 +72,30 @@ def compare_retrieval(ix: binding.Index, o: Oracle, what="", gather=True):
         np.testing.assert_array_equal(st["scores"][u, :len(sc)], sc, err_msg=w + " scores")
 
 
-def compare_state(ix: binding.Index, o: Oracle, what="", full=True):
+def compare_state(ix: binding.Index, o: Oracle, what="", full=True, units=None):
     """Partition and per-cluster statistics of every unit, bit for bit."""
     fields = ["n_clusters", "n_tokens", "error", "size", "buffered", "flag", "last_assign"]
     if full:
         fields += ["tau", "centroids", "m2", "offsets", "members", "counters"]
     st = {k: v.numpy() for k, v in ix.dynakv_export_state(fields).items()}
-    for u in range(ix.cfg.n_units):
+    for ou, u in _pairs(ix, units):
         w = "%s unit %d" % (what, u)
-        M, N = o.num_clusters(u), o.num_tokens(u)
+        M, N = o.num_clusters(ou), o.num_tokens(ou)
         assert st["n_clusters"][u] == M and st["n_tokens"][u] == N, w
-        assert st["error"][u] == o.error(u), w
-        c = o.clusters(u)
+        assert st["error"][u] == o.error(ou), w
+        c = o.clusters(ou)
         np.testing.assert_array_equal(st["size"][u, :M], c["n"], err_msg=w)
         np.testing.assert_array_equal(st["buffered"][u, :M], c["b"], err_msg=w)
         np.testing.assert_array_equal(st["flag"][u, :M], c["flag"], err_msg=w)
-        assert st["last_assign"][u] == o.last_assign(u), w
+        assert st["last_assign"][u] == o.last_assign(ou), w
         if full:
-            off, mem = o.members(u)
+            off, mem = o.members(ou)
             np.testing.assert_array_equal(st["offsets"][u, :M + 1], off, err_msg=w)
             np.testing.assert_array_equal(st["members"][u, :N], mem, err_msg=w + " memberships")
             np.testing.assert_array_equal(st["centroids"][u, :M], c["centroids"], err_msg=w + " centroids")
             np.testing.assert_array_equal(st["m2"][u, :M], c["M2"], err_msg=w + " M2")
-            assert st["tau"][u] == o.tau(u), w
-            d = o.diagnostics(u)
+            assert st["tau"][u] == o.tau(ou), w
+            d = o.diagnostics(ou)
             assert (st["counters"][u, 0], st["counters"][u, 1], st["counters"][u, 2]) == \
                 (d["splits"], d["failed_splits"], d["forced_splits"]), w
     return st
@@ -140,3 +145,41 @@ def run_trajectory(spec: WorkloadSpec, units, steps: int, budget: int | None = N
                 splits=sum(dd["splits"] for dd in diag), forced=sum(dd["forced_splits"] for dd in diag),
                 clusters=[o.num_clusters(u) for u in range(U)], most_splits_in_a_step=most_splits,
                 index=ix, oracle=o, workload=w)
+
+
+def run_full_size(spec: WorkloadSpec, sample, steps: int, check_every: int = 16, full_every: int = 64):
+    """The library on ALL units of the configuration, through the whole-step call and in its default launch
+    shape (what the benchmark times), beside the oracle on the units `sample`: attention outputs, retrieval and
+    index state of the sampled units are compared as in run_trajectory."""
+    sample = list(sample)
+    w = generate(spec, steps=steps, workers=16)
+    kw = dict(group_size=spec.group_size, n_clusters_init=spec.n_clusters_init, max_clusters=spec.max_clusters,
+              max_tokens=spec.prefill + steps, kmeans_iters=spec.kmeans_iters, buffer_max=spec.buffer_max, group_reduce=0,
+              var_alpha=spec.var_alpha, size_factor=spec.size_factor, softmax_scale=0.0)
+    ix = binding.Index(binding.Config(dtype=spec.dtype, head_dim=spec.head_dim, n_units=spec.n_units, **kw), DEV)
+    o = Oracle(OracleConfig(head_dim=spec.head_dim, seed=0, dtype=spec.dtype, n_units=len(sample), **kw))
+    ix.dynakv_build_index(to_dev(w["K0"], spec.dtype), to_dev(w["V0"], spec.dtype), torch.from_numpy(w["init_idx"]).to(DEV))
+    o.build_index(w["K0"][sample], w["V0"][sample], w["init_idx"][sample])
+    compare_state(ix, o, "after build_index", units=sample)
+    Qd, Kd, Vd = to_dev(w["Q"], spec.dtype), to_dev(w["Knew"], spec.dtype), to_dev(w["Vnew"], spec.dtype)
+    out = torch.empty(spec.n_units, spec.group_size, spec.head_dim, dtype=torch.float32, device=DEV)
+    lse = torch.empty(spec.n_units, spec.group_size, dtype=torch.float32, device=DEV)
+    worst = 0.0
+    for t in range(steps):
+        check = t % check_every == 0 or t == steps - 1
+        oo, ol = o.retrieve_attend(w["Q"][t][sample], spec.budget)
+        ix.dynakv_decode_step(Qd[t], spec.budget, out, lse, Kd[t], Vd[t])
+        if check:
+            og, lg = out.cpu().numpy(), lse.cpu().numpy()
+            assert np.isfinite(og).all(), "step %d" % t
+            worst = max(worst, check_attention(og[sample], lg[sample], oo, ol, "step %d" % t))
+            compare_retrieval(ix, o, "step %d" % t, gather=False, units=sample)
+        o.append(w["Knew"][t][sample], w["Vnew"][t][sample])
+        o.split()
+        if check:
+            compare_state(ix, o, "step %d" % t, full=(t % full_every == 0 or t == steps - 1), units=sample)
+    err = ix.dynakv_export_state(["error"])["error"].numpy()
+    assert not err.any(), "error words %s" % np.unique(err)
+    diag = [o.diagnostics(k) for k in range(len(sample))]
+    return dict(worst_rel=worst, splits=sum(dd["splits"] for dd in diag), forced=sum(dd["forced_splits"] for dd in diag),
+                clusters=[o.num_clusters(k) for k in range(len(sample))])
