@@ -59,7 +59,9 @@ def main():
     ap.add_argument("--steps", type=int, default=8192)
     ap.add_argument("--warmup", type=int, default=64)
     ap.add_argument("--config", default="llama3_8b")
-    ap.add_argument("--units", type=int, default=0, help="debug: use only the first UNITS units")
+    ap.add_argument("--units", type=int, default=0,
+                    help="run UNITS units instead of the configuration's own count: fewer = its first units; more = "
+                         "further independent draws of the same shape (more layers or sequences), labelled as such")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="skip the HIP events around the dominant kernel")
     a = ap.parse_args()
@@ -73,6 +75,7 @@ def main():
     from paper_2511_07427_amd.workload import CONFIGS, generate
 
     spec = CONFIGS[a.config]
+    own_units = spec.n_units
     if a.units:
         spec = spec.scaled(n_units=a.units)
     T = a.warmup + a.steps
@@ -166,9 +169,10 @@ def main():
         "unit": "decode steps/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": dt / a.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": spec.dtype, "data": "synthetic",
-        "config": {"workload": "%s: %d units (layers x KV heads), G=%d, d=%d, %s, prefill %d, M0=%d clusters, "
+        "config": {"workload": "%s: %d units (layers x KV heads)%s, G=%d, d=%d, %s, prefill %d, M0=%d clusters, "
                                "token budget %d, decode steps %d..%d of a drifting %d-component mixture" %
-                               (spec.name, U, G, d, spec.dtype, spec.prefill, spec.n_clusters_init, spec.budget,
+                               (spec.name, U, "" if U == own_units else " INSTEAD OF THE CONFIGURATION'S %d" % own_units,
+                                G, d, spec.dtype, spec.prefill, spec.n_clusters_init, spec.budget,
                                 a.warmup, T, spec.n_components),
                    "kv_splits": ix and int(os.environ.get("DYNAKV_KV_SPLITS", "0")) or None},
         "roofline": roof,

@@ -394,6 +394,11 @@ __device__ inline unsigned long long block_excl_scan64(unsigned long long val, u
 }
 
 // k-th page of the cluster with flat index cj (= u * Mcap + j); `prev` is its page k-1.
+// Adds n to counter k of unit u without waiting for the old value (the counters are statistics: nothing in a
+// kernel reads them back).
+__device__ __forceinline__ void count(const View& v, int u, int k, long long n) {
+  __hip_atomic_fetch_add(&v.counters[(size_t)u * kCounters + k], n, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 __device__ inline int cluster_page(const View& v, int u, size_t cj, int k, int prev) {
   return k < kInlinePages ? v.cpg[cj * kInlinePages + k] : v.pnext[(size_t)u * v.Pcap + prev];
 }

@@ -209,9 +209,9 @@ __device__ inline int select_sorted(const View& v, int u, int M, int budget, con
   }
   if (tid == 0) {
     v.n_sel[u] = cut; v.t_sel[u] = tsel; v.n_list[u] = total; v.ticket[u] = 0;
-    v.counters[(size_t)u * kCounters + 4] += tsel;
-    v.counters[(size_t)u * kCounters + 5] += 1;
-    v.counters[(size_t)u * kCounters + 6] += M;
+    count(v, u, 4, tsel);
+    count(v, u, 5, 1);
+    count(v, u, 6, M);
   }
   return total;
 }
@@ -456,9 +456,9 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
   const int nlist = s.misc[6];
   if (tid == 0) {
     v.n_sel[u] = cut; v.t_sel[u] = tsel; v.n_list[u] = nlist; v.ticket[u] = 0;
-    v.counters[(size_t)u * kCounters + 4] += tsel;
-    v.counters[(size_t)u * kCounters + 5] += 1;
-    v.counters[(size_t)u * kCounters + 6] += M;
+    count(v, u, 4, tsel);
+    count(v, u, 5, 1);
+    count(v, u, 6, M);
   }
 #undef DYNAKV_WEIGHT
   return nlist;

@@ -303,7 +303,7 @@ __device__ __forceinline__ void split_cluster_impl(const View& v, int u, int j, 
       v.cn[cbase + j] = m; v.csz[cbase + j] = m; v.cb[cbase + j] = 0; v.cflag[cbase + j] = 0; v.cM2[cbase + j] = s.m2[0];
       s.nflag -= 1;
       v.flist[cbase + pos] = v.flist[cbase + s.nflag];     // the last flagged id takes the freed place
-      v.counters[(size_t)u * kCounters + 1] += 1;
+      count(v, u, 1, 1);
     }
     __syncthreads();
     return;
@@ -376,7 +376,7 @@ __device__ __forceinline__ void split_cluster_impl(const View& v, int u, int j, 
     s.a_bump = bump + (need - from_free);
     s.nflag -= 1;
     v.flist[cbase + pos] = v.flist[cbase + s.nflag];
-    v.counters[(size_t)u * kCounters + 0] += 1;
+    count(v, u, 0, 1);
   }
   __syncthreads();
 }
@@ -945,7 +945,7 @@ __device__ inline void split_assign(const View& v, int u, WaveCtx* wc, SplitPlan
 __device__ inline void split_recycle(const View& v, int u, const WaveCtx* wc, SplitPlan& pl, int n) {
   for (int w = 0; w < n; ++w) {
     const WaveCtx& cw = wc[ctx_of(w)];
-    v.counters[(size_t)u * kCounters + (cw.ok ? 0 : 1)] += 1;
+    count(v, u, (cw.ok ? 0 : 1), 1);
     if (!cw.ok) continue;
     const int npg = (cw.m + kPageTokens - 1) / kPageTokens;
     for (int k = 0; k < npg; ++k) v.freelist[(size_t)u * v.Pcap + pl.top++] = cw.chain[k];
@@ -1017,13 +1017,13 @@ __device__ __forceinline__ void split_unit(const View& v, int u, unsigned char* 
         if (tid == 0) split_recycle(v, u, wc, pl, n);            // the parents' pages are recycled only now
         __syncthreads();
       }
-      if (tid == 0) {
+      if (tid == 0 && nc > 0) {            // (no split: list and counters are as they were)
         int n = 0;
         for (int k = 0; k < nc; ++k) pl.id[pl.cand[k]] = -1;
         for (int i = 0; i < nf0; ++i)
           if (pl.id[i] >= 0) v.flist[cbase + n++] = pl.id[i];
         v.nflag[u] = n; v.M[u] = pl.M; v.free_top[u] = pl.top; v.bump[u] = pl.bump;
-        if (pl.forced) v.counters[(size_t)u * kCounters + 2] += 1;
+        if (pl.forced) count(v, u, 2, 1);
       }
       return;
     }
@@ -1072,7 +1072,7 @@ __device__ __forceinline__ void split_unit(const View& v, int u, unsigned char* 
       const long long total = s_tot;
       __syncthreads();
       if (!(arg >= 0 && total >= v.Bmax)) break;
-      if (tid == 0) v.counters[(size_t)u * kCounters + 2] += 1;
+      if (tid == 0) count(v, u, 2, 1);
       j = arg / kMaxClusters; pos = arg % kMaxClusters;
     }
     split_cluster<DT>(v, u, j, pos, s);

@@ -332,6 +332,24 @@ def test_prefill_with_a_wide_key_range_sums_in_storage_order():
     compare_state(ix, o, "wide-range build")
 
 
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_prefill_with_coinciding_centres(dtype):
+    """Keys drawn from a handful of distinct vectors, so that many initial centres coincide: points whose nearest
+    centre is one of several equal ones (lowest id wins), few enough of them for the candidate lists of the
+    matrix-core assignment (unit 1) and too many (unit 0, every such point gets the full float64 scan)."""
+    s = WorkloadSpec("dup", dtype, 2, 2, 900, 4, 40, 256, 6, 0.05, var_alpha=0.0, size_factor=0.0, seed=321)
+    w = generate(s)
+    K0 = w["K0"].copy()
+    for u, distinct in enumerate((3, 11)):
+        base = K0[u, :distinct].copy()
+        K0[u, :600] = base[np.arange(600) % distinct]          # the remaining 300 keys stay as drawn
+    init = np.tile(np.arange(40, dtype=np.int32), (2, 1))      # the first 40 keys: 3 resp. 11 distinct centres
+    ix, o = make_pair(s, 2, kmeans_iters=4)
+    ix.dynakv_build_index(to_dev(K0, dtype), to_dev(w["V0"], dtype), torch.from_numpy(init).to(DEV))
+    o.build_index(K0, w["V0"], init)
+    compare_state(ix, o, "coinciding centres")
+
+
 def test_rebuild_resets_the_index_and_runs_are_deterministic():
     s = CONFIGS["tiny"].scaled(prefill=777, n_clusters_init=19)
     w = generate(s, steps=8)
