@@ -23,10 +23,10 @@ MFMA_PEAK_TFLOPS = 2500.0      # dense fp16/bf16, published
 # HBM bytes per launch of the dominant kernel from two `rocprofv3 --pmc` runs of this file with its default
 # arguments (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch averaged over the timed launches), each scaled by what
 # the same counter reads for the float32 -> float16 copy of the 134 217 728-element prefill keys (512 MiB read,
-# 256 MiB written): FETCH_SIZE reads 262 169 KiB for it (factor 2.000), WRITE_SIZE 262 144 KiB (factor 1.000).
+# 256 MiB written): FETCH_SIZE reads 262 166 KiB for it (factor 2.000), WRITE_SIZE 262 144 KiB (factor 1.000).
 # Only valid for exactly that workload; any other arguments report null.
-PMC_TRAFFIC = {("llama3_8b", 8192, 64, 0): {"fetch_kib": 106706.7, "fetch_scale": 524288.0 / 262168.9,
-                                            "write_kib": 8687.5, "write_scale": 1.0}}
+PMC_TRAFFIC = {("llama3_8b", 8192, 64, 0): {"fetch_kib": 107229.4, "fetch_scale": 524288.0 / 262166.25,
+                                            "write_kib": 7809.2, "write_scale": 1.0}}
 
 
 def cpu_baseline(spec, n_units, steps, budget):

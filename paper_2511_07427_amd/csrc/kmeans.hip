@@ -350,7 +350,7 @@ __global__ __launch_bounds__(256) void kmeans_prep_kernel(View v) {
 // filtered values of point p for the centres 8*(i/4) + 4*h + i%4 of every tile, so the running best / second
 // best need no cross-lane work until the very end.
 template <bool BF>
-__global__ __launch_bounds__(256) void kmeans_assign_mfma_kernel(View v, const void* X, int N0) {
+__global__ __launch_bounds__(256, 3) void kmeans_assign_mfma_kernel(View v, const void* X, int N0) {
   constexpr int NT = BF ? 3 : 2;
   __shared__ uint4 sA[2][NT * 8 * 64];     // two tiles: the next one is fetched while this one is consumed
   __shared__ float shn[2][32];
