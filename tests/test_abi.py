@@ -69,12 +69,16 @@ def test_create_and_call_order_errors(lib):
     assert lib.dynakv_strerror(3).decode().startswith("call out of order")
 
 
-def test_page_layout_is_a_bijection():
-    """The page layout formulas of csrc/common.hpp, retyped here only to check they tile a page exactly once."""
-    def k16(s, d): return (d >> 5) * 512 + ((((d & 31) >> 3) << 4) + s) * 8 + (d & 7)
-    def v16(s, d): return 2048 + ((d >> 4) >> 1) * 512 + (((s >> 2) << 4) + (d & 15)) * 8 + ((d >> 4) & 1) * 4 + (s & 3)
-    def k32(s, d): return (d >> 4) * 256 + ((((d & 15) >> 2) << 4) + s) * 4 + (d & 3)
-    def v32(s, d): return 2048 + (d >> 4) * 256 + (((s >> 2) << 4) + (d & 15)) * 4 + (s & 3)
-    for k, v in ((k16, v16), (k32, v32)):
-        idx = [f(s, d) for f in (k, v) for s in range(16) for d in range(128)]
-        assert sorted(idx) == list(range(4096))
+def test_page_and_centroid_table_layouts_are_bijections():
+    """The index formulas of csrc/common.hpp, retyped here only to check that they tile their arrays exactly once:
+    a page (K rows, then V rows, one row of 128 per token slot) and the two lane-interleaved centroid tables
+    (float32 master [tile of 64][d/4][64][4], 16-bit search copy [tile of 64][d/8][64][8])."""
+    def k(s_, d): return s_ * 128 + d
+    def v(s_, d): return 2048 + s_ * 128 + d
+    idx = [f(s_, d) for f in (k, v) for s_ in range(16) for d in range(128)]
+    assert sorted(idx) == list(range(4096))
+    def r(j, d): return ((j >> 6) * 32 + (d >> 2)) * 256 + (j & 63) * 4 + (d & 3)
+    def rq(j, d): return ((j >> 6) * 16 + (d >> 3)) * 512 + (j & 63) * 8 + (d & 7)
+    for f in (r, rq):
+        idx = [f(j, d) for j in range(192) for d in range(128)]
+        assert sorted(idx) == list(range(192 * 128))
