@@ -23,10 +23,12 @@
  *               (a split that has no room leaves its cluster flagged); dynakv_export_state
  *               reports the word.
  *   numerics  - decisions (nearest cluster, split trigger, 2-means sides, cluster order) are taken
- *               on float64 values accumulated left to right over the coordinate index, so that
- *               they can be reproduced exactly; cluster scores are rounded to float32 before they
- *               are ordered; ties go to the lowest index.  Attention uses matrix cores with
- *               float32 accumulation.
+ *               on float64 values summed in one fixed order (over the 128 coordinates: blocks of 8
+ *               consecutive coordinates accumulated left to right from zero with one fused
+ *               multiply-add per term, then the 16 block sums added left to right; over members:
+ *               in ascending position), so that they can be reproduced exactly; cluster scores
+ *               are rounded to float32 before they are ordered; ties go to the lowest index.
+ *               Attention uses matrix cores with float32 accumulation.
  */
 #ifndef DYNAKV_H
 #define DYNAKV_H
