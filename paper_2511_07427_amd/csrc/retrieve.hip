@@ -825,12 +825,12 @@ __global__ __launch_bounds__(NW * 64) void gather_attend_kernel(View v, const vo
   }
 }
 
-// Whole retrieval of one unit in one workgroup (used when there is at least one unit per compute unit):
-// scores -> LDS, sort and budget cut in LDS, gather list in LDS, then the same page loop and merge as
-// gather_attend_kernel.  Saves two launches and every trip through the workspace between the phases.
+// Whole retrieval of one unit in one workgroup (16-bit storage, at most kFusedClusters clusters and 8 query heads
+// per unit; at every unit count, because the step is bound by dependent round trips rather than by the number of
+// busy compute units): scores -> LDS, budget cut in LDS, gather list in LDS, then the same page loop and merge
+// as gather_attend_kernel.  Saves two launches and every trip through the workspace between the phases.
 constexpr int kFusedList = 2048;       // gather-list entries it keeps in LDS (longer lists are read from the workspace)
 
-//
 // With APPEND the same pass over the centroid table also finds the cluster nearest to the step's new key
 // (one more accumulator per centroid), and the append itself is committed after the selection (the gather list is
 // fixed by then and the append touches nothing it names): a decode step then reads the table once instead of
