@@ -62,6 +62,9 @@ def main():
     ap.add_argument("--units", type=int, default=0,
                     help="run UNITS units instead of the configuration's own count: fewer = its first units; more = "
                          "further independent draws of the same shape (more layers or sequences), labelled as such")
+    ap.add_argument("--max-cluster-factor", type=int, default=0,
+                    help="max_clusters = FACTOR x the initial cluster count instead of the configuration's own factor "
+                         "(long runs whose drift needs more clusters; above 4096 clusters the separate kernels run)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="skip the HIP events around the dominant kernel")
     a = ap.parse_args()
@@ -78,6 +81,8 @@ def main():
     own_units = spec.n_units
     if a.units:
         spec = spec.scaled(n_units=a.units)
+    if a.max_cluster_factor:
+        spec = spec.scaled(max_cluster_factor=a.max_cluster_factor)
     T = a.warmup + a.steps
     U, G, d = spec.n_units, spec.group_size, spec.head_dim
     dev = torch.device("cuda:0")
@@ -170,9 +175,9 @@ def main():
         "ms_per_step": dt / a.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": spec.dtype, "data": "synthetic",
         "config": {"workload": "%s: %d units (layers x KV heads)%s, G=%d, d=%d, %s, prefill %d, M0=%d clusters, "
-                               "token budget %d, decode steps %d..%d of a drifting %d-component mixture" %
+                               "token budget %d, at most %d clusters, decode steps %d..%d of a drifting %d-component mixture" %
                                (spec.name, U, "" if U == own_units else " INSTEAD OF THE CONFIGURATION'S %d" % own_units,
-                                G, d, spec.dtype, spec.prefill, spec.n_clusters_init, spec.budget,
+                                G, d, spec.dtype, spec.prefill, spec.n_clusters_init, spec.budget, spec.max_clusters,
                                 a.warmup, T, spec.n_components),
                    "kv_splits": ix and int(os.environ.get("DYNAKV_KV_SPLITS", "0")) or None},
         "roofline": roof,

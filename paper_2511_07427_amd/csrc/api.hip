@@ -92,6 +92,7 @@ size_t carve(const dynakv_config_t& c, char* base, View* out) {
   v.M = (int*)take(U * 4); v.N = (int*)take(U * 4); v.err = (int*)take(U * 4); v.tau = (double*)take(U * 8);
   v.nflag = (int*)take(U * 4); v.n_sel = (int*)take(U * 4); v.t_sel = (int*)take(U * 4); v.n_list = (int*)take(U * 4);
   v.ticket = (int*)take(U * 4); v.bump = (int*)take(U * 4); v.free_top = (int*)take(U * 4);
+  v.near_d = (double*)take(U * kNearBlocks * 8); v.near_j = (int*)take(U * kNearBlocks * 4);
   v.last_assign = (int*)take(U * 4); v.counters = (long long*)take(U * kCounters * 8);
   v.Rstride = r_stride(v.Mcap);
   v.R = (float*)take(U * v.Rstride * 4);
@@ -165,7 +166,7 @@ static dynakv_status_t retrieve_impl(dynakv_index_t* ix, const void* Q, int32_t 
                                      const void* kin, const void* vin, bool split, hipStream_t st, bool* appended) {
   const bool fused = retrieve_is_fused(ix->view);
   *appended = fused && kin;
-  if (!fused && launch_score_select(ix->view, Q, token_budget, st) != hipSuccess) return DYNAKV_EHIP;
+  if (!fused && launch_score_select(ix->view, Q, token_budget, kin, st) != hipSuccess) return DYNAKV_EHIP;
   const bool prof = ix->profiling && 2 * (ix->n_prof + 1) <= (int)ix->ev.size();
   if (prof && hipEventRecord(ix->ev[2 * ix->n_prof], st) != hipSuccess) return DYNAKV_EHIP;
   if (fused) {
@@ -198,14 +199,15 @@ dynakv_status_t dynakv_decode_step(dynakv_index_t* ix, const void* Q, int32_t to
   const dynakv_status_t rc = retrieve_impl(ix, Q, token_budget, out, lse, k_new, v_new, one_kernel, st, &appended);
   if (rc != DYNAKV_OK) return rc;
   if (appended && one_kernel) return DYNAKV_OK;
-  if (!appended && launch_append(ix->view, k_new, v_new, st) != hipSuccess) return DYNAKV_EHIP;
+  // (the score kernel of this step has already looked for the new key's nearest cluster)
+  if (!appended && launch_append(ix->view, k_new, v_new, true, st) != hipSuccess) return DYNAKV_EHIP;
   return launch_split(ix->view, st) == hipSuccess ? DYNAKV_OK : DYNAKV_EHIP;
 }
 
 dynakv_status_t dynakv_append(dynakv_index_t* ix, const void* k_new, const void* v_new, void* stream) {
   if (!ix || !k_new || !v_new) return DYNAKV_EINVAL;
   if (!ix->built) return DYNAKV_ESTATE;
-  return launch_append(ix->view, k_new, v_new, (hipStream_t)stream) == hipSuccess ? DYNAKV_OK : DYNAKV_EHIP;
+  return launch_append(ix->view, k_new, v_new, false, (hipStream_t)stream) == hipSuccess ? DYNAKV_OK : DYNAKV_EHIP;
 }
 
 dynakv_status_t dynakv_split(dynakv_index_t* ix, void* stream) {

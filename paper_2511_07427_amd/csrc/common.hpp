@@ -18,6 +18,7 @@ constexpr int kFusedClusters = 4096;            // clusters per unit the single-
 constexpr int kMaxSplitMembers = 4096;          // largest cluster the split kernel handles
 constexpr int kMaxKvSplits = 64;
 constexpr int kCounters = 8;
+constexpr int kNearBlocks = 32;                // blocks of 256 clusters in the largest index (8192 clusters)
 constexpr int kInlinePages = 8;                 // pages of a cluster found without walking its chain                // workgroups that share one unit's gathered pages
 
 typedef float f4 __attribute__((ext_vector_type(4)));
@@ -39,6 +40,8 @@ struct View {
   int* t_sel;        // [U] entries gathered by the last retrieval
   int* n_list;       // [U] entries in the gather list
   int* ticket;       // [U] arrival counter of the split-KV workgroups
+  double* near_d;    // [U][kNearBlocks] nearest cluster of the step's new key among clusters 256b .. 256b+255, left by
+  int* near_j;       //                  the score kernel of a whole decode step for the append that follows it
   int* bump;         // [U] pages handed out from the pool so far
   int* free_top;     // [U] entries on the free-page stack
   int* last_assign;  // [U]
@@ -433,12 +436,14 @@ __device__ inline void free_page(const View& v, int u, int page) {
 // ---- launchers (one per source file) ------------------------------------------------------------
 hipError_t launch_build_index(const View& v, const void* K, const void* V, int n_tokens, const int* init_idx,
                               int iters, void* workspace, size_t workspace_bytes, hipStream_t st);
-hipError_t launch_score_select(const View& v, const void* Q, int budget, hipStream_t st);
+// kin != null: the scores' pass over the centroid table also leaves, per block of 256 clusters, the cluster nearest
+// to the new key `kin` (near_d / near_j), for launch_append(.., prescanned = true).
+hipError_t launch_score_select(const View& v, const void* Q, int budget, const void* kin, hipStream_t st);
 bool retrieve_is_fused(const View& v);
 hipError_t launch_retrieve_fused(const View& v, const void* Q, int budget, float* out, float* lse, const void* kin,
                                  const void* vin, bool split, hipStream_t st);
 hipError_t launch_gather_attend(const View& v, const void* Q, float* out, float* lse, hipStream_t st);
-hipError_t launch_append(const View& v, const void* k, const void* val, hipStream_t st);
+hipError_t launch_append(const View& v, const void* k, const void* val, bool prescanned, hipStream_t st);
 hipError_t launch_split(const View& v, hipStream_t st);
 hipError_t launch_export(const View& v, const dynakv_state_t& dst, hipStream_t st);
 

@@ -11,7 +11,8 @@ namespace dynakv {
 namespace {
 
 // ------------------------------------------------------------------------------------------- append
-template <int DT>
+// PRE: the score kernel of the same step has left the nearest cluster of every block of 256 clusters.
+template <int DT, bool PRE>
 __global__ __launch_bounds__(256) void append_kernel(View v, const void* kin, const void* vin) {
   __shared__ AppendSmem a;
   __shared__ double sv[16];
@@ -21,7 +22,11 @@ __global__ __launch_bounds__(256) void append_kernel(View v, const void* kin, co
   const uint16_t* Rq = unit_Rq(v, u);
   f4 row[8];
   uint4 hrow[1][4];
-  if ((size_t)(tid | 63) * kHeadDim < v.Rstride) {    // requested before anything else
+  double best = __builtin_inf();
+  int arg = -1;
+  if constexpr (PRE) {                                  // requested before anything else
+    if (tid < kNearBlocks) { best = v.near_d[(size_t)u * kNearBlocks + tid]; arg = v.near_j[(size_t)u * kNearBlocks + tid]; }
+  } else if ((size_t)(tid | 63) * kHeadDim < v.Rstride) {
     const int js[1] = {tid};
     if constexpr (DT == DYNAKV_F32) load_centroid_head(R, tid, row);
     else load_search_head<1>(Rq, js, hrow);
@@ -33,27 +38,29 @@ __global__ __launch_bounds__(256) void append_kernel(View v, const void* kin, co
   }
   if (tid < kHeadDim) a.kd[tid] = (double)load_elem(kin, (size_t)u * kHeadDim + tid, v.dtype);
   __syncthreads();
-  // nearest centre (squared Euclidean distance); lane = cluster, 16 contiguous bytes per lane and load
-  double best = __builtin_inf();
-  int arg = -1;
-  for (int j = tid; j < M; j += 256) {
-    const int js[1] = {j};
-    double dist[1][1];
-    if constexpr (DT == DYNAKV_F32) {
-      if (j != tid) load_centroid_head(R, j, row);
-      centroid_sums<1>(R, j, row, dist[0], [&](int d, float rv, double (&acc)[1]) __attribute__((always_inline)) {
-        const double t = a.kd[d] - (double)rv;
-        acc[0] = fma(t, t, acc[0]);
-      });
-    } else {
-      if (j != tid) load_search_head<1>(Rq, js, hrow);
-      search_sums<1, 1, DT == DYNAKV_BF16>(Rq, js, hrow, dist,
-          [&](int d, const float (&x)[1], double (&acc)[1][1]) __attribute__((always_inline)) {
-        const double t = a.kd[d] - (double)x[0];
-        acc[0][0] = fma(t, t, acc[0][0]);
-      });
+  if constexpr (PRE) {
+    if (tid * 256 >= M) arg = -1;                       // blocks past the last cluster hold nothing of this step
+  } else {
+    // nearest centre (squared Euclidean distance); lane = cluster, 16 contiguous bytes per lane and load
+    for (int j = tid; j < M; j += 256) {
+      const int js[1] = {j};
+      double dist[1][1];
+      if constexpr (DT == DYNAKV_F32) {
+        if (j != tid) load_centroid_head(R, j, row);
+        centroid_sums<1>(R, j, row, dist[0], [&](int d, float rv, double (&acc)[1]) __attribute__((always_inline)) {
+          const double t = a.kd[d] - (double)rv;
+          acc[0] = fma(t, t, acc[0]);
+        });
+      } else {
+        if (j != tid) load_search_head<1>(Rq, js, hrow);
+        search_sums<1, 1, DT == DYNAKV_BF16>(Rq, js, hrow, dist,
+            [&](int d, const float (&x)[1], double (&acc)[1][1]) __attribute__((always_inline)) {
+          const double t = a.kd[d] - (double)x[0];
+          acc[0][0] = fma(t, t, acc[0][0]);
+        });
+      }
+      if (dist[0][0] < best || arg < 0) { best = dist[0][0]; arg = j; }
     }
-    if (dist[0][0] < best || arg < 0) { best = dist[0][0]; arg = j; }
   }
   const int j = block_argmin<256>(best, arg, sv, si);
   const AppendFetch f = append_fetch(v, u, j);
@@ -145,10 +152,16 @@ __global__ __launch_bounds__(1024) void export_kernel(View v, dynakv_state_t o) 
 
 }  // namespace
 
-hipError_t launch_append(const View& v, const void* k, const void* val, hipStream_t st) {
-  if (v.dtype == DYNAKV_F32) append_kernel<DYNAKV_F32><<<v.U, 256, 0, st>>>(v, k, val);
-  else if (v.dtype == DYNAKV_F16) append_kernel<DYNAKV_F16><<<v.U, 256, 0, st>>>(v, k, val);
-  else append_kernel<DYNAKV_BF16><<<v.U, 256, 0, st>>>(v, k, val);
+hipError_t launch_append(const View& v, const void* k, const void* val, bool prescanned, hipStream_t st) {
+#define DYNAKV_APPEND(DT)                                                        \
+  do {                                                                           \
+    if (prescanned) append_kernel<DT, true><<<v.U, 256, 0, st>>>(v, k, val);     \
+    else append_kernel<DT, false><<<v.U, 256, 0, st>>>(v, k, val);               \
+  } while (0)
+  if (v.dtype == DYNAKV_F32) DYNAKV_APPEND(DYNAKV_F32);
+  else if (v.dtype == DYNAKV_F16) DYNAKV_APPEND(DYNAKV_F16);
+  else DYNAKV_APPEND(DYNAKV_BF16);
+#undef DYNAKV_APPEND
   return hipGetLastError();
 }
 hipError_t launch_split(const View& v, hipStream_t st) {

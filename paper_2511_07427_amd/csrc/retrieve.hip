@@ -17,9 +17,15 @@ namespace {
 
 // ------------------------------------------------------------------------------------------- scores
 // Lane = cluster: the centroid table is lane-interleaved, so every load below is 1 KB contiguous per wavefront.
-template <int GP, int DT>
-__global__ __launch_bounds__(256) void score_kernel(View v, const void* Q) {
+// NEAR: the same pass also finds, per workgroup (256 clusters), the cluster nearest to the step's new key (one
+// more accumulator per centroid, the arithmetic of the append kernel's own scan) and leaves it in near_d / near_j.
+template <int GP, int DT, bool NEAR>
+__global__ __launch_bounds__(256) void score_kernel(View v, const void* Q, const void* kin) {
+  constexpr int NA = GP + (NEAR ? 1 : 0);
   __shared__ double qs[kHeadDim][GP];
+  __shared__ double kd[NEAR ? kHeadDim : 1];
+  __shared__ double am_v[16];
+  __shared__ int am_i[16];
   const int u = blockIdx.y, tid = threadIdx.x;
   const int j = blockIdx.x * 256 + tid;
   const float* R = unit_R(v, u);
@@ -43,32 +49,55 @@ __global__ __launch_bounds__(256) void score_kernel(View v, const void* Q) {
     const int g = t / kHeadDim, d = t % kHeadDim;
     qs[d][g] = g < v.G ? (double)load_elem(Q, ((size_t)u * v.G + g) * kHeadDim + d, v.dtype) : 0.0;
   }
+  if constexpr (NEAR)
+    if (tid < kHeadDim) kd[tid] = (double)load_elem(kin, (size_t)u * kHeadDim + tid, v.dtype);
   __syncthreads();
-  if ((j & ~63) >= M) return;                       // whole wavefront past the last cluster
-  double acc[GP];
-  if constexpr (DT == DYNAKV_F32) {
-    centroid_sums<GP>(R, j, row, acc, [&](int d, float rv, double (&a)[GP]) __attribute__((always_inline)) {
-      const double rd = (double)rv;
+  const bool live = (j & ~63) < M;                  // false: whole wavefront past the last cluster
+  if (!NEAR && !live) return;
+  double acc[NA];
+  if (live) {
+    if constexpr (DT == DYNAKV_F32) {
+      centroid_sums<NA>(R, j, row, acc, [&](int d, float rv, double (&a)[NA]) __attribute__((always_inline)) {
+        const double rd = (double)rv;
 #pragma unroll
-      for (int g = 0; g < GP; ++g) a[g] = fma(qs[d][g], rd, a[g]);
-    });
-  } else {
-    double acc1[1][GP];
-    search_sums<GP, 1, DT == DYNAKV_BF16>(Rq, js, hrow, acc1,
-        [&](int d, const float (&x)[1], double (&a)[1][GP]) __attribute__((always_inline)) {
-      const double rd = (double)x[0];
+        for (int g = 0; g < GP; ++g) a[g] = fma(qs[d][g], rd, a[g]);
+        if constexpr (NEAR) {
+          const double t = kd[d] - rd;
+          a[GP] = fma(t, t, a[GP]);
+        }
+      });
+    } else {
+      double acc1[1][NA];
+      search_sums<NA, 1, DT == DYNAKV_BF16>(Rq, js, hrow, acc1,
+          [&](int d, const float (&x)[1], double (&a)[1][NA]) __attribute__((always_inline)) {
+        const double rd = (double)x[0];
 #pragma unroll
-      for (int g = 0; g < GP; ++g) a[0][g] = fma(qs[d][g], rd, a[0][g]);
-    });
+        for (int g = 0; g < GP; ++g) a[0][g] = fma(qs[d][g], rd, a[0][g]);
+        if constexpr (NEAR) {
+          const double t = kd[d] - rd;
+          a[0][GP] = fma(t, t, a[0][GP]);
+        }
+      });
 #pragma unroll
-    for (int g = 0; g < GP; ++g) acc[g] = acc1[0][g];
+      for (int a = 0; a < NA; ++a) acc[a] = acc1[0][a];
+    }
   }
-  if (j >= M) return;
-  double red = acc[0];
+  const bool mine = live && j < M;
+  if (mine) {
+    double red = acc[0];
 #pragma unroll
-  for (int g = 1; g < GP; ++g)
-    if (g < v.G) red = v.group_reduce == DYNAKV_GROUP_MAX ? fmax(red, acc[g]) : red + acc[g];
-  v.score[(size_t)u * v.Mcap + j] = (float)(red * v.scale_d);
+    for (int g = 1; g < GP; ++g)
+      if (g < v.G) red = v.group_reduce == DYNAKV_GROUP_MAX ? fmax(red, acc[g]) : red + acc[g];
+    v.score[(size_t)u * v.Mcap + j] = (float)(red * v.scale_d);
+  }
+  if constexpr (NEAR) {
+    const double dist = mine ? acc[NA - 1] : 0.0;
+    const int jw = block_argmin<256>(dist, mine ? j : -1, am_v, am_i);
+    if (mine && j == jw) {
+      v.near_d[(size_t)u * kNearBlocks + blockIdx.x] = dist;
+      v.near_j[(size_t)u * kNearBlocks + blockIdx.x] = j;
+    }
+  }
 }
 
 // ------------------------------------------------------------------------------------------- selection
@@ -1153,18 +1182,25 @@ hipError_t launch_retrieve_fused(const View& v, const void* Q, int budget, float
   return hipGetLastError();
 }
 
-hipError_t launch_score_select(const View& v, const void* Q, int budget, hipStream_t st) {
+hipError_t launch_score_select(const View& v, const void* Q, int budget, const void* kin, hipStream_t st) {
   const dim3 grid((v.Mcap + 255) / 256, v.U);
-#define DYNAKV_SCORE(DT)                                                \
-  do {                                                                  \
-    if (v.G <= 4) score_kernel<4, DT><<<grid, 256, 0, st>>>(v, Q);      \
-    else if (v.G <= 8) score_kernel<8, DT><<<grid, 256, 0, st>>>(v, Q); \
-    else score_kernel<16, DT><<<grid, 256, 0, st>>>(v, Q);              \
+  static_assert(kMaxClusters <= kNearBlocks * 256, "one near_d / near_j entry per workgroup of the score kernel");
+#define DYNAKV_SCORE_G(GP, DT)                                                          \
+  do {                                                                                  \
+    if (kin) score_kernel<GP, DT, true><<<grid, 256, 0, st>>>(v, Q, kin);               \
+    else score_kernel<GP, DT, false><<<grid, 256, 0, st>>>(v, Q, nullptr);              \
+  } while (0)
+#define DYNAKV_SCORE(DT)                               \
+  do {                                                 \
+    if (v.G <= 4) DYNAKV_SCORE_G(4, DT);               \
+    else if (v.G <= 8) DYNAKV_SCORE_G(8, DT);          \
+    else DYNAKV_SCORE_G(16, DT);                       \
   } while (0)
   if (v.dtype == DYNAKV_F32) DYNAKV_SCORE(DYNAKV_F32);
   else if (v.dtype == DYNAKV_F16) DYNAKV_SCORE(DYNAKV_F16);
   else DYNAKV_SCORE(DYNAKV_BF16);
 #undef DYNAKV_SCORE
+#undef DYNAKV_SCORE_G
   select_kernel<<<v.U, 1024, 0, st>>>(v, budget);
   return hipGetLastError();
 }
