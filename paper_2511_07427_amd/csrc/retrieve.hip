@@ -250,6 +250,52 @@ __device__ inline int select_sorted(const View& v, int u, int M, int budget, con
 // (or the best cluster alone, cut to the budget, if even that one does not fit).  Records the active set and
 // writes the gather list in that order.  Returns the number of gather-list entries.
 //
+// Puts the positions 0 .. cut-1 of the candidate keys ck into 256 bins by the leading bits in which the keys'
+// scores differ (counting sort, bins in descending order) and returns the shift that yields a key's bin:
+// ((key >> 16) >> shift) & 255.  hist[0..255]: bin sizes, [256..511]: candidates in higher bins, [512..767]: fill
+// counters; misc[0..1]: scratch; lst: the positions in bin order.  Whole workgroup; kept out of line, it is rarely
+// needed.
+template <int NT>
+__device__ __noinline__ int bin_candidates(int* hist, int* misc, int* lst, const unsigned long long* ck, int cut) {
+  const int tid = threadIdx.x, lane = tid & 63;
+  if (tid == 0) { misc[0] = -1; misc[1] = 0; }
+  for (int i = tid; i < 768; i += NT) hist[i] = 0;
+  __syncthreads();
+  uint32_t lo = 0xFFFFFFFFu, hi = 0u;
+  for (int p = tid; p < cut; p += NT) {
+    const uint32_t k = (uint32_t)(ck[p] >> 16);
+    lo = min(lo, k); hi = max(hi, k);
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) { lo = min(lo, (uint32_t)__shfl_xor((int)lo, o)); hi = max(hi, (uint32_t)__shfl_xor((int)hi, o)); }
+  if (lane == 0) { atomicMin((unsigned*)&misc[0], lo); atomicMax((unsigned*)&misc[1], hi); }
+  __syncthreads();
+  const uint32_t differ = (uint32_t)misc[0] ^ (uint32_t)misc[1];
+  const int shift = differ ? max(31 - __clz((int)differ) - 7, 0) : 0;
+  for (int p = tid; p < cut; p += NT) atomicAdd(&hist[((uint32_t)(ck[p] >> 16) >> shift) & 255u], 1);
+  __syncthreads();
+  if (tid < 64) {                      // lane l owns the bins 255 - 4l .. 252 - 4l, highest first
+    int hv[4], t = 0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) { hv[k] = hist[255 - (4 * lane + k)]; t += hv[k]; }
+    int inc = t;
+    for (int o = 1; o < 64; o <<= 1) {
+      const int y = __shfl_up(inc, o);
+      if (lane >= o) inc += y;
+    }
+    int run = inc - t;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) { hist[256 + 255 - (4 * lane + k)] = run; run += hv[k]; }
+  }
+  __syncthreads();
+  for (int p = tid; p < cut; p += NT) {
+    const int d = ((uint32_t)(ck[p] >> 16) >> shift) & 255u;
+    lst[hist[256 + d] + atomicAdd(&hist[512 + d], 1)] = p;
+  }
+  __syncthreads();
+  return shift;
+}
+
 // Only the selected clusters are ordered.  The score at which the running size first exceeds the budget is
 // found by a radix search over the 32-bit orderable scores (four passes of size-weighted 256-bin histograms);
 // everything above it is selected, equal scores are taken by ascending id while they fit.  Each selected
@@ -388,6 +434,16 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
   constexpr int PER = (kCountMax + NT - 1) / NT;
   int tpc = 1, tsh = 0;
   while (tpc < 8 && cut * tpc * 2 <= NT) { tpc <<= 1; ++tsh; }
+  // Many selected clusters: counting against all of them costs cut^2 LDS reads; they are binned first
+  // (bin_candidates), and a cluster's rank is the number of clusters in higher bins plus those of its own bin that
+  // precede it (the sizes in s.sw, which s.srt may alias, are not read any more).
+  const bool binned = cut > 256;
+  int* const lst = s.srt;
+  int bin_shift = 0;
+  if (__builtin_expect(binned, 0)) {
+    tpc = 1; tsh = 0;
+    bin_shift = bin_candidates<NT>(s.hist, s.misc, lst, ck, cut);
+  }
   const int sub = tid & (tpc - 1);
   const int chunk = ((cut + tpc - 1) / tpc + 7) & ~7;
   int rk[PER], idw[PER], wt[PER], pg[PER][kInlinePages];
@@ -410,13 +466,20 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
         }
       }
       int rank = 0;
-      const int q0 = r == 0 ? sub * chunk : 0, q1 = r == 0 ? min(cut, q0 + chunk) : cut;
-      for (int qb = q0; qb < q1; qb += 8) {           // eight candidates per round trip to LDS
-        unsigned long long o[8];
+      if (__builtin_expect(binned, 0)) {
+        const int d = ((uint32_t)(my >> 16) >> bin_shift) & 255u;
+        const int b0 = s.hist[256 + d], b1 = b0 + s.hist[d];
+        rank = b0;
+        for (int q = b0; q < b1; ++q) rank += ck[lst[q]] > my ? 1 : 0;
+      } else {
+        const int q0 = r == 0 ? sub * chunk : 0, q1 = r == 0 ? min(cut, q0 + chunk) : cut;
+        for (int qb = q0; qb < q1; qb += 8) {           // eight candidates per round trip to LDS
+          unsigned long long o[8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) o[i] = ck[min(qb + i, cut - 1)];
+          for (int i = 0; i < 8; ++i) o[i] = ck[min(qb + i, cut - 1)];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) rank += (qb + i < q1 && o[i] > my) ? 1 : 0;
+          for (int i = 0; i < 8; ++i) rank += (qb + i < q1 && o[i] > my) ? 1 : 0;
+        }
       }
       if (r == 0)
         for (int o = 1; o < tpc; o <<= 1) rank += __shfl_xor(rank, o);
@@ -505,10 +568,14 @@ __global__ __launch_bounds__(1024) void select_kernel(View v, int budget) {
   const int M = v.M[u];
   int Mpad = 2;
   while (Mpad < M) Mpad <<= 1;
-  for (int i = tid; i < Mpad; i += 1024) skey[i] = i < M ? orderable(v.score[(size_t)u * v.Mcap + i]) : 0u;
+  __shared__ int ssz[kMaxClusters];                 // cluster sizes: every pass of the selection reads them
+  for (int i = tid; i < Mpad; i += 1024) {
+    skey[i] = i < M ? orderable(v.score[(size_t)u * v.Mcap + i]) : 0u;
+    if (i < M) ssz[i] = v.csz[(size_t)u * v.Mcap + i];
+  }
   __syncthreads();
   __shared__ int srt[kCountMax];
-  const SelectLds s{skey, nullptr, region, hist, srt, sm, misc, nullptr, 0};
+  const SelectLds s{skey, ssz, region, hist, srt, sm, misc, nullptr, 0};
   select_phase<1024>(v, u, M, budget, s);
 }
 
