@@ -199,15 +199,16 @@ dynakv_status_t dynakv_decode_step(dynakv_index_t* ix, const void* Q, int32_t to
   const dynakv_status_t rc = retrieve_impl(ix, Q, token_budget, out, lse, k_new, v_new, one_kernel, st, &appended);
   if (rc != DYNAKV_OK) return rc;
   if (appended && one_kernel) return DYNAKV_OK;
-  // (the score kernel of this step has already looked for the new key's nearest cluster)
-  if (!appended && launch_append(ix->view, k_new, v_new, true, st) != hipSuccess) return DYNAKV_EHIP;
+  // separate kernels: the score kernel of this step has already looked for the new key's nearest cluster, and the
+  // splits follow the append in its launch
+  if (!appended) return launch_append(ix->view, k_new, v_new, true, true, st) == hipSuccess ? DYNAKV_OK : DYNAKV_EHIP;
   return launch_split(ix->view, st) == hipSuccess ? DYNAKV_OK : DYNAKV_EHIP;
 }
 
 dynakv_status_t dynakv_append(dynakv_index_t* ix, const void* k_new, const void* v_new, void* stream) {
   if (!ix || !k_new || !v_new) return DYNAKV_EINVAL;
   if (!ix->built) return DYNAKV_ESTATE;
-  return launch_append(ix->view, k_new, v_new, false, (hipStream_t)stream) == hipSuccess ? DYNAKV_OK : DYNAKV_EHIP;
+  return launch_append(ix->view, k_new, v_new, false, false, (hipStream_t)stream) == hipSuccess ? DYNAKV_OK : DYNAKV_EHIP;
 }
 
 dynakv_status_t dynakv_split(dynakv_index_t* ix, void* stream) {

@@ -443,7 +443,8 @@ bool retrieve_is_fused(const View& v);
 hipError_t launch_retrieve_fused(const View& v, const void* Q, int budget, float* out, float* lse, const void* kin,
                                  const void* vin, bool split, hipStream_t st);
 hipError_t launch_gather_attend(const View& v, const void* Q, float* out, float* lse, hipStream_t st);
-hipError_t launch_append(const View& v, const void* k, const void* val, bool prescanned, hipStream_t st);
+// split: the unit's due splits follow in the same launch.
+hipError_t launch_append(const View& v, const void* k, const void* val, bool prescanned, bool split, hipStream_t st);
 hipError_t launch_split(const View& v, hipStream_t st);
 hipError_t launch_export(const View& v, const dynakv_state_t& dst, hipStream_t st);
 

@@ -12,11 +12,21 @@ namespace {
 
 // ------------------------------------------------------------------------------------------- append
 // PRE: the score kernel of the same step has left the nearest cluster of every block of 256 clusters.
-template <int DT, bool PRE>
+// SPLIT: the unit's due splits follow in the same launch (the rest of a decode step on the separate-kernel path).
+template <bool ON>
+struct SplitLds {
+  alignas(16) unsigned char raw[kSplitRaw];
+  SplitWork wk;
+};
+template <>
+struct SplitLds<false> {};
+template <int DT, bool PRE, bool SPLIT>
 __global__ __launch_bounds__(256) void append_kernel(View v, const void* kin, const void* vin) {
+  static_assert(kSplitThreads == 256, "split_unit is run by this kernel's whole workgroup");
   __shared__ AppendSmem a;
   __shared__ double sv[16];
   __shared__ int si[16];
+  __shared__ SplitLds<SPLIT> sp;
   const int u = blockIdx.x, tid = threadIdx.x;
   const float* R = unit_R(v, u);
   const uint16_t* Rq = unit_Rq(v, u);
@@ -32,8 +42,12 @@ __global__ __launch_bounds__(256) void append_kernel(View v, const void* kin, co
     else load_search_head<1>(Rq, js, hrow);
   }
   const int M = v.M[u], N = v.N[u];
-  if (N >= v.Ncap || M <= 0) {
+  if (N >= v.Ncap || M <= 0) {                          // refused (workgroup-uniform); due splits still run
     if (tid == 0) v.err[u] |= DYNAKV_ERR_TOKENS;
+    if constexpr (SPLIT) {
+      __syncthreads();
+      split_unit<DT>(v, u, sp.raw, sp.wk, false);
+    }
     return;
   }
   if (tid < kHeadDim) a.kd[tid] = (double)load_elem(kin, (size_t)u * kHeadDim + tid, v.dtype);
@@ -65,6 +79,10 @@ __global__ __launch_bounds__(256) void append_kernel(View v, const void* kin, co
   const int j = block_argmin<256>(best, arg, sv, si);
   const AppendFetch f = append_fetch(v, u, j);
   append_commit<256>(v, u, j, M, N, kin, vin, a, f);
+  if constexpr (SPLIT) {
+    __syncthreads();                                    // the append's record is in place for the whole workgroup
+    split_unit<DT>(v, u, sp.raw, sp.wk, false);
+  }
 }
 
 // ------------------------------------------------------------------------------------------- split
@@ -152,11 +170,13 @@ __global__ __launch_bounds__(1024) void export_kernel(View v, dynakv_state_t o) 
 
 }  // namespace
 
-hipError_t launch_append(const View& v, const void* k, const void* val, bool prescanned, hipStream_t st) {
-#define DYNAKV_APPEND(DT)                                                        \
-  do {                                                                           \
-    if (prescanned) append_kernel<DT, true><<<v.U, 256, 0, st>>>(v, k, val);     \
-    else append_kernel<DT, false><<<v.U, 256, 0, st>>>(v, k, val);               \
+hipError_t launch_append(const View& v, const void* k, const void* val, bool prescanned, bool split, hipStream_t st) {
+#define DYNAKV_APPEND(DT)                                                                    \
+  do {                                                                                       \
+    if (prescanned && split) append_kernel<DT, true, true><<<v.U, 256, 0, st>>>(v, k, val);  \
+    else if (prescanned) append_kernel<DT, true, false><<<v.U, 256, 0, st>>>(v, k, val);     \
+    else if (split) append_kernel<DT, false, true><<<v.U, 256, 0, st>>>(v, k, val);          \
+    else append_kernel<DT, false, false><<<v.U, 256, 0, st>>>(v, k, val);                    \
   } while (0)
   if (v.dtype == DYNAKV_F32) DYNAKV_APPEND(DYNAKV_F32);
   else if (v.dtype == DYNAKV_F16) DYNAKV_APPEND(DYNAKV_F16);
