@@ -25,8 +25,8 @@ MFMA_PEAK_TFLOPS = 2500.0      # dense fp16/bf16, published
 # the same counter reads for the float32 -> float16 copy of the 134 217 728-element prefill keys (512 MiB read,
 # 256 MiB written): FETCH_SIZE reads 262 166 KiB for it (factor 2.000), WRITE_SIZE 262 144 KiB (factor 1.000).
 # Only valid for exactly that workload; any other arguments report null.
-PMC_TRAFFIC = {("llama3_8b", 8192, 64, 0): {"fetch_kib": 107229.4, "fetch_scale": 524288.0 / 262166.25,
-                                            "write_kib": 7809.2, "write_scale": 1.0}}
+PMC_TRAFFIC = {("llama3_8b", 8192, 64, 0): {"fetch_kib": 107346.2, "fetch_scale": 524288.0 / 262165.9,
+                                            "write_kib": 7669.1, "write_scale": 1.0}}
 
 
 def cpu_baseline(spec, n_units, steps, budget):
