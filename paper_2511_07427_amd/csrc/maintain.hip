@@ -1,9 +1,11 @@
 // Decode, second half of a step (Algorithm 1, decode block; Section 4.2):
-//   append_kernel - nearest cluster, UpdateVar, threshold test, AddEntry + UpdateStats or buffer + flag
+//   append_kernel - nearest cluster (its own scan of the table, or the per-block results the score kernel of a
+//                   whole-step call left), UpdateVar, threshold test, AddEntry + UpdateStats or buffer + flag;
+//                   in a whole-step call the due splits follow in the same launch
 //   split_kernel  - delayed splits of flagged clusters in the active set, then the forced split
 //   export_kernel - snapshot of the index for tests
 // One workgroup per unit; each unit's record is touched by that workgroup only.  All decisions are
-// taken on float64 values accumulated left to right, ties to the lowest index.
+// taken on float64 values summed in the fixed order of common.hpp, ties to the lowest index.
 #include "split.hpp"
 
 namespace dynakv {
