@@ -49,7 +49,11 @@ int pow2_floor(int x) {
 // (measured on the 8-unit configuration: 4 workgroups per unit beat 1, 2, 8, 16 and 32; with 112 and 128 units
 // 1 beats 2 and 3).  DYNAKV_KV_SPLITS / DYNAKV_ATT_WAVES override for tuning runs.
 void plan_attention(const dynakv_config_t& c, int* S, int* NW) {
-  int s = (32 + c.n_units - 1) / c.n_units;
+  // split-KV (separate kernels): measured at 16384 + tokens per unit, budget 4096, with 1..128 units: 8 workgroups
+  // per unit up to 32 units, then 256 / units (e.g. 16 units: 10.8k steps/s with 8, 9.5k with 2; 64 units: 7.6k with 4,
+  // 6.1k with 1; more than 8 lose to the merge of the partial results)
+  int s = (256 + c.n_units - 1) / c.n_units;
+  if (s > 8) s = 8;
   // where the single-kernel retrieval can run (see retrieve_is_fused) it beats split-KV at every unit count:
   // measured 16.5k against 15.5k steps/s with 8 units, 15.1k against 13.1k with 24 (configuration 2's shape)
   if (c.dtype != DYNAKV_F32 && c.max_clusters <= kFusedClusters && c.group_size <= 8) s = 1;
