@@ -135,7 +135,9 @@ dynakv_status_t dynakv_split(dynakv_index_t* index, void* stream);
  * step is a chain of short dependent phases: with 16-bit storage, at most 4096 clusters and at most 8 query
  * heads per unit the whole step is ONE kernel launch that reads the table once, commits the
  * append before it streams the selected pages, and prepares the due splits while it streams them.
- * Arguments as in the three calls. */
+ * Otherwise (float32 storage, more clusters, more query heads) it is four launches instead of the five of
+ * the three calls: the score kernel also finds the new key's nearest cluster, and the splits run in the
+ * append's launch.  Arguments as in the three calls. */
 dynakv_status_t dynakv_decode_step(dynakv_index_t* index, const void* Q, int32_t token_budget, float* out,
                                    float* lse, const void* k_new, const void* v_new, void* stream);
 
