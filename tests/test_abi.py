@@ -82,3 +82,13 @@ def test_page_and_centroid_table_layouts_are_bijections():
     for f in (r, rq):
         idx = [f(j, d) for j in range(192) for d in range(128)]
         assert sorted(idx) == list(range(192 * 128))
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU's throughput; asked for more it says so and exits before touching a device."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""
