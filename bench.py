@@ -37,7 +37,7 @@ def cpu_baseline(spec, n_units, steps, budget):
     w = generate(spec, units=range(n_units), steps=steps)
     o = Oracle(OracleConfig(n_units, spec.group_size, spec.head_dim, spec.n_clusters_init, spec.max_clusters,
                             spec.prefill + steps, spec.kmeans_iters, spec.buffer_max, 0, spec.var_alpha,
-                            spec.size_factor, 0.0, 0, dtype=spec.dtype))
+                            spec.size_factor, 0.0, dtype=spec.dtype))
     t0 = time.perf_counter()
     o.build_index(w["K0"], w["V0"], w["init_idx"])
     t1 = time.perf_counter()

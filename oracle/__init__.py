@@ -38,7 +38,7 @@ class _Cfg(C.Structure):
     _fields_ = [(k, C.c_int32) for k in ("n_units", "group_size", "head_dim", "n_clusters_init", "max_clusters",
                                           "max_tokens", "kmeans_iters", "buffer_max", "group_reduce")] + \
                [(k, C.c_float) for k in ("var_alpha", "size_factor", "softmax_scale")] + \
-               [("dtype", C.c_int32), ("seed", C.c_uint64)]
+               [(k, C.c_int32) for k in ("dtype", "search_copy", "score_round", "update_mode")]
 
 
 @dataclass
@@ -55,8 +55,10 @@ class OracleConfig:
     var_alpha: float = 0.0
     size_factor: float = 0.0
     softmax_scale: float = 0.0
-    seed: int = 0
-    dtype: str = "f32"          # storage type of K, V, Q ("f32" | "f16" | "bf16"): fixes the type of the search copy
+    dtype: str = "f32"          # storage type of K, V, Q ("f32" | "f16" | "bf16")
+    search_copy: int = 0        # 0: searches read the centroids rounded to the storage type; 1: the float32 means
+    score_round: int = 0        # 1: cluster scores are rounded to float32 before they are ordered
+    update_mode: int = 0        # 0: Algorithm 1; 1: static update (never flag, never split)
 
 
 _lib = None
@@ -86,6 +88,11 @@ def _load():
         lib.oracle_get_selected.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_int]
         lib.oracle_get_gather.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_int]
         lib.oracle_get_scores.argtypes = [C.c_void_p, C.c_int, C.c_void_p]
+        lib.oracle_get_kmeans_margins.argtypes = [C.c_void_p, C.c_int, C.c_void_p]
+        lib.oracle_get_kv.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
+        lib.oracle_last_split_rounds.argtypes = [C.c_void_p, C.c_int]
+        lib.oracle_import_unit.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_int] + \
+            [C.c_void_p] * 7 + [C.c_double, C.c_int, C.c_void_p]
         lib.oracle_get_diagnostics.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
         _lib = lib
     return _lib
@@ -118,22 +125,37 @@ class Oracle:
         return self._lib.oracle_threads_used(self._h)
 
     # ---- the four calls -------------------------------------------------------------------
-    def build_index(self, K, V, init_idx=None):
-        """K, V: [U, N0, d].  Returns the k-means objective per unit and iteration, [U, iters]."""
+    def build_index(self, K, V, init_idx):
+        """K, V: [U, N0, d]; init_idx [U, M0]: positions of the M0 distinct keys that start as centres.
+        Returns the k-means objective per unit and iteration, [U, iters]."""
         K, kp = _f32(K)
         V, vp = _f32(V)
         U, N0, d = K.shape
         assert (U, d) == (self.cfg.n_units, self.cfg.head_dim) and V.shape == K.shape
-        ip = None
-        if init_idx is not None:
-            init_idx = np.ascontiguousarray(init_idx, dtype=np.int32)
-            assert init_idx.shape == (U, self.cfg.n_clusters_init)
-            ip = init_idx.ctypes.data
+        init_idx = np.ascontiguousarray(init_idx, dtype=np.int32)
+        assert init_idx.shape == (U, self.cfg.n_clusters_init)
         J = np.zeros((U, self.cfg.kmeans_iters), dtype=np.float64)
-        rc = self._lib.oracle_build_index(self._h, kp, vp, N0, ip, J.ctypes.data)
+        rc = self._lib.oracle_build_index(self._h, kp, vp, N0, init_idx.ctypes.data, J.ctypes.data)
         if rc:
-            raise ValueError("oracle_build_index: invalid sizes")
+            raise ValueError("oracle_build_index: invalid sizes or initial positions")
         return J
+
+    def import_unit(self, u, K, V, centroids, n, b, flag, M2, offsets, members, tau, selected=()):
+        """Replaces the state of unit u: K, V [N, d] by token position; per-cluster arrays of length M; members of
+        cluster j = members[offsets[j]:offsets[j+1]] in storage order; `selected` = ids of the last active set."""
+        K, kp = _f32(K)
+        V, vp = _f32(V)
+        r, rp = _f32(centroids)
+        M, N = len(n), K.shape[0]
+        i32 = lambda a: np.ascontiguousarray(a, dtype=np.int32)
+        n, b, flag, offsets, members, selected = (i32(a) for a in (n, b, flag, offsets, members, selected))
+        M2 = np.ascontiguousarray(M2, dtype=np.float64)
+        assert r.shape == (M, self.cfg.head_dim) and len(offsets) == M + 1 and len(members) >= N
+        rc = self._lib.oracle_import_unit(self._h, u, N, kp, vp, M, rp, n.ctypes.data, b.ctypes.data, flag.ctypes.data,
+                                          M2.ctypes.data, offsets.ctypes.data, members.ctypes.data, float(tau),
+                                          len(selected), selected.ctypes.data)
+        if rc:
+            raise ValueError("oracle_import_unit: inconsistent state")
 
     def retrieve_attend(self, Q, budget: int):
         """Q: [U, G, d].  Returns (out [U, G, d] float64, lse [U, G] float64)."""
@@ -203,16 +225,31 @@ class Oracle:
         return pos[:n]
 
     def scores(self, u):
-        s = np.zeros(self.num_clusters(u), np.float32)
+        """float64 cluster scores of the last retrieval (already rounded to float32 values if score_round is set)."""
+        s = np.zeros(self.num_clusters(u), np.float64)
         self._lib.oracle_get_scores(self._h, u, s.ctypes.data)
         return s
 
+    def kv(self, u):
+        """(K, V), each [N, d] float32 by token position."""
+        N, d = self.num_tokens(u), self.cfg.head_dim
+        K, V = np.zeros((N, d), np.float32), np.zeros((N, d), np.float32)
+        self._lib.oracle_get_kv(self._h, u, K.ctypes.data, V.ctypes.data)
+        return K, V
+
+    def kmeans_margins(self, u, n0):
+        m = np.zeros(n0, np.float64)
+        self._lib.oracle_get_kmeans_margins(self._h, u, m.ctypes.data)
+        return m
+
+    def last_split_rounds(self, u): return self._lib.oracle_last_split_rounds(self._h, u)
+
     def diagnostics(self, u):
-        mg = np.zeros(3, np.float64)
+        mg = np.zeros(4, np.float64)
         ties = np.zeros(5, np.int64)
         ev = np.zeros(3, np.int64)
         self._lib.oracle_get_diagnostics(self._h, u, mg.ctypes.data, ties.ctypes.data, ev.ctypes.data)
-        return dict(margin_assign=mg[0], margin_trigger=mg[1], margin_select=mg[2],
+        return dict(margin_assign=mg[0], margin_trigger=mg[1], margin_select=mg[2], margin_split=mg[3],
                     ties=dict(zip(("kmeans", "assign", "trigger", "select", "split_side"), ties.tolist())),
                     splits=int(ev[0]), failed_splits=int(ev[1]), forced_splits=int(ev[2]))
 

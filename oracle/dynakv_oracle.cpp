@@ -6,17 +6,21 @@
 // against the paper by eye.  Only tests, the smoke check and the CPU-baseline leg of the
 // benchmark may call it.  It shares no code with the GPU library.
 //
-// Arithmetic contract (so that every integer decision below is reproducible elsewhere):
+// Arithmetic (the plain definitions, nothing blocked or reordered):
 //   * inputs are float32 values (already rounded to the K/V storage type by the caller);
-//   * every dot product, squared distance, sum, mean and variance is accumulated in
-//     float64; sums over the coordinate index 0..d-1 run in one fixed order (blocks of 8 left
-//     to right from zero, block sums added left to right: see blocked_sum), sums over members
-//     run in storage order, one fused multiply-add per term;
+//   * every dot product, squared distance, sum, mean and variance is a float64 sum taken left
+//     to right over the coordinate index 0..d-1; sums over members run in storage order;
 //   * centroids are STORED as float32 (rounded once per update); M2 (= n * variance) and the
-//     split threshold tau are stored as float64; cluster scores are rounded to float32
-//     before they are ordered; ties go to the lowest index.
+//     split threshold tau are stored as float64; ties go to the lowest index;
+//   * two readings that the paper leaves open are configuration fields: which copy of a
+//     centroid the searches read (`search_copy`: the mean rounded to the storage type of the
+//     keys, or the float32 mean itself) and whether cluster scores are rounded to float32
+//     before they are ordered (`score_round`).
+// Every decision (nearest cluster, threshold test, budget cut, 2-means seeds and sides) also
+// reports its normalised margin, so that a caller comparing another implementation against
+// this one can tell a genuine disagreement from a tie below 1e-4.
 //
-// Pins: see tests/test_oracle_*.py (dense attention at budget >= N, scipy/sklearn special
+// Pins: tests/test_oracle_pins.py (dense attention at budget >= N, scipy / scikit-learn special
 // cases, closed forms, invariants, brute force on tiny inputs, hand-computed fixtures in
 // tests/golden/).  Long trajectories at the real configuration sizes are pinned only
 // through those per-step properties: "parity unpinned" beyond them.
@@ -49,7 +53,10 @@ struct Config {
   float size_factor;        // split when n' > size_factor * mean cluster size; <= 0: off
   float softmax_scale;      // 0: 1/sqrt(d)
   int32_t dtype;            // storage type of K, V, Q: 0 float32, 1 float16, 2 bfloat16
-  uint64_t seed;            // k-means seeding when no initial indices are given
+  int32_t search_copy;      // 0: searches read r_j rounded to the storage type; 1: the float32 mean
+  int32_t score_round;      // 0: clusters are ordered by their float64 scores; 1: rounded to float32 first
+  int32_t update_mode;      // 0: Algorithm 1 (adaptive); 1: static update (entries join the nearest cluster,
+                            //    statistics are updated, nothing is ever flagged or split: Section 2.3)
 };
 
 struct Cluster {
@@ -58,12 +65,13 @@ struct Cluster {
   int32_t flag = 0;         // f_j = SPLIT
   double M2 = 0.0;          // n_j * sigma_j^2 of the committed members
   std::vector<float> r;     // centroid r_j, float32
-  std::vector<float> rs;    // r_j rounded to the storage type: the copy that searches read (see search_copy)
+  std::vector<float> rs;    // the copy of r_j that searches read (see search_copy)
   std::vector<int32_t> members;  // token positions in storage order
 };
 
-struct Margins {            // normalised margins of the last call's decisions
-  double assign = 0, trigger = 0, select = 0;
+// Normalised margins of the decisions of the last call of each kind (infinity: no such decision was taken).
+struct Margins {
+  double assign = 0, trigger = 0, select = 0, split = 0;
 };
 
 struct Unit {
@@ -74,8 +82,10 @@ struct Unit {
   std::vector<int32_t> selected;    // ids in score order (P_req of the last retrieval)
   std::vector<uint8_t> in_req;      // bitmap of P_req by cluster id
   std::vector<int32_t> gather;      // token positions attended by the last retrieval
-  std::vector<float> scores;        // last float32 cluster scores
+  std::vector<double> scores;       // last cluster scores (after score_round, if set)
+  std::vector<double> kmeans_margin;  // per prefill point: smallest assignment margin over the Lloyd iterations
   int32_t last_assign = -1;
+  int32_t last_split_rounds = 0;    // Lloyd rounds of the most recent 2-means
   int32_t error = 0;
   int64_t n_splits = 0, n_failed_splits = 0, n_forced = 0;
   int64_t ties[5] = {0, 0, 0, 0, 0};   // kmeans, assign, trigger, select, split-side
@@ -89,43 +99,33 @@ struct Oracle {
 };
 
 constexpr double kTieMargin = 1e-4;
+constexpr double kInf = std::numeric_limits<double>::infinity();
 
 // ---- the arithmetic primitives everything else is made of ---------------------------------
 
-// Fixed summation order of every sum over the coordinate index ("blocked order"): the terms are taken in
-// blocks of 8 consecutive coordinates; inside a block they are accumulated left to right from zero, one
-// fused multiply-add per term; the block sums are then added left to right.  The paper fixes no order;
-// this one is part of this repository's arithmetic contract (short dependency chains on a GPU).
-constexpr int kBlock = 8;
-// sum over i of one term per coordinate, in the order above; fma_term(i, acc) returns fma(factors of term i, acc)
-template <class F>
-inline double blocked_sum(int d, F&& fma_term) {
-  double total = 0.0;
-  for (int i0 = 0; i0 < d; i0 += kBlock) {
-    double acc = 0.0;
-    for (int i = i0; i < std::min(d, i0 + kBlock); ++i) acc = fma_term(i, acc);
-    total += acc;
-  }
-  return total;
-}
-
-// float64 dot product of two float32 vectors.
+// float64 dot product of two float32 vectors, left to right.
 inline double dot_ff(const float* a, const float* b, int d) {
-  return blocked_sum(d, [&](int i, double acc) { return std::fma((double)a[i], (double)b[i], acc); });
+  double acc = 0.0;
+  for (int i = 0; i < d; ++i) acc += (double)a[i] * (double)b[i];
+  return acc;
 }
 // float64 squared distance between a float32 point and a float32 centre.
 inline double sqdist_ff(const float* x, const float* c, int d) {
-  return blocked_sum(d, [&](int i, double acc) {
+  double acc = 0.0;
+  for (int i = 0; i < d; ++i) {
     const double t = (double)x[i] - (double)c[i];
-    return std::fma(t, t, acc);
-  });
+    acc += t * t;
+  }
+  return acc;
 }
 // Same, centre held in float64 (used inside a split, where centres are not rounded).
 inline double sqdist_fd(const float* x, const double* c, int d) {
-  return blocked_sum(d, [&](int i, double acc) {
+  double acc = 0.0;
+  for (int i = 0; i < d; ++i) {
     const double t = (double)x[i] - c[i];
-    return std::fma(t, t, acc);
-  });
+    acc += t * t;
+  }
+  return acc;
 }
 
 // Round to nearest, ties to even, onto the grid of a binary format with `mant` explicit mantissa bits, smallest
@@ -137,7 +137,7 @@ inline float round_to_format(float x, int mant, int emin, double fmax) {
   const int ex = std::max(e - 1, emin);
   const double quantum = std::ldexp(1.0, ex - mant);
   const double y = std::nearbyint((double)x / quantum) * quantum;   // default rounding mode: ties to even
-  if (std::fabs(y) > fmax) return (float)std::copysign(std::numeric_limits<double>::infinity(), y);
+  if (std::fabs(y) > fmax) return (float)std::copysign(kInf, y);
   return (float)y;
 }
 inline float round_to_storage(float x, int dtype) {
@@ -146,30 +146,25 @@ inline float round_to_storage(float x, int dtype) {
   return x;
 }
 
+// Margin of a decision between two candidate values a (taken) and b (runner-up): their gap over the larger of
+// 1, |a| and |b|.
 inline double norm_margin(double gap, double a, double b) {
   return gap / std::max(1.0, std::max(std::fabs(a), std::fabs(b)));
 }
 
-// splitmix64, the counter-based generator used when the caller gives no initial indices.
-inline uint64_t splitmix64(uint64_t& s) {
-  uint64_t z = (s += 0x9E3779B97F4A7C15ull);
-  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
-  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
-  return z ^ (z >> 31);
-}
-
 // The representatives that a search reads (query similarity, Section 4.1; nearest cluster of a new entry,
-// Algorithm 1) are kept in the storage type of the keys, like the entries they stand for; the statistics
-// (float32 mean, M2) are not touched by this.  Called whenever r_j changes.
+// Algorithm 1).  The paper fixes no precision for them.  search_copy = 0: kept in the storage type of the keys,
+// like the entries they stand for; 1: the float32 mean itself.  The statistics (float32 mean, M2) are not
+// touched by this.  Called whenever r_j changes.
 void search_copy(const Config& c, Cluster& cl) {
   cl.rs.resize(cl.r.size());
-  for (size_t i = 0; i < cl.r.size(); ++i) cl.rs[i] = round_to_storage(cl.r[i], c.dtype);
+  for (size_t i = 0; i < cl.r.size(); ++i) cl.rs[i] = c.search_copy == 0 ? round_to_storage(cl.r[i], c.dtype) : cl.r[i];
 }
 
 // Nearest centre of x among all clusters (Algorithm 1, "assign to nearest cluster";
 // squared Euclidean distance, the k-means metric).  Ties -> lowest id.
 int nearest_cluster(const Unit& u, const float* x, int d, double* best_out, double* second_out) {
-  double best = std::numeric_limits<double>::infinity(), second = best;
+  double best = kInf, second = kInf;
   int arg = -1;
   for (int j = 0; j < (int)u.clusters.size(); ++j) {
     const double dj = sqdist_ff(x, u.clusters[j].rs.data(), d);
@@ -195,41 +190,31 @@ void exact_stats(const Unit& u, const std::vector<int32_t>& mem, int d, std::vec
 
 // ---- prefill: NewCluster(K0) = Lloyd's k-means (Section 4.1, Eq. 3-4; Algorithm 1) ----
 
-int build_unit(const Config& c, Unit& u, int uid, const float* K, const float* V, int N0,
-               const int32_t* init_idx, double* J_hist) {
+int build_unit(const Config& c, Unit& u, const float* K, const float* V, int N0, const int32_t* init_idx,
+               double* J_hist) {
   const int d = c.head_dim, M0 = c.n_clusters_init, T = c.kmeans_iters;
   u = Unit();
   u.N = N0;
   u.K.assign(K, K + (size_t)N0 * d);
   u.V.assign(V, V + (size_t)N0 * d);
 
-  // initial centres: M0 distinct points
-  std::vector<int32_t> init(M0);
-  if (init_idx) {
-    std::copy(init_idx, init_idx + M0, init.begin());
-  } else {  // partial Fisher-Yates over [0, N0), driven by splitmix64
-    uint64_t s = c.seed ^ ((uint64_t)uid * 0x9E3779B97F4A7C15ull);
-    std::vector<int32_t> perm(N0);
-    std::iota(perm.begin(), perm.end(), 0);
-    for (int j = 0; j < M0; ++j) {
-      const uint64_t rem = (uint64_t)(N0 - j);
-      const int pick = j + (int)(splitmix64(s) % rem);
-      std::swap(perm[j], perm[pick]);
-      init[j] = perm[j];
-    }
-  }
+  // initial centres: the M0 distinct points the caller names
   std::vector<float> R((size_t)M0 * d);
-  for (int j = 0; j < M0; ++j) std::copy(&u.K[(size_t)init[j] * d], &u.K[(size_t)init[j] * d] + d, &R[(size_t)j * d]);
+  for (int j = 0; j < M0; ++j) {
+    const int32_t p = init_idx[j];
+    if (p < 0 || p >= N0) return 1;
+    std::copy(&u.K[(size_t)p * d], &u.K[(size_t)p * d] + d, &R[(size_t)j * d]);
+  }
 
   std::vector<int32_t> label(N0, 0), count(M0, 0);
   std::vector<double> dist(N0, 0.0);
-  std::vector<uint8_t> tie_point(N0, 0);
+  u.kmeans_margin.assign(N0, kInf);
   for (int it = 0; it < T; ++it) {
     // (a) assignment: nearest centre, ties -> lowest j
     double J = 0.0;
     for (int i = 0; i < N0; ++i) {
       const float* x = &u.K[(size_t)i * d];
-      double best = std::numeric_limits<double>::infinity(), second = best;
+      double best = kInf, second = kInf;
       int arg = 0;
       for (int j = 0; j < M0; ++j) {
         const double dj = sqdist_ff(x, &R[(size_t)j * d], d);
@@ -241,7 +226,7 @@ int build_unit(const Config& c, Unit& u, int uid, const float* K, const float* V
       J += best;
       if (M0 > 1) {
         const double xx = dot_ff(x, x, d);
-        if (norm_margin(second - best, xx - best, xx - second) <= kTieMargin) tie_point[i] = 1;
+        u.kmeans_margin[i] = std::min(u.kmeans_margin[i], norm_margin(second - best, xx - best, xx - second));
       }
     }
     if (J_hist) J_hist[it] = J;
@@ -272,7 +257,7 @@ int build_unit(const Config& c, Unit& u, int uid, const float* K, const float* V
       }
     }
   }
-  for (int i = 0; i < N0; ++i) u.ties[0] += tie_point[i];
+  for (int i = 0; i < N0; ++i) u.ties[0] += u.kmeans_margin[i] <= kTieMargin;
 
   // cluster records: members in ascending position, n, r, M2 about the stored centre
   u.clusters.assign(M0, Cluster());
@@ -290,6 +275,7 @@ int build_unit(const Config& c, Unit& u, int uid, const float* K, const float* V
   // head-specific threshold: a multiple of the unit's own mean squared distance to centre
   u.tau = (double)c.var_alpha * (Jfinal / (double)N0);
   u.in_req.assign(M0, 0);
+  u.mg = Margins{kInf, kInf, kInf, kInf};
   return 0;
 }
 
@@ -300,7 +286,7 @@ void retrieve_attend_unit(const Config& c, Unit& u, const float* Q, int budget, 
   const double scale = c.softmax_scale > 0.f ? (double)c.softmax_scale : 1.0 / std::sqrt((double)d);
 
   // query-representative similarity: inner product per head, reduced over the group
-  u.scores.assign(M, 0.f);
+  u.scores.assign(M, 0.0);
   for (int j = 0; j < M; ++j) {
     double red = 0.0;
     for (int g = 0; g < G; ++g) {
@@ -309,7 +295,7 @@ void retrieve_attend_unit(const Config& c, Unit& u, const float* Q, int budget, 
       else if (c.group_reduce == 0) red = std::max(red, s);
       else red += s;
     }
-    u.scores[j] = (float)(red * scale);
+    u.scores[j] = c.score_round ? (double)(float)(red * scale) : red * scale;
   }
   // order by (score desc, id asc)
   std::vector<int32_t> order(M);
@@ -341,8 +327,8 @@ void retrieve_attend_unit(const Config& c, Unit& u, const float* Q, int budget, 
       for (int32_t p : cl.members) u.gather.push_back(p);
     }
   }
-  // selection margin: the two score gaps around the cut
-  u.mg.select = std::numeric_limits<double>::infinity();
+  // selection margin: the two score gaps around the cut (last taken vs first left out, first left out vs next)
+  u.mg.select = kInf;
   for (int r = cut; r <= cut + 1; ++r)
     if (r >= 1 && r < M) {
       const double a = u.scores[order[r - 1]], b = u.scores[order[r]];
@@ -355,7 +341,7 @@ void retrieve_attend_unit(const Config& c, Unit& u, const float* Q, int budget, 
     const float* q = Q + (size_t)g * d;
     const size_t T = u.gather.size();
     std::vector<double> logit(T);
-    double mx = -std::numeric_limits<double>::infinity();
+    double mx = -kInf;
     for (size_t t = 0; t < T; ++t) {
       logit[t] = scale * dot_ff(q, &u.K[(size_t)u.gather[t] * d], d);
       mx = std::max(mx, logit[t]);
@@ -369,7 +355,7 @@ void retrieve_attend_unit(const Config& c, Unit& u, const float* Q, int budget, 
       for (int k = 0; k < d; ++k) acc[k] += p * (double)v[k];
     }
     for (int k = 0; k < d; ++k) out[(size_t)g * d + k] = T ? acc[k] / den : 0.0;
-    if (lse) lse[g] = T ? mx + std::log(den) : -std::numeric_limits<double>::infinity();
+    if (lse) lse[g] = T ? mx + std::log(den) : -kInf;
   }
 }
 
@@ -383,7 +369,7 @@ void append_unit(const Config& c, Unit& u, const float* k, const float* v) {
   u.last_assign = j;
   {
     const double xx = dot_ff(k, k, d);
-    u.mg.assign = M > 1 ? norm_margin(second - best, xx - best, xx - second) : std::numeric_limits<double>::infinity();
+    u.mg.assign = M > 1 ? norm_margin(second - best, xx - best, xx - second) : kInf;
     if (u.mg.assign <= kTieMargin) ++u.ties[1];
   }
   const int32_t pos = u.N;
@@ -392,19 +378,18 @@ void append_unit(const Config& c, Unit& u, const float* k, const float* v) {
   u.N += 1;
   Cluster& cl = u.clusters[j];
   cl.members.push_back(pos);          // stored with its cluster whatever the branch
-  u.mg.trigger = std::numeric_limits<double>::infinity();
+  u.mg.trigger = kInf;
   if (cl.flag) { cl.b += 1; return; }  // already flagged: goes to Buf_j
 
   // UpdateVar: tentative size, centroid and M2 from (n, r, M2) and the new entry alone
   const int32_t n1 = cl.n + 1;
   std::vector<double> r1(d);
   for (int i = 0; i < d; ++i) r1[i] = (double)cl.r[i] + ((double)k[i] - (double)cl.r[i]) / (double)n1;
-  const double M2 = cl.M2 + blocked_sum(d, [&](int i, double acc) {
-    return std::fma((double)k[i] - (double)cl.r[i], (double)k[i] - r1[i], acc);   // delta_i * (k_i - r'_i)
-  });
+  double M2 = cl.M2;
+  for (int i = 0; i < d; ++i) M2 += ((double)k[i] - (double)cl.r[i]) * ((double)k[i] - r1[i]);   // delta_i * (k_i - r'_i)
   const double var1 = M2 / (double)n1;
   bool trig = false;
-  if (n1 >= 2) {
+  if (n1 >= 2 && c.update_mode == 0) {
     if (c.var_alpha > 0.f) {
       if (var1 > u.tau) trig = true;
       u.mg.trigger = std::fabs(var1 - u.tau) / std::max(1.0, u.tau);
@@ -426,6 +411,16 @@ void append_unit(const Config& c, Unit& u, const float* k, const float* v) {
 
 // ---- SplitCluster: local 2-means on one cluster (Algorithm 1; Sections 4.2, 5.2) --------
 
+// Gap between the largest and the second largest of v (ties: 0), over the larger of 1 and the largest.
+double top_gap(const std::vector<double>& v) {
+  double a = -kInf, b = -kInf;
+  for (double t : v) {
+    if (t > a) { b = a; a = t; }
+    else if (t > b) b = t;
+  }
+  return v.size() < 2 ? kInf : (a - b) / std::max(1.0, a);
+}
+
 // Returns 1 if split, 0 if it could not be split (flag cleared, statistics made exact),
 // -1 if there is no room for a new cluster (left flagged).
 int split_cluster(const Config& c, Unit& u, int j) {
@@ -433,6 +428,7 @@ int split_cluster(const Config& c, Unit& u, int j) {
   Cluster& cl = u.clusters[j];
   const std::vector<int32_t> mem = cl.members;
   const int m = (int)mem.size();
+  u.last_split_rounds = 0;
   auto fail = [&]() {
     exact_stats(u, cl.members, d, cl.r, cl.M2);
     search_copy(c, cl);
@@ -448,11 +444,13 @@ int split_cluster(const Config& c, Unit& u, int j) {
   for (int i = 0; i < m; ++i)
     for (int k = 0; k < d; ++k) mean[k] += (double)X(i)[k];
   for (int k = 0; k < d; ++k) mean[k] /= (double)m;
-  int a = 0; double da = -1.0;
-  for (int i = 0; i < m; ++i) { const double t = sqdist_fd(X(i), mean.data(), d); if (t > da) { da = t; a = i; } }
-  int b = 0; double db = -1.0;
-  for (int i = 0; i < m; ++i) { const double t = sqdist_ff(X(i), X(a), d); if (t > db) { db = t; b = i; } }
-  if (!(db > 0.0)) return fail();     // all members identical
+  std::vector<double> dm(m), da(m);
+  int a = 0;
+  for (int i = 0; i < m; ++i) { dm[i] = sqdist_fd(X(i), mean.data(), d); if (dm[i] > dm[a]) a = i; }
+  int b = 0;
+  for (int i = 0; i < m; ++i) { da[i] = sqdist_ff(X(i), X(a), d); if (da[i] > da[b]) b = i; }
+  if (!(da[b] > 0.0)) return fail();     // all members identical
+  u.mg.split = std::min(u.mg.split, std::min(top_gap(dm), top_gap(da)));
 
   std::vector<double> cA(d), cB(d);
   for (int k = 0; k < d; ++k) { cA[k] = (double)X(a)[k]; cB[k] = (double)X(b)[k]; }
@@ -461,13 +459,14 @@ int split_cluster(const Config& c, Unit& u, int j) {
     for (int i = 0; i < m; ++i) {
       const double dA = sqdist_fd(X(i), cA.data(), d), dB = sqdist_fd(X(i), cB.data(), d);
       nside[i] = dA <= dB ? 0 : 1;    // tie -> side A
-      if (it == 0 || nside[i] != side[i]) {
-        const double xx = dot_ff(X(i), X(i), d);
-        if (norm_margin(std::fabs(dA - dB), xx - dA, xx - dB) <= kTieMargin) ++u.ties[4];
-      }
+      const double xx = dot_ff(X(i), X(i), d);
+      const double mg = norm_margin(std::fabs(dA - dB), xx - dA, xx - dB);
+      u.mg.split = std::min(u.mg.split, mg);
+      if ((it == 0 || nside[i] != side[i]) && mg <= kTieMargin) ++u.ties[4];
     }
     if (nside == side) break;
     side = nside;
+    u.last_split_rounds = it + 1;
     int nA = 0;
     for (int i = 0; i < m; ++i) nA += side[i] == 0;
     if (nA == 0 || nA == m) return fail();
@@ -498,13 +497,14 @@ int split_cluster(const Config& c, Unit& u, int j) {
 }
 
 void split_unit(const Config& c, Unit& u) {
+  u.mg.split = kInf;
   // delayed splits: flagged clusters that the last retrieval brought in
   const int M = (int)u.clusters.size();
   for (int j = 0; j < M; ++j) {
     const Cluster& cl = u.clusters[j];
     if (cl.flag && (c.buffer_max == 0 || (j < (int)u.in_req.size() && u.in_req[j]))) split_cluster(c, u, j);
   }
-  // forced split once the buffers hold B_max entries: the cluster with the fullest buffer
+  // forced split once the buffers hold B_max entries: the cluster with the fullest buffer (lowest id among equals)
   if (c.buffer_max > 0) {
     int64_t tot = 0; int arg = -1;
     for (int j = 0; j < (int)u.clusters.size(); ++j) {
@@ -513,7 +513,9 @@ void split_unit(const Config& c, Unit& u) {
       tot += cl.b;
       if (arg < 0 || cl.b > u.clusters[arg].b) arg = j;
     }
-    if (arg >= 0 && tot >= c.buffer_max) { ++u.n_forced; split_cluster(c, u, arg); }
+    if (arg >= 0 && tot >= c.buffer_max) {
+      if (split_cluster(c, u, arg) == 1) ++u.n_forced;    // counted when the split was carried out
+    }
   }
 }
 
@@ -527,15 +529,14 @@ struct oracle_config {
   int32_t n_units, group_size, head_dim, n_clusters_init, max_clusters, max_tokens, kmeans_iters, buffer_max,
       group_reduce;
   float var_alpha, size_factor, softmax_scale;
-  int32_t dtype;
-  uint64_t seed;
+  int32_t dtype, search_copy, score_round, update_mode;
 };
 
 void* oracle_create(const oracle_config* c) {
   Oracle* o = new Oracle();
   o->cfg = Config{c->n_units, c->group_size, c->head_dim, c->n_clusters_init, c->max_clusters, c->max_tokens,
                   c->kmeans_iters, c->buffer_max, c->group_reduce, c->var_alpha, c->size_factor, c->softmax_scale,
-                  c->dtype, c->seed};
+                  c->dtype, c->search_copy, c->score_round, c->update_mode};
   o->units.resize(c->n_units);
   return o;
 }
@@ -558,20 +559,63 @@ int oracle_threads_used(void* h) {
 #define UNIT_LOOP(o)
 #endif
 
-// K, V: [U][n_tokens][d] float32; init_idx: [U][M0] or null; J_hist: [U][iters] or null.
+// K, V: [U][n_tokens][d] float32; init_idx: [U][M0], positions of the initial centres; J_hist: [U][iters] or null.
 int oracle_build_index(void* h, const float* K, const float* V, int n_tokens, const int32_t* init_idx,
                        double* J_hist) {
   Oracle* o = (Oracle*)h;
   const Config& c = o->cfg;
-  if (n_tokens < c.n_clusters_init || n_tokens > c.max_tokens || c.n_clusters_init > c.max_clusters ||
+  if (!init_idx || n_tokens < c.n_clusters_init || n_tokens > c.max_tokens || c.n_clusters_init > c.max_clusters ||
       c.n_clusters_init < 1 || c.kmeans_iters < 1)
     return 1;
   const size_t stride = (size_t)n_tokens * c.head_dim;
+  std::vector<int> rc(c.n_units, 0);
   UNIT_LOOP(o)
   for (int u = 0; u < c.n_units; ++u)
-    build_unit(c, o->units[u], u, K + u * stride, V + u * stride, n_tokens,
-               init_idx ? init_idx + (size_t)u * c.n_clusters_init : nullptr,
-               J_hist ? J_hist + (size_t)u * c.kmeans_iters : nullptr);
+    rc[u] = build_unit(c, o->units[u], K + u * stride, V + u * stride, n_tokens, init_idx + (size_t)u * c.n_clusters_init,
+                       J_hist ? J_hist + (size_t)u * c.kmeans_iters : nullptr);
+  for (int r : rc)
+    if (r) return 1;
+  return 0;
+}
+
+// Replaces the state of unit u by the given one (the counterpart of the GPU library's exported state):
+// K, V [N][d] float32 by token position; per cluster centroids [M][d] float32, n, b, flag [M], M2 [M] float64;
+// offsets [M+1] and members [N]: token positions of cluster j in storage order = members[offsets[j]..offsets[j+1]);
+// selected [n_sel]: ids of the last active set.  Returns nonzero on inconsistent sizes.
+int oracle_import_unit(void* h, int u, int N, const float* K, const float* V, int M, const float* centroids,
+                       const int32_t* n, const int32_t* b, const int32_t* flag, const double* M2,
+                       const int32_t* offsets, const int32_t* members, double tau, int n_sel, const int32_t* selected) {
+  Oracle* o = (Oracle*)h;
+  const Config& c = o->cfg;
+  const int d = c.head_dim;
+  if (u < 0 || u >= c.n_units || N < 0 || N > c.max_tokens || M < 1 || M > c.max_clusters || offsets[M] != N) return 1;
+  Unit nu;
+  nu.N = N;
+  nu.K.assign(K, K + (size_t)N * d);
+  nu.V.assign(V, V + (size_t)N * d);
+  nu.clusters.assign(M, Cluster());
+  for (int j = 0; j < M; ++j) {
+    Cluster& cl = nu.clusters[j];
+    cl.n = n[j]; cl.b = b[j]; cl.flag = flag[j]; cl.M2 = M2[j];
+    if (offsets[j + 1] - offsets[j] != n[j] + b[j]) return 1;
+    cl.r.assign(centroids + (size_t)j * d, centroids + (size_t)(j + 1) * d);
+    cl.members.assign(members + offsets[j], members + offsets[j + 1]);
+    search_copy(c, cl);
+  }
+  nu.tau = tau;
+  nu.in_req.assign(M, 0);
+  for (int i = 0; i < n_sel; ++i) {
+    if (selected[i] < 0 || selected[i] >= M) return 1;
+    nu.selected.push_back(selected[i]);
+    nu.in_req[selected[i]] = 1;
+  }
+  nu.mg = Margins{kInf, kInf, kInf, kInf};
+  // counters carry over: they describe the run, not the state
+  const Unit& old = o->units[u];
+  nu.n_splits = old.n_splits; nu.n_failed_splits = old.n_failed_splits; nu.n_forced = old.n_forced;
+  std::copy(old.ties, old.ties + 5, nu.ties);
+  nu.last_assign = old.last_assign;
+  o->units[u] = std::move(nu);
   return 0;
 }
 
@@ -608,6 +652,7 @@ int oracle_num_tokens(void* h, int u) { return ((Oracle*)h)->units[u].N; }
 int oracle_error(void* h, int u) { return ((Oracle*)h)->units[u].error; }
 double oracle_tau(void* h, int u) { return ((Oracle*)h)->units[u].tau; }
 int oracle_last_assign(void* h, int u) { return ((Oracle*)h)->units[u].last_assign; }
+int oracle_last_split_rounds(void* h, int u) { return ((Oracle*)h)->units[u].last_split_rounds; }
 
 // centroids [M][d] f32, n/b/flag [M] i32, M2 [M] f64 (any may be null)
 void oracle_get_clusters(void* h, int u, float* centroids, int32_t* n, int32_t* b, int32_t* flag, double* M2) {
@@ -645,7 +690,13 @@ int oracle_get_gather(void* h, int u, int32_t* pos, int cap) {
   for (int i = 0; i < n && i < cap; ++i) pos[i] = un.gather[i];
   return n;
 }
-// search copies [M][d] f32 (the values, exactly representable in the storage type)
+// keys and values by token position, [N][d] float32 each (either may be null)
+void oracle_get_kv(void* h, int u, float* K, float* V) {
+  const Unit& un = ((Oracle*)h)->units[u];
+  if (K) std::copy(un.K.begin(), un.K.end(), K);
+  if (V) std::copy(un.V.begin(), un.V.end(), V);
+}
+// the copies of the centroids that searches read, [M][d] f32
 void oracle_get_search_copy(void* h, int u, float* out) {
   const Oracle* o = (Oracle*)h;
   const int d = o->cfg.head_dim;
@@ -657,16 +708,21 @@ void oracle_round_to_storage(const float* in, float* out, int64_t n, int dtype) 
   for (int64_t i = 0; i < n; ++i) out[i] = round_to_storage(in[i], dtype);
 }
 
-void oracle_get_scores(void* h, int u, float* s) {
+void oracle_get_scores(void* h, int u, double* s) {
   const Unit& un = ((Oracle*)h)->units[u];
   std::copy(un.scores.begin(), un.scores.end(), s);
 }
-// margins[3] = assign, trigger, select of the last calls; ties[5] = counts of decisions whose
-// margin was <= 1e-4 (k-means points, assignments, triggers, selections, split sides);
-// events[3] = splits, failed splits, forced splits
+// per prefill point, the smallest margin of its nearest-centre decisions over the Lloyd iterations, [N0]
+void oracle_get_kmeans_margins(void* h, int u, double* out) {
+  const Unit& un = ((Oracle*)h)->units[u];
+  std::copy(un.kmeans_margin.begin(), un.kmeans_margin.end(), out);
+}
+// margins[4] = assign, trigger, select, split (smallest over the last call's 2-means decisions) of the last
+// calls; ties[5] = counts of decisions whose margin was <= 1e-4 (k-means points, assignments, triggers,
+// selections, split sides); events[3] = splits, failed splits, forced splits
 void oracle_get_diagnostics(void* h, int u, double* margins, int64_t* ties, int64_t* events) {
   const Unit& un = ((Oracle*)h)->units[u];
-  if (margins) { margins[0] = un.mg.assign; margins[1] = un.mg.trigger; margins[2] = un.mg.select; }
+  if (margins) { margins[0] = un.mg.assign; margins[1] = un.mg.trigger; margins[2] = un.mg.select; margins[3] = un.mg.split; }
   if (ties) std::copy(un.ties, un.ties + 5, ties);
   if (events) { events[0] = un.n_splits; events[1] = un.n_failed_splits; events[2] = un.n_forced; }
 }

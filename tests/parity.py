@@ -28,7 +28,7 @@ def make_pair(spec: WorkloadSpec, n_units: int, max_tokens: int | None = None, *
               softmax_scale=0.0)
     kw.update(over)
     ix = binding.Index(binding.Config(dtype=spec.dtype, head_dim=spec.head_dim, **kw), DEV)
-    o = Oracle(OracleConfig(head_dim=spec.head_dim, seed=0, dtype=spec.dtype, **kw))
+    o = Oracle(OracleConfig(head_dim=spec.head_dim, dtype=spec.dtype, **kw))
     return ix, o
 
 
@@ -157,7 +157,7 @@ def run_full_size(spec: WorkloadSpec, sample, steps: int, check_every: int = 16,
               max_tokens=spec.prefill + steps, kmeans_iters=spec.kmeans_iters, buffer_max=spec.buffer_max, group_reduce=0,
               var_alpha=spec.var_alpha, size_factor=spec.size_factor, softmax_scale=0.0)
     ix = binding.Index(binding.Config(dtype=spec.dtype, head_dim=spec.head_dim, n_units=spec.n_units, **kw), DEV)
-    o = Oracle(OracleConfig(head_dim=spec.head_dim, seed=0, dtype=spec.dtype, n_units=len(sample), **kw))
+    o = Oracle(OracleConfig(head_dim=spec.head_dim, dtype=spec.dtype, n_units=len(sample), **kw))
     ix.dynakv_build_index(to_dev(w["K0"], spec.dtype), to_dev(w["V0"], spec.dtype), torch.from_numpy(w["init_idx"]).to(DEV))
     o.build_index(w["K0"][sample], w["V0"][sample], w["init_idx"][sample])
     compare_state(ix, o, "after build_index", units=sample)

@@ -17,8 +17,8 @@ from paper_2511_07427_amd.workload import CONFIGS, generate
 GOLD = os.path.join(os.path.dirname(__file__), "golden")
 
 
-def cfg(U=1, G=1, d=2, M0=2, maxc=8, maxt=64, iters=3, bmax=16, alpha=0.0, size=0.0, reduce=0, scale=0.0):
-    return OracleConfig(U, G, d, M0, maxc, maxt, iters, bmax, reduce, alpha, size, scale, 0)
+def cfg(U=1, G=1, d=2, M0=2, maxc=8, maxt=64, iters=3, bmax=16, alpha=0.0, size=0.0, reduce=0, scale=0.0, **kw):
+    return OracleConfig(U, G, d, M0, maxc, maxt, iters, bmax, reduce, alpha, size, scale, **kw)
 
 
 def blobs(rng, n, d, k, sep=6.0, std=0.5):
@@ -85,7 +85,7 @@ def test_kmeans_closed_forms():
 def test_centroid_is_member_mean_and_variance_is_mean_sqdist():
     s = CONFIGS["tiny"]
     w = generate(s)
-    o = Oracle(OracleConfig(1, 4, 128, 32, 128, s.max_tokens, 10, 16, 0, 1.5, 0.0, 0.0, 0))
+    o = Oracle(OracleConfig(1, 4, 128, 32, 128, s.max_tokens, 10, 16, 0, 1.5, 0.0, 0.0))
     J = o.build_index(w["K0"], w["V0"], w["init_idx"])
     assert np.all(np.diff(J[0]) <= 0)
     c, (off, mem) = o.clusters(0), o.members(0)
@@ -110,17 +110,6 @@ def test_empty_cluster_is_reseeded_with_the_farthest_point():
     assert np.all(np.diff(J[0]) <= 0)
     np.testing.assert_array_equal(o.labels(0), [0, 0, 0, 0, 1])
     np.testing.assert_allclose(o.clusters(0)["centroids"], [[0.25, 0.25], [50, 50]])
-
-
-def test_seeded_init_is_deterministic_and_gives_a_partition():
-    rng = np.random.default_rng(4)
-    X = rng.standard_normal((2, 300, 4)).astype(np.float32)
-    a, b = Oracle(cfg(U=2, d=4, M0=7, maxc=7, maxt=300)), Oracle(cfg(U=2, d=4, M0=7, maxc=7, maxt=300))
-    a.build_index(X, X)
-    b.build_index(X, X)
-    for u in range(2):
-        np.testing.assert_array_equal(a.labels(u), b.labels(u))
-        assert sorted(a.members(u)[1].tolist()) == list(range(300))
 
 
 # ---------------------------------------------------------------- hand examples
@@ -267,13 +256,206 @@ def test_ties_go_to_the_lowest_index():
     assert o.selected(0).tolist() == [0]
 
 
+# ---------------------------------------------------------------- triggers, unsplittable clusters, forced-split ties
+
+def test_hand_example_4_size_trigger_at_its_exact_boundary():
+    g = json.load(open(os.path.join(GOLD, "hand_example_4_size_trigger.json")))
+    K = np.array(g["keys"], np.float32)[None]
+    o = Oracle(cfg(M0=4, maxt=16, size=g["size_factor"], bmax=16))
+    o.build_index(K, K, np.array([g["init_idx"]], np.int32))
+    off, mem = o.members(0)
+    assert [mem[off[j]:off[j + 1]].tolist() for j in range(4)] == g["clusters"]["members"]
+    for step in (g["step_a"], g["step_b"]):
+        assert step["lhs_n_prime_times_M"] == step["n_prime"] * step["M"]
+        assert step["rhs_factor_times_N_plus_1"] == g["size_factor"] * step["N_plus_1"]
+        assert o.num_tokens(0) + 1 == step["N_plus_1"] and o.num_clusters(0) == step["M"]
+        k = np.array([step["new_key"]], np.float32)
+        o.append(k, k)
+        c = o.clusters(0)
+        assert o.last_assign(0) == step["assigned"]
+        assert (c["flag"][0], c["n"][0], c["b"][0]) == (step["flag"], step["n_after"], step["b_after"]), step
+
+
+def _import_fixture(o, keys, clusters, selected=(), tau=0.0):
+    keys = np.array(keys, np.float32)
+    mem = sum((c["members"] for c in clusters), [])
+    off = np.cumsum([0] + [len(c["members"]) for c in clusters])
+    o.import_unit(0, keys, keys, np.array([c["centroid"] for c in clusters], np.float32), [c["n"] for c in clusters],
+                  [c["b"] for c in clusters], [c["flag"] for c in clusters], [c["M2"] for c in clusters], off, mem, tau,
+                  selected)
+
+
+def test_hand_example_5_forced_split_tie_goes_to_the_lowest_id():
+    g = json.load(open(os.path.join(GOLD, "hand_example_5_forced_tie_and_unsplittable.json")))["forced_tie"]
+    o = Oracle(cfg(maxt=16, alpha=1.5, bmax=g["buffer_max"]))
+    _import_fixture(o, g["keys"], g["clusters"], g["selected"], tau=1.0)
+    o.split()
+    a = g["after"]
+    d = o.diagnostics(0)
+    assert (o.num_clusters(0), d["forced_splits"], d["splits"], d["failed_splits"]) == (a["n_clusters"], 1, 1, 0)
+    c, (off, mem) = o.clusters(0), o.members(0)
+    for j, key in ((0, "cluster_0"), (1, "cluster_1"), (3, "cluster_3")):
+        w = a[key]
+        assert mem[off[j]:off[j + 1]].tolist() == w["members"]
+        assert (c["n"][j], c["flag"][j], c["b"][j]) == (w["n"], w["flag"], w["b"])
+        if "centroid" in w:
+            np.testing.assert_array_equal(c["centroids"][j], np.array(w["centroid"], np.float32))
+            assert c["M2"][j] == pytest.approx(w["M2"], abs=1e-15)
+
+
+def test_hand_example_5_unsplittable_clusters_are_unflagged_with_exact_statistics():
+    g = json.load(open(os.path.join(GOLD, "hand_example_5_forced_tie_and_unsplittable.json")))
+    # all members equal: flagged by the size trigger, 2-means finds no second seed
+    e = g["all_equal"]
+    K = np.array(e["keys"], np.float32)[None]
+    o = Oracle(cfg(maxt=16, size=e["size_factor"], bmax=0))
+    o.build_index(K, K, np.array([e["init_idx"]], np.int32))
+    k = np.array([e["new_key"]], np.float32)
+    o.append(k, k)
+    c = o.clusters(0)
+    assert (c["flag"][0], c["b"][0], c["n"][0]) == tuple(e["after_append"][x] for x in ("flag", "b", "n"))
+    o.split()
+    a, c, d = e["after_split"], o.clusters(0), o.diagnostics(0)
+    assert (o.num_clusters(0), d["failed_splits"], d["splits"]) == (a["n_clusters"], a["failed_splits"], a["splits"])
+    assert (c["flag"][0], c["b"][0], c["n"][0], c["M2"][0]) == (a["flag"], a["b"], a["n"], a["M2"])
+    np.testing.assert_array_equal(c["centroids"][0], np.array(a["centroid"], np.float32))
+    assert o.members(0)[1][:6].tolist() == [0, 1, 2, 3, 4, 6]
+    # a flagged cluster with a single entry (only reachable through an imported state)
+    e = g["single_member"]
+    o = Oracle(cfg(maxt=16, alpha=1.5, bmax=0))
+    _import_fixture(o, e["keys"], e["clusters"], tau=1.0)
+    o.split()
+    a, c, d = e["after_split"], o.clusters(0), o.diagnostics(0)
+    assert (o.num_clusters(0), d["failed_splits"], d["splits"]) == (a["n_clusters"], a["failed_splits"], 0)
+    assert (c["flag"][0], c["b"][0], c["n"][0], c["M2"][0]) == (a["flag"], a["b"], a["n"], a["M2"])
+    np.testing.assert_array_equal(c["centroids"][0], np.array(a["centroid"], np.float32))
+
+
+def test_two_means_of_a_split_is_sklearn_lloyd_from_the_same_seeds():
+    """A 2-means that needs several Lloyd rounds: partition and centres against scikit-learn started from the two
+    seeds (member farthest from the mean, member farthest from that one)."""
+    from sklearn.cluster import KMeans
+    rounds_seen = []
+    for seed in range(12):
+        rng = np.random.default_rng(100 + seed)
+        m, d = 90, 6
+        X = np.concatenate([rng.standard_normal((m // 2, d)) * [4, 1, 1, 1, 1, 1],
+                            rng.standard_normal((m - m // 2, d)) * [1, 4, 1, 1, 1, 1] + [2.5, 2.5, 0, 0, 0, 0]])
+        X = X[rng.permutation(m)].astype(np.float32)
+        o = Oracle(cfg(d=d, M0=1, maxc=4, maxt=m + 1, iters=1, size=0.5, bmax=0))
+        o.build_index(X[None, :m - 1], X[None, :m - 1], np.zeros((1, 1), np.int32))
+        o.append(X[None, m - 1], X[None, m - 1])
+        assert o.clusters(0)["flag"][0] == 1
+        o.split()
+        assert o.num_clusters(0) == 2 and o.diagnostics(0)["splits"] == 1
+        rounds_seen.append(o.last_split_rounds(0))
+        Xd = X.astype(np.float64)
+        a = int(((Xd - Xd.mean(0)) ** 2).sum(1).argmax())
+        b = int(((Xd - Xd[a]) ** 2).sum(1).argmax())
+        km = KMeans(2, init=Xd[[a, b]], n_init=1, algorithm="lloyd", max_iter=16, tol=0).fit(Xd)
+        assert km.n_iter_ < 16
+        lab = o.labels(0)
+        same = lab == lab[0]
+        np.testing.assert_array_equal(same, km.labels_ == km.labels_[0])
+        c = o.clusters(0)
+        for j in (0, 1):
+            np.testing.assert_allclose(c["centroids"][j], Xd[lab == j].mean(0), rtol=1e-6, atol=1e-6)
+        np.testing.assert_allclose(sorted(c["M2"]), sorted(((Xd[km.labels_ == s] - km.cluster_centers_[s]) ** 2).sum()
+                                                          for s in (0, 1)), rtol=1e-9)
+    assert max(rounds_seen) >= 4 and sum(r >= 3 for r in rounds_seen) >= 4, rounds_seen
+
+
+def test_reported_margins_on_the_hand_examples():
+    """The normalised margins that classify a disagreement as a tie: gap / max(1, |taken|, |runner-up|) on
+    z = 2 k.r - |r|^2 for nearest-cluster decisions, on the scores around the budget cut, |variance - tau| /
+    max(1, tau) for the threshold, and for a split the smallest over its seed choices and side decisions."""
+    g1, K, V = _example1()
+    o = Oracle(cfg(maxt=16))
+    o.build_index(K, V, np.array([g1["init_idx"]], np.int32))
+    o.retrieve_attend(np.array(g1["query"], np.float32)[None, None], 2)
+    assert o.diagnostics(0)["margin_select"] == pytest.approx(20.0 / 21.0, rel=1e-12)    # scores 21/sqrt2 and 1/sqrt2
+    k = np.array([[1, 2]], np.float32)
+    o.append(k, k)
+    # squared distances 2.5 and 162, |k|^2 = 5: z = 2.5 and -157
+    assert o.diagnostics(0)["margin_assign"] == pytest.approx(159.5 / 157.0, rel=1e-12)
+    g3 = json.load(open(os.path.join(GOLD, "hand_example_3_split.json")))
+    K3 = np.array(g3["keys"], np.float32)[None]
+    o = Oracle(cfg(maxt=16, alpha=1.5, bmax=0))
+    o.build_index(K3, K3, np.array([g3["init_idx"]], np.int32))
+    k = np.array([g3["new_key"]], np.float32)
+    o.append(k, k)
+    o.split()
+    # seed B: distances to (9,9) are 162, 145, 145, 128, 0: gap 17 over 162 is the smallest margin of this split
+    assert o.diagnostics(0)["margin_split"] == pytest.approx(17.0 / 162.0, rel=1e-12)
+    assert o.last_split_rounds(0) == 1
+
+
+def test_static_update_never_flags_and_config_fields_select_the_readings():
+    s = CONFIGS["tiny"].scaled(dtype="bf16", var_alpha=1.2, size_factor=2.0)
+    w = generate(s, steps=64)
+    base = dict(n_units=1, group_size=4, head_dim=128, n_clusters_init=32, max_clusters=128, max_tokens=s.prefill + 64,
+                kmeans_iters=3, buffer_max=4, var_alpha=1.2, size_factor=2.0, dtype="bf16")
+    runs = {}
+    for name, kw in (("copy", {}), ("mean", dict(search_copy=1)), ("round", dict(score_round=1)),
+                     ("static", dict(update_mode=1))):
+        o = Oracle(OracleConfig(**base, **kw))
+        o.build_index(w["K0"], w["V0"], w["init_idx"])
+        for t in range(64):
+            o.retrieve_attend(w["Q"][t], 256)
+            if t == 0:
+                q = w["Q"][0, 0].astype(np.float64)
+                r = (o.search_copy(0) if name != "mean" else o.clusters(0)["centroids"]).astype(np.float64)
+                want = (q @ r.T).max(0) / np.sqrt(128)
+                if name == "round":
+                    np.testing.assert_array_equal(o.scores(0), want.astype(np.float32).astype(np.float64))
+                else:
+                    np.testing.assert_allclose(o.scores(0), want, rtol=1e-13)
+            o.append(w["Knew"][t], w["Vnew"][t])
+            o.split()
+        runs[name] = o
+    np.testing.assert_array_equal(runs["mean"].search_copy(0), runs["mean"].clusters(0)["centroids"])
+    assert not np.array_equal(runs["copy"].search_copy(0), runs["copy"].clusters(0)["centroids"])
+    st = runs["static"]
+    assert st.num_clusters(0) == 32 and st.clusters(0)["flag"].sum() == 0 and st.clusters(0)["n"].sum() == s.prefill + 64
+    assert runs["copy"].num_clusters(0) > 32
+
+
+def test_imported_state_continues_like_the_original():
+    s = CONFIGS["tiny"].scaled(var_alpha=1.2, buffer_max=4)
+    w = generate(s, steps=96)
+    kw = dict(n_units=1, group_size=4, head_dim=128, n_clusters_init=32, max_clusters=128, max_tokens=s.prefill + 96,
+              kmeans_iters=3, buffer_max=4, var_alpha=1.2, size_factor=2.0)
+    a = Oracle(OracleConfig(**kw))
+    a.build_index(w["K0"], w["V0"], w["init_idx"])
+    for t in range(48):
+        a.retrieve_attend(w["Q"][t], 256); a.append(w["Knew"][t], w["Vnew"][t]); a.split()
+    a.retrieve_attend(w["Q"][48], 256)            # the active set travels with the state
+    b = Oracle(OracleConfig(**kw))
+    c, (off, mem), (K, V) = a.clusters(0), a.members(0), a.kv(0)
+    assert c["flag"].sum() > 0                    # the state carries flagged clusters and their buffers
+    b.import_unit(0, K, V, c["centroids"], c["n"], c["b"], c["flag"], c["M2"], off, mem, a.tau(0), a.selected(0))
+    for t in range(48, 96):
+        if t > 48:
+            oa, la = a.retrieve_attend(w["Q"][t], 256)
+            ob, lb = b.retrieve_attend(w["Q"][t], 256)
+            np.testing.assert_array_equal(oa, ob)
+            np.testing.assert_array_equal(a.gather(0), b.gather(0))
+        for o in (a, b):
+            o.append(w["Knew"][t], w["Vnew"][t]); o.split()
+    ca, cb = a.clusters(0), b.clusters(0)
+    for k in ca:
+        np.testing.assert_array_equal(ca[k], cb[k])
+    np.testing.assert_array_equal(a.members(0)[1], b.members(0)[1])
+    assert a.num_clusters(0) == b.num_clusters(0) > c["n"].shape[0]
+
+
 # ---------------------------------------------------------------- decode properties on a realistic workload
 
 @pytest.fixture(scope="module")
 def tiny_run():
     s = CONFIGS["tiny"].scaled(var_alpha=1.2)
     w = generate(s)
-    o = Oracle(OracleConfig(1, 4, 128, 32, 128, s.max_tokens, 10, 4, 0, s.var_alpha, s.size_factor, 0.0, 0))
+    o = Oracle(OracleConfig(1, 4, 128, 32, 128, s.max_tokens, 10, 4, 0, s.var_alpha, s.size_factor, 0.0))
     o.build_index(w["K0"], w["V0"], w["init_idx"])
     return s, w, o
 
@@ -322,7 +504,7 @@ def test_trajectory_invariants_and_split_partition(tiny_run):
 def test_updatevar_is_the_two_pass_variance():
     s = CONFIGS["tiny"]
     w = generate(s)
-    o = Oracle(OracleConfig(1, 4, 128, 32, 32, s.max_tokens, 10, 16, 0, 0.0, 0.0, 0.0, 0))   # no trigger at all
+    o = Oracle(OracleConfig(1, 4, 128, 32, 32, s.max_tokens, 10, 16, 0, 0.0, 0.0, 0.0))   # no trigger at all
     o.build_index(w["K0"], w["V0"], w["init_idx"])
     for t in range(s.steps):
         o.append(w["Knew"][t], w["Vnew"][t])
@@ -340,7 +522,7 @@ def test_full_budget_is_dense_attention_and_order_does_not_matter(tiny_run):
     rng = np.random.default_rng(7)
     K, V, Q = w["K0"][:, :512], w["V0"][:, :512], w["Q"][0]
     init = rng.choice(512, 16, replace=False).astype(np.int32)[None]
-    o = Oracle(OracleConfig(1, 4, 128, 16, 16, 600, 4, 16, 0, 0.0, 0.0, 0.0, 0))
+    o = Oracle(OracleConfig(1, 4, 128, 16, 16, 600, 4, 16, 0, 0.0, 0.0, 0.0))
     o.build_index(K, V, init)
     out, lse = o.retrieve_attend(Q, 512)
     assert len(o.selected(0)) == 16 and sorted(o.gather(0).tolist()) == list(range(512))
@@ -349,7 +531,7 @@ def test_full_budget_is_dense_attention_and_order_does_not_matter(tiny_run):
     np.testing.assert_allclose(lse[0], rl, rtol=1e-12)
     # the same tokens in another order give the same attention; huge logits do not overflow
     perm = rng.permutation(512)
-    o2 = Oracle(OracleConfig(1, 4, 128, 16, 16, 600, 4, 16, 0, 0.0, 0.0, 0.0, 0))
+    o2 = Oracle(OracleConfig(1, 4, 128, 16, 16, 600, 4, 16, 0, 0.0, 0.0, 0.0))
     o2.build_index(K[:, perm], V[:, perm], init)
     out2, _ = o2.retrieve_attend(Q, 512)
     np.testing.assert_allclose(out2, out, rtol=1e-10, atol=1e-12)
@@ -410,7 +592,7 @@ def test_full_budget_splits_every_flagged_cluster_at_once_and_keeps_every_token(
     w = generate(s)
     runs = {}
     for name, bmax, budget in (("all_resident", 0, 64), ("full_budget", 16, 10 ** 6)):
-        o = Oracle(OracleConfig(1, 4, 128, 32, 128, s.max_tokens, 10, bmax, 0, s.var_alpha, s.size_factor, 0.0, 0))
+        o = Oracle(OracleConfig(1, 4, 128, 32, 128, s.max_tokens, 10, bmax, 0, s.var_alpha, s.size_factor, 0.0))
         o.build_index(w["K0"], w["V0"], w["init_idx"])
         for t in range(s.steps):
             o.retrieve_attend(w["Q"][t], budget)
@@ -464,7 +646,7 @@ def test_searches_read_the_centroids_in_the_storage_type(dtype):
     statistics do not change.  Checked against numpy on a drifting trajectory with appends and splits."""
     s = CONFIGS["tiny"].scaled(dtype=dtype, var_alpha=1.2, size_factor=0.0, buffer_max=4)
     w = generate(s, steps=96)
-    o = Oracle(OracleConfig(1, 4, 128, 32, 128, s.max_tokens, 5, 4, 0, s.var_alpha, 0.0, 0.0, 0, dtype=dtype))
+    o = Oracle(OracleConfig(1, 4, 128, 32, 128, s.max_tokens, 5, 4, 0, s.var_alpha, 0.0, 0.0, dtype=dtype))
     o.build_index(w["K0"], w["V0"], w["init_idx"])
     conv = (lambda a: a.astype(np.float16).astype(np.float32)) if dtype == "f16" else _bf16
     differ = 0
@@ -488,3 +670,17 @@ def test_searches_read_the_centroids_in_the_storage_type(dtype):
         o.split()
     assert differ > 0          # the rounding is visible: scores are not those of the unrounded means
     assert o.diagnostics(0)["splits"] > 0
+
+
+def test_oracle_runs_clean_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    """oracle/sanitize_check.cpp drives every call of the oracle (prefill, retrievals, appends, delayed and forced
+    splits, a state import, the capacity limits) in a build with -fsanitize=address,undefined."""
+    import subprocess
+    src = os.path.join(os.path.dirname(GOLD), "..", "oracle", "sanitize_check.cpp")
+    exe = str(tmp_path / "sanitize_check")
+    subprocess.check_call(["g++", "-O1", "-g", "-std=c++17", "-fopenmp", "-fsanitize=address,undefined",
+                           "-fno-sanitize-recover=all", src, "-o", exe])
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=300,
+                       env=dict(os.environ, ASAN_OPTIONS="verify_asan_link_order=0", OMP_NUM_THREADS="2"))
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "sanitize_check ok" in r.stdout
