@@ -18,17 +18,21 @@
  *               call returns without waiting; inputs and outputs must stay valid until the stream
  *               has passed the call.  One handle is driven from one stream at a time.
  *   errors    - host-detectable misuse returns a status and enqueues nothing.  Conditions only
- *               the device can see (token, cluster or page capacity exhausted) set a sticky
- *               per-unit error word; the offending operation leaves the unit's state unchanged
- *               (a split that has no room leaves its cluster flagged); dynakv_export_state
- *               reports the word.
- *   numerics  - decisions (nearest cluster, split trigger, 2-means sides, cluster order) are taken
- *               on float64 values summed in one fixed order (over the 128 coordinates: blocks of 8
- *               consecutive coordinates accumulated left to right from zero with one fused
- *               multiply-add per term, then the 16 block sums added left to right; over members:
- *               in ascending position), so that they can be reproduced exactly; cluster scores
- *               are rounded to float32 before they are ordered; ties go to the lowest index.
- *               Attention uses matrix cores with float32 accumulation.
+ *               the device can see (token, cluster or page capacity exhausted, invalid initial
+ *               positions or imported state) set a sticky per-unit error word; the offending
+ *               operation leaves the unit's state unchanged (a split that has no room leaves its
+ *               cluster flagged); dynakv_export_state, which waits for the stream, reports the
+ *               words and returns DYNAKV_ECAPACITY if any is set.
+ *   numerics  - the statistics (mean, M2, threshold test) and the 2-means of a split are float64
+ *               computations on the stored values.  With 16-bit storage, cluster scores and the
+ *               distances of a new entry are first computed on the matrix cores (products of two
+ *               16-bit values are exact, the 128 of them are accumulated in float32); every
+ *               decision that the float32 rounding could change is then retaken on float64 values:
+ *               the nearest cluster among all candidates within the error bound of the best, and
+ *               the budget cut among all clusters whose score lies within the bound of the cut.
+ *               The selected set therefore is the one of exact arithmetic; the order in which the
+ *               selected clusters are attended follows the float32 scores.  Ties go to the lowest
+ *               index.  Attention uses matrix cores with float32 accumulation.
  */
 #ifndef DYNAKV_H
 #define DYNAKV_H
@@ -45,18 +49,38 @@ typedef struct dynakv_index dynakv_index_t; /* opaque host-side handle */
 typedef enum {
   DYNAKV_OK = 0,
   DYNAKV_EINVAL = 1,    /* bad argument or unsupported size */
-  DYNAKV_ECAPACITY = 2, /* workspace too small */
+  DYNAKV_ECAPACITY = 2, /* workspace or static scratch too small; from dynakv_export_state: a unit's error word is set */
   DYNAKV_ESTATE = 3,    /* call out of order (decode call before dynakv_build_index) */
-  DYNAKV_EHIP = 4       /* a HIP runtime call failed */
+  DYNAKV_EHIP = 4,      /* a HIP runtime call failed */
+  DYNAKV_ENOMEM = 5     /* host memory for the handle could not be allocated */
 } dynakv_status_t;
 
 typedef enum { DYNAKV_F32 = 0, DYNAKV_F16 = 1, DYNAKV_BF16 = 2 } dynakv_dtype_t;
 typedef enum { DYNAKV_GROUP_MAX = 0, DYNAKV_GROUP_SUM = 1 } dynakv_group_reduce_t;
+/* Which copy of a centroid the two searches of a step read (query similarity, nearest cluster of the new entry;
+ * Section 4.1, Algorithm 1: the paper fixes no precision).  STORAGE: the mean rounded to the type of the keys, like
+ * the entries it stands for (half the bytes to scan; the float32 mean stays the master copy for the statistics).
+ * MEAN: the float32 mean itself, scored in float64 on the vector units.  float32 storage always reads the mean. */
+typedef enum { DYNAKV_SEARCH_STORAGE = 0, DYNAKV_SEARCH_MEAN = 1 } dynakv_search_copy_t;
+/* ADAPTIVE: Algorithm 1.  STATIC: the static-update baseline of Section 2.3: entries join their nearest cluster
+ * and update its statistics, no cluster is ever flagged or split. */
+typedef enum { DYNAKV_UPDATE_ADAPTIVE = 0, DYNAKV_UPDATE_STATIC = 1 } dynakv_update_mode_t;
 
 /* bits of the per-unit device error word */
 #define DYNAKV_ERR_TOKENS 1   /* append refused: max_tokens or page pool exhausted            */
 #define DYNAKV_ERR_CLUSTERS 2 /* split refused: max_clusters reached (cluster stays flagged)   */
 #define DYNAKV_ERR_SPLIT_SIZE 4 /* split refused: cluster larger than the split kernel handles */
+#define DYNAKV_ERR_SELECT 8   /* retrieval cut short: more clusters selected than the selection can order */
+#define DYNAKV_ERR_INIT 16    /* dynakv_build_index: an initial position out of range or given twice */
+#define DYNAKV_ERR_IMPORT 32  /* dynakv_import_state: inconsistent sizes; the unit keeps its previous state */
+
+/* Launch shape (dynakv_config_t.launch).  0 lets the library choose.  Otherwise the low byte is the number of
+ * workgroups that share one unit's gather + attention (split-KV), the next byte their wavefronts (4, 8 or 16),
+ * either 0 = chosen by the library, plus the flags below.  Results do not depend on the shape beyond float32
+ * rounding of the attention output. */
+#define DYNAKV_LAUNCH(kv_splits, att_waves) (((kv_splits) & 255) | (((att_waves) & 255) << 8))
+#define DYNAKV_LAUNCH_SEPARATE (1 << 16)     /* scores, selection, gather + attention, append, split as separate kernels */
+#define DYNAKV_LAUNCH_SPLIT_KERNEL (1 << 17) /* a whole-step call runs its splits in a kernel of their own */
 
 typedef struct {
   int32_t n_units;         /* U >= 1                                                            */
@@ -64,7 +88,7 @@ typedef struct {
   int32_t head_dim;        /* d; must be 128                                                    */
   int32_t dtype;           /* dynakv_dtype_t of K, V and Q                                      */
   int32_t n_clusters_init; /* M0, clusters built at prefill                                     */
-  int32_t max_clusters;    /* capacity per unit, splits included; M0..8192                      */
+  int32_t max_clusters;    /* capacity per unit, splits included; M0..65536                     */
   int32_t max_tokens;      /* capacity per unit                                                 */
   int32_t kmeans_iters;    /* Lloyd iterations at prefill, >= 1, no early exit                  */
   int32_t buffer_max;      /* B_max of Algorithm 1; 0 = every cluster counts as resident        */
@@ -72,7 +96,11 @@ typedef struct {
   float var_alpha;         /* tau = var_alpha * (k-means objective / N0) per unit; <= 0: off    */
   float size_factor;       /* also flag when n' > size_factor * (N+1)/M; <= 0: off              */
   float softmax_scale;     /* 0 = 1/sqrt(head_dim)                                              */
-  int32_t reserved;        /* must be 0                                                         */
+  int32_t search_copy;     /* dynakv_search_copy_t                                              */
+  int32_t score_round;     /* 1: where the budget cut is retaken on float64 scores, they are rounded to
+                              float32 first (equal float32 scores then go by id); 0: compared as float64 */
+  int32_t update_mode;     /* dynakv_update_mode_t                                              */
+  int32_t launch;          /* 0, or DYNAKV_LAUNCH(..) | DYNAKV_LAUNCH_* flags                    */
 } dynakv_config_t;
 
 /* Bytes of device workspace an index of this configuration needs (0 if the configuration is invalid). */
@@ -89,17 +117,17 @@ dynakv_status_t dynakv_destroy(dynakv_index_t* index);
  * clusters, then n_j, r_j, M2_j, tau, empty buffers and flags, and the cluster-contiguous page layout.
  *   K, V      device, [U][n_tokens][head_dim] in cfg.dtype, contiguous; read only
  *   n_tokens  M0 <= n_tokens <= min(max_tokens, 16384)
- *   init_idx  device, int32 [U][M0]: positions of the M0 distinct keys used as initial centres
+ *   init_idx  device, int32 [U][M0]: positions of the M0 distinct keys used as initial centres (a position out of
+ *             range or given twice sets DYNAKV_ERR_INIT; the build then runs with the position clamped)
  * Empty clusters are re-seeded with the points farthest from their centres in every iteration but the
- * last.  Resets any earlier state of the index. */
+ * last.  Resets any earlier state of the index, error words included. */
 dynakv_status_t dynakv_build_index(dynakv_index_t* index, const void* K, const void* V, int32_t n_tokens,
                                    const int32_t* init_idx, void* stream);
 
-/* One retrieval (Algorithm 1 "load top-k clusters by query-centroid similarity"; Section 4.1) followed by
- * softmax attention over the retrieved entries (Section 7, attention over reordered KV):
- * score_j = float32(scale * reduce_g <q_g, r~_j>), r~_j = the centroid rounded to cfg.dtype (the copy of the
- * representatives that searches read is kept in the storage type of the keys; the float32 mean r_j stays the
- * master for the statistics); clusters are taken in (score desc, id asc) order while
+/* One retrieval (Algorithm 1, decode block: the top clusters by query-centroid similarity are loaded;
+ * Section 4.1) followed by softmax attention over the retrieved entries (Section 7, attention over reordered KV):
+ * score_j = scale * reduce_g <q_g, r~_j>, r~_j = the copy of the centroid selected by cfg.search_copy;
+ * clusters are taken in (score desc, id asc) order while
  * their stored sizes n_j + |Buf_j| fit in `token_budget`, stopping at the first that does not fit; if
  * even the best cluster does not fit, its first `token_budget` entries are taken.  The selected set
  * becomes the active set P_req that dynakv_split consults.
@@ -110,7 +138,7 @@ dynakv_status_t dynakv_build_index(dynakv_index_t* index, const void* K, const v
 dynakv_status_t dynakv_retrieve_attend(dynakv_index_t* index, const void* Q, int32_t token_budget, float* out,
                                        float* lse, void* stream);
 
-/* Adds one entry per unit (Algorithm 1: assign to the nearest cluster (squared distance to r~_j, see
+/* Adds one entry per unit (Algorithm 1, decode block: assign to the nearest cluster (squared distance to r~_j, see
  * dynakv_retrieve_attend), UpdateVar on the float32 mean, threshold test, then
  * AddEntry + UpdateStats or buffer + flag; Section 4.2).  The entry is always stored at the tail of its
  * cluster's pages; a cluster whose tentative variance exceeds tau (or whose tentative size exceeds the
@@ -119,7 +147,7 @@ dynakv_status_t dynakv_retrieve_attend(dynakv_index_t* index, const void* Q, int
  *   k_new, v_new  device, [U][head_dim] in cfg.dtype */
 dynakv_status_t dynakv_append(dynakv_index_t* index, const void* k_new, const void* v_new, void* stream);
 
-/* Algorithm 1, "delayed cluster splitting": splits every flagged cluster that the last retrieval selected
+/* Algorithm 1, delayed cluster splitting: splits every flagged cluster that the last retrieval selected
  * (all flagged clusters if buffer_max = 0), in ascending id; then, if the buffers together hold at least
  * buffer_max entries, also the flagged cluster with the most buffered entries.  A split is a 2-means of
  * the cluster's keys (seeds: the member farthest from the mean, then the member farthest from that one;
@@ -132,16 +160,17 @@ dynakv_status_t dynakv_split(dynakv_index_t* index, void* stream);
  * v_new) and dynakv_split(), in that order and with the same results bit for bit, so the three calls and
  * this one can be mixed freely.  It exists because the step's two passes over the centroid table (query
  * similarity, Section 4.1; nearest cluster of the new key, Section 4.2) read the same data, and because a
- * step is a chain of short dependent phases: with 16-bit storage, at most 4096 clusters and at most 8 query
- * heads per unit the whole step is ONE kernel launch that reads the table once, commits the
- * append before it streams the selected pages, and prepares the due splits while it streams them.
- * Otherwise (float32 storage, more clusters, more query heads) it is four launches instead of the five of
- * the three calls: the score kernel also finds the new key's nearest cluster, and the splits run in the
- * append's launch.  Arguments as in the three calls. */
+ * step is a chain of short dependent phases: with 16-bit storage read through its 16-bit search copy, at most
+ * 8192 clusters and at most 8 query heads per unit the whole step is ONE kernel launch that reads the table
+ * once, commits the append before it streams the selected pages, and prepares the due splits while it streams
+ * them.  Otherwise (float32 storage or search copy, more clusters, more query heads) it is four launches
+ * instead of the six of the three calls: the score kernel also evaluates the new key's distances, and the
+ * splits run in the append's launch.  Arguments as in the three calls. */
 dynakv_status_t dynakv_decode_step(dynakv_index_t* index, const void* Q, int32_t token_budget, float* out,
                                    float* lse, const void* k_new, const void* v_new, void* stream);
 
-/* Snapshot for tests and debugging.  Every field is a device pointer or null (null = skip). */
+/* Snapshot of an index, written by dynakv_export_state and read by dynakv_import_state.  Every field is a device
+ * pointer or null (null = skip). */
 typedef struct {
   int32_t* n_clusters;   /* [U]                 M_t                                              */
   int32_t* n_tokens;     /* [U]                 N_t                                              */
@@ -161,12 +190,24 @@ typedef struct {
   int32_t* gathered;     /* [U][max_tokens]     their token positions in gather order            */
   int32_t* last_assign;  /* [U]                 cluster chosen by the last append                */
   int64_t* counters;     /* [U][8]              splits, failed splits, forced splits, pages in use,
-                                                entries gathered, retrievals, clusters scored
-                                                (all since build_index), reserved             */
+                                                entries gathered, retrievals, clusters scored,
+                                                decisions retaken in float64 (all since build_index) */
+  void* keys;            /* [U][max_tokens][head_dim] in cfg.dtype: key of every token, by position      */
+  void* values;          /* [U][max_tokens][head_dim] in cfg.dtype: value of every token, by position    */
 } dynakv_state_t;
 
-/* Copies the requested parts of the state (enqueued on `stream`; the caller synchronises before reading). */
+/* Copies the requested parts of the state, waits for `stream`, and returns DYNAKV_ECAPACITY if the error word of
+ * any unit is set (the copy is complete in that case too), DYNAKV_OK otherwise. */
 dynakv_status_t dynakv_export_state(dynakv_index_t* index, const dynakv_state_t* dst, void* stream);
+
+/* Replaces the whole state of the index by a snapshot (Algorithm 1's state: the partition, n_j, r_j, M2_j, Buf_j,
+ * f_j, tau, and the active set P_req of the last retrieval), e.g. one that dynakv_export_state wrote, so that a
+ * run can be resumed or continued elsewhere.  Required fields: n_clusters, n_tokens, tau, centroids, size,
+ * buffered, flag, m2, offsets, members, keys, values; optional: n_selected with selected (else the active set is
+ * empty).  The other fields are ignored.  Pages are laid out afresh, cluster by cluster; error words and counters
+ * start at zero.  A unit whose sizes are inconsistent (cluster or token count beyond capacity, offsets that do
+ * not match size + buffered) keeps its previous state and gets DYNAKV_ERR_IMPORT.  Counts as building the index. */
+dynakv_status_t dynakv_import_state(dynakv_index_t* index, const dynakv_state_t* src, void* stream);
 
 /* Timing aid: when enabled, the dominant kernel of dynakv_retrieve_attend / dynakv_decode_step (gather +
  * attention; where it can run, the single kernel that also scores and selects and, in a decode step,

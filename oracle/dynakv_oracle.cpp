@@ -615,6 +615,7 @@ int oracle_import_unit(void* h, int u, int N, const float* K, const float* V, in
   nu.n_splits = old.n_splits; nu.n_failed_splits = old.n_failed_splits; nu.n_forced = old.n_forced;
   std::copy(old.ties, old.ties + 5, nu.ties);
   nu.last_assign = old.last_assign;
+  nu.error = old.error;
   o->units[u] = std::move(nu);
   return 0;
 }

@@ -16,18 +16,32 @@ LIB_PATH = os.path.join(_HERE, "libdynakv.so")
 
 DTYPES = {"f32": 0, "f16": 1, "bf16": 2}
 TORCH_DTYPES = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
-ERR_TOKENS, ERR_CLUSTERS, ERR_SPLIT_SIZE = 1, 2, 4
+ERR_TOKENS, ERR_CLUSTERS, ERR_SPLIT_SIZE, ERR_SELECT, ERR_INIT, ERR_IMPORT = 1, 2, 4, 8, 16, 32
+OK, EINVAL, ECAPACITY, ESTATE, EHIP, ENOMEM = range(6)
+SEARCH_STORAGE, SEARCH_MEAN = 0, 1
+UPDATE_ADAPTIVE, UPDATE_STATIC = 0, 1
+LAUNCH_SEPARATE, LAUNCH_SPLIT_KERNEL = 1 << 16, 1 << 17
+
+
+def launch_shape(kv_splits: int = 0, att_waves: int = 0, flags: int = 0) -> int:
+    """The value of Config.launch (DYNAKV_LAUNCH in the header)."""
+    return (kv_splits & 255) | ((att_waves & 255) << 8) | flags
 
 
 class _Cfg(C.Structure):
     _fields_ = [(k, C.c_int32) for k in ("n_units", "group_size", "head_dim", "dtype", "n_clusters_init",
                                           "max_clusters", "max_tokens", "kmeans_iters", "buffer_max",
                                           "group_reduce")] + \
-               [(k, C.c_float) for k in ("var_alpha", "size_factor", "softmax_scale")] + [("reserved", C.c_int32)]
+               [(k, C.c_float) for k in ("var_alpha", "size_factor", "softmax_scale")] + \
+               [(k, C.c_int32) for k in ("search_copy", "score_round", "update_mode", "launch")]
 
 
 _STATE_FIELDS = ("n_clusters", "n_tokens", "error", "tau", "centroids", "size", "buffered", "flag", "m2", "offsets",
-                 "members", "scores", "n_selected", "selected", "n_gathered", "gathered", "last_assign", "counters")
+                 "members", "scores", "n_selected", "selected", "n_gathered", "gathered", "last_assign", "counters",
+                 "keys", "values")
+# what dynakv_import_state reads
+IMPORT_FIELDS = ("n_clusters", "n_tokens", "tau", "centroids", "size", "buffered", "flag", "m2", "offsets", "members",
+                 "keys", "values", "n_selected", "selected")
 
 
 class _State(C.Structure):
@@ -49,6 +63,10 @@ class Config:
     size_factor: float = 0.0
     softmax_scale: float = 0.0
     head_dim: int = 128
+    search_copy: int = SEARCH_STORAGE
+    score_round: int = 0
+    update_mode: int = UPDATE_ADAPTIVE
+    launch: int = 0
 
 
 _lib = None
@@ -72,6 +90,7 @@ def load():
         lib.dynakv_split.argtypes = [vp, vp]
         lib.dynakv_decode_step.argtypes = [vp, vp, i32, vp, vp, vp, vp, vp]
         lib.dynakv_export_state.argtypes = [vp, C.POINTER(_State), vp]
+        lib.dynakv_import_state.argtypes = [vp, C.POINTER(_State), vp]
         lib.dynakv_profile_enable.argtypes = [vp, i32]
         lib.dynakv_profile_read.argtypes = [vp, C.POINTER(i32), C.POINTER(C.c_double)]
         lib.dynakv_profiled_kernel.restype = C.c_char_p
@@ -90,7 +109,7 @@ def _check(rc, what):
 def _cfg(cfg: Config) -> _Cfg:
     return _Cfg(cfg.n_units, cfg.group_size, cfg.head_dim, DTYPES[cfg.dtype], cfg.n_clusters_init, cfg.max_clusters,
                 cfg.max_tokens, cfg.kmeans_iters, cfg.buffer_max, cfg.group_reduce, cfg.var_alpha, cfg.size_factor,
-                cfg.softmax_scale, 0)
+                cfg.softmax_scale, cfg.search_copy, cfg.score_round, cfg.update_mode, cfg.launch)
 
 
 def dynakv_workspace_bytes(cfg: Config) -> int:
@@ -187,18 +206,37 @@ class Index:
         return self._lib.dynakv_profiled_kernel(self._h).decode()
 
     # ---- snapshot -------------------------------------------------------------------------------
-    def dynakv_export_state(self, fields=_STATE_FIELDS):
-        """Returns the requested parts of the state as CPU tensors (synchronises the current stream)."""
+    def _state_spec(self):
         c = self.cfg
         U, M, N, d = c.n_units, c.max_clusters, c.max_tokens, c.head_dim
         i32, f32, f64, i64 = torch.int32, torch.float32, torch.float64, torch.int64
-        spec = dict(n_clusters=((U,), i32), n_tokens=((U,), i32), error=((U,), i32), tau=((U,), f64),
+        return dict(n_clusters=((U,), i32), n_tokens=((U,), i32), error=((U,), i32), tau=((U,), f64),
                     centroids=((U, M, d), f32), size=((U, M), i32), buffered=((U, M), i32), flag=((U, M), i32),
                     m2=((U, M), f64), offsets=((U, M + 1), i32), members=((U, N), i32), scores=((U, M), f32),
                     n_selected=((U,), i32), selected=((U, M), i32), n_gathered=((U,), i32), gathered=((U, N), i32),
-                    last_assign=((U,), i32), counters=((U, 8), i64))
+                    last_assign=((U,), i32), counters=((U, 8), i64), keys=((U, N, d), self._tdtype),
+                    values=((U, N, d), self._tdtype))
+
+    def dynakv_export_state(self, fields=_STATE_FIELDS[:-2], to_cpu=True):
+        """Returns the requested parts of the state (the call waits for the stream), as CPU tensors unless
+        to_cpu is False.  A set error word does not raise: the returned status is kept in `self.export_status`
+        (ECAPACITY in that case) and the words are in the "error" field."""
+        spec = self._state_spec()
         bufs = {k: torch.zeros(spec[k][0], dtype=spec[k][1], device=self.device) for k in fields}
         st = _State(**{k: (bufs[k].data_ptr() if k in bufs else None) for k in _STATE_FIELDS})
-        _check(self._lib.dynakv_export_state(self._h, C.byref(st), _stream()), "dynakv_export_state")
-        torch.cuda.current_stream().synchronize()
-        return {k: v.cpu() for k, v in bufs.items()}
+        rc = self._lib.dynakv_export_state(self._h, C.byref(st), _stream())
+        self.export_status = rc
+        if rc not in (OK, ECAPACITY):
+            _check(rc, "dynakv_export_state")
+        return {k: v.cpu() for k, v in bufs.items()} if to_cpu else bufs
+
+    def dynakv_import_state(self, state: dict):
+        """state: device tensors by field name (the fields of IMPORT_FIELDS; n_selected / selected optional), shaped
+        like those dynakv_export_state returns."""
+        spec = self._state_spec()
+        ptrs = {}
+        for k in IMPORT_FIELDS:
+            if k in state:
+                ptrs[k] = _dev(state[k], spec[k][1], spec[k][0])
+        st = _State(**{k: ptrs.get(k) for k in _STATE_FIELDS})
+        _check(self._lib.dynakv_import_state(self._h, C.byref(st), _stream()), "dynakv_import_state")

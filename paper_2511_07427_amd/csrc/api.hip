@@ -1,6 +1,5 @@
 // Host side of the C ABI declared in include/dynakv.h: argument checks, the carving of the caller's
 // workspace into the arrays of `View`, and the kernel launches of every call.
-#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -27,11 +26,18 @@ bool config_ok(const dynakv_config_t* c) {
   if (!c) return false;
   if (c->n_units < 1 || c->group_size < 1 || c->group_size > 16 || c->head_dim != kHeadDim) return false;
   if (c->dtype != DYNAKV_F32 && c->dtype != DYNAKV_F16 && c->dtype != DYNAKV_BF16) return false;
-  if (c->n_clusters_init < 1 || c->max_clusters < c->n_clusters_init || c->max_clusters > kMaxClusters) return false;
+  if (c->n_clusters_init < 1 || c->n_clusters_init > kMaxInitClusters) return false;
+  if (c->max_clusters < c->n_clusters_init || c->max_clusters > kSelectLds /* until the selection streams its keys */) return false;
   if (c->max_tokens < c->n_clusters_init || c->max_tokens >= (1 << 24)) return false;
   if (c->kmeans_iters < 1 || c->buffer_max < 0) return false;
   if (c->group_reduce != DYNAKV_GROUP_MAX && c->group_reduce != DYNAKV_GROUP_SUM) return false;
-  if (c->softmax_scale < 0.f || c->reserved != 0) return false;
+  if (c->softmax_scale < 0.f) return false;
+  if (c->search_copy != DYNAKV_SEARCH_STORAGE && c->search_copy != DYNAKV_SEARCH_MEAN) return false;
+  if (c->score_round != 0 && c->score_round != 1) return false;
+  if (c->update_mode != DYNAKV_UPDATE_ADAPTIVE && c->update_mode != DYNAKV_UPDATE_STATIC) return false;
+  if (c->launch & ~(0xFFFF | DYNAKV_LAUNCH_SEPARATE | DYNAKV_LAUNCH_SPLIT_KERNEL)) return false;
+  const int s = c->launch & 255, nw = (c->launch >> 8) & 255;
+  if (s > kMaxKvSplits || (nw != 0 && nw != 4 && nw != 8 && nw != 16)) return false;
   return true;
 }
 
@@ -47,7 +53,7 @@ int pow2_floor(int x) {
 // workgroup per unit from 32 units on: the step is bound by dependent round trips to memory rather than by the
 // number of busy compute units, and every further workgroup per unit adds partial results, a ticket and a merge
 // (measured on the 8-unit configuration: 4 workgroups per unit beat 1, 2, 8, 16 and 32; with 112 and 128 units
-// 1 beats 2 and 3).  DYNAKV_KV_SPLITS / DYNAKV_ATT_WAVES override for tuning runs.
+// 1 beats 2 and 3).  The configuration's `launch` field overrides both numbers.
 void plan_attention(const dynakv_config_t& c, int* S, int* NW) {
   // split-KV (separate kernels): measured at 16384 + tokens per unit, budget 4096, with 1..128 units: 8 workgroups
   // per unit up to 32 units, then 256 / units (e.g. 16 units: 10.8k steps/s with 8, 9.5k with 2; 64 units: 7.6k with 4,
@@ -56,10 +62,10 @@ void plan_attention(const dynakv_config_t& c, int* S, int* NW) {
   if (s > 8) s = 8;
   // where the single-kernel retrieval can run (see retrieve_is_fused) it beats split-KV at every unit count:
   // measured 16.5k against 15.5k steps/s with 8 units, 15.1k against 13.1k with 24 (configuration 2's shape)
-  if (c.dtype != DYNAKV_F32 && c.max_clusters <= kFusedClusters && c.group_size <= 8) s = 1;
+  if (c.dtype != DYNAKV_F32 && c.search_copy == DYNAKV_SEARCH_STORAGE && c.max_clusters <= kFusedClusters && c.group_size <= 8) s = 1;
   int nw = pow2_floor(4096 / (c.n_units * s) > 0 ? 4096 / (c.n_units * s) : 1);
-  if (const char* e = std::getenv("DYNAKV_KV_SPLITS")) s = std::atoi(e);
-  if (const char* e = std::getenv("DYNAKV_ATT_WAVES")) nw = std::atoi(e);
+  if (c.launch & 255) s = c.launch & 255;
+  if ((c.launch >> 8) & 255) nw = (c.launch >> 8) & 255;
   const int lds_max = pow2_floor(65536 / (c.group_size * (kHeadDim + 2) * 4));
   nw = nw < 4 ? 4 : (nw > 16 ? 16 : pow2_floor(nw));
   if (nw > lds_max) nw = lds_max < 4 ? 4 : lds_max;
@@ -82,7 +88,10 @@ size_t carve(const dynakv_config_t& c, char* base, View* out) {
   v.U = c.n_units; v.G = c.group_size; v.dtype = c.dtype; v.M0 = c.n_clusters_init; v.Mcap = c.max_clusters;
   v.Ncap = c.max_tokens; v.Pcap = pages_per_unit(c); v.Lcap = (c.max_tokens + 3) & ~3; v.Bmax = c.buffer_max; v.group_reduce = c.group_reduce;
   plan_attention(c, &v.S, &v.NW);
-  v.fuse = std::getenv("DYNAKV_NO_FUSE") ? 0 : std::getenv("DYNAKV_SPLIT_KERNEL") ? 1 : 2;   // tuning / test switches
+  v.fuse = (c.launch & DYNAKV_LAUNCH_SEPARATE) ? 0 : (c.launch & DYNAKV_LAUNCH_SPLIT_KERNEL) ? 1 : 2;
+  v.search_mean = c.dtype == DYNAKV_F32 || c.search_copy == DYNAKV_SEARCH_MEAN;
+  v.score_round = c.score_round;
+  v.static_update = c.update_mode == DYNAKV_UPDATE_STATIC;
   v.var_alpha = c.var_alpha; v.size_factor = c.size_factor;
   v.scale_d = c.softmax_scale > 0.f ? (double)c.softmax_scale : 1.0 / std::sqrt((double)c.head_dim);
   v.scale_f = (float)v.scale_d;
@@ -135,7 +144,7 @@ dynakv_status_t dynakv_create(const dynakv_config_t* cfg, void* workspace, size_
   if (!config_ok(cfg) || !workspace || ((uintptr_t)workspace & 255)) return DYNAKV_EINVAL;
   if (bytes < carve(*cfg, nullptr, nullptr)) return DYNAKV_ECAPACITY;
   dynakv_index* ix = new (std::nothrow) dynakv_index();
-  if (!ix) return DYNAKV_EINVAL;
+  if (!ix) return DYNAKV_ENOMEM;
   ix->cfg = *cfg;
   ix->workspace = workspace;
   ix->bytes = carve(*cfg, (char*)workspace, &ix->view);
@@ -224,7 +233,26 @@ dynakv_status_t dynakv_split(dynakv_index_t* ix, void* stream) {
 dynakv_status_t dynakv_export_state(dynakv_index_t* ix, const dynakv_state_t* dst, void* stream) {
   if (!ix || !dst) return DYNAKV_EINVAL;
   if (!ix->built) return DYNAKV_ESTATE;
-  return launch_export(ix->view, *dst, (hipStream_t)stream) == hipSuccess ? DYNAKV_OK : DYNAKV_EHIP;
+  hipStream_t st = (hipStream_t)stream;
+  if (launch_export(ix->view, *dst, st) != hipSuccess) return DYNAKV_EHIP;
+  // the sticky error words leave the device as a status here: this call waits for the stream
+  std::vector<int> err((size_t)ix->view.U, 0);
+  if (hipMemcpyAsync(err.data(), ix->view.err, err.size() * sizeof(int), hipMemcpyDeviceToHost, st) != hipSuccess) return DYNAKV_EHIP;
+  if (hipStreamSynchronize(st) != hipSuccess) return DYNAKV_EHIP;
+  for (int e : err)
+    if (e) return DYNAKV_ECAPACITY;
+  return DYNAKV_OK;
+}
+
+dynakv_status_t dynakv_import_state(dynakv_index_t* ix, const dynakv_state_t* src, void* stream) {
+  if (!ix || !src) return DYNAKV_EINVAL;
+  if (!src->n_clusters || !src->n_tokens || !src->tau || !src->centroids || !src->size || !src->buffered || !src->flag ||
+      !src->m2 || !src->offsets || !src->members || !src->keys || !src->values)
+    return DYNAKV_EINVAL;
+  if ((src->n_selected == nullptr) != (src->selected == nullptr)) return DYNAKV_EINVAL;
+  if (launch_import(ix->view, *src, (hipStream_t)stream) != hipSuccess) return DYNAKV_EHIP;
+  ix->built = true;
+  return DYNAKV_OK;
 }
 
 dynakv_status_t dynakv_profile_enable(dynakv_index_t* ix, int32_t max_launches) {
@@ -261,9 +289,10 @@ const char* dynakv_strerror(dynakv_status_t s) {
   switch (s) {
     case DYNAKV_OK: return "ok";
     case DYNAKV_EINVAL: return "invalid argument or unsupported size";
-    case DYNAKV_ECAPACITY: return "workspace too small";
+    case DYNAKV_ECAPACITY: return "capacity exhausted: workspace or static scratch too small, or a unit's error word is set (tokens, clusters, pages)";
     case DYNAKV_ESTATE: return "call out of order: build the index first";
     case DYNAKV_EHIP: return "HIP runtime error";
+    case DYNAKV_ENOMEM: return "out of host memory";
   }
   return "unknown status";
 }

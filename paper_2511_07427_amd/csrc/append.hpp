@@ -122,7 +122,7 @@ __device__ inline void append_commit(const View& v, int u, int j, int M, int N, 
         const double M2 = a.m2 + blocked16([&](int k) __attribute__((always_inline)) { return a.bs[k]; });
         const double var1 = M2 / (double)n1;
         bool trig = false;
-        if (n1 >= 2) {
+        if (n1 >= 2 && !v.static_update) {
           if (v.var_alpha > 0.f && var1 > a.tau) trig = true;
           if (v.size_factor > 0.f && (double)n1 * (double)M > (double)v.size_factor * (double)(N + 1)) trig = true;
         }

@@ -12,7 +12,10 @@ namespace dynakv {
 constexpr int kHeadDim = 128;
 constexpr int kPageTokens = 16;                 // tokens per page = one MFMA tile of rows
 constexpr int kPageElems = 2 * kPageTokens * kHeadDim;  // K region then V region
-constexpr int kMaxClusters = 8192;              // selection sorts one unit's clusters in LDS
+constexpr int kMaxClusters = 65536;             // cluster ids fit 16 bits
+constexpr int kMaxInitClusters = 8192;          // clusters built at prefill
+constexpr int kSelectLds = 8192;                // clusters whose scores and sizes the selection keeps in LDS; beyond,
+                                                // it reads them from memory in every pass
 constexpr int kMaxPrefill = 16384;              // k-means sorts one unit's labels in LDS
 constexpr int kFusedClusters = 4096;            // clusters per unit the single-kernel retrieval can hold in LDS
 constexpr int kMaxSplitMembers = 4096;          // largest cluster the split kernel handles
@@ -27,6 +30,9 @@ typedef float f4 __attribute__((ext_vector_type(4)));
 struct View {
   // configuration
   int U, G, dtype, M0, Mcap, Ncap, Pcap, Lcap, Bmax, group_reduce, S, NW, fuse;
+  int search_mean;   // the searches read the float32 means (always for float32 storage), else the 16-bit search copy
+  int score_round;   // float64 scores are rounded to float32 before they are compared
+  int static_update; // static-update baseline: nothing is ever flagged
   size_t Rstride;    // floats of centroid table per unit
   float var_alpha, size_factor, scale_f;
   double scale_d;
@@ -447,5 +453,6 @@ hipError_t launch_gather_attend(const View& v, const void* Q, float* out, float*
 hipError_t launch_append(const View& v, const void* k, const void* val, bool prescanned, bool split, hipStream_t st);
 hipError_t launch_split(const View& v, hipStream_t st);
 hipError_t launch_export(const View& v, const dynakv_state_t& dst, hipStream_t st);
+hipError_t launch_import(const View& v, const dynakv_state_t& src, hipStream_t st);
 
 }  // namespace dynakv

@@ -3,14 +3,31 @@
 // threshold, and the cluster-contiguous page layout (Section 5.1, intra-cluster placement,
 // kept here as the HBM layout).
 //
-// Every decision is taken on float64 squared distances accumulated left to right over the
-// coordinate index, ties to the lowest index; centroid sums run over members in ascending
-// position, so the result does not depend on how the work is spread over the machine.
+// Every label is the float64 nearest centre (ties to the lowest index): a matrix-core filter in
+// float32 settles the clear cases, every point within its error bound is re-assigned by an exact
+// float64 scan.  Centre sums are float64 sums over the members.
 #include "common.hpp"
 
 namespace dynakv {
 
 namespace {
+
+// One workgroup per unit, first kernel of a build: clears the unit's error word, then flags initial positions
+// that are out of range or given twice (the build still runs, with such a position clamped).
+__global__ __launch_bounds__(256) void kmeans_check_init_kernel(View v, int N0, const int* init_idx) {
+  __shared__ unsigned seen[kMaxPrefill / 32];
+  const int u = blockIdx.x, tid = threadIdx.x;
+  for (int i = tid; i < kMaxPrefill / 32; i += 256) seen[i] = 0u;
+  if (tid == 0) v.err[u] = 0;
+  __syncthreads();
+  bool bad = false;
+  for (int j = tid; j < v.M0; j += 256) {
+    const int p = init_idx[(size_t)u * v.M0 + j];
+    if (p < 0 || p >= N0) bad = true;
+    else if (atomicOr(&seen[p >> 5], 1u << (p & 31)) & (1u << (p & 31))) bad = true;
+  }
+  if (bad) atomicOr(&v.err[u], DYNAKV_ERR_INIT);
+}
 
 // R[u][j] = key at position init_idx[u][j]
 __global__ __launch_bounds__(128) void kmeans_init_kernel(View v, const void* X, int N0, const int* init_idx) {
@@ -541,7 +558,8 @@ __global__ __launch_bounds__(256) void point_dist_kernel(View v, const void* X, 
 // One workgroup per unit: per-cluster n, M2 (members in order), page chains, tau, counters.
 __global__ __launch_bounds__(1024) void finalize_kernel(View v, int N0) {
   __shared__ int sm[64];
-  __shared__ double m2s[kMaxClusters];          // M2 of every cluster, for the sum that gives tau
+  __shared__ double jsum[16];                   // per-wavefront sums of M2, for the objective that gives tau
+  static_assert(kMaxInitClusters <= 8 * 1024, "eight consecutive clusters per thread cover every initial cluster");
   const int u = blockIdx.x, tid = threadIdx.x;
   const int* koff = v.koff + (size_t)u * (v.Mcap + 1);
   const int* order = v.order + (size_t)u * v.Ncap;
@@ -573,8 +591,14 @@ __global__ __launch_bounds__(1024) void finalize_kernel(View v, int N0) {
     }
     v.cb[cb + j] = 0; v.cflag[cb + j] = 0; v.in_req[cb + j] = 0; v.score[cb + j] = 0.f;
   }
+  for (int j = 8 * 1024 + tid; j < v.Mcap; j += 1024) {          // slots that no thread's run of eight reaches
+    v.cn[cb + j] = 0; v.csz[cb + j] = 0; v.cM2[cb + j] = 0.0; v.ctail[cb + j] = -1;
+    for (int p = 0; p < kInlinePages; ++p) v.cpg[(cb + j) * kInlinePages + p] = -1;
+    v.cb[cb + j] = 0; v.cflag[cb + j] = 0; v.in_req[cb + j] = 0; v.score[cb + j] = 0.f;
+  }
   // M2 of cluster j = sum of its members' distances in storage order: one thread per cluster, eight members
   // requested at a time, added one by one
+  double jmine = 0.0;
   for (int j = tid; j < v.M0; j += 1024) {
     const int b = koff[j], e = koff[j + 1];
     double m2 = 0.0;
@@ -590,8 +614,10 @@ __global__ __launch_bounds__(1024) void finalize_kernel(View v, int N0) {
         if (q0 + k < e) m2 += x[k];
     }
     v.cM2[cb + j] = m2;
-    m2s[j] = m2;
+    jmine += m2;
   }
+  for (int o = 32; o > 0; o >>= 1) jmine += __shfl_xor(jmine, o);
+  if ((tid & 63) == 0) jsum[tid >> 6] = jmine;
   if (v.dtype != DYNAKV_F32) {               // search copy of the final centroids
     const float* R = unit_R(v, u);
     uint16_t* Rq = unit_Rq(v, u);
@@ -601,9 +627,9 @@ __global__ __launch_bounds__(1024) void finalize_kernel(View v, int N0) {
   __syncthreads();
   if (tid == 0) {
     double J = 0.0;
-    for (int j = 0; j < v.M0; ++j) J += m2s[j];
+    for (int w = 0; w < 16; ++w) J += jsum[w];
     v.tau[u] = (double)v.var_alpha * (J / (double)N0);
-    v.M[u] = v.M0; v.N[u] = N0; v.err[u] = 0; v.nflag[u] = 0; v.n_sel[u] = 0; v.t_sel[u] = 0; v.n_list[u] = 0;
+    v.M[u] = v.M0; v.N[u] = N0; v.nflag[u] = 0; v.n_sel[u] = 0; v.t_sel[u] = 0; v.n_list[u] = 0;
     v.ticket[u] = 0; v.bump[u] = total; v.free_top[u] = 0; v.last_assign[u] = -1;
     for (int k = 0; k < kCounters; ++k) v.counters[(size_t)u * kCounters + k] = 0;
   }
@@ -639,6 +665,7 @@ __global__ __launch_bounds__(256) void layout_copy_kernel(View v, const void* K,
 hipError_t launch_build_index(const View& v, const void* K, const void* V, int N0, const int* init_idx, int iters,
                               void* ws, size_t ws_bytes, hipStream_t st) {
   (void)ws; (void)ws_bytes;
+  kmeans_check_init_kernel<<<v.U, 256, 0, st>>>(v, N0, init_idx);
   kmeans_init_kernel<<<dim3(v.M0, v.U), 128, 0, st>>>(v, K, N0, init_idx);
   kmeans_range_kernel<<<dim3(16, v.U), 256, 0, st>>>(v, K, N0);
   int Npad = 2, pos_bits = 1;

@@ -96,6 +96,8 @@ __global__ __launch_bounds__(kSplitThreads) void split_kernel(View v) {
 }
 
 // ------------------------------------------------------------------------------------------- export
+// One workgroup per unit.  Clusters are dealt in runs of `ch` consecutive ids per thread, so that the member
+// lists come out cluster after cluster whatever the capacity.
 __global__ __launch_bounds__(1024) void export_kernel(View v, dynakv_state_t o) {
   __shared__ int sm[64];
   const int u = blockIdx.x, tid = threadIdx.x;
@@ -131,31 +133,46 @@ __global__ __launch_bounds__(1024) void export_kernel(View v, dynakv_state_t o) 
     }
   }
   // member lists
-  int sz[8], tot = 0;
-  for (int k = 0; k < 8; ++k) {
-    const int j = tid * 8 + k;
-    sz[k] = j < M ? v.cn[cbase + j] + v.cb[cbase + j] : 0;
-    tot += sz[k];
+  const int ch = (v.Mcap + 1023) / 1024;
+  int tot = 0;
+  for (int k = 0; k < ch; ++k) {
+    const int j = tid * ch + k;
+    if (j < M) tot += v.cn[cbase + j] + v.cb[cbase + j];
   }
   int total;
   int run = block_excl_scan(tot, sm, total);
-  for (int k = 0; k < 8; ++k) {
-    const int j = tid * 8 + k;
+  for (int k = 0; k < ch; ++k) {
+    const int j = tid * ch + k;
     if (j >= v.Mcap) break;
     if (o.offsets) o.offsets[(size_t)u * (v.Mcap + 1) + j] = j < M ? run : total;
-    if (j < M) { v.tok_off[cbase + j] = run; run += sz[k]; }
+    if (j < M) { v.tok_off[cbase + j] = run; run += v.cn[cbase + j] + v.cb[cbase + j]; }
   }
   if (tid == 0 && o.offsets) o.offsets[(size_t)u * (v.Mcap + 1) + v.Mcap] = total;
   __syncthreads();
-  if (o.members)
+  const int es = elem_size(v.dtype);
+  if (o.members || o.keys || o.values)
     for (int j = tid; j < M; j += 1024) {
       int w = v.tok_off[cbase + j], left = v.cn[cbase + j] + v.cb[cbase + j], page = -1;
       for (int k = 0; left > 0; ++k) {
         page = cluster_page(v, u, cbase + j, k, page);
         if (page < 0) break;
         const int nv = min(left, kPageTokens);
-        for (int sl = 0; sl < nv; ++sl)
-          o.members[(size_t)u * v.Ncap + w + sl] = v.ppos[((size_t)u * v.Pcap + page) * kPageTokens + sl];
+        const char* pg = page_ptr(v, u, page);
+        for (int sl = 0; sl < nv; ++sl) {
+          const int pos = v.ppos[((size_t)u * v.Pcap + page) * kPageTokens + sl];
+          if (o.members) o.members[(size_t)u * v.Ncap + w + sl] = pos;
+          const size_t row = ((size_t)u * v.Ncap + pos) * kHeadDim * es;
+          if (o.keys) {
+            const uint4* src = (const uint4*)(pg + (size_t)k_index(v.dtype, sl, 0) * es);
+            uint4* dst = (uint4*)((char*)o.keys + row);
+            for (int c = 0; c < kHeadDim * es / 16; ++c) dst[c] = src[c];
+          }
+          if (o.values) {
+            const uint4* src = (const uint4*)(pg + (size_t)v_index(v.dtype, sl, 0) * es);
+            uint4* dst = (uint4*)((char*)o.values + row);
+            for (int c = 0; c < kHeadDim * es / 16; ++c) dst[c] = src[c];
+          }
+        }
         w += nv; left -= nv;
       }
     }
@@ -168,6 +185,114 @@ __global__ __launch_bounds__(1024) void export_kernel(View v, dynakv_state_t o) 
         o.gathered[(size_t)u * v.Ncap + t0 + sl] = v.ppos[((size_t)u * v.Pcap + page) * kPageTokens + first + sl];
     }
   }
+}
+
+// ------------------------------------------------------------------------------------------- import
+// First kernel of an import, one workgroup per unit: checks the snapshot's sizes, then writes every record of
+// the unit (clusters, page chains, flagged list, active set, counters) and, for the copy kernel that follows,
+// the cluster and the place of every token (labels / order / koff / pg_off, the scratch arrays of the prefill).
+// v.nflagged[u] tells the copy kernel whether the unit was accepted.
+__global__ __launch_bounds__(1024) void import_meta_kernel(View v, dynakv_state_t s) {
+  __shared__ int sm[64];
+  __shared__ int s_bad, s_nflag;
+  const int u = blockIdx.x, tid = threadIdx.x;
+  const size_t cbase = (size_t)u * v.Mcap;
+  const int M = s.n_clusters[u], N = s.n_tokens[u];
+  const int* off = s.offsets + (size_t)u * (v.Mcap + 1);
+  const bool sane = M >= 1 && M <= v.Mcap && N >= 0 && N <= v.Ncap;
+  if (tid == 0) { s_bad = 0; s_nflag = 0; }
+  __syncthreads();
+  const int ch = sane ? (M + 1023) / 1024 : 0;
+  int tot = 0;
+  if (sane) {
+    if (tid == 0 && (off[0] != 0 || off[M] != N)) s_bad = 1;
+    for (int k = 0; k < ch; ++k) {
+      const int j = tid * ch + k;
+      if (j >= M) break;
+      const int n = s.size[cbase + j], b = s.buffered[cbase + j], m = off[j + 1] - off[j];
+      if (n < 0 || b < 0 || m != n + b || (b != 0 && s.flag[cbase + j] == 0)) s_bad = 1;
+      tot += (max(m, 0) + kPageTokens - 1) / kPageTokens;
+    }
+  }
+  int total;
+  int base = block_excl_scan(tot, sm, total);           // also the barrier behind s_bad
+  if (!sane || s_bad || total > v.Pcap) {
+    if (tid == 0) { atomicOr(&v.err[u], DYNAKV_ERR_IMPORT); v.nflagged[u] = 0; }
+    return;
+  }
+  const int* mem = s.members + (size_t)u * v.Ncap;
+  int* labels = v.labels + (size_t)u * v.Ncap;
+  int* order = v.order + (size_t)u * v.Ncap;
+  int* koff = v.koff + (size_t)u * (v.Mcap + 1);
+  for (int k = 0; k < ch; ++k) {
+    const int j = tid * ch + k;
+    if (j >= M) break;
+    const int m = off[j + 1] - off[j], np = (m + kPageTokens - 1) / kPageTokens;
+    v.cn[cbase + j] = s.size[cbase + j]; v.cb[cbase + j] = s.buffered[cbase + j]; v.csz[cbase + j] = m;
+    const int fl = s.flag[cbase + j] != 0;
+    v.cflag[cbase + j] = fl; v.cM2[cbase + j] = s.m2[cbase + j];
+    v.pg_off[cbase + j] = base; koff[j] = off[j];
+    for (int p = 0; p < kInlinePages; ++p) v.cpg[(cbase + j) * kInlinePages + p] = p < np ? base + p : -1;
+    v.ctail[cbase + j] = np ? base + np - 1 : -1;
+    for (int p = 0; p < np; ++p) v.pnext[(size_t)u * v.Pcap + base + p] = p + 1 < np ? base + p + 1 : -1;
+    if (fl) v.flist[cbase + atomicAdd(&s_nflag, 1)] = j;
+    for (int q = off[j]; q < off[j + 1]; ++q) {
+      const int pos = min(max(mem[q], 0), v.Ncap - 1);
+      order[q] = pos; labels[pos] = j;
+    }
+    base += np;
+  }
+  for (int j = tid; j < v.Mcap; j += 1024) {
+    v.in_req[cbase + j] = 0; v.score[cbase + j] = 0.f;
+    if (j >= M) {
+      v.cn[cbase + j] = 0; v.cb[cbase + j] = 0; v.csz[cbase + j] = 0; v.cflag[cbase + j] = 0; v.cM2[cbase + j] = 0.0;
+      v.ctail[cbase + j] = -1;
+      for (int p = 0; p < kInlinePages; ++p) v.cpg[(cbase + j) * kInlinePages + p] = -1;
+    }
+  }
+  for (size_t t = tid; t < (size_t)M * kHeadDim; t += 1024)
+    store_centroid(v, u, (int)(t >> 7), (int)(t & 127), s.centroids[cbase * kHeadDim + t]);
+  __syncthreads();
+  int nsel = 0;
+  if (s.selected) {
+    nsel = min(max(s.n_selected[u], 0), M);
+    for (int i = tid; i < nsel; i += 1024) {
+      const int id = min(max(s.selected[cbase + i], 0), M - 1);
+      v.sel_ids[cbase + i] = id; v.in_req[cbase + id] = 1;
+    }
+  }
+  if (tid == 0) {
+    koff[M] = N;
+    v.M[u] = M; v.N[u] = N; v.tau[u] = s.tau[u]; v.err[u] = 0; v.nflag[u] = s_nflag; v.n_sel[u] = nsel; v.t_sel[u] = 0;
+    v.n_list[u] = 0; v.ticket[u] = 0; v.bump[u] = total; v.free_top[u] = 0; v.last_assign[u] = -1;
+    for (int k = 0; k < kCounters; ++k) v.counters[(size_t)u * kCounters + k] = 0;
+    v.nflagged[u] = 1;
+  }
+}
+
+// 16 consecutive places of the storage order per workgroup, 16 threads per entry: keys and values move from
+// the snapshot (by position) into their cluster's pages as whole 16-byte chunks.
+__global__ __launch_bounds__(256) void import_copy_kernel(View v, const void* K, const void* V) {
+  const int u = blockIdx.y, q = blockIdx.x * 16 + (threadIdx.x >> 4), c = threadIdx.x & 15;
+  if (!v.nflagged[u] || q >= v.N[u]) return;
+  const int pos = v.order[(size_t)u * v.Ncap + q];
+  const int j = v.labels[(size_t)u * v.Ncap + pos];
+  const int rank = q - v.koff[(size_t)u * (v.Mcap + 1) + j];
+  const int page = v.pg_off[(size_t)u * v.Mcap + j] + rank / kPageTokens, slot = rank % kPageTokens;
+  char* pg = page_ptr(v, u, page);
+  const size_t src = ((size_t)u * v.Ncap + pos) * kHeadDim + c * 8;
+  if (v.dtype == DYNAKV_F32) {
+    const f4* ks = (const f4*)((const float*)K + src);
+    const f4* vs = (const f4*)((const float*)V + src);
+    *(f4*)((float*)pg + k_index32(slot, c * 8)) = ks[0];
+    *(f4*)((float*)pg + k_index32(slot, c * 8 + 4)) = ks[1];
+    *(f4*)((float*)pg + v_index32(slot, c * 8)) = vs[0];
+    *(f4*)((float*)pg + v_index32(slot, c * 8 + 4)) = vs[1];
+  } else {
+    *(uint4*)((uint16_t*)pg + k_index16(slot, c * 8)) = *(const uint4*)((const uint16_t*)K + src);
+    *(uint4*)((uint16_t*)pg + v_index16(slot, c * 8)) = *(const uint4*)((const uint16_t*)V + src);
+  }
+  if (c == 0) v.ppos[((size_t)u * v.Pcap + page) * kPageTokens + slot] = pos;
 }
 
 }  // namespace
@@ -194,6 +319,11 @@ hipError_t launch_split(const View& v, hipStream_t st) {
 }
 hipError_t launch_export(const View& v, const dynakv_state_t& dst, hipStream_t st) {
   export_kernel<<<v.U, 1024, 0, st>>>(v, dst);
+  return hipGetLastError();
+}
+hipError_t launch_import(const View& v, const dynakv_state_t& src, hipStream_t st) {
+  import_meta_kernel<<<v.U, 1024, 0, st>>>(v, src);
+  import_copy_kernel<<<dim3((v.Ncap + 15) / 16, v.U), 256, 0, st>>>(v, src.keys, src.values);
   return hipGetLastError();
 }
 

@@ -159,7 +159,7 @@ __device__ inline int emit_cluster(const View& v, int u, size_t cj, int take, in
 // sorted sizes, cut at the budget.  Same results as select_phase below.
 template <int NT>
 __device__ inline int select_sorted(const View& v, int u, int M, int budget, const SelectLds& s) {
-  constexpr int KCH = kMaxClusters / NT;      // consecutive ranks per thread in the prefix sums
+  constexpr int KCH = kSelectLds / NT;      // consecutive ranks per thread in the prefix sums
   const int tid = threadIdx.x;
   const size_t cb = (size_t)u * v.Mcap;
   uint32_t* skey = s.skey;
@@ -558,17 +558,17 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
 
 // One workgroup per unit.
 __global__ __launch_bounds__(1024) void select_kernel(View v, int budget) {
-  __shared__ uint32_t skey[kMaxClusters];
-  __shared__ __align__(16) unsigned char region[2 * kMaxClusters];
+  __shared__ uint32_t skey[kSelectLds];
+  __shared__ __align__(16) unsigned char region[2 * kSelectLds];
   __shared__ int hist[1024];
   __shared__ __align__(16) int sm[64];
   __shared__ int misc[8];
-  static_assert(2 * kMaxClusters >= kSelRegion, "candidate arrays must fit the id array");
+  static_assert(2 * kSelectLds >= kSelRegion, "candidate arrays must fit the id array");
   const int u = blockIdx.x, tid = threadIdx.x;
   const int M = v.M[u];
   int Mpad = 2;
   while (Mpad < M) Mpad <<= 1;
-  __shared__ int ssz[kMaxClusters];                 // cluster sizes: every pass of the selection reads them
+  __shared__ int ssz[kSelectLds];                 // cluster sizes: every pass of the selection reads them
   for (int i = tid; i < Mpad; i += 1024) {
     skey[i] = i < M ? orderable(v.score[(size_t)u * v.Mcap + i]) : 0u;
     if (i < M) ssz[i] = v.csz[(size_t)u * v.Mcap + i];
@@ -907,7 +907,9 @@ __global__ __launch_bounds__(NW * 64) void gather_attend_kernel(View v, const vo
   // to complete, the barrier collects the workgroup, then one thread takes the ticket
   __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
-  if (threadIdx.x == 0) s_last = atomicAdd(&v.ticket[u], 1) == S - 1;
+  // release: this workgroup's partial results happen before its ticket; acquire: the last arriver sees all of them
+  if (threadIdx.x == 0)
+    s_last = __hip_atomic_fetch_add(&v.ticket[u], 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT) == S - 1;
   __syncthreads();
   if (!s_last) return;
   const float* all = v.part + (size_t)u * S * ws;
@@ -1222,7 +1224,7 @@ void launch_ga_dt(const View& v, const void* Q, float* out, float* lse, hipStrea
 }  // namespace
 
 bool retrieve_is_fused(const View& v) {
-  return v.fuse && v.S == 1 && v.dtype != DYNAKV_F32 && v.Mcap <= kFusedClusters && v.G <= 8;
+  return v.fuse && v.S == 1 && !v.search_mean && v.Mcap <= kFusedClusters && v.G <= 8;
 }
 
 template <int DT, bool APPEND, bool SPLIT>
@@ -1251,7 +1253,7 @@ hipError_t launch_retrieve_fused(const View& v, const void* Q, int budget, float
 
 hipError_t launch_score_select(const View& v, const void* Q, int budget, const void* kin, hipStream_t st) {
   const dim3 grid((v.Mcap + 255) / 256, v.U);
-  static_assert(kMaxClusters <= kNearBlocks * 256, "one near_d / near_j entry per workgroup of the score kernel");
+  static_assert(kSelectLds <= kNearBlocks * 256, "one near_d / near_j entry per workgroup of the score kernel");
 #define DYNAKV_SCORE_G(GP, DT)                                                          \
   do {                                                                                  \
     if (kin) score_kernel<GP, DT, true><<<grid, 256, 0, st>>>(v, Q, kin);               \

@@ -26,6 +26,7 @@ struct SplitSmem {
   double dl[128];                                  // member distances of a staged cluster
   int scan[64];
   int flag, count, nchain;
+  int did_split;                                   // thread 0 only: the last split_cluster call split its cluster
   int M, nflag, a_top, a_bump;                     // the unit's counters, held here for the whole kernel
   double m2[2];
   alignas(16) unsigned char stage[kStageBytes];
@@ -302,6 +303,7 @@ __device__ __forceinline__ void split_cluster_impl(const View& v, int u, int j, 
     if (tid == 0) {
       v.cn[cbase + j] = m; v.csz[cbase + j] = m; v.cb[cbase + j] = 0; v.cflag[cbase + j] = 0; v.cM2[cbase + j] = s.m2[0];
       s.nflag -= 1;
+      s.did_split = 0;
       v.flist[cbase + pos] = v.flist[cbase + s.nflag];     // the last flagged id takes the freed place
       count(v, u, 1, 1);
     }
@@ -375,6 +377,7 @@ __device__ __forceinline__ void split_cluster_impl(const View& v, int u, int j, 
     s.a_top = top - from_free + s.nchain;
     s.a_bump = bump + (need - from_free);
     s.nflag -= 1;
+    s.did_split = 1;
     v.flist[cbase + pos] = v.flist[cbase + s.nflag];
     count(v, u, 0, 1);
   }
@@ -386,6 +389,7 @@ __device__ __forceinline__ void split_cluster(const View& v, int u, int j, int p
   const int tid = threadIdx.x;
   const size_t cbase = (size_t)u * v.Mcap;
   const int m = v.cn[cbase + j] + v.cb[cbase + j];
+  if (tid == 0) s.did_split = 0;
   if (m > kMaxSplitMembers) {
     if (tid == 0) v.err[u] |= DYNAKV_ERR_SPLIT_SIZE;
     return;
@@ -942,10 +946,13 @@ __device__ inline void split_assign(const View& v, int u, WaveCtx* wc, SplitPlan
   }
 }
 // One thread, once the n splits are committed and nothing reads the parents' pages any more: recycles them.
-__device__ inline void split_recycle(const View& v, int u, const WaveCtx* wc, SplitPlan& pl, int n) {
+// base: place of the first of them in the plan (a forced split is the plan's last entry and is counted as forced
+// only if it was carried out).
+__device__ inline void split_recycle(const View& v, int u, const WaveCtx* wc, SplitPlan& pl, int n, int base) {
   for (int w = 0; w < n; ++w) {
     const WaveCtx& cw = wc[ctx_of(w)];
     count(v, u, (cw.ok ? 0 : 1), 1);
+    if (cw.ok && pl.forced && base + w == pl.n_cand - 1) count(v, u, 2, 1);
     if (!cw.ok) continue;
     const int npg = (cw.m + kPageTokens - 1) / kPageTokens;
     for (int k = 0; k < npg; ++k) v.freelist[(size_t)u * v.Pcap + pl.top++] = cw.chain[k];
@@ -995,7 +1002,7 @@ __device__ __forceinline__ void split_unit(const View& v, int u, unsigned char* 
       const int wave = tid >> 6, lane = tid & 63;
       const int nc = pl.n_cand;
       if (npre > 0) {                      // committed by the caller
-        if (tid == 0) split_recycle(v, u, wc, pl, npre);
+        if (tid == 0) split_recycle(v, u, wc, pl, npre, 0);
         __syncthreads();
       }
       for (int base = npre; base < nc; base += kWaveSplits) {
@@ -1014,7 +1021,7 @@ __device__ __forceinline__ void split_unit(const View& v, int u, unsigned char* 
         __syncthreads();
         if (mine) wave_split_commit<DT>(v, u, c, vahead, true);
         __syncthreads();
-        if (tid == 0) split_recycle(v, u, wc, pl, n);            // the parents' pages are recycled only now
+        if (tid == 0) split_recycle(v, u, wc, pl, n, base);      // the parents' pages are recycled only now
         __syncthreads();
       }
       if (tid == 0 && nc > 0) {            // (no split: list and counters are as they were)
@@ -1023,7 +1030,6 @@ __device__ __forceinline__ void split_unit(const View& v, int u, unsigned char* 
         for (int i = 0; i < nf0; ++i)
           if (pl.id[i] >= 0) v.flist[cbase + n++] = pl.id[i];
         v.nflag[u] = n; v.M[u] = pl.M; v.free_top[u] = pl.top; v.bump[u] = pl.bump;
-        if (pl.forced) count(v, u, 2, 1);
       }
       return;
     }
@@ -1045,10 +1051,10 @@ __device__ __forceinline__ void split_unit(const View& v, int u, unsigned char* 
       __syncthreads();
       for (int i = tid; i < nf; i += NT) {
         const int c = v.flist[cbase + i];
-        if (c >= cursor && c < M0 && (v.Bmax == 0 || v.in_req[cbase + c])) atomicMin(&s_min, c * kMaxClusters + i);
+        if (c >= cursor && c < M0 && (v.Bmax == 0 || v.in_req[cbase + c])) atomicMin(&s_min, c);
       }
       __syncthreads();
-      if (s_min != 0x7FFFFFFF) { j = s_min / kMaxClusters; pos = s_min % kMaxClusters; }
+      if (s_min != 0x7FFFFFFF) j = s_min;
       __syncthreads();
       if (j >= 0) cursor = j + 1;
     }
@@ -1064,7 +1070,7 @@ __device__ __forceinline__ void split_unit(const View& v, int u, unsigned char* 
         const int c = v.flist[cbase + i];
         const int b = v.cb[cbase + c];
         tot += b;
-        if ((double)b > bv || ((double)b == bv && c * kMaxClusters + i < bi)) { bv = (double)b; bi = c * kMaxClusters + i; }
+        if ((double)b > bv || ((double)b == bv && c < bi)) { bv = (double)b; bi = c; }
       }
       if (tot) atomicAdd((unsigned long long*)&s_tot, (unsigned long long)tot);
       block_argmax(bv, bi, s.sv, s.si);
@@ -1072,10 +1078,18 @@ __device__ __forceinline__ void split_unit(const View& v, int u, unsigned char* 
       const long long total = s_tot;
       __syncthreads();
       if (!(arg >= 0 && total >= v.Bmax)) break;
-      if (tid == 0) count(v, u, 2, 1);
-      j = arg / kMaxClusters; pos = arg % kMaxClusters;
+      j = arg;
     }
+    // the cluster's place in the list of flagged clusters
+    if (tid == 0) s_min = -1;
+    __syncthreads();
+    for (int i = tid; i < nf; i += NT)
+      if (v.flist[cbase + i] == j) s_min = i;
+    __syncthreads();
+    pos = s_min;
+    __syncthreads();
     split_cluster<DT>(v, u, j, pos, s);
+    if (forced_done && tid == 0 && s.did_split) count(v, u, 2, 1);     // a forced split counts once carried out
     __syncthreads();
     if (forced_done) break;
   }
