@@ -138,6 +138,19 @@ dynakv_status_t dynakv_build_index(dynakv_index_t* index, const void* K, const v
 dynakv_status_t dynakv_retrieve_attend(dynakv_index_t* index, const void* Q, int32_t token_budget, float* out,
                                        float* lse, void* stream);
 
+/* dynakv_retrieve_attend for callers that cannot allocate device memory or hand over a workspace region for
+ * scratch (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same
+ * kernels and results, but the scratch of the split-KV gather + attention (every workgroup's partial sums,
+ * maxima and accumulators, and the arrival tickets of each unit) lives in a device array inside the library
+ * of DYNAKV_STATIC_SCRATCH_BYTES, which every GPU the library runs on holds until the process ends.  The call
+ * allocates nothing.  It needs n_units * kv_splits * group_size * 130 * 4 + n_units * 4 bytes; a configuration
+ * that needs more returns DYNAKV_ECAPACITY and enqueues nothing.  All calls on one GPU share the array: calls
+ * that overlap on one GPU (two streams, two indexes) race; what must start at zero is cleared by the call itself.
+ * Arguments as dynakv_retrieve_attend. */
+#define DYNAKV_STATIC_SCRATCH_BYTES (8u << 20)
+dynakv_status_t dynakv_retrieve_attend_static(dynakv_index_t* index, const void* Q, int32_t token_budget, float* out,
+                                              float* lse, void* stream);
+
 /* Adds one entry per unit (Algorithm 1, decode block: assign to the nearest cluster (squared distance to r~_j, see
  * dynakv_retrieve_attend), UpdateVar on the float32 mean, threshold test, then
  * AddEntry + UpdateStats or buffer + flag; Section 4.2).  The entry is always stored at the tail of its

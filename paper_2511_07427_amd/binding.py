@@ -86,6 +86,7 @@ def load():
         lib.dynakv_destroy.argtypes = [vp]
         lib.dynakv_build_index.argtypes = [vp, vp, vp, i32, vp, vp]
         lib.dynakv_retrieve_attend.argtypes = [vp, vp, i32, vp, vp, vp]
+        lib.dynakv_retrieve_attend_static.argtypes = [vp, vp, i32, vp, vp, vp]
         lib.dynakv_append.argtypes = [vp, vp, vp, vp]
         lib.dynakv_split.argtypes = [vp, vp]
         lib.dynakv_decode_step.argtypes = [vp, vp, i32, vp, vp, vp, vp, vp]
@@ -165,6 +166,18 @@ class Index:
         lp = _dev(lse, torch.float32, (c.n_units, c.group_size)) if lse is not None else None
         _check(self._lib.dynakv_retrieve_attend(self._h, qp, int(token_budget), op, lp, _stream()),
                "dynakv_retrieve_attend")
+
+    def dynakv_retrieve_attend_static(self, Q: torch.Tensor, token_budget: int, out: torch.Tensor, lse: torch.Tensor | None):
+        """The same retrieval with the split-KV scratch in the library's static device array; returns the status
+        (ECAPACITY if the configuration needs more scratch than the array holds) instead of raising on it."""
+        c = self.cfg
+        qp = _dev(Q, self._tdtype, (c.n_units, c.group_size, c.head_dim))
+        op = _dev(out, torch.float32, (c.n_units, c.group_size, c.head_dim))
+        lp = _dev(lse, torch.float32, (c.n_units, c.group_size)) if lse is not None else None
+        rc = self._lib.dynakv_retrieve_attend_static(self._h, qp, int(token_budget), op, lp, _stream())
+        if rc not in (OK, ECAPACITY):
+            _check(rc, "dynakv_retrieve_attend_static")
+        return rc
 
     def dynakv_append(self, k_new: torch.Tensor, v_new: torch.Tensor):
         c = self.cfg

@@ -1,6 +1,7 @@
 // Host side of the C ABI declared in include/dynakv.h: argument checks, the carving of the caller's
 // workspace into the arrays of `View`, and the kernel launches of every call.
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -173,18 +174,20 @@ dynakv_status_t dynakv_build_index(dynakv_index_t* ix, const void* K, const void
   return DYNAKV_OK;
 }
 
-// Retrieval, and with kin != null the append as well if one kernel can do both (*appended says whether it did),
-// and with `split` the due splits too (*appended then covers them).
-static dynakv_status_t retrieve_impl(dynakv_index_t* ix, const void* Q, int32_t token_budget, float* out, float* lse,
-                                     const void* kin, const void* vin, bool split, hipStream_t st, bool* appended) {
-  const bool fused = retrieve_is_fused(ix->view);
+// Retrieval on the index as `view` shows it (the index's own view, or one whose scratch arrays point elsewhere),
+// and with kin != null the append as well if one kernel can do both (*appended says whether it did), and with
+// `split` the due splits too (*appended then covers them).
+static dynakv_status_t retrieve_impl(dynakv_index_t* ix, const View& view, const void* Q, int32_t token_budget, float* out,
+                                     float* lse, const void* kin, const void* vin, bool split, hipStream_t st,
+                                     bool* appended) {
+  const bool fused = retrieve_is_fused(view);
   *appended = fused && kin;
-  if (!fused && launch_score_select(ix->view, Q, token_budget, kin, st) != hipSuccess) return DYNAKV_EHIP;
+  if (!fused && launch_score_select(view, Q, token_budget, kin, st) != hipSuccess) return DYNAKV_EHIP;
   const bool prof = ix->profiling && 2 * (ix->n_prof + 1) <= (int)ix->ev.size();
   if (prof && hipEventRecord(ix->ev[2 * ix->n_prof], st) != hipSuccess) return DYNAKV_EHIP;
   if (fused) {
-    if (launch_retrieve_fused(ix->view, Q, token_budget, out, lse, kin, vin, split, st) != hipSuccess) return DYNAKV_EHIP;
-  } else if (launch_gather_attend(ix->view, Q, out, lse, st) != hipSuccess) {
+    if (launch_retrieve_fused(view, Q, token_budget, out, lse, kin, vin, split, st) != hipSuccess) return DYNAKV_EHIP;
+  } else if (launch_gather_attend(view, Q, out, lse, st) != hipSuccess) {
     return DYNAKV_EHIP;
   }
   if (prof) {
@@ -199,7 +202,51 @@ dynakv_status_t dynakv_retrieve_attend(dynakv_index_t* ix, const void* Q, int32_
   if (!ix || !Q || !out || token_budget < 0) return DYNAKV_EINVAL;
   if (!ix->built) return DYNAKV_ESTATE;
   bool appended;
-  return retrieve_impl(ix, Q, token_budget, out, lse, nullptr, nullptr, false, (hipStream_t)stream, &appended);
+  return retrieve_impl(ix, ix->view, Q, token_budget, out, lse, nullptr, nullptr, false, (hipStream_t)stream, &appended);
+}
+
+// ---- retrieval for callers that cannot allocate ---------------------------------------------------
+// The scratch of the split-KV gather + attention (partial results of every workgroup and the arrival tickets)
+// in a file-scope device array instead of the caller's workspace.  Each GPU holds its own copy of the array at
+// its own address: the address is looked up once per device, with that device current, and kept.
+constexpr size_t kStaticScratchBytes = DYNAKV_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices];
+static std::mutex g_scratch_mutex;
+
+static hipError_t scratch_of_current_device(unsigned char** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = (unsigned char*)g_scratch_ptr[dev];
+  return hipSuccess;
+}
+
+dynakv_status_t dynakv_retrieve_attend_static(dynakv_index_t* ix, const void* Q, int32_t token_budget, float* out,
+                                              float* lse, void* stream) {
+  if (!ix || !Q || !out || token_budget < 0) return DYNAKV_EINVAL;
+  const View& v = ix->view;
+  const size_t part_bytes = ((size_t)v.U * v.S * v.G * (kHeadDim + 2) * sizeof(float) + 255) & ~(size_t)255;
+  const size_t ticket_bytes = (size_t)v.U * sizeof(int);
+  if (part_bytes + ticket_bytes > kStaticScratchBytes) return DYNAKV_ECAPACITY;
+  if (!ix->built) return DYNAKV_ESTATE;
+  unsigned char* base = nullptr;
+  if (scratch_of_current_device(&base) != hipSuccess) return DYNAKV_EHIP;
+  View vs = v;                       // the kernels take the scratch as they take the workspace's: through the view
+  vs.part = (float*)base;
+  vs.ticket = (int*)(base + part_bytes);   // reset by the selection of this very call before any workgroup takes one
+  bool appended;
+  return retrieve_impl(ix, vs, Q, token_budget, out, lse, nullptr, nullptr, false, (hipStream_t)stream, &appended);
 }
 
 dynakv_status_t dynakv_decode_step(dynakv_index_t* ix, const void* Q, int32_t token_budget, float* out, float* lse,
@@ -209,7 +256,7 @@ dynakv_status_t dynakv_decode_step(dynakv_index_t* ix, const void* Q, int32_t to
   hipStream_t st = (hipStream_t)stream;
   bool appended;
   const bool one_kernel = ix->view.fuse == 2;        // the splits too, where the retrieval kernel takes the append
-  const dynakv_status_t rc = retrieve_impl(ix, Q, token_budget, out, lse, k_new, v_new, one_kernel, st, &appended);
+  const dynakv_status_t rc = retrieve_impl(ix, ix->view, Q, token_budget, out, lse, k_new, v_new, one_kernel, st, &appended);
   if (rc != DYNAKV_OK) return rc;
   if (appended && one_kernel) return DYNAKV_OK;
   // separate kernels: the score kernel of this step has already looked for the new key's nearest cluster, and the
