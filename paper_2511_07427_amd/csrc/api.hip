@@ -103,10 +103,13 @@ size_t carve(const dynakv_config_t& c, char* base, View* out) {
     return p;
   };
   const size_t U = v.U, UM = U * v.Mcap, UP = U * v.Pcap, UN = U * v.Ncap;
+  v.search_mean = c.dtype == DYNAKV_F32 || c.search_copy == DYNAKV_SEARCH_MEAN;
   v.M = (int*)take(U * 4); v.N = (int*)take(U * 4); v.err = (int*)take(U * 4); v.tau = (double*)take(U * 8);
   v.nflag = (int*)take(U * 4); v.n_sel = (int*)take(U * 4); v.t_sel = (int*)take(U * 4); v.n_list = (int*)take(U * 4);
   v.ticket = (int*)take(U * 4); v.bump = (int*)take(U * 4); v.free_top = (int*)take(U * 4);
-  v.near_d = (double*)take(U * kNearBlocks * 8); v.near_j = (int*)take(U * kNearBlocks * 4);
+  v.NB = (v.Mcap + 255) / 256;
+  v.near_d = (double*)take(U * v.NB * 8); v.near_j = (int*)take(U * v.NB * 4);
+  v.zdist = (float*)take(v.search_mean ? 0 : UM * 4); v.rmax2 = (int*)take(U * 4);
   v.last_assign = (int*)take(U * 4); v.counters = (long long*)take(U * kCounters * 8);
   v.Rstride = r_stride(v.Mcap);
   v.R = (float*)take(U * v.Rstride * 4);

@@ -21,7 +21,6 @@ constexpr int kFusedClusters = 4096;            // clusters per unit the single-
 constexpr int kMaxSplitMembers = 4096;          // largest cluster the split kernel handles
 constexpr int kMaxKvSplits = 64;
 constexpr int kCounters = 8;
-constexpr int kNearBlocks = 32;                // blocks of 256 clusters in the largest index (8192 clusters)
 constexpr int kInlinePages = 8;                 // pages of a cluster found without walking its chain                // workgroups that share one unit's gathered pages
 
 typedef float f4 __attribute__((ext_vector_type(4)));
@@ -46,8 +45,12 @@ struct View {
   int* t_sel;        // [U] entries gathered by the last retrieval
   int* n_list;       // [U] entries in the gather list
   int* ticket;       // [U] arrival counter of the split-KV workgroups
-  double* near_d;    // [U][kNearBlocks] nearest cluster of the step's new key among clusters 256b .. 256b+255, left by
-  int* near_j;       //                  the score kernel of a whole decode step for the append that follows it
+  int NB;            // blocks of 256 clusters per unit (ceil(Mcap / 256))
+  double* near_d;    // [U][NB] float32 means only: nearest cluster of the step's new key among clusters 256b .. 256b+255,
+  int* near_j;       //         left by the score kernel of a whole decode step for the append that follows it
+  float* zdist;      // [U][Mcap] 16-bit search copy only: z_j = <k_new, r~_j> - |r~_j|^2 / 2 of the step's new key as the
+                     // matrix cores computed it (largest = nearest), for the append to pick from
+  int* rmax2;        // [U] bits of the largest |r~_j|^2 seen by a score pass since the index was built (a float >= 0)
   int* bump;         // [U] pages handed out from the pool so far
   int* free_top;     // [U] entries on the free-page stack
   int* last_assign;  // [U]
@@ -127,12 +130,17 @@ __host__ __device__ inline size_t r_stride(int Mcap) { return (size_t)((Mcap + 6
 __device__ inline float* unit_R(const View& v, int u) { return v.R + (size_t)u * v.Rstride; }
 
 // The representatives that a search reads (query similarity, Section 4.1; nearest cluster of a new entry,
-// Algorithm 1) are kept in the storage type of the keys, like the entries they stand for; the float32 table
-// above stays the master copy for the statistics.  16-bit copy: [tile of 64 clusters][d/8][64][8], 16 bytes per
-// lane and load, one block of the summation order per load.
+// Algorithm 1) are kept in the storage type of the keys, like the entries they stand for (unless the configuration
+// asks for the float32 means); the float32 table above stays the master copy for the statistics.  The 16-bit copy
+// is stored as the B operand of v_mfma_f32_16x16x32_{f16,bf16}: [tile of 16 clusters][chunk of 32 coordinates]
+// [lane][8], lane = 16 * (slice of 8 coordinates inside the chunk) + cluster inside the tile, so that lane l of a
+// wavefront reads its 16 bytes of chunk c of tile T at byte offset ((4 T + c) * 64 + l) * 16: 1 KB contiguous per
+// load, a whole tile (4 KB) per four loads.
 __host__ __device__ inline size_t rq_index(int j, int d) {
-  return ((size_t)(j >> 6) * (kHeadDim / 8) + (d >> 3)) * 512 + (size_t)(j & 63) * 8 + (d & 7);
+  return ((((size_t)(j >> 4) * 4 + (d >> 5)) * 64 + ((d >> 3) & 3) * 16 + (j & 15)) << 3) + (d & 7);
 }
+constexpr int kTileClusters = 16;                       // clusters per tile of the search copy
+constexpr int kTileElems = kTileClusters * kHeadDim;    // 16-bit elements per tile
 __device__ inline uint16_t* unit_Rq(const View& v, int u) { return v.Rq + (size_t)u * v.Rstride; }
 // float32 -> 16-bit storage type, round to nearest even; the bits.
 __device__ inline uint16_t round_bits16(float x, int dtype) {
@@ -239,79 +247,6 @@ __device__ __forceinline__ void centroid_sums(const float* R, int j, f4 (&cur)[8
 // ---- element access -----------------------------------------------------------------------------
 __device__ inline float bf16_to_float(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
 __device__ inline float f16_to_float(uint16_t h) { return (float)__builtin_bit_cast(_Float16, h); }
-
-// ---- the same sums over the 16-bit search copy ---------------------------------------------------
-// BF selects bfloat16; NR centroids (1 or 2) of one lane at once, j[r] each: term(d, values, acc) gets the NR
-// coordinate values and adds into acc[r][a].  One 16-byte load is one block of 8 coordinates; the next four
-// blocks are in flight while four are consumed.
-template <int NR>
-__device__ inline void load_search_head(const uint16_t* Rq, const int (&j)[NR], uint4 (&first)[NR][4]) {
-#pragma unroll
-  for (int r = 0; r < NR; ++r) {
-    const uint4* p = (const uint4*)(Rq + rq_index(j[r], 0));
-#pragma unroll
-    for (int i = 0; i < 4; ++i) first[r][i] = p[i * 64];
-  }
-}
-template <bool BF>
-__device__ __forceinline__ float half_at(const uint4& w, int e) {
-  const uint32_t ww = e < 2 ? w.x : e < 4 ? w.y : e < 6 ? w.z : w.w;
-  const uint16_t h = (uint16_t)(ww >> ((e & 1) * 16));
-  return BF ? bf16_to_float(h) : f16_to_float(h);
-}
-template <int NACC, int NR, bool BF, class F>
-__device__ __forceinline__ void search_batch(int b, const uint4 (&cur)[NR][4], double (&out)[NR][NACC], F&& term) {
-#pragma unroll
-  for (int k = 0; k < 4; ++k) {
-    double acc[NR][NACC];
-#pragma unroll
-    for (int r = 0; r < NR; ++r)
-#pragma unroll
-      for (int a = 0; a < NACC; ++a) acc[r][a] = 0.0;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      float x[NR];
-#pragma unroll
-      for (int r = 0; r < NR; ++r) x[r] = half_at<BF>(cur[r][k], e);
-      term(b * 32 + k * 8 + e, x, acc);
-    }
-#pragma unroll
-    for (int r = 0; r < NR; ++r)
-#pragma unroll
-      for (int a = 0; a < NACC; ++a) out[r][a] += acc[r][a];
-    __builtin_amdgcn_sched_barrier(0);   // keeps the operand loads of later blocks from piling up in registers
-  }
-}
-template <int NACC, int NR, bool BF, class F>
-__device__ __forceinline__ void search_sums(const uint16_t* Rq, const int (&j)[NR], uint4 (&cur)[NR][4],
-                                            double (&out)[NR][NACC], F&& term) {
-  const uint4* p[NR];
-#pragma unroll
-  for (int r = 0; r < NR; ++r) {
-    p[r] = (const uint4*)(Rq + rq_index(j[r], 0));
-#pragma unroll
-    for (int a = 0; a < NACC; ++a) out[r][a] = 0.0;
-  }
-#pragma unroll 1
-  for (int b = 0; b < 3; ++b) {
-    uint4 nxt[NR][4];
-#pragma unroll
-    for (int r = 0; r < NR; ++r)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) nxt[r][i] = p[r][((b + 1) * 4 + i) * 64];
-    search_batch<NACC, NR, BF>(b, cur, out, term);
-#pragma unroll
-    for (int r = 0; r < NR; ++r)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) cur[r][i] = nxt[r][i];
-  }
-  search_batch<NACC, NR, BF>(3, cur, out, term);
-  // the sums are complete here (see centroid_sums)
-#pragma unroll
-  for (int r = 0; r < NR; ++r)
-#pragma unroll
-    for (int a = 0; a < NACC; ++a) asm volatile("" : "+v"(out[r][a]));
-}
 
 // Element `i` of an array of the index's storage type, as float (exact).
 __device__ inline float load_elem(const void* base, size_t i, int dtype) {
@@ -445,6 +380,7 @@ hipError_t launch_build_index(const View& v, const void* K, const void* V, int n
 // kin != null: the scores' pass over the centroid table also leaves, per block of 256 clusters, the cluster nearest
 // to the new key `kin` (near_d / near_j), for launch_append(.., prescanned = true).
 hipError_t launch_score_select(const View& v, const void* Q, int budget, const void* kin, hipStream_t st);
+hipError_t launch_near(const View& v, const void* kin, hipStream_t st);
 bool retrieve_is_fused(const View& v);
 hipError_t launch_retrieve_fused(const View& v, const void* Q, int budget, float* out, float* lse, const void* kin,
                                  const void* vin, bool split, hipStream_t st);

@@ -7,14 +7,23 @@
 // One workgroup per unit; each unit's record is touched by that workgroup only.  All decisions are
 // taken on float64 values summed in the fixed order of common.hpp, ties to the lowest index.
 #include "split.hpp"
+#include "score.hpp"
 
 namespace dynakv {
 
 namespace {
 
 // ------------------------------------------------------------------------------------------- append
-// PRE: the score kernel of the same step has left the nearest cluster of every block of 256 clusters.
+// How the kernel finds the nearest cluster:
+//   kScanMean  its own float64 scan of the float32 means
+//   kPreMean   the score kernel of the same step has left the nearest cluster of every block of 256 clusters
+//              (float64, float32 means)
+//   kPreZ      a matrix-core pass (the score kernel of the same step, or a pass of its own launched before this
+//              kernel) has left z_j = <k, r~_j> - |r~_j|^2 / 2 of every cluster of the 16-bit search copy: the
+//              largest is taken if the runner-up lies beyond the float32 error bound, otherwise the clusters within
+//              the bound are compared in float64
 // SPLIT: the unit's due splits follow in the same launch (the rest of a decode step on the separate-kernel path).
+enum { kScanMean = 0, kPreMean = 1, kPreZ = 2 };
 template <bool ON>
 struct SplitLds {
   alignas(16) unsigned char raw[kSplitRaw];
@@ -22,27 +31,19 @@ struct SplitLds {
 };
 template <>
 struct SplitLds<false> {};
-template <int DT, bool PRE, bool SPLIT>
+template <int DT, int MODE, bool SPLIT>
 __global__ __launch_bounds__(256) void append_kernel(View v, const void* kin, const void* vin) {
   static_assert(kSplitThreads == 256, "split_unit is run by this kernel's whole workgroup");
   __shared__ AppendSmem a;
   __shared__ double sv[16];
   __shared__ int si[16];
+  __shared__ float s2[16];
   __shared__ SplitLds<SPLIT> sp;
   const int u = blockIdx.x, tid = threadIdx.x;
   const float* R = unit_R(v, u);
-  const uint16_t* Rq = unit_Rq(v, u);
   f4 row[8];
-  uint4 hrow[1][4];
-  double best = __builtin_inf();
-  int arg = -1;
-  if constexpr (PRE) {                                  // requested before anything else
-    if (tid < kNearBlocks) { best = v.near_d[(size_t)u * kNearBlocks + tid]; arg = v.near_j[(size_t)u * kNearBlocks + tid]; }
-  } else if ((size_t)(tid | 63) * kHeadDim < v.Rstride) {
-    const int js[1] = {tid};
-    if constexpr (DT == DYNAKV_F32) load_centroid_head(R, tid, row);
-    else load_search_head<1>(Rq, js, hrow);
-  }
+  if constexpr (MODE == kScanMean)
+    if ((size_t)(tid | 63) * kHeadDim < v.Rstride) load_centroid_head(R, tid, row);     // requested before anything else
   const int M = v.M[u], N = v.N[u];
   if (N >= v.Ncap || M <= 0) {                          // refused (workgroup-uniform); due splits still run
     if (tid == 0) v.err[u] |= DYNAKV_ERR_TOKENS;
@@ -52,33 +53,51 @@ __global__ __launch_bounds__(256) void append_kernel(View v, const void* kin, co
     }
     return;
   }
-  if (tid < kHeadDim) a.kd[tid] = (double)load_elem(kin, (size_t)u * kHeadDim + tid, v.dtype);
+  float k2 = 0.f;
+  if (tid < kHeadDim) {
+    const float kf = load_elem(kin, (size_t)u * kHeadDim + tid, v.dtype);
+    a.kd[tid] = (double)kf;
+    k2 = kf * kf;
+  }
   __syncthreads();
-  if constexpr (PRE) {
-    if (tid * 256 >= M) arg = -1;                       // blocks past the last cluster hold nothing of this step
+  int j;
+  if constexpr (MODE == kPreZ) {
+    for (int o = 32; o > 0; o >>= 1) k2 += __shfl_xor(k2, o);
+    if ((tid & 63) == 0) s2[tid >> 6] = k2;
+    __syncthreads();
+    const float kn = __builtin_sqrtf(s2[0] + s2[1]) * 1.0001f;
+    const float* zd = v.zdist + (size_t)u * v.Mcap;
+    float zb = -__builtin_inff(), z2 = -__builtin_inff();
+    int jb = -1;
+    for (int jj = tid; jj < M; jj += 256) {
+      const float z = zd[jj];
+      if (jb < 0 || z > zb) { z2 = jb < 0 ? z2 : zb; zb = z; jb = jj; }
+      else z2 = fmaxf(z2, z);
+    }
+    j = nearest_resolve<256>(v, u, M, zb, jb, z2, kn, __int_as_float(v.rmax2[u]), zd, unit_Rq(v, u), a.kd, sv, si, s2);
   } else {
-    // nearest centre (squared Euclidean distance); lane = cluster, 16 contiguous bytes per lane and load
-    for (int j = tid; j < M; j += 256) {
-      const int js[1] = {j};
-      double dist[1][1];
-      if constexpr (DT == DYNAKV_F32) {
-        if (j != tid) load_centroid_head(R, j, row);
-        centroid_sums<1>(R, j, row, dist[0], [&](int d, float rv, double (&acc)[1]) __attribute__((always_inline)) {
+    double best = __builtin_inf();
+    int arg = -1;
+    if constexpr (MODE == kPreMean) {
+      for (int b = tid; b * 256 < M; b += 256) {          // blocks past the last cluster hold nothing of this step
+        const double d = v.near_d[(size_t)u * v.NB + b];
+        const int jj = v.near_j[(size_t)u * v.NB + b];
+        if (arg < 0 || d < best || (d == best && jj < arg)) { best = d; arg = jj; }
+      }
+    } else {
+      // nearest centre (squared Euclidean distance); lane = cluster, 16 contiguous bytes per lane and load
+      for (int jj = tid; jj < M; jj += 256) {
+        double dist[1];
+        if (jj != tid) load_centroid_head(R, jj, row);
+        centroid_sums<1>(R, jj, row, dist, [&](int d, float rv, double (&acc)[1]) __attribute__((always_inline)) {
           const double t = a.kd[d] - (double)rv;
           acc[0] = fma(t, t, acc[0]);
         });
-      } else {
-        if (j != tid) load_search_head<1>(Rq, js, hrow);
-        search_sums<1, 1, DT == DYNAKV_BF16>(Rq, js, hrow, dist,
-            [&](int d, const float (&x)[1], double (&acc)[1][1]) __attribute__((always_inline)) {
-          const double t = a.kd[d] - (double)x[0];
-          acc[0][0] = fma(t, t, acc[0][0]);
-        });
+        if (dist[0] < best || arg < 0) { best = dist[0]; arg = jj; }
       }
-      if (dist[0][0] < best || arg < 0) { best = dist[0][0]; arg = j; }
     }
+    j = block_argmin<256>(best, arg, sv, si);
   }
-  const int j = block_argmin<256>(best, arg, sv, si);
   const AppendFetch f = append_fetch(v, u, j);
   append_commit<256>(v, u, j, M, N, kin, vin, a, f);
   if constexpr (SPLIT) {
@@ -297,18 +316,33 @@ __global__ __launch_bounds__(256) void import_copy_kernel(View v, const void* K,
 
 }  // namespace
 
+// prescanned: the score kernel of the same step has already looked at the new key (launch_score_select with kin).
+// Otherwise, with the 16-bit search copy, a matrix-core pass of its own comes first.
 hipError_t launch_append(const View& v, const void* k, const void* val, bool prescanned, bool split, hipStream_t st) {
-#define DYNAKV_APPEND(DT)                                                                    \
-  do {                                                                                       \
-    if (prescanned && split) append_kernel<DT, true, true><<<v.U, 256, 0, st>>>(v, k, val);  \
-    else if (prescanned) append_kernel<DT, true, false><<<v.U, 256, 0, st>>>(v, k, val);     \
-    else if (split) append_kernel<DT, false, true><<<v.U, 256, 0, st>>>(v, k, val);          \
-    else append_kernel<DT, false, false><<<v.U, 256, 0, st>>>(v, k, val);                    \
+  if (!v.search_mean && !prescanned) {
+    const hipError_t e = launch_near(v, k, st);
+    if (e != hipSuccess) return e;
+  }
+  const int mode = !v.search_mean ? kPreZ : prescanned ? kPreMean : kScanMean;
+#define DYNAKV_APPEND_M(DT, MODE)                                                         \
+  do {                                                                                     \
+    if (split) append_kernel<DT, MODE, true><<<v.U, 256, 0, st>>>(v, k, val);              \
+    else append_kernel<DT, MODE, false><<<v.U, 256, 0, st>>>(v, k, val);                   \
   } while (0)
-  if (v.dtype == DYNAKV_F32) DYNAKV_APPEND(DYNAKV_F32);
+#define DYNAKV_APPEND(DT)                                                                  \
+  do {                                                                                     \
+    if (mode == kPreZ) DYNAKV_APPEND_M(DT, kPreZ);                                         \
+    else if (mode == kPreMean) DYNAKV_APPEND_M(DT, kPreMean);                              \
+    else DYNAKV_APPEND_M(DT, kScanMean);                                                   \
+  } while (0)
+  if (v.dtype == DYNAKV_F32) {
+    if (prescanned) DYNAKV_APPEND_M(DYNAKV_F32, kPreMean);
+    else DYNAKV_APPEND_M(DYNAKV_F32, kScanMean);
+  }
   else if (v.dtype == DYNAKV_F16) DYNAKV_APPEND(DYNAKV_F16);
   else DYNAKV_APPEND(DYNAKV_BF16);
 #undef DYNAKV_APPEND
+#undef DYNAKV_APPEND_M
   return hipGetLastError();
 }
 hipError_t launch_split(const View& v, hipStream_t st) {

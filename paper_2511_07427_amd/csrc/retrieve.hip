@@ -10,17 +10,19 @@
 #include <type_traits>
 
 #include "split.hpp"
+#include "score.hpp"
 
 namespace dynakv {
 
 namespace {
 
 // ------------------------------------------------------------------------------------------- scores
-// Lane = cluster: the centroid table is lane-interleaved, so every load below is 1 KB contiguous per wavefront.
+// (a) float32 means (float32 storage, or a configuration that asks for them): float64 on the vector units.
+// Lane = cluster: the float32 table is lane-interleaved, so every load below is 1 KB contiguous per wavefront.
 // NEAR: the same pass also finds, per workgroup (256 clusters), the cluster nearest to the step's new key (one
-// more accumulator per centroid, the arithmetic of the append kernel's own scan) and leaves it in near_d / near_j.
-template <int GP, int DT, bool NEAR>
-__global__ __launch_bounds__(256) void score_kernel(View v, const void* Q, const void* kin) {
+// more accumulator per centroid) and leaves it in near_d / near_j.
+template <int GP, bool NEAR>
+__global__ __launch_bounds__(256) void score_mean_kernel(View v, const void* Q, const void* kin) {
   constexpr int NA = GP + (NEAR ? 1 : 0);
   __shared__ double qs[kHeadDim][GP];
   __shared__ double kd[NEAR ? kHeadDim : 1];
@@ -29,22 +31,11 @@ __global__ __launch_bounds__(256) void score_kernel(View v, const void* Q, const
   const int u = blockIdx.y, tid = threadIdx.x;
   const int j = blockIdx.x * 256 + tid;
   const float* R = unit_R(v, u);
-  const uint16_t* Rq = unit_Rq(v, u);
-  const int js[1] = {j};
-  // the first quarter of the row is requested before anything else (rows up to the table's padded end exist)
-  f4 row[8];
-  uint4 hrow[1][4];
-  const bool early = blockIdx.x * 256 < v.M0;        // these rows exist in every state: M never drops below M0
-  if (early) {
-    if constexpr (DT == DYNAKV_F32) load_centroid_head(R, j, row);
-    else load_search_head<1>(Rq, js, hrow);
-  }
   const int M = v.M[u];
   if (blockIdx.x * 256 >= M) return;
-  if (!early && (j & ~63) < M) {
-    if constexpr (DT == DYNAKV_F32) load_centroid_head(R, j, row);
-    else load_search_head<1>(Rq, js, hrow);
-  }
+  f4 row[8];
+  const bool live = (j & ~63) < M;                  // false: whole wavefront past the last cluster
+  if (live) load_centroid_head(R, j, row);
   for (int t = tid; t < GP * kHeadDim; t += 256) {
     const int g = t / kHeadDim, d = t % kHeadDim;
     qs[d][g] = g < v.G ? (double)load_elem(Q, ((size_t)u * v.G + g) * kHeadDim + d, v.dtype) : 0.0;
@@ -52,35 +43,18 @@ __global__ __launch_bounds__(256) void score_kernel(View v, const void* Q, const
   if constexpr (NEAR)
     if (tid < kHeadDim) kd[tid] = (double)load_elem(kin, (size_t)u * kHeadDim + tid, v.dtype);
   __syncthreads();
-  const bool live = (j & ~63) < M;                  // false: whole wavefront past the last cluster
   if (!NEAR && !live) return;
   double acc[NA];
   if (live) {
-    if constexpr (DT == DYNAKV_F32) {
-      centroid_sums<NA>(R, j, row, acc, [&](int d, float rv, double (&a)[NA]) __attribute__((always_inline)) {
-        const double rd = (double)rv;
+    centroid_sums<NA>(R, j, row, acc, [&](int d, float rv, double (&a)[NA]) __attribute__((always_inline)) {
+      const double rd = (double)rv;
 #pragma unroll
-        for (int g = 0; g < GP; ++g) a[g] = fma(qs[d][g], rd, a[g]);
-        if constexpr (NEAR) {
-          const double t = kd[d] - rd;
-          a[GP] = fma(t, t, a[GP]);
-        }
-      });
-    } else {
-      double acc1[1][NA];
-      search_sums<NA, 1, DT == DYNAKV_BF16>(Rq, js, hrow, acc1,
-          [&](int d, const float (&x)[1], double (&a)[1][NA]) __attribute__((always_inline)) {
-        const double rd = (double)x[0];
-#pragma unroll
-        for (int g = 0; g < GP; ++g) a[0][g] = fma(qs[d][g], rd, a[0][g]);
-        if constexpr (NEAR) {
-          const double t = kd[d] - rd;
-          a[0][GP] = fma(t, t, a[0][GP]);
-        }
-      });
-#pragma unroll
-      for (int a = 0; a < NA; ++a) acc[a] = acc1[0][a];
-    }
+      for (int g = 0; g < GP; ++g) a[g] = fma(qs[d][g], rd, a[g]);
+      if constexpr (NEAR) {
+        const double t = kd[d] - rd;
+        a[GP] = fma(t, t, a[GP]);
+      }
+    });
   }
   const bool mine = live && j < M;
   if (mine) {
@@ -94,10 +68,48 @@ __global__ __launch_bounds__(256) void score_kernel(View v, const void* Q, const
     const double dist = mine ? acc[NA - 1] : 0.0;
     const int jw = block_argmin<256>(dist, mine ? j : -1, am_v, am_i);
     if (mine && j == jw) {
-      v.near_d[(size_t)u * kNearBlocks + blockIdx.x] = dist;
-      v.near_j[(size_t)u * kNearBlocks + blockIdx.x] = j;
+      v.near_d[(size_t)u * v.NB + blockIdx.x] = dist;
+      v.near_j[(size_t)u * v.NB + blockIdx.x] = j;
     }
   }
+}
+
+// (b) 16-bit search copy: matrix cores.  grid (ceil(Mcap / 256), U), four wavefronts, four tiles of 16 clusters
+// each: 16 KB per wavefront in flight.  SCORES: rows 0..G-1 are the query heads and the scaled, group-reduced
+// scores go to v.score; NEAR: row G is the step's new key and z_j = <k, r~_j> - |r~_j|^2 / 2 goes to v.zdist for
+// the append kernel to pick the nearest cluster from.  The largest |r~_j|^2 is folded into v.rmax2.
+template <bool BF, int NBLK, bool SCORES, bool NEAR>
+__global__ __launch_bounds__(256) void score_mfma_kernel(View v, const void* Q, const void* kin) {
+  const int u = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const uint4* tiles = (const uint4*)unit_Rq(v, u);
+  const int t0 = blockIdx.x * 16 + wave * 4;
+  uint4 b[4][4];
+#pragma unroll
+  for (int t = 0; t < 4; ++t)            // rows up to the table's padded end exist: requested before M is known
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+      b[t][s] = (size_t)(t0 + t + 1) * kTileElems <= v.Rstride ? tiles[((size_t)(t0 + t) * 4 + s) * 64 + lane] : uint4{0, 0, 0, 0};
+  const int M = v.M[u];
+  if (t0 * kTileClusters >= M) return;
+  ScoreRows<NBLK> A;
+  load_score_rows<NBLK>(A, SCORES ? v.G : 0, Q, NEAR ? kin : nullptr, u, lane);
+  const int G = SCORES ? v.G : 0;
+  float rmax2 = 0.f;
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    if ((t0 + t) * kTileClusters >= M) break;
+    float red, kdot, nrm2;
+    score_tile<BF, NBLK, NEAR>(b[t], A, G, v.group_reduce, lane, red, kdot, nrm2);
+    const int j = (t0 + t) * kTileClusters + lane;
+    if (lane < kTileClusters && j < M) {
+      if constexpr (SCORES) v.score[(size_t)u * v.Mcap + j] = red * v.scale_f;
+      if constexpr (NEAR) v.zdist[(size_t)u * v.Mcap + j] = kdot - 0.5f * nrm2;
+      rmax2 = fmaxf(rmax2, nrm2);
+    }
+  }
+#pragma unroll
+  for (int o = 8; o > 0; o >>= 1) rmax2 = fmaxf(rmax2, __shfl_xor(rmax2, o));
+  if (lane == 0) atomicMax(&v.rmax2[u], __float_as_int(rmax2));      // non-negative floats order like their bits
 }
 
 // ------------------------------------------------------------------------------------------- selection
@@ -111,6 +123,18 @@ constexpr int kSelRegion = kCountMax * 12;   // bytes of candidate keys (8) and 
 
 // LDS of the selection.  `region` holds the candidates of the fast path (or the ids of the full sort) and
 // needs max(kSelRegion, 2 * Mpad) bytes; `list` receives the first `list_cap` gather-list entries.
+// What the selection needs to retake the budget cut in float64 (16-bit search copy only): eps = bound on the error
+// of a float32 score (0: scores are exact, nothing is retaken), Q = the queries.
+struct SelectExact {
+  float eps;
+  const void* Q;
+};
+constexpr int kBandMax = 64;        // clusters within the bound of the cut that are re-scored in float64
+
+__device__ inline float unorderable(uint32_t k) {
+  return __uint_as_float((k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k);
+}
+
 struct SelectLds {
   uint32_t* skey;          // [Mpad] orderable scores, padded with 0 up to the next power of two
   const int* sw;           // [M] stored sizes, or null: they are read from the workspace
@@ -302,8 +326,17 @@ __device__ __noinline__ int bin_candidates(int* hist, int* misc, int* lst, const
 // cluster then finds its rank and its gather offsets by counting the selected clusters that precede it.
 // first_ready: the caller has zeroed s.hist and set s.misc (entry 4 = 0x7fffffff, the others 0), has added every
 // cluster's size to bin (key >> 24) of the first histogram, and a barrier lies behind all of that.
+//
+// Scores computed in float32 on the matrix cores carry an error of at most ex.eps.  The cut that exact scores
+// would give lies within eps of the float32 one, so every cluster more than 2 eps above it is selected and every
+// cluster more than 2 eps below it is not, whatever the exact values; the clusters in between (the band, normally
+// the cluster at the cut alone) are re-scored in float64 by the first wavefront and taken in exact order while
+// they fit.  The selected SET is therefore that of exact arithmetic; the order of the selected clusters (the
+// gather order) follows the float32 scores.  Bands of more than kBandMax clusters (degenerate inputs: many equal
+// scores) and selections of more than kCountMax clusters are resolved on the float32 scores alone.
 template <int NT>
-__device__ inline int select_phase(const View& v, int u, int M, int budget, const SelectLds& s, bool first_ready = false) {
+__device__ inline int select_phase(const View& v, int u, int M, int budget, const SelectLds& s, const SelectExact& ex,
+                                   bool first_ready = false) {
   const int tid = threadIdx.x, lane = tid & 63;
   const size_t cb = (size_t)u * v.Mcap;
   unsigned long long* ck = (unsigned long long*)s.region;       // (score << 16) | (0xFFFF - id): larger goes first
@@ -358,10 +391,82 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
     above = __shfl(ab, src);
   }
 
+  // ---- the band around the cut, retaken in float64
+  bool refined = false;
+  uint32_t klo = 0, khi = 0;
+  int* const band = s.hist;                             // [kBandMax] ids; the histograms are dead
+  int* const bsz = s.hist + kBandMax;                   // [kBandMax] their sizes
+  int* const bmask = s.hist + 2 * kBandMax;             // [2] which of them are selected
+  double* const bex = (double*)(s.hist + 2 * kBandMax + 2);   // [kBandMax] their exact scores
+  if (cross && ex.eps > 0.f) {
+    __syncthreads();                                    // every wavefront has read the last histogram
+    const float astar = unorderable(kstar);
+    klo = orderable(astar - 2.f * ex.eps); khi = orderable(astar + 2.f * ex.eps);
+    for (int j = tid; j < M; j += NT) {
+      const uint32_t k = s.skey[j];
+      if (k >= klo && k <= khi) {
+        const int pos = atomicAdd(&s.misc[7], 1);
+        const int w = DYNAKV_WEIGHT(j);
+        if (pos < kBandMax) { band[pos] = j; bsz[pos] = w; }
+        if (k > kstar && w) atomicAdd(&s.misc[5], w);
+      }
+    }
+    __syncthreads();
+    const int nb = s.misc[7];
+    refined = nb > 1 && nb <= kBandMax;
+    if (refined) {
+      if (tid < 64) {
+        const uint16_t* Rq = unit_Rq(v, u);
+        for (int base = 0; base < nb; base += 16) {       // four lanes per cluster, 16 clusters at a time
+          const int m = base + (lane >> 2);
+          const double e = quad_exact_score(v, Rq, ex.Q, u, band[min(m, nb - 1)], lane & 3);
+          if ((lane & 3) == 0 && m < nb) bex[m] = e;
+        }
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_wave_barrier();
+        asm volatile("" ::: "memory");
+        const bool have = lane < nb;
+        const double e = have ? bex[lane] : 0.0;
+        const int jm = have ? band[lane] : 0x7fffffff, szm = have ? bsz[lane] : 0;
+        int rank = 0, cum = above - s.misc[5];            // sizes of everything above the band
+        for (int k = 0; k < nb; ++k) {
+          const double ek = bex[k];
+          const int jk = band[k];
+          if (ek > e || (ek == e && jk < jm)) { ++rank; cum += bsz[k]; }
+        }
+        int rstar = have && cum + szm > budget ? rank : nb;    // rank of the first cluster that does not fit
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) rstar = min(rstar, __shfl_xor(rstar, o));
+        const bool selb = have && rank < rstar;
+        const unsigned long long mask = __ballot(selb);
+        int tsb = selb ? szm : 0;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) tsb += __shfl_xor(tsb, o);
+        if (have && rank == 0) s.misc[4] = jm;            // the best of the band: cut to the budget if nothing fits
+        if (lane == 0) {
+          bmask[0] = (int)(unsigned)mask; bmask[1] = (int)(unsigned)(mask >> 32);
+          s.misc[5] = above - s.misc[5] + tsb;            // entries selected in all
+          count(v, u, 7, 1);
+        }
+      }
+      __syncthreads();
+    }
+  }
+
   // candidates: every score above kstar; the clusters at kstar are counted and resolved below
   for (int j = tid; j < M; j += NT) {
     const uint32_t k = s.skey[j];
-    if (cross && k == kstar) {
+    if (refined && k >= klo && k <= khi) {               // a cluster of the band: its float64 decision
+      bool sel = false;
+      const int nb = s.misc[7];
+      for (int i = 0; i < nb; ++i)
+        if (band[i] == j) sel = (((unsigned)bmask[i >> 5]) >> (i & 31)) & 1u;
+      v.in_req[cb + j] = sel;
+      if (sel) {
+        const int pos = atomicAdd(&s.misc[2], 1);
+        if (pos < kCountMax) { ck[pos] = ((unsigned long long)k << 16) | (unsigned)(0xFFFF - j); cw[pos] = DYNAKV_WEIGHT(j); }
+      }
+    } else if (cross && !refined && k == kstar) {
       atomicAdd(&s.misc[3], 1);
       atomicMin(&s.misc[4], j);
     } else {
@@ -375,7 +480,7 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
   }
   __syncthreads();
   int xid = s.misc[4], tie_w = 0;        // xid: the cluster at which the budget is first exceeded
-  if (cross && s.misc[3] > 1) {          // several equal scores at the cut: by ascending id while they fit
+  if (cross && !refined && s.misc[3] > 1) {          // several equal scores at the cut: by ascending id while they fit
     if (tid < 64) {
       int cum = above, x = -1;
       for (int base = 0; base < M && x < 0; base += 64) {
@@ -410,10 +515,10 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
         }
       }
     __syncthreads();
-  } else if (cross && tid == 0) {
+  } else if (cross && !refined && tid == 0) {
     v.in_req[cb + xid] = 0;
   }
-  int cut = s.misc[2], tsel = cross ? above + tie_w : total;
+  int cut = s.misc[2], tsel = !cross ? total : refined ? s.misc[5] : above + tie_w;
   if (cut > kCountMax) {
     __syncthreads();
     return select_sorted<NT>(v, u, M, budget, s);
@@ -556,13 +661,19 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
   return nlist;
 }
 
+// Bound on |float32 score - exact score| of a unit: float32 accumulation of 128 exact products, scaled.
+__device__ inline float score_eps(const View& v, float qbound, float rmax2) {
+  return kAccBound * v.scale_f * qbound * __builtin_sqrtf(rmax2) * 1.0002f * 1.01f;
+}
+
 // One workgroup per unit.
-__global__ __launch_bounds__(1024) void select_kernel(View v, int budget) {
+__global__ __launch_bounds__(1024) void select_kernel(View v, const void* Q, int budget) {
   __shared__ uint32_t skey[kSelectLds];
   __shared__ __align__(16) unsigned char region[2 * kSelectLds];
-  __shared__ int hist[1024];
+  __shared__ __align__(16) int hist[1024];
   __shared__ __align__(16) int sm[64];
   __shared__ int misc[8];
+  __shared__ float qn[16];
   static_assert(2 * kSelectLds >= kSelRegion, "candidate arrays must fit the id array");
   const int u = blockIdx.x, tid = threadIdx.x;
   const int M = v.M[u];
@@ -573,16 +684,31 @@ __global__ __launch_bounds__(1024) void select_kernel(View v, int budget) {
     skey[i] = i < M ? orderable(v.score[(size_t)u * v.Mcap + i]) : 0u;
     if (i < M) ssz[i] = v.csz[(size_t)u * v.Mcap + i];
   }
+  // |q_g| of every head, one wavefront per head (only where the scores came from the matrix cores)
+  SelectExact ex{0.f, Q};
+  if (!v.search_mean) {
+    const int g = tid >> 6, lane = tid & 63;
+    if (g < v.G) {
+      const float a = load_elem(Q, ((size_t)u * v.G + g) * kHeadDim + lane, v.dtype);
+      const float b = load_elem(Q, ((size_t)u * v.G + g) * kHeadDim + 64 + lane, v.dtype);
+      float s2 = a * a + b * b;
+      for (int o = 32; o > 0; o >>= 1) s2 += __shfl_xor(s2, o);
+      if (lane == 0) qn[g] = __builtin_sqrtf(s2) * 1.0001f;
+    }
+  }
   __syncthreads();
+  if (!v.search_mean) {
+    float qb = 0.f;
+    for (int g = 0; g < v.G; ++g) qb = v.group_reduce == DYNAKV_GROUP_MAX ? fmaxf(qb, qn[g]) : qb + qn[g];
+    ex.eps = score_eps(v, qb, __int_as_float(v.rmax2[u]));
+  }
   __shared__ int srt[kCountMax];
   const SelectLds s{skey, ssz, region, hist, srt, sm, misc, nullptr, 0};
-  select_phase<1024>(v, u, M, budget, s);
+  select_phase<1024>(v, u, M, budget, s, ex);
 }
 
 // ------------------------------------------------------------------------------------------- attention
-typedef _Float16 h8 __attribute__((ext_vector_type(8)));
 typedef _Float16 h4 __attribute__((ext_vector_type(4)));
-typedef __bf16 b8 __attribute__((ext_vector_type(8)));
 typedef short s4 __attribute__((ext_vector_type(4)));
 
 constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
@@ -959,10 +1085,11 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   static_assert(!SPLIT || kRawOff + kSplitRaw + 16 * 1024 <= 160 * 1024, "LDS of one compute unit");
   __shared__ __align__(16) unsigned char smem[SPLIT ? kRawOff + kSplitRaw : kPhases];
   __shared__ SplitWork wk;
-  __shared__ double qs[kHeadDim][GP];
   __shared__ AppendSmem ap;
   __shared__ double am_v[16];
   __shared__ int am_i[16];
+  __shared__ float am_2[16];
+  __shared__ int s_rmax2;
   __shared__ __align__(16) int sm[64];
   __shared__ int misc[8];
   uint32_t* skey = (uint32_t*)smem;
@@ -975,19 +1102,23 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   const int lane = tid & 63, wave = tid >> 6;
   const int G = v.G;
 
-  // ---- scores (float64).  The clusters are dealt in groups of 64 (one per lane): wavefront w takes the groups
-  // w, w + NW, w + 2 NW, ... and works on up to kAtOnce of them at once, so that the query operands it reads from
-  // LDS serve all of them and every wavefront gets the same number of groups to within one.
-  constexpr int kAtOnce = GP <= 4 ? 3 : 2;           // register budget: accumulators and rows in flight per lane
-  constexpr int NA = GP + (APPEND ? 1 : 0);
+  // ---- scores on the matrix cores.  Tiles of 16 clusters are dealt round-robin: wavefront w takes the tiles w,
+  // w + NW, ...; kBatch of them are consumed while the loads of the next kBatch are in flight (16 KB per wavefront).
+  constexpr bool BF = DT == DYNAKV_BF16;
+  constexpr int kBatch = 4;
   const uint16_t* Rq = unit_Rq(v, u);
-  // the first rows are requested before anything is waited for (rows up to the table's padded end exist)
-  uint4 e0 = {}, e1 = {}, e2 = {}, e3 = {};
-  const bool early = (size_t)(wave * 64 + 63) * kHeadDim < v.Rstride;
-  if (early) {
-    const uint4* p = (const uint4*)(Rq + rq_index(wave * 64 + lane, 0));
-    e0 = p[0]; e1 = p[64]; e2 = p[128]; e3 = p[192];
-  }
+  const uint4* tiles = (const uint4*)Rq;
+  const int table_tiles = (int)(v.Rstride / kTileElems);   // the table's padded end: these rows exist in every state
+  uint4 cur[kBatch][4], nxt[kBatch][4];
+  auto fetch = [&](uint4 (&dst)[kBatch][4], int t0) __attribute__((always_inline)) {
+#pragma unroll
+    for (int b = 0; b < kBatch; ++b) {
+      const int T = t0 + b * NW;
+#pragma unroll
+      for (int s2 = 0; s2 < 4; ++s2) dst[b][s2] = T < table_tiles ? tiles[((size_t)T * 4 + s2) * 64 + lane] : uint4{0, 0, 0, 0};
+    }
+  };
+  fetch(cur, wave);                                   // requested before anything is waited for
   // the flagged list and the free-page stack as they are before this step's append: the plan of the splits
   // starts from them
   int flagged0 = 0, nflag0 = 0, top0 = 0;            // kept in LDS (wk) until the selection is done
@@ -1005,10 +1136,8 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
     const int j = tid + k * NT;
     szr[k] = j < v.Mcap ? v.csz[(size_t)u * v.Mcap + j] : 0;
   }
-  for (int t = tid; t < GP * kHeadDim; t += NT) {
-    const int g = t / kHeadDim, d = t % kHeadDim;
-    qs[d][g] = g < G ? (double)load_elem(Q, ((size_t)u * G + g) * kHeadDim + d, v.dtype) : 0.0;
-  }
+  ScoreRows<1> A;
+  load_score_rows<1>(A, G, Q, APPEND ? kin : nullptr, u, lane);
   const int N = APPEND ? v.N[u] : 0;
   const bool room = APPEND && N < v.Ncap;              // otherwise the append is refused, as by the append kernel
   if (APPEND && tid < kHeadDim) ap.kd[tid] = (double)load_elem(kin, (size_t)u * kHeadDim + tid, v.dtype);
@@ -1017,96 +1146,71 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   for (int i = M + tid; i < Mpad; i += NT) skey[i] = 0u;
   for (int i = tid; i < 1024; i += NT) hist[i] = 0;
   if (tid < 8) misc[tid] = tid == 4 ? 0x7fffffff : 0;
-  // stored sizes: a thread scores exactly the clusters tid + k * NT, so each size goes through LDS from the thread
-  // that requested it to itself (and is there for the selection afterwards)
+  if (tid == 0) s_rmax2 = 0;
 #pragma unroll
   for (int k = 0; k < kFusedClusters / NT; ++k)
     if (tid + k * NT < M) ssz[tid + k * NT] = szr[k];
-  static_assert(NW * 64 == NT, "group g of wavefront w holds the clusters tid + (g / NW) * NT");
   if constexpr (SPLIT)
     if (wave == 0) {
       wk.flagged0[lane] = flagged0;
       if (lane == 0) { wk.nflag0 = nflag0; wk.top0 = top0; }
     }
+  const RowNorms rn = row_norms<BF, 1>(A, G, v.group_reduce, lane);
   __syncthreads();
-  double near_d = __builtin_inf();
-  int near_j = -1;
-  // NR groups of this wavefront from group g0 on, NW groups apart
-  auto score_groups = [&](auto nr_tag, int g0, bool first) __attribute__((always_inline)) {
-    constexpr int NR = decltype(nr_tag)::value;
-    int js[NR];
-    uint4 row[NR][4];
+  float zb = -__builtin_inff(), z2 = -__builtin_inff(), rmax2 = 0.f;
+  int jb = -1;
+  const int nctile = (M + kTileClusters - 1) / kTileClusters;
+  for (int t0 = wave; t0 < nctile; t0 += kBatch * NW) {
+    const bool more = t0 + kBatch * NW < nctile;
+    if (more) fetch(nxt, t0 + kBatch * NW);
 #pragma unroll
-    for (int r = 0; r < NR; ++r) {
-      js[r] = (g0 + r * NW) * 64 + lane;
-      if (r == 0 && first && early) {
-        row[0][0] = e0; row[0][1] = e1; row[0][2] = e2; row[0][3] = e3;
-      } else {
-        const uint4* p = (const uint4*)(Rq + rq_index(js[r], 0));
-#pragma unroll
-        for (int i = 0; i < 4; ++i) row[r][i] = p[i * 64];
-      }
-    }
-    double acc[NR][NA];
-    search_sums<NA, NR, DT == DYNAKV_BF16>(Rq, js, row, acc,
-        [&](int d, const float (&x)[NR], double (&a)[NR][NA]) __attribute__((always_inline)) {
-      double r64[NR];
-#pragma unroll
-      for (int r = 0; r < NR; ++r) r64[r] = (double)x[r];
-#pragma unroll
-      for (int g = 0; g < GP; ++g) {
-        const double qv = qs[d][g];
-#pragma unroll
-        for (int r = 0; r < NR; ++r) a[r][g] = fma(qv, r64[r], a[r][g]);
-      }
-      if constexpr (APPEND) {
-        const double kv = ap.kd[d];
-#pragma unroll
-        for (int r = 0; r < NR; ++r) {
-          const double t = kv - r64[r];
-          a[r][GP] = fma(t, t, a[r][GP]);
-        }
-      }
-    });
-#pragma unroll
-    for (int r = 0; r < NR; ++r) {
-      const int j = js[r];
-      if (j < M) {
-        if constexpr (APPEND)
-          if (acc[r][GP] < near_d || near_j < 0) { near_d = acc[r][GP]; near_j = j; }
-        double red = acc[r][0];
-#pragma unroll
-        for (int g = 1; g < GP; ++g)
-          if (g < G) red = v.group_reduce == DYNAKV_GROUP_MAX ? fmax(red, acc[r][g]) : red + acc[r][g];
-        const float sc = (float)(red * v.scale_d);
+    for (int b = 0; b < kBatch; ++b) {
+      const int T = t0 + b * NW;
+      if (T >= nctile) break;                          // wavefront-uniform
+      float red, kdot, nrm2;
+      score_tile<BF, 1, APPEND>(cur[b], A, G, v.group_reduce, lane, red, kdot, nrm2);
+      const int j = T * kTileClusters + lane;
+      if (lane < kTileClusters && j < M) {
+        const float sc = red * v.scale_f;
         v.score[(size_t)u * v.Mcap + j] = sc;
         const uint32_t key = orderable(sc);
         skey[j] = key;
         const int w = ssz[j];                          // first pass of the selection's radix search
         if (w) atomicAdd(&hist[key >> 24], w);
+        rmax2 = fmaxf(rmax2, nrm2);
+        if constexpr (APPEND) {
+          const float z = kdot - 0.5f * nrm2;
+          v.zdist[(size_t)u * v.Mcap + j] = z;
+          if (jb < 0 || z > zb) { z2 = jb < 0 ? z2 : zb; zb = z; jb = j; }     // ascending j per lane: the first maximum stays
+          else z2 = fmaxf(z2, z);
+        }
       }
     }
-  };
-  const int ngroup = (M + 63) >> 6;
-  for (int g0 = wave; g0 < ngroup; g0 += kAtOnce * NW) {
-    const int cnt = min(kAtOnce, (ngroup - g0 + NW - 1) / NW);      // wavefront-uniform
-    const bool first = g0 == wave;
-    if (cnt == 1) score_groups(std::integral_constant<int, 1>{}, g0, first);
-    else if (cnt == 2) score_groups(std::integral_constant<int, 2>{}, g0, first);
-    else if constexpr (kAtOnce == 3) score_groups(std::integral_constant<int, 3>{}, g0, first);
+    if (more) {
+#pragma unroll
+      for (int b = 0; b < kBatch; ++b)
+#pragma unroll
+        for (int s2 = 0; s2 < 4; ++s2) cur[b][s2] = nxt[b][s2];
+    }
   }
-  // the append's nearest cluster is known now: its record is requested here and used after the selection
+#pragma unroll
+  for (int o = 8; o > 0; o >>= 1) rmax2 = fmaxf(rmax2, __shfl_xor(rmax2, o));
+  if (lane == 0) atomicMax(&s_rmax2, __float_as_int(rmax2));
+  __syncthreads();                                    // scores, first histogram, z and the largest norm are in place
+  const float unit_rmax2 = __int_as_float(s_rmax2);
+  // the append's nearest cluster: its record is requested here and used after the selection
   int ja = -1;
   AppendFetch apf{0.0, 0, 0};
   if constexpr (APPEND) {
-    ja = block_argmin<NT>(near_d, near_j, am_v, am_i);
+    ja = nearest_resolve<NT>(v, u, M, zb, jb, z2, rn.kn, unit_rmax2, v.zdist + (size_t)u * v.Mcap, Rq, ap.kd, am_v, am_i, am_2);
     if (room) apf = append_fetch(v, u, ja);
   }
   __syncthreads();
 
   // ---- selection
   const SelectLds sel{skey, ssz, smem + kKeys + kSizes, hist, ssz, sm, misc, list, kFusedList};
-  const int nlist = select_phase<NT>(v, u, M, budget, sel, true);
+  const SelectExact ex{score_eps(v, rn.qbound, unit_rmax2), Q};
+  const int nlist = select_phase<NT>(v, u, M, budget, sel, ex, true);
   __syncthreads();
 
   // ---- the append (scores and selection saw the index as it was before); with SPLIT the first wavefront
@@ -1253,24 +1357,37 @@ hipError_t launch_retrieve_fused(const View& v, const void* Q, int budget, float
 
 hipError_t launch_score_select(const View& v, const void* Q, int budget, const void* kin, hipStream_t st) {
   const dim3 grid((v.Mcap + 255) / 256, v.U);
-  static_assert(kSelectLds <= kNearBlocks * 256, "one near_d / near_j entry per workgroup of the score kernel");
-#define DYNAKV_SCORE_G(GP, DT)                                                          \
+  if (v.search_mean) {
+#define DYNAKV_SCORE_G(GP)                                                              \
   do {                                                                                  \
-    if (kin) score_kernel<GP, DT, true><<<grid, 256, 0, st>>>(v, Q, kin);               \
-    else score_kernel<GP, DT, false><<<grid, 256, 0, st>>>(v, Q, nullptr);              \
+    if (kin) score_mean_kernel<GP, true><<<grid, 256, 0, st>>>(v, Q, kin);              \
+    else score_mean_kernel<GP, false><<<grid, 256, 0, st>>>(v, Q, nullptr);             \
   } while (0)
-#define DYNAKV_SCORE(DT)                               \
-  do {                                                 \
-    if (v.G <= 4) DYNAKV_SCORE_G(4, DT);               \
-    else if (v.G <= 8) DYNAKV_SCORE_G(8, DT);          \
-    else DYNAKV_SCORE_G(16, DT);                       \
-  } while (0)
-  if (v.dtype == DYNAKV_F32) DYNAKV_SCORE(DYNAKV_F32);
-  else if (v.dtype == DYNAKV_F16) DYNAKV_SCORE(DYNAKV_F16);
-  else DYNAKV_SCORE(DYNAKV_BF16);
-#undef DYNAKV_SCORE
+    if (v.G <= 4) DYNAKV_SCORE_G(4);
+    else if (v.G <= 8) DYNAKV_SCORE_G(8);
+    else DYNAKV_SCORE_G(16);
 #undef DYNAKV_SCORE_G
-  select_kernel<<<v.U, 1024, 0, st>>>(v, budget);
+  } else {
+    // G query heads and, with kin, the new key: one block of 16 rows, two if that makes 17
+#define DYNAKV_SCORE_B(BF, NBLK)                                                               \
+  do {                                                                                         \
+    if (kin) score_mfma_kernel<BF, NBLK, true, true><<<grid, 256, 0, st>>>(v, Q, kin);          \
+    else score_mfma_kernel<BF, NBLK, true, false><<<grid, 256, 0, st>>>(v, Q, nullptr);         \
+  } while (0)
+    const bool two = v.G + (kin ? 1 : 0) > 16;
+    if (v.dtype == DYNAKV_BF16) { if (two) DYNAKV_SCORE_B(true, 2); else DYNAKV_SCORE_B(true, 1); }
+    else { if (two) DYNAKV_SCORE_B(false, 2); else DYNAKV_SCORE_B(false, 1); }
+#undef DYNAKV_SCORE_B
+  }
+  select_kernel<<<v.U, 1024, 0, st>>>(v, Q, budget);
+  return hipGetLastError();
+}
+
+// The distances of a new key alone (an append outside a whole-step call, 16-bit search copy).
+hipError_t launch_near(const View& v, const void* kin, hipStream_t st) {
+  const dim3 grid((v.Mcap + 255) / 256, v.U);
+  if (v.dtype == DYNAKV_BF16) score_mfma_kernel<true, 1, false, true><<<grid, 256, 0, st>>>(v, nullptr, kin);
+  else score_mfma_kernel<false, 1, false, true><<<grid, 256, 0, st>>>(v, nullptr, kin);
   return hipGetLastError();
 }
 

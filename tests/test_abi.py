@@ -72,13 +72,14 @@ def test_create_and_call_order_errors(lib):
 def test_page_and_centroid_table_layouts_are_bijections():
     """The index formulas of csrc/common.hpp, retyped here only to check that they tile their arrays exactly once:
     a page (K rows, then V rows, one row of 128 per token slot) and the two lane-interleaved centroid tables
-    (float32 master [tile of 64][d/4][64][4], 16-bit search copy [tile of 64][d/8][64][8])."""
+    (float32 master [tile of 64][d/4][64][4]; 16-bit search copy in matrix-core operand order, [tile of 16][chunk of
+    32 coordinates][16 * slice of 8 + cluster][8])."""
     def k(s_, d): return s_ * 128 + d
     def v(s_, d): return 2048 + s_ * 128 + d
     idx = [f(s_, d) for f in (k, v) for s_ in range(16) for d in range(128)]
     assert sorted(idx) == list(range(4096))
     def r(j, d): return ((j >> 6) * 32 + (d >> 2)) * 256 + (j & 63) * 4 + (d & 3)
-    def rq(j, d): return ((j >> 6) * 16 + (d >> 3)) * 512 + (j & 63) * 8 + (d & 7)
+    def rq(j, d): return (((j >> 4) * 4 + (d >> 5)) * 64 + ((d >> 3) & 3) * 16 + (j & 15)) * 8 + (d & 7)
     for f in (r, rq):
         idx = [f(j, d) for j in range(192) for d in range(128)]
         assert sorted(idx) == list(range(192 * 128))
