@@ -20,24 +20,33 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_PEAK_TFLOPS = 2500.0      # dense fp16/bf16, published
 
-# HBM bytes per launch of the dominant kernel from two `rocprofv3 --pmc` runs of this file with its default
-# arguments (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch averaged over the timed launches), each scaled by what
-# the same counter reads for the float32 -> float16 copy of the 134 217 728-element prefill keys (512 MiB read,
-# 256 MiB written): FETCH_SIZE reads 262 166 KiB for it (factor 2.000), WRITE_SIZE 262 144 KiB (factor 1.000).
-# Only valid for exactly that workload; any other arguments report null.
-PMC_TRAFFIC = {("llama3_8b", 8192, 64, 0): {"fetch_kib": 107346.2, "fetch_scale": 524288.0 / 262165.9,
-                                            "write_kib": 7669.1, "write_scale": 1.0}}
+# HBM bytes per launch of the dominant kernel from two `rocprofv3 --pmc` runs of this file (FETCH_SIZE, then
+# WRITE_SIZE, KiB per dispatch averaged over the timed launches), each scaled by what the same counter reads for
+# torch's float32 -> float16 conversion of the 134 217 728-element prefill keys in the same run (512 MiB read,
+# 256 MiB written).  Keyed by (config, steps, warmup, units); "rev" is kernel_revision() of the sources the
+# counters were taken with: another revision of the kernels, or other arguments, report null.
+PMC_TRAFFIC = {}
 
 
-def cpu_baseline(spec, n_units, steps, budget):
-    """The oracle as it stands, on a bounded sample: `n_units` units, k-means prefill plus `steps` decode steps."""
+def kernel_revision() -> str:
+    """First 12 hex digits of the SHA-256 over the kernel sources: ties measured counters to the code they measured."""
+    import hashlib
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_2511_07427_amd", "csrc")
+    for f in sorted(os.listdir(d)):
+        with open(os.path.join(d, f), "rb") as fh:
+            h.update(f.encode() + b"\0" + fh.read())
+    return h.hexdigest()[:12]
+
+
+def _oracle_run(spec, n_units, steps, budget, threads):
     import numpy as np
     from oracle import Oracle, OracleConfig
     from paper_2511_07427_amd.workload import generate
     w = generate(spec, units=range(n_units), steps=steps)
     o = Oracle(OracleConfig(n_units, spec.group_size, spec.head_dim, spec.n_clusters_init, spec.max_clusters,
                             spec.prefill + steps, spec.kmeans_iters, spec.buffer_max, 0, spec.var_alpha,
-                            spec.size_factor, 0.0, dtype=spec.dtype))
+                            spec.size_factor, 0.0, dtype=spec.dtype), threads=threads)
     t0 = time.perf_counter()
     o.build_index(w["K0"], w["V0"], w["init_idx"])
     t1 = time.perf_counter()
@@ -46,11 +55,24 @@ def cpu_baseline(spec, n_units, steps, budget):
         o.append(w["Knew"][t], w["Vnew"][t])
         o.split()
     t2 = time.perf_counter()
-    whole_job = steps / ((t2 - t1) * spec.n_units / n_units)      # all units at this per-unit rate, same cores
-    return dict(value=whole_job, unit="decode steps/s", cores=o.threads_used, kind="oracle",
-                sample="%d of %d units, %d-token k-means prefill (%.1f s, not in value) then %d decode steps in %.1f s; "
-                       "scaled to all units" % (n_units, spec.n_units, spec.prefill, t1 - t0, steps, t2 - t1),
-                prefill_s_all_units=(t1 - t0) * spec.n_units / n_units)
+    return t1 - t0, t2 - t1, o.threads_used
+
+
+def cpu_baseline(spec, budget):
+    """The oracle as it stands on bounded samples of the same workload: k-means prefill plus decode steps of the
+    first units, once on all host threads and once on one; the rates are scaled to all units of the workload."""
+    cores = os.cpu_count() or 1
+    nu = min(spec.n_units, 32)
+    steps = 1536
+    pre, dec, used = _oracle_run(spec, nu, steps, budget, 0)
+    nu1, steps1 = min(spec.n_units, 2), 384
+    pre1, dec1, _ = _oracle_run(spec, nu1, steps1, budget, 1)
+    return dict(value=steps / (dec * spec.n_units / nu), unit="decode steps/s", cores=used, kind="oracle",
+                sample="%d of %d units, %d-token k-means prefill (%.1f s, not in value) then %d decode steps in %.1f s on %d "
+                       "threads; 1 thread: %d units, %d steps in %.1f s; rates scaled to all units" %
+                       (nu, spec.n_units, spec.prefill, pre, steps, dec, used, nu1, steps1, dec1),
+                value_1_thread=steps1 / (dec1 * spec.n_units / nu1), host_threads=cores,
+                prefill_s_all_units=pre * spec.n_units / nu, prefill_s_all_units_1_thread=pre1 * spec.n_units / nu1)
 
 
 def main():
@@ -65,6 +87,9 @@ def main():
     ap.add_argument("--max-cluster-factor", type=int, default=0,
                     help="max_clusters = FACTOR x the initial cluster count instead of the configuration's own factor "
                          "(long runs whose drift needs more clusters; above 4096 clusters the separate kernels run)")
+    ap.add_argument("--full-horizon", action="store_true",
+                    help="run the configuration to the end of its own decode length (steps = that length minus the "
+                         "warm-up) with the cluster capacity such a run needs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="skip the HIP events around the dominant kernel")
     a = ap.parse_args()
@@ -77,7 +102,11 @@ def main():
     from paper_2511_07427_amd import binding
     from paper_2511_07427_amd.workload import CONFIGS, generate
 
+    from paper_2511_07427_amd.workload import FULL_HORIZON_FACTOR
     spec = CONFIGS[a.config]
+    if a.full_horizon:
+        a.steps = spec.steps - a.warmup
+        spec = spec.scaled(max_cluster_factor=FULL_HORIZON_FACTOR[a.config])
     own_units = spec.n_units
     if a.units:
         spec = spec.scaled(n_units=a.units)
@@ -89,9 +118,13 @@ def main():
     tdt = binding.TORCH_DTYPES[spec.dtype]
     esz = 4 if spec.dtype == "f32" else 2
 
+    def say(msg):                      # progress on stderr: long runs must not look hung
+        print("[bench] " + msg, file=sys.stderr, flush=True)
+
     t0 = time.perf_counter()
     w = generate(spec, steps=T, workers=16)
     gen_s = time.perf_counter() - t0
+    say("inputs generated in %.1f s" % gen_s)
     K0 = torch.from_numpy(w["K0"]).to(dev).to(tdt)
     V0 = torch.from_numpy(w["V0"]).to(dev).to(tdt)
     init = torch.from_numpy(w["init_idx"]).to(dev)
@@ -104,6 +137,7 @@ def main():
         Kn[lo:hi] = torch.from_numpy(w["Knew"][lo:hi]).to(dev).to(tdt)
         Vn[lo:hi] = torch.from_numpy(w["Vnew"][lo:hi]).to(dev).to(tdt)
     del w
+    say("inputs resident in HBM")
 
     ix = binding.Index(binding.Config(U, G, spec.dtype, spec.n_clusters_init, spec.max_clusters, spec.prefill + T,
                                       spec.kmeans_iters, spec.buffer_max, 0, spec.var_alpha, spec.size_factor, 0.0), dev)
@@ -126,8 +160,12 @@ def main():
     qs, ks, os_, ls = Q.data_ptr(), Kn.data_ptr(), out.data_ptr(), lse.data_ptr()
     q_stride, k_stride = U * G * d * esz, U * d * esz
     step = ix.decode_step_ptrs
+    say("prefill %.2f ms" % prefill_ms)
     for t in range(a.warmup):
         step(qs + t * q_stride, spec.budget, os_, ls, ks + t * k_stride, Vn.data_ptr() + t * k_stride, stream)
+        if t % 8192 == 8191:
+            torch.cuda.synchronize()
+            say("warm-up step %d" % (t + 1))
     torch.cuda.synchronize()
     c0 = ix.dynakv_export_state(["counters"])["counters"].numpy().copy()
     if not a.no_kernel_events:
@@ -137,6 +175,8 @@ def main():
     t0 = time.perf_counter()
     for t in range(a.warmup, T):
         step(qs + t * q_stride, spec.budget, os_, ls, ks + t * k_stride, vs + t * k_stride, stream)
+        if (t & 16383) == 16383:
+            say("enqueued step %d" % (t + 1))           # no synchronisation inside the timed region
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     state = ix.dynakv_export_state(["counters", "error", "n_clusters", "n_tokens"])
@@ -161,10 +201,12 @@ def main():
         centroid_bytes = scored / a.steps * d * esz if kernel == "retrieve_fused_kernel" else 0.0   # search copy in the storage type, once
         bytes_per_launch = kv_bytes + centroid_bytes
         achieved = bytes_per_launch / (ms / n * 1e-3) / 1e9
-        pmc = PMC_TRAFFIC.get((a.config, a.steps, a.warmup, a.units)) if kernel == "retrieve_fused_kernel" else None
+        pmc = PMC_TRAFFIC.get((a.config, a.steps, a.warmup, a.units))
+        if pmc and (pmc["rev"] != kernel_revision() or pmc["kernel"] != kernel or a.max_cluster_factor or a.full_horizon):
+            pmc = None
         traffic = (pmc["fetch_kib"] * pmc["fetch_scale"] + pmc["write_kib"] * pmc["write_scale"]) * 1024.0 if pmc else None
         roof = dict(bound="hbm", kernel=kernel, achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=achieved / HBM_PEAK_GBS, traffic=traffic, avg_launch_us=ms / n * 1e3,
+                    frac=achieved / HBM_PEAK_GBS, traffic=traffic, kernel_rev=kernel_revision(), avg_launch_us=ms / n * 1e3,
                     algorithmic_bytes_per_launch=bytes_per_launch, kv_bytes_per_launch=kv_bytes,
                     centroid_bytes_per_launch=centroid_bytes, gathered_entries_per_unit=gathered / retrievals,
                     clusters_per_unit=scored / retrievals)
@@ -178,16 +220,17 @@ def main():
                                "token budget %d, at most %d clusters, decode steps %d..%d of a drifting %d-component mixture" %
                                (spec.name, U, "" if U == own_units else " INSTEAD OF THE CONFIGURATION'S %d" % own_units,
                                 G, d, spec.dtype, spec.prefill, spec.n_clusters_init, spec.budget, spec.max_clusters,
-                                a.warmup, T, spec.n_components),
-                   "kv_splits": ix and int(os.environ.get("DYNAKV_KV_SPLITS", "0")) or None},
+                                a.warmup, T, spec.n_components)},
         "roofline": roof,
         "prefill": {"ms": prefill_ms, "kmeans_algorithmic_tflops": kmeans_flop / (prefill_ms * 1e-3) / 1e12,
                     "frac_of_mfma_peak": kmeans_flop / (prefill_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS},
-        "index": {"clusters_mean": float(state["n_clusters"].float().mean()), "splits": int(c1[:, 0].sum()),
+        "index": {"clusters_mean": float(state["n_clusters"].float().mean()), "clusters_max": int(state["n_clusters"].max()),
+                  "splits": int(c1[:, 0].sum()),
                   "forced_splits": int(c1[:, 2].sum()), "input_generation_s": gen_s},
     }
     if not a.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline(spec, min(U, 32), 1536, spec.budget)
+        say("timing the oracle on the host")
+        res["cpu_baseline"] = cpu_baseline(spec, spec.budget)
     print(json.dumps(res), flush=True)
 
 

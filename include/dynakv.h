@@ -88,7 +88,7 @@ typedef struct {
   int32_t head_dim;        /* d; must be 128                                                    */
   int32_t dtype;           /* dynakv_dtype_t of K, V and Q                                      */
   int32_t n_clusters_init; /* M0, clusters built at prefill                                     */
-  int32_t max_clusters;    /* capacity per unit, splits included; M0..65536                     */
+  int32_t max_clusters;    /* capacity per unit, splits included; M0..131072                     */
   int32_t max_tokens;      /* capacity per unit                                                 */
   int32_t kmeans_iters;    /* Lloyd iterations at prefill, >= 1, no early exit                  */
   int32_t buffer_max;      /* B_max of Algorithm 1; 0 = every cluster counts as resident        */
@@ -174,7 +174,7 @@ dynakv_status_t dynakv_split(dynakv_index_t* index, void* stream);
  * this one can be mixed freely.  It exists because the step's two passes over the centroid table (query
  * similarity, Section 4.1; nearest cluster of the new key, Section 4.2) read the same data, and because a
  * step is a chain of short dependent phases: with 16-bit storage read through its 16-bit search copy, at most
- * 8192 clusters and at most 8 query heads per unit the whole step is ONE kernel launch that reads the table
+ * 4096 clusters and at most 8 query heads per unit the whole step is ONE kernel launch that reads the table
  * once, commits the append before it streams the selected pages, and prepares the due splits while it streams
  * them.  Otherwise (float32 storage or search copy, more clusters, more query heads) it is four launches
  * instead of the six of the three calls: the score kernel also evaluates the new key's distances, and the

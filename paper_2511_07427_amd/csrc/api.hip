@@ -28,8 +28,8 @@ bool config_ok(const dynakv_config_t* c) {
   if (c->n_units < 1 || c->group_size < 1 || c->group_size > 16 || c->head_dim != kHeadDim) return false;
   if (c->dtype != DYNAKV_F32 && c->dtype != DYNAKV_F16 && c->dtype != DYNAKV_BF16) return false;
   if (c->n_clusters_init < 1 || c->n_clusters_init > kMaxInitClusters) return false;
-  if (c->max_clusters < c->n_clusters_init || c->max_clusters > kSelectLds /* until the selection streams its keys */) return false;
-  if (c->max_tokens < c->n_clusters_init || c->max_tokens >= (1 << 24)) return false;
+  if (c->max_clusters < c->n_clusters_init || c->max_clusters > kMaxClusters) return false;
+  if (c->max_tokens < c->n_clusters_init || c->max_tokens >= (1 << 22)) return false;
   if (c->kmeans_iters < 1 || c->buffer_max < 0) return false;
   if (c->group_reduce != DYNAKV_GROUP_MAX && c->group_reduce != DYNAKV_GROUP_SUM) return false;
   if (c->softmax_scale < 0.f) return false;
@@ -110,6 +110,8 @@ size_t carve(const dynakv_config_t& c, char* base, View* out) {
   v.NB = (v.Mcap + 255) / 256;
   v.near_d = (double*)take(U * v.NB * 8); v.near_j = (int*)take(U * v.NB * 4);
   v.zdist = (float*)take(v.search_mean ? 0 : UM * 4); v.rmax2 = (int*)take(U * 4);
+  const size_t nw = v.search_mean ? 0 : U * v.NB * 4;
+  v.near_zb = (float*)take(nw * 4); v.near_z2 = (float*)take(nw * 4); v.near_zj = (int*)take(nw * 4);
   v.last_assign = (int*)take(U * 4); v.counters = (long long*)take(U * kCounters * 8);
   v.Rstride = r_stride(v.Mcap);
   v.R = (float*)take(U * v.Rstride * 4);

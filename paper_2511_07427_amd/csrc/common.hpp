@@ -12,7 +12,7 @@ namespace dynakv {
 constexpr int kHeadDim = 128;
 constexpr int kPageTokens = 16;                 // tokens per page = one MFMA tile of rows
 constexpr int kPageElems = 2 * kPageTokens * kHeadDim;  // K region then V region
-constexpr int kMaxClusters = 65536;             // cluster ids fit 16 bits
+constexpr int kMaxClusters = 131072;            // per unit (the selection packs an id into 18 bits)
 constexpr int kMaxInitClusters = 8192;          // clusters built at prefill
 constexpr int kSelectLds = 8192;                // clusters whose scores and sizes the selection keeps in LDS; beyond,
                                                 // it reads them from memory in every pass
@@ -48,6 +48,9 @@ struct View {
   int NB;            // blocks of 256 clusters per unit (ceil(Mcap / 256))
   double* near_d;    // [U][NB] float32 means only: nearest cluster of the step's new key among clusters 256b .. 256b+255,
   int* near_j;       //         left by the score kernel of a whole decode step for the append that follows it
+  float* near_zb;    // [U][4 NB] 16-bit search copy only: per wavefront of the score kernel (64 clusters), the largest z_j
+  float* near_z2;    //           of the step's new key, the second largest, and the cluster of the largest (< 0: none)
+  int* near_zj;
   float* zdist;      // [U][Mcap] 16-bit search copy only: z_j = <k_new, r~_j> - |r~_j|^2 / 2 of the step's new key as the
                      // matrix cores computed it (largest = nearest), for the append to pick from
   int* rmax2;        // [U] bits of the largest |r~_j|^2 seen by a score pass since the index was built (a float >= 0)

@@ -67,13 +67,11 @@ __global__ __launch_bounds__(256) void append_kernel(View v, const void* kin, co
     __syncthreads();
     const float kn = __builtin_sqrtf(s2[0] + s2[1]) * 1.0001f;
     const float* zd = v.zdist + (size_t)u * v.Mcap;
+    // the matrix-core pass has left best / runner-up per 64 clusters
     float zb = -__builtin_inff(), z2 = -__builtin_inff();
     int jb = -1;
-    for (int jj = tid; jj < M; jj += 256) {
-      const float z = zd[jj];
-      if (jb < 0 || z > zb) { z2 = jb < 0 ? z2 : zb; zb = z; jb = jj; }
-      else z2 = fmaxf(z2, z);
-    }
+    const size_t wbase = (size_t)u * v.NB * 4;
+    for (int w = tid; w * 64 < M; w += 256) merge_best2(zb, jb, z2, v.near_zb[wbase + w], v.near_zj[wbase + w], v.near_z2[wbase + w]);
     j = nearest_resolve<256>(v, u, M, zb, jb, z2, kn, __int_as_float(v.rmax2[u]), zd, unit_Rq(v, u), a.kd, sv, si, s2);
   } else {
     double best = __builtin_inf();

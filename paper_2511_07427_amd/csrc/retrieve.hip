@@ -84,17 +84,24 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(View v, const void* Q, 
   const uint4* tiles = (const uint4*)unit_Rq(v, u);
   const int t0 = blockIdx.x * 16 + wave * 4;
   uint4 b[4][4];
+  auto fetch = [&]() __attribute__((always_inline)) {
 #pragma unroll
-  for (int t = 0; t < 4; ++t)            // rows up to the table's padded end exist: requested before M is known
+    for (int t = 0; t < 4; ++t)
 #pragma unroll
-    for (int s = 0; s < 4; ++s)
-      b[t][s] = (size_t)(t0 + t + 1) * kTileElems <= v.Rstride ? tiles[((size_t)(t0 + t) * 4 + s) * 64 + lane] : uint4{0, 0, 0, 0};
+      for (int s = 0; s < 4; ++s)
+        b[t][s] = (size_t)(t0 + t + 1) * kTileElems <= v.Rstride ? tiles[((size_t)(t0 + t) * 4 + s) * 64 + lane] : uint4{0, 0, 0, 0};
+  };
+  // the first M0 clusters exist in every state (M never drops below M0): their rows are requested before M is known
+  const bool early = (t0 + 4) * kTileClusters <= v.M0;
+  if (early) fetch();
   const int M = v.M[u];
   if (t0 * kTileClusters >= M) return;
+  if (!early) fetch();
   ScoreRows<NBLK> A;
   load_score_rows<NBLK>(A, SCORES ? v.G : 0, Q, NEAR ? kin : nullptr, u, lane);
   const int G = SCORES ? v.G : 0;
-  float rmax2 = 0.f;
+  float rmax2 = 0.f, zb = -__builtin_inff(), z2 = -__builtin_inff();
+  int jb = -1;
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
     if ((t0 + t) * kTileClusters >= M) break;
@@ -103,8 +110,20 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(View v, const void* Q, 
     const int j = (t0 + t) * kTileClusters + lane;
     if (lane < kTileClusters && j < M) {
       if constexpr (SCORES) v.score[(size_t)u * v.Mcap + j] = red * v.scale_f;
-      if constexpr (NEAR) v.zdist[(size_t)u * v.Mcap + j] = kdot - 0.5f * nrm2;
+      if constexpr (NEAR) {
+        const float z = kdot - 0.5f * nrm2;
+        v.zdist[(size_t)u * v.Mcap + j] = z;
+        if (jb < 0 || z > zb) { z2 = jb < 0 ? z2 : zb; zb = z; jb = j; }
+        else z2 = fmaxf(z2, z);
+      }
       rmax2 = fmaxf(rmax2, nrm2);
+    }
+  }
+  if constexpr (NEAR) {             // this wavefront's 64 clusters: best, its cluster, runner-up
+    wave_best2(zb, jb, z2);
+    if (lane == 0) {
+      const size_t w = (size_t)u * v.NB * 4 + blockIdx.x * 4 + wave;
+      v.near_zb[w] = zb; v.near_z2[w] = z2; v.near_zj[w] = jb;
     }
   }
 #pragma unroll
@@ -118,6 +137,8 @@ __device__ inline uint32_t orderable(float f) {
   return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
 
+constexpr int kIdBits = 18, kIdMask = (1 << kIdBits) - 1;   // a candidate's key: score above, kIdMask - id below
+static_assert(kMaxClusters <= kIdMask + 1, "cluster ids must fit the candidate keys");
 constexpr int kCountMax = 1024;     // selected clusters ordered by counting; larger selections take the full sort
 constexpr int kSelRegion = kCountMax * 12;   // bytes of candidate keys (8) and sizes (4)
 
@@ -136,11 +157,12 @@ __device__ inline float unorderable(uint32_t k) {
 }
 
 struct SelectLds {
-  uint32_t* skey;          // [Mpad] orderable scores, padded with 0 up to the next power of two
+  uint32_t* skey;          // [Mpad] orderable scores, padded with 0 up to the next power of two; null: the scores are
+                           // read from the workspace in every pass (more clusters than LDS holds)
   const int* sw;           // [M] stored sizes, or null: they are read from the workspace
   unsigned char* region;
   int* hist;               // [4][256]
-  int* srt;                // [kCountMax] sizes in rank order; may alias sw, must not alias hist or list
+  int* srt;                // [CMAX] sizes in rank order; may alias sw, must not alias hist or list
   int* sm;                 // [64]
   int* misc;               // [8]
   int* list;
@@ -287,7 +309,7 @@ __device__ __noinline__ int bin_candidates(int* hist, int* misc, int* lst, const
   __syncthreads();
   uint32_t lo = 0xFFFFFFFFu, hi = 0u;
   for (int p = tid; p < cut; p += NT) {
-    const uint32_t k = (uint32_t)(ck[p] >> 16);
+    const uint32_t k = (uint32_t)(ck[p] >> kIdBits);
     lo = min(lo, k); hi = max(hi, k);
   }
 #pragma unroll
@@ -296,7 +318,7 @@ __device__ __noinline__ int bin_candidates(int* hist, int* misc, int* lst, const
   __syncthreads();
   const uint32_t differ = (uint32_t)misc[0] ^ (uint32_t)misc[1];
   const int shift = differ ? max(31 - __clz((int)differ) - 7, 0) : 0;
-  for (int p = tid; p < cut; p += NT) atomicAdd(&hist[((uint32_t)(ck[p] >> 16) >> shift) & 255u], 1);
+  for (int p = tid; p < cut; p += NT) atomicAdd(&hist[((uint32_t)(ck[p] >> kIdBits) >> shift) & 255u], 1);
   __syncthreads();
   if (tid < 64) {                      // lane l owns the bins 255 - 4l .. 252 - 4l, highest first
     int hv[4], t = 0;
@@ -313,11 +335,25 @@ __device__ __noinline__ int bin_candidates(int* hist, int* misc, int* lst, const
   }
   __syncthreads();
   for (int p = tid; p < cut; p += NT) {
-    const int d = ((uint32_t)(ck[p] >> 16) >> shift) & 255u;
+    const int d = ((uint32_t)(ck[p] >> kIdBits) >> shift) & 255u;
     lst[hist[256 + d] + atomicAdd(&hist[512 + d], 1)] = p;
   }
   __syncthreads();
   return shift;
+}
+
+// Calls f(j, key of cluster j) for the clusters j = tid, tid + NT, ... < M of the calling thread; four keys are
+// requested at a time, so that passes which read them from memory pay the latency once per four.
+template <int NT, class KeyAt, class F>
+__device__ __forceinline__ void for_each_key(int M, KeyAt&& key_at, F&& f) {
+  for (int j0 = threadIdx.x; j0 < M; j0 += 4 * NT) {
+    uint32_t kk[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) kk[i] = j0 + i * NT < M ? key_at(j0 + i * NT) : 0u;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (j0 + i * NT < M) f(j0 + i * NT, kk[i]);
+  }
 }
 
 // Only the selected clusters are ordered.  The score at which the running size first exceeds the budget is
@@ -334,14 +370,16 @@ __device__ __noinline__ int bin_candidates(int* hist, int* misc, int* lst, const
 // they fit.  The selected SET is therefore that of exact arithmetic; the order of the selected clusters (the
 // gather order) follows the float32 scores.  Bands of more than kBandMax clusters (degenerate inputs: many equal
 // scores) and selections of more than kCountMax clusters are resolved on the float32 scores alone.
-template <int NT>
+template <int NT, int CMAX = kCountMax>
 __device__ inline int select_phase(const View& v, int u, int M, int budget, const SelectLds& s, const SelectExact& ex,
                                    bool first_ready = false) {
   const int tid = threadIdx.x, lane = tid & 63;
   const size_t cb = (size_t)u * v.Mcap;
-  unsigned long long* ck = (unsigned long long*)s.region;       // (score << 16) | (0xFFFF - id): larger goes first
-  int* cw = (int*)(s.region + kCountMax * 8);
-#define DYNAKV_WEIGHT(j) (s.sw ? s.sw[j] : v.cn[cb + (j)] + v.cb[cb + (j)])
+  unsigned long long* ck = (unsigned long long*)s.region;       // (score << kIdBits) | (kIdMask - id): larger goes first
+  int* cw = (int*)(s.region + CMAX * 8);
+#define DYNAKV_WEIGHT(j) (s.sw ? s.sw[j] : v.csz[cb + (j)])
+#define DYNAKV_KEY(j) (s.skey ? s.skey[j] : orderable(v.score[cb + (j)]))
+  auto key_at = [&](int j) __attribute__((always_inline)) { return DYNAKV_KEY(j); };
   if (!first_ready) {
     for (int i = tid; i < 1024; i += NT) s.hist[i] = 0;
     if (tid < 8) s.misc[tid] = tid == 4 ? 0x7fffffff : 0;
@@ -355,13 +393,12 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
     const int shift = 24 - 8 * pass;
     int* h = s.hist + 256 * pass;
     if (pass > 0 || !first_ready) {
-      for (int j = tid; j < M; j += NT) {
-        const uint32_t k = s.skey[j];
+      for_each_key<NT>(M, key_at, [&](int j, uint32_t k) __attribute__((always_inline)) {
         if ((k & mask) == kstar) {
           const int w = DYNAKV_WEIGHT(j);
           if (w) atomicAdd(&h[(k >> shift) & 255], w);
         }
-      }
+      });
       __syncthreads();
     }
     // every wavefront: lane l owns the digits 255 - 4l .. 252 - 4l, highest first
@@ -402,15 +439,14 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
     __syncthreads();                                    // every wavefront has read the last histogram
     const float astar = unorderable(kstar);
     klo = orderable(astar - 2.f * ex.eps); khi = orderable(astar + 2.f * ex.eps);
-    for (int j = tid; j < M; j += NT) {
-      const uint32_t k = s.skey[j];
+    for_each_key<NT>(M, key_at, [&](int j, uint32_t k) __attribute__((always_inline)) {
       if (k >= klo && k <= khi) {
         const int pos = atomicAdd(&s.misc[7], 1);
         const int w = DYNAKV_WEIGHT(j);
         if (pos < kBandMax) { band[pos] = j; bsz[pos] = w; }
         if (k > kstar && w) atomicAdd(&s.misc[5], w);
       }
-    }
+    });
     __syncthreads();
     const int nb = s.misc[7];
     refined = nb > 1 && nb <= kBandMax;
@@ -454,8 +490,7 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
   }
 
   // candidates: every score above kstar; the clusters at kstar are counted and resolved below
-  for (int j = tid; j < M; j += NT) {
-    const uint32_t k = s.skey[j];
+  for_each_key<NT>(M, key_at, [&](int j, uint32_t k) __attribute__((always_inline)) {
     if (refined && k >= klo && k <= khi) {               // a cluster of the band: its float64 decision
       bool sel = false;
       const int nb = s.misc[7];
@@ -464,7 +499,7 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
       v.in_req[cb + j] = sel;
       if (sel) {
         const int pos = atomicAdd(&s.misc[2], 1);
-        if (pos < kCountMax) { ck[pos] = ((unsigned long long)k << 16) | (unsigned)(0xFFFF - j); cw[pos] = DYNAKV_WEIGHT(j); }
+        if (pos < CMAX) { ck[pos] = ((unsigned long long)k << kIdBits) | (unsigned)(kIdMask - j); cw[pos] = DYNAKV_WEIGHT(j); }
       }
     } else if (cross && !refined && k == kstar) {
       atomicAdd(&s.misc[3], 1);
@@ -474,10 +509,10 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
       v.in_req[cb + j] = sel;
       if (sel) {
         const int pos = atomicAdd(&s.misc[2], 1);
-        if (pos < kCountMax) { ck[pos] = ((unsigned long long)k << 16) | (unsigned)(0xFFFF - j); cw[pos] = DYNAKV_WEIGHT(j); }
+        if (pos < CMAX) { ck[pos] = ((unsigned long long)k << kIdBits) | (unsigned)(kIdMask - j); cw[pos] = DYNAKV_WEIGHT(j); }
       }
     }
-  }
+  });
   __syncthreads();
   int xid = s.misc[4], tie_w = 0;        // xid: the cluster at which the budget is first exceeded
   if (cross && !refined && s.misc[3] > 1) {          // several equal scores at the cut: by ascending id while they fit
@@ -485,7 +520,7 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
       int cum = above, x = -1;
       for (int base = 0; base < M && x < 0; base += 64) {
         const int j = base + lane;
-        const bool tie = j < M && s.skey[j] == kstar;
+        const bool tie = j < M && DYNAKV_KEY(j) == kstar;
         const int w = tie ? DYNAKV_WEIGHT(j) : 0;
         int inc = w;
         for (int o = 1; o < 64; o <<= 1) {
@@ -506,12 +541,12 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
     __syncthreads();
     xid = s.misc[4]; tie_w = s.misc[5];
     for (int j = tid; j < M; j += NT)
-      if (s.skey[j] == kstar) {
+      if (DYNAKV_KEY(j) == kstar) {
         const bool sel = j < xid;
         v.in_req[cb + j] = sel;
         if (sel) {
           const int pos = atomicAdd(&s.misc[2], 1);
-          if (pos < kCountMax) { ck[pos] = ((unsigned long long)kstar << 16) | (unsigned)(0xFFFF - j); cw[pos] = DYNAKV_WEIGHT(j); }
+          if (pos < CMAX) { ck[pos] = ((unsigned long long)kstar << kIdBits) | (unsigned)(kIdMask - j); cw[pos] = DYNAKV_WEIGHT(j); }
         }
       }
     __syncthreads();
@@ -519,13 +554,18 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
     v.in_req[cb + xid] = 0;
   }
   int cut = s.misc[2], tsel = !cross ? total : refined ? s.misc[5] : above + tie_w;
-  if (cut > kCountMax) {
+  if (cut > CMAX) {
     __syncthreads();
-    return select_sorted<NT>(v, u, M, budget, s);
+    if (s.skey) return select_sorted<NT>(v, u, M, budget, s);
+    // keys are not in LDS (more than kSelectLds clusters) and more clusters are selected than can be ordered:
+    // the retrieval is cut short to the CMAX candidates at hand and the unit's error word says so
+    if (tid == 0) atomicOr(&v.err[u], DYNAKV_ERR_SELECT);
+    cut = CMAX;
+    tsel = -1;                                          // recomputed from the sizes below
   }
   if (cross && cut == 0 && budget > 0) {           // the best cluster alone is over budget: its first entries
     if (tid == 0) {
-      ck[0] = ((unsigned long long)kstar << 16) | (unsigned)(0xFFFF - xid);
+      ck[0] = ((unsigned long long)kstar << kIdBits) | (unsigned)(kIdMask - xid);
       cw[0] = budget;
       v.in_req[cb + xid] = 1;
     }
@@ -536,7 +576,7 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
   // rank of every selected cluster = number of selected clusters that precede it.  While the workgroup has
   // several threads per selected cluster, `tpc` adjacent lanes share one cluster's count (and the first of them
   // goes on as its owner).
-  constexpr int PER = (kCountMax + NT - 1) / NT;
+  constexpr int PER = (CMAX + NT - 1) / NT;
   int tpc = 1, tsh = 0;
   while (tpc < 8 && cut * tpc * 2 <= NT) { tpc <<= 1; ++tsh; }
   // Many selected clusters: counting against all of them costs cut^2 LDS reads; they are binned first
@@ -561,7 +601,7 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
     if (p < cut && (r == 0 || tpc == 1)) {              // wavefront-uniform per group of tpc lanes
       const unsigned long long my = ck[p];
       {   // the cluster's page table is requested now and used once its place in the list is known
-        const int id = 0xFFFF - (int)(my & 0xFFFF);
+        const int id = kIdMask - (int)(my & kIdMask);
         const int4* row = (const int4*)&v.cpg[(cb + id) * kInlinePages];
         const int4 a = row[0];
         pg[r][0] = a.x; pg[r][1] = a.y; pg[r][2] = a.z; pg[r][3] = a.w;
@@ -572,7 +612,7 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
       }
       int rank = 0;
       if (__builtin_expect(binned, 0)) {
-        const int d = ((uint32_t)(my >> 16) >> bin_shift) & 255u;
+        const int d = ((uint32_t)(my >> kIdBits) >> bin_shift) & 255u;
         const int b0 = s.hist[256 + d], b1 = b0 + s.hist[d];
         rank = b0;
         for (int q = b0; q < b1; ++q) rank += ck[lst[q]] > my ? 1 : 0;
@@ -588,7 +628,7 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
       }
       if (r == 0)
         for (int o = 1; o < tpc; o <<= 1) rank += __shfl_xor(rank, o);
-      if (r != 0 || sub == 0) { rk[r] = rank; idw[r] = 0xFFFF - (int)(my & 0xFFFF); wt[r] = cw[p]; }
+      if (r != 0 || sub == 0) { rk[r] = rank; idw[r] = kIdMask - (int)(my & kIdMask); wt[r] = cw[p]; }
     }
   }
   __syncthreads();
@@ -617,10 +657,11 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
   for (int k = 0; k < PER; ++k) {
     const int r = tid * PER + k;
     if (r < cut)      // id, first gather offset, first list entry
-      ck[r] = ((unsigned long long)by_id[r] << 48) | ((pre & 0xFFFFFFu) << 24) | ((pre >> 32) & 0xFFFFFFu);
+      ck[r] = ((unsigned long long)by_id[r] << 46) | ((pre & 0xFFFFFFu) << 22) | ((pre >> 32) & 0x3FFFFFu);   // 18 + 24 + 22 bits
     pre += loc[k];
   }
   const int quads = tid == 0 ? (int)(total64 >> 32) : 0;
+  if (tsel < 0) tsel = (int)(total64 & 0xFFFFFFFFull);
   __syncthreads();
   // list entries, by the thread that ranked the cluster (every page but the last is full, so a page's place in
   // the list follows from its index); pages past the inline table are found by walking the chain
@@ -630,7 +671,7 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
   for (int r = 0; r < PER; ++r) {
     if (rk[r] < 0) continue;
     const unsigned long long pk = ck[rk[r]];
-    const int t0 = (int)(pk >> 24) & 0xFFFFFF, q0 = (int)pk & 0xFFFFFF;
+    const int t0 = (int)(pk >> 22) & 0xFFFFFF, q0 = (int)pk & 0x3FFFFF;
     const int take = wt[r], npages = (take + kPageTokens - 1) / kPageTokens;
     int page = -1;
 #pragma unroll
@@ -658,6 +699,7 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
     count(v, u, 6, M);
   }
 #undef DYNAKV_WEIGHT
+#undef DYNAKV_KEY
   return nlist;
 }
 
@@ -666,23 +708,32 @@ __device__ inline float score_eps(const View& v, float qbound, float rmax2) {
   return kAccBound * v.scale_f * qbound * __builtin_sqrtf(rmax2) * 1.0002f * 1.01f;
 }
 
-// One workgroup per unit.
+// One workgroup per unit.  BIG: more than kSelectLds clusters per unit: scores and sizes stay in the workspace (they
+// are a few hundred KB per unit and sit in L2 after the score kernel) and are read in every pass; the LDS goes to
+// a larger candidate list instead.
+constexpr int kCountBig = 4096;
+template <bool BIG>
 __global__ __launch_bounds__(1024) void select_kernel(View v, const void* Q, int budget) {
-  __shared__ uint32_t skey[kSelectLds];
-  __shared__ __align__(16) unsigned char region[2 * kSelectLds];
+  constexpr int CMAX = BIG ? kCountBig : kCountMax;
+  constexpr int kRegion = BIG ? CMAX * 12 : 2 * kSelectLds;
+  __shared__ uint32_t skey_[BIG ? 1 : kSelectLds];
+  __shared__ int ssz_[BIG ? 1 : kSelectLds];                 // cluster sizes: every pass of the selection reads them
+  __shared__ __align__(16) unsigned char region[kRegion];
   __shared__ __align__(16) int hist[1024];
   __shared__ __align__(16) int sm[64];
   __shared__ int misc[8];
   __shared__ float qn[16];
-  static_assert(2 * kSelectLds >= kSelRegion, "candidate arrays must fit the id array");
+  __shared__ int srt[CMAX];
+  static_assert(kRegion >= CMAX * 12, "candidate arrays must fit");
   const int u = blockIdx.x, tid = threadIdx.x;
   const int M = v.M[u];
-  int Mpad = 2;
-  while (Mpad < M) Mpad <<= 1;
-  __shared__ int ssz[kSelectLds];                 // cluster sizes: every pass of the selection reads them
-  for (int i = tid; i < Mpad; i += 1024) {
-    skey[i] = i < M ? orderable(v.score[(size_t)u * v.Mcap + i]) : 0u;
-    if (i < M) ssz[i] = v.csz[(size_t)u * v.Mcap + i];
+  if constexpr (!BIG) {
+    int Mpad = 2;
+    while (Mpad < M) Mpad <<= 1;
+    for (int i = tid; i < Mpad; i += 1024) {
+      skey_[i] = i < M ? orderable(v.score[(size_t)u * v.Mcap + i]) : 0u;
+      if (i < M) ssz_[i] = v.csz[(size_t)u * v.Mcap + i];
+    }
   }
   // |q_g| of every head, one wavefront per head (only where the scores came from the matrix cores)
   SelectExact ex{0.f, Q};
@@ -702,9 +753,8 @@ __global__ __launch_bounds__(1024) void select_kernel(View v, const void* Q, int
     for (int g = 0; g < v.G; ++g) qb = v.group_reduce == DYNAKV_GROUP_MAX ? fmaxf(qb, qn[g]) : qb + qn[g];
     ex.eps = score_eps(v, qb, __int_as_float(v.rmax2[u]));
   }
-  __shared__ int srt[kCountMax];
-  const SelectLds s{skey, ssz, region, hist, srt, sm, misc, nullptr, 0};
-  select_phase<1024>(v, u, M, budget, s, ex);
+  const SelectLds s{BIG ? nullptr : skey_, BIG ? nullptr : ssz_, region, hist, srt, sm, misc, nullptr, 0};
+  select_phase<1024, CMAX>(v, u, M, budget, s, ex);
 }
 
 // ------------------------------------------------------------------------------------------- attention
@@ -1379,7 +1429,8 @@ hipError_t launch_score_select(const View& v, const void* Q, int budget, const v
     else { if (two) DYNAKV_SCORE_B(false, 2); else DYNAKV_SCORE_B(false, 1); }
 #undef DYNAKV_SCORE_B
   }
-  select_kernel<<<v.U, 1024, 0, st>>>(v, Q, budget);
+  if (v.Mcap > kSelectLds) select_kernel<true><<<v.U, 1024, 0, st>>>(v, Q, budget);
+  else select_kernel<false><<<v.U, 1024, 0, st>>>(v, Q, budget);
   return hipGetLastError();
 }
 

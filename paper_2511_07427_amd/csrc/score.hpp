@@ -176,6 +176,25 @@ __device__ inline double quad_exact_score(const View& v, const uint16_t* Rq, con
 }
 
 // ---- nearest cluster of the new key ----------------------------------------------------------------------
+// (zb, jb, z2) = largest value, its index (lowest among equals; < 0: none) and the second largest value of a set;
+// merges the triple of a disjoint set into it.
+__device__ __forceinline__ void merge_best2(float& zb, int& jb, float& z2, float ob, int oj, float o2) {
+  const bool take = oj >= 0 && (jb < 0 || ob > zb || (ob == zb && oj < jb));
+  const float loser = take ? zb : ob;                   // the better of the two bests stays, the other competes for second
+  const bool loser_ok = take ? jb >= 0 : oj >= 0;
+  if (take) { zb = ob; jb = oj; }
+  z2 = fmaxf(fmaxf(z2, o2), loser_ok ? loser : -__builtin_inff());
+}
+// The same over the 64 lanes of a wavefront; every lane gets the result.
+__device__ __forceinline__ void wave_best2(float& zb, int& jb, float& z2) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const float ob = __shfl_xor(zb, o), o2 = __shfl_xor(z2, o);
+    const int oj = __shfl_xor(jb, o);
+    merge_best2(zb, jb, z2, ob, oj, o2);
+  }
+}
+
 // Every thread brings the best and the second best z it has seen (z_j = <k, r~_j> - |r~_j|^2 / 2 as the matrix
 // cores computed it: largest = nearest; jb < 0: none) and the whole workgroup of NT threads gets the cluster that
 // exact arithmetic finds nearest (lowest id among equals): if the runner-up lies beyond the error bound of the
@@ -187,30 +206,13 @@ __device__ inline int nearest_resolve(const View& v, int u, int M, float zb, int
                                       const float* zd, const uint16_t* Rq, const double* kd, double* sv, int* si,
                                       float* s2) {
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    const float ob = __shfl_xor(zb, o), o2 = __shfl_xor(z2, o);
-    const int oj = __shfl_xor(jb, o);
-    const bool take = oj >= 0 && (jb < 0 || ob > zb || (ob == zb && oj < jb));
-    const float loser = take ? zb : ob;                 // the better of the two bests stays, the other competes for second
-    const bool loser_ok = take ? jb >= 0 : oj >= 0;
-    if (take) { zb = ob; jb = oj; }
-    z2 = fmaxf(fmaxf(z2, o2), loser_ok ? loser : -__builtin_inff());
-  }
+  wave_best2(zb, jb, z2);
   __syncthreads();
   if (lane == 0) { sv[w] = (double)zb; si[w] = jb; s2[w] = z2; }
   __syncthreads();
   zb = (float)sv[0]; jb = si[0]; z2 = s2[0];
 #pragma unroll
-  for (int k = 1; k < NT / 64; ++k) {
-    const float ob = (float)sv[k], o2 = s2[k];
-    const int oj = si[k];
-    const bool take = oj >= 0 && (jb < 0 || ob > zb || (ob == zb && oj < jb));
-    const float loser = take ? zb : ob;
-    const bool loser_ok = take ? jb >= 0 : oj >= 0;
-    if (take) { zb = ob; jb = oj; }
-    z2 = fmaxf(fmaxf(z2, o2), loser_ok ? loser : -__builtin_inff());
-  }
+  for (int k = 1; k < NT / 64; ++k) merge_best2(zb, jb, z2, (float)sv[k], si[k], s2[k]);
   const float rmax = __builtin_sqrtf(rmax2) * 1.0001f;
   const float eps = kAccBound * (kn * rmax + 0.5f * rmax * rmax) * 1.01f;
   if (jb < 0 || zb - z2 > 2.f * eps) return jb;        // workgroup-uniform

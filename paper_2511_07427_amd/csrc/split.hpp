@@ -20,7 +20,8 @@ struct SplitSmem {
   unsigned char side[kMaxSplitMembers];
   unsigned short perm[kMaxSplitMembers];           // members of the staying child in order, then of the moved one
   double cA[kHeadDim], cB[kHeadDim];
-  float rA[kHeadDim], rB[kHeadDim];
+  alignas(16) float rA[kHeadDim], rB[kHeadDim];
+  double tpart[4];                                 // per-wavefront parts of a sum over the coordinates
   double sv[16];
   int si[16];
   double dl[128];                                  // member distances of a staged cluster
@@ -115,6 +116,42 @@ __device__ inline void quad_sqdist(const K& ks, int i, int q, const C* cA, const
   }
   dA = blocked16_quad(sa);
   dB = cB ? blocked16_quad(sb) : 0.0;
+}
+
+// Side of member i in a round of the 2-means: A (0) if |x - cA|^2 <= |x - cB|^2, which is <x, w> <= t with
+// w = cB - cA and t = (|cB|^2 - |cA|^2) / 2 (ties to A).  Called by the four lanes of a quad at once (lane q takes
+// coordinates 32 q .. 32 q + 31); every lane gets the side.  The inner product is first taken in float32 against wf
+// (= w rounded to float32); only if it lies within eps of t, the bound on what float32 can have changed, it is
+// retaken in float64 against wd.
+template <class K>
+__device__ inline unsigned char quad_side(const K& ks, int i, int q, const float* wf, const double* wd, double t, float eps) {
+  float x[4][8];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) ks.get8(i, q * 4 + k, x[k]);
+  float s = 0.f;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const f4 a = *(const f4*)(wf + (q * 4 + k) * 8), b = *(const f4*)(wf + (q * 4 + k) * 8 + 4);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { s = fmaf(x[k][e], a[e], s); s = fmaf(x[k][4 + e], b[e], s); }
+  }
+  s += __shfl_xor(s, 1);
+  s += __shfl_xor(s, 2);
+  const float tf = (float)t;
+  if (fabsf(s - tf) > eps) return s <= tf ? 0 : 1;            // uniform over the quad
+  double sd = 0.0;
+#pragma unroll
+  for (int k = 0; k < 4; ++k)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) sd = fma((double)x[k][e], wd[(q * 4 + k) * 8 + e], sd);
+  sd += __shfl_xor(sd, 1);
+  sd += __shfl_xor(sd, 2);
+  return sd <= t ? 0 : 1;
+}
+// Bound for quad_side: float32 accumulation of 128 products (128 * 2^-24 |x| |w|, doubled for the rounding of w and
+// of the products' partial sums across the quad) plus the rounding of t.  xmax >= every member's norm, wmax >= |w|.
+__device__ inline float side_eps(float xmax, float wmax, double t) {
+  return 1.53e-5f * xmax * wmax + 2.4e-7f * fabsf((float)t) + 1e-30f;
 }
 
 // Sum over r = 0..n-1, in that order, of key(r) for the r that use(r) accepts: eight operands are requested
@@ -224,9 +261,14 @@ __device__ __forceinline__ void split_cluster_impl(const View& v, int u, int j, 
   bool can_split = m >= 2;
   if (can_split) {
     // seeds: A = member farthest from the mean of all members, B = member farthest from A
+    double total_d = 0.0;                 // thread d < 128: sum of coordinate d over all members
     if (tid < kHeadDim) {
-      const double sum = ordered_sum(m, [&](int i) { return ks.get(i, tid); }, [](int) { return true; });
-      s.cA[tid] = sum / (double)m;
+      total_d = ordered_sum(m, [&](int i) { return ks.get(i, tid); }, [](int) { return true; });
+      const double mu = total_d / (double)m;
+      s.cA[tid] = mu;
+      double mu2 = mu * mu;
+      for (int o = 32; o > 0; o >>= 1) mu2 += __shfl_xor(mu2, o);
+      if ((tid & 63) == 0) s.tpart[2 + (tid >> 6)] = mu2;            // |mean|^2, for the rounding bound of the rounds
     }
     __syncthreads();
     double dummy;
@@ -240,6 +282,8 @@ __device__ __forceinline__ void split_cluster_impl(const View& v, int u, int j, 
     }
     serial_argmax(seed_dist, m, s.sv, s.si);
     const int a = s.si[0];
+    const float spread = (float)sqrt(s.sv[0]) * 1.0001f;                 // every member lies this close to the mean
+    const float xmax = spread + (float)sqrt(s.tpart[2] + s.tpart[3]) * 1.0001f;
     __syncthreads();
     if (tid < kHeadDim) s.cB[tid] = (double)ks.get(a, tid);
     __syncthreads();
@@ -256,21 +300,31 @@ __device__ __forceinline__ void split_cluster_impl(const View& v, int u, int j, 
     __syncthreads();
     can_split = db > 0.0;                 // false: all members identical
     if (can_split) {
-      if (tid < kHeadDim) { s.cA[tid] = s.cB[tid]; }
-      __syncthreads();
-      if (tid < kHeadDim) s.cB[tid] = (double)ks.get(b, tid);
+      // Lloyd rounds.  Thread d < 128 owns coordinate d of both centres (registers); a round's side test is one
+      // inner product with w = cB - cA per member (quad_side): w goes to s.cA (float64) and s.rA (float32).
+      // Every member and every centre lies within sqrt(dmax) of the mean.
+      double ca = 0.0, cb = 0.0;
+      if (tid < kHeadDim) { ca = s.cB[tid]; cb = (double)ks.get(b, tid); }
       for (int i = tid; i < m; i += NT) s.side[i] = 2;
       if (tid == 0) { s.flag = 0; s.count = 0; }
       __syncthreads();
       for (int it = 0; it < 16; ++it) {
+        if (tid < kHeadDim) {
+          const double w = cb - ca;
+          s.cA[tid] = w; s.rA[tid] = (float)w;
+          double tp = 0.5 * (cb * cb - ca * ca);
+          for (int o = 32; o > 0; o >>= 1) tp += __shfl_xor(tp, o);
+          if ((tid & 63) == 0) s.tpart[tid >> 6] = tp;
+        }
+        __syncthreads();
+        const double t = s.tpart[0] + s.tpart[1];
+        const float eps = side_eps(xmax, 2.f * spread, t);
         int changed = 0, na = 0;
         for (int base = 0; base < m; base += NT / 4) {
           if (base + wave_first >= m) continue;
           const int i = base + grp;
-          double dA, dB;
-          quad_sqdist<decltype(ks), double>(ks, min(i, m - 1), kb, s.cA, s.cB, dA, dB);
+          const unsigned char ns = quad_side(ks, min(i, m - 1), kb, s.rA, s.cA, t, eps);
           if (kb == 0 && i < m) {
-            const unsigned char ns = dA <= dB ? 0 : 1;   // tie -> side A
             changed |= ns != s.side[i];
             s.side[i] = ns;
             na += ns == 0;
@@ -284,12 +338,10 @@ __device__ __forceinline__ void split_cluster_impl(const View& v, int u, int j, 
         __syncthreads();
         if (!moved) break;
         if (nA == 0 || nA == m) { can_split = false; break; }
-        if (tid < 2 * kHeadDim) {
-          const int d = tid & (kHeadDim - 1);
-          const unsigned char mine = tid < kHeadDim ? 0 : 1;
-          const double sum = ordered_sum(m, [&](int i) { return ks.get(i, d); }, [&](int i) { return s.side[i] == mine; });
-          if (mine == 0) s.cA[d] = sum / (double)nA;
-          else s.cB[d] = sum / (double)(m - nA);
+        if (tid < kHeadDim) {       // sums of side A; side B is what is left of the total
+          const double sum = ordered_sum(m, [&](int i) { return ks.get(i, tid); }, [&](int i) { return s.side[i] == 0; });
+          ca = sum / (double)nA;
+          cb = (total_d - sum) / (double)(m - nA);
         }
         if (tid == 0) { s.flag = 0; s.count = 0; }
         __syncthreads();
@@ -425,7 +477,7 @@ constexpr int kVAhead = 4;
 struct WaveCtx {
   alignas(16) unsigned char stage[kWaveStage];
   double cA[kHeadDim], cB[kHeadDim];
-  float rA[kHeadDim], rB[kHeadDim];
+  alignas(16) float rA[kHeadDim], rB[kHeadDim];
   double dist[64];
   double m2[2];
   unsigned char side[64], perm[64], inv[64];     // inv[member] = its place in perm
@@ -487,7 +539,8 @@ __device__ __forceinline__ void wave_argmax(double& val, int& idx) {
 // With SIDES the members of side 0 go to (a0, a1) and those of side 1 to (b0, b1); otherwise all go to (a0, a1).
 // A member that does not belong to a sum adds +0.0, which leaves a float64 sum unchanged.  Eight loads per
 // round trip to LDS.
-template <int DT, bool SIDES, class At>
+// A_ONLY (with SIDES): only the sums of side 0 are formed.
+template <int DT, bool SIDES, bool A_ONLY = false, class At>
 __device__ __forceinline__ void wave_sums(const WaveCtx& c, int q0, int q1, int d, At&& at, double& a0, double& a1,
                                           double& b0, double& b1) {
   a0 = 0.0; a1 = 0.0; b0 = 0.0; b1 = 0.0;
@@ -509,7 +562,7 @@ __device__ __forceinline__ void wave_sums(const WaveCtx& c, int q0, int q1, int 
     for (int k = 0; k < 8; ++k) {
       a0 += (double)(sa[k] ? x0[k] : 0.f);
       a1 += (double)(sa[k] ? x1[k] : 0.f);
-      if (SIDES) {
+      if (SIDES && !A_ONLY) {
         b0 += (double)(sb[k] ? x0[k] : 0.f);
         b1 += (double)(sb[k] ? x1[k] : 0.f);
       }
@@ -561,6 +614,7 @@ __device__ inline void wave_split_decide(const View& v, int u, WaveCtx& c, uint4
     // seeds: A = member farthest from the mean of all members, B = member farthest from A
     double s0, s1, u0, u1, dummy;
     wave_sums<DT, false>(c, 0, m, lane, ident, s0, s1, u0, u1);
+    const double tot0 = s0, tot1 = s1;
     c.cA[lane] = s0 / (double)m; c.cA[lane + 64] = s1 / (double)m;
     wave_sync();
     double bv = -1.0;
@@ -572,6 +626,7 @@ __device__ inline void wave_split_decide(const View& v, int u, WaveCtx& c, uint4
       if (kb == 0 && i < m && (a < 0 || t > bv)) { bv = t; a = i; }
     }
     wave_argmax(bv, a);
+    const double dmax = bv;                   // largest squared distance of a member to the mean
     c.cB[lane] = (double)wkey<DT>(c, a, lane); c.cB[lane + 64] = (double)wkey<DT>(c, a, lane + 64);
     wave_sync();
     bv = -1.0;
@@ -585,19 +640,31 @@ __device__ inline void wave_split_decide(const View& v, int u, WaveCtx& c, uint4
     wave_argmax(bv, b);
     can = bv > 0.0;                          // false: all members identical
     if (can) {
-      c.cA[lane] = c.cB[lane]; c.cA[lane + 64] = c.cB[lane + 64];
-      c.cB[lane] = (double)wkey<DT>(c, b, lane); c.cB[lane + 64] = (double)wkey<DT>(c, b, lane + 64);
+      // every member lies within sqrt(dmax) of the mean, and so does every centre (a mean of members)
+      double mn2 = c.cA[lane] * c.cA[lane] + c.cA[lane + 64] * c.cA[lane + 64];
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) mn2 += __shfl_xor(mn2, o);
+      const float spread = (float)sqrt(dmax) * 1.0001f;
+      const float xmax = spread + (float)sqrt(mn2) * 1.0001f;
+      double ca0 = c.cB[lane], ca1 = c.cB[lane + 64];                       // seed A
+      double cb0 = (double)wkey<DT>(c, b, lane), cb1 = (double)wkey<DT>(c, b, lane + 64);   // seed B
       c.side[lane] = 2;
-      wave_sync();
       for (int it = 0; it < 16; ++it) {
+        // w = cB - cA into c.cA (float64) and c.rA (float32), t = (|cB|^2 - |cA|^2) / 2
+        const double w0 = cb0 - ca0, w1 = cb1 - ca1;
+        double t = 0.5 * ((cb0 * cb0 - ca0 * ca0) + (cb1 * cb1 - ca1 * ca1));
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) t += __shfl_xor(t, o);
+        c.cA[lane] = w0; c.cA[lane + 64] = w1;
+        c.rA[lane] = (float)w0; c.rA[lane + 64] = (float)w1;
+        wave_sync();
+        const float eps = side_eps(xmax, 2.f * spread, t);
         bool moved = false;
         int nA = 0;
         for (int base = 0; base < m; base += 16) {
           const int i = base + grp;
-          double dA, dB;
-          quad_sqdist<WaveKeys<DT>, double>(ks, min(i, m - 1), kb, c.cA, c.cB, dA, dB);
+          const unsigned char ns = quad_side(ks, min(i, m - 1), kb, c.rA, c.cA, t, eps);
           const bool own = kb == 0 && i < m;
-          const unsigned char ns = dA <= dB ? 0 : 1;     // tie -> side A
           moved = moved || __ballot(own && ns != c.side[min(i, 63)]) != 0;
           nA += __popcll(__ballot(own && ns == 0));
           if (own) c.side[i] = ns;
@@ -605,11 +672,11 @@ __device__ inline void wave_split_decide(const View& v, int u, WaveCtx& c, uint4
         wave_sync();
         if (!moved) break;
         if (nA == 0 || nA == m) { can = false; break; }
+        // sums of side A; side B is what is left of the total (float64 sums of 16-bit values: exact or very nearly so)
         double a0, a1, b0, b1;
-        wave_sums<DT, true>(c, 0, m, lane, ident, a0, a1, b0, b1);
-        c.cA[lane] = a0 / (double)nA; c.cA[lane + 64] = a1 / (double)nA;
-        c.cB[lane] = b0 / (double)(m - nA); c.cB[lane + 64] = b1 / (double)(m - nA);
-        wave_sync();
+        wave_sums<DT, true, true>(c, 0, m, lane, ident, a0, a1, b0, b1);
+        ca0 = a0 / (double)nA; ca1 = a1 / (double)nA;
+        cb0 = (tot0 - a0) / (double)(m - nA); cb1 = (tot1 - a1) / (double)(m - nA);
       }
     }
   }

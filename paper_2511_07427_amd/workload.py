@@ -71,6 +71,12 @@ CONFIGS = {
     "long131k": WorkloadSpec("long131k", "bf16", 8, 8, 16384, 114688, 2048, 4096, 64, 0.1, 256, 1,
                              seed=251107000 + 5000),
 }
+# Cluster capacity (as a multiple of the initial count) that the full horizon of a configuration needs: drift keeps
+# splitting clusters (the paper describes no merge), so long runs end with one cluster per 4 to 6 entries.  The
+# factors in CONFIGS keep at most 4096 clusters per unit where the early part of a run fits them (one kernel
+# launch per step); these are for runs to the end.
+FULL_HORIZON_FACTOR = {"tiny": 4, "llama3_8b": 16, "qwen25_7b": 128, "batched16": 20, "long131k": 64
+}
 
 
 def round_to_dtype(x: np.ndarray, dtype: str) -> np.ndarray:

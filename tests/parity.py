@@ -3,7 +3,8 @@ inputs, call by call, and compares them.
 
 Bars (the benchmark spec): cluster memberships, selected-cluster sets and gather indices bit-exact wherever
 the oracle's margin for the decision exceeds 1e-4; centroids and attention outputs within 2e-3 relative, M2 and
-tau within 2e-3 relative, log-sum-exp within 2e-3 absolute.  A disagreement on a decision whose margin is at
+tau within 2e-3 relative, log-sum-exp within 2e-3 absolute (plus 2^-17 of its magnitude, the float32 accumulation
+bound, which only matters for logits of the order of 10^4).  A disagreement on a decision whose margin is at
 most 1e-4 is a tie: it is counted per class (assign, trigger, select, split), printed by the tests, and the
 oracle's unit is then re-synchronised from the library's exported state (dynakv_export_state ->
 Oracle.import_unit) so that the run can go on side by side.  A disagreement above the margin fails.
@@ -55,8 +56,11 @@ def check_attention(out_g: np.ndarray, lse_g: np.ndarray, out_o: np.ndarray, lse
     fin = np.isfinite(lse_o)
     assert np.array_equal(np.isfinite(lse_g), fin), what
     if fin.any():
-        err = np.abs(lse_g[fin] - lse_o[fin]).max()
-        assert err <= LSE_TOL, "%s lse off by %.3g" % (what, err)
+        # 2e-3 absolute, plus what float32 can hold at the value's magnitude: the logits are 128 exact products
+        # accumulated in float32 (relative error up to 128 * 2^-24 = 2^-17), and keys that have drifted far make
+        # logits, and with them the log-sum-exp, of the order of 10^4
+        err = np.abs(lse_g[fin] - lse_o[fin]) - 2.0 ** -17 * np.abs(lse_o[fin])
+        assert err.max() <= LSE_TOL, "%s lse off by %.3g" % (what, np.abs(lse_g[fin] - lse_o[fin]).max())
     return float(rel.max())
 
 
@@ -91,10 +95,12 @@ def resync(ix: binding.Index, o: Oracle, units, dirty, tally: Tally):
     """The oracle's units `dirty` (oracle numbering) take the library's exported state."""
     if not dirty:
         return
-    st = {k: v.cpu() for k, v in ix.dynakv_export_state(binding.IMPORT_FIELDS + ("counters",), to_cpu=False).items()}
-    for ou, u in _pairs(ix, units):
-        if ou not in dirty:
-            continue
+    pairs = [(ou, u) for ou, u in _pairs(ix, units) if ou in dirty]
+    dev = ix.dynakv_export_state(binding.IMPORT_FIELDS + ("counters",), to_cpu=False)
+    idx = torch.tensor([u for _, u in pairs], device=DEV)
+    st = {k: v.index_select(0, idx).cpu() for k, v in dev.items()}      # only the units that are taken cross the bus
+    del dev
+    for u, (ou, _) in enumerate(pairs):
         M, N, ns = int(st["n_clusters"][u]), int(st["n_tokens"][u]), int(st["n_selected"][u])
         o.import_unit(ou, st["keys"][u, :N].float().numpy(), st["values"][u, :N].float().numpy(),
                       st["centroids"][u, :M].numpy(), st["size"][u, :M].numpy(), st["buffered"][u, :M].numpy(),
@@ -151,7 +157,7 @@ def _rel(a, b, floor):
     return np.abs(a - b) / np.maximum(np.abs(b), floor)
 
 
-def compare_state(ix: binding.Index, o: Oracle, tally: Tally, what="", full=True, units=None, skip=()):
+def compare_state(ix: binding.Index, o: Oracle, tally: Tally, what="", full=True, units=None, skip=(), assign=True):
     """Partition and per-cluster statistics.  Returns the oracle units that differ from the library by a tie
     (their comparison stops at the decision that differs)."""
     fields = ["n_clusters", "n_tokens", "error", "size", "buffered", "flag", "last_assign"]
@@ -167,7 +173,7 @@ def compare_state(ix: binding.Index, o: Oracle, tally: Tally, what="", full=True
         c, d = o.clusters(ou), o.diagnostics(ou)
         assert st["n_tokens"][u] == N and st["error"][u] == o.error(ou), w
         # the step's decisions in the order they were taken: nearest cluster, threshold test, splits
-        if st["last_assign"][u] != o.last_assign(ou):
+        if assign and st["last_assign"][u] != o.last_assign(ou):
             assert d["margin_assign"] <= MARGIN, "%s nearest cluster %d vs %d at margin %.3g" % (
                 w, st["last_assign"][u], o.last_assign(ou), d["margin_assign"])
             tally["tie_assign"] += 1
@@ -333,7 +339,7 @@ def run_window(spec: WorkloadSpec, sample, start: int, steps: int, check_every: 
     err = ix.dynakv_export_state(["error"])["error"].numpy()
     assert not err.any(), "error words %s before the window" % np.unique(err)
     resync(ix, o, sample, set(range(len(sample))), s.tally)
-    d0 = compare_state(ix, o, s.tally, "imported state", units=sample)
+    d0 = compare_state(ix, o, s.tally, "imported state", units=sample, assign=False)
     assert not d0
     for t in range(start, T):
         s.step(t, True, attention=((t - start) % check_every == 0 or t == T - 1), full=(t == T - 1))

@@ -135,6 +135,24 @@ def test_full_size_configurations_on_sampled_units(name, sample, steps, iters):
     assert r["splits"] > 0 or name in ("batched16", "long131k")
 
 
+# --------------------------------------------------------------------------- late windows of the full horizons
+
+@pytest.mark.parametrize("name,sample,start,steps", [
+    ("batched16", [0, 77, 127], 24576 - 64, 64),     # the end of the window the configuration times (128 units, ~7200 clusters each)
+    ("qwen25_7b", [0, 58, 111], 30000 - 64, 64),     # 112 units, ~12000 clusters each
+    ("long131k", [0, 5], 114688 - 48, 48),           # 8 units, 131 072 entries each
+])
+def test_late_window_of_the_full_horizon(name, sample, start, steps):
+    """All units of the configuration run alone from prefill to `start` (whole-step calls, the launch shape the
+    benchmark times, cluster capacity for the full horizon); the state is then exported, the oracle imports the
+    sampled units, and the last steps of the horizon run side by side under the parity protocol."""
+    from paper_2511_07427_amd.workload import FULL_HORIZON_FACTOR
+    s = CONFIGS[name].scaled(max_cluster_factor=FULL_HORIZON_FACTOR[name])
+    r = parity.run_window(s, sample, start, steps, check_every=8)
+    say("late window, %s:" % name, r)
+    assert r["splits"] > 0 and min(r["clusters"]) > 4 * s.n_clusters_init
+
+
 # --------------------------------------------------------------------------- hand-worked fixtures, padded to d = 128
 
 def _pad(a):
