@@ -63,8 +63,11 @@ typedef enum { DYNAKV_GROUP_MAX = 0, DYNAKV_GROUP_SUM = 1 } dynakv_group_reduce_
  * MEAN: the float32 mean itself, scored in float64 on the vector units.  float32 storage always reads the mean. */
 typedef enum { DYNAKV_SEARCH_STORAGE = 0, DYNAKV_SEARCH_MEAN = 1 } dynakv_search_copy_t;
 /* ADAPTIVE: Algorithm 1.  STATIC: the static-update baseline of Section 2.3: entries join their nearest cluster
- * and update its statistics, no cluster is ever flagged or split. */
-typedef enum { DYNAKV_UPDATE_ADAPTIVE = 0, DYNAKV_UPDATE_STATIC = 1 } dynakv_update_mode_t;
+ * and update its statistics, no cluster is ever flagged or split.  TOKENS: the baseline without clustering of
+ * Section 8.1: every appended entry becomes a cluster of its own (build the index with n_clusters_init = n_tokens
+ * and init_idx = 0..n_tokens-1), so that the retrieval is an exact top-B over tokens; needs max_clusters >=
+ * max_tokens (an append beyond it is refused with DYNAKV_ERR_CLUSTERS). */
+typedef enum { DYNAKV_UPDATE_ADAPTIVE = 0, DYNAKV_UPDATE_STATIC = 1, DYNAKV_UPDATE_TOKENS = 2 } dynakv_update_mode_t;
 
 /* bits of the per-unit device error word */
 #define DYNAKV_ERR_TOKENS 1   /* append refused: max_tokens or page pool exhausted            */

@@ -56,7 +56,9 @@ struct Config {
   int32_t search_copy;      // 0: searches read r_j rounded to the storage type; 1: the float32 mean
   int32_t score_round;      // 0: clusters are ordered by their float64 scores; 1: rounded to float32 first
   int32_t update_mode;      // 0: Algorithm 1 (adaptive); 1: static update (entries join the nearest cluster,
-                            //    statistics are updated, nothing is ever flagged or split: Section 2.3)
+                            //    statistics are updated, nothing is ever flagged or split: Section 2.3);
+                            //    2: no clustering (the naive baseline of Section 8.1): every entry is a cluster of
+                            //    its own, so retrieval is exact top-B over tokens
 };
 
 struct Cluster {
@@ -364,6 +366,22 @@ void retrieve_attend_unit(const Config& c, Unit& u, const float* Q, int budget, 
 void append_unit(const Config& c, Unit& u, const float* k, const float* v) {
   const int d = c.head_dim, M = (int)u.clusters.size();
   if (u.N >= c.max_tokens || M == 0) { u.error |= 1; return; }
+  if (c.update_mode == 2) {           // token level: the entry becomes cluster M, its own representative
+    if (M >= c.max_clusters) { u.error |= 2; return; }
+    Cluster cl;
+    cl.n = 1;
+    cl.r.assign(k, k + d);
+    cl.members.push_back(u.N);
+    search_copy(c, cl);
+    u.K.insert(u.K.end(), k, k + d);
+    u.V.insert(u.V.end(), v, v + d);
+    u.N += 1;
+    u.clusters.push_back(cl);
+    u.in_req.push_back(0);
+    u.last_assign = M;
+    u.mg.assign = kInf; u.mg.trigger = kInf;
+    return;
+  }
   double best, second;
   const int j = nearest_cluster(u, k, d, &best, &second);
   u.last_assign = j;

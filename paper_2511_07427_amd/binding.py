@@ -19,7 +19,7 @@ TORCH_DTYPES = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat
 ERR_TOKENS, ERR_CLUSTERS, ERR_SPLIT_SIZE, ERR_SELECT, ERR_INIT, ERR_IMPORT = 1, 2, 4, 8, 16, 32
 OK, EINVAL, ECAPACITY, ESTATE, EHIP, ENOMEM = range(6)
 SEARCH_STORAGE, SEARCH_MEAN = 0, 1
-UPDATE_ADAPTIVE, UPDATE_STATIC = 0, 1
+UPDATE_ADAPTIVE, UPDATE_STATIC, UPDATE_TOKENS = 0, 1, 2
 LAUNCH_SEPARATE, LAUNCH_SPLIT_KERNEL = 1 << 16, 1 << 17
 
 

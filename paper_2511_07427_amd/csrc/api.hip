@@ -35,7 +35,7 @@ bool config_ok(const dynakv_config_t* c) {
   if (c->softmax_scale < 0.f) return false;
   if (c->search_copy != DYNAKV_SEARCH_STORAGE && c->search_copy != DYNAKV_SEARCH_MEAN) return false;
   if (c->score_round != 0 && c->score_round != 1) return false;
-  if (c->update_mode != DYNAKV_UPDATE_ADAPTIVE && c->update_mode != DYNAKV_UPDATE_STATIC) return false;
+  if (c->update_mode < DYNAKV_UPDATE_ADAPTIVE || c->update_mode > DYNAKV_UPDATE_TOKENS) return false;
   if (c->launch & ~(0xFFFF | DYNAKV_LAUNCH_SEPARATE | DYNAKV_LAUNCH_SPLIT_KERNEL)) return false;
   const int s = c->launch & 255, nw = (c->launch >> 8) & 255;
   if (s > kMaxKvSplits || (nw != 0 && nw != 4 && nw != 8 && nw != 16)) return false;
@@ -63,7 +63,9 @@ void plan_attention(const dynakv_config_t& c, int* S, int* NW) {
   if (s > 8) s = 8;
   // where the single-kernel retrieval can run (see retrieve_is_fused) it beats split-KV at every unit count:
   // measured 16.5k against 15.5k steps/s with 8 units, 15.1k against 13.1k with 24 (configuration 2's shape)
-  if (c.dtype != DYNAKV_F32 && c.search_copy == DYNAKV_SEARCH_STORAGE && c.max_clusters <= kFusedClusters && c.group_size <= 8) s = 1;
+  if (c.dtype != DYNAKV_F32 && c.search_copy == DYNAKV_SEARCH_STORAGE && c.max_clusters <= kFusedClusters && c.group_size <= 8 &&
+      c.update_mode != DYNAKV_UPDATE_TOKENS)
+    s = 1;
   int nw = pow2_floor(4096 / (c.n_units * s) > 0 ? 4096 / (c.n_units * s) : 1);
   if (c.launch & 255) s = c.launch & 255;
   if ((c.launch >> 8) & 255) nw = (c.launch >> 8) & 255;
@@ -93,6 +95,7 @@ size_t carve(const dynakv_config_t& c, char* base, View* out) {
   v.search_mean = c.dtype == DYNAKV_F32 || c.search_copy == DYNAKV_SEARCH_MEAN;
   v.score_round = c.score_round;
   v.static_update = c.update_mode == DYNAKV_UPDATE_STATIC;
+  v.token_level = c.update_mode == DYNAKV_UPDATE_TOKENS;
   v.var_alpha = c.var_alpha; v.size_factor = c.size_factor;
   v.scale_d = c.softmax_scale > 0.f ? (double)c.softmax_scale : 1.0 / std::sqrt((double)c.head_dim);
   v.scale_f = (float)v.scale_d;
@@ -260,6 +263,11 @@ dynakv_status_t dynakv_decode_step(dynakv_index_t* ix, const void* Q, int32_t to
   if (!ix->built) return DYNAKV_ESTATE;
   hipStream_t st = (hipStream_t)stream;
   bool appended;
+  if (ix->view.token_level) {                        // no nearest-cluster search, no splits
+    const dynakv_status_t rc = retrieve_impl(ix, ix->view, Q, token_budget, out, lse, nullptr, nullptr, false, st, &appended);
+    if (rc != DYNAKV_OK) return rc;
+    return launch_append(ix->view, k_new, v_new, false, false, st) == hipSuccess ? DYNAKV_OK : DYNAKV_EHIP;
+  }
   const bool one_kernel = ix->view.fuse == 2;        // the splits too, where the retrieval kernel takes the append
   const dynakv_status_t rc = retrieve_impl(ix, ix->view, Q, token_budget, out, lse, k_new, v_new, one_kernel, st, &appended);
   if (rc != DYNAKV_OK) return rc;
@@ -279,6 +287,7 @@ dynakv_status_t dynakv_append(dynakv_index_t* ix, const void* k_new, const void*
 dynakv_status_t dynakv_split(dynakv_index_t* ix, void* stream) {
   if (!ix) return DYNAKV_EINVAL;
   if (!ix->built) return DYNAKV_ESTATE;
+  if (ix->view.token_level || ix->view.static_update) return DYNAKV_OK;       // nothing is ever flagged
   return launch_split(ix->view, (hipStream_t)stream) == hipSuccess ? DYNAKV_OK : DYNAKV_EHIP;
 }
 

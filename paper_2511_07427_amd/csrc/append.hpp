@@ -67,7 +67,7 @@ __device__ inline void append_commit(const View& v, int u, int j, int M, int N, 
     case 8: a.free_top = f.i; a.free_page = f.k; break;
     default: break;
   }
-  __syncthreads();
+  lds_barrier();
   // UpdateVar, element-wise part: delta_d = k_d - r_d, r'_d = r_d + delta_d / n'
   const int n1 = a.cn + 1;
   if (tid < kHeadDim) {
@@ -75,14 +75,14 @@ __device__ inline void append_commit(const View& v, int u, int j, int M, int N, 
     a.delta[tid] = dl;
     a.r1[tid] = r + dl / (double)n1;
   }
-  __syncthreads();
+  lds_barrier();
   if (tid < 16) {                           // block tid of sum_d delta_d * (k_d - r'_d)
     double s = 0.0;
 #pragma unroll
     for (int e = 0; e < 8; ++e) s = fma(a.delta[tid * 8 + e], a.kd[tid * 8 + e] - a.r1[tid * 8 + e], s);
     a.bs[tid] = s;
   }
-  __syncthreads();
+  lds_barrier();
   if (tid == 0) {
     const int sz = a.cn + a.cb;
     const int slot = sz % kPageTokens;
@@ -145,7 +145,7 @@ __device__ inline void append_commit(const View& v, int u, int j, int M, int N, 
     }
     a.ok = ok; a.commit = commit; a.page = page; a.slot = slot;
   }
-  __syncthreads();
+  lds_barrier();
   if (!a.ok) return;
   if (a.commit && tid < kHeadDim) store_centroid(v, u, j, tid, (float)a.r1[tid]);
   char* pg = page_ptr(v, u, a.page);
@@ -165,9 +165,9 @@ __device__ inline int block_argmin(double val, int idx, double* sv, int* si) {
     const int oi = __shfl_xor(idx, o);
     if (oi >= 0 && (idx < 0 || ov < val || (ov == val && oi < idx))) { val = ov; idx = oi; }
   }
-  __syncthreads();
+  lds_barrier();
   if (lane == 0) { sv[w] = val; si[w] = idx; }
-  __syncthreads();
+  lds_barrier();
   val = sv[0]; idx = si[0];
 #pragma unroll
   for (int k = 1; k < NT / 64; ++k) {

@@ -32,6 +32,7 @@ struct View {
   int search_mean;   // the searches read the float32 means (always for float32 storage), else the 16-bit search copy
   int score_round;   // float64 scores are rounded to float32 before they are compared
   int static_update; // static-update baseline: nothing is ever flagged
+  int token_level;   // baseline without clustering: every appended entry is a cluster of its own
   size_t Rstride;    // floats of centroid table per unit
   float var_alpha, size_factor, scale_f;
   double scale_d;
@@ -290,9 +291,22 @@ __device__ inline float page_key(const View& v, int u, int page, int slot, int d
 }
 
 // ---- block helpers ------------------------------------------------------------------------------
+// Workgroup barrier for data that travels through LDS only: it waits for this wavefront's LDS (and scalar)
+// operations, not for its outstanding global loads and stores as __syncthreads() does.  A stage that has issued
+// global stores (scores, active-set flags, list entries) or loads it will only need later then does not pay a
+// memory round trip at every barrier.  Data that other threads of the workgroup read back from global memory
+// still needs __syncthreads().
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+template <bool LDS_ONLY>
+__device__ __forceinline__ void block_barrier() {
+  if constexpr (LDS_ONLY) lds_barrier();
+  else __syncthreads();
+}
+
 // Exclusive prefix sum over the threads of a block (blockDim.x a multiple of 64, at most 1024), or over its
 // first 64 * nw threads if nw > 0 (then only those may call).
 // `sm` needs 64 ints.  Returns the prefix of this thread; `total` receives the block sum.
+template <bool LDS_ONLY = false>
 __device__ inline int block_excl_scan(int val, int* sm, int& total, int nw = 0) {
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   if (nw == 0) nw = blockDim.x >> 6;
@@ -301,9 +315,9 @@ __device__ inline int block_excl_scan(int val, int* sm, int& total, int nw = 0) 
     const int y = __shfl_up(x, o);
     if (lane >= o) x += y;
   }
-  __syncthreads();
+  block_barrier<LDS_ONLY>();
   if (lane == 63) sm[w] = x;
-  __syncthreads();
+  block_barrier<LDS_ONLY>();
   if (w == 0) {
     int t = lane < nw ? sm[lane] : 0;
     for (int o = 1; o < 64; o <<= 1) {
@@ -312,13 +326,14 @@ __device__ inline int block_excl_scan(int val, int* sm, int& total, int nw = 0) 
     }
     sm[lane] = t;
   }
-  __syncthreads();
+  block_barrier<LDS_ONLY>();
   const int base = w ? sm[w - 1] : 0;
   total = sm[nw - 1];
   return base + x - val;
 }
 
 // The same over 64-bit values (two 32-bit sums side by side); `sm` needs 16 entries.
+template <bool LDS_ONLY = false>
 __device__ inline unsigned long long block_excl_scan64(unsigned long long val, unsigned long long* sm,
                                                        unsigned long long& total) {
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = blockDim.x >> 6;
@@ -327,9 +342,9 @@ __device__ inline unsigned long long block_excl_scan64(unsigned long long val, u
     const unsigned long long y = __shfl_up(x, o);
     if (lane >= o) x += y;
   }
-  __syncthreads();
+  block_barrier<LDS_ONLY>();
   if (lane == 63) sm[w] = x;
-  __syncthreads();
+  block_barrier<LDS_ONLY>();
   unsigned long long base = 0, all = 0;
   for (int k = 0; k < nw; ++k) {
     const unsigned long long t = sm[k];

@@ -104,6 +104,46 @@ __global__ __launch_bounds__(256) void append_kernel(View v, const void* kin, co
   }
 }
 
+// Baseline without clustering (Section 8.1): the new entry becomes cluster M of its unit, its own representative.
+__global__ __launch_bounds__(256) void append_token_kernel(View v, const void* kin, const void* vin) {
+  __shared__ int s_page;
+  const int u = blockIdx.x, tid = threadIdx.x;
+  const int M = v.M[u], N = v.N[u];
+  const size_t cbase = (size_t)u * v.Mcap;
+  if (tid == 0) {
+    int page = -1;
+    if (N >= v.Ncap) v.err[u] |= DYNAKV_ERR_TOKENS;
+    else if (M >= v.Mcap) v.err[u] |= DYNAKV_ERR_CLUSTERS;
+    else {
+      const int top = v.free_top[u], bump = v.bump[u];
+      if (top > 0) { page = v.freelist[(size_t)u * v.Pcap + top - 1]; v.free_top[u] = top - 1; }
+      else if (bump < v.Pcap) { page = bump; v.bump[u] = bump + 1; }
+      else v.err[u] |= DYNAKV_ERR_TOKENS;
+    }
+    if (page >= 0) {
+      v.pnext[(size_t)u * v.Pcap + page] = -1;
+      for (int p = 0; p < kInlinePages; ++p) v.cpg[(cbase + M) * kInlinePages + p] = p == 0 ? page : -1;
+      v.ctail[cbase + M] = page;
+      v.cn[cbase + M] = 1; v.cb[cbase + M] = 0; v.csz[cbase + M] = 1; v.cflag[cbase + M] = 0; v.cM2[cbase + M] = 0.0;
+      v.in_req[cbase + M] = 0;
+      v.ppos[((size_t)u * v.Pcap + page) * kPageTokens] = N;
+      v.last_assign[u] = M;
+      v.M[u] = M + 1; v.N[u] = N + 1;
+    }
+    s_page = page;
+  }
+  __syncthreads();
+  const int page = s_page;
+  if (page < 0) return;
+  char* pg = page_ptr(v, u, page);
+  if (tid < kHeadDim) {
+    store_centroid(v, u, M, tid, load_elem(kin, (size_t)u * kHeadDim + tid, v.dtype));
+    copy_elem(pg, k_index(v.dtype, 0, tid), kin, (size_t)u * kHeadDim + tid, v.dtype);
+  } else {
+    copy_elem(pg, v_index(v.dtype, 0, tid - kHeadDim), vin, (size_t)u * kHeadDim + tid - kHeadDim, v.dtype);
+  }
+}
+
 // ------------------------------------------------------------------------------------------- split
 template <int DT>
 __global__ __launch_bounds__(kSplitThreads) void split_kernel(View v) {
@@ -317,6 +357,10 @@ __global__ __launch_bounds__(256) void import_copy_kernel(View v, const void* K,
 // prescanned: the score kernel of the same step has already looked at the new key (launch_score_select with kin).
 // Otherwise, with the 16-bit search copy, a matrix-core pass of its own comes first.
 hipError_t launch_append(const View& v, const void* k, const void* val, bool prescanned, bool split, hipStream_t st) {
+  if (v.token_level) {
+    append_token_kernel<<<v.U, 256, 0, st>>>(v, k, val);
+    return hipGetLastError();
+  }
   if (!v.search_mean && !prescanned) {
     const hipError_t e = launch_near(v, k, st);
     if (e != hipSuccess) return e;

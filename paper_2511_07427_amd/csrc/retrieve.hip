@@ -306,7 +306,7 @@ __device__ __noinline__ int bin_candidates(int* hist, int* misc, int* lst, const
   const int tid = threadIdx.x, lane = tid & 63;
   if (tid == 0) { misc[0] = -1; misc[1] = 0; }
   for (int i = tid; i < 768; i += NT) hist[i] = 0;
-  __syncthreads();
+  lds_barrier();
   uint32_t lo = 0xFFFFFFFFu, hi = 0u;
   for (int p = tid; p < cut; p += NT) {
     const uint32_t k = (uint32_t)(ck[p] >> kIdBits);
@@ -315,11 +315,11 @@ __device__ __noinline__ int bin_candidates(int* hist, int* misc, int* lst, const
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) { lo = min(lo, (uint32_t)__shfl_xor((int)lo, o)); hi = max(hi, (uint32_t)__shfl_xor((int)hi, o)); }
   if (lane == 0) { atomicMin((unsigned*)&misc[0], lo); atomicMax((unsigned*)&misc[1], hi); }
-  __syncthreads();
+  lds_barrier();
   const uint32_t differ = (uint32_t)misc[0] ^ (uint32_t)misc[1];
   const int shift = differ ? max(31 - __clz((int)differ) - 7, 0) : 0;
   for (int p = tid; p < cut; p += NT) atomicAdd(&hist[((uint32_t)(ck[p] >> kIdBits) >> shift) & 255u], 1);
-  __syncthreads();
+  lds_barrier();
   if (tid < 64) {                      // lane l owns the bins 255 - 4l .. 252 - 4l, highest first
     int hv[4], t = 0;
 #pragma unroll
@@ -333,12 +333,12 @@ __device__ __noinline__ int bin_candidates(int* hist, int* misc, int* lst, const
 #pragma unroll
     for (int k = 0; k < 4; ++k) { hist[256 + 255 - (4 * lane + k)] = run; run += hv[k]; }
   }
-  __syncthreads();
+  lds_barrier();
   for (int p = tid; p < cut; p += NT) {
     const int d = ((uint32_t)(ck[p] >> kIdBits) >> shift) & 255u;
     lst[hist[256 + d] + atomicAdd(&hist[512 + d], 1)] = p;
   }
-  __syncthreads();
+  lds_barrier();
   return shift;
 }
 
@@ -383,7 +383,7 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
   if (!first_ready) {
     for (int i = tid; i < 1024; i += NT) s.hist[i] = 0;
     if (tid < 8) s.misc[tid] = tid == 4 ? 0x7fffffff : 0;
-    __syncthreads();
+    lds_barrier();
   }
 
   uint32_t kstar = 0, mask = 0;
@@ -399,7 +399,7 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
           if (w) atomicAdd(&h[(k >> shift) & 255], w);
         }
       });
-      __syncthreads();
+      lds_barrier();
     }
     // every wavefront: lane l owns the digits 255 - 4l .. 252 - 4l, highest first
     int hv[4], t = 0;
@@ -436,7 +436,7 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
   int* const bmask = s.hist + 2 * kBandMax;             // [2] which of them are selected
   double* const bex = (double*)(s.hist + 2 * kBandMax + 2);   // [kBandMax] their exact scores
   if (cross && ex.eps > 0.f) {
-    __syncthreads();                                    // every wavefront has read the last histogram
+    lds_barrier();                                    // every wavefront has read the last histogram
     const float astar = unorderable(kstar);
     klo = orderable(astar - 2.f * ex.eps); khi = orderable(astar + 2.f * ex.eps);
     for_each_key<NT>(M, key_at, [&](int j, uint32_t k) __attribute__((always_inline)) {
@@ -447,7 +447,7 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
         if (k > kstar && w) atomicAdd(&s.misc[5], w);
       }
     });
-    __syncthreads();
+    lds_barrier();
     const int nb = s.misc[7];
     refined = nb > 1 && nb <= kBandMax;
     if (refined) {
@@ -485,7 +485,7 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
           count(v, u, 7, 1);
         }
       }
-      __syncthreads();
+      lds_barrier();
     }
   }
 
@@ -513,7 +513,7 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
       }
     }
   });
-  __syncthreads();
+  lds_barrier();
   int xid = s.misc[4], tie_w = 0;        // xid: the cluster at which the budget is first exceeded
   if (cross && !refined && s.misc[3] > 1) {          // several equal scores at the cut: by ascending id while they fit
     if (tid < 64) {
@@ -538,7 +538,7 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
       }
       if (lane == 0) { s.misc[4] = x < 0 ? M : x; s.misc[5] = cum - above; }
     }
-    __syncthreads();
+    lds_barrier();
     xid = s.misc[4]; tie_w = s.misc[5];
     for (int j = tid; j < M; j += NT)
       if (DYNAKV_KEY(j) == kstar) {
@@ -549,7 +549,7 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
           if (pos < CMAX) { ck[pos] = ((unsigned long long)kstar << kIdBits) | (unsigned)(kIdMask - j); cw[pos] = DYNAKV_WEIGHT(j); }
         }
       }
-    __syncthreads();
+    lds_barrier();
   } else if (cross && !refined && tid == 0) {
     v.in_req[cb + xid] = 0;
   }
@@ -564,12 +564,13 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
     tsel = -1;                                          // recomputed from the sizes below
   }
   if (cross && cut == 0 && budget > 0) {           // the best cluster alone is over budget: its first entries
+    __syncthreads();                                 // (another thread may have cleared the same active-set flag)
     if (tid == 0) {
       ck[0] = ((unsigned long long)kstar << kIdBits) | (unsigned)(kIdMask - xid);
       cw[0] = budget;
       v.in_req[cb + xid] = 1;
     }
-    __syncthreads();
+    lds_barrier();
     cut = 1; tsel = budget;
   }
 
@@ -631,7 +632,7 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
       if (r != 0 || sub == 0) { rk[r] = rank; idw[r] = kIdMask - (int)(my & kIdMask); wt[r] = cw[p]; }
     }
   }
-  __syncthreads();
+  lds_barrier();
   int* by_id = cw;                 // from here on indexed by rank
   int* by_w = s.srt;
 #pragma unroll
@@ -641,7 +642,7 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
       by_w[rk[r]] = wt[r];
       v.sel_ids[cb + rk[r]] = idw[r];
     }
-  __syncthreads();
+  lds_barrier();
   // gather offsets in rank order: running sums of the sizes (low half) and of the list entries (high half)
   unsigned long long loc[PER], run = 0;
 #pragma unroll
@@ -652,7 +653,7 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
     run += loc[k];
   }
   unsigned long long total64;
-  unsigned long long pre = block_excl_scan64(run, (unsigned long long*)s.sm, total64);
+  unsigned long long pre = block_excl_scan64<true>(run, (unsigned long long*)s.sm, total64);
 #pragma unroll
   for (int k = 0; k < PER; ++k) {
     const int r = tid * PER + k;
@@ -662,7 +663,7 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
   }
   const int quads = tid == 0 ? (int)(total64 >> 32) : 0;
   if (tsel < 0) tsel = (int)(total64 & 0xFFFFFFFFull);
-  __syncthreads();
+  lds_barrier();
   // list entries, by the thread that ranked the cluster (every page but the last is full, so a page's place in
   // the list follows from its index); pages past the inline table are found by walking the chain
   int* plist = v.plist + (size_t)u * v.Lcap;
@@ -690,7 +691,7 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
     }
   }
   if (quads) atomicAdd(&s.misc[6], quads);
-  __syncthreads();
+  lds_barrier();
   const int nlist = s.misc[6];
   if (tid == 0) {
     v.n_sel[u] = cut; v.t_sel[u] = tsel; v.n_list[u] = nlist; v.ticket[u] = 0;
@@ -1206,7 +1207,7 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
       if (lane == 0) { wk.nflag0 = nflag0; wk.top0 = top0; }
     }
   const RowNorms rn = row_norms<BF, 1>(A, G, v.group_reduce, lane);
-  __syncthreads();
+  lds_barrier();
   float zb = -__builtin_inff(), z2 = -__builtin_inff(), rmax2 = 0.f;
   int jb = -1;
   const int nctile = (M + kTileClusters - 1) / kTileClusters;
@@ -1246,7 +1247,7 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
 #pragma unroll
   for (int o = 8; o > 0; o >>= 1) rmax2 = fmaxf(rmax2, __shfl_xor(rmax2, o));
   if (lane == 0) atomicMax(&s_rmax2, __float_as_int(rmax2));
-  __syncthreads();                                    // scores, first histogram, z and the largest norm are in place
+  lds_barrier();                                      // scores, first histogram and the largest norm are in place
   const float unit_rmax2 = __int_as_float(s_rmax2);
   // the append's nearest cluster: its record is requested here and used after the selection
   int ja = -1;
@@ -1255,13 +1256,14 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
     ja = nearest_resolve<NT>(v, u, M, zb, jb, z2, rn.kn, unit_rmax2, v.zdist + (size_t)u * v.Mcap, Rq, ap.kd, am_v, am_i, am_2);
     if (room) apf = append_fetch(v, u, ja);
   }
-  __syncthreads();
+  lds_barrier();
 
   // ---- selection
   const SelectLds sel{skey, ssz, smem + kKeys + kSizes, hist, ssz, sm, misc, list, kFusedList};
   const SelectExact ex{score_eps(v, rn.qbound, unit_rmax2), Q};
   const int nlist = select_phase<NT>(v, u, M, budget, sel, ex, true);
-  __syncthreads();
+  if (nlist > kFusedList) __syncthreads();            // the page loop will read the list back from memory
+  else lds_barrier();
 
   // ---- the append (scores and selection saw the index as it was before); with SPLIT the first wavefront
   // requests what the plan of the splits needs beforehand and makes the plan right after
@@ -1274,12 +1276,13 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   if constexpr (APPEND) {
     if (room) append_commit<NT>(v, u, ja, M, N, kin, vin, ap, apf);
     else if (tid == 0) v.err[u] |= DYNAKV_ERR_TOKENS;
-    __syncthreads();
+    if constexpr (SPLIT) __syncthreads();             // wavefronts that decide splits read the appended entry from its page
+    else lds_barrier();
   }
   int nprep = 0;
   if constexpr (SPLIT) {
     if (wave == 0) plan_finish<DT>(v, wk, pe, nflag0, top0, M, ja, room ? &ap : nullptr, kPreSplits);
-    __syncthreads();
+    lds_barrier();
     nprep = wk.npre;
   }
 
@@ -1326,7 +1329,7 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   float l = st.l;
   l += __shfl_xor(l, 16);
   l += __shfl_xor(l, 32);
-  __syncthreads();                                    // the list is dead: its space becomes the merge buffer
+  lds_barrier();                                      // the list is dead: its space becomes the merge buffer
   const int hs = kHeadDim + 2, ws = G * hs;
   if (g < G) {
     float* o = sm_o + wave * ws + g * hs;
@@ -1339,7 +1342,7 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   // the splits decided meanwhile get their ids and pages in plan order (one thread) ...
   if constexpr (SPLIT)
     if (tid == 0 && nprep > 0) split_assign(v, u, (WaveCtx*)(smem + kRawOff), wk.pl, nprep);
-  __syncthreads();
+  lds_barrier();
   if (SPLIT && wave < nprep) {
     // ... and are written by the wavefronts that decided them, while the others merge the attention output
     wave_split_commit<DT>(v, u, ((WaveCtx*)(smem + kRawOff))[ctx_of(wave)], pre_v, true);
@@ -1378,7 +1381,7 @@ void launch_ga_dt(const View& v, const void* Q, float* out, float* lse, hipStrea
 }  // namespace
 
 bool retrieve_is_fused(const View& v) {
-  return v.fuse && v.S == 1 && !v.search_mean && v.Mcap <= kFusedClusters && v.G <= 8;
+  return v.fuse && v.S == 1 && !v.search_mean && !v.token_level && v.Mcap <= kFusedClusters && v.G <= 8;
 }
 
 template <int DT, bool APPEND, bool SPLIT>

@@ -207,16 +207,17 @@ __device__ inline int nearest_resolve(const View& v, int u, int M, float zb, int
                                       float* s2) {
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   wave_best2(zb, jb, z2);
-  __syncthreads();
+  lds_barrier();
   if (lane == 0) { sv[w] = (double)zb; si[w] = jb; s2[w] = z2; }
-  __syncthreads();
+  lds_barrier();
   zb = (float)sv[0]; jb = si[0]; z2 = s2[0];
 #pragma unroll
   for (int k = 1; k < NT / 64; ++k) merge_best2(zb, jb, z2, (float)sv[k], si[k], s2[k]);
   const float rmax = __builtin_sqrtf(rmax2) * 1.0001f;
   const float eps = kAccBound * (kn * rmax + 0.5f * rmax * rmax) * 1.01f;
   if (jb < 0 || zb - z2 > 2.f * eps) return jb;        // workgroup-uniform
-  // several clusters within the bound of the best: float64 distances of all of them
+  // several clusters within the bound of the best: float64 distances of all of them (read back from memory)
+  __syncthreads();
   const float thr = zb - 2.f * eps;
   double best = __builtin_inf();
   int arg = -1;

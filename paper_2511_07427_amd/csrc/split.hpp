@@ -21,7 +21,10 @@ struct SplitSmem {
   unsigned short perm[kMaxSplitMembers];           // members of the staying child in order, then of the moved one
   double cA[kHeadDim], cB[kHeadDim];
   alignas(16) float rA[kHeadDim], rB[kHeadDim];
-  double tpart[4];                                 // per-wavefront parts of a sum over the coordinates
+  double tpart[4];                                 // per-wavefront parts of a sum over the coordinates, two rounds' worth
+  double mu2[2];                                   // |mean of the members|^2, in two parts
+  int nchg[2];                                     // members that changed side in a round (two rounds' worth)
+  unsigned short chg[2][kMaxSplitMembers];         // who they are: member | what happens to the sums of side A << 12
   double sv[16];
   int si[16];
   double dl[128];                                  // member distances of a staged cluster
@@ -268,7 +271,7 @@ __device__ __forceinline__ void split_cluster_impl(const View& v, int u, int j, 
       s.cA[tid] = mu;
       double mu2 = mu * mu;
       for (int o = 32; o > 0; o >>= 1) mu2 += __shfl_xor(mu2, o);
-      if ((tid & 63) == 0) s.tpart[2 + (tid >> 6)] = mu2;            // |mean|^2, for the rounding bound of the rounds
+      if ((tid & 63) == 0) s.mu2[tid >> 6] = mu2;                    // |mean|^2, for the rounding bound of the rounds
     }
     __syncthreads();
     double dummy;
@@ -283,7 +286,7 @@ __device__ __forceinline__ void split_cluster_impl(const View& v, int u, int j, 
     serial_argmax(seed_dist, m, s.sv, s.si);
     const int a = s.si[0];
     const float spread = (float)sqrt(s.sv[0]) * 1.0001f;                 // every member lies this close to the mean
-    const float xmax = spread + (float)sqrt(s.tpart[2] + s.tpart[3]) * 1.0001f;
+    const float xmax = spread + (float)sqrt(s.mu2[0] + s.mu2[1]) * 1.0001f;
     __syncthreads();
     if (tid < kHeadDim) s.cB[tid] = (double)ks.get(a, tid);
     __syncthreads();
@@ -300,50 +303,70 @@ __device__ __forceinline__ void split_cluster_impl(const View& v, int u, int j, 
     __syncthreads();
     can_split = db > 0.0;                 // false: all members identical
     if (can_split) {
-      // Lloyd rounds.  Thread d < 128 owns coordinate d of both centres (registers); a round's side test is one
-      // inner product with w = cB - cA per member (quad_side): w goes to s.cA (float64) and s.rA (float32).
-      // Every member and every centre lies within sqrt(dmax) of the mean.
-      double ca = 0.0, cb = 0.0;
+      // Lloyd rounds.  Thread d < 128 owns coordinate d: both centres and the sum of side A (registers); side B is
+      // what is left of the total.  A round's side test is one inner product with w = cB - cA per member
+      // (quad_side): w goes to s.cA (float64) and s.rA (float32).  Members that change side are listed, and the
+      // sums follow the list instead of being formed anew (float64 sums of 16-bit values: exact, or very nearly).
+      // Every member and every centre lies within sqrt(dmax) of the mean.  Two barriers per round.
+      double ca = 0.0, cb = 0.0, sa = 0.0;
       if (tid < kHeadDim) { ca = s.cB[tid]; cb = (double)ks.get(b, tid); }
       for (int i = tid; i < m; i += NT) s.side[i] = 2;
-      if (tid == 0) { s.flag = 0; s.count = 0; }
-      __syncthreads();
-      for (int it = 0; it < 16; ++it) {
+      if (tid == 0) { s.nchg[0] = 0; s.nchg[1] = 0; }
+      auto publish = [&](int slot) __attribute__((always_inline)) {       // w and t of the coming round
         if (tid < kHeadDim) {
           const double w = cb - ca;
           s.cA[tid] = w; s.rA[tid] = (float)w;
           double tp = 0.5 * (cb * cb - ca * ca);
           for (int o = 32; o > 0; o >>= 1) tp += __shfl_xor(tp, o);
-          if ((tid & 63) == 0) s.tpart[tid >> 6] = tp;
+          if ((tid & 63) == 0) s.tpart[slot * 2 + (tid >> 6)] = tp;
         }
-        __syncthreads();
-        const double t = s.tpart[0] + s.tpart[1];
+      };
+      publish(0);
+      __syncthreads();
+      int nA = 0;
+      for (int it = 0; it < 16; ++it) {
+        const int p = it & 1;
+        const double t = s.tpart[p * 2] + s.tpart[p * 2 + 1];
         const float eps = side_eps(xmax, 2.f * spread, t);
-        int changed = 0, na = 0;
         for (int base = 0; base < m; base += NT / 4) {
           if (base + wave_first >= m) continue;
           const int i = base + grp;
           const unsigned char ns = quad_side(ks, min(i, m - 1), kb, s.rA, s.cA, t, eps);
           if (kb == 0 && i < m) {
-            changed |= ns != s.side[i];
-            s.side[i] = ns;
-            na += ns == 0;
+            const unsigned char old = s.side[i];
+            if (ns != old) {     // 0: joins side A; 1: leaves nothing (first round, side B); 2: leaves side A
+              s.side[i] = ns;
+              const int code = ns == 0 ? 0 : old == 2 ? 1 : 2;
+              s.chg[p][atomicAdd(&s.nchg[p], 1)] = (unsigned short)(i | (code << 12));
+            }
           }
         }
-        if (changed) s.flag = 1;
-        if (na) atomicAdd(&s.count, na);
         __syncthreads();
-        const int nA = s.count;
-        const bool moved = s.flag != 0;
-        __syncthreads();
-        if (!moved) break;
-        if (nA == 0 || nA == m) { can_split = false; break; }
-        if (tid < kHeadDim) {       // sums of side A; side B is what is left of the total
-          const double sum = ordered_sum(m, [&](int i) { return ks.get(i, tid); }, [&](int i) { return s.side[i] == 0; });
-          ca = sum / (double)nA;
-          cb = (total_d - sum) / (double)(m - nA);
+        const int nc = s.nchg[p];
+        if (nc == 0) break;                                  // no member moved
+        for (int e = 0; e < nc; ++e) {
+          const int code = s.chg[p][e] >> 12;
+          nA += code == 0 ? 1 : code == 2 ? -1 : 0;
         }
-        if (tid == 0) { s.flag = 0; s.count = 0; }
+        if (nA == 0 || nA == m) { can_split = false; break; }
+        if (tid < kHeadDim) {
+          for (int e0 = 0; e0 < nc; e0 += 8) {               // eight members requested at a time
+            float x[8];
+            int cd[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+              const int en = s.chg[p][min(e0 + k, nc - 1)];
+              cd[k] = e0 + k < nc ? en >> 12 : 1;
+              x[k] = ks.get(en & 0xFFF, tid);
+            }
+#pragma unroll
+            for (int k = 0; k < 8; ++k) sa += cd[k] == 0 ? (double)x[k] : cd[k] == 2 ? -(double)x[k] : 0.0;
+          }
+          ca = sa / (double)nA;
+          cb = (total_d - sa) / (double)(m - nA);
+        }
+        if (tid == 0) s.nchg[p ^ 1] = 0;
+        publish(p ^ 1);
         __syncthreads();
       }
     }

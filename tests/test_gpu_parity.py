@@ -322,6 +322,21 @@ def test_readings_behind_config_fields(dtype, kw):
         assert r["splits"] > 0
 
 
+@pytest.mark.parametrize("dtype,N0,M0", [("f16", 8292, 8192), ("bf16", 700, 640), ("f32", 700, 700)])
+def test_token_level_mode(dtype, N0, M0):
+    """The baseline without clustering: every entry its own cluster (retrieval = exact top-B over tokens), appended
+    entries become new clusters; more clusters than the selection keeps in LDS, and the capacity error at the end."""
+    s = CONFIGS["llama3_8b"].scaled(dtype=dtype, prefill=N0, n_clusters_init=M0, budget=300, max_cluster_factor=1)
+    r = run_trajectory(s, [0, 1], 40, check_every=1, full_every=10, step_call="mixed", update_mode=2, kmeans_iters=1,
+                       max_clusters=M0 + 36)
+    say("token level", dtype, {k: r[k] for k in ("worst_rel", "ties", "splits", "clusters")})
+    ix, o = r["index"], r["oracle"]
+    st = ix.dynakv_export_state(["error", "n_clusters", "n_tokens", "size"])
+    assert r["splits"] == 0 and st["n_clusters"].tolist() == [M0 + 36] * 2 and st["n_tokens"].tolist() == [N0 + 36] * 2
+    assert st["error"].tolist() == [binding.ERR_CLUSTERS] * 2 and o.error(0) == 2
+    assert int(st["size"][:, M0:M0 + 36].min()) == 1
+
+
 def test_capacity_limits_set_the_error_word_and_keep_state():
     s = WorkloadSpec("cap", "f16", 1, 2, 64, 8, 4, 32, 4, 0.5, var_alpha=0.5, size_factor=0.0, buffer_max=0,
                      max_cluster_factor=1, seed=5)

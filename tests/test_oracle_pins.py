@@ -420,6 +420,28 @@ def test_static_update_never_flags_and_config_fields_select_the_readings():
     assert runs["copy"].num_clusters(0) > 32
 
 
+def test_token_level_mode_retrieves_the_exact_top_b_tokens():
+    """update_mode = 2 (no clustering): every entry is its own cluster, so the selected entries are the B entries
+    with the largest scores max_g <q_g, k> (brute force over all tokens), appended ones included."""
+    s = CONFIGS["tiny"].scaled(prefill=300, n_clusters_init=300)
+    w = generate(s, steps=40)
+    o = Oracle(OracleConfig(1, 4, 128, 300, 400, 340, 1, 16, 0, 1.5, 2.0, 0.0, search_copy=1, update_mode=2))
+    o.build_index(w["K0"], w["V0"], w["init_idx"])
+    assert o.clusters(0)["n"].tolist() == [1] * 300
+    for t in range(40):
+        o.retrieve_attend(w["Q"][t], 37)
+        allK = np.concatenate([w["K0"][0], w["Knew"][:t, 0]]).astype(np.float64)
+        sc = (w["Q"][t, 0].astype(np.float64) @ allK.T).max(0)
+        want = np.argsort(-sc, kind="stable")[:37]
+        assert sorted(o.gather(0).tolist()) == sorted(want.tolist())
+        o.append(w["Knew"][t], w["Vnew"][t])
+        o.split()
+        assert o.num_clusters(0) == 301 + t and o.last_assign(0) == 300 + t
+    c = o.clusters(0)
+    assert c["flag"].sum() == 0 and c["M2"].sum() == 0.0 and c["n"].sum() == 340
+    np.testing.assert_array_equal(c["centroids"][300:], w["Knew"][:, 0])
+
+
 def test_imported_state_continues_like_the_original():
     s = CONFIGS["tiny"].scaled(var_alpha=1.2, buffer_max=4)
     w = generate(s, steps=96)
