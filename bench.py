@@ -75,6 +75,78 @@ def cpu_baseline(spec, budget):
                 prefill_s_all_units=pre * spec.n_units / nu, prefill_s_all_units_1_thread=pre1 * spec.n_units / nu1)
 
 
+def variants_report(a):
+    """The update strategies the paper compares (Section 2.3, Section 8.1, Table 5) on the same drifting workload and
+    kernels: adaptive (Algorithm 1), static update (append to the nearest cluster, never split) and no clustering
+    (every entry its own cluster: exact top-B over tokens).  Per strategy: decode steps/s, recall of the dense top-B
+    tokens, share of the dense attention mass that the retrieved entries carry, error of the attention output
+    against dense attention, mean intra-cluster variance, clusters per unit.  Quality is sampled every
+    `--variant-every` steps through the three-call API (the gather list is read back before the split)."""
+    import numpy as np
+    import torch
+    from paper_2511_07427_amd import binding
+    from paper_2511_07427_amd.workload import CONFIGS, generate
+    base = CONFIGS[a.config].scaled(n_units=a.units or 32)
+    T, every = a.steps, a.variant_every
+    dev = torch.device("cuda:0")
+    tdt = binding.TORCH_DTYPES[base.dtype]
+    w = generate(base, steps=T, workers=16)
+    K0, V0 = torch.from_numpy(w["K0"]).to(dev).to(tdt), torch.from_numpy(w["V0"]).to(dev).to(tdt)
+    Q, Kn, Vn = (torch.from_numpy(w[k]).to(dev).to(tdt) for k in ("Q", "Knew", "Vnew"))
+    U, G, d, B = base.n_units, base.group_size, base.head_dim, base.budget
+    scale = 1.0 / np.sqrt(d)
+    out, lse = torch.empty(U, G, d, device=dev), torch.empty(U, G, device=dev)
+    res = {}
+    for name, mode in (("adaptive", binding.UPDATE_ADAPTIVE), ("static", binding.UPDATE_STATIC), ("tokens", binding.UPDATE_TOKENS)):
+        tok = mode == binding.UPDATE_TOKENS
+        M0 = base.prefill if tok else base.n_clusters_init
+        Mcap = base.prefill + T if tok else base.max_clusters
+        ix = binding.Index(binding.Config(U, G, base.dtype, M0, Mcap, base.prefill + T, 1 if tok else base.kmeans_iters,
+                                          base.buffer_max, 0, base.var_alpha, base.size_factor, 0.0, update_mode=mode), dev)
+        init = torch.arange(base.prefill, dtype=torch.int32, device=dev).repeat(U, 1) if tok else torch.from_numpy(w["init_idx"]).to(dev)
+        ix.dynakv_build_index(K0, V0, init.contiguous())
+        torch.cuda.synchronize()
+        recall, mass, err, busy = [], [], [], 0.0
+        for t in range(T):
+            if t % every == every - 1:
+                ix.dynakv_retrieve_attend(Q[t], B, out, lse)
+                st = ix.dynakv_export_state(["n_gathered", "gathered", "n_tokens", "keys", "values"], to_cpu=False)
+                N = int(st["n_tokens"][0])
+                Kf, Vf, qf = st["keys"][:, :N].float(), st["values"][:, :N].float(), Q[t].float()
+                logit = torch.einsum("ugd,und->ugn", qf, Kf) * scale
+                p = torch.softmax(logit, -1)
+                dense = torch.einsum("ugn,und->ugd", p, Vf)
+                sel = torch.zeros(U, N, device=dev)
+                for u in range(U):
+                    sel[u, st["gathered"][u, :int(st["n_gathered"][u])].long()] = 1.0
+                top = logit.max(1).values.topk(min(B, N), -1).indices
+                recall.append(float(sel.gather(1, top).mean()))
+                mass.append(float((p * sel[:, None, :]).sum(-1).mean()))
+                err.append(float(((out - dense).norm(dim=-1) / dense.norm(dim=-1).clamp_min(1e-6)).mean()))
+                ix.dynakv_append(Kn[t], Vn[t])
+                ix.dynakv_split()
+                torch.cuda.synchronize()
+            else:
+                t0 = time.perf_counter()
+                ix.dynakv_decode_step(Q[t], B, out, lse, Kn[t], Vn[t])
+                if t % every == every - 2:
+                    torch.cuda.synchronize()
+                busy += time.perf_counter() - t0
+        torch.cuda.synchronize()
+        st = ix.dynakv_export_state(["n_clusters", "size", "m2", "error"])
+        n, m2 = st["size"].double().sum(), st["m2"].sum()
+        res[name] = dict(steps_per_s=(T - T // every) / busy, recall_of_dense_top_b=float(np.mean(recall)),
+                         dense_attention_mass_retrieved=float(np.mean(mass)), attention_error_vs_dense=float(np.mean(err)),
+                         mean_cluster_variance=float(m2 / n), clusters_per_unit=float(st["n_clusters"].float().mean()),
+                         error_words=int(st["error"].abs().sum()))
+        print("[bench] %s: %s" % (name, res[name]), file=sys.stderr, flush=True)
+        del ix
+    print(json.dumps({"metric": "update strategies on the same drifting workload", "n_gpus": 1, "steps": T, "data": "synthetic",
+                      "config": {"workload": "%s shape, %d units, prefill %d, budget %d, %d decode steps, quality sampled every %d steps"
+                                             % (base.name, U, base.prefill, B, T, every)},
+                      "variants": res}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -90,12 +162,19 @@ def main():
     ap.add_argument("--full-horizon", action="store_true",
                     help="run the configuration to the end of its own decode length (steps = that length minus the "
                          "warm-up) with the cluster capacity such a run needs")
+    ap.add_argument("--variants", action="store_true",
+                    help="instead of the benchmark line: adaptive, static-update and token-level retrieval on the same "
+                         "workload (default 32 units), with recall, attention error and cluster variance")
+    ap.add_argument("--variant-every", type=int, default=128)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="skip the HIP events around the dominant kernel")
     a = ap.parse_args()
     if a.gpus != 1:
         sys.exit("bench.py: this path runs on one GPU; units (layer, sequence, KV head) are independent and would "
                  "shard over GPUs without communication, but no multi-GPU run exists here. Use --gpus 1.")
+
+    if a.variants:
+        return variants_report(a)
 
     import numpy as np
     import torch
@@ -155,6 +234,23 @@ def main():
     e1.record(st)
     torch.cuda.synchronize()
     prefill_ms = e0.elapsed_time(e1)
+    # the same prompt through chunked prefill: k-means on the first half, adaptive extension with the second half
+    half = spec.prefill // 2
+    Ka, Va, Kb, Vb = (x.contiguous() for x in (K0[:, :half], V0[:, :half], K0[:, half:], V0[:, half:]))
+    init_half = (init % half).contiguous() if spec.n_clusters_init <= half else None
+    chunked = None
+    if init_half is not None and int(torch.stack([torch.unique(r).numel() == r.numel() for r in init_half]).all()):
+        ix.dynakv_build_index(Ka, Va, init_half)
+        e0.record(st)
+        ix.dynakv_extend_index(Kb, Vb)
+        e1.record(st)
+        torch.cuda.synchronize()
+        sx = ix.dynakv_export_state(["n_clusters", "error"])
+        chunked = {"extend_ms": e0.elapsed_time(e1), "tokens_per_unit": spec.prefill - half,
+                   "tokens_per_s_all_units": (spec.prefill - half) * U / (e0.elapsed_time(e1) * 1e-3),
+                   "clusters_mean_after": float(sx["n_clusters"].float().mean()), "error_words": int(sx["error"].abs().sum())}
+    ix.dynakv_build_index(K0, V0, init)          # back to the index the decode steps start from
+    torch.cuda.synchronize()
     kmeans_flop = 2.0 * spec.prefill * spec.n_clusters_init * d * spec.kmeans_iters * U
 
     qs, ks, os_, ls = Q.data_ptr(), Kn.data_ptr(), out.data_ptr(), lse.data_ptr()
@@ -223,7 +319,8 @@ def main():
                                 a.warmup, T, spec.n_components)},
         "roofline": roof,
         "prefill": {"ms": prefill_ms, "kmeans_algorithmic_tflops": kmeans_flop / (prefill_ms * 1e-3) / 1e12,
-                    "frac_of_mfma_peak": kmeans_flop / (prefill_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS},
+                    "frac_of_mfma_peak": kmeans_flop / (prefill_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS,
+                    "chunked_second_half": chunked},
         "index": {"clusters_mean": float(state["n_clusters"].float().mean()), "clusters_max": int(state["n_clusters"].max()),
                   "splits": int(c1[:, 0].sum()),
                   "forced_splits": int(c1[:, 2].sum()), "input_generation_s": gen_s},

@@ -127,6 +127,16 @@ dynakv_status_t dynakv_destroy(dynakv_index_t* index);
 dynakv_status_t dynakv_build_index(dynakv_index_t* index, const void* K, const void* V, int32_t n_tokens,
                                    const int32_t* init_idx, void* stream);
 
+/* Adaptive clustering applied continuously through a long prefill (Section 7, Discussion 1): instead of one k-means
+ * over the whole prompt (whose keys must all be resident at once), the index is built from the first chunk and
+ * every further chunk is added with this call: its entries go through Algorithm 1's decode block one after the
+ * other (nearest cluster, UpdateVar, threshold test), and because the chunk is resident a flagged cluster is
+ * split at once (as with buffer_max = 0), whatever the configured buffer.  The active set is not consulted.
+ *   K, V      device, [U][n_tokens][head_dim] in cfg.dtype, contiguous; read only
+ *   n_tokens  >= 1; tokens beyond max_tokens are refused with DYNAKV_ERR_TOKENS
+ * One kernel: each unit's workgroup walks its chunk in order. */
+dynakv_status_t dynakv_extend_index(dynakv_index_t* index, const void* K, const void* V, int32_t n_tokens, void* stream);
+
 /* One retrieval (Algorithm 1, decode block: the top clusters by query-centroid similarity are loaded;
  * Section 4.1) followed by softmax attention over the retrieved entries (Section 7, attention over reordered KV):
  * score_j = scale * reduce_g <q_g, r~_j>, r~_j = the copy of the centroid selected by cfg.search_copy;

@@ -77,6 +77,7 @@ def _load():
         lib.oracle_retrieve_attend.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
         lib.oracle_append.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         lib.oracle_split.argtypes = [C.c_void_p]
+        lib.oracle_extend.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int]
         for f in ("oracle_num_clusters", "oracle_num_tokens", "oracle_error", "oracle_last_assign"):
             getattr(lib, f).argtypes = [C.c_void_p, C.c_int]
         lib.oracle_tau.argtypes = [C.c_void_p, C.c_int]
@@ -175,6 +176,13 @@ class Oracle:
 
     def split(self):
         self._lib.oracle_split(self._h)
+
+    def extend(self, K, V):
+        """K, V: [U, n, d]: n more prefill entries per unit, clustered adaptively one by one (every cluster resident)."""
+        K, kp = _f32(K)
+        V, vp = _f32(V)
+        assert K.shape[0] == self.cfg.n_units and K.shape[2] == self.cfg.head_dim and V.shape == K.shape
+        self._lib.oracle_extend(self._h, kp, vp, K.shape[1])
 
     # ---- state ------------------------------------------------------------------------------
     def num_clusters(self, u): return self._lib.oracle_num_clusters(self._h, u)

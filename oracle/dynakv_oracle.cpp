@@ -659,6 +659,23 @@ int oracle_append(void* h, const float* k, const float* v) {
   return 0;
 }
 
+// Adaptive clustering applied continuously through a long prefill (Section 7, Discussion 1): n more entries per
+// unit, one after the other, each assigned, tested against the threshold and, since the chunk is resident, split
+// at once where flagged (the decode block of Algorithm 1 with every cluster in memory).  K, V: [U][n][d].
+int oracle_extend(void* h, const float* K, const float* V, int n) {
+  Oracle* o = (Oracle*)h;
+  Config c = o->cfg;
+  c.buffer_max = 0;
+  const size_t stride = (size_t)n * c.head_dim;
+  UNIT_LOOP(o)
+  for (int u = 0; u < c.n_units; ++u)
+    for (int t = 0; t < n; ++t) {
+      append_unit(c, o->units[u], K + u * stride + (size_t)t * c.head_dim, V + u * stride + (size_t)t * c.head_dim);
+      split_unit(c, o->units[u]);
+    }
+  return 0;
+}
+
 int oracle_split(void* h) {
   Oracle* o = (Oracle*)h;
   UNIT_LOOP(o)

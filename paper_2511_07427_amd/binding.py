@@ -85,6 +85,7 @@ def load():
         lib.dynakv_create.argtypes = [C.POINTER(_Cfg), vp, C.c_size_t, C.POINTER(vp)]
         lib.dynakv_destroy.argtypes = [vp]
         lib.dynakv_build_index.argtypes = [vp, vp, vp, i32, vp, vp]
+        lib.dynakv_extend_index.argtypes = [vp, vp, vp, i32, vp]
         lib.dynakv_retrieve_attend.argtypes = [vp, vp, i32, vp, vp, vp]
         lib.dynakv_retrieve_attend_static.argtypes = [vp, vp, i32, vp, vp, vp]
         lib.dynakv_append.argtypes = [vp, vp, vp, vp]
@@ -158,6 +159,13 @@ class Index:
         vp = _dev(V, self._tdtype, (c.n_units, n, c.head_dim))
         ip = _dev(init_idx, torch.int32, (c.n_units, c.n_clusters_init))
         _check(self._lib.dynakv_build_index(self._h, kp, vp, n, ip, _stream()), "dynakv_build_index")
+
+    def dynakv_extend_index(self, K: torch.Tensor, V: torch.Tensor):
+        c = self.cfg
+        n = K.shape[1]
+        kp = _dev(K, self._tdtype, (c.n_units, n, c.head_dim))
+        vp = _dev(V, self._tdtype, (c.n_units, n, c.head_dim))
+        _check(self._lib.dynakv_extend_index(self._h, kp, vp, n, _stream()), "dynakv_extend_index")
 
     def dynakv_retrieve_attend(self, Q: torch.Tensor, token_budget: int, out: torch.Tensor, lse: torch.Tensor | None):
         c = self.cfg

@@ -284,6 +284,15 @@ dynakv_status_t dynakv_append(dynakv_index_t* ix, const void* k_new, const void*
   return launch_append(ix->view, k_new, v_new, false, false, (hipStream_t)stream) == hipSuccess ? DYNAKV_OK : DYNAKV_EHIP;
 }
 
+dynakv_status_t dynakv_extend_index(dynakv_index_t* ix, const void* K, const void* V, int32_t n_tokens, void* stream) {
+  if (!ix || !K || !V || n_tokens < 1) return DYNAKV_EINVAL;
+  if (!ix->built) return DYNAKV_ESTATE;
+  if (ix->view.token_level) return DYNAKV_EINVAL;
+  View v = ix->view;
+  v.Bmax = 0;                                        // the chunk is resident: flagged clusters are split at once
+  return launch_extend(v, K, V, n_tokens, (hipStream_t)stream) == hipSuccess ? DYNAKV_OK : DYNAKV_EHIP;
+}
+
 dynakv_status_t dynakv_split(dynakv_index_t* ix, void* stream) {
   if (!ix) return DYNAKV_EINVAL;
   if (!ix->built) return DYNAKV_ESTATE;

@@ -406,6 +406,7 @@ hipError_t launch_gather_attend(const View& v, const void* Q, float* out, float*
 // split: the unit's due splits follow in the same launch.
 hipError_t launch_append(const View& v, const void* k, const void* val, bool prescanned, bool split, hipStream_t st);
 hipError_t launch_split(const View& v, hipStream_t st);
+hipError_t launch_extend(const View& v, const void* K, const void* V, int n, hipStream_t st);
 hipError_t launch_export(const View& v, const dynakv_state_t& dst, hipStream_t st);
 hipError_t launch_import(const View& v, const dynakv_state_t& src, hipStream_t st);
 

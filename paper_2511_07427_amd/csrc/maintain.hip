@@ -104,6 +104,96 @@ __global__ __launch_bounds__(256) void append_kernel(View v, const void* kin, co
   }
 }
 
+// ------------------------------------------------------------------------------------------- chunked prefill
+// Adaptive clustering through a long prefill (Section 7, Discussion 1): one workgroup per unit walks the chunk's n
+// entries in order; each entry is assigned to its nearest cluster (matrix cores + float64 where needed for the
+// 16-bit search copy, float64 scan for float32 means), appended with UpdateVar and the threshold test, and a
+// flagged cluster is split at once (the view's B_max is 0).  K, V: [U][n][128].
+template <int DT, bool MEAN>
+__global__ __launch_bounds__(256) void extend_kernel(View v, const void* K, const void* V, int n) {
+  __shared__ AppendSmem a;
+  __shared__ double sv[16];
+  __shared__ int si[16];
+  __shared__ float s2[16];
+  __shared__ int s_rmax2;
+  __shared__ SplitLds<true> sp;
+  constexpr bool BF = DT == DYNAKV_BF16;
+  const int u = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int es = elem_size(v.dtype);
+  for (int t = 0; t < n; ++t) {
+    // the entry's rows, as pointers that the per-unit indexing of the append (u * 128 + d) lands on
+    const size_t shift = ((size_t)u * n + t - u) * kHeadDim * es;
+    const void* kin = (const char*)K + shift;
+    const void* vin = (const char*)V + shift;
+    const int M = v.M[u], N = v.N[u];
+    if (N >= v.Ncap || M <= 0) {                       // workgroup-uniform
+      if (tid == 0) v.err[u] |= DYNAKV_ERR_TOKENS;
+      return;
+    }
+    float k2 = 0.f;
+    if (tid < kHeadDim) {
+      const float kf = load_elem(kin, (size_t)u * kHeadDim + tid, v.dtype);
+      a.kd[tid] = (double)kf;
+      k2 = kf * kf;
+    }
+    if (tid == 0) s_rmax2 = 0;
+    __syncthreads();
+    int j;
+    if constexpr (MEAN) {
+      const float* R = unit_R(v, u);
+      double best = __builtin_inf();
+      int arg = -1;
+      for (int jj = tid; jj < M; jj += 256) {
+        f4 row[8];
+        double dist[1];
+        load_centroid_head(R, jj, row);
+        centroid_sums<1>(R, jj, row, dist, [&](int d, float rv, double (&acc)[1]) __attribute__((always_inline)) {
+          const double x = a.kd[d] - (double)rv;
+          acc[0] = fma(x, x, acc[0]);
+        });
+        if (dist[0] < best || arg < 0) { best = dist[0]; arg = jj; }
+      }
+      j = block_argmin<256>(best, arg, sv, si);
+    } else {
+      for (int o = 32; o > 0; o >>= 1) k2 += __shfl_xor(k2, o);
+      if (lane == 0) s2[wave] = k2;
+      const uint4* tiles = (const uint4*)unit_Rq(v, u);
+      float* zd = v.zdist + (size_t)u * v.Mcap;
+      ScoreRows<1> A;
+      load_score_rows<1>(A, 0, nullptr, (const char*)kin + (size_t)u * kHeadDim * es, 0, lane);    // row 0 = the entry
+      float zb = -__builtin_inff(), z2 = -__builtin_inff(), rmax2 = 0.f;
+      int jb = -1;
+      const int ntile = (M + kTileClusters - 1) / kTileClusters;
+      for (int T = wave; T < ntile; T += 4) {
+        uint4 b[4];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) b[s] = tiles[((size_t)T * 4 + s) * 64 + lane];
+        float red, kdot, nrm2;
+        score_tile<BF, 1, true>(b, A, 0, DYNAKV_GROUP_MAX, lane, red, kdot, nrm2);
+        const int jj = T * kTileClusters + lane;
+        if (lane < kTileClusters && jj < M) {
+          const float z = kdot - 0.5f * nrm2;
+          zd[jj] = z;
+          rmax2 = fmaxf(rmax2, nrm2);
+          if (jb < 0 || z > zb) { z2 = jb < 0 ? z2 : zb; zb = z; jb = jj; }
+          else z2 = fmaxf(z2, z);
+        }
+      }
+#pragma unroll
+      for (int o = 8; o > 0; o >>= 1) rmax2 = fmaxf(rmax2, __shfl_xor(rmax2, o));
+      if (lane == 0) atomicMax(&s_rmax2, __float_as_int(rmax2));
+      __syncthreads();
+      const float kn = __builtin_sqrtf(s2[0] + s2[1]) * 1.0001f;
+      j = nearest_resolve<256>(v, u, M, zb, jb, z2, kn, __int_as_float(s_rmax2), zd, unit_Rq(v, u), a.kd, sv, si, s2);
+    }
+    const AppendFetch f = append_fetch(v, u, j);
+    append_commit<256>(v, u, j, M, N, kin, vin, a, f);
+    __syncthreads();                                    // the append's record is in place for the whole workgroup
+    split_unit<DT>(v, u, sp.raw, sp.wk, false);
+    __syncthreads();                                    // and the unit's counters for the next entry
+  }
+}
+
 // Baseline without clustering (Section 8.1): the new entry becomes cluster M of its unit, its own representative.
 __global__ __launch_bounds__(256) void append_token_kernel(View v, const void* kin, const void* vin) {
   __shared__ int s_page;
@@ -385,6 +475,17 @@ hipError_t launch_append(const View& v, const void* k, const void* val, bool pre
   else DYNAKV_APPEND(DYNAKV_BF16);
 #undef DYNAKV_APPEND
 #undef DYNAKV_APPEND_M
+  return hipGetLastError();
+}
+hipError_t launch_extend(const View& v, const void* K, const void* V, int n, hipStream_t st) {
+  if (v.dtype == DYNAKV_F32) extend_kernel<DYNAKV_F32, true><<<v.U, 256, 0, st>>>(v, K, V, n);
+  else if (v.dtype == DYNAKV_F16) {
+    if (v.search_mean) extend_kernel<DYNAKV_F16, true><<<v.U, 256, 0, st>>>(v, K, V, n);
+    else extend_kernel<DYNAKV_F16, false><<<v.U, 256, 0, st>>>(v, K, V, n);
+  } else {
+    if (v.search_mean) extend_kernel<DYNAKV_BF16, true><<<v.U, 256, 0, st>>>(v, K, V, n);
+    else extend_kernel<DYNAKV_BF16, false><<<v.U, 256, 0, st>>>(v, K, V, n);
+  }
   return hipGetLastError();
 }
 hipError_t launch_split(const View& v, hipStream_t st) {

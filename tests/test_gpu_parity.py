@@ -337,6 +337,40 @@ def test_token_level_mode(dtype, N0, M0):
     assert int(st["size"][:, M0:M0 + 36].min()) == 1
 
 
+@pytest.mark.parametrize("dtype,kw", [("f16", {}), ("bf16", {}), ("f32", {}), ("f16", dict(search_copy=1))])
+def test_chunked_prefill_extension(dtype, kw):
+    """dynakv_extend_index: k-means on the first chunk, the second chunk (drifted keys) added entry by entry with every
+    cluster resident; compared with the oracle's extension, then decode steps go on from the extended index."""
+    s = CONFIGS["llama3_8b"].scaled(dtype=dtype, prefill=1024, n_clusters_init=48, budget=300, var_alpha=1.25, drift_std=0.1)
+    U, n2, steps = 3, 384, 24
+    w = generate(s, units=range(U), steps=n2 + steps)
+    ix, o = make_pair(s, U, max_tokens=1024 + n2 + steps, kmeans_iters=4, **kw)
+    ix.dynakv_build_index(to_dev(w["K0"], dtype), to_dev(w["V0"], dtype), torch.from_numpy(w["init_idx"]).to(DEV))
+    o.build_index(w["K0"], w["V0"], w["init_idx"])
+    tally = Tally()
+    compare_build(ix, o, tally, 1024)
+    K1, V1 = np.ascontiguousarray(w["Knew"][:n2].transpose(1, 0, 2)), np.ascontiguousarray(w["Vnew"][:n2].transpose(1, 0, 2))
+    ix.dynakv_extend_index(to_dev(K1, dtype), to_dev(V1, dtype))
+    o.extend(K1, V1)
+    # the extension takes hundreds of decisions between two comparisons: a tie in any of them shows as a different
+    # partition with no single margin to blame, so the comparison is strict (none occurred on these inputs)
+    st = ix.dynakv_export_state(["n_clusters", "n_tokens", "flag", "members", "offsets", "error"])
+    for u in range(U):
+        M = o.num_clusters(u)
+        off, mem = o.members(u)
+        assert st["n_clusters"][u] == M > 48 and st["n_tokens"][u] == 1024 + n2 and st["error"][u] == 0
+        assert int(st["flag"][u].sum()) == 0
+        np.testing.assert_array_equal(st["offsets"][u, :M + 1].numpy(), off)
+        np.testing.assert_array_equal(st["members"][u, :1024 + n2].numpy(), mem)
+    assert not compare_state(ix, o, tally, "after the extension", assign=False)
+    w2 = {k: (v[n2:] if k in ("Q", "Knew", "Vnew") else v) for k, v in w.items()}
+    sp = parity.Stepper(ix, o, s, w2, None, 300)
+    sp.tally = tally
+    for t in range(steps):
+        sp.step(t, t % 2 == 1, attention=True, full=(t % 8 == 0 or t == steps - 1))
+    say("chunked prefill", dtype, kw, sp.report())
+
+
 def test_capacity_limits_set_the_error_word_and_keep_state():
     s = WorkloadSpec("cap", "f16", 1, 2, 64, 8, 4, 32, 4, 0.5, var_alpha=0.5, size_factor=0.0, buffer_max=0,
                      max_cluster_factor=1, seed=5)

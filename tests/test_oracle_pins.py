@@ -442,6 +442,41 @@ def test_token_level_mode_retrieves_the_exact_top_b_tokens():
     np.testing.assert_array_equal(c["centroids"][300:], w["Knew"][:, 0])
 
 
+def test_chunked_prefill_extension_keeps_the_partition_and_splits_at_once():
+    """Adaptive clustering through a long prefill: the first chunk is clustered by k-means, the rest is added entry by
+    entry with every cluster resident.  Invariants (every token in exactly one cluster, no flag left, Eq. 4 and the
+    two-pass variance on every cluster that was split), and the lower variance than appending without splits."""
+    s = CONFIGS["tiny"].scaled(prefill=1024, n_clusters_init=24, var_alpha=1.2, size_factor=0.0, drift_std=0.15)
+    w = generate(s, steps=512)
+    K1, V1 = w["Knew"].transpose(1, 0, 2), w["Vnew"].transpose(1, 0, 2)          # the second chunk: drifted keys
+    kw = dict(n_units=1, group_size=4, head_dim=128, n_clusters_init=24, max_clusters=512, max_tokens=1536, kmeans_iters=4,
+              buffer_max=16, var_alpha=1.2)
+    o = Oracle(OracleConfig(**kw))
+    o.build_index(w["K0"], w["V0"], w["init_idx"])
+    o.extend(K1, V1)
+    c, (off, mem) = o.clusters(0), o.members(0)
+    assert o.num_tokens(0) == 1536 and sorted(mem.tolist()) == list(range(1536))
+    assert c["flag"].sum() == 0 and c["b"].sum() == 0 and o.num_clusters(0) > 24 and o.diagnostics(0)["forced_splits"] == 0
+    allK = np.concatenate([w["K0"][0], K1[0]]).astype(np.float64)
+    for j in range(24, o.num_clusters(0)):                                        # children of splits: exact statistics
+        m = mem[off[j]:off[j + 1]]
+        np.testing.assert_allclose(c["centroids"][j], allK[m].mean(0), rtol=1e-5, atol=1e-6)
+        assert c["M2"][j] == pytest.approx(((allK[m] - allK[m].mean(0)) ** 2).sum(), rel=1e-5, abs=1e-9)
+    # the same entries through append + split with an empty active set but buffer_max = 0 give the same index
+    p = Oracle(OracleConfig(**dict(kw, buffer_max=0)))
+    p.build_index(w["K0"], w["V0"], w["init_idx"])
+    for t in range(512):
+        p.append(K1[:, t], V1[:, t]); p.split()
+    np.testing.assert_array_equal(p.members(0)[1], mem)
+    np.testing.assert_array_equal(p.clusters(0)["M2"], c["M2"])
+    # static update of the same chunk leaves wider clusters
+    q = Oracle(OracleConfig(**dict(kw, update_mode=1)))
+    q.build_index(w["K0"], w["V0"], w["init_idx"])
+    q.extend(K1, V1)
+    cq = q.clusters(0)
+    assert q.num_clusters(0) == 24 and c["M2"].sum() / 1536 < 0.8 * cq["M2"].sum() / 1536
+
+
 def test_imported_state_continues_like_the_original():
     s = CONFIGS["tiny"].scaled(var_alpha=1.2, buffer_max=4)
     w = generate(s, steps=96)
