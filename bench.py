@@ -237,9 +237,9 @@ def main():
     # the same prompt through chunked prefill: k-means on the first half, adaptive extension with the second half
     half = spec.prefill // 2
     Ka, Va, Kb, Vb = (x.contiguous() for x in (K0[:, :half], V0[:, :half], K0[:, half:], V0[:, half:]))
-    init_half = (init % half).contiguous() if spec.n_clusters_init <= half else None
     chunked = None
-    if init_half is not None and int(torch.stack([torch.unique(r).numel() == r.numel() for r in init_half]).all()):
+    if spec.n_clusters_init <= half:
+        init_half = (torch.arange(spec.n_clusters_init, dtype=torch.int32, device=dev) * (half // spec.n_clusters_init)).repeat(U, 1).contiguous()
         ix.dynakv_build_index(Ka, Va, init_half)
         e0.record(st)
         ix.dynakv_extend_index(Kb, Vb)

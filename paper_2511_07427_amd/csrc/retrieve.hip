@@ -1262,7 +1262,9 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   const SelectLds sel{skey, ssz, smem + kKeys + kSizes, hist, ssz, sm, misc, list, kFusedList};
   const SelectExact ex{score_eps(v, rn.qbound, unit_rmax2), Q};
   const int nlist = select_phase<NT>(v, u, M, budget, sel, ex, true);
-  if (nlist > kFusedList) __syncthreads();            // the page loop will read the list back from memory
+  // a full barrier where other threads read back what the selection wrote to memory: the active-set flags (plan of
+  // the splits) or a list too long for LDS (page loop)
+  if (SPLIT || nlist > kFusedList) __syncthreads();
   else lds_barrier();
 
   // ---- the append (scores and selection saw the index as it was before); with SPLIT the first wavefront
