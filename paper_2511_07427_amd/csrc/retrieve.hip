@@ -74,56 +74,68 @@ __global__ __launch_bounds__(256) void score_mean_kernel(View v, const void* Q, 
   }
 }
 
-// (b) 16-bit search copy: matrix cores.  grid (ceil(Mcap / 256), U), four wavefronts, four tiles of 16 clusters
-// each: 16 KB per wavefront in flight.  SCORES: rows 0..G-1 are the query heads and the scaled, group-reduced
+// (b) 16-bit search copy: matrix cores.  grid (workgroups per unit, U), four wavefronts, each taking groups of four
+// tiles of 16 clusters: 16 KB per wavefront in flight, twice that while the next group is requested.  SCORES: rows 0..G-1 are the query heads and the scaled, group-reduced
 // scores go to v.score; NEAR: row G is the step's new key and z_j = <k, r~_j> - |r~_j|^2 / 2 goes to v.zdist for
 // the append kernel to pick the nearest cluster from.  The largest |r~_j|^2 is folded into v.rmax2.
 template <bool BF, int NBLK, bool SCORES, bool NEAR>
 __global__ __launch_bounds__(256) void score_mfma_kernel(View v, const void* Q, const void* kin) {
   const int u = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const uint4* tiles = (const uint4*)unit_Rq(v, u);
-  const int t0 = blockIdx.x * 16 + wave * 4;
-  uint4 b[4][4];
-  auto fetch = [&]() __attribute__((always_inline)) {
+  // groups of 64 clusters (four tiles) are dealt round-robin to the wavefronts of the unit's workgroups
+  const int g0 = blockIdx.x * 4 + wave, gstep = gridDim.x * 4;
+  uint4 b[4][4], nb[4][4];
+  auto fetch = [&](uint4 (&dst)[4][4], int g) __attribute__((always_inline)) {
 #pragma unroll
     for (int t = 0; t < 4; ++t)
 #pragma unroll
       for (int s = 0; s < 4; ++s)
-        b[t][s] = (size_t)(t0 + t + 1) * kTileElems <= v.Rstride ? tiles[((size_t)(t0 + t) * 4 + s) * 64 + lane] : uint4{0, 0, 0, 0};
+        dst[t][s] = (size_t)(g * 4 + t + 1) * kTileElems <= v.Rstride ? tiles[((size_t)(g * 4 + t) * 4 + s) * 64 + lane] : uint4{0, 0, 0, 0};
   };
   // the first M0 clusters exist in every state (M never drops below M0): their rows are requested before M is known
-  const bool early = (t0 + 4) * kTileClusters <= v.M0;
-  if (early) fetch();
+  const bool early = (g0 + 1) * 64 <= v.M0;
+  if (early) fetch(b, g0);
   const int M = v.M[u];
-  if (t0 * kTileClusters >= M) return;
-  if (!early) fetch();
+  if (g0 * 64 >= M) return;
+  if (!early) fetch(b, g0);
   ScoreRows<NBLK> A;
   load_score_rows<NBLK>(A, SCORES ? v.G : 0, Q, NEAR ? kin : nullptr, u, lane);
   const int G = SCORES ? v.G : 0;
-  float rmax2 = 0.f, zb = -__builtin_inff(), z2 = -__builtin_inff();
-  int jb = -1;
+  float rmax2 = 0.f;
+  for (int g = g0; g * 64 < M; g += gstep) {
+    const bool more = (g + gstep) * 64 < M;
+    if (more) fetch(nb, g + gstep);                   // the next group's rows are in flight while this one is consumed
+    float zb = -__builtin_inff(), z2 = -__builtin_inff();
+    int jb = -1;
 #pragma unroll
-  for (int t = 0; t < 4; ++t) {
-    if ((t0 + t) * kTileClusters >= M) break;
-    float red, kdot, nrm2;
-    score_tile<BF, NBLK, NEAR>(b[t], A, G, v.group_reduce, lane, red, kdot, nrm2);
-    const int j = (t0 + t) * kTileClusters + lane;
-    if (lane < kTileClusters && j < M) {
-      if constexpr (SCORES) v.score[(size_t)u * v.Mcap + j] = red * v.scale_f;
-      if constexpr (NEAR) {
-        const float z = kdot - 0.5f * nrm2;
-        v.zdist[(size_t)u * v.Mcap + j] = z;
-        if (jb < 0 || z > zb) { z2 = jb < 0 ? z2 : zb; zb = z; jb = j; }
-        else z2 = fmaxf(z2, z);
+    for (int t = 0; t < 4; ++t) {
+      if ((g * 4 + t) * kTileClusters >= M) break;
+      float red, kdot, nrm2;
+      score_tile<BF, NBLK, NEAR>(b[t], A, G, v.group_reduce, lane, red, kdot, nrm2);
+      const int j = (g * 4 + t) * kTileClusters + lane;
+      if (lane < kTileClusters && j < M) {
+        if constexpr (SCORES) v.score[(size_t)u * v.Mcap + j] = red * v.scale_f;
+        if constexpr (NEAR) {
+          const float z = kdot - 0.5f * nrm2;
+          v.zdist[(size_t)u * v.Mcap + j] = z;
+          if (jb < 0 || z > zb) { z2 = jb < 0 ? z2 : zb; zb = z; jb = j; }
+          else z2 = fmaxf(z2, z);
+        }
+        rmax2 = fmaxf(rmax2, nrm2);
       }
-      rmax2 = fmaxf(rmax2, nrm2);
     }
-  }
-  if constexpr (NEAR) {             // this wavefront's 64 clusters: best, its cluster, runner-up
-    wave_best2(zb, jb, z2);
-    if (lane == 0) {
-      const size_t w = (size_t)u * v.NB * 4 + blockIdx.x * 4 + wave;
-      v.near_zb[w] = zb; v.near_z2[w] = z2; v.near_zj[w] = jb;
+    if constexpr (NEAR) {             // this group's 64 clusters: best, its cluster, runner-up
+      wave_best2(zb, jb, z2);
+      if (lane == 0) {
+        const size_t w = (size_t)u * v.NB * 4 + g;
+        v.near_zb[w] = zb; v.near_z2[w] = z2; v.near_zj[w] = jb;
+      }
+    }
+    if (more) {
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int s = 0; s < 4; ++s) b[t][s] = nb[t][s];
     }
   }
 #pragma unroll
@@ -1410,8 +1422,16 @@ hipError_t launch_retrieve_fused(const View& v, const void* Q, int budget, float
   return hipGetLastError();
 }
 
+// Workgroups per unit of the matrix-core score kernel: about five per compute unit over all units, each wavefront
+// walking several groups of 64 clusters with the next group's rows in flight.
+static dim3 score_grid(const View& v) {
+  int gx = (1280 + v.U - 1) / v.U;
+  gx = gx < 1 ? 1 : (gx > v.NB ? v.NB : gx);
+  return dim3(gx, v.U);
+}
+
 hipError_t launch_score_select(const View& v, const void* Q, int budget, const void* kin, hipStream_t st) {
-  const dim3 grid((v.Mcap + 255) / 256, v.U);
+  dim3 grid((v.Mcap + 255) / 256, v.U);
   if (v.search_mean) {
 #define DYNAKV_SCORE_G(GP)                                                              \
   do {                                                                                  \
@@ -1429,6 +1449,7 @@ hipError_t launch_score_select(const View& v, const void* Q, int budget, const v
     if (kin) score_mfma_kernel<BF, NBLK, true, true><<<grid, 256, 0, st>>>(v, Q, kin);          \
     else score_mfma_kernel<BF, NBLK, true, false><<<grid, 256, 0, st>>>(v, Q, nullptr);         \
   } while (0)
+    grid = score_grid(v);
     const bool two = v.G + (kin ? 1 : 0) > 16;
     if (v.dtype == DYNAKV_BF16) { if (two) DYNAKV_SCORE_B(true, 2); else DYNAKV_SCORE_B(true, 1); }
     else { if (two) DYNAKV_SCORE_B(false, 2); else DYNAKV_SCORE_B(false, 1); }
@@ -1441,7 +1462,7 @@ hipError_t launch_score_select(const View& v, const void* Q, int budget, const v
 
 // The distances of a new key alone (an append outside a whole-step call, 16-bit search copy).
 hipError_t launch_near(const View& v, const void* kin, hipStream_t st) {
-  const dim3 grid((v.Mcap + 255) / 256, v.U);
+  const dim3 grid = score_grid(v);
   if (v.dtype == DYNAKV_BF16) score_mfma_kernel<true, 1, false, true><<<grid, 256, 0, st>>>(v, nullptr, kin);
   else score_mfma_kernel<false, 1, false, true><<<grid, 256, 0, st>>>(v, nullptr, kin);
   return hipGetLastError();
