@@ -166,6 +166,9 @@ def main():
                     help="instead of the benchmark line: adaptive, static-update and token-level retrieval on the same "
                          "workload (default 32 units), with recall, attention error and cluster variance")
     ap.add_argument("--variant-every", type=int, default=128)
+    ap.add_argument("--coretrieval-refs", type=int, default=0,
+                    help="after the prefill, lay the pages out by co-retrieval (dynakv_place_by_coretrieval) with the "
+                         "first N queries as the reference input")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="skip the HIP events around the dominant kernel")
     a = ap.parse_args()
@@ -250,6 +253,8 @@ def main():
                    "tokens_per_s_all_units": (spec.prefill - half) * U / (e0.elapsed_time(e1) * 1e-3),
                    "clusters_mean_after": float(sx["n_clusters"].float().mean()), "error_words": int(sx["error"].abs().sum())}
     ix.dynakv_build_index(K0, V0, init)          # back to the index the decode steps start from
+    if a.coretrieval_refs:
+        ix.dynakv_place_by_coretrieval(K0, V0, Q[:a.coretrieval_refs].contiguous(), spec.budget)
     torch.cuda.synchronize()
     kmeans_flop = 2.0 * spec.prefill * spec.n_clusters_init * d * spec.kmeans_iters * U
 
@@ -316,7 +321,8 @@ def main():
                                "token budget %d, at most %d clusters, decode steps %d..%d of a drifting %d-component mixture" %
                                (spec.name, U, "" if U == own_units else " INSTEAD OF THE CONFIGURATION'S %d" % own_units,
                                 G, d, spec.dtype, spec.prefill, spec.n_clusters_init, spec.budget, spec.max_clusters,
-                                a.warmup, T, spec.n_components)},
+                                a.warmup, T, spec.n_components),
+                   "coretrieval_refs": a.coretrieval_refs},
         "roofline": roof,
         "prefill": {"ms": prefill_ms, "kmeans_algorithmic_tflops": kmeans_flop / (prefill_ms * 1e-3) / 1e12,
                     "frac_of_mfma_peak": kmeans_flop / (prefill_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS,

@@ -76,6 +76,7 @@ typedef enum { DYNAKV_UPDATE_ADAPTIVE = 0, DYNAKV_UPDATE_STATIC = 1, DYNAKV_UPDA
 #define DYNAKV_ERR_SELECT 8   /* retrieval cut short: more clusters selected than the selection can order */
 #define DYNAKV_ERR_INIT 16    /* dynakv_build_index: an initial position out of range or given twice */
 #define DYNAKV_ERR_IMPORT 32  /* dynakv_import_state: inconsistent sizes; the unit keeps its previous state */
+#define DYNAKV_ERR_PLACE 64   /* dynakv_place_by_coretrieval: the unit is not as dynakv_build_index left it; not re-placed */
 
 /* Launch shape (dynakv_config_t.launch).  0 lets the library choose.  Otherwise the low byte is the number of
  * workgroups that share one unit's gather + attention (split-KV), the next byte their wavefronts (4, 8 or 16),
@@ -136,6 +137,23 @@ dynakv_status_t dynakv_build_index(dynakv_index_t* index, const void* K, const v
  *   n_tokens  >= 1; tokens beyond max_tokens are refused with DYNAKV_ERR_TOKENS
  * One kernel: each unit's workgroup walks its chunk in order. */
 dynakv_status_t dynakv_extend_index(dynakv_index_t* index, const void* K, const void* V, int32_t n_tokens, void* stream);
+
+/* Correlation-aware placement (Section 5.1, inter-cluster correlation, Eq. 8), kept here as a page-placement hint:
+ * once, right after dynakv_build_index, n_ref reference retrievals (scores and budget cut only) count how often
+ * two clusters are selected together, f(C_i, C_j) for i != j; P(ij) = f(C_i, C_j) / sum over all ordered pairs;
+ * the clusters are then chained greedily (start: largest total count; next: the cluster co-selected most often
+ * with the last one; lowest id among equals) and their pages are laid out afresh in that order, so that clusters
+ * which tend to be retrieved together sit next to each other in the page pool.  Nothing else changes: partition,
+ * statistics and retrieval results are the same as before (the active set is left as the last reference query
+ * selected it).
+ *   K, V        device, the arrays that were given to dynakv_build_index, [U][n_tokens][head_dim]
+ *   Qref        device, [n_ref][U][G][head_dim] in cfg.dtype: the reference queries (the initial input)
+ *   P           device, float32 [U][M0][M0]: receives Eq. 8's probabilities (used as the counting matrix meanwhile)
+ *   order       device, int32 [U][M0] or null: receives the chain
+ * A unit that has changed since it was built (appends, splits) is left alone and gets DYNAKV_ERR_PLACE. */
+dynakv_status_t dynakv_place_by_coretrieval(dynakv_index_t* index, const void* K, const void* V, int32_t n_tokens,
+                                            const void* Qref, int32_t n_ref, int32_t token_budget, float* P,
+                                            int32_t* order, void* stream);
 
 /* One retrieval (Algorithm 1, decode block: the top clusters by query-centroid similarity are loaded;
  * Section 4.1) followed by softmax attention over the retrieved entries (Section 7, attention over reordered KV):
@@ -220,6 +238,8 @@ typedef struct {
                                                 decisions retaken in float64 (all since build_index) */
   void* keys;            /* [U][max_tokens][head_dim] in cfg.dtype: key of every token, by position      */
   void* values;          /* [U][max_tokens][head_dim] in cfg.dtype: value of every token, by position    */
+  int32_t* first_page;   /* [U][max_clusters]   first page of cluster j in the unit's page pool (-1: none);
+                                                export only                                      */
 } dynakv_state_t;
 
 /* Copies the requested parts of the state, waits for `stream`, and returns DYNAKV_ECAPACITY if the error word of

@@ -78,6 +78,7 @@ def _load():
         lib.oracle_append.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         lib.oracle_split.argtypes = [C.c_void_p]
         lib.oracle_extend.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int]
+        lib.oracle_coretrieval.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
         for f in ("oracle_num_clusters", "oracle_num_tokens", "oracle_error", "oracle_last_assign"):
             getattr(lib, f).argtypes = [C.c_void_p, C.c_int]
         lib.oracle_tau.argtypes = [C.c_void_p, C.c_int]
@@ -176,6 +177,18 @@ class Oracle:
 
     def split(self):
         self._lib.oracle_split(self._h)
+
+    def coretrieval(self, Qref, budget: int):
+        """Qref: [n_ref, U, G, d] reference queries.  Returns (P [U, M, M] float64: co-retrieval probabilities of Eq. 8,
+        order [U, M]: the placement chain)."""
+        Q, qp = _f32(Qref)
+        U, M = self.cfg.n_units, self.num_clusters(0)
+        assert Q.shape[1:] == (U, self.cfg.group_size, self.cfg.head_dim)
+        P = np.zeros((U, M, M), np.float64)
+        order = np.zeros((U, M), np.int32)
+        if self._lib.oracle_coretrieval(self._h, qp, Q.shape[0], int(budget), P.ctypes.data, order.ctypes.data):
+            raise ValueError("oracle_coretrieval: units with different cluster counts")
+        return P, order
 
     def extend(self, K, V):
         """K, V: [U, n, d]: n more prefill entries per unit, clustered adaptively one by one (every cluster resident)."""

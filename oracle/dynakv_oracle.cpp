@@ -676,6 +676,57 @@ int oracle_extend(void* h, const float* K, const float* V, int n) {
   return 0;
 }
 
+// Inter-cluster correlation (Section 5.1, Eq. 8).  n_ref reference retrievals (query similarity and budget cut as
+// in a decode step; no attention) on the index as it stands; f(i, j) = number of them that select both cluster i and
+// cluster j (i != j; the diagonal stays 0), P(i, j) = f(i, j) / sum over all ordered pairs.  The placement order
+// puts highly correlated clusters next to each other: a greedy chain that starts at the cluster with the largest
+// total co-retrieval count and always continues with the not yet placed cluster that is co-retrieved most often with
+// the last one (lowest id among equals, also at the start).
+// Q: [n_ref][U][G][d]; P: [U][M][M] float64 (or null); order: [U][M] (or null); M = clusters of unit 0 = of every unit.
+int oracle_coretrieval(void* h, const float* Q, int n_ref, int budget, double* P, int32_t* order) {
+  Oracle* o = (Oracle*)h;
+  const Config& c = o->cfg;
+  const size_t qs = (size_t)c.group_size * c.head_dim;
+  const int M = (int)o->units[0].clusters.size();
+  for (const Unit& un : o->units)
+    if ((int)un.clusters.size() != M) return 1;
+  UNIT_LOOP(o)
+  for (int u = 0; u < c.n_units; ++u) {
+    Unit& un = o->units[u];
+    std::vector<int64_t> f((size_t)M * M, 0);
+    std::vector<double> out(qs), lse(c.group_size);
+    for (int r = 0; r < n_ref; ++r) {
+      retrieve_attend_unit(c, un, Q + ((size_t)r * c.n_units + u) * qs, budget, out.data(), lse.data());
+      for (int32_t a : un.selected)
+        for (int32_t b : un.selected)
+          if (a != b) ++f[(size_t)a * M + b];
+    }
+    int64_t total = 0;
+    for (int64_t x : f) total += x;
+    if (P)
+      for (size_t i = 0; i < f.size(); ++i) P[(size_t)u * M * M + i] = total ? (double)f[i] / (double)total : 0.0;
+    if (order) {
+      std::vector<uint8_t> placed(M, 0);
+      int last = 0;
+      int64_t best = -1;
+      for (int i = 0; i < M; ++i) {
+        int64_t row = 0;
+        for (int j = 0; j < M; ++j) row += f[(size_t)i * M + j];
+        if (row > best) { best = row; last = i; }
+      }
+      for (int k = 0; k < M; ++k) {
+        order[(size_t)u * M + k] = last;
+        placed[last] = 1;
+        int next = -1;
+        for (int j = 0; j < M; ++j)
+          if (!placed[j] && (next < 0 || f[(size_t)last * M + j] > f[(size_t)last * M + next])) next = j;
+        last = next;
+      }
+    }
+  }
+  return 0;
+}
+
 int oracle_split(void* h) {
   Oracle* o = (Oracle*)h;
   UNIT_LOOP(o)

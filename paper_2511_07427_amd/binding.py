@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libdynakv.so")
 
 DTYPES = {"f32": 0, "f16": 1, "bf16": 2}
 TORCH_DTYPES = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
-ERR_TOKENS, ERR_CLUSTERS, ERR_SPLIT_SIZE, ERR_SELECT, ERR_INIT, ERR_IMPORT = 1, 2, 4, 8, 16, 32
+ERR_TOKENS, ERR_CLUSTERS, ERR_SPLIT_SIZE, ERR_SELECT, ERR_INIT, ERR_IMPORT, ERR_PLACE = 1, 2, 4, 8, 16, 32, 64
 OK, EINVAL, ECAPACITY, ESTATE, EHIP, ENOMEM = range(6)
 SEARCH_STORAGE, SEARCH_MEAN = 0, 1
 UPDATE_ADAPTIVE, UPDATE_STATIC, UPDATE_TOKENS = 0, 1, 2
@@ -38,7 +38,7 @@ class _Cfg(C.Structure):
 
 _STATE_FIELDS = ("n_clusters", "n_tokens", "error", "tau", "centroids", "size", "buffered", "flag", "m2", "offsets",
                  "members", "scores", "n_selected", "selected", "n_gathered", "gathered", "last_assign", "counters",
-                 "keys", "values")
+                 "keys", "values", "first_page")
 # what dynakv_import_state reads
 IMPORT_FIELDS = ("n_clusters", "n_tokens", "tau", "centroids", "size", "buffered", "flag", "m2", "offsets", "members",
                  "keys", "values", "n_selected", "selected")
@@ -86,6 +86,7 @@ def load():
         lib.dynakv_destroy.argtypes = [vp]
         lib.dynakv_build_index.argtypes = [vp, vp, vp, i32, vp, vp]
         lib.dynakv_extend_index.argtypes = [vp, vp, vp, i32, vp]
+        lib.dynakv_place_by_coretrieval.argtypes = [vp, vp, vp, i32, vp, i32, i32, vp, vp, vp]
         lib.dynakv_retrieve_attend.argtypes = [vp, vp, i32, vp, vp, vp]
         lib.dynakv_retrieve_attend_static.argtypes = [vp, vp, i32, vp, vp, vp]
         lib.dynakv_append.argtypes = [vp, vp, vp, vp]
@@ -175,6 +176,20 @@ class Index:
         _check(self._lib.dynakv_retrieve_attend(self._h, qp, int(token_budget), op, lp, _stream()),
                "dynakv_retrieve_attend")
 
+    def dynakv_place_by_coretrieval(self, K: torch.Tensor, V: torch.Tensor, Qref: torch.Tensor, token_budget: int):
+        """Returns (P [U, M0, M0] float32: Eq. 8's co-retrieval probabilities, order [U, M0] int32: the placement chain),
+        both device tensors; the index's pages are laid out afresh in chain order."""
+        c = self.cfg
+        n, r = K.shape[1], Qref.shape[0]
+        kp = _dev(K, self._tdtype, (c.n_units, n, c.head_dim))
+        vp = _dev(V, self._tdtype, (c.n_units, n, c.head_dim))
+        qp = _dev(Qref, self._tdtype, (r, c.n_units, c.group_size, c.head_dim))
+        P = torch.empty(c.n_units, c.n_clusters_init, c.n_clusters_init, dtype=torch.float32, device=self.device)
+        order = torch.empty(c.n_units, c.n_clusters_init, dtype=torch.int32, device=self.device)
+        _check(self._lib.dynakv_place_by_coretrieval(self._h, kp, vp, n, qp, r, int(token_budget), P.data_ptr(),
+                                                      order.data_ptr(), _stream()), "dynakv_place_by_coretrieval")
+        return P, order
+
     def dynakv_retrieve_attend_static(self, Q: torch.Tensor, token_budget: int, out: torch.Tensor, lse: torch.Tensor | None):
         """The same retrieval with the split-KV scratch in the library's static device array; returns the status
         (ECAPACITY if the configuration needs more scratch than the array holds) instead of raising on it."""
@@ -236,9 +251,9 @@ class Index:
                     m2=((U, M), f64), offsets=((U, M + 1), i32), members=((U, N), i32), scores=((U, M), f32),
                     n_selected=((U,), i32), selected=((U, M), i32), n_gathered=((U,), i32), gathered=((U, N), i32),
                     last_assign=((U,), i32), counters=((U, 8), i64), keys=((U, N, d), self._tdtype),
-                    values=((U, N, d), self._tdtype))
+                    values=((U, N, d), self._tdtype), first_page=((U, M), i32))
 
-    def dynakv_export_state(self, fields=_STATE_FIELDS[:-2], to_cpu=True):
+    def dynakv_export_state(self, fields=_STATE_FIELDS[:-3], to_cpu=True):
         """Returns the requested parts of the state (the call waits for the stream), as CPU tensors unless
         to_cpu is False.  A set error word does not raise: the returned status is kept in `self.export_status`
         (ECAPACITY in that case) and the words are in the "error" field."""

@@ -293,6 +293,16 @@ dynakv_status_t dynakv_extend_index(dynakv_index_t* ix, const void* K, const voi
   return launch_extend(v, K, V, n_tokens, (hipStream_t)stream) == hipSuccess ? DYNAKV_OK : DYNAKV_EHIP;
 }
 
+dynakv_status_t dynakv_place_by_coretrieval(dynakv_index_t* ix, const void* K, const void* V, int32_t n_tokens,
+                                            const void* Qref, int32_t n_ref, int32_t token_budget, float* P,
+                                            int32_t* order, void* stream) {
+  if (!ix || !K || !V || !Qref || !P || n_ref < 1 || token_budget < 0) return DYNAKV_EINVAL;
+  if (n_tokens < ix->cfg.n_clusters_init || n_tokens > ix->cfg.max_tokens) return DYNAKV_EINVAL;
+  if (!ix->built) return DYNAKV_ESTATE;
+  return launch_place(ix->view, K, V, n_tokens, Qref, n_ref, token_budget, P, order, (hipStream_t)stream) == hipSuccess
+             ? DYNAKV_OK : DYNAKV_EHIP;
+}
+
 dynakv_status_t dynakv_split(dynakv_index_t* ix, void* stream) {
   if (!ix) return DYNAKV_EINVAL;
   if (!ix->built) return DYNAKV_ESTATE;

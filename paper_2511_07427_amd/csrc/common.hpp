@@ -409,5 +409,7 @@ hipError_t launch_split(const View& v, hipStream_t st);
 hipError_t launch_extend(const View& v, const void* K, const void* V, int n, hipStream_t st);
 hipError_t launch_export(const View& v, const dynakv_state_t& dst, hipStream_t st);
 hipError_t launch_import(const View& v, const dynakv_state_t& src, hipStream_t st);
+hipError_t launch_place(const View& v, const void* K, const void* V, int n_tokens, const void* Qref, int n_ref, int budget,
+                        float* P, int* order, hipStream_t st);
 
 }  // namespace dynakv

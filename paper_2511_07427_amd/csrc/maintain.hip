@@ -271,6 +271,7 @@ __global__ __launch_bounds__(1024) void export_kernel(View v, dynakv_state_t o) 
     if (o.m2) o.m2[cbase + j] = in ? v.cM2[cbase + j] : 0.0;
     if (o.scores) o.scores[cbase + j] = in ? v.score[cbase + j] : 0.f;
     if (o.selected) o.selected[cbase + j] = j < v.n_sel[u] ? v.sel_ids[cbase + j] : -1;
+    if (o.first_page) o.first_page[cbase + j] = in && v.cn[cbase + j] + v.cb[cbase + j] > 0 ? v.cpg[(cbase + j) * kInlinePages] : -1;
   }
   if (o.centroids) {
     const float* R = unit_R(v, u);
@@ -419,7 +420,8 @@ __global__ __launch_bounds__(1024) void import_meta_kernel(View v, dynakv_state_
 
 // 16 consecutive places of the storage order per workgroup, 16 threads per entry: keys and values move from
 // the snapshot (by position) into their cluster's pages as whole 16-byte chunks.
-__global__ __launch_bounds__(256) void import_copy_kernel(View v, const void* K, const void* V) {
+// `stride`: tokens per unit in K and V.
+__global__ __launch_bounds__(256) void import_copy_kernel(View v, const void* K, const void* V, int stride) {
   const int u = blockIdx.y, q = blockIdx.x * 16 + (threadIdx.x >> 4), c = threadIdx.x & 15;
   if (!v.nflagged[u] || q >= v.N[u]) return;
   const int pos = v.order[(size_t)u * v.Ncap + q];
@@ -427,7 +429,7 @@ __global__ __launch_bounds__(256) void import_copy_kernel(View v, const void* K,
   const int rank = q - v.koff[(size_t)u * (v.Mcap + 1) + j];
   const int page = v.pg_off[(size_t)u * v.Mcap + j] + rank / kPageTokens, slot = rank % kPageTokens;
   char* pg = page_ptr(v, u, page);
-  const size_t src = ((size_t)u * v.Ncap + pos) * kHeadDim + c * 8;
+  const size_t src = ((size_t)u * stride + pos) * kHeadDim + c * 8;
   if (v.dtype == DYNAKV_F32) {
     const f4* ks = (const f4*)((const float*)K + src);
     const f4* vs = (const f4*)((const float*)V + src);
@@ -442,6 +444,111 @@ __global__ __launch_bounds__(256) void import_copy_kernel(View v, const void* K,
   if (c == 0) v.ppos[((size_t)u * v.Pcap + page) * kPageTokens + slot] = pos;
 }
 
+// ------------------------------------------------------------------------------------------- placement
+// Correlation-aware placement (Section 5.1, Eq. 8).  F = P while counting: [U][M0][M0] float32 counts (exact).
+__global__ __launch_bounds__(256) void cor_zero_kernel(float* F, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) F[i] = 0.f;
+}
+// After one reference retrieval: every ordered pair of different selected clusters is counted once.  One
+// workgroup per unit; a pair belongs to one thread, and the launches of different queries follow each other.
+__global__ __launch_bounds__(256) void cor_count_kernel(View v, float* F) {
+  const int u = blockIdx.x, n = v.n_sel[u], M0 = v.M0;
+  const int* ids = v.sel_ids + (size_t)u * v.Mcap;
+  float* f = F + (size_t)u * M0 * M0;
+  for (long long t = threadIdx.x; t < (long long)n * n; t += 256) {
+    const int a = ids[t / n], b = ids[t % n];
+    if (a != b && a < M0 && b < M0) f[(size_t)a * M0 + b] += 1.f;
+  }
+}
+// One workgroup of 1024 threads per unit: the greedy chain on the counts, Eq. 8's normalisation, and the page
+// table of the unit in chain order (pg_off / cpg / ctail / pnext), for the copy kernel that follows.
+__global__ __launch_bounds__(1024) void cor_finish_kernel(View v, float* F, int* order_out, int n_tokens) {
+  __shared__ float rowsum[kMaxInitClusters];
+  __shared__ unsigned char placed[kMaxInitClusters];
+  __shared__ float rv[16];
+  __shared__ int ri[16];
+  __shared__ double rt[16];
+  __shared__ int s_last;
+  const int u = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6, M0 = v.M0;
+  const size_t cb = (size_t)u * v.Mcap;
+  float* f = F + (size_t)u * M0 * M0;
+  int* chain = v.tok_off + cb;
+  const bool fresh = v.M[u] == M0 && v.N[u] == n_tokens && v.nflag[u] == 0 && v.free_top[u] == 0;
+  if (!fresh) {                                            // workgroup-uniform
+    if (tid == 0) { atomicOr(&v.err[u], DYNAKV_ERR_PLACE); v.nflagged[u] = 0; }
+    return;
+  }
+  double tot = 0.0;
+  for (int i = tid; i < M0; i += 1024) {
+    float rs = 0.f;
+    for (int j = 0; j < M0; ++j) rs += f[(size_t)i * M0 + j];          // whole numbers below 2^24: exact
+    rowsum[i] = rs; placed[i] = 0;
+    tot += (double)rs;
+  }
+  for (int o = 32; o > 0; o >>= 1) tot += __shfl_xor(tot, o);
+  if (lane == 0) rt[w] = tot;
+  __syncthreads();
+  double total = 0.0;
+  for (int k = 0; k < 16; ++k) total += rt[k];
+  // arg-max over (value, id) pairs of the workgroup, lowest id among equals; id < 0: none
+  auto argmax = [&](float val, int id) {
+    for (int o = 32; o > 0; o >>= 1) {
+      const float ov = __shfl_xor(val, o);
+      const int oi = __shfl_xor(id, o);
+      if (oi >= 0 && (id < 0 || ov > val || (ov == val && oi < id))) { val = ov; id = oi; }
+    }
+    __syncthreads();
+    if (lane == 0) { rv[w] = val; ri[w] = id; }
+    __syncthreads();
+    if (tid == 0) {
+      float bv = rv[0]; int bi = ri[0];
+      for (int k = 1; k < 16; ++k)
+        if (ri[k] >= 0 && (bi < 0 || rv[k] > bv || (rv[k] == bv && ri[k] < bi))) { bv = rv[k]; bi = ri[k]; }
+      s_last = bi;
+    }
+    __syncthreads();
+    return s_last;
+  };
+  int last;
+  {
+    float bv = -1.f; int bi = -1;
+    for (int i = tid; i < M0; i += 1024)
+      if (rowsum[i] > bv) { bv = rowsum[i]; bi = i; }                  // ascending i per thread: the first maximum stays
+    last = argmax(bv, bi);
+  }
+  for (int k = 0; k < M0; ++k) {
+    if (tid == 0) { chain[k] = last; placed[last] = 1; }
+    __syncthreads();
+    if (k + 1 == M0) break;
+    float bv = -1.f; int bi = -1;
+    for (int j = tid; j < M0; j += 1024)
+      if (!placed[j] && f[(size_t)last * M0 + j] > bv) { bv = f[(size_t)last * M0 + j]; bi = j; }
+    last = argmax(bv, bi);
+  }
+  // Eq. 8
+  const float inv = total > 0.0 ? (float)(1.0 / total) : 0.f;
+  for (size_t t = tid; t < (size_t)M0 * M0; t += 1024) f[t] = total > 0.0 ? (float)((double)f[t] / total) : 0.f;
+  (void)inv;
+  if (order_out)
+    for (int k = tid; k < M0; k += 1024) order_out[(size_t)u * M0 + k] = chain[k];
+  // pages in chain order
+  if (tid == 0) {
+    int base = 0;
+    for (int k = 0; k < M0; ++k) {
+      const int j = chain[k];
+      v.pg_off[cb + j] = base;
+      base += (v.cn[cb + j] + kPageTokens - 1) / kPageTokens;
+    }
+    v.nflagged[u] = 1;
+  }
+  __syncthreads();
+  for (int j = tid; j < M0; j += 1024) {
+    const int np = (v.cn[cb + j] + kPageTokens - 1) / kPageTokens, base = v.pg_off[cb + j];
+    for (int p = 0; p < kInlinePages; ++p) v.cpg[(cb + j) * kInlinePages + p] = p < np ? base + p : -1;
+    v.ctail[cb + j] = np ? base + np - 1 : -1;
+    for (int p = 0; p < np; ++p) v.pnext[(size_t)u * v.Pcap + base + p] = p + 1 < np ? base + p + 1 : -1;
+  }
+}
 }  // namespace
 
 // prescanned: the score kernel of the same step has already looked at the new key (launch_score_select with kin).
@@ -498,9 +605,23 @@ hipError_t launch_export(const View& v, const dynakv_state_t& dst, hipStream_t s
   export_kernel<<<v.U, 1024, 0, st>>>(v, dst);
   return hipGetLastError();
 }
+hipError_t launch_place(const View& v, const void* K, const void* V, int n_tokens, const void* Qref, int n_ref, int budget,
+                        float* P, int* order, hipStream_t st) {
+  const size_t n = (size_t)v.U * v.M0 * v.M0;
+  cor_zero_kernel<<<1024, 256, 0, st>>>(P, n);
+  const size_t qbytes = (size_t)v.U * v.G * kHeadDim * elem_size(v.dtype);
+  for (int r = 0; r < n_ref; ++r) {
+    const hipError_t e = launch_score_select(v, (const char*)Qref + (size_t)r * qbytes, budget, nullptr, st);
+    if (e != hipSuccess) return e;
+    cor_count_kernel<<<v.U, 256, 0, st>>>(v, P);
+  }
+  cor_finish_kernel<<<v.U, 1024, 0, st>>>(v, P, order, n_tokens);
+  import_copy_kernel<<<dim3((n_tokens + 15) / 16, v.U), 256, 0, st>>>(v, K, V, n_tokens);
+  return hipGetLastError();
+}
 hipError_t launch_import(const View& v, const dynakv_state_t& src, hipStream_t st) {
   import_meta_kernel<<<v.U, 1024, 0, st>>>(v, src);
-  import_copy_kernel<<<dim3((v.Ncap + 15) / 16, v.U), 256, 0, st>>>(v, src.keys, src.values);
+  import_copy_kernel<<<dim3((v.Ncap + 15) / 16, v.U), 256, 0, st>>>(v, src.keys, src.values, v.Ncap);
   return hipGetLastError();
 }
 

@@ -30,7 +30,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_struct_sizes_match_the_header():
     assert C.sizeof(binding._Cfg) == 17 * 4
-    assert C.sizeof(binding._State) == 20 * 8
+    assert C.sizeof(binding._State) == 21 * 8
 
 
 def _cfg(**kw):

@@ -371,6 +371,57 @@ def test_chunked_prefill_extension(dtype, kw):
     say("chunked prefill", dtype, kw, sp.report())
 
 
+@pytest.mark.parametrize("dtype,launch", [("f16", 0), ("bf16", launch_shape(2, 0, LAUNCH_SEPARATE)), ("f32", 0)])
+def test_coretrieval_placement(dtype, launch):
+    """dynakv_place_by_coretrieval (Section 5.1, Eq. 8): co-retrieval probabilities and placement chain against the
+    oracle's; the page pool then follows the chain, everything else (partition, statistics, retrieval results) is
+    as before, and decode steps go on under the parity protocol."""
+    s = CONFIGS["llama3_8b"].scaled(dtype=dtype, prefill=1536, n_clusters_init=64, budget=400, var_alpha=1.3)
+    U, R, steps = 3, 24, 32
+    w = generate(s, units=range(U), steps=R + steps)
+    ix, o = make_pair(s, U, max_tokens=1536 + steps, kmeans_iters=4, launch=launch)
+    K0, V0 = to_dev(w["K0"], dtype), to_dev(w["V0"], dtype)
+    ix.dynakv_build_index(K0, V0, torch.from_numpy(w["init_idx"]).to(DEV))
+    o.build_index(w["K0"], w["V0"], w["init_idx"])
+    tally = Tally()
+    compare_build(ix, o, tally, 1536)
+    out0, lse0 = torch.empty(U, s.group_size, 128, device=DEV), torch.empty(U, s.group_size, device=DEV)
+    q_probe = to_dev(w["Q"][R], dtype)
+    ix.dynakv_retrieve_attend(q_probe, 400, out0, lse0)
+    before = ix.dynakv_export_state(["offsets", "members", "centroids", "m2", "size", "gathered", "n_gathered", "first_page"])
+    P, order = ix.dynakv_place_by_coretrieval(K0, V0, to_dev(w["Q"][:R], dtype), 400)
+    Po, oo = o.coretrieval(w["Q"][:R], 400)
+    np.testing.assert_allclose(P.cpu().numpy(), Po, rtol=1e-6, atol=1e-9)
+    np.testing.assert_array_equal(order.cpu().numpy(), oo)
+    assert float(P.sum()) == pytest.approx(U, rel=1e-4) and int((P > 0).sum()) > 0
+    out1, lse1 = torch.empty_like(out0), torch.empty_like(lse0)
+    ix.dynakv_retrieve_attend(q_probe, 400, out1, lse1)
+    after = ix.dynakv_export_state(["offsets", "members", "centroids", "m2", "size", "gathered", "n_gathered", "first_page", "error"])
+    assert not after["error"].any()
+    for k in ("offsets", "members", "centroids", "m2", "size", "gathered", "n_gathered"):
+        assert torch.equal(before[k], after[k]), k
+    assert torch.allclose(out0, out1, rtol=1e-6, atol=1e-7) and torch.allclose(lse0, lse1, atol=1e-6)
+    fp, sz, ch = after["first_page"].numpy(), after["size"].numpy(), order.cpu().numpy()
+    assert not np.array_equal(before["first_page"].numpy(), fp)
+    for u in range(U):                                  # the pool follows the chain: each cluster right after its predecessor
+        nxt = 0
+        for j in ch[u]:
+            if sz[u, j] > 0:
+                assert fp[u, j] == nxt
+                nxt += (sz[u, j] + 15) // 16
+    o.retrieve_attend(w["Q"][R], 400)                   # the oracle's active set as the library's
+    w2 = {k: (v[R:] if k in ("Q", "Knew", "Vnew") else v) for k, v in w.items()}
+    sp = parity.Stepper(ix, o, s, w2, None, 400)
+    sp.tally = tally
+    for t in range(steps):
+        sp.step(t, t % 2 == 0, attention=True, full=(t % 8 == 0 or t == steps - 1))
+    say("co-retrieval placement", dtype, hex(launch), sp.report())
+    # an index that has moved on since it was built is refused
+    ix.dynakv_place_by_coretrieval(K0, V0, to_dev(w["Q"][:2], dtype), 400)
+    st = ix.dynakv_export_state(["error"])
+    assert st["error"].tolist() == [binding.ERR_PLACE] * U
+
+
 def test_capacity_limits_set_the_error_word_and_keep_state():
     s = WorkloadSpec("cap", "f16", 1, 2, 64, 8, 4, 32, 4, 0.5, var_alpha=0.5, size_factor=0.0, buffer_max=0,
                      max_cluster_factor=1, seed=5)

@@ -477,6 +477,26 @@ def test_chunked_prefill_extension_keeps_the_partition_and_splits_at_once():
     assert q.num_clusters(0) == 24 and c["M2"].sum() / 1536 < 0.8 * cq["M2"].sum() / 1536
 
 
+def test_coretrieval_probabilities_and_placement_chain_on_a_hand_example():
+    """Section 5.1, Eq. 8 by hand: three clusters of one entry each at (10,0), (0,10), (-10,0); budget 2 selects the
+    two best clusters.  Queries (1,1) x2 -> {0,1}; (-1,1) -> {1,2}: f(0,1) = f(1,0) = 2, f(1,2) = f(2,1) = 1, sum 6;
+    cluster 1 has the largest total (3), is co-retrieved most often with 0, then 2 is left: chain 1, 0, 2."""
+    K = np.array([[10, 0], [0, 10], [-10, 0]], np.float32)[None]
+    o = Oracle(cfg(M0=3, maxc=3, maxt=8, iters=1))
+    o.build_index(K, K, np.array([[0, 1, 2]], np.int32))
+    Q = np.array([[1, 1], [1, 1], [-1, 1]], np.float32)[:, None, None, :]
+    P, order = o.coretrieval(Q, 2)
+    want = np.zeros((3, 3))
+    want[0, 1] = want[1, 0] = 2 / 6
+    want[1, 2] = want[2, 1] = 1 / 6
+    np.testing.assert_allclose(P[0], want, rtol=1e-15)
+    assert order[0].tolist() == [1, 0, 2]
+    assert P[0].sum() == pytest.approx(1.0)
+    # no co-retrieval at all (budget for one cluster): zero matrix, chain by id
+    P, order = o.coretrieval(Q, 1)
+    assert P.sum() == 0 and order[0].tolist() == [0, 1, 2]
+
+
 def test_imported_state_continues_like_the_original():
     s = CONFIGS["tiny"].scaled(var_alpha=1.2, buffer_max=4)
     w = generate(s, steps=96)
