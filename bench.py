@@ -77,8 +77,9 @@ def cpu_baseline(spec, budget):
 
 def variants_report(a):
     """The update strategies the paper compares (Section 2.3, Section 8.1, Table 5) on the same drifting workload and
-    kernels: adaptive (Algorithm 1), static update (append to the nearest cluster, never split) and no clustering
-    (every entry its own cluster: exact top-B over tokens).  Per strategy: decode steps/s, recall of the dense top-B
+    kernels: adaptive (Algorithm 1), static update (append to the nearest cluster, never split), local update (new
+    entries clustered among themselves, window by window) and no clustering (every entry its own cluster: exact
+    top-B over tokens).  Per strategy: decode steps/s, recall of the dense top-B
     tokens, share of the dense attention mass that the retrieved entries carry, error of the attention output
     against dense attention, mean intra-cluster variance, clusters per unit.  Quality is sampled every
     `--variant-every` steps through the three-call API (the gather list is read back before the split)."""
@@ -97,12 +98,15 @@ def variants_report(a):
     scale = 1.0 / np.sqrt(d)
     out, lse = torch.empty(U, G, d, device=dev), torch.empty(U, G, device=dev)
     res = {}
-    for name, mode in (("adaptive", binding.UPDATE_ADAPTIVE), ("static", binding.UPDATE_STATIC), ("tokens", binding.UPDATE_TOKENS)):
-        tok = mode == binding.UPDATE_TOKENS
+    LW, LK = 128, 16                      # local update: windows of 128 entries into 16 clusters (8 entries each)
+    for name, mode in (("adaptive", binding.UPDATE_ADAPTIVE), ("static", binding.UPDATE_STATIC), ("local", binding.UPDATE_LOCAL),
+                       ("tokens", binding.UPDATE_TOKENS)):
+        tok, loc = mode == binding.UPDATE_TOKENS, mode == binding.UPDATE_LOCAL
         M0 = base.prefill if tok else base.n_clusters_init
-        Mcap = base.prefill + T if tok else base.max_clusters
+        Mcap = base.prefill + T if tok else base.n_clusters_init + LW + LK * (T // LW + 1) if loc else base.max_clusters
         ix = binding.Index(binding.Config(U, G, base.dtype, M0, Mcap, base.prefill + T, 1 if tok else base.kmeans_iters,
-                                          base.buffer_max, 0, base.var_alpha, base.size_factor, 0.0, update_mode=mode), dev)
+                                          base.buffer_max, 0, base.var_alpha, base.size_factor, 0.0, update_mode=mode,
+                                          local_window=LW if loc else 0, local_clusters=LK if loc else 0), dev)
         init = torch.arange(base.prefill, dtype=torch.int32, device=dev).repeat(U, 1) if tok else torch.from_numpy(w["init_idx"]).to(dev)
         ix.dynakv_build_index(K0, V0, init.contiguous())
         torch.cuda.synchronize()

@@ -66,8 +66,15 @@ typedef enum { DYNAKV_SEARCH_STORAGE = 0, DYNAKV_SEARCH_MEAN = 1 } dynakv_search
  * and update its statistics, no cluster is ever flagged or split.  TOKENS: the baseline without clustering of
  * Section 8.1: every appended entry becomes a cluster of its own (build the index with n_clusters_init = n_tokens
  * and init_idx = 0..n_tokens-1), so that the retrieval is an exact top-B over tokens; needs max_clusters >=
- * max_tokens (an append beyond it is refused with DYNAKV_ERR_CLUSTERS). */
-typedef enum { DYNAKV_UPDATE_ADAPTIVE = 0, DYNAKV_UPDATE_STATIC = 1, DYNAKV_UPDATE_TOKENS = 2 } dynakv_update_mode_t;
+ * max_tokens (an append beyond it is refused with DYNAKV_ERR_CLUSTERS).  LOCAL: the local-update baseline of
+ * Section 2.3: new entries are clustered among themselves, apart from the existing clusters: each is a cluster of
+ * its own until local_window of them have come in; Lloyd's k-means over those (initial centres: every
+ * (local_window / local_clusters)-th of them, kmeans_iters iterations, a centre without members stays where it is)
+ * then replaces them by local_clusters clusters, which take the ids of the first of them.  The prefill's clusters
+ * never change.  Needs max_clusters >= n_clusters_init + local_window + local_clusters * (appends / local_window). */
+typedef enum {
+  DYNAKV_UPDATE_ADAPTIVE = 0, DYNAKV_UPDATE_STATIC = 1, DYNAKV_UPDATE_TOKENS = 2, DYNAKV_UPDATE_LOCAL = 3
+} dynakv_update_mode_t;
 
 /* bits of the per-unit device error word */
 #define DYNAKV_ERR_TOKENS 1   /* append refused: max_tokens or page pool exhausted            */
@@ -105,6 +112,8 @@ typedef struct {
                               float32 first (equal float32 scores then go by id); 0: compared as float64 */
   int32_t update_mode;     /* dynakv_update_mode_t                                              */
   int32_t launch;          /* 0, or DYNAKV_LAUNCH(..) | DYNAKV_LAUNCH_* flags                    */
+  int32_t local_window;    /* DYNAKV_UPDATE_LOCAL: entries per local clustering, 2..128; else 0  */
+  int32_t local_clusters;  /* DYNAKV_UPDATE_LOCAL: clusters it forms, 1..min(32, local_window); else 0 */
 } dynakv_config_t;
 
 /* Bytes of device workspace an index of this configuration needs (0 if the configuration is invalid). */

@@ -38,7 +38,7 @@ class _Cfg(C.Structure):
     _fields_ = [(k, C.c_int32) for k in ("n_units", "group_size", "head_dim", "n_clusters_init", "max_clusters",
                                           "max_tokens", "kmeans_iters", "buffer_max", "group_reduce")] + \
                [(k, C.c_float) for k in ("var_alpha", "size_factor", "softmax_scale")] + \
-               [(k, C.c_int32) for k in ("dtype", "search_copy", "score_round", "update_mode")]
+               [(k, C.c_int32) for k in ("dtype", "search_copy", "score_round", "update_mode", "local_window", "local_clusters")]
 
 
 @dataclass
@@ -58,7 +58,9 @@ class OracleConfig:
     dtype: str = "f32"          # storage type of K, V, Q ("f32" | "f16" | "bf16")
     search_copy: int = 0        # 0: searches read the centroids rounded to the storage type; 1: the float32 means
     score_round: int = 0        # 1: cluster scores are rounded to float32 before they are ordered
-    update_mode: int = 0        # 0: Algorithm 1; 1: static update (never flag, never split)
+    update_mode: int = 0        # 0: Algorithm 1; 1: static update; 2: every entry its own cluster; 3: local update
+    local_window: int = 0       # update_mode 3: entries per local clustering
+    local_clusters: int = 0     # update_mode 3: clusters it forms
 
 
 _lib = None

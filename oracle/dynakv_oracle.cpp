@@ -58,7 +58,12 @@ struct Config {
   int32_t update_mode;      // 0: Algorithm 1 (adaptive); 1: static update (entries join the nearest cluster,
                             //    statistics are updated, nothing is ever flagged or split: Section 2.3);
                             //    2: no clustering (the naive baseline of Section 8.1): every entry is a cluster of
-                            //    its own, so retrieval is exact top-B over tokens
+                            //    its own, so retrieval is exact top-B over tokens;
+                            //    3: local update (Section 2.3): new entries are clustered among themselves, apart from
+                            //    the existing clusters: each becomes a cluster of its own until local_window of them
+                            //    have come in, which a k-means of their own then turns into local_clusters clusters
+  int32_t local_window;     // W (update_mode 3)
+  int32_t local_clusters;   // k <= W (update_mode 3)
 };
 
 struct Cluster {
@@ -87,6 +92,7 @@ struct Unit {
   std::vector<double> scores;       // last cluster scores (after score_round, if set)
   std::vector<double> kmeans_margin;  // per prefill point: smallest assignment margin over the Lloyd iterations
   int32_t last_assign = -1;
+  int32_t local_count = 0;          // update_mode 3: entries since the last local clustering
   int32_t last_split_rounds = 0;    // Lloyd rounds of the most recent 2-means
   int32_t error = 0;
   int64_t n_splits = 0, n_failed_splits = 0, n_forced = 0;
@@ -361,12 +367,67 @@ void retrieve_attend_unit(const Config& c, Unit& u, const float* Q, int budget, 
   }
 }
 
+// ---- local update (Section 2.3): the last W entries, each a cluster of its own so far, are clustered among
+// themselves by Lloyd's k-means into k clusters that take their place (ids M - W .. M - W + k - 1).  Initial centres:
+// the entries 0, W/k, 2W/k, ... of the window (integer division); kmeans_iters iterations of assign (nearest
+// centre, ties to the lowest) and update (mean of the members, stored as float32; a centre without members stays
+// where it is); members in ascending position; exact statistics about the stored centre.
+void local_recluster(const Config& c, Unit& u) {
+  const int d = c.head_dim, W = c.local_window, k = c.local_clusters;
+  const int base = (int)u.clusters.size() - W;
+  std::vector<int32_t> pos(W);
+  for (int i = 0; i < W; ++i) pos[i] = u.clusters[base + i].members[0];
+  auto X = [&](int i) { return &u.K[(size_t)pos[i] * d]; };
+  std::vector<float> R((size_t)k * d);
+  for (int j = 0; j < k; ++j) std::copy(X(j * W / k), X(j * W / k) + d, &R[(size_t)j * d]);
+  std::vector<int32_t> label(W, 0);
+  for (int it = 0; it < c.kmeans_iters; ++it) {
+    for (int i = 0; i < W; ++i) {
+      double best = kInf, second = kInf;
+      int arg = 0;
+      for (int j = 0; j < k; ++j) {
+        const double dj = sqdist_ff(X(i), &R[(size_t)j * d], d);
+        if (dj < best) { second = best; best = dj; arg = j; }
+        else if (dj < second) second = dj;
+      }
+      label[i] = arg;
+      if (k > 1) {
+        const double xx = dot_ff(X(i), X(i), d);
+        u.mg.split = std::min(u.mg.split, norm_margin(second - best, xx - best, xx - second));
+      }
+    }
+    std::vector<double> S((size_t)k * d, 0.0);
+    std::vector<int32_t> cnt(k, 0);
+    for (int i = 0; i < W; ++i) {
+      ++cnt[label[i]];
+      for (int t = 0; t < d; ++t) S[(size_t)label[i] * d + t] += (double)X(i)[t];
+    }
+    for (int j = 0; j < k; ++j)
+      if (cnt[j] > 0)
+        for (int t = 0; t < d; ++t) R[(size_t)j * d + t] = (float)(S[(size_t)j * d + t] / (double)cnt[j]);
+  }
+  std::vector<Cluster> fresh(k);
+  for (int j = 0; j < k; ++j) fresh[j].r.assign(&R[(size_t)j * d], &R[(size_t)j * d] + d);
+  for (int i = 0; i < W; ++i) fresh[label[i]].members.push_back(pos[i]);
+  for (int j = 0; j < k; ++j) {
+    Cluster& cl = fresh[j];
+    cl.n = (int32_t)cl.members.size();
+    cl.M2 = 0.0;
+    for (int32_t p : cl.members) cl.M2 += sqdist_ff(&u.K[(size_t)p * d], cl.r.data(), d);
+    search_copy(c, cl);
+  }
+  u.clusters.resize(base);
+  for (int j = 0; j < k; ++j) u.clusters.push_back(fresh[j]);
+  u.in_req.assign(u.clusters.size(), 0);
+  if (u.mg.split <= kTieMargin) ++u.ties[4];
+}
+
 // ---- decode: assign + UpdateVar + keep / flag (Algorithm 1; Section 4.2) ----------------
 
 void append_unit(const Config& c, Unit& u, const float* k, const float* v) {
   const int d = c.head_dim, M = (int)u.clusters.size();
   if (u.N >= c.max_tokens || M == 0) { u.error |= 1; return; }
-  if (c.update_mode == 2) {           // token level: the entry becomes cluster M, its own representative
+  if (c.update_mode == 2 || c.update_mode == 3) {   // the entry becomes cluster M, its own representative
     if (M >= c.max_clusters) { u.error |= 2; return; }
     Cluster cl;
     cl.n = 1;
@@ -379,7 +440,11 @@ void append_unit(const Config& c, Unit& u, const float* k, const float* v) {
     u.clusters.push_back(cl);
     u.in_req.push_back(0);
     u.last_assign = M;
-    u.mg.assign = kInf; u.mg.trigger = kInf;
+    u.mg.assign = kInf; u.mg.trigger = kInf; u.mg.split = kInf;
+    if (c.update_mode == 3 && ++u.local_count == c.local_window) {
+      local_recluster(c, u);
+      u.local_count = 0;
+    }
     return;
   }
   double best, second;
@@ -515,6 +580,7 @@ int split_cluster(const Config& c, Unit& u, int j) {
 }
 
 void split_unit(const Config& c, Unit& u) {
+  if (c.update_mode != 0) return;     // nothing is ever flagged (and a local clustering has left its margin)
   u.mg.split = kInf;
   // delayed splits: flagged clusters that the last retrieval brought in
   const int M = (int)u.clusters.size();
@@ -547,14 +613,14 @@ struct oracle_config {
   int32_t n_units, group_size, head_dim, n_clusters_init, max_clusters, max_tokens, kmeans_iters, buffer_max,
       group_reduce;
   float var_alpha, size_factor, softmax_scale;
-  int32_t dtype, search_copy, score_round, update_mode;
+  int32_t dtype, search_copy, score_round, update_mode, local_window, local_clusters;
 };
 
 void* oracle_create(const oracle_config* c) {
   Oracle* o = new Oracle();
   o->cfg = Config{c->n_units, c->group_size, c->head_dim, c->n_clusters_init, c->max_clusters, c->max_tokens,
                   c->kmeans_iters, c->buffer_max, c->group_reduce, c->var_alpha, c->size_factor, c->softmax_scale,
-                  c->dtype, c->search_copy, c->score_round, c->update_mode};
+                  c->dtype, c->search_copy, c->score_round, c->update_mode, c->local_window, c->local_clusters};
   o->units.resize(c->n_units);
   return o;
 }
@@ -634,6 +700,7 @@ int oracle_import_unit(void* h, int u, int N, const float* K, const float* V, in
   std::copy(old.ties, old.ties + 5, nu.ties);
   nu.last_assign = old.last_assign;
   nu.error = old.error;
+  nu.local_count = old.local_count;
   o->units[u] = std::move(nu);
   return 0;
 }

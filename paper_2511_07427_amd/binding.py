@@ -19,7 +19,7 @@ TORCH_DTYPES = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat
 ERR_TOKENS, ERR_CLUSTERS, ERR_SPLIT_SIZE, ERR_SELECT, ERR_INIT, ERR_IMPORT, ERR_PLACE = 1, 2, 4, 8, 16, 32, 64
 OK, EINVAL, ECAPACITY, ESTATE, EHIP, ENOMEM = range(6)
 SEARCH_STORAGE, SEARCH_MEAN = 0, 1
-UPDATE_ADAPTIVE, UPDATE_STATIC, UPDATE_TOKENS = 0, 1, 2
+UPDATE_ADAPTIVE, UPDATE_STATIC, UPDATE_TOKENS, UPDATE_LOCAL = 0, 1, 2, 3
 LAUNCH_SEPARATE, LAUNCH_SPLIT_KERNEL = 1 << 16, 1 << 17
 
 
@@ -33,7 +33,7 @@ class _Cfg(C.Structure):
                                           "max_clusters", "max_tokens", "kmeans_iters", "buffer_max",
                                           "group_reduce")] + \
                [(k, C.c_float) for k in ("var_alpha", "size_factor", "softmax_scale")] + \
-               [(k, C.c_int32) for k in ("search_copy", "score_round", "update_mode", "launch")]
+               [(k, C.c_int32) for k in ("search_copy", "score_round", "update_mode", "launch", "local_window", "local_clusters")]
 
 
 _STATE_FIELDS = ("n_clusters", "n_tokens", "error", "tau", "centroids", "size", "buffered", "flag", "m2", "offsets",
@@ -67,6 +67,8 @@ class Config:
     score_round: int = 0
     update_mode: int = UPDATE_ADAPTIVE
     launch: int = 0
+    local_window: int = 0
+    local_clusters: int = 0
 
 
 _lib = None
@@ -112,7 +114,8 @@ def _check(rc, what):
 def _cfg(cfg: Config) -> _Cfg:
     return _Cfg(cfg.n_units, cfg.group_size, cfg.head_dim, DTYPES[cfg.dtype], cfg.n_clusters_init, cfg.max_clusters,
                 cfg.max_tokens, cfg.kmeans_iters, cfg.buffer_max, cfg.group_reduce, cfg.var_alpha, cfg.size_factor,
-                cfg.softmax_scale, cfg.search_copy, cfg.score_round, cfg.update_mode, cfg.launch)
+                cfg.softmax_scale, cfg.search_copy, cfg.score_round, cfg.update_mode, cfg.launch, cfg.local_window,
+                cfg.local_clusters)
 
 
 def dynakv_workspace_bytes(cfg: Config) -> int:

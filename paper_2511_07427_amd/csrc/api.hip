@@ -15,6 +15,7 @@ struct dynakv_index {
   void* workspace;
   size_t bytes;
   bool built;
+  int local_count;   // local update: appends enqueued since the last local clustering
   // optional timing of the gather + attention kernel
   bool profiling;
   std::vector<hipEvent_t> ev;   // start/stop pairs
@@ -35,7 +36,13 @@ bool config_ok(const dynakv_config_t* c) {
   if (c->softmax_scale < 0.f) return false;
   if (c->search_copy != DYNAKV_SEARCH_STORAGE && c->search_copy != DYNAKV_SEARCH_MEAN) return false;
   if (c->score_round != 0 && c->score_round != 1) return false;
-  if (c->update_mode < DYNAKV_UPDATE_ADAPTIVE || c->update_mode > DYNAKV_UPDATE_TOKENS) return false;
+  if (c->update_mode < DYNAKV_UPDATE_ADAPTIVE || c->update_mode > DYNAKV_UPDATE_LOCAL) return false;
+  if (c->update_mode == DYNAKV_UPDATE_LOCAL) {
+    if (c->local_window < 2 || c->local_window > kLocalWindowMax) return false;
+    if (c->local_clusters < 1 || c->local_clusters > kLocalClustersMax || c->local_clusters > c->local_window) return false;
+  } else if (c->local_window != 0 || c->local_clusters != 0) {
+    return false;
+  }
   if (c->launch & ~(0xFFFF | DYNAKV_LAUNCH_SEPARATE | DYNAKV_LAUNCH_SPLIT_KERNEL)) return false;
   const int s = c->launch & 255, nw = (c->launch >> 8) & 255;
   if (s > kMaxKvSplits || (nw != 0 && nw != 4 && nw != 8 && nw != 16)) return false;
@@ -64,7 +71,7 @@ void plan_attention(const dynakv_config_t& c, int* S, int* NW) {
   // where the single-kernel retrieval can run (see retrieve_is_fused) it beats split-KV at every unit count:
   // measured 16.5k against 15.5k steps/s with 8 units, 15.1k against 13.1k with 24 (configuration 2's shape)
   if (c.dtype != DYNAKV_F32 && c.search_copy == DYNAKV_SEARCH_STORAGE && c.max_clusters <= kFusedClusters && c.group_size <= 8 &&
-      c.update_mode != DYNAKV_UPDATE_TOKENS)
+      c.update_mode != DYNAKV_UPDATE_TOKENS && c.update_mode != DYNAKV_UPDATE_LOCAL)
     s = 1;
   int nw = pow2_floor(4096 / (c.n_units * s) > 0 ? 4096 / (c.n_units * s) : 1);
   if (c.launch & 255) s = c.launch & 255;
@@ -95,7 +102,8 @@ size_t carve(const dynakv_config_t& c, char* base, View* out) {
   v.search_mean = c.dtype == DYNAKV_F32 || c.search_copy == DYNAKV_SEARCH_MEAN;
   v.score_round = c.score_round;
   v.static_update = c.update_mode == DYNAKV_UPDATE_STATIC;
-  v.token_level = c.update_mode == DYNAKV_UPDATE_TOKENS;
+  v.token_level = c.update_mode == DYNAKV_UPDATE_TOKENS || c.update_mode == DYNAKV_UPDATE_LOCAL;
+  v.local_W = c.local_window; v.local_k = c.local_clusters;
   v.var_alpha = c.var_alpha; v.size_factor = c.size_factor;
   v.scale_d = c.softmax_scale > 0.f ? (double)c.softmax_scale : 1.0 / std::sqrt((double)c.head_dim);
   v.scale_f = (float)v.scale_d;
@@ -112,7 +120,7 @@ size_t carve(const dynakv_config_t& c, char* base, View* out) {
   v.ticket = (int*)take(U * 4); v.bump = (int*)take(U * 4); v.free_top = (int*)take(U * 4);
   v.NB = (v.Mcap + 255) / 256;
   v.near_d = (double*)take(U * v.NB * 8); v.near_j = (int*)take(U * v.NB * 4);
-  v.zdist = (float*)take(v.search_mean ? 0 : UM * 4); v.rmax2 = (int*)take(U * 4);
+  v.zdist = (float*)take(v.search_mean ? 0 : UM * 4); v.rmax2 = (int*)take(U * 4); v.lcount = (int*)take(U * 4);
   const size_t nw = v.search_mean ? 0 : U * v.NB * 4;
   v.near_zb = (float*)take(nw * 4); v.near_z2 = (float*)take(nw * 4); v.near_zj = (int*)take(nw * 4);
   v.last_assign = (int*)take(U * 4); v.counters = (long long*)take(U * kCounters * 8);
@@ -140,6 +148,17 @@ size_t carve(const dynakv_config_t& c, char* base, View* out) {
 
 }  // namespace
 
+// An append where every entry becomes a cluster of its own; in local-update mode the window's clustering follows
+// the append that fills it (the device keeps its own count and skips the clustering if an append was refused).
+static dynakv_status_t append_own_cluster(dynakv_index* ix, const void* k, const void* val, hipStream_t st) {
+  if (launch_append(ix->view, k, val, false, false, st) != hipSuccess) return DYNAKV_EHIP;
+  if (ix->view.local_W > 0 && ++ix->local_count >= ix->view.local_W) {
+    ix->local_count = 0;
+    if (launch_local_recluster(ix->view, ix->cfg.kmeans_iters, st) != hipSuccess) return DYNAKV_EHIP;
+  }
+  return DYNAKV_OK;
+}
+
 extern "C" {
 
 size_t dynakv_workspace_bytes(const dynakv_config_t* cfg) {
@@ -158,6 +177,7 @@ dynakv_status_t dynakv_create(const dynakv_config_t* cfg, void* workspace, size_
   ix->workspace = workspace;
   ix->bytes = carve(*cfg, (char*)workspace, &ix->view);
   ix->built = false;
+  ix->local_count = 0;
   ix->profiling = false;
   ix->n_prof = 0;
   *out = ix;
@@ -179,6 +199,7 @@ dynakv_status_t dynakv_build_index(dynakv_index_t* ix, const void* K, const void
                                           ix->bytes, (hipStream_t)stream);
   if (e != hipSuccess) return DYNAKV_EHIP;
   ix->built = true;
+  ix->local_count = 0;
   return DYNAKV_OK;
 }
 
@@ -266,7 +287,7 @@ dynakv_status_t dynakv_decode_step(dynakv_index_t* ix, const void* Q, int32_t to
   if (ix->view.token_level) {                        // no nearest-cluster search, no splits
     const dynakv_status_t rc = retrieve_impl(ix, ix->view, Q, token_budget, out, lse, nullptr, nullptr, false, st, &appended);
     if (rc != DYNAKV_OK) return rc;
-    return launch_append(ix->view, k_new, v_new, false, false, st) == hipSuccess ? DYNAKV_OK : DYNAKV_EHIP;
+    return append_own_cluster(ix, k_new, v_new, st);
   }
   const bool one_kernel = ix->view.fuse == 2;        // the splits too, where the retrieval kernel takes the append
   const dynakv_status_t rc = retrieve_impl(ix, ix->view, Q, token_budget, out, lse, k_new, v_new, one_kernel, st, &appended);
@@ -281,6 +302,7 @@ dynakv_status_t dynakv_decode_step(dynakv_index_t* ix, const void* Q, int32_t to
 dynakv_status_t dynakv_append(dynakv_index_t* ix, const void* k_new, const void* v_new, void* stream) {
   if (!ix || !k_new || !v_new) return DYNAKV_EINVAL;
   if (!ix->built) return DYNAKV_ESTATE;
+  if (ix->view.token_level) return append_own_cluster(ix, k_new, v_new, (hipStream_t)stream);
   return launch_append(ix->view, k_new, v_new, false, false, (hipStream_t)stream) == hipSuccess ? DYNAKV_OK : DYNAKV_EHIP;
 }
 
@@ -332,6 +354,7 @@ dynakv_status_t dynakv_import_state(dynakv_index_t* ix, const dynakv_state_t* sr
   if ((src->n_selected == nullptr) != (src->selected == nullptr)) return DYNAKV_EINVAL;
   if (launch_import(ix->view, *src, (hipStream_t)stream) != hipSuccess) return DYNAKV_EHIP;
   ix->built = true;
+  ix->local_count = 0;
   return DYNAKV_OK;
 }
 

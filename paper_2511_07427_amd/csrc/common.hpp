@@ -21,6 +21,7 @@ constexpr int kFusedClusters = 4096;            // clusters per unit the single-
 constexpr int kMaxSplitMembers = 4096;          // largest cluster the split kernel handles
 constexpr int kMaxKvSplits = 64;
 constexpr int kCounters = 8;
+constexpr int kLocalWindowMax = 128, kLocalClustersMax = 32;   // local update: largest window and cluster count
 constexpr int kInlinePages = 8;                 // pages of a cluster found without walking its chain                // workgroups that share one unit's gathered pages
 
 typedef float f4 __attribute__((ext_vector_type(4)));
@@ -32,7 +33,8 @@ struct View {
   int search_mean;   // the searches read the float32 means (always for float32 storage), else the 16-bit search copy
   int score_round;   // float64 scores are rounded to float32 before they are compared
   int static_update; // static-update baseline: nothing is ever flagged
-  int token_level;   // baseline without clustering: every appended entry is a cluster of its own
+  int token_level;   // every appended entry becomes a cluster of its own (baseline without clustering; local update)
+  int local_W, local_k;  // local update: entries per local clustering and clusters it forms (0: not this mode)
   size_t Rstride;    // floats of centroid table per unit
   float var_alpha, size_factor, scale_f;
   double scale_d;
@@ -54,6 +56,7 @@ struct View {
   int* near_zj;
   float* zdist;      // [U][Mcap] 16-bit search copy only: z_j = <k_new, r~_j> - |r~_j|^2 / 2 of the step's new key as the
                      // matrix cores computed it (largest = nearest), for the append to pick from
+  int* lcount;       // [U] local update: entries appended since the last local clustering
   int* rmax2;        // [U] bits of the largest |r~_j|^2 seen by a score pass since the index was built (a float >= 0)
   int* bump;         // [U] pages handed out from the pool so far
   int* free_top;     // [U] entries on the free-page stack
@@ -406,6 +409,7 @@ hipError_t launch_gather_attend(const View& v, const void* Q, float* out, float*
 // split: the unit's due splits follow in the same launch.
 hipError_t launch_append(const View& v, const void* k, const void* val, bool prescanned, bool split, hipStream_t st);
 hipError_t launch_split(const View& v, hipStream_t st);
+hipError_t launch_local_recluster(const View& v, int iters, hipStream_t st);
 hipError_t launch_extend(const View& v, const void* K, const void* V, int n, hipStream_t st);
 hipError_t launch_export(const View& v, const dynakv_state_t& dst, hipStream_t st);
 hipError_t launch_import(const View& v, const dynakv_state_t& src, hipStream_t st);

@@ -630,7 +630,7 @@ __global__ __launch_bounds__(1024) void finalize_kernel(View v, int N0) {
     for (int w = 0; w < 16; ++w) J += jsum[w];
     v.tau[u] = (double)v.var_alpha * (J / (double)N0);
     v.M[u] = v.M0; v.N[u] = N0; v.nflag[u] = 0; v.n_sel[u] = 0; v.t_sel[u] = 0; v.n_list[u] = 0;
-    v.ticket[u] = 0; v.bump[u] = total; v.free_top[u] = 0; v.last_assign[u] = -1;
+    v.ticket[u] = 0; v.bump[u] = total; v.free_top[u] = 0; v.last_assign[u] = -1; v.lcount[u] = 0; v.rmax2[u] = 0;
     for (int k = 0; k < kCounters; ++k) v.counters[(size_t)u * kCounters + k] = 0;
   }
 }

@@ -219,6 +219,7 @@ __global__ __launch_bounds__(256) void append_token_kernel(View v, const void* k
       v.ppos[((size_t)u * v.Pcap + page) * kPageTokens] = N;
       v.last_assign[u] = M;
       v.M[u] = M + 1; v.N[u] = N + 1;
+      if (v.local_W > 0) v.lcount[u] += 1;
     }
     s_page = page;
   }
@@ -231,6 +232,126 @@ __global__ __launch_bounds__(256) void append_token_kernel(View v, const void* k
     copy_elem(pg, k_index(v.dtype, 0, tid), kin, (size_t)u * kHeadDim + tid, v.dtype);
   } else {
     copy_elem(pg, v_index(v.dtype, 0, tid - kHeadDim), vin, (size_t)u * kHeadDim + tid - kHeadDim, v.dtype);
+  }
+}
+
+// Local update (Section 2.3): the last W clusters of the unit, one entry each, are clustered among themselves by
+// Lloyd's k-means into k clusters that take their place.  One workgroup per unit; keys staged in LDS as float32
+// (exact for every storage type), float64 distances and sums, centres stored as float32.
+__global__ __launch_bounds__(256) void local_recluster_kernel(View v, int iters) {
+  __shared__ float x[kLocalWindowMax][kHeadDim + 1];
+  __shared__ float r[kLocalClustersMax][kHeadDim];
+  __shared__ double dist[kLocalWindowMax], m2[kLocalClustersMax];
+  __shared__ int label[kLocalWindowMax], pos[kLocalWindowMax], opage[kLocalWindowMax], rank[kLocalWindowMax];
+  __shared__ int cnt[kLocalClustersMax], pgbase[kLocalClustersMax + 1], npage[kLocalClustersMax + kLocalWindowMax / kPageTokens + 1];
+  __shared__ int s_ok;
+  const int u = blockIdx.x, tid = threadIdx.x, W = v.local_W, k = v.local_k;
+  if (v.lcount[u] != W) return;                         // workgroup-uniform: an append of this window was refused
+  const int M = v.M[u], base = M - W;
+  const size_t cb = (size_t)u * v.Mcap;
+  const int es = elem_size(v.dtype);
+  if (tid < W) {
+    const int pg = v.cpg[(cb + base + tid) * kInlinePages];
+    opage[tid] = pg;
+    pos[tid] = v.ppos[((size_t)u * v.Pcap + pg) * kPageTokens];
+  }
+  __syncthreads();
+  for (int t = tid; t < W * kHeadDim; t += 256) x[t >> 7][t & 127] = page_key(v, u, opage[t >> 7], 0, t & 127);
+  __syncthreads();
+  for (int t = tid; t < k * kHeadDim; t += 256) r[t >> 7][t & 127] = x[(t >> 7) * W / k][t & 127];
+  __syncthreads();
+  for (int it = 0; it < iters; ++it) {
+    if (tid < W) {                                      // nearest centre, ties to the lowest
+      double best = __builtin_inf();
+      int arg = 0;
+      for (int j = 0; j < k; ++j) {
+        double acc = 0.0;
+#pragma unroll 8
+        for (int d = 0; d < kHeadDim; ++d) {
+          const double t = (double)x[tid][d] - (double)r[j][d];
+          acc = fma(t, t, acc);
+        }
+        if (acc < best) { best = acc; arg = j; }
+      }
+      label[tid] = arg;
+    }
+    __syncthreads();
+    for (int t = tid; t < k * kHeadDim; t += 256) {     // mean of the members; a centre without members stays
+      const int j = t >> 7, d = t & 127;
+      double sum = 0.0;
+      int n = 0;
+      for (int i = 0; i < W; ++i)
+        if (label[i] == j) { sum += (double)x[i][d]; ++n; }
+      if (n > 0) r[j][d] = (float)(sum / (double)n);
+    }
+    __syncthreads();
+  }
+  if (tid < W) {                                        // distance to the stored centre, place inside the cluster
+    const int j = label[tid];
+    double acc = 0.0;
+    for (int d = 0; d < kHeadDim; ++d) {
+      const double t = (double)x[tid][d] - (double)r[j][d];
+      acc = fma(t, t, acc);
+    }
+    dist[tid] = acc;
+    int rk = 0;
+    for (int i = 0; i < tid; ++i) rk += label[i] == j;
+    rank[tid] = rk;
+  }
+  __syncthreads();
+  if (tid < k) {
+    int n = 0;
+    double s = 0.0;
+    for (int i = 0; i < W; ++i)
+      if (label[i] == tid) { ++n; s += dist[i]; }
+    cnt[tid] = n; m2[tid] = s;
+  }
+  __syncthreads();
+  if (tid == 0) {                                       // fresh pages for the k clusters; the W old pages are freed below
+    int need = 0;
+    for (int j = 0; j < k; ++j) { pgbase[j] = need; need += (cnt[j] + kPageTokens - 1) / kPageTokens; }
+    pgbase[k] = need;
+    int top = v.free_top[u], bump = v.bump[u];
+    s_ok = top + (v.Pcap - bump) >= need;
+    if (s_ok) {
+      for (int p = 0; p < need; ++p) npage[p] = top > 0 ? v.freelist[(size_t)u * v.Pcap + --top] : bump++;
+      v.free_top[u] = top; v.bump[u] = bump;
+    } else {
+      v.err[u] |= DYNAKV_ERR_TOKENS;
+      v.lcount[u] = 0;
+    }
+  }
+  __syncthreads();
+  if (!s_ok) return;
+  char* pool = v.pages + (size_t)u * v.Pcap * ((size_t)kPageElems * es);
+  const int chunks = kHeadDim * es / 16;                // 16-byte chunks per row
+  for (int t = tid; t < W * 2 * chunks; t += 256) {     // keys and values, row by row, old page -> new page
+    const int i = t / (2 * chunks), c = t % (2 * chunks), kv = c / chunks, ch = c % chunks;
+    const int j = label[i], dpage = npage[pgbase[j] + rank[i] / kPageTokens], slot = rank[i] % kPageTokens;
+    const size_t so = (size_t)(kv ? v_index(v.dtype, 0, 0) : k_index(v.dtype, 0, 0)) * es + (size_t)ch * 16;
+    const size_t dof = (size_t)(kv ? v_index(v.dtype, slot, 0) : k_index(v.dtype, slot, 0)) * es + (size_t)ch * 16;
+    *(uint4*)(pool + (size_t)dpage * kPageElems * es + dof) = *(const uint4*)(pool + (size_t)opage[i] * kPageElems * es + so);
+  }
+  if (tid < W) {
+    const int j = label[tid];
+    v.ppos[((size_t)u * v.Pcap + npage[pgbase[j] + rank[tid] / kPageTokens]) * kPageTokens + rank[tid] % kPageTokens] = pos[tid];
+  }
+  for (int t = tid; t < k * kHeadDim; t += 256) store_centroid(v, u, base + (t >> 7), t & 127, r[t >> 7][t & 127]);
+  if (tid < k) {
+    const size_t cj = cb + base + tid;
+    const int np = pgbase[tid + 1] - pgbase[tid];
+    v.cn[cj] = cnt[tid]; v.cb[cj] = 0; v.csz[cj] = cnt[tid]; v.cflag[cj] = 0; v.cM2[cj] = m2[tid];
+    for (int p = 0; p < kInlinePages; ++p) v.cpg[cj * kInlinePages + p] = p < np ? npage[pgbase[tid] + p] : -1;
+    v.ctail[cj] = np ? npage[pgbase[tid] + np - 1] : -1;
+    for (int p = 0; p < np; ++p) v.pnext[(size_t)u * v.Pcap + npage[pgbase[tid] + p]] = p + 1 < np ? npage[pgbase[tid] + p + 1] : -1;
+  }
+  for (int j = base + tid; j < M; j += 256) v.in_req[cb + j] = 0;
+  __syncthreads();                                      // every copy has read its old page
+  if (tid == 0) {
+    int top = v.free_top[u];
+    for (int i = 0; i < W; ++i) v.freelist[(size_t)u * v.Pcap + top++] = opage[i];
+    v.free_top[u] = top;
+    v.M[u] = base + k; v.lcount[u] = 0;
   }
 }
 
@@ -412,7 +533,7 @@ __global__ __launch_bounds__(1024) void import_meta_kernel(View v, dynakv_state_
   if (tid == 0) {
     koff[M] = N;
     v.M[u] = M; v.N[u] = N; v.tau[u] = s.tau[u]; v.err[u] = 0; v.nflag[u] = s_nflag; v.n_sel[u] = nsel; v.t_sel[u] = 0;
-    v.n_list[u] = 0; v.ticket[u] = 0; v.bump[u] = total; v.free_top[u] = 0; v.last_assign[u] = -1;
+    v.n_list[u] = 0; v.ticket[u] = 0; v.bump[u] = total; v.free_top[u] = 0; v.last_assign[u] = -1; v.lcount[u] = 0; v.rmax2[u] = 0;
     for (int k = 0; k < kCounters; ++k) v.counters[(size_t)u * kCounters + k] = 0;
     v.nflagged[u] = 1;
   }
@@ -582,6 +703,10 @@ hipError_t launch_append(const View& v, const void* k, const void* val, bool pre
   else DYNAKV_APPEND(DYNAKV_BF16);
 #undef DYNAKV_APPEND
 #undef DYNAKV_APPEND_M
+  return hipGetLastError();
+}
+hipError_t launch_local_recluster(const View& v, int iters, hipStream_t st) {
+  local_recluster_kernel<<<v.U, 256, 0, st>>>(v, iters);
   return hipGetLastError();
 }
 hipError_t launch_extend(const View& v, const void* K, const void* V, int n, hipStream_t st) {

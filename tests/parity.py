@@ -115,7 +115,7 @@ def compare_retrieval(ix: binding.Index, o: Oracle, tally: Tally, what="", gathe
     """Scores, selected set, order and gather indices of the last retrieval.  Returns the oracle units whose
     selection differs by a tie.  The gather indices can only be read back before the next split (which may
     recycle the pages the gather list points to): after a whole-step call pass gather=False."""
-    fields = ["n_selected", "selected", "n_gathered", "scores"] + (["gathered"] if gather else [])
+    fields = ["n_selected", "selected", "n_gathered", "scores", "n_clusters"] + (["gathered"] if gather else [])
     st = {k: v.numpy() for k, v in ix.dynakv_export_state(fields).items()}
     dirty = set()
     for ou, u in _pairs(ix, units):
@@ -123,7 +123,8 @@ def compare_retrieval(ix: binding.Index, o: Oracle, tally: Tally, what="", gathe
             continue
         w = "%s unit %d" % (what, u)
         sel, gat, sc = o.selected(ou), o.gather(ou), o.scores(ou)
-        M = len(sc)
+        M = min(len(sc), int(st["n_clusters"][u]))      # (a local clustering after the retrieval leaves fewer clusters)
+        sc_all, sc = sc, sc[:M]
         if Q is not None:
             tol = score_bound(ix, Q[ou], o.search_copy(ou))
             err = np.abs(st["scores"][u, :M].astype(np.float64) - sc).max()
@@ -139,7 +140,7 @@ def compare_retrieval(ix: binding.Index, o: Oracle, tally: Tally, what="", gathe
             continue
         # same set: the library's order must follow the oracle's scores up to the bound on its own scores
         if len(gsel) > 1:
-            s_in_order = sc[gsel]
+            s_in_order = sc_all[gsel]
             slack = (score_bound(ix, Q[ou], o.search_copy(ou)) if Q is not None else 0.0) * 2 + 1.2e-7 * np.abs(s_in_order).max()
             worst = (s_in_order[1:] - s_in_order[:-1]).max()
             assert worst <= slack, "%s selected clusters out of score order by %.3g" % (w, worst)

@@ -29,7 +29,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 
 def test_struct_sizes_match_the_header():
-    assert C.sizeof(binding._Cfg) == 17 * 4
+    assert C.sizeof(binding._Cfg) == 19 * 4
     assert C.sizeof(binding._State) == 21 * 8
 
 
@@ -45,7 +45,7 @@ def test_workspace_bytes_and_invalid_configs(lib):
     c = binding.dynakv_workspace_bytes(_cfg(dtype="f32"))
     assert 0 < a < b and a < c and a % 256 == 0
     for bad in (dict(n_units=0), dict(group_size=17), dict(head_dim=64), dict(max_clusters=4), dict(max_clusters=131073), dict(n_clusters_init=8193, max_clusters=9000, max_tokens=9000), dict(search_copy=2),
-                dict(score_round=2), dict(update_mode=9), dict(launch=1 << 20), dict(launch=3 << 8),
+                dict(score_round=2), dict(update_mode=9), dict(update_mode=3), dict(update_mode=3, local_window=200, local_clusters=4), dict(local_window=8), dict(launch=1 << 20), dict(launch=3 << 8),
                 dict(kmeans_iters=0), dict(buffer_max=-1), dict(group_reduce=2), dict(max_tokens=4),
                 dict(softmax_scale=-1.0)):
         assert binding.dynakv_workspace_bytes(_cfg(**bad)) == 0, bad

@@ -422,6 +422,18 @@ def test_coretrieval_placement(dtype, launch):
     assert st["error"].tolist() == [binding.ERR_PLACE] * U
 
 
+@pytest.mark.parametrize("dtype,W,k", [("f16", 32, 4), ("bf16", 128, 32), ("f32", 20, 3)])
+def test_local_update_mode(dtype, W, k):
+    """The local-update baseline: new entries are clusters of their own until a window is full, its own k-means then
+    replaces them; several windows, mixed call styles, the prefill's clusters untouched."""
+    s = CONFIGS["llama3_8b"].scaled(dtype=dtype, prefill=1024, n_clusters_init=40, budget=300, max_cluster_factor=8, drift_std=0.08)
+    steps = 2 * W + 9
+    r = run_trajectory(s, [0, 1], steps, check_every=1, full_every=7, step_call="mixed", update_mode=3, local_window=W,
+                       local_clusters=k, kmeans_iters=3)
+    say("local update", dtype, W, k, {x: r[x] for x in ("worst_rel", "ties", "splits", "clusters")})
+    assert r["clusters"] == [40 + 2 * k + 9] * 2 and r["splits"] == 0
+
+
 def test_capacity_limits_set_the_error_word_and_keep_state():
     s = WorkloadSpec("cap", "f16", 1, 2, 64, 8, 4, 32, 4, 0.5, var_alpha=0.5, size_factor=0.0, buffer_max=0,
                      max_cluster_factor=1, seed=5)

@@ -497,6 +497,46 @@ def test_coretrieval_probabilities_and_placement_chain_on_a_hand_example():
     assert P.sum() == 0 and order[0].tolist() == [0, 1, 2]
 
 
+def test_local_update_clusters_each_window_of_new_entries_on_its_own():
+    """update_mode = 3 (Section 2.3, local update): new entries stay clusters of their own until a window is full; its
+    k-means (initial centres = every (W/k)-th entry) then replaces them by k clusters; the prefill's clusters never
+    change.  The window's k-means against scikit-learn from the same centres."""
+    from sklearn.cluster import KMeans
+    s = CONFIGS["tiny"].scaled(prefill=400, n_clusters_init=10, drift_std=0.1)
+    W, k, T = 48, 6, 4
+    w = generate(s, steps=2 * W + 5)
+    o = Oracle(OracleConfig(1, 4, 128, 10, 400, 400 + 2 * W + 5, T, 16, 0, 1.5, 2.0, 0.0, search_copy=1, update_mode=3,
+                            local_window=W, local_clusters=k))
+    o.build_index(w["K0"], w["V0"], w["init_idx"])
+    c0 = o.clusters(0)
+    for t in range(2 * W + 5):
+        o.retrieve_attend(w["Q"][t], 64)
+        o.append(w["Knew"][t], w["Vnew"][t])
+        o.split()
+        done = (t + 1) // W
+        assert o.num_clusters(0) == 10 + done * k + (t + 1) % W
+    c, (off, mem) = o.clusters(0), o.members(0)
+    for key in ("centroids", "n", "M2"):
+        np.testing.assert_array_equal(c[key][:10], c0[key])                      # existing clusters are left alone
+    assert c["flag"].sum() == 0 and sorted(mem.tolist()) == list(range(400 + 2 * W + 5))
+    for win in range(2):
+        X = w["Knew"][win * W:(win + 1) * W, 0].astype(np.float64)
+        init = X[[j * W // k for j in range(k)]]
+        full = KMeans(k, init=init, n_init=1, algorithm="lloyd", max_iter=T, tol=0).fit(X)
+        prev = KMeans(k, init=init, n_init=1, algorithm="lloyd", max_iter=T - 1, tol=0).fit(X)
+        ids = range(10 + win * k, 10 + (win + 1) * k)
+        lab = np.full(W, -1)
+        for j in ids:
+            lab[mem[off[j]:off[j + 1]] - (400 + win * W)] = j - ids[0]
+        np.testing.assert_array_equal(lab, prev.labels_)
+        assert c["n"][list(ids)].min() > 0
+        np.testing.assert_allclose(c["centroids"][list(ids)], full.cluster_centers_, rtol=1e-6, atol=1e-6)
+        for j in ids:
+            m = mem[off[j]:off[j + 1]] - (400 + win * W)
+            assert c["M2"][j] == pytest.approx(((X[m] - c["centroids"][j].astype(np.float64)) ** 2).sum(), rel=1e-12)
+    assert (c["n"][10 + 2 * k:] == 1).all()                                      # the open window: clusters of one
+
+
 def test_imported_state_continues_like_the_original():
     s = CONFIGS["tiny"].scaled(var_alpha=1.2, buffer_max=4)
     w = generate(s, steps=96)
