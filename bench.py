@@ -98,7 +98,7 @@ def variants_report(a):
     scale = 1.0 / np.sqrt(d)
     out, lse = torch.empty(U, G, d, device=dev), torch.empty(U, G, device=dev)
     res = {}
-    LW, LK = 128, 16                      # local update: windows of 128 entries into 16 clusters (8 entries each)
+    LW, LK = 64, 32                       # local update: windows of 64 entries into 32 clusters (many small clusters)
     for name, mode in (("adaptive", binding.UPDATE_ADAPTIVE), ("static", binding.UPDATE_STATIC), ("local", binding.UPDATE_LOCAL),
                        ("tokens", binding.UPDATE_TOKENS)):
         tok, loc = mode == binding.UPDATE_TOKENS, mode == binding.UPDATE_LOCAL
