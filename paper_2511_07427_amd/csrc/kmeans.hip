@@ -1,5 +1,5 @@
 // Prefill: Lloyd's k-means per unit (Section 4.1, Eq. 3-4; Algorithm 1, prefill block; the
-// "robust to empty clusters" remark of Section 7), cluster statistics, the head-specific
+// remark of Section 7 that it must cope with empty clusters), cluster statistics, the head-specific
 // threshold, and the cluster-contiguous page layout (Section 5.1, intra-cluster placement,
 // kept here as the HBM layout).
 //
@@ -306,7 +306,11 @@ __global__ __launch_bounds__(256) void kmeans_reseed_kernel(View v, const void* 
 typedef _Float16 h8v __attribute__((ext_vector_type(8)));
 typedef __bf16 b8v __attribute__((ext_vector_type(8)));
 typedef float f16v __attribute__((ext_vector_type(16)));
-constexpr float kFilterGamma = 1.0f / 8192.0f;   // >> 2^-22 operand error + float32 accumulation over 384 products
+// Bound on the relative error of a filtered inner product, |error| <= gamma |x| |r|: the products of two 16-bit
+// values are exact in float32; their accumulation (128 per term: 256 for f16's two terms, 384 for bf16's three)
+// errs by at most n * 2^-24 of the sum of their magnitudes (2^-16 and 2^-15.4); what the terms leave of r is below
+// 2^-22 |r|.  The constants below are twice the sum of those.
+constexpr float kFilterGammaF16 = 1.0f / 32768.0f, kFilterGammaBF16 = 1.0f / 16384.0f;
 
 // A-operand order of one 32-cluster tile: [term][k-step of 16][lane][8], lane = (k%16)/8*32 + row.
 __device__ inline size_t kmA_index(int nterms, int j, int term, int d) {
@@ -469,7 +473,7 @@ __global__ __launch_bounds__(256, 3) void kmeans_assign_mfma_kernel(View v, cons
     const int pt = pbase + t * 32 + p;
     if (h == 0 && pt < N0) {
       v.labels[(size_t)u * v.Ncap + pt] = idx;
-      const float eps = kFilterGamma * xnorm[t] * rmax + 2.4e-7f * rmax * rmax;
+      const float eps = (BF ? kFilterGammaBF16 : kFilterGammaF16) * xnorm[t] * rmax + 2.4e-7f * rmax * rmax;
       if (!(nb - ns > 2.f * eps)) v.order[(size_t)u * v.Ncap + atomicAdd(&v.nflagged[u], 1)] = pt;
     }
   }

@@ -1,6 +1,7 @@
-// Decode, first half of a step (Algorithm 1 "load top-k clusters by query-centroid similarity";
-// Section 4.1; attention over the reordered entries, Section 7):
-//   score_kernel   - float64 inner products <q_g, r_j>, reduced over the query group, rounded to float32
+// Decode, first half of a step (Algorithm 1, decode block: the top clusters by query-centroid similarity are
+// loaded; Section 4.1; attention over the reordered entries, Section 7):
+//   score kernels  - inner products <q_g, r_j> reduced over the query group: on the matrix cores over the 16-bit
+//                    search copy (score.hpp), or in float64 over the float32 means
 //   select_kernel  - order by (score desc, id asc), longest prefix under the token budget, gather list
 //   gather_attend  - streams the selected clusters' pages once; QK^T and PV on matrix cores with an
 //                    online (running-max) softmax, so any gather order is overflow-safe; split over

@@ -1,7 +1,7 @@
 """Shared driver of the GPU parity tests: runs the HIP library and the CPU oracle on the same seeded
 inputs, call by call, and compares them.
 
-Bars (the benchmark spec): cluster memberships, selected-cluster sets and gather indices bit-exact wherever
+Bars: cluster memberships, selected-cluster sets and gather indices bit-exact wherever
 the oracle's margin for the decision exceeds 1e-4; centroids and attention outputs within 2e-3 relative, M2 and
 tau within 2e-3 relative, log-sum-exp within 2e-3 absolute (plus 2^-17 of its magnitude, the float32 accumulation
 bound, which only matters for logits of the order of 10^4).  A disagreement on a decision whose margin is at
