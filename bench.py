@@ -25,7 +25,12 @@ MFMA_PEAK_TFLOPS = 2500.0      # dense fp16/bf16, published
 # torch's float32 -> float16 conversion of the 134 217 728-element prefill keys in the same run (512 MiB read,
 # 256 MiB written).  Keyed by (config, steps, warmup, units); "rev" is kernel_revision() of the sources the
 # counters were taken with: another revision of the kernels, or other arguments, report null.
-PMC_TRAFFIC = {}
+PMC_TRAFFIC = {
+    ("llama3_8b", 8192, 64, 0): {"rev": "09d9f8b136f0", "kernel": "retrieve_fused_kernel", "fetch_kib": 111229.3,
+                                 "fetch_scale": 524288.0 / 262169.0, "write_kib": 4658.5, "write_scale": 262144.0 / 262144.0},
+    ("llama3_8b", 20, 5, 0): {"rev": "09d9f8b136f0", "kernel": "retrieve_fused_kernel", "fetch_kib": 85329.3,
+                              "fetch_scale": 524288.0 / 262169.7, "write_kib": 2378.4, "write_scale": 262144.0 / 262144.0},
+}
 
 
 def kernel_revision() -> str:
@@ -307,7 +312,8 @@ def main():
         bytes_per_launch = kv_bytes + centroid_bytes
         achieved = bytes_per_launch / (ms / n * 1e-3) / 1e9
         pmc = PMC_TRAFFIC.get((a.config, a.steps, a.warmup, a.units))
-        if pmc and (pmc["rev"] != kernel_revision() or pmc["kernel"] != kernel or a.max_cluster_factor or a.full_horizon):
+        if pmc and (pmc["rev"] != kernel_revision() or pmc["kernel"] != kernel or a.max_cluster_factor or a.full_horizon or
+                    a.coretrieval_refs):
             pmc = None
         traffic = (pmc["fetch_kib"] * pmc["fetch_scale"] + pmc["write_kib"] * pmc["write_scale"]) * 1024.0 if pmc else None
         roof = dict(bound="hbm", kernel=kernel, achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s",
