@@ -293,6 +293,32 @@ __device__ inline float page_key(const View& v, int u, int page, int slot, int d
   return load_elem(page_ptr(v, u, page), k_index(v.dtype, slot, d), v.dtype);
 }
 
+// ---- wavefront scans and reductions on DPP ----------------------------------------------------------
+// Cross-lane moves inside a row of 16 lanes (row shifts, quad permutes, mirrors) and from one row to the next (row
+// broadcasts) are operand modifiers of ordinary vector instructions: a 64-lane scan or reduction built from them
+// costs a few dozen cycles, where the same built from lane permutes through LDS (what __shfl compiles to) costs a
+// dependent LDS round trip per step.  A lane whose source lies outside its row, or whose row is masked out, gets 0.
+template <int CTRL, int ROWS = 0xF>
+__device__ __forceinline__ int dpp_or_zero(int x) { return __builtin_amdgcn_update_dpp(0, x, CTRL, ROWS, 0xF, false); }
+// A lane whose row is masked out keeps `old`.
+template <int CTRL, int ROWS = 0xF>
+__device__ __forceinline__ int dpp_or(int old, int x) { return __builtin_amdgcn_update_dpp(old, x, CTRL, ROWS, 0xF, false); }
+constexpr int kDppXor1 = 0xB1, kDppXor2 = 0x4E;            // quad_perm [1,0,3,2], [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141, kDppMirror = 0x140;  // lane i <-> 7 - i inside 8 lanes, i <-> 15 - i inside a row
+constexpr int kDppBcast15 = 0x142, kDppBcast31 = 0x143;    // lane 15 of every row to the next row; lane 31 to rows 2 and 3
+// Inclusive prefix sum over the 64 lanes of a wavefront.
+__device__ __forceinline__ int wave_incl_scan(int x) {
+  x += dpp_or_zero<0x111>(x);            // row_shr:1, 2, 4, 8
+  x += dpp_or_zero<0x112>(x);
+  x += dpp_or_zero<0x114>(x);
+  x += dpp_or_zero<0x118>(x);
+  x += dpp_or_zero<kDppBcast15, 0xA>(x); // rows 1 and 3 add the total of the row before them
+  x += dpp_or_zero<kDppBcast31, 0xC>(x); // rows 2 and 3 add the total of rows 0 and 1
+  return x;
+}
+// Sum over the 64 lanes; every lane gets it.
+__device__ __forceinline__ int wave_sum(int x) { return __builtin_amdgcn_readlane(wave_incl_scan(x), 63); }
+
 // ---- block helpers ------------------------------------------------------------------------------
 // Workgroup barrier for data that travels through LDS only: it waits for this wavefront's LDS (and scalar)
 // operations, not for its outstanding global loads and stores as __syncthreads() does.  A stage that has issued
@@ -313,25 +339,17 @@ template <bool LDS_ONLY = false>
 __device__ inline int block_excl_scan(int val, int* sm, int& total, int nw = 0) {
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   if (nw == 0) nw = blockDim.x >> 6;
-  int x = val;
-  for (int o = 1; o < 64; o <<= 1) {
-    const int y = __shfl_up(x, o);
-    if (lane >= o) x += y;
-  }
+  const int x = wave_incl_scan(val);
   block_barrier<LDS_ONLY>();
   if (lane == 63) sm[w] = x;
   block_barrier<LDS_ONLY>();
-  if (w == 0) {
-    int t = lane < nw ? sm[lane] : 0;
-    for (int o = 1; o < 64; o <<= 1) {
-      const int y = __shfl_up(t, o);
-      if (lane >= o) t += y;
-    }
-    sm[lane] = t;
+  int base = 0, all = 0;
+  for (int k = 0; k < nw; ++k) {
+    const int t = sm[k];
+    if (k < w) base += t;
+    all += t;
   }
-  block_barrier<LDS_ONLY>();
-  const int base = w ? sm[w - 1] : 0;
-  total = sm[nw - 1];
+  total = all;
   return base + x - val;
 }
 
@@ -340,11 +358,9 @@ template <bool LDS_ONLY = false>
 __device__ inline unsigned long long block_excl_scan64(unsigned long long val, unsigned long long* sm,
                                                        unsigned long long& total) {
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = blockDim.x >> 6;
-  unsigned long long x = val;
-  for (int o = 1; o < 64; o <<= 1) {
-    const unsigned long long y = __shfl_up(x, o);
-    if (lane >= o) x += y;
-  }
+  // the two halves are sums of their own (neither overflows 32 bits): two 32-bit scans
+  const unsigned lo = (unsigned)wave_incl_scan((int)(unsigned)val), hi = (unsigned)wave_incl_scan((int)(unsigned)(val >> 32));
+  const unsigned long long x = (unsigned long long)lo | ((unsigned long long)hi << 32);
   block_barrier<LDS_ONLY>();
   if (lane == 63) sm[w] = x;
   block_barrier<LDS_ONLY>();

@@ -418,11 +418,7 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
     int hv[4], t = 0;
 #pragma unroll
     for (int k = 0; k < 4; ++k) { hv[k] = h[255 - (4 * lane + k)]; t += hv[k]; }
-    int inc = t;
-    for (int o = 1; o < 64; o <<= 1) {
-      const int y = __shfl_up(inc, o);
-      if (lane >= o) inc += y;
-    }
+    const int inc = wave_incl_scan(t);
     int run = above + inc - t, dstar = -1, ab = 0;
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
@@ -432,13 +428,13 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
     const unsigned long long bal = __ballot(dstar >= 0);
     if (bal == 0) {                      // everything fits (first pass only)
       cross = false;
-      total = __shfl(run, 63);
+      total = __builtin_amdgcn_readlane(run, 63);
       break;
     }
-    const int src = __ffsll((long long)bal) - 1;
-    kstar |= (uint32_t)__shfl(dstar, src) << shift;
+    const int src = __ffsll((long long)bal) - 1;       // wavefront-uniform
+    kstar |= (uint32_t)__builtin_amdgcn_readlane(dstar, src) << shift;
     mask |= 255u << shift;
-    above = __shfl(ab, src);
+    above = __builtin_amdgcn_readlane(ab, src);
   }
 
   // ---- the band around the cut, retaken in float64
@@ -640,8 +636,11 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
           for (int i = 0; i < 8; ++i) rank += (qb + i < q1 && o[i] > my) ? 1 : 0;
         }
       }
-      if (r == 0)
-        for (int o = 1; o < tpc; o <<= 1) rank += __shfl_xor(rank, o);
+      if (r == 0) {                                     // sum over the tpc (1, 2, 4 or 8) adjacent lanes of the cluster
+        if (tpc > 1) rank += dpp_or_zero<kDppXor1>(rank);
+        if (tpc > 2) rank += dpp_or_zero<kDppXor2>(rank);
+        if (tpc > 4) rank += dpp_or_zero<kDppHalfMirror>(rank);
+      }
       if (r != 0 || sub == 0) { rk[r] = rank; idw[r] = kIdMask - (int)(my & kIdMask); wt[r] = cw[p]; }
     }
   }

@@ -185,14 +185,26 @@ __device__ __forceinline__ void merge_best2(float& zb, int& jb, float& z2, float
   if (take) { zb = ob; jb = oj; }
   z2 = fmaxf(fmaxf(z2, o2), loser_ok ? loser : -__builtin_inff());
 }
-// The same over the 64 lanes of a wavefront; every lane gets the result.
+// The same over the 64 lanes of a wavefront; every lane gets the result.  Butterfly inside each row of 16 lanes
+// (the sets that meet are disjoint at every step), then row to row, then the last lane's triple for everybody.
+template <int CTRL, int ROWS>
+__device__ __forceinline__ void best2_step(float& zb, int& jb, float& z2) {
+  // a lane that gets nothing from this step (its row is masked out) merges the empty set: index -1, -inf
+  const float ob = __int_as_float(dpp_or<CTRL, ROWS>(0, __float_as_int(zb)));
+  const int oj = dpp_or<CTRL, ROWS>(-1, jb);
+  const float o2 = __int_as_float(dpp_or<CTRL, ROWS>(__float_as_int(-__builtin_inff()), __float_as_int(z2)));
+  merge_best2(zb, jb, z2, ob, oj, o2);
+}
 __device__ __forceinline__ void wave_best2(float& zb, int& jb, float& z2) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    const float ob = __shfl_xor(zb, o), o2 = __shfl_xor(z2, o);
-    const int oj = __shfl_xor(jb, o);
-    merge_best2(zb, jb, z2, ob, oj, o2);
-  }
+  best2_step<kDppXor1, 0xF>(zb, jb, z2);
+  best2_step<kDppXor2, 0xF>(zb, jb, z2);
+  best2_step<kDppHalfMirror, 0xF>(zb, jb, z2);
+  best2_step<kDppMirror, 0xF>(zb, jb, z2);
+  best2_step<kDppBcast15, 0xA>(zb, jb, z2);
+  best2_step<kDppBcast31, 0xC>(zb, jb, z2);
+  zb = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(zb), 63));
+  jb = __builtin_amdgcn_readlane(jb, 63);
+  z2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(z2), 63));
 }
 
 // Every thread brings the best and the second best z it has seen (z_j = <k, r~_j> - |r~_j|^2 / 2 as the matrix
