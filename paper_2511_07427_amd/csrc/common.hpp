@@ -318,6 +318,18 @@ __device__ __forceinline__ int wave_incl_scan(int x) {
 }
 // Sum over the 64 lanes; every lane gets it.
 __device__ __forceinline__ int wave_sum(int x) { return __builtin_amdgcn_readlane(wave_incl_scan(x), 63); }
+// Largest value over the 64 lanes; every lane gets it.  (Butterfly inside each row, then row to row; a lane that a
+// step does not reach keeps its own value, which leaves a maximum unchanged.)
+__device__ __forceinline__ int wave_max(int x) {
+  x = max(x, dpp_or<kDppXor1>(x, x));
+  x = max(x, dpp_or<kDppXor2>(x, x));
+  x = max(x, dpp_or<kDppHalfMirror>(x, x));
+  x = max(x, dpp_or<kDppMirror>(x, x));
+  x = max(x, dpp_or<kDppBcast15, 0xA>(x, x));
+  x = max(x, dpp_or<kDppBcast31, 0xC>(x, x));
+  return __builtin_amdgcn_readlane(x, 63);
+}
+__device__ __forceinline__ int wave_min(int x) { return -wave_max(-x); }
 
 // ---- block helpers ------------------------------------------------------------------------------
 // Workgroup barrier for data that travels through LDS only: it waits for this wavefront's LDS (and scalar)

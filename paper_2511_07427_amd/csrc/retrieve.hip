@@ -180,6 +180,8 @@ struct SelectLds {
   int* misc;               // [8]
   int* list;
   int list_cap;
+  unsigned* selbits;       // [ceil(M / 32)] zeroed by the caller, or null: bit j is set for every selected cluster j, so that
+                           // threads of the same workgroup can read the active set without a trip through memory
 };
 
 // List entries of one page holding nv tokens, from list position w and gather offset t0 on.
@@ -291,6 +293,7 @@ __device__ inline int select_sorted(const View& v, int u, int M, int budget, con
     const int id = sid[p];
     v.sel_ids[cb + p] = id;
     v.in_req[cb + id] = p < cut;
+    if (p < cut && s.selbits) atomicOr(&s.selbits[id >> 5], 1u << (id & 31));
     if (p < cut)
       emit_cluster(v, u, cb + id, truncated ? budget : v.cn[cb + id] + v.cb[cb + id], v.pg_off[cb + p],
                    v.tok_off[cb + p], plist, poff, s.list, s.list_cap);
@@ -507,6 +510,7 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
         if (band[i] == j) sel = (((unsigned)bmask[i >> 5]) >> (i & 31)) & 1u;
       v.in_req[cb + j] = sel;
       if (sel) {
+        if (s.selbits) atomicOr(&s.selbits[j >> 5], 1u << (j & 31));
         const int pos = atomicAdd(&s.misc[2], 1);
         if (pos < CMAX) { ck[pos] = ((unsigned long long)k << kIdBits) | (unsigned)(kIdMask - j); cw[pos] = DYNAKV_WEIGHT(j); }
       }
@@ -517,6 +521,7 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
       const bool sel = !cross || k > kstar;
       v.in_req[cb + j] = sel;
       if (sel) {
+        if (s.selbits) atomicOr(&s.selbits[j >> 5], 1u << (j & 31));
         const int pos = atomicAdd(&s.misc[2], 1);
         if (pos < CMAX) { ck[pos] = ((unsigned long long)k << kIdBits) | (unsigned)(kIdMask - j); cw[pos] = DYNAKV_WEIGHT(j); }
       }
@@ -554,6 +559,7 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
         const bool sel = j < xid;
         v.in_req[cb + j] = sel;
         if (sel) {
+          if (s.selbits) atomicOr(&s.selbits[j >> 5], 1u << (j & 31));
           const int pos = atomicAdd(&s.misc[2], 1);
           if (pos < CMAX) { ck[pos] = ((unsigned long long)kstar << kIdBits) | (unsigned)(kIdMask - j); cw[pos] = DYNAKV_WEIGHT(j); }
         }
@@ -578,6 +584,7 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
       ck[0] = ((unsigned long long)kstar << kIdBits) | (unsigned)(kIdMask - xid);
       cw[0] = budget;
       v.in_req[cb + xid] = 1;
+      if (s.selbits) atomicOr(&s.selbits[xid >> 5], 1u << (xid & 31));
     }
     lds_barrier();
     cut = 1; tsel = budget;
@@ -766,7 +773,7 @@ __global__ __launch_bounds__(1024) void select_kernel(View v, const void* Q, int
     for (int g = 0; g < v.G; ++g) qb = v.group_reduce == DYNAKV_GROUP_MAX ? fmaxf(qb, qn[g]) : qb + qn[g];
     ex.eps = score_eps(v, qb, __int_as_float(v.rmax2[u]));
   }
-  const SelectLds s{BIG ? nullptr : skey_, BIG ? nullptr : ssz_, region, hist, srt, sm, misc, nullptr, 0};
+  const SelectLds s{BIG ? nullptr : skey_, BIG ? nullptr : ssz_, region, hist, srt, sm, misc, nullptr, 0, nullptr};
   select_phase<1024, CMAX>(v, u, M, budget, s, ex);
 }
 
@@ -1152,7 +1159,8 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   __shared__ double am_v[16];
   __shared__ int am_i[16];
   __shared__ float am_2[16];
-  __shared__ int s_rmax2;
+  __shared__ int am_r[16];
+  __shared__ unsigned selbits[kFusedClusters / 32];    // the active set, for the plan of the splits
   __shared__ __align__(16) int sm[64];
   __shared__ int misc[8];
   uint32_t* skey = (uint32_t*)smem;
@@ -1209,7 +1217,7 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   for (int i = M + tid; i < Mpad; i += NT) skey[i] = 0u;
   for (int i = tid; i < 1024; i += NT) hist[i] = 0;
   if (tid < 8) misc[tid] = tid == 4 ? 0x7fffffff : 0;
-  if (tid == 0) s_rmax2 = 0;
+  if (SPLIT && tid < kFusedClusters / 32) selbits[tid] = 0u;
 #pragma unroll
   for (int k = 0; k < kFusedClusters / NT; ++k)
     if (tid + k * NT < M) ssz[tid + k * NT] = szr[k];
@@ -1256,27 +1264,34 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
         for (int s2 = 0; s2 < 4; ++s2) cur[b][s2] = nxt[b][s2];
     }
   }
+  // every wavefront leaves its largest |r|^2 and, for the append, its best / runner-up; one barrier, and every thread
+  // combines the NW entries
+  const int rm = wave_max(__float_as_int(rmax2));      // non-negative floats order like their bits
+  if constexpr (APPEND) wave_best2(zb, jb, z2);
+  if (lane == 0) {
+    am_r[wave] = rm;
+    if constexpr (APPEND) { am_v[wave] = (double)zb; am_i[wave] = jb; am_2[wave] = z2; }
+  }
+  lds_barrier();                                      // scores, first histogram and the wavefronts' results are in place
+  int rmu = am_r[0];
 #pragma unroll
-  for (int o = 8; o > 0; o >>= 1) rmax2 = fmaxf(rmax2, __shfl_xor(rmax2, o));
-  if (lane == 0) atomicMax(&s_rmax2, __float_as_int(rmax2));
-  lds_barrier();                                      // scores, first histogram and the largest norm are in place
-  const float unit_rmax2 = __int_as_float(s_rmax2);
+  for (int k = 1; k < NW; ++k) rmu = max(rmu, am_r[k]);
+  const float unit_rmax2 = __int_as_float(rmu);
   // the append's nearest cluster: its record is requested here and used after the selection
   int ja = -1;
   AppendFetch apf{0.0, 0, 0};
   if constexpr (APPEND) {
-    ja = nearest_resolve<NT>(v, u, M, zb, jb, z2, rn.kn, unit_rmax2, v.zdist + (size_t)u * v.Mcap, Rq, ap.kd, am_v, am_i, am_2);
+    ja = nearest_decide<NT>(v, u, M, rn.kn, unit_rmax2, v.zdist + (size_t)u * v.Mcap, Rq, ap.kd, am_v, am_i, am_2);
     if (room) apf = append_fetch(v, u, ja);
   }
-  lds_barrier();
 
   // ---- selection
-  const SelectLds sel{skey, ssz, smem + kKeys + kSizes, hist, ssz, sm, misc, list, kFusedList};
+  const SelectLds sel{skey, ssz, smem + kKeys + kSizes, hist, ssz, sm, misc, list, kFusedList, SPLIT ? selbits : nullptr};
   const SelectExact ex{score_eps(v, rn.qbound, unit_rmax2), Q};
   const int nlist = select_phase<NT>(v, u, M, budget, sel, ex, true);
-  // a full barrier where other threads read back what the selection wrote to memory: the active-set flags (plan of
-  // the splits) or a list too long for LDS (page loop)
-  if (SPLIT || nlist > kFusedList) __syncthreads();
+  // a full barrier only where other threads read back what the selection wrote to memory: a list too long for LDS
+  // (page loop); the plan of the splits takes the active set from the bitmap in LDS
+  if (nlist > kFusedList) __syncthreads();
   else lds_barrier();
 
   // ---- the append (scores and selection saw the index as it was before); with SPLIT the first wavefront
@@ -1285,7 +1300,7 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   if constexpr (SPLIT)
     if (wave == 0) {
       flagged0 = wk.flagged0[lane]; nflag0 = wk.nflag0; top0 = wk.top0;
-      pe = plan_fetch_early(v, u, flagged0, nflag0, top0, room ? ja : -1, lane);
+      pe = plan_fetch_early(v, u, flagged0, nflag0, top0, room ? ja : -1, lane, selbits);
     }
   if constexpr (APPEND) {
     if (room) append_commit<NT>(v, u, ja, M, N, kin, vin, ap, apf);

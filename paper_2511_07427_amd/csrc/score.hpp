@@ -213,16 +213,13 @@ __device__ __forceinline__ void wave_best2(float& zb, int& jb, float& z2) {
 // best, the best is it; otherwise every cluster within the bound (read back from zd[0..M), which the caller has
 // made visible to the workgroup) is evaluated in float64.  kd: the key in float64 (LDS); kn, rmax2: |k| and the
 // largest |r~_j|^2.  sv / si / s2: 16 entries of LDS each.
+// Second half of nearest_resolve: every wavefront's (best, its cluster, runner-up) is in sv / si / s2 [0 .. NT / 64)
+// and a barrier lies behind that.
 template <int NT>
-__device__ inline int nearest_resolve(const View& v, int u, int M, float zb, int jb, float z2, float kn, float rmax2,
-                                      const float* zd, const uint16_t* Rq, const double* kd, double* sv, int* si,
-                                      float* s2) {
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  wave_best2(zb, jb, z2);
-  lds_barrier();
-  if (lane == 0) { sv[w] = (double)zb; si[w] = jb; s2[w] = z2; }
-  lds_barrier();
-  zb = (float)sv[0]; jb = si[0]; z2 = s2[0];
+__device__ inline int nearest_decide(const View& v, int u, int M, float kn, float rmax2, const float* zd, const uint16_t* Rq,
+                                     const double* kd, double* sv, int* si, float* s2) {
+  float zb = (float)sv[0], z2 = s2[0];
+  int jb = si[0];
 #pragma unroll
   for (int k = 1; k < NT / 64; ++k) merge_best2(zb, jb, z2, (float)sv[k], si[k], s2[k]);
   const float rmax = __builtin_sqrtf(rmax2) * 1.0001f;
@@ -240,6 +237,17 @@ __device__ inline int nearest_resolve(const View& v, int u, int M, float zb, int
     }
   if (threadIdx.x == 0) count(v, u, 7, 1);
   return block_argmin<NT>(best, arg, sv, si);
+}
+template <int NT>
+__device__ inline int nearest_resolve(const View& v, int u, int M, float zb, int jb, float z2, float kn, float rmax2,
+                                      const float* zd, const uint16_t* Rq, const double* kd, double* sv, int* si,
+                                      float* s2) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  wave_best2(zb, jb, z2);
+  lds_barrier();
+  if (lane == 0) { sv[w] = (double)zb; si[w] = jb; s2[w] = z2; }
+  lds_barrier();
+  return nearest_decide<NT>(v, u, M, kn, rmax2, zd, Rq, kd, sv, si, s2);
 }
 
 }  // namespace dynakv

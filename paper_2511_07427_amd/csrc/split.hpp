@@ -907,14 +907,11 @@ __device__ inline void plan_splits(const View& v, SplitPlan& pl, const PlanEntry
   int nc = __popcll(dmask), forced = 0, fl = -1;
   if (v.Bmax > 0) {
     const bool rest = have && !delayed;
-    int total = rest ? e.cb : 0;
-    int bcb = rest ? e.cb : -1, bid = rest ? e.id : 0x7fffffff, bl = lane;
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-      total += __shfl_xor(total, o);
-      const int ocb = __shfl_xor(bcb, o), oid = __shfl_xor(bid, o), ol = __shfl_xor(bl, o);
-      if (ocb > bcb || (ocb == bcb && oid < bid)) { bcb = ocb; bid = oid; bl = ol; }
-    }
+    const int total = wave_sum(rest ? e.cb : 0);
+    const int bcb = wave_max(rest ? e.cb : -1);                                  // the fullest buffer ...
+    const int bid = wave_min(rest && e.cb == bcb ? e.id : 0x7ffffffe);           // ... of the lowest id among equals
+    const unsigned long long who = __ballot(rest && e.cb == bcb && e.id == bid);
+    const int bl = who ? __ffsll((long long)who) - 1 : 0;
     if (bcb >= 0 && total >= v.Bmax) {
       if (lane == 0) pl.cand[nc] = bl;
       fl = bl; ++nc; forced = 1;
@@ -952,13 +949,14 @@ struct PlanEarly {
 };
 // flagged0: entry `lane` of the flagged list, nflag0 its length, top0 the height of the free-page stack, all as
 // they are before the append; ja: the cluster the append goes to (< 0: no append).
+// selbits: the active set of the selection that has just run, one bit per cluster (LDS).
 __device__ __forceinline__ PlanEarly plan_fetch_early(const View& v, int u, int flagged0, int nflag0, int top0, int ja,
-                                                      int lane) {
+                                                      int lane, const unsigned* selbits) {
   const size_t cbase = (size_t)u * v.Mcap;
   PlanEarly e{-1, 0, 0, 0, 0, 0, int4{-1, -1, -1, -1}};
   const int c = lane < nflag0 ? flagged0 : lane == nflag0 ? ja : -1;
   if (c >= 0 && nflag0 <= 64) {
-    e.id = c; e.req = v.in_req[cbase + c]; e.cb = v.cb[cbase + c]; e.cn = v.cn[cbase + c];
+    e.id = c; e.req = (selbits[c >> 5] >> (c & 31)) & 1u; e.cb = v.cb[cbase + c]; e.cn = v.cn[cbase + c];
     e.pg = *(const int4*)&v.cpg[(cbase + c) * kInlinePages];
   }
   if (lane <= kFreeAhead && lane < top0) e.fl0 = v.freelist[(size_t)u * v.Pcap + top0 - 1 - lane];
