@@ -1160,6 +1160,7 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   __shared__ int am_i[16];
   __shared__ float am_2[16];
   __shared__ int am_r[16];
+  __shared__ int s_tile;                              // next tile of the page stream
   __shared__ unsigned selbits[kFusedClusters / 32];    // the active set, for the plan of the splits
   __shared__ __align__(16) int sm[64];
   __shared__ int misc[8];
@@ -1217,6 +1218,7 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   for (int i = M + tid; i < Mpad; i += NT) skey[i] = 0u;
   for (int i = tid; i < 1024; i += NT) hist[i] = 0;
   if (tid < 8) misc[tid] = tid == 4 ? 0x7fffffff : 0;
+  if (tid == 0) { s_tile = 0; if constexpr (SPLIT) wk.ready = 0; }
   if (SPLIT && tid < kFusedClusters / 32) selbits[tid] = 0u;
 #pragma unroll
   for (int k = 0; k < kFusedClusters / NT; ++k)
@@ -1279,10 +1281,10 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   const float unit_rmax2 = __int_as_float(rmu);
   // the append's nearest cluster: its record is requested here and used after the selection
   int ja = -1;
-  AppendFetch apf{0.0, 0, 0};
+  AppendFetchWave apf{0.0, 0.0, 0.0, 0, 0};
   if constexpr (APPEND) {
     ja = nearest_decide<NT>(v, u, M, rn.kn, unit_rmax2, v.zdist + (size_t)u * v.Mcap, Rq, ap.kd, am_v, am_i, am_2);
-    if (room) apf = append_fetch(v, u, ja);
+    if (room && wave == 0) apf = append_fetch_wave(v, u, ja);       // the first wavefront will carry out the append
   }
 
   // ---- selection
@@ -1294,32 +1296,12 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   if (nlist > kFusedList) __syncthreads();
   else lds_barrier();
 
-  // ---- the append (scores and selection saw the index as it was before); with SPLIT the first wavefront
-  // requests what the plan of the splits needs beforehand and makes the plan right after
-  PlanEarly pe{};
-  if constexpr (SPLIT)
-    if (wave == 0) {
-      flagged0 = wk.flagged0[lane]; nflag0 = wk.nflag0; top0 = wk.top0;
-      pe = plan_fetch_early(v, u, flagged0, nflag0, top0, room ? ja : -1, lane, selbits);
-    }
-  if constexpr (APPEND) {
-    if (room) append_commit<NT>(v, u, ja, M, N, kin, vin, ap, apf);
-    else if (tid == 0) v.err[u] |= DYNAKV_ERR_TOKENS;
-    if constexpr (SPLIT) __syncthreads();             // wavefronts that decide splits read the appended entry from its page
-    else lds_barrier();
-  }
-  int nprep = 0;
-  if constexpr (SPLIT) {
-    if (wave == 0) plan_finish<DT>(v, wk, pe, nflag0, top0, M, ja, room ? &ap : nullptr, kPreSplits);
-    lds_barrier();
-    nprep = wk.npre;
-  }
-
-  // ---- gather + attention (with SPLIT the first nprep wavefronts decide the first splits of the plan meanwhile)
-  const int GW = NW - nprep, gw = wave - nprep;
-  uint4 pre_v[kVAhead] = {};
-  if constexpr (SPLIT)
-    if (wave < nprep) split_predecide<DT>(v, u, smem + kRawOff, wk, wave, pre_v);
+  // ---- the append, the plan of the splits, and gather + attention.  Scores and selection saw the index as it was
+  // before the append; the gather list is fixed, and the append touches nothing it names.  So the first wavefront
+  // carries out the append and plans the step's splits on its own (no workgroup barrier) while the others already
+  // stream pages.  Tiles are handed out through an LDS counter, so it does not matter who streams: once the plan is
+  // known (wk.ready), the first wk.npre wavefronts turn to deciding one split each (they only read the index),
+  // the first of them being the wavefront that made the plan; everybody else streams until the tiles run out.
   const int g = lane & 15, lg = lane >> 4;
   typename F::Qf q;
   F::load_q(q, Q, (size_t)u * G + (g < G ? g : 0), lg, g < G);
@@ -1332,33 +1314,83 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   for (int c = 0; c < 8; ++c) st.acc[c] = f4{0, 0, 0, 0};
   const int* src = nlist <= kFusedList ? list : plist;
   const int ntile = (nlist + 3) >> 2, selK = (lane & 15) >> 2;
-  char* vtile = (char*)smem + max(gw, 0) * F::kVTile;      // scores, sizes and candidates are dead
-#define DYNAKV_TILE(T) make_tile<ES>(pages, 4 * (T) + selK < nlist ? src[4 * (T) + selK] : -1, \
-                                     4 * (T) + lg < nlist ? src[4 * (T) + lg] : -1, lane)
-  if (gw >= 0) {                                      // two tiles in flight per wavefront
-    typename F::KV a, b;
-    Tile ta = DYNAKV_TILE(gw), tb = ta;
-    if (gw < ntile) F::load(a, ta);
-    for (int p = gw; p < ntile; p += 2 * GW) {
-      if (p + GW < ntile) {
-        tb = DYNAKV_TILE(p + GW);
-        F::load(b, tb);
+  char* vtile = (char*)smem + wave * F::kVTile;            // scores, sizes and candidates are dead
+  uint4 pre_v[kVAhead] = {};
+  bool decides = false;                                // this wavefront decides a split instead of streaming
+  if constexpr (APPEND) {
+    if (wave == 0) {
+      PlanEarly pe{};
+      if constexpr (SPLIT) {
+        flagged0 = wk.flagged0[lane]; nflag0 = wk.nflag0; top0 = wk.top0;
+        pe = plan_fetch_early(v, u, flagged0, nflag0, top0, room ? ja : -1, lane, selbits);
       }
-      consume_page<F>(st, a, q, ta.nvq, sc, vtile, lane);
-      if (p + GW < ntile) {
-        if (p + 2 * GW < ntile) {
-          ta = DYNAKV_TILE(p + 2 * GW);
-          F::load(a, ta);
-        }
-        consume_page<F>(st, b, q, tb.nvq, sc, vtile, lane);
+      if (room) append_commit_wave(v, u, ja, M, N, kin, vin, ap, apf);
+      else if (lane == 0) v.err[u] |= DYNAKV_ERR_TOKENS;
+      if constexpr (SPLIT) {
+        wave_sync();
+        plan_finish<DT>(v, wk, pe, nflag0, top0, M, ja, room ? &ap : nullptr, kPreSplits);
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");     // plan and appended entry before the flag
+        if (lane == 0) __hip_atomic_store(&wk.ready, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+        decides = wk.npre > 0;
       }
     }
   }
+#define DYNAKV_TILE(T) make_tile<ES>(pages, 4 * (T) + selK < nlist ? src[4 * (T) + selK] : -1, \
+                                     4 * (T) + lg < nlist ? src[4 * (T) + lg] : -1, lane)
+  // next tile of the unit (wavefront-uniform); tiles past the end mean there is nothing left
+  auto grab = [&]() __attribute__((always_inline)) {
+    int t = 0;
+    if (lane == 0) t = atomicAdd(&s_tile, 1);
+    return __builtin_amdgcn_readfirstlane(t);
+  };
+  // a wavefront that may be asked to decide a split looks at the plan between two tiles
+  auto called_away = [&]() __attribute__((always_inline)) {
+    if constexpr (SPLIT) {
+      if (wave > 0 && wave < kPreSplits && !decides &&
+          __hip_atomic_load(&wk.ready, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) != 0 && wave < wk.npre)
+        decides = true;
+    }
+    return decides;
+  };
+  if (!decides) {                                     // two tiles in flight per wavefront
+    typename F::KV a, b;
+    int p0 = called_away() ? ntile : grab(), p1;
+    Tile ta = DYNAKV_TILE(min(p0, max(ntile - 1, 0))), tb = ta;
+    if (p0 < ntile) F::load(a, ta);
+    while (p0 < ntile) {
+      p1 = called_away() ? ntile : grab();
+      if (p1 < ntile) {
+        tb = DYNAKV_TILE(p1);
+        F::load(b, tb);
+      }
+      consume_page<F>(st, a, q, ta.nvq, sc, vtile, lane);
+      if (p1 >= ntile) break;
+      p0 = called_away() ? ntile : grab();
+      if (p0 < ntile) {
+        ta = DYNAKV_TILE(p0);
+        F::load(a, ta);
+      }
+      consume_page<F>(st, b, q, tb.nvq, sc, vtile, lane);
+    }
+  }
 #undef DYNAKV_TILE
+  if constexpr (SPLIT) {
+    // wavefronts 1 .. kPreSplits - 1 whose tiles ran out before the plan was there wait for it (it is a few
+    // microseconds away at most: the first wavefront does nothing else first)
+    if (wave > 0 && wave < kPreSplits && !decides) {
+      int spins = 0;
+      while (__hip_atomic_load(&wk.ready, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) == 0 && ++spins < (1 << 20))
+        __builtin_amdgcn_s_sleep(1);
+      decides = wave < wk.npre;
+    }
+    if (decides) split_predecide<DT>(v, u, smem + kRawOff, wk, wave, pre_v);
+  }
   float l = st.l;
   l += __shfl_xor(l, 16);
   l += __shfl_xor(l, 32);
   lds_barrier();                                      // the list is dead: its space becomes the merge buffer
+  int nprep = 0;
+  if constexpr (SPLIT) nprep = wk.npre;
   const int hs = kHeadDim + 2, ws = G * hs;
   if (g < G) {
     float* o = sm_o + wave * ws + g * hs;

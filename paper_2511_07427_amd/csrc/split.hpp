@@ -862,6 +862,8 @@ struct SplitWork {
   long long s_tot;
   int s_min;
   int nf0, M0, npre;                     // left by plan_finish: flagged clusters, clusters, splits decided ahead
+  int ready;                             // set (release) once the plan is in place, for wavefronts that do not share a
+                                         // barrier with the one that made it
   int flagged0[64], nflag0, top0;        // for plan_fetch_early: the flagged list and the free stack before the append
 };
 // Candidate k of a round of wavefront splits is handled by wavefront k and held in context ctx_of(k): the
