@@ -1151,7 +1151,6 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   // the split's LDS follows everything the streaming uses: its wavefront contexts are filled meanwhile
   constexpr int kPreSplits = kWaveSplits;              // splits decided while the pages are streamed
   constexpr size_t kRawOff = SPLIT ? (kPhases + 15) / 16 * 16 : 0;
-  static_assert(sizeof(WaveCtx) % 16 == 0 && kWaveSplits * sizeof(WaveCtx) <= kSplitRaw, "split contexts");
   static_assert(!SPLIT || kRawOff + kSplitRaw + 16 * 1024 <= 160 * 1024, "LDS of one compute unit");
   __shared__ __align__(16) unsigned char smem[SPLIT ? kRawOff + kSplitRaw : kPhases];
   __shared__ SplitWork wk;

@@ -485,29 +485,43 @@ __device__ __forceinline__ void split_cluster(const View& v, int u, int j, int p
 // ---- small clusters: one wavefront per split ---------------------------------------------------------
 // Most clusters that get split hold a few dozen entries at most.  Such a split keeps one wavefront busy, so
 // up to four flagged clusters of a unit are split side by side, one per wavefront, with no workgroup barrier
-// inside the 2-means: lane = member for distances and assignments, lane = coordinate (two each) for sums over
-// members.  The arithmetic is the one of split_cluster_impl, term for term.  What depends on the order of the
-// splits (new cluster ids, page allocation) is done by one thread between the two wavefront phases.
+// inside the 2-means: four lanes per member for distances and side tests, lane = coordinate (two each) for sums
+// over members.  Same 2-means as split_cluster_impl (seeds, side test with its float64 re-check, rounds, stable
+// partition, exact statistics); sums over members are float64 sums of 16-bit values, whose order does not matter.
+// What depends on the order of the splits (new cluster ids, page allocation) is done by one thread between the
+// two wavefront phases.
+// A cluster of up to twice that size (128 entries of a 16-bit type) is split the same way; such a split takes the
+// staging rows of two contexts, so only two of them run side by side (a "wide" plan).
 constexpr int kWaveSplits = kSplitThreads / 64;
 constexpr int kWaveStage = 64 * kStageRow16 * 2;                 // 64 rows of a 16-bit type, 32 of float32
 static_assert(32 * kStageRow32 * 4 <= kWaveStage, "float32 rows must fit");
-constexpr int kWavePages = 64 / kPageTokens;                     // pages of the largest such cluster
+constexpr int kWaveRows = 128;                                   // members of the largest such cluster (16-bit types)
+constexpr int kWavePages = kWaveRows / kPageTokens;              // its pages
+static_assert(kWavePages <= kInlinePages && kWavePages == 8, "the pages of such a cluster are found without walking its chain");
 // Values of the first members (16-byte chunk t = 64k + lane of the member-major array of V rows, k < kVAhead:
 // 16 members of a 16-bit type, 8 of float32) are requested together with the keys and wait in registers until
 // the children's pages are known.
 constexpr int kVAhead = 4;
 
 struct WaveCtx {
-  alignas(16) unsigned char stage[kWaveStage];
   double cA[kHeadDim], cB[kHeadDim];
   alignas(16) float rA[kHeadDim], rB[kHeadDim];
-  double dist[64];
   double m2[2];
-  unsigned char side[64], perm[64], inv[64];     // inv[member] = its place in perm
+  unsigned char side[kWaveRows], perm[kWaveRows], inv[kWaveRows];     // inv[member] = its place in perm
   int chain[kWavePages], newpg[kWavePages + 2];
-  int pos[64];                                   // sequence positions of the members
+  int pos[kWaveRows];                            // sequence positions of the members
   int j, m, ok, nS, idM;
+  int stage_off;                                 // the staged keys start this many bytes past the context itself
+  int pad_[2];
 };
+// The contexts lie at the front of the split's LDS, the staging rows of all of them behind: context x of a plan
+// of small clusters has rows 64x .. 64x + 63, context x = 2, 3 of a wide plan rows 128(x - 2) .. 128(x - 2) + 127.
+__device__ __forceinline__ void wave_place_stage(WaveCtx* wc, int x, bool wide) {
+  const int row0 = wide ? 128 * (x - 2) : 64 * x;
+  wc[x].stage_off = (int)((kWaveSplits - x) * sizeof(WaveCtx)) + row0 * (kWaveStage / 64);
+}
+__device__ __forceinline__ unsigned char* wave_stage(WaveCtx& c) { return (unsigned char*)&c + c.stage_off; }
+__device__ __forceinline__ const unsigned char* wave_stage(const WaveCtx& c) { return (const unsigned char*)&c + c.stage_off; }
 
 __device__ __forceinline__ void wave_sync() {   // LDS written by some lanes of this wavefront, read by others
   asm volatile("" ::: "memory");
@@ -516,22 +530,22 @@ __device__ __forceinline__ void wave_sync() {   // LDS written by some lanes of 
 }
 
 template <int DT>
-__device__ __forceinline__ float wkey(const WaveCtx& c, int i, int d) {
-  if constexpr (DT == DYNAKV_F32) return ((const float*)c.stage)[i * kStageRow32 + d];
+__device__ __forceinline__ float wkey(const unsigned char* stage, int i, int d) {
+  if constexpr (DT == DYNAKV_F32) return ((const float*)stage)[i * kStageRow32 + d];
   else {
-    const uint16_t h = ((const uint16_t*)c.stage)[i * kStageRow16 + d];
+    const uint16_t h = ((const uint16_t*)stage)[i * kStageRow16 + d];
     return DT == DYNAKV_F16 ? f16_to_float(h) : bf16_to_float(h);
   }
 }
 template <int DT>
-__device__ __forceinline__ void wkey8(const WaveCtx& c, int i, int d8, float (&x)[8]) {
+__device__ __forceinline__ void wkey8(const unsigned char* stage, int i, int d8, float (&x)[8]) {
   if constexpr (DT == DYNAKV_F32) {
-    const f4* p = (const f4*)((const float*)c.stage + i * kStageRow32 + d8 * 8);
+    const f4* p = (const f4*)((const float*)stage + i * kStageRow32 + d8 * 8);
     const f4 a = p[0], b = p[1];
 #pragma unroll
     for (int e = 0; e < 4; ++e) { x[e] = a[e]; x[4 + e] = b[e]; }
   } else {
-    const uint4 w = *(const uint4*)((const uint16_t*)c.stage + i * kStageRow16 + d8 * 8);
+    const uint4 w = *(const uint4*)((const uint16_t*)stage + i * kStageRow16 + d8 * 8);
     const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
@@ -544,230 +558,320 @@ __device__ __forceinline__ void wkey8(const WaveCtx& c, int i, int d8, float (&x
 // Key access in the form quad_sqdist expects.
 template <int DT>
 struct WaveKeys {
-  const WaveCtx& c;
-  __device__ void get8(int i, int d8, float (&x)[8]) const { wkey8<DT>(c, i, d8, x); }
+  const unsigned char* stage;
+  __device__ void get8(int i, int d8, float (&x)[8]) const { wkey8<DT>(stage, i, d8, x); }
 };
 
 // Wavefront arg-max of (value, index), index < 0 = none, equal values to the lowest index; all lanes get it.
+// DPP butterfly inside the rows of 16 lanes, row broadcasts across them; lane 63 ends up with the result.
+template <int CTRL, int ROWS>
+__device__ __forceinline__ void argmax_step(double& val, int& idx) {
+  // a lane that the step does not reach sees its own pair
+  const int lo = __builtin_amdgcn_update_dpp(__double2loint(val), __double2loint(val), CTRL, ROWS, 0xF, false);
+  const int hi = __builtin_amdgcn_update_dpp(__double2hiint(val), __double2hiint(val), CTRL, ROWS, 0xF, false);
+  const int oi = __builtin_amdgcn_update_dpp(idx, idx, CTRL, ROWS, 0xF, false);
+  const double ov = __hiloint2double(hi, lo);
+  if (oi >= 0 && (idx < 0 || ov > val || (ov == val && oi < idx))) { val = ov; idx = oi; }
+}
 __device__ __forceinline__ void wave_argmax(double& val, int& idx) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    const double ov = __shfl_xor(val, o);
-    const int oi = __shfl_xor(idx, o);
-    if (oi >= 0 && (idx < 0 || ov > val || (ov == val && oi < idx))) { val = ov; idx = oi; }
+  argmax_step<kDppXor1, 0xF>(val, idx);
+  argmax_step<kDppXor2, 0xF>(val, idx);
+  argmax_step<kDppHalfMirror, 0xF>(val, idx);
+  argmax_step<kDppMirror, 0xF>(val, idx);
+  argmax_step<kDppBcast15, 0xA>(val, idx);
+  argmax_step<kDppBcast31, 0xC>(val, idx);
+  val = readlane_f64(val, 63);
+  idx = __builtin_amdgcn_readlane(idx, 63);
+}
+
+// A set of members, wavefront-uniform: bit i of lo = member i, bit i of hi = member 64 + i.
+struct MemberSet {
+  unsigned long long lo, hi;
+};
+__device__ __forceinline__ MemberSet first_members(int m) {
+  return MemberSet{m >= 64 ? ~0ull : (1ull << m) - 1ull, m <= 64 ? 0ull : m >= 128 ? ~0ull : (1ull << (m - 64)) - 1ull};
+}
+__device__ __forceinline__ int set_count(MemberSet s) { return __popcll(s.lo) + __popcll(s.hi); }
+__device__ __forceinline__ MemberSet set_minus(MemberSet a, MemberSet b) { return MemberSet{a.lo & ~b.lo, a.hi & ~b.hi}; }
+
+// Coordinates 2 lane and 2 lane + 1 of staged member i: one LDS load.
+template <int DT>
+__device__ __forceinline__ void wpair(const unsigned char* stage, int i, int lane, float& a, float& b) {
+  if constexpr (DT == DYNAKV_F32) {
+    const float2 x = ((const float2*)((const float*)stage + i * kStageRow32))[lane];
+    a = x.x; b = x.y;
+  } else {
+    const uint32_t w = ((const uint32_t*)((const uint16_t*)stage + i * kStageRow16))[lane];
+    a = DT == DYNAKV_F16 ? f16_to_float((uint16_t)w) : bf16_to_float((uint16_t)w);
+    b = DT == DYNAKV_F16 ? f16_to_float((uint16_t)(w >> 16)) : bf16_to_float((uint16_t)(w >> 16));
   }
 }
 
-// Sums over the members at(q), q = q0..q1-1, of coordinates d and d + 64, each added one by one in that order.
-// With SIDES the members of side 0 go to (a0, a1) and those of side 1 to (b0, b1); otherwise all go to (a0, a1).
-// A member that does not belong to a sum adds +0.0, which leaves a float64 sum unchanged.  Eight loads per
-// round trip to LDS.
-// A_ONLY (with SIDES): only the sums of side 0 are formed.
-template <int DT, bool SIDES, bool A_ONLY = false, class At>
-__device__ __forceinline__ void wave_sums(const WaveCtx& c, int q0, int q1, int d, At&& at, double& a0, double& a1,
-                                          double& b0, double& b1) {
-  a0 = 0.0; a1 = 0.0; b0 = 0.0; b1 = 0.0;
-  for (int r0 = q0; r0 < q1; r0 += 8) {
-    float x0[8], x1[8];
-    bool sa[8], sb[8];
+// Sums over the members of `set`, in ascending order, of coordinates 2 lane and 2 lane + 1, in float64 (sums of up
+// to 128 values of a 16-bit type: exact for float16, and for bfloat16 unless the values of one coordinate span
+// more than 2^45).  Eight loads per round trip to LDS; the set is walked with scalar instructions.
+template <int DT>
+__device__ __forceinline__ void wave_set_sums(const unsigned char* stage, MemberSet set, int lane, double& s0, double& s1) {
+  s0 = 0.0; s1 = 0.0;
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      const int i = at(min(r0 + k, q1 - 1));
-      const bool in = r0 + k < q1;
-      x0[k] = wkey<DT>(c, i, d);
-      x1[k] = wkey<DT>(c, i, d + 64);
-      const unsigned char sd = SIDES ? c.side[i] : (unsigned char)0;
-      sa[k] = in && sd == 0;
-      sb[k] = in && sd == 1;
-    }
-    asm volatile("" ::: "memory");
+  for (int half = 0; half < 2; ++half) {
+    unsigned long long mk = half ? set.hi : set.lo;
+    while (mk) {
+      float x0[8], x1[8];
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      a0 += (double)(sa[k] ? x0[k] : 0.f);
-      a1 += (double)(sa[k] ? x1[k] : 0.f);
-      if (SIDES && !A_ONLY) {
-        b0 += (double)(sb[k] ? x0[k] : 0.f);
-        b1 += (double)(sb[k] ? x1[k] : 0.f);
+      for (int k = 0; k < 8; ++k) {
+        const bool in = mk != 0;
+        const int i = in ? 64 * half + (int)__builtin_ctzll(mk) : 0;     // member 0 always exists
+        mk &= mk - 1;
+        float a, b;
+        wpair<DT>(stage, i, lane, a, b);
+        x0[k] = in ? a : 0.f; x1[k] = in ? b : 0.f;
       }
+      asm volatile("" ::: "memory");
+#pragma unroll
+      for (int k = 0; k < 8; ++k) { s0 += (double)x0[k]; s1 += (double)x1[k]; }
     }
   }
 }
 
-// First phase, one wavefront: stage the keys (c.chain lists their pages), 2-means, stable partition.  Sets
-// c.ok, c.nS, c.perm.
+// quad_sqdist with the centre's coordinates 32 q .. 32 q + 31 already in registers (cr), one centre.
+template <class K, class C>
+__device__ __forceinline__ double quad_sqdist_reg(const K& ks, int i, int q, const C (&cr)[32]) {
+  double sa[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    float x[8];
+    ks.get8(i, q * 4 + k, x);
+    double a = 0.0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const double ta = (double)x[e] - (double)cr[k * 8 + e];
+      a = fma(ta, ta, a);
+    }
+    sa[k] = a;
+  }
+  return blocked16_quad(sa);
+}
+// quad_side with the float32 weights of coordinates 32 q .. 32 q + 31 already in registers (wr).
+template <class K>
+__device__ __forceinline__ unsigned char quad_side_reg(const K& ks, int i, int q, const float (&wr)[32], const double* wd,
+                                                       double t, float eps) {
+  float x[4][8];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) ks.get8(i, q * 4 + k, x[k]);
+  float s = 0.f;
+#pragma unroll
+  for (int k = 0; k < 4; ++k)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s = fmaf(x[k][e], wr[k * 8 + e], s);
+  s += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(s), kDppXor1, 0xF, 0xF, false));
+  s += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(s), kDppXor2, 0xF, 0xF, false));
+  const float tf = (float)t;
+  if (fabsf(s - tf) > eps) return s <= tf ? 0 : 1;            // uniform over the quad
+  double sd = 0.0;
+#pragma unroll
+  for (int k = 0; k < 4; ++k)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) sd = fma((double)x[k][e], wd[(q * 4 + k) * 8 + e], sd);
+  sd += dpp_f64<kDppXor1, 0xF>(sd);
+  sd += dpp_f64<kDppXor2, 0xF>(sd);
+  return sd <= t ? 0 : 1;
+}
+
+// One wavefront decides one split: stages the keys (c.chain lists their pages), 2-means, stable partition, exact
+// statistics of the children (of the unsplit cluster if the 2-means finds nothing to split).  Sets c.ok, c.nS,
+// c.perm, c.inv, c.pos, the float32 means c.rA / c.rB and the M2 about them, c.m2.
+// Lanes stand for coordinates (2 lane, 2 lane + 1) in sums over members, for quarter members (four lanes each) in
+// distances and side tests; the sides of a round are two 64-bit sets, and the sum of side A follows the members
+// that changed side instead of being formed anew.
 template <int DT, bool AHEAD>
 __device__ inline void wave_split_decide(const View& v, int u, WaveCtx& c, uint4 (&vahead)[kVAhead]) {
   const int lane = threadIdx.x & 63;
   constexpr int kEs = DT == DYNAKV_F32 ? 4 : 2;
   constexpr int kChunks = kHeadDim * kEs / 16;
   constexpr int kRowBytes = (DT == DYNAKV_F32 ? kStageRow32 : kStageRow16) * kEs;
+  constexpr int kAhead = 16;                               // key loads in flight per lane
   const char* const pool = v.pages + (size_t)u * v.Pcap * ((size_t)kPageElems * kEs);
   const int m = c.m;
-  for (int t0 = 0; t0 < m * kChunks; t0 += 4 * 64) {       // four loads in flight per lane
-    f4 w[4];                                               // (a plain vector type: these stay in registers)
+  unsigned char* const stage = wave_stage(c);
+  for (int t0 = 0; t0 < m * kChunks; t0 += kAhead * 64) {
+    f4 w[kAhead];                                          // (a plain vector type: these stay in registers)
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
+    for (int k = 0; k < kAhead; ++k) {
       const int t = min(t0 + k * 64 + lane, m * kChunks - 1);
       const int i = t / kChunks, ch = t % kChunks;
       const size_t off = (size_t)(DT == DYNAKV_F32 ? k_index32(i & 15, 4 * ch) : k_index16(i & 15, 8 * ch)) * kEs;
       w[k] = *(const f4*)(pool + (size_t)c.chain[i >> 4] * (kPageElems * kEs) + off);
     }
+    if (t0 == 0) {                                         // the values requested ahead and the positions ride along
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
+      for (int k = 0; k < kVAhead; ++k) {
+        const int t = k * 64 + lane, i = t / kChunks, ch = t % kChunks;
+        vahead[k] = uint4{0, 0, 0, 0};
+        if (AHEAD && i < m) {
+          const size_t off = (size_t)(DT == DYNAKV_F32 ? v_index32(i & 15, 4 * ch) : v_index16(i & 15, 8 * ch)) * kEs;
+          vahead[k] = *(const uint4*)(pool + (size_t)c.chain[i >> 4] * (kPageElems * kEs) + off);
+        }
+      }
+      for (int i = lane; i < m; i += 64) c.pos[i] = v.ppos[((size_t)u * v.Pcap + c.chain[i >> 4]) * kPageTokens + (i & 15)];
+    }
+#pragma unroll
+    for (int k = 0; k < kAhead; ++k) {
       const int t = t0 + k * 64 + lane;
-      if (t < m * kChunks) *(f4*)(c.stage + (size_t)(t / kChunks) * kRowBytes + (t % kChunks) * 16) = w[k];
+      if (t < m * kChunks) *(f4*)(stage + (size_t)(t / kChunks) * kRowBytes + (t % kChunks) * 16) = w[k];
     }
   }
-#pragma unroll
-  for (int k = 0; k < kVAhead; ++k) {
-    const int t = k * 64 + lane, i = t / kChunks, ch = t % kChunks;
-    vahead[k] = uint4{0, 0, 0, 0};
-    if (AHEAD && i < m) {
-      const size_t off = (size_t)(DT == DYNAKV_F32 ? v_index32(i & 15, 4 * ch) : v_index16(i & 15, 8 * ch)) * kEs;
-      vahead[k] = *(const uint4*)(pool + (size_t)c.chain[i >> 4] * (kPageElems * kEs) + off);
-    }
-  }
-  if (lane < m) c.pos[lane] = v.ppos[((size_t)u * v.Pcap + c.chain[lane >> 4]) * kPageTokens + (lane & 15)];
   wave_sync();
-  const WaveKeys<DT> ks{c};
+  const WaveKeys<DT> ks{stage};
   const int grp = lane >> 2, kb = lane & 3;      // four lanes per member in the distance passes
-  auto ident = [](int q) { return q; };
+  const MemberSet all = first_members(m);
+  double tot0, tot1;
+  wave_set_sums<DT>(stage, all, lane, tot0, tot1);
+  double sa0 = tot0, sa1 = tot1;                 // sum of side A
+  MemberSet A = all;
   bool can = m >= 2;
   if (can) {
     // seeds: A = member farthest from the mean of all members, B = member farthest from A
-    double s0, s1, u0, u1, dummy;
-    wave_sums<DT, false>(c, 0, m, lane, ident, s0, s1, u0, u1);
-    const double tot0 = s0, tot1 = s1;
-    c.cA[lane] = s0 / (double)m; c.cA[lane + 64] = s1 / (double)m;
+    const double mu0 = tot0 / (double)m, mu1 = tot1 / (double)m;
+    c.cA[2 * lane] = mu0; c.cA[2 * lane + 1] = mu1;
     wave_sync();
+    double cr[32];
+#pragma unroll
+    for (int e = 0; e < 32; ++e) cr[e] = c.cA[kb * 32 + e];
     double bv = -1.0;
     int a = -1;
     for (int base = 0; base < m; base += 16) {
       const int i = base + grp;
-      double t;
-      quad_sqdist<WaveKeys<DT>, double>(ks, min(i, m - 1), kb, c.cA, nullptr, t, dummy);
+      const double t = quad_sqdist_reg(ks, min(i, m - 1), kb, cr);
       if (kb == 0 && i < m && (a < 0 || t > bv)) { bv = t; a = i; }
     }
     wave_argmax(bv, a);
     const double dmax = bv;                   // largest squared distance of a member to the mean
-    c.cB[lane] = (double)wkey<DT>(c, a, lane); c.cB[lane + 64] = (double)wkey<DT>(c, a, lane + 64);
+    float fa0, fa1;
+    wpair<DT>(stage, a, lane, fa0, fa1);
+    double ca0 = (double)fa0, ca1 = (double)fa1;                             // seed A
+    c.cB[2 * lane] = ca0; c.cB[2 * lane + 1] = ca1;
     wave_sync();
+#pragma unroll
+    for (int e = 0; e < 32; ++e) cr[e] = c.cB[kb * 32 + e];
     bv = -1.0;
     int b = -1;
     for (int base = 0; base < m; base += 16) {
       const int i = base + grp;
-      double t;
-      quad_sqdist<WaveKeys<DT>, double>(ks, min(i, m - 1), kb, c.cB, nullptr, t, dummy);
+      const double t = quad_sqdist_reg(ks, min(i, m - 1), kb, cr);
       if (kb == 0 && i < m && (b < 0 || t > bv)) { bv = t; b = i; }
     }
     wave_argmax(bv, b);
     can = bv > 0.0;                          // false: all members identical
     if (can) {
       // every member lies within sqrt(dmax) of the mean, and so does every centre (a mean of members)
-      double mn2 = c.cA[lane] * c.cA[lane] + c.cA[lane + 64] * c.cA[lane + 64];
-#pragma unroll
-      for (int o = 32; o > 0; o >>= 1) mn2 += __shfl_xor(mn2, o);
+      const double mn2 = wave_sum_f64(mu0 * mu0 + mu1 * mu1);
       const float spread = (float)sqrt(dmax) * 1.0001f;
       const float xmax = spread + (float)sqrt(mn2) * 1.0001f;
-      double ca0 = c.cB[lane], ca1 = c.cB[lane + 64];                       // seed A
-      double cb0 = (double)wkey<DT>(c, b, lane), cb1 = (double)wkey<DT>(c, b, lane + 64);   // seed B
-      c.side[lane] = 2;
+      float fb0, fb1;
+      wpair<DT>(stage, b, lane, fb0, fb1);
+      double cb0 = (double)fb0, cb1 = (double)fb1;                           // seed B
+      bool first = true;
       for (int it = 0; it < 16; ++it) {
         // w = cB - cA into c.cA (float64) and c.rA (float32), t = (|cB|^2 - |cA|^2) / 2
         const double w0 = cb0 - ca0, w1 = cb1 - ca1;
-        double t = 0.5 * ((cb0 * cb0 - ca0 * ca0) + (cb1 * cb1 - ca1 * ca1));
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) t += __shfl_xor(t, o);
-        c.cA[lane] = w0; c.cA[lane + 64] = w1;
-        c.rA[lane] = (float)w0; c.rA[lane + 64] = (float)w1;
+        const double t = wave_sum_f64(0.5 * ((cb0 * cb0 - ca0 * ca0) + (cb1 * cb1 - ca1 * ca1)));
+        c.cA[2 * lane] = w0; c.cA[2 * lane + 1] = w1;
+        c.rA[2 * lane] = (float)w0; c.rA[2 * lane + 1] = (float)w1;
         wave_sync();
         const float eps = side_eps(xmax, 2.f * spread, t);
-        bool moved = false;
-        int nA = 0;
+        float wr[32];
+#pragma unroll
+        for (int e = 0; e < 32; e += 4) {
+          const f4 x = *(const f4*)(c.rA + kb * 32 + e);
+          wr[e] = x[0]; wr[e + 1] = x[1]; wr[e + 2] = x[2]; wr[e + 3] = x[3];
+        }
         for (int base = 0; base < m; base += 16) {
           const int i = base + grp;
-          const unsigned char ns = quad_side(ks, min(i, m - 1), kb, c.rA, c.cA, t, eps);
-          const bool own = kb == 0 && i < m;
-          moved = moved || __ballot(own && ns != c.side[min(i, 63)]) != 0;
-          nA += __popcll(__ballot(own && ns == 0));
-          if (own) c.side[i] = ns;
+          const unsigned char ns = quad_side_reg(ks, min(i, m - 1), kb, wr, c.cA, t, eps);
+          if (kb == 0 && i < m) c.side[i] = ns;
         }
         wave_sync();
-        if (!moved) break;
+        MemberSet nw;
+        nw.lo = __ballot(lane < m && c.side[lane] == 0);
+        nw.hi = m > 64 ? __ballot(lane + 64 < m && c.side[lane + 64] == 0) : 0ull;
+        if (!first && nw.lo == A.lo && nw.hi == A.hi) break;          // no member moved
+        const int nA = set_count(nw);
         if (nA == 0 || nA == m) { can = false; break; }
-        // sums of side A; side B is what is left of the total (float64 sums of 16-bit values: exact or very nearly so)
-        double a0, a1, b0, b1;
-        wave_sums<DT, true, true>(c, 0, m, lane, ident, a0, a1, b0, b1);
-        ca0 = a0 / (double)nA; ca1 = a1 / (double)nA;
-        cb0 = (tot0 - a0) / (double)(m - nA); cb1 = (tot1 - a1) / (double)(m - nA);
+        // the sum of side A: formed from the smaller side in the first round, then corrected by the members that
+        // moved; side B is what is left of the total
+        double j0, j1, l0, l1;
+        if (first) {
+          if (2 * nA <= m) wave_set_sums<DT>(stage, nw, lane, sa0, sa1);
+          else {
+            wave_set_sums<DT>(stage, set_minus(all, nw), lane, l0, l1);
+            sa0 = tot0 - l0; sa1 = tot1 - l1;
+          }
+        } else {
+          wave_set_sums<DT>(stage, set_minus(nw, A), lane, j0, j1);
+          wave_set_sums<DT>(stage, set_minus(A, nw), lane, l0, l1);
+          sa0 += j0 - l0; sa1 += j1 - l1;
+        }
+        A = nw; first = false;
+        ca0 = sa0 / (double)nA; ca1 = sa1 / (double)nA;
+        cb0 = (tot0 - sa0) / (double)(m - nA); cb1 = (tot1 - sa1) / (double)(m - nA);
       }
     }
   }
-  int nS = m;
-  if (can) {        // stable partition: the child that holds the earliest entry comes first and keeps the id
-    const unsigned char keep = c.side[0];
-    const unsigned long long mask = __ballot(lane < m && c.side[lane] == keep);
-    const int before = __popcll(mask & ((1ull << lane) - 1ull));
-    nS = __popcll(mask);
+  // stable partition: the child that holds the earliest entry comes first and keeps the id
+  MemberSet S = all;
+  if (can) S = (A.lo & 1ull) ? A : set_minus(all, A);
+  const int n0 = __popcll(S.lo), nS = n0 + __popcll(S.hi), nM = m - nS;
+  {
+    const unsigned long long below = (1ull << lane) - 1ull;
     if (lane < m) {
-      const int q = (mask >> lane) & 1ull ? before : nS + lane - before;
+      const int before = __popcll(S.lo & below);
+      const int q = (S.lo >> lane) & 1ull ? before : nS + lane - before;
       c.perm[q] = (unsigned char)lane;
       c.inv[lane] = (unsigned char)q;
     }
-  } else if (lane < m) {
-    c.perm[lane] = (unsigned char)lane;
-    c.inv[lane] = (unsigned char)lane;
+    if (lane + 64 < m) {
+      const int before = n0 + __popcll(S.hi & below);
+      const int q = (S.hi >> lane) & 1ull ? before : nS + (lane + 64) - before;
+      c.perm[q] = (unsigned char)(lane + 64);
+      c.inv[lane + 64] = (unsigned char)q;
+    }
   }
   if (lane == 0) { c.ok = can ? 1 : 0; c.nS = nS; }
-  wave_sync();
-}
-
-// Exact statistics of the children (of the unsplit cluster if c.ok == 0), one wavefront, LDS only: float32
-// means into c.rA / c.rB, then M2 about those means into c.m2, members in their new order.
-template <int DT>
-__device__ __forceinline__ void wave_split_stats(WaveCtx& c) {
-  const int lane = threadIdx.x & 63;
-  const int m = c.m, nS = c.nS, nM = m - nS;
-  auto at = [&](int q) { return (int)c.perm[q]; };
-  double s0, s1, u0, u1;
-  wave_sums<DT, false>(c, 0, nS, lane, at, s0, s1, u0, u1);
-  c.rA[lane] = nS > 0 ? (float)(s0 / (double)nS) : 0.f;
-  c.rA[lane + 64] = nS > 0 ? (float)(s1 / (double)nS) : 0.f;
-  if (c.ok) {
-    wave_sums<DT, false>(c, nS, m, lane, at, s0, s1, u0, u1);
-    c.rB[lane] = nM > 0 ? (float)(s0 / (double)nM) : 0.f;
-    c.rB[lane + 64] = nM > 0 ? (float)(s1 / (double)nM) : 0.f;
+  // exact statistics: float32 means of the children, then M2 about those means
+  double sS0 = tot0, sS1 = tot1;
+  if (can && (A.lo & 1ull)) { sS0 = sa0; sS1 = sa1; }
+  else if (can) { sS0 = tot0 - sa0; sS1 = tot1 - sa1; }
+  c.rA[2 * lane] = (float)(sS0 / (double)nS); c.rA[2 * lane + 1] = (float)(sS1 / (double)nS);
+  if (can) {
+    c.rB[2 * lane] = (float)((tot0 - sS0) / (double)nM); c.rB[2 * lane + 1] = (float)((tot1 - sS1) / (double)nM);
   }
   wave_sync();
-  {
-    const WaveKeys<DT> ks{c};
-    const int grp = lane >> 2, kb = lane & 3;
-    for (int base = 0; base < m; base += 16) {
-      const int q = base + grp, qc = min(q, m - 1);
-      double dv, dummy;
-      quad_sqdist<WaveKeys<DT>, float>(ks, c.perm[qc], kb, qc < nS ? c.rA : c.rB, nullptr, dv, dummy);
-      if (kb == 0 && q < m) c.dist[q] = dv;
+  double acc[2] = {0.0, 0.0};
+#pragma unroll
+  for (int child = 0; child < 2; ++child) {
+    const int q0 = child ? nS : 0, q1 = child ? m : nS;
+    if (q1 <= q0) continue;
+    const float* r = child ? c.rB : c.rA;
+    float fr[32];
+#pragma unroll
+    for (int e = 0; e < 32; e += 4) {
+      const f4 x = *(const f4*)(r + kb * 32 + e);
+      fr[e] = x[0]; fr[e + 1] = x[1]; fr[e + 2] = x[2]; fr[e + 3] = x[3];
+    }
+    for (int base = q0; base < q1; base += 16) {
+      const int q = base + grp;
+      const double dv = quad_sqdist_reg(ks, c.perm[min(q, q1 - 1)], kb, fr);
+      if (kb == 0 && q < q1) acc[child] += dv;
     }
   }
-  wave_sync();
-  if (lane < 2) {
-    const int q0 = lane ? nS : 0, q1 = lane ? m : nS;
-    double acc = 0.0;
-    for (int r0 = q0; r0 < q1; r0 += 8) {
-      double x[8];
-#pragma unroll
-      for (int k = 0; k < 8; ++k) x[k] = r0 + k < q1 ? c.dist[r0 + k] : 0.0;
-      asm volatile("" ::: "memory");
-#pragma unroll
-      for (int k = 0; k < 8; ++k) acc += x[k];
-    }
-    c.m2[lane] = acc;
-  }
+  const double m2S = wave_sum_f64(acc[0]), m2M = wave_sum_f64(acc[1]);
+  if (lane == 0) { c.m2[0] = m2S; c.m2[1] = m2M; }
   wave_sync();
 }
 
 // Last phase, one wavefront, once the children's id and pages are assigned: pages, centroids and records.  With
-// c.ok == 0 the cluster is only unflagged, with exact statistics.  wave_split_stats has run on c.
+// c.ok == 0 the cluster is only unflagged, with exact statistics.  wave_split_decide has run on c.
 template <int DT>
 __device__ inline void wave_split_commit(const View& v, int u, WaveCtx& c, const uint4 (&vahead)[kVAhead],
                                          bool ahead) {
@@ -780,6 +884,7 @@ __device__ inline void wave_split_commit(const View& v, int u, WaveCtx& c, const
   char* const pool = v.pages + (size_t)u * v.Pcap * kPageBytes;
   const int m = c.m, j = c.j, nS = c.nS, nM = m - nS, idM = c.ok ? c.idM : -1;
   const int pS = (nS + kPageTokens - 1) / kPageTokens, pM = (nM + kPageTokens - 1) / kPageTokens, need = pS + pM;
+  const unsigned char* const stage = wave_stage(c);
   if (c.ok) {
     if (lane < need) v.pnext[(size_t)u * v.Pcap + c.newpg[lane]] = (lane == pS - 1 || lane == need - 1) ? -1 : c.newpg[lane + 1];
     for (int t = lane; t < m * kChunks; t += 64) {
@@ -788,7 +893,7 @@ __device__ inline void wave_split_commit(const View& v, int u, WaveCtx& c, const
       const int r = q < nS ? q : q - nS;
       const int dpage = c.newpg[(q < nS ? 0 : pS) + (r >> 4)];
       const size_t off = (size_t)(DT == DYNAKV_F32 ? k_index32(r & 15, 4 * ch) : k_index16(r & 15, 8 * ch)) * kEs;
-      *(uint4*)(pool + (size_t)dpage * kPageBytes + off) = *(const uint4*)(c.stage + (size_t)i * kRowBytes + ch * 16);
+      *(uint4*)(pool + (size_t)dpage * kPageBytes + off) = *(const uint4*)(stage + (size_t)i * kRowBytes + ch * 16);
     }
     // values chunk by chunk like the keys, straight from their old pages: first the chunks requested ahead
     auto vchunk = [](int slot, int ch) -> size_t {
@@ -820,11 +925,11 @@ __device__ inline void wave_split_commit(const View& v, int u, WaveCtx& c, const
         if (t < m * kChunks) *(f4*)vdest(t / kChunks, t % kChunks) = w[k];
       }
     }
-    if (lane < m) {
-      const int q = c.inv[lane];
+    for (int i = lane; i < m; i += 64) {
+      const int q = c.inv[i];
       const int r = q < nS ? q : q - nS;
       const int dpage = c.newpg[(q < nS ? 0 : pS) + (r >> 4)];
-      v.ppos[((size_t)u * v.Pcap + dpage) * kPageTokens + (r & 15)] = c.pos[lane];
+      v.ppos[((size_t)u * v.Pcap + dpage) * kPageTokens + (r & 15)] = c.pos[i];
     }
   }
   store_centroid(v, u, j, lane, c.rA[lane]); store_centroid(v, u, j, lane + 64, c.rA[lane + 64]);
@@ -848,15 +953,18 @@ __device__ inline void wave_split_commit(const View& v, int u, WaveCtx& c, const
 constexpr int kFreeAhead = 24;
 struct SplitPlan {
   int id[64], req[64], cb[64], m[64];   // the flagged clusters
-  int pg[64][kWavePages];               // their first pages
+  alignas(16) int pg[64][kWavePages];   // their first pages
   int cand[64];                          // positions in the list, in the order of the splits
   int n_cand, forced, fast;
+  int wide;                              // some cluster of the plan needs two members per lane: two splits at a time
   int M, top, bump;                      // the unit's counters while the plan is carried out
   int fl[kFreeAhead], fl_base;           // top of the free-page stack, read ahead: fl[k] = entry fl_base - 1 - k
 };
 
 // LDS of one unit's splits: `raw` holds either the workgroup-wide split or four wavefront splits.
-constexpr size_t kSplitRaw = sizeof(SplitSmem) > kWaveSplits * sizeof(WaveCtx) ? sizeof(SplitSmem) : kWaveSplits * sizeof(WaveCtx);
+constexpr size_t kWaveRaw = kWaveSplits * (sizeof(WaveCtx) + kWaveStage);
+constexpr size_t kSplitRaw = sizeof(SplitSmem) > kWaveRaw ? sizeof(SplitSmem) : kWaveRaw;
+static_assert(sizeof(WaveCtx) % 16 == 0, "the staging rows behind the contexts are 16-byte aligned");
 struct SplitWork {
   SplitPlan pl;
   long long s_tot;
@@ -879,9 +987,10 @@ struct PlanEntry {
 __device__ __forceinline__ PlanEntry plan_fetch(const View& v, size_t cbase, SplitPlan& pl, int i, int c) {
   const int b = v.cb[cbase + c];
   const int4 pg = *(const int4*)&v.cpg[(cbase + c) * kInlinePages];
+  const int4 pg2 = *(const int4*)&v.cpg[(cbase + c) * kInlinePages + 4];
   const PlanEntry e{c, v.in_req[cbase + c], b, v.cn[cbase + c] + b};
   pl.id[i] = e.id; pl.req[i] = e.req; pl.cb[i] = e.cb; pl.m[i] = e.m;
-  pl.pg[i][0] = pg.x; pl.pg[i][1] = pg.y; pl.pg[i][2] = pg.z; pl.pg[i][3] = pg.w;
+  *(int4*)&pl.pg[i][0] = pg; *(int4*)&pl.pg[i][4] = pg2;
   return e;
 }
 // Everything the page allocation will need, requested in the same round trip: entry k of the read-ahead.
@@ -920,21 +1029,23 @@ __device__ inline void plan_splits(const View& v, SplitPlan& pl, const PlanEntry
     }
   }
   // the wavefront path takes the plan if every cluster is small and no capacity limit can be hit
-  constexpr int kSmall = DT == DYNAKV_F32 ? 32 : 64;
+  constexpr int kSmall = DT == DYNAKV_F32 ? 32 : 64;                 // one member per lane; twice that: a wide plan
   const bool isc = delayed || lane == fl;
-  const bool small = __ballot(isc && e.m > kSmall) == 0;
+  const bool small = __ballot(isc && e.m > 2 * kSmall) == 0;
+  const bool wide = __ballot(isc && e.m > kSmall) != 0;
   int pages = isc ? (e.m + kPageTokens - 1) / kPageTokens + 1 : 0;
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) pages += __shfl_xor(pages, o);
   if (lane == 0) {
-    pl.n_cand = nc; pl.forced = forced;
+    pl.n_cand = nc; pl.forced = forced; pl.wide = wide ? 1 : 0;
     pl.fast = small && pl.M + nc <= v.Mcap && pages <= pl.top + (v.Pcap - pl.bump);
   }
 }
 
 // Hands candidate `at` of the plan to context c (one wavefront).
-__device__ __forceinline__ void wave_take(const SplitPlan& pl, int at, WaveCtx& c, int lane) {
-  if (lane == 0) { c.j = pl.id[at]; c.m = pl.m[at]; }
+__device__ __forceinline__ void wave_take(const SplitPlan& pl, int at, WaveCtx* wc, int x, int lane) {
+  WaveCtx& c = wc[x];
+  if (lane == 0) { c.j = pl.id[at]; c.m = pl.m[at]; wave_place_stage(wc, x, pl.wide != 0); }
   if (lane < kWavePages) c.chain[lane] = pl.pg[at][lane];
   wave_sync();
 }
@@ -947,7 +1058,7 @@ __device__ __forceinline__ void wave_take(const SplitPlan& pl, int at, WaveCtx& 
 struct PlanEarly {
   int id, req, cb, cn;     // lane i < nflag0: flagged cluster i; lane nflag0: the cluster the append may flag
   int fl0, bump0;          // free-page stack entry top0 - 1 - lane; bump pointer
-  int4 pg;
+  int4 pg, pg2;
 };
 // flagged0: entry `lane` of the flagged list, nflag0 its length, top0 the height of the free-page stack, all as
 // they are before the append; ja: the cluster the append goes to (< 0: no append).
@@ -955,11 +1066,12 @@ struct PlanEarly {
 __device__ __forceinline__ PlanEarly plan_fetch_early(const View& v, int u, int flagged0, int nflag0, int top0, int ja,
                                                       int lane, const unsigned* selbits) {
   const size_t cbase = (size_t)u * v.Mcap;
-  PlanEarly e{-1, 0, 0, 0, 0, 0, int4{-1, -1, -1, -1}};
+  PlanEarly e{-1, 0, 0, 0, 0, 0, int4{-1, -1, -1, -1}, int4{-1, -1, -1, -1}};
   const int c = lane < nflag0 ? flagged0 : lane == nflag0 ? ja : -1;
   if (c >= 0 && nflag0 <= 64) {
     e.id = c; e.req = (selbits[c >> 5] >> (c & 31)) & 1u; e.cb = v.cb[cbase + c]; e.cn = v.cn[cbase + c];
     e.pg = *(const int4*)&v.cpg[(cbase + c) * kInlinePages];
+    e.pg2 = *(const int4*)&v.cpg[(cbase + c) * kInlinePages + 4];
   }
   if (lane <= kFreeAhead && lane < top0) e.fl0 = v.freelist[(size_t)u * v.Pcap + top0 - 1 - lane];
   e.bump0 = v.bump[u];
@@ -985,6 +1097,10 @@ __device__ inline void plan_finish(const View& v, SplitWork& wk, PlanEarly e, in
         else if (k == 1) e.pg.y = a->page;
         else if (k == 2) e.pg.z = a->page;
         else if (k == 3) e.pg.w = a->page;
+        else if (k == 4) e.pg2.x = a->page;
+        else if (k == 5) e.pg2.y = a->page;
+        else if (k == 6) e.pg2.z = a->page;
+        else if (k == 7) e.pg2.w = a->page;
       }
     }
   }
@@ -998,12 +1114,12 @@ __device__ inline void plan_finish(const View& v, SplitWork& wk, PlanEarly e, in
   if (lane < kFreeAhead && lane < top) pl.fl[lane] = fl;
   if (e.id >= 0) {
     pl.id[lane] = e.id; pl.req[lane] = e.req; pl.cb[lane] = e.cb; pl.m[lane] = e.cn + e.cb;
-    pl.pg[lane][0] = e.pg.x; pl.pg[lane][1] = e.pg.y; pl.pg[lane][2] = e.pg.z; pl.pg[lane][3] = e.pg.w;
+    *(int4*)&pl.pg[lane][0] = e.pg; *(int4*)&pl.pg[lane][4] = e.pg2;
   }
   wave_sync();
   plan_splits<DT>(v, pl, PlanEntry{e.id, e.req, e.cb, e.cn + e.cb});
   wave_sync();
-  if (lane == 0) wk.npre = pl.fast ? min(pl.n_cand, max_pre) : 0;
+  if (lane == 0) wk.npre = pl.fast ? min(pl.n_cand, min(max_pre, pl.wide ? kWaveSplits / 2 : kWaveSplits)) : 0;
 }
 // Wavefront k < wk.npre decides split k of the plan and computes the children's statistics, into context
 // ctx_of(k) of `raw`; pre_v: the values requested ahead, for the same wavefront to hand to split_unit.
@@ -1011,9 +1127,8 @@ template <int DT>
 __device__ inline void split_predecide(const View& v, int u, unsigned char* raw, const SplitWork& wk, int k,
                                        uint4 (&pre_v)[kVAhead]) {
   WaveCtx& c = ((WaveCtx*)raw)[ctx_of(k)];
-  wave_take(wk.pl, wk.pl.cand[k], c, threadIdx.x & 63);
+  wave_take(wk.pl, wk.pl.cand[k], (WaveCtx*)raw, ctx_of(k), threadIdx.x & 63);
   wave_split_decide<DT, true>(v, u, c, pre_v);
-  wave_split_stats<DT>(c);
 }
 
 // One thread: ids and pages for the decided splits base .. base + n - 1 of the plan (contexts ctx_of(0 .. n-1)),
@@ -1091,20 +1206,20 @@ __device__ __forceinline__ void split_unit(const View& v, int u, unsigned char* 
     if (pl.fast) {
       const int wave = tid >> 6, lane = tid & 63;
       const int nc = pl.n_cand;
+      const int side_by_side = pl.wide ? kWaveSplits / 2 : kWaveSplits;
       if (npre > 0) {                      // committed by the caller
         if (tid == 0) split_recycle(v, u, wc, pl, npre, 0);
         __syncthreads();
       }
-      for (int base = npre; base < nc; base += kWaveSplits) {
+      for (int base = npre; base < nc; base += side_by_side) {
         const int mk = base + wave;                    // this wavefront's candidate
-        const bool mine = mk < nc;
-        const int n = min(kWaveSplits, nc - base);
+        const bool mine = wave < side_by_side && mk < nc;
+        const int n = min(side_by_side, nc - base);
         uint4 vahead[kVAhead];
         WaveCtx& c = wc[ctx_of(wave)];
         if (mine) {
-          wave_take(pl, pl.cand[mk], c, lane);
+          wave_take(pl, pl.cand[mk], wc, ctx_of(wave), lane);
           wave_split_decide<DT, true>(v, u, c, vahead);
-          wave_split_stats<DT>(c);
         }
         __syncthreads();
         if (tid == 0) split_assign(v, u, wc, pl, n);             // ids and pages, in the order of the splits
