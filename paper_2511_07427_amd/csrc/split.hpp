@@ -506,6 +506,7 @@ constexpr int kVAhead = 4;
 struct WaveCtx {
   double cA[kHeadDim], cB[kHeadDim];
   alignas(16) float rA[kHeadDim], rB[kHeadDim];
+  float d32[kWaveRows];                          // member distances of a seed search
   double m2[2];
   unsigned char side[kWaveRows], perm[kWaveRows], inv[kWaveRows];     // inv[member] = its place in perm
   int chain[kWavePages], newpg[kWavePages + 2];
@@ -634,24 +635,125 @@ __device__ __forceinline__ void wave_set_sums(const unsigned char* stage, Member
   }
 }
 
-// quad_sqdist with the centre's coordinates 32 q .. 32 q + 31 already in registers (cr), one centre.
-template <class K, class C>
-__device__ __forceinline__ double quad_sqdist_reg(const K& ks, int i, int q, const C (&cr)[32]) {
-  double sa[4];
+// Squared distance of member i to a centre whose coordinates 32 q .. 32 q + 31 are in cr, by the four lanes of a
+// quad; every lane gets the total.  Differences, squares and sums in float32: a difference is off by 2^-24 of itself,
+// the total by less than 2^-18 of itself.
+template <class K>
+__device__ __forceinline__ float quad_sqdist32(const K& ks, int i, int q, const float (&cr)[32]) {
+  float acc[4];
 #pragma unroll
   for (int k = 0; k < 4; ++k) {
     float x[8];
     ks.get8(i, q * 4 + k, x);
-    double a = 0.0;
+    float a = 0.f;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      const double ta = (double)x[e] - (double)cr[k * 8 + e];
-      a = fma(ta, ta, a);
+      const float t = x[e] - cr[k * 8 + e];
+      a = fmaf(t, t, a);
     }
-    sa[k] = a;
+    acc[k] = a;
   }
-  return blocked16_quad(sa);
+  float s = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+  s += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(s), kDppXor1, 0xF, 0xF, false));
+  s += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(s), kDppXor2, 0xF, 0xF, false));
+  return s;
 }
+// This lane's 32 coordinates (32 q ..) of a float32 vector in LDS.
+__device__ __forceinline__ void load_quarter(const float* r, int q, float (&fr)[32]) {
+#pragma unroll
+  for (int e = 0; e < 32; e += 4) {
+    const f4 x = *(const f4*)(r + q * 32 + e);
+    fr[e] = x[0]; fr[e + 1] = x[1]; fr[e + 2] = x[2]; fr[e + 3] = x[3];
+  }
+}
+
+// The member farthest from a centre (the lowest index among equals), by one wavefront.  The distances are first
+// taken in float32 against the centre rounded to float32 (c.rA); the members within the rounding bound of the
+// largest, if there are several, are then compared in float64 against the centre itself (c0, c1: its coordinates
+// 2 lane and 2 lane + 1).  cnorm: the centre's norm if rounding it to float32 changed it, else 0.  dub: an upper
+// bound of that largest squared distance (the exact value after a float64 comparison).
+template <int DT>
+__device__ __forceinline__ int wave_farthest(const WaveKeys<DT>& ks, const unsigned char* stage, WaveCtx& c, int m,
+                                             double c0, double c1, float cnorm, double& dub) {
+  const int lane = threadIdx.x & 63, grp = lane >> 2, kb = lane & 3;
+  float cr[32];
+  load_quarter(c.rA, kb, cr);
+  float fm = -1.f;
+  for (int base = 0; base < m; base += 16) {
+    const int i = base + grp;
+    const float d = quad_sqdist32(ks, min(i, m - 1), kb, cr);
+    if (kb == 0 && i < m) { c.d32[i] = d; fm = fmaxf(fm, d); }
+  }
+  const float top = __int_as_float(wave_max(__float_as_int(fm)));       // distances are >= 0: ordered like their bits
+  wave_sync();
+  // rounding the centre moves a difference by 2^-24 |centre|, hence the distance by 2^-23 |centre| sqrt(distance)
+  const float eps = 2.4e-7f * cnorm * sqrtf(top) + 3.1e-5f * top;
+  const float thr = top - 2.f * eps;
+  MemberSet cand;
+  cand.lo = __ballot(lane < m && c.d32[lane] >= thr);
+  cand.hi = m > 64 ? __ballot(lane + 64 < m && c.d32[lane + 64] >= thr) : 0ull;
+  if (set_count(cand) == 1) {
+    dub = (double)(top + eps);
+    return cand.lo ? (int)__builtin_ctzll(cand.lo) : 64 + (int)__builtin_ctzll(cand.hi);
+  }
+  int best = -1;
+  double bv = -1.0;
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    unsigned long long mk = half ? cand.hi : cand.lo;
+    while (mk) {
+      const int i = 64 * half + (int)__builtin_ctzll(mk);
+      mk &= mk - 1;
+      float a, b;
+      wpair<DT>(stage, i, lane, a, b);
+      const double d0 = (double)a - c0, d1 = (double)b - c1;
+      const double d = wave_sum_f64(fma(d0, d0, d1 * d1));
+      if (d > bv) { bv = d; best = i; }
+    }
+  }
+  dub = bv;
+  return best;
+}
+
+// The same sums for a large set: the four rows of 16 lanes take every fourth member each, a lane adding up the
+// eight coordinates of its 16-byte chunk (one LDS load per member and lane); the rows' parts are then added and
+// handed to the lanes that own the coordinates through c.cB (which must be free).
+template <int DT>
+__device__ __forceinline__ void wave_set_sums_rows(const unsigned char* stage, WaveCtx& c, MemberSet set, int m, int lane,
+                                                   double& s0, double& s1) {
+  const int r = lane >> 4, ch = lane & 15;
+  double acc[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) acc[e] = 0.0;
+#pragma unroll 2
+  for (int i = r; i < m; i += 4) {
+    const bool in = (((i < 64 ? set.lo : set.hi) >> (i & 63)) & 1ull) != 0;
+    float x[8];
+    wkey8<DT>(stage, i, ch, x);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] += in ? (double)x[e] : 0.0;
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    acc[e] += __shfl_xor(acc[e], 16);
+    acc[e] += __shfl_xor(acc[e], 32);
+  }
+  if (r == 0) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) c.cB[8 * ch + e] = acc[e];
+  }
+  wave_sync();
+  s0 = c.cB[2 * lane]; s1 = c.cB[2 * lane + 1];
+  wave_sync();
+}
+// Either way, by the size of the set.
+template <int DT>
+__device__ __forceinline__ void wave_sums_of(const unsigned char* stage, WaveCtx& c, MemberSet set, int m, int lane,
+                                             double& s0, double& s1) {
+  if (set_count(set) > 48) wave_set_sums_rows<DT>(stage, c, set, m, lane, s0, s1);
+  else wave_set_sums<DT>(stage, set, lane, s0, s1);
+}
+
 // quad_side with the float32 weights of coordinates 32 q .. 32 q + 31 already in registers (wr).
 template <class K>
 __device__ __forceinline__ unsigned char quad_side_reg(const K& ks, int i, int q, const float (&wr)[32], const double* wd,
@@ -659,11 +761,15 @@ __device__ __forceinline__ unsigned char quad_side_reg(const K& ks, int i, int q
   float x[4][8];
 #pragma unroll
   for (int k = 0; k < 4; ++k) ks.get8(i, q * 4 + k, x[k]);
-  float s = 0.f;
+  float part[4];
 #pragma unroll
-  for (int k = 0; k < 4; ++k)
+  for (int k = 0; k < 4; ++k) {
+    float a = 0.f;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) s = fmaf(x[k][e], wr[k * 8 + e], s);
+    for (int e = 0; e < 8; ++e) a = fmaf(x[k][e], wr[k * 8 + e], a);
+    part[k] = a;
+  }
+  float s = (part[0] + part[1]) + (part[2] + part[3]);
   s += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(s), kDppXor1, 0xF, 0xF, false));
   s += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(s), kDppXor2, 0xF, 0xF, false));
   const float tf = (float)t;
@@ -694,11 +800,12 @@ __device__ inline void wave_split_decide(const View& v, int u, WaveCtx& c, uint4
   const char* const pool = v.pages + (size_t)u * v.Pcap * ((size_t)kPageElems * kEs);
   const int m = c.m;
   unsigned char* const stage = wave_stage(c);
-  for (int t0 = 0; t0 < m * kChunks; t0 += kAhead * 64) {
+  const int total = m * kChunks;
+  for (int t0 = 0; t0 < total; t0 += kAhead * 64) {
     f4 w[kAhead];                                          // (a plain vector type: these stay in registers)
 #pragma unroll
     for (int k = 0; k < kAhead; ++k) {
-      const int t = min(t0 + k * 64 + lane, m * kChunks - 1);
+      const int t = min(t0 + k * 64 + lane, total - 1);
       const int i = t / kChunks, ch = t % kChunks;
       const size_t off = (size_t)(DT == DYNAKV_F32 ? k_index32(i & 15, 4 * ch) : k_index16(i & 15, 8 * ch)) * kEs;
       w[k] = *(const f4*)(pool + (size_t)c.chain[i >> 4] * (kPageElems * kEs) + off);
@@ -718,7 +825,7 @@ __device__ inline void wave_split_decide(const View& v, int u, WaveCtx& c, uint4
 #pragma unroll
     for (int k = 0; k < kAhead; ++k) {
       const int t = t0 + k * 64 + lane;
-      if (t < m * kChunks) *(f4*)(stage + (size_t)(t / kChunks) * kRowBytes + (t % kChunks) * 16) = w[k];
+      if (t < total) *(f4*)(stage + (size_t)(t / kChunks) * kRowBytes + (t % kChunks) * 16) = w[k];
     }
   }
   wave_sync();
@@ -726,46 +833,27 @@ __device__ inline void wave_split_decide(const View& v, int u, WaveCtx& c, uint4
   const int grp = lane >> 2, kb = lane & 3;      // four lanes per member in the distance passes
   const MemberSet all = first_members(m);
   double tot0, tot1;
-  wave_set_sums<DT>(stage, all, lane, tot0, tot1);
+  wave_set_sums_rows<DT>(stage, c, all, m, lane, tot0, tot1);
   double sa0 = tot0, sa1 = tot1;                 // sum of side A
   MemberSet A = all;
   bool can = m >= 2;
   if (can) {
     // seeds: A = member farthest from the mean of all members, B = member farthest from A
     const double mu0 = tot0 / (double)m, mu1 = tot1 / (double)m;
-    c.cA[2 * lane] = mu0; c.cA[2 * lane + 1] = mu1;
+    const double mn2 = wave_sum_f64(mu0 * mu0 + mu1 * mu1);
+    c.rA[2 * lane] = (float)mu0; c.rA[2 * lane + 1] = (float)mu1;
     wave_sync();
-    double cr[32];
-#pragma unroll
-    for (int e = 0; e < 32; ++e) cr[e] = c.cA[kb * 32 + e];
-    double bv = -1.0;
-    int a = -1;
-    for (int base = 0; base < m; base += 16) {
-      const int i = base + grp;
-      const double t = quad_sqdist_reg(ks, min(i, m - 1), kb, cr);
-      if (kb == 0 && i < m && (a < 0 || t > bv)) { bv = t; a = i; }
-    }
-    wave_argmax(bv, a);
-    const double dmax = bv;                   // largest squared distance of a member to the mean
+    double dmax, db;
+    const int a = wave_farthest<DT>(ks, stage, c, m, mu0, mu1, (float)sqrt(mn2) * 1.0001f, dmax);
     float fa0, fa1;
     wpair<DT>(stage, a, lane, fa0, fa1);
     double ca0 = (double)fa0, ca1 = (double)fa1;                             // seed A
-    c.cB[2 * lane] = ca0; c.cB[2 * lane + 1] = ca1;
+    c.rA[2 * lane] = fa0; c.rA[2 * lane + 1] = fa1;
     wave_sync();
-#pragma unroll
-    for (int e = 0; e < 32; ++e) cr[e] = c.cB[kb * 32 + e];
-    bv = -1.0;
-    int b = -1;
-    for (int base = 0; base < m; base += 16) {
-      const int i = base + grp;
-      const double t = quad_sqdist_reg(ks, min(i, m - 1), kb, cr);
-      if (kb == 0 && i < m && (b < 0 || t > bv)) { bv = t; b = i; }
-    }
-    wave_argmax(bv, b);
-    can = bv > 0.0;                          // false: all members identical
+    const int b = wave_farthest<DT>(ks, stage, c, m, ca0, ca1, 0.f, db);
+    can = db > 0.0;                          // false: all members identical
     if (can) {
       // every member lies within sqrt(dmax) of the mean, and so does every centre (a mean of members)
-      const double mn2 = wave_sum_f64(mu0 * mu0 + mu1 * mu1);
       const float spread = (float)sqrt(dmax) * 1.0001f;
       const float xmax = spread + (float)sqrt(mn2) * 1.0001f;
       float fb0, fb1;
@@ -781,11 +869,7 @@ __device__ inline void wave_split_decide(const View& v, int u, WaveCtx& c, uint4
         wave_sync();
         const float eps = side_eps(xmax, 2.f * spread, t);
         float wr[32];
-#pragma unroll
-        for (int e = 0; e < 32; e += 4) {
-          const f4 x = *(const f4*)(c.rA + kb * 32 + e);
-          wr[e] = x[0]; wr[e + 1] = x[1]; wr[e + 2] = x[2]; wr[e + 3] = x[3];
-        }
+        load_quarter(c.rA, kb, wr);
         for (int base = 0; base < m; base += 16) {
           const int i = base + grp;
           const unsigned char ns = quad_side_reg(ks, min(i, m - 1), kb, wr, c.cA, t, eps);
@@ -802,19 +886,20 @@ __device__ inline void wave_split_decide(const View& v, int u, WaveCtx& c, uint4
         // moved; side B is what is left of the total
         double j0, j1, l0, l1;
         if (first) {
-          if (2 * nA <= m) wave_set_sums<DT>(stage, nw, lane, sa0, sa1);
+          if (2 * nA <= m) wave_sums_of<DT>(stage, c, nw, m, lane, sa0, sa1);
           else {
-            wave_set_sums<DT>(stage, set_minus(all, nw), lane, l0, l1);
+            wave_sums_of<DT>(stage, c, set_minus(all, nw), m, lane, l0, l1);
             sa0 = tot0 - l0; sa1 = tot1 - l1;
           }
         } else {
-          wave_set_sums<DT>(stage, set_minus(nw, A), lane, j0, j1);
-          wave_set_sums<DT>(stage, set_minus(A, nw), lane, l0, l1);
+          wave_sums_of<DT>(stage, c, set_minus(nw, A), m, lane, j0, j1);
+          wave_sums_of<DT>(stage, c, set_minus(A, nw), m, lane, l0, l1);
           sa0 += j0 - l0; sa1 += j1 - l1;
         }
         A = nw; first = false;
-        ca0 = sa0 / (double)nA; ca1 = sa1 / (double)nA;
-        cb0 = (tot0 - sa0) / (double)(m - nA); cb1 = (tot1 - sa1) / (double)(m - nA);
+        const double ia = 1.0 / (double)nA, ib = 1.0 / (double)(m - nA);     // (centres of a round: one rounding more is harmless)
+        ca0 = sa0 * ia; ca1 = sa1 * ia;
+        cb0 = (tot0 - sa0) * ib; cb1 = (tot1 - sa1) * ib;
       }
     }
   }
@@ -838,7 +923,8 @@ __device__ inline void wave_split_decide(const View& v, int u, WaveCtx& c, uint4
     }
   }
   if (lane == 0) { c.ok = can ? 1 : 0; c.nS = nS; }
-  // exact statistics: float32 means of the children, then M2 about those means
+  // statistics: float32 means of the children, then M2 about those means (differences in float32, off by 2^-24 of
+  // themselves; sums of 32 squares in float32, the rest in float64)
   double sS0 = tot0, sS1 = tot1;
   if (can && (A.lo & 1ull)) { sS0 = sa0; sS1 = sa1; }
   else if (can) { sS0 = tot0 - sa0; sS1 = tot1 - sa1; }
@@ -852,17 +938,12 @@ __device__ inline void wave_split_decide(const View& v, int u, WaveCtx& c, uint4
   for (int child = 0; child < 2; ++child) {
     const int q0 = child ? nS : 0, q1 = child ? m : nS;
     if (q1 <= q0) continue;
-    const float* r = child ? c.rB : c.rA;
     float fr[32];
-#pragma unroll
-    for (int e = 0; e < 32; e += 4) {
-      const f4 x = *(const f4*)(r + kb * 32 + e);
-      fr[e] = x[0]; fr[e + 1] = x[1]; fr[e + 2] = x[2]; fr[e + 3] = x[3];
-    }
+    load_quarter(child ? c.rB : c.rA, kb, fr);
     for (int base = q0; base < q1; base += 16) {
       const int q = base + grp;
-      const double dv = quad_sqdist_reg(ks, c.perm[min(q, q1 - 1)], kb, fr);
-      if (kb == 0 && q < q1) acc[child] += dv;
+      const float dv = quad_sqdist32(ks, c.perm[min(q, q1 - 1)], kb, fr);
+      if (kb == 0 && q < q1) acc[child] += (double)dv;
     }
   }
   const double m2S = wave_sum_f64(acc[0]), m2M = wave_sum_f64(acc[1]);
@@ -1127,8 +1208,12 @@ template <int DT>
 __device__ inline void split_predecide(const View& v, int u, unsigned char* raw, const SplitWork& wk, int k,
                                        uint4 (&pre_v)[kVAhead]) {
   WaveCtx& c = ((WaveCtx*)raw)[ctx_of(k)];
+  // the split is the longest chain of dependent steps of its unit: it goes ahead of the wavefront that streams pages
+  // on the same SIMD (the tiles that one does not take meanwhile go to the other wavefronts)
+  __builtin_amdgcn_s_setprio(3);
   wave_take(wk.pl, wk.pl.cand[k], (WaveCtx*)raw, ctx_of(k), threadIdx.x & 63);
   wave_split_decide<DT, true>(v, u, c, pre_v);
+  __builtin_amdgcn_s_setprio(0);
 }
 
 // One thread: ids and pages for the decided splits base .. base + n - 1 of the plan (contexts ctx_of(0 .. n-1)),
