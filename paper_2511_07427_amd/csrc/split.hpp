@@ -992,16 +992,17 @@ __device__ inline void wave_split_commit(const View& v, int u, WaveCtx& c, const
         if (i < m) *(uint4*)vdest(i, t % kChunks) = vahead[k];
       }
     }
-    // then the members past those (all, if nothing was requested ahead), four loads in flight per lane
-    for (int t0 = ahead ? kVAhead * 64 : 0; t0 < m * kChunks; t0 += 4 * 64) {
-      f4 w[4];
+    // then the members past those (all, if nothing was requested ahead), sixteen loads in flight per lane
+    constexpr int kVFlight = 16;
+    for (int t0 = ahead ? kVAhead * 64 : 0; t0 < m * kChunks; t0 += kVFlight * 64) {
+      f4 w[kVFlight];
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
+      for (int k = 0; k < kVFlight; ++k) {
         const int t = min(t0 + k * 64 + lane, m * kChunks - 1), i = t / kChunks;
         w[k] = *(const f4*)(pool + (size_t)c.chain[i >> 4] * kPageBytes + vchunk(i & 15, t % kChunks));
       }
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
+      for (int k = 0; k < kVFlight; ++k) {
         const int t = t0 + k * 64 + lane;
         if (t < m * kChunks) *(f4*)vdest(t / kChunks, t % kChunks) = w[k];
       }
