@@ -269,6 +269,14 @@ dynakv_status_t dynakv_import_state(dynakv_index_t* index, const dynakv_state_t*
  * appends and splits) is bracketed by HIP events on its own stream.  dynakv_profile_read synchronises those events and
  * returns the number of launches and their summed duration in milliseconds since the last enable. */
 dynakv_status_t dynakv_profile_enable(dynakv_index_t* index, int32_t max_launches);
+/* Two events around a launch cost the stream several microseconds between kernels and are themselves inside
+ * what they measure.  With every > 1 only the launches k (counted from the last enable) with k % every < run are
+ * timed, each such run of consecutive launches inside ONE bracket: an even sample of the whole run of calls.
+ * dynakv_profile_enable's max_launches then counts brackets, and dynakv_profile_read returns the launches inside
+ * completed brackets with their summed duration.  run > 1 is meant for dynakv_decode_step where the step is one
+ * kernel: whatever else the stream executes between the launches of a run lies inside the bracket.
+ * every < 1, run < 1 or run > every: DYNAKV_EINVAL.  Stays in force until set again; (1, 1) at creation. */
+dynakv_status_t dynakv_profile_sample(dynakv_index_t* index, int32_t every, int32_t run);
 dynakv_status_t dynakv_profile_read(dynakv_index_t* index, int32_t* n_launches, double* total_ms);
 /* Name of the kernel those events bracket: "retrieve_fused_kernel" (scores + selection + gather + attention in
  * one launch; in dynakv_decode_step the append and the splits as well) or "gather_attend_kernel". */

@@ -97,6 +97,7 @@ def load():
         lib.dynakv_export_state.argtypes = [vp, C.POINTER(_State), vp]
         lib.dynakv_import_state.argtypes = [vp, C.POINTER(_State), vp]
         lib.dynakv_profile_enable.argtypes = [vp, i32]
+        lib.dynakv_profile_sample.argtypes = [vp, i32, i32]
         lib.dynakv_profile_read.argtypes = [vp, C.POINTER(i32), C.POINTER(C.c_double)]
         lib.dynakv_profiled_kernel.restype = C.c_char_p
         lib.dynakv_profiled_kernel.argtypes = [vp]
@@ -235,6 +236,9 @@ class Index:
     # ---- timing aid ---------------------------------------------------------------------------
     def dynakv_profile_enable(self, max_launches: int):
         _check(self._lib.dynakv_profile_enable(self._h, int(max_launches)), "dynakv_profile_enable")
+
+    def dynakv_profile_sample(self, every: int, run: int = 1):
+        _check(self._lib.dynakv_profile_sample(self._h, int(every), int(run)), "dynakv_profile_sample")
 
     def dynakv_profile_read(self):
         n, ms = C.c_int32(), C.c_double()

@@ -20,6 +20,8 @@ struct dynakv_index {
   bool profiling;
   std::vector<hipEvent_t> ev;   // start/stop pairs
   int n_prof;
+  int prof_every = 1, prof_run = 1;   // of every prof_every launches the first prof_run are timed, as one bracket
+  long long prof_seen = 0;            // launches since the last enable
 };
 
 namespace {
@@ -212,16 +214,19 @@ static dynakv_status_t retrieve_impl(dynakv_index_t* ix, const View& view, const
   const bool fused = retrieve_is_fused(view);
   *appended = fused && kin;
   if (!fused && launch_score_select(view, Q, token_budget, kin, st) != hipSuccess) return DYNAKV_EHIP;
-  const bool prof = ix->profiling && 2 * (ix->n_prof + 1) <= (int)ix->ev.size();
-  if (prof && hipEventRecord(ix->ev[2 * ix->n_prof], st) != hipSuccess) return DYNAKV_EHIP;
+  const int phase = ix->profiling ? (int)(ix->prof_seen++ % ix->prof_every) : -1;
+  const bool prof = phase >= 0 && phase < ix->prof_run && 2 * (ix->n_prof + 1) <= (int)ix->ev.size();
+  if (prof && phase == 0 && hipEventRecord(ix->ev[2 * ix->n_prof], st) != hipSuccess) return DYNAKV_EHIP;
   if (fused) {
     if (launch_retrieve_fused(view, Q, token_budget, out, lse, kin, vin, split, st) != hipSuccess) return DYNAKV_EHIP;
   } else if (launch_gather_attend(view, Q, out, lse, st) != hipSuccess) {
     return DYNAKV_EHIP;
   }
   if (prof) {
-    if (hipEventRecord(ix->ev[2 * ix->n_prof + 1], st) != hipSuccess) return DYNAKV_EHIP;
-    ++ix->n_prof;
+    if (phase == ix->prof_run - 1) {
+      if (hipEventRecord(ix->ev[2 * ix->n_prof + 1], st) != hipSuccess) return DYNAKV_EHIP;
+      ++ix->n_prof;
+    }
   }
   return DYNAKV_OK;
 }
@@ -367,6 +372,14 @@ dynakv_status_t dynakv_profile_enable(dynakv_index_t* ix, int32_t max_launches) 
   }
   ix->profiling = max_launches > 0;
   ix->n_prof = 0;
+  ix->prof_seen = 0;
+  return DYNAKV_OK;
+}
+
+dynakv_status_t dynakv_profile_sample(dynakv_index_t* ix, int32_t every, int32_t run) {
+  if (!ix || every < 1 || run < 1 || run > every) return DYNAKV_EINVAL;
+  ix->prof_every = every;
+  ix->prof_run = run;
   return DYNAKV_OK;
 }
 
@@ -379,7 +392,7 @@ dynakv_status_t dynakv_profile_read(dynakv_index_t* ix, int32_t* n_launches, dou
     if (hipEventElapsedTime(&ms, ix->ev[2 * i], ix->ev[2 * i + 1]) != hipSuccess) return DYNAKV_EHIP;
     tot += ms;
   }
-  *n_launches = ix->n_prof;
+  *n_launches = ix->n_prof * ix->prof_run;       // launches inside completed brackets
   *total_ms = tot;
   return DYNAKV_OK;
 }
