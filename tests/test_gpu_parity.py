@@ -120,6 +120,39 @@ def test_long_run_through_the_whole_step_call_group_of_7():
     assert r["splits"] > 500 and r["most_splits_in_a_step"] >= 2
 
 
+@pytest.mark.parametrize("dtype,step_call", [("f16", "one"), ("bf16", "one"), ("f32", "three"), ("f16", "three")])
+def test_splits_of_large_clusters(dtype, step_call):
+    # prefill clusters of several dozen to a few hundred entries that the drift splits early: up to 64 entries of a
+    # 16-bit type (32 of float32) one wavefront each, four side by side; up to 128 (64) one wavefront each, two
+    # side by side; larger ones by the whole workgroup.  The sizes of the clusters that were split are taken from
+    # the oracle's records before and after every step.
+    s = CONFIGS["llama3_8b"].scaled(dtype=dtype, prefill=1536, n_clusters_init=20, var_alpha=1.02, max_cluster_factor=16,
+                                    kmeans_iters=4, budget=512)
+    units, steps = [0, 1, 2, 3], 192
+    w = generate(s, units=units, steps=steps)
+    ix, o = make_pair(s, len(units), max_tokens=s.prefill + steps)
+    ix.dynakv_build_index(to_dev(w["K0"], s.dtype), to_dev(w["V0"], s.dtype), torch.from_numpy(w["init_idx"]).to(DEV))
+    o.build_index(w["K0"], w["V0"], w["init_idx"])
+    st = parity.Stepper(ix, o, s, w, None, None)
+    compare_build(ix, o, st.tally, s.prefill)
+    parents = []
+    for t in range(steps):
+        before = [o.clusters(k) for k in range(len(units))]
+        st.step(t, step_call == "one", attention=t % 4 == 0, full=t % 32 == 0 or t == steps - 1)
+        for k in range(len(units)):
+            after = o.clusters(k)
+            if len(after["n"]) > len(before[k]["n"]):
+                m0 = before[k]["n"] + before[k]["b"]
+                m1 = (after["n"] + after["b"])[:len(m0)]
+                parents += [int(x) for x in m0[m1 < m0]]
+    r = st.report()
+    small = 32 if dtype == "f32" else 64
+    hist = dict(one_per_lane=sum(p <= small for p in parents), two_per_lane=sum(small < p <= 2 * small for p in parents),
+                workgroup=sum(p > 2 * small for p in parents))
+    say("large clusters,", dtype, step_call, hist, {k: r[k] for k in ("worst_rel", "ties", "splits", "forced", "clusters")})
+    assert hist["two_per_lane"] >= 3 and hist["workgroup"] >= 1 and (hist["one_per_lane"] >= 3 or dtype == "f32")
+
+
 @pytest.mark.parametrize("name,sample,steps,iters", [
     ("llama3_8b", [0, 131, 255], 1280, None),     # what the benchmark times
     ("batched16", [0, 77, 127], 96, None),
