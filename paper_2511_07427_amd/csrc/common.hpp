@@ -75,7 +75,7 @@ struct View {
   int* cpg;          // [.][8] first pages of the cluster (-1: none); later pages follow pnext
   int* ctail;        // last page
   float* score;      // last scores
-  int* sel_ids;      // ids in score order
+  int* sel_ids;      // the active set in the order it is attended: ascending id, or (selection with its keys in memory) descending score
   unsigned char* in_req;  // membership in the last active set
   int* tok_off;      // scratch: exclusive prefix of sizes in score order
   int* pg_off;       // scratch: exclusive prefix of gather-list entry counts in score order

@@ -196,121 +196,13 @@ __device__ __forceinline__ void emit_page(int page, int nv, int w, int t0, int* 
 }
 
 // Gather-list entry: one aligned group of four token slots ("quad") of a page,
-// page * 16 + quad * 4 + (valid tokens - 1); `t0` is the gather offset of its first token.
-__device__ inline int emit_cluster(const View& v, int u, size_t cj, int take, int w, int t0, int* plist, int* poff,
-                                   int* lds_list, int lds_cap) {
-  int left = take, page = -1;
-  for (int k = 0; left > 0; ++k) {
-    page = cluster_page(v, u, cj, k, page);
-    if (page < 0) break;
-    const int nv = min(left, kPageTokens);
-    for (int qd = 0; 4 * qd < nv; ++qd) {
-      const int e = page * 16 + qd * 4 + (min(4, nv - 4 * qd) - 1);
-      plist[w] = e;
-      if (w < lds_cap) lds_list[w] = e;
-      poff[w] = t0 + 4 * qd;
-      ++w;
-    }
-    t0 += nv; left -= nv;
-  }
-  return w;
-}
-
-// Full sort (any selection size): bitonic sort of all clusters by (score desc, id asc), prefix sums over the
-// sorted sizes, cut at the budget.  Same results as select_phase below.
-template <int NT>
-__device__ inline int select_sorted(const View& v, int u, int M, int budget, const SelectLds& s) {
-  constexpr int KCH = kSelectLds / NT;      // consecutive ranks per thread in the prefix sums
-  const int tid = threadIdx.x;
-  const size_t cb = (size_t)u * v.Mcap;
-  uint32_t* skey = s.skey;
-  uint16_t* sid = (uint16_t*)s.region;
-  int* s_cut = s.misc, *s_tsel = s.misc + 1;
-  int Mpad = 2;
-  while (Mpad < M) Mpad <<= 1;
-  for (int i = tid; i < Mpad; i += NT) sid[i] = i < M ? (uint16_t)i : (uint16_t)0xFFFF;
-  if (tid == 0) { *s_cut = 0; *s_tsel = 0; }
-  __syncthreads();
-  // a goes before b if its score is larger, or equal with the smaller id
-  for (int k = 2; k <= Mpad; k <<= 1)
-    for (int j = k >> 1; j > 0; j >>= 1) {
-      for (int i = tid; i < Mpad; i += NT) {
-        const int ixj = i ^ j;
-        if (ixj > i) {
-          const uint32_t ka = skey[i], kb = skey[ixj];
-          const uint16_t ia = sid[i], ib = sid[ixj];
-          const bool b_first = kb > ka || (kb == ka && ib < ia);
-          const bool up = (i & k) == 0;
-          if (b_first == up) { skey[i] = kb; skey[ixj] = ka; sid[i] = ib; sid[ixj] = ia; }
-        }
-      }
-      __syncthreads();
-    }
-  // token prefix in score order: KCH consecutive ranks per thread
-  int sz[KCH], tot = 0;
-#pragma unroll
-  for (int k = 0; k < KCH; ++k) {
-    const int p = tid * KCH + k;
-    sz[k] = p < M ? v.cn[cb + sid[p]] + v.cb[cb + sid[p]] : 0;
-    tot += sz[k];
-  }
-  int total;
-  int run = block_excl_scan(tot, s.sm, total);
-  int cnt = 0, fit = 0;
-#pragma unroll
-  for (int k = 0; k < KCH; ++k) {
-    const int p = tid * KCH + k;
-    if (p < M) {
-      v.tok_off[cb + p] = run;
-      run += sz[k];
-      if (run <= budget) { ++cnt; fit = run; }   // prefix sums are monotone: these ranks form a prefix
-    }
-  }
-  if (cnt) { atomicAdd(s_cut, cnt); atomicMax(s_tsel, fit); }
-  __syncthreads();
-  int cut = *s_cut, tsel = *s_tsel;
-  const bool truncated = cut == 0 && M > 0 && budget > 0;     // best cluster alone is over budget
-  if (truncated) { cut = 1; tsel = budget; }
-  // quad prefix over the selected ranks
-  tot = 0;
-#pragma unroll
-  for (int k = 0; k < KCH; ++k) {
-    const int p = tid * KCH + k;
-    const int t = truncated ? budget : sz[k];
-    sz[k] = p < cut ? (t + 3) / 4 : 0;
-    tot += sz[k];
-  }
-  run = block_excl_scan(tot, s.sm, total);
-#pragma unroll
-  for (int k = 0; k < KCH; ++k) {
-    const int p = tid * KCH + k;
-    if (p < M) { v.pg_off[cb + p] = run; run += sz[k]; }
-  }
-  __syncthreads();
-  int* plist = v.plist + (size_t)u * v.Lcap;
-  int* poff = v.plist_off + (size_t)u * v.Lcap;
-  for (int p = tid; p < M; p += NT) {
-    const int id = sid[p];
-    v.sel_ids[cb + p] = id;
-    v.in_req[cb + id] = p < cut;
-    if (p < cut && s.selbits) atomicOr(&s.selbits[id >> 5], 1u << (id & 31));
-    if (p < cut)
-      emit_cluster(v, u, cb + id, truncated ? budget : v.cn[cb + id] + v.cb[cb + id], v.pg_off[cb + p],
-                   v.tok_off[cb + p], plist, poff, s.list, s.list_cap);
-  }
-  if (tid == 0) {
-    v.n_sel[u] = cut; v.t_sel[u] = tsel; v.n_list[u] = total; v.ticket[u] = 0;
-    count(v, u, 4, tsel);
-    count(v, u, 5, 1);
-    count(v, u, 6, M);
-  }
-  return total;
-}
+// page * 16 + quad * 4 + (valid tokens - 1); its gather offset is that of its first token.
 
 // Selection for one unit, run by a whole workgroup of NT threads (NT >= 256).  Clusters are ordered by
 // (score desc, id asc); the active set is the longest prefix of that order whose stored sizes fit the budget
 // (or the best cluster alone, cut to the budget, if even that one does not fit).  Records the active set and
-// writes the gather list in that order.  Returns the number of gather-list entries.
+// writes the gather list: in ascending cluster id where keys, sizes and the set's bitmap are in LDS (emit_by_id;
+// no selected cluster is ranked), in score order otherwise.  Returns the number of gather-list entries.
 //
 // Puts the positions 0 .. cut-1 of the candidate keys ck into 256 bins by the leading bits in which the keys'
 // scores differ (counting sort, bins in descending order) and returns the shift that yields a key's bin:
@@ -372,10 +264,102 @@ __device__ __forceinline__ void for_each_key(int M, KeyAt&& key_at, F&& f) {
   }
 }
 
-// Only the selected clusters are ordered.  The score at which the running size first exceeds the budget is
-// found by a radix search over the 32-bit orderable scores (four passes of size-weighted 256-bin histograms);
-// everything above it is selected, equal scores are taken by ascending id while they fit.  Each selected
-// cluster then finds its rank and its gather offsets by counting the selected clusters that precede it.
+// Exclusive prefix sums of three ints over the threads of a block at once (blockDim.x a multiple of 64, at most
+// 1024); `sm` needs 48 ints.  a, b, c become the prefixes, ta, tb, tc the block sums.
+template <bool LDS_ONLY>
+__device__ inline void block_excl_scan3(int& a, int& b, int& c, int* sm, int& ta, int& tb, int& tc) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  const int xa = wave_incl_scan(a), xb = wave_incl_scan(b), xc = wave_incl_scan(c);
+  block_barrier<LDS_ONLY>();
+  if (lane == 63) { sm[3 * w] = xa; sm[3 * w + 1] = xb; sm[3 * w + 2] = xc; }
+  block_barrier<LDS_ONLY>();
+  int ba = 0, bb = 0, bc = 0;
+  ta = 0; tb = 0; tc = 0;
+  for (int k = 0; k < nw; ++k) {
+    const int ya = sm[3 * k], yb = sm[3 * k + 1], yc = sm[3 * k + 2];
+    if (k < w) { ba += ya; bb += yb; bc += yc; }
+    ta += ya; tb += yb; tc += yc;
+  }
+  a = ba + xa - a; b = bb + xb - b; c = bc + xc - c;
+}
+
+// Records the active set held in s.selbits and writes its gather list, in ascending cluster id: thread t takes the
+// R = ceil(M / NT) <= 8 clusters t R .. t R + R - 1 (sizes in s.sw), one block-wide prefix sum places every cluster's
+// entries.  No cluster is ranked: the order in which selected clusters are attended does not matter to the method.
+// take_all >= 0: the one selected cluster contributes this many entries instead of its size.
+// Returns the number of gather-list entries; the caller's barrier makes the list in LDS visible.
+template <int NT>
+__device__ inline int emit_by_id(const View& v, int u, int M, const SelectLds& s, int take_all) {
+  const int tid = threadIdx.x;
+  const size_t cb = (size_t)u * v.Mcap;
+  const int R = max(1, (M + NT - 1) / NT);               // workgroup-uniform
+  const int j0 = tid * R;
+  unsigned bits = 0;
+  if (j0 < M) {                                          // the R bits from j0 on (they may straddle two words)
+    const int wd = j0 >> 5, sh = j0 & 31;
+    const unsigned lo = s.selbits[wd], hi = sh + R > 32 ? s.selbits[wd + 1] : 0u;
+    bits = (unsigned)((((unsigned long long)hi << 32) | lo) >> sh) & ((1u << R) - 1u);
+  }
+  int w[8];
+  int tok = 0, quads = 0, cnt = 0;
+  int4 pa[8], pb[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    pa[e] = int4{-1, -1, -1, -1}; pb[e] = int4{-1, -1, -1, -1};
+    w[e] = 0;
+    if (e < R && ((bits >> e) & 1u)) {
+      w[e] = take_all >= 0 ? take_all : s.sw[j0 + e];
+      tok += w[e]; quads += (w[e] + 3) >> 2; ++cnt;
+      // the cluster's page table is requested now and used once its place in the list is known
+      const int4* row = (const int4*)&v.cpg[(cb + j0 + e) * kInlinePages];
+      pa[e] = row[0];
+      if (w[e] > 4 * kPageTokens) pb[e] = row[1];
+    }
+  }
+  int t_tok, t_quads, t_cnt;
+  block_excl_scan3<true>(tok, quads, cnt, s.sm, t_tok, t_quads, t_cnt);
+  int* plist = v.plist + (size_t)u * v.Lcap;
+  int* poff = v.plist_off + (size_t)u * v.Lcap;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    if (e >= R) break;                                   // workgroup-uniform
+    if (!((bits >> e) & 1u)) continue;
+    v.sel_ids[cb + cnt] = j0 + e;
+    const int take = w[e], npages = (take + kPageTokens - 1) / kPageTokens;
+    const int pgs[kInlinePages] = {pa[e].x, pa[e].y, pa[e].z, pa[e].w, pb[e].x, pb[e].y, pb[e].z, pb[e].w};
+    int page = -1;
+#pragma unroll
+    for (int k = 0; k < kInlinePages; ++k)
+      if (k < npages) {
+        page = pgs[k];
+        if (page >= 0)
+          emit_page(page, min(kPageTokens, take - k * kPageTokens), quads + 4 * k, tok + k * kPageTokens, plist, poff,
+                    s.list, s.list_cap);
+      }
+    for (int kk = kInlinePages; kk < npages && page >= 0; ++kk) {    // pages past the inline table: walk the chain
+      page = v.pnext[(size_t)u * v.Pcap + page];
+      if (page >= 0)
+        emit_page(page, min(kPageTokens, take - kk * kPageTokens), quads + 4 * kk, tok + kk * kPageTokens, plist, poff,
+                  s.list, s.list_cap);
+    }
+    tok += take; quads += (take + 3) >> 2; ++cnt;
+  }
+  if (tid == 0) {
+    v.n_sel[u] = t_cnt; v.t_sel[u] = t_tok; v.n_list[u] = t_quads; v.ticket[u] = 0;
+    count(v, u, 4, t_tok);
+    count(v, u, 5, 1);
+    count(v, u, 6, M);
+  }
+  return t_quads;
+}
+
+// No cluster outside the active set is ever ordered.  The score at which the running size first exceeds the budget
+// is found by a radix search over the 32-bit orderable scores (four passes of size-weighted 256-bin histograms);
+// everything above it is selected, equal scores are taken by ascending id while they fit.  With keys, sizes and
+// the active set's bitmap in LDS (s.skey, s.sw, s.selbits; at most 8 clusters per thread) the gather list then
+// follows the cluster ids (emit_by_id).  Otherwise (more clusters than LDS holds) each selected cluster finds its
+// rank and its gather offsets by counting the selected clusters that precede it: the list is in score order, and at
+// most CMAX clusters can be selected (more: the retrieval is cut short and DYNAKV_ERR_SELECT is set).
 // first_ready: the caller has zeroed s.hist and set s.misc (entry 4 = 0x7fffffff, the others 0), has added every
 // cluster's size to bin (key >> 24) of the first histogram, and a barrier lies behind all of that.
 //
@@ -383,9 +367,8 @@ __device__ __forceinline__ void for_each_key(int M, KeyAt&& key_at, F&& f) {
 // would give lies within eps of the float32 one, so every cluster more than 2 eps above it is selected and every
 // cluster more than 2 eps below it is not, whatever the exact values; the clusters in between (the band, normally
 // the cluster at the cut alone) are re-scored in float64 by the first wavefront and taken in exact order while
-// they fit.  The selected SET is therefore that of exact arithmetic; the order of the selected clusters (the
-// gather order) follows the float32 scores.  Bands of more than kBandMax clusters (degenerate inputs: many equal
-// scores) and selections of more than kCountMax clusters are resolved on the float32 scores alone.
+// they fit.  The selected SET is therefore that of exact arithmetic.  Bands of more than kBandMax clusters
+// (degenerate inputs: many equal scores) are resolved on the float32 scores alone.
 template <int NT, int CMAX = kCountMax>
 __device__ inline int select_phase(const View& v, int u, int M, int budget, const SelectLds& s, const SelectExact& ex,
                                    bool first_ready = false) {
@@ -396,6 +379,8 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
 #define DYNAKV_WEIGHT(j) (s.sw ? s.sw[j] : v.csz[cb + (j)])
 #define DYNAKV_KEY(j) (s.skey ? s.skey[j] : orderable(v.score[cb + (j)]))
   auto key_at = [&](int j) __attribute__((always_inline)) { return DYNAKV_KEY(j); };
+  // keys, sizes and the active set's bitmap in LDS: nothing is ranked, the list follows the cluster ids (emit_by_id)
+  const bool id_order = s.skey && s.sw && s.selbits && M <= 8 * NT;
   if (!first_ready) {
     for (int i = tid; i < 1024; i += NT) s.hist[i] = 0;
     if (tid < 8) s.misc[tid] = tid == 4 ? 0x7fffffff : 0;
@@ -511,8 +496,11 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
       v.in_req[cb + j] = sel;
       if (sel) {
         if (s.selbits) atomicOr(&s.selbits[j >> 5], 1u << (j & 31));
-        const int pos = atomicAdd(&s.misc[2], 1);
-        if (pos < CMAX) { ck[pos] = ((unsigned long long)k << kIdBits) | (unsigned)(kIdMask - j); cw[pos] = DYNAKV_WEIGHT(j); }
+        if (id_order) s.misc[2] = 1;                        // (something is selected)
+        else {
+          const int pos = atomicAdd(&s.misc[2], 1);
+          if (pos < CMAX) { ck[pos] = ((unsigned long long)k << kIdBits) | (unsigned)(kIdMask - j); cw[pos] = DYNAKV_WEIGHT(j); }
+        }
       }
     } else if (cross && !refined && k == kstar) {
       atomicAdd(&s.misc[3], 1);
@@ -522,8 +510,11 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
       v.in_req[cb + j] = sel;
       if (sel) {
         if (s.selbits) atomicOr(&s.selbits[j >> 5], 1u << (j & 31));
-        const int pos = atomicAdd(&s.misc[2], 1);
-        if (pos < CMAX) { ck[pos] = ((unsigned long long)k << kIdBits) | (unsigned)(kIdMask - j); cw[pos] = DYNAKV_WEIGHT(j); }
+        if (id_order) s.misc[2] = 1;                        // (something is selected)
+        else {
+          const int pos = atomicAdd(&s.misc[2], 1);
+          if (pos < CMAX) { ck[pos] = ((unsigned long long)k << kIdBits) | (unsigned)(kIdMask - j); cw[pos] = DYNAKV_WEIGHT(j); }
+        }
       }
     }
   });
@@ -560,18 +551,32 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
         v.in_req[cb + j] = sel;
         if (sel) {
           if (s.selbits) atomicOr(&s.selbits[j >> 5], 1u << (j & 31));
-          const int pos = atomicAdd(&s.misc[2], 1);
-          if (pos < CMAX) { ck[pos] = ((unsigned long long)kstar << kIdBits) | (unsigned)(kIdMask - j); cw[pos] = DYNAKV_WEIGHT(j); }
+          if (id_order) s.misc[2] = 1;
+          else {
+            const int pos = atomicAdd(&s.misc[2], 1);
+            if (pos < CMAX) { ck[pos] = ((unsigned long long)kstar << kIdBits) | (unsigned)(kIdMask - j); cw[pos] = DYNAKV_WEIGHT(j); }
+          }
         }
       }
     lds_barrier();
   } else if (cross && !refined && tid == 0) {
     v.in_req[cb + xid] = 0;
   }
+  if (id_order) {
+    const bool truncated = cross && s.misc[2] == 0 && budget > 0;    // the best cluster alone is over budget: its first entries
+    if (truncated) {
+      __syncthreads();                                 // (another thread may have cleared the same active-set flag)
+      if (tid == 0) {
+        v.in_req[cb + xid] = 1;
+        atomicOr(&s.selbits[xid >> 5], 1u << (xid & 31));
+      }
+      lds_barrier();
+    }
+    return emit_by_id<NT>(v, u, M, s, truncated ? budget : -1);
+  }
   int cut = s.misc[2], tsel = !cross ? total : refined ? s.misc[5] : above + tie_w;
   if (cut > CMAX) {
     __syncthreads();
-    if (s.skey) return select_sorted<NT>(v, u, M, budget, s);
     // keys are not in LDS (more than kSelectLds clusters) and more clusters are selected than can be ordered:
     // the retrieval is cut short to the CMAX candidates at hand and the unit's error word says so
     if (tid == 0) atomicOr(&v.err[u], DYNAKV_ERR_SELECT);
@@ -737,7 +742,8 @@ __global__ __launch_bounds__(1024) void select_kernel(View v, const void* Q, int
   constexpr int CMAX = BIG ? kCountBig : kCountMax;
   constexpr int kRegion = BIG ? CMAX * 12 : 2 * kSelectLds;
   __shared__ uint32_t skey_[BIG ? 1 : kSelectLds];
-  __shared__ int ssz_[BIG ? 1 : kSelectLds];                 // cluster sizes: every pass of the selection reads them
+  __shared__ __align__(16) int ssz_[BIG ? 1 : kSelectLds];   // cluster sizes: every pass of the selection reads them
+  __shared__ unsigned selbits_[BIG ? 1 : kSelectLds / 32];   // the active set, one bit per cluster
   __shared__ __align__(16) unsigned char region[kRegion];
   __shared__ __align__(16) int hist[1024];
   __shared__ __align__(16) int sm[64];
@@ -754,6 +760,7 @@ __global__ __launch_bounds__(1024) void select_kernel(View v, const void* Q, int
       skey_[i] = i < M ? orderable(v.score[(size_t)u * v.Mcap + i]) : 0u;
       if (i < M) ssz_[i] = v.csz[(size_t)u * v.Mcap + i];
     }
+    if (tid < kSelectLds / 32) selbits_[tid] = 0u;
   }
   // |q_g| of every head, one wavefront per head (only where the scores came from the matrix cores)
   SelectExact ex{0.f, Q};
@@ -773,7 +780,7 @@ __global__ __launch_bounds__(1024) void select_kernel(View v, const void* Q, int
     for (int g = 0; g < v.G; ++g) qb = v.group_reduce == DYNAKV_GROUP_MAX ? fmaxf(qb, qn[g]) : qb + qn[g];
     ex.eps = score_eps(v, qb, __int_as_float(v.rmax2[u]));
   }
-  const SelectLds s{BIG ? nullptr : skey_, BIG ? nullptr : ssz_, region, hist, srt, sm, misc, nullptr, 0, nullptr};
+  const SelectLds s{BIG ? nullptr : skey_, BIG ? nullptr : ssz_, region, hist, srt, sm, misc, nullptr, 0, BIG ? nullptr : selbits_};
   select_phase<1024, CMAX>(v, u, M, budget, s, ex);
 }
 
@@ -1160,7 +1167,7 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   __shared__ float am_2[16];
   __shared__ int am_r[16];
   __shared__ int s_tile;                              // next tile of the page stream
-  __shared__ unsigned selbits[kFusedClusters / 32];    // the active set, for the plan of the splits
+  __shared__ unsigned selbits[kFusedClusters / 32];    // the active set: for the gather list and the plan of the splits
   __shared__ __align__(16) int sm[64];
   __shared__ int misc[8];
   uint32_t* skey = (uint32_t*)smem;
@@ -1218,7 +1225,7 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   for (int i = tid; i < 1024; i += NT) hist[i] = 0;
   if (tid < 8) misc[tid] = tid == 4 ? 0x7fffffff : 0;
   if (tid == 0) { s_tile = 0; if constexpr (SPLIT) wk.ready = 0; }
-  if (SPLIT && tid < kFusedClusters / 32) selbits[tid] = 0u;
+  if (tid < kFusedClusters / 32) selbits[tid] = 0u;
 #pragma unroll
   for (int k = 0; k < kFusedClusters / NT; ++k)
     if (tid + k * NT < M) ssz[tid + k * NT] = szr[k];
@@ -1287,7 +1294,7 @@ __global__ __launch_bounds__(NW * 64) void retrieve_fused_kernel(View v, const v
   }
 
   // ---- selection
-  const SelectLds sel{skey, ssz, smem + kKeys + kSizes, hist, ssz, sm, misc, list, kFusedList, SPLIT ? selbits : nullptr};
+  const SelectLds sel{skey, ssz, smem + kKeys + kSizes, hist, ssz, sm, misc, list, kFusedList, selbits};
   const SelectExact ex{score_eps(v, rn.qbound, unit_rmax2), Q};
   const int nlist = select_phase<NT>(v, u, M, budget, sel, ex, true);
   // a full barrier only where other threads read back what the selection wrote to memory: a list too long for LDS

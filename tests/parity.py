@@ -138,8 +138,9 @@ def compare_retrieval(ix: binding.Index, o: Oracle, tally: Tally, what="", gathe
             tally["tie_select"] += 1
             dirty.add(ou)
             continue
-        # same set: the library's order must follow the oracle's scores up to the bound on its own scores
-        if len(gsel) > 1:
+        # same set.  The order in which the clusters are attended is the library's own: ascending id, or, where the
+        # selection keeps its keys in memory (more than 8192 clusters), the oracle's score order up to the bound
+        if len(gsel) > 1 and not (np.diff(gsel) > 0).all():
             s_in_order = sc_all[gsel]
             slack = (score_bound(ix, Q[ou], o.search_copy(ou)) if Q is not None else 0.0) * 2 + 1.2e-7 * np.abs(s_in_order).max()
             worst = (s_in_order[1:] - s_in_order[:-1]).max()
