@@ -572,6 +572,29 @@ def test_rebuild_resets_the_index_and_runs_are_deterministic():
         assert torch.equal(a[k], b[k]), k
 
 
+def test_timing_aid_brackets_an_even_sample_of_the_launches():
+    s = CONFIGS["llama3_8b"].scaled(prefill=512, n_clusters_init=32, budget=128)
+    U = 2
+    w = generate(s, units=range(U), steps=32)
+    ix = binding.Index(binding.Config(U, s.group_size, s.dtype, 32, 128, 512 + 32, 3, 16, 0, s.var_alpha, s.size_factor, 0.0), DEV)
+    ix.dynakv_build_index(to_dev(w["K0"], s.dtype), to_dev(w["V0"], s.dtype), torch.from_numpy(w["init_idx"]).to(DEV))
+    Qd, Kd, Vd = to_dev(w["Q"], s.dtype), to_dev(w["Knew"], s.dtype), to_dev(w["Vnew"], s.dtype)
+    out, lse = torch.empty(U, s.group_size, 128, device=DEV), torch.empty(U, s.group_size, device=DEV)
+    lib = binding.load()
+    assert lib.dynakv_profile_sample(ix._h, 0, 1) == binding.EINVAL and lib.dynakv_profile_sample(ix._h, 4, 5) == binding.EINVAL
+    t = 0
+    for every, run, steps, want in ((1, 1, 6, 6), (4, 2, 10, 6), (4, 4, 7, 4), (3, 1, 6, 2)):
+        ix.dynakv_profile_sample(every, run)
+        ix.dynakv_profile_enable(16)
+        for _ in range(steps):
+            ix.dynakv_decode_step(Qd[t], 128, out, lse, Kd[t], Vd[t])
+            t += 1
+        n, ms = ix.dynakv_profile_read()
+        assert n == want and 0.0 < ms < 50.0, (every, run, steps, n, ms)
+    ix.dynakv_profile_sample(1, 1)
+    ix.dynakv_profile_enable(0)
+
+
 # --------------------------------------------------------------------------- exported and imported state
 
 @pytest.mark.parametrize("name,launch", [("llama3_8b", 0), ("tiny", 0), ("qwen25_7b", launch_shape(2, 0, LAUNCH_SEPARATE))])
