@@ -153,6 +153,43 @@ def test_splits_of_large_clusters(dtype, step_call):
     assert hist["two_per_lane"] >= 3 and hist["workgroup"] >= 1 and (hist["one_per_lane"] >= 3 or dtype == "f32")
 
 
+@pytest.mark.parametrize("dtype,step_call", [("f16", "one"), ("bf16", "one"), ("f16", "three"), ("f32", "three")])
+def test_splits_of_degenerate_large_clusters(dtype, step_call):
+    # one large cluster per unit that the size trigger flags at the first append and that is split at once
+    # (B_max = 0): 100 equal keys (no second seed: unflagged with exact statistics), 99 equal keys and one apart
+    # (split 99 / 1, the second seed is the lowest of 99 equally far members), two values of 60 keys each, and 129
+    # equal keys (workgroup path)
+    N0, d = 160, 128
+    s = WorkloadSpec("degenerate", dtype, 4, 2, N0, 2, 2, 64, 6, 0.05, var_alpha=0.0, size_factor=1.0, buffer_max=0,
+                     kmeans_iters=2, max_cluster_factor=8, seed=77)
+    w = generate(s, steps=2)
+    a = np.full(d, 5.0, np.float32)
+    apart = a.copy(); apart[0] = 8.0
+    b = a.copy(); b[:4] += 0.5
+    K0 = w["K0"].copy()
+    sizes = (100, 100, 120, 129)
+    K0[0, :100] = a
+    K0[1, :100] = a; K0[1, 57] = apart
+    K0[2, :120:2] = a; K0[2, 1:120:2] = b
+    K0[3, :129] = a
+    init = np.array([[0, n] for n in sizes], np.int32)
+    w = dict(w, K0=K0, init_idx=init)
+    w["Knew"] = w["Knew"].copy(); w["Knew"][0, :] = a
+    ix, o = make_pair(s, 4, max_tokens=N0 + 2)
+    ix.dynakv_build_index(to_dev(K0, dtype), to_dev(w["V0"], dtype), torch.from_numpy(init).to(DEV))
+    o.build_index(K0, w["V0"], init)
+    st = parity.Stepper(ix, o, s, w, None, None)
+    compare_build(ix, o, st.tally, N0)
+    assert [int(o.clusters(k)["n"][0]) for k in range(4)] == list(sizes)
+    for t in range(2):
+        st.step(t, step_call == "one", attention=True, full=True)
+    r = st.report()
+    say("degenerate clusters,", dtype, step_call, {k: r[k] for k in ("worst_rel", "ties", "splits", "failed", "clusters")})
+    assert r["failed"] == 2 and r["splits"] >= 2
+    c1, c2 = o.clusters(1), o.clusters(2)
+    assert {1, 100} <= set(c1["n"].tolist()) and {60, 61} <= set(c2["n"].tolist())
+
+
 @pytest.mark.parametrize("name,sample,steps,iters", [
     ("llama3_8b", [0, 131, 255], 1280, None),     # what the benchmark times
     ("batched16", [0, 77, 127], 96, None),
