@@ -26,10 +26,10 @@ MFMA_PEAK_TFLOPS = 2500.0      # dense fp16/bf16, published
 # 256 MiB written).  Keyed by (config, steps, warmup, units); "rev" is kernel_revision() of the sources the
 # counters were taken with: another revision of the kernels, or other arguments, report null.
 PMC_TRAFFIC = {
-    ("llama3_8b", 8192, 64, 0): {"rev": "549ff4e0e0bd", "kernel": "retrieve_fused_kernel", "fetch_kib": 111289.5,
-                                 "fetch_scale": 524288.0 / 262169.56, "write_kib": 4662.0, "write_scale": 262144.0 / 262144.0},
-    ("llama3_8b", 20, 5, 0): {"rev": "549ff4e0e0bd", "kernel": "retrieve_fused_kernel", "fetch_kib": 85349.2,
-                              "fetch_scale": 524288.0 / 262169.75, "write_kib": 2379.5, "write_scale": 262144.0 / 262144.0},
+    ("llama3_8b", 8192, 64, 0): {"rev": "1035b3543096", "kernel": "retrieve_fused_kernel", "fetch_kib": 111299.5,
+                                 "fetch_scale": 524288.0 / 262168.94, "write_kib": 4661.7, "write_scale": 262144.0 / 262144.0},
+    ("llama3_8b", 20, 5, 0): {"rev": "1035b3543096", "kernel": "retrieve_fused_kernel", "fetch_kib": 85354.7,
+                              "fetch_scale": 524288.0 / 262170.0, "write_kib": 2379.3, "write_scale": 262144.0 / 262144.0},
 }
 
 

@@ -239,7 +239,7 @@ typedef struct {
   float* scores;         /* [U][max_clusters]   scores of the last retrieval                     */
   int32_t* n_selected;   /* [U]                 clusters selected by the last retrieval          */
   int32_t* selected;     /* [U][max_clusters]   their ids in the order they are attended: ascending id
-                                                (descending score where max_clusters > 8192)     */
+                                                (descending score where max_clusters > 16384)     */
   int32_t* n_gathered;   /* [U]                 entries attended by the last retrieval           */
   int32_t* gathered;     /* [U][max_tokens]     their token positions in gather order            */
   int32_t* last_assign;  /* [U]                 cluster chosen by the last append                */

@@ -14,7 +14,7 @@ constexpr int kPageTokens = 16;                 // tokens per page = one MFMA ti
 constexpr int kPageElems = 2 * kPageTokens * kHeadDim;  // K region then V region
 constexpr int kMaxClusters = 131072;            // per unit (the selection packs an id into 18 bits)
 constexpr int kMaxInitClusters = 8192;          // clusters built at prefill
-constexpr int kSelectLds = 8192;                // clusters whose scores and sizes the selection keeps in LDS; beyond,
+constexpr int kSelectLds = 16384;               // clusters whose scores and sizes the selection keeps in LDS; beyond,
                                                 // it reads them from memory in every pass
 constexpr int kMaxPrefill = 16384;              // k-means sorts one unit's labels in LDS
 constexpr int kFusedClusters = 4096;            // clusters per unit the single-kernel retrieval can hold in LDS

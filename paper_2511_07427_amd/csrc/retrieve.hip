@@ -284,12 +284,14 @@ __device__ inline void block_excl_scan3(int& a, int& b, int& c, int* sm, int& ta
 }
 
 // Records the active set held in s.selbits and writes its gather list, in ascending cluster id: thread t takes the
-// R = ceil(M / NT) <= 8 clusters t R .. t R + R - 1 (sizes in s.sw), one block-wide prefix sum places every cluster's
-// entries.  No cluster is ranked: the order in which selected clusters are attended does not matter to the method.
+// R = ceil(M / NT) <= MAXR (8 or 16) clusters t R .. t R + R - 1 (sizes in s.sw), one block-wide prefix sum places
+// every cluster's entries.  No cluster is ranked: the order in which selected clusters are attended does not matter
+// to the method.  Page tables are requested and lists written eight clusters at a time.
 // take_all >= 0: the one selected cluster contributes this many entries instead of its size.
 // Returns the number of gather-list entries; the caller's barrier makes the list in LDS visible.
-template <int NT>
+template <int NT, int MAXR>
 __device__ inline int emit_by_id(const View& v, int u, int M, const SelectLds& s, int take_all) {
+  static_assert(MAXR == 8 || MAXR == 16, "rounds of eight clusters");
   const int tid = threadIdx.x;
   const size_t cb = (size_t)u * v.Mcap;
   const int R = max(1, (M + NT - 1) / NT);               // workgroup-uniform
@@ -300,49 +302,62 @@ __device__ inline int emit_by_id(const View& v, int u, int M, const SelectLds& s
     const unsigned lo = s.selbits[wd], hi = sh + R > 32 ? s.selbits[wd + 1] : 0u;
     bits = (unsigned)((((unsigned long long)hi << 32) | lo) >> sh) & ((1u << R) - 1u);
   }
-  int w[8];
+  int w[MAXR];
   int tok = 0, quads = 0, cnt = 0;
   int4 pa[8], pb[8];
+  // the page tables of a round's clusters are requested together and used once their places in the list are known
+  auto request = [&](int base) __attribute__((always_inline)) {
 #pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    pa[e] = int4{-1, -1, -1, -1}; pb[e] = int4{-1, -1, -1, -1};
+    for (int e = 0; e < 8; ++e) {
+      pa[e] = int4{-1, -1, -1, -1}; pb[e] = int4{-1, -1, -1, -1};
+      if (base + e < R && ((bits >> (base + e)) & 1u)) {
+        const int4* row = (const int4*)&v.cpg[(cb + j0 + base + e) * kInlinePages];
+        pa[e] = row[0];
+        if (w[base + e] > 4 * kPageTokens) pb[e] = row[1];
+      }
+    }
+  };
+#pragma unroll
+  for (int e = 0; e < MAXR; ++e) {
     w[e] = 0;
     if (e < R && ((bits >> e) & 1u)) {
       w[e] = take_all >= 0 ? take_all : s.sw[j0 + e];
       tok += w[e]; quads += (w[e] + 3) >> 2; ++cnt;
-      // the cluster's page table is requested now and used once its place in the list is known
-      const int4* row = (const int4*)&v.cpg[(cb + j0 + e) * kInlinePages];
-      pa[e] = row[0];
-      if (w[e] > 4 * kPageTokens) pb[e] = row[1];
     }
   }
+  request(0);
   int t_tok, t_quads, t_cnt;
   block_excl_scan3<true>(tok, quads, cnt, s.sm, t_tok, t_quads, t_cnt);
   int* plist = v.plist + (size_t)u * v.Lcap;
   int* poff = v.plist_off + (size_t)u * v.Lcap;
 #pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    if (e >= R) break;                                   // workgroup-uniform
-    if (!((bits >> e) & 1u)) continue;
-    v.sel_ids[cb + cnt] = j0 + e;
-    const int take = w[e], npages = (take + kPageTokens - 1) / kPageTokens;
-    const int pgs[kInlinePages] = {pa[e].x, pa[e].y, pa[e].z, pa[e].w, pb[e].x, pb[e].y, pb[e].z, pb[e].w};
-    int page = -1;
+  for (int base = 0; base < MAXR; base += 8) {
+    if (base >= R) break;                                // workgroup-uniform
+    if (base > 0) request(base);
 #pragma unroll
-    for (int k = 0; k < kInlinePages; ++k)
-      if (k < npages) {
-        page = pgs[k];
+    for (int e = 0; e < 8; ++e) {
+      if (base + e >= R) break;                          // workgroup-uniform
+      if (!((bits >> (base + e)) & 1u)) continue;
+      v.sel_ids[cb + cnt] = j0 + base + e;
+      const int take = w[base + e], npages = (take + kPageTokens - 1) / kPageTokens;
+      const int pgs[kInlinePages] = {pa[e].x, pa[e].y, pa[e].z, pa[e].w, pb[e].x, pb[e].y, pb[e].z, pb[e].w};
+      int page = -1;
+#pragma unroll
+      for (int k = 0; k < kInlinePages; ++k)
+        if (k < npages) {
+          page = pgs[k];
+          if (page >= 0)
+            emit_page(page, min(kPageTokens, take - k * kPageTokens), quads + 4 * k, tok + k * kPageTokens, plist, poff,
+                      s.list, s.list_cap);
+        }
+      for (int kk = kInlinePages; kk < npages && page >= 0; ++kk) {    // pages past the inline table: walk the chain
+        page = v.pnext[(size_t)u * v.Pcap + page];
         if (page >= 0)
-          emit_page(page, min(kPageTokens, take - k * kPageTokens), quads + 4 * k, tok + k * kPageTokens, plist, poff,
+          emit_page(page, min(kPageTokens, take - kk * kPageTokens), quads + 4 * kk, tok + kk * kPageTokens, plist, poff,
                     s.list, s.list_cap);
       }
-    for (int kk = kInlinePages; kk < npages && page >= 0; ++kk) {    // pages past the inline table: walk the chain
-      page = v.pnext[(size_t)u * v.Pcap + page];
-      if (page >= 0)
-        emit_page(page, min(kPageTokens, take - kk * kPageTokens), quads + 4 * kk, tok + kk * kPageTokens, plist, poff,
-                  s.list, s.list_cap);
+      tok += take; quads += (take + 3) >> 2; ++cnt;
     }
-    tok += take; quads += (take + 3) >> 2; ++cnt;
   }
   if (tid == 0) {
     v.n_sel[u] = t_cnt; v.t_sel[u] = t_tok; v.n_list[u] = t_quads; v.ticket[u] = 0;
@@ -356,7 +371,7 @@ __device__ inline int emit_by_id(const View& v, int u, int M, const SelectLds& s
 // No cluster outside the active set is ever ordered.  The score at which the running size first exceeds the budget
 // is found by a radix search over the 32-bit orderable scores (four passes of size-weighted 256-bin histograms);
 // everything above it is selected, equal scores are taken by ascending id while they fit.  With keys, sizes and
-// the active set's bitmap in LDS (s.skey, s.sw, s.selbits; at most 8 clusters per thread) the gather list then
+// the active set's bitmap in LDS (s.skey, s.sw, s.selbits; at most MAXR clusters per thread) the gather list then
 // follows the cluster ids (emit_by_id).  Otherwise (more clusters than LDS holds) each selected cluster finds its
 // rank and its gather offsets by counting the selected clusters that precede it: the list is in score order, and at
 // most CMAX clusters can be selected (more: the retrieval is cut short and DYNAKV_ERR_SELECT is set).
@@ -369,7 +384,7 @@ __device__ inline int emit_by_id(const View& v, int u, int M, const SelectLds& s
 // the cluster at the cut alone) are re-scored in float64 by the first wavefront and taken in exact order while
 // they fit.  The selected SET is therefore that of exact arithmetic.  Bands of more than kBandMax clusters
 // (degenerate inputs: many equal scores) are resolved on the float32 scores alone.
-template <int NT, int CMAX = kCountMax>
+template <int NT, int CMAX = kCountMax, int MAXR = 8>
 __device__ inline int select_phase(const View& v, int u, int M, int budget, const SelectLds& s, const SelectExact& ex,
                                    bool first_ready = false) {
   const int tid = threadIdx.x, lane = tid & 63;
@@ -380,7 +395,7 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
 #define DYNAKV_KEY(j) (s.skey ? s.skey[j] : orderable(v.score[cb + (j)]))
   auto key_at = [&](int j) __attribute__((always_inline)) { return DYNAKV_KEY(j); };
   // keys, sizes and the active set's bitmap in LDS: nothing is ranked, the list follows the cluster ids (emit_by_id)
-  const bool id_order = s.skey && s.sw && s.selbits && M <= 8 * NT;
+  const bool id_order = s.skey && s.sw && s.selbits && M <= MAXR * NT;
   if (!first_ready) {
     for (int i = tid; i < 1024; i += NT) s.hist[i] = 0;
     if (tid < 8) s.misc[tid] = tid == 4 ? 0x7fffffff : 0;
@@ -572,7 +587,7 @@ __device__ inline int select_phase(const View& v, int u, int M, int budget, cons
       }
       lds_barrier();
     }
-    return emit_by_id<NT>(v, u, M, s, truncated ? budget : -1);
+    return emit_by_id<NT, MAXR>(v, u, M, s, truncated ? budget : -1);
   }
   int cut = s.misc[2], tsel = !cross ? total : refined ? s.misc[5] : above + tie_w;
   if (cut > CMAX) {
@@ -740,7 +755,7 @@ constexpr int kCountBig = 4096;
 template <bool BIG>
 __global__ __launch_bounds__(1024) void select_kernel(View v, const void* Q, int budget) {
   constexpr int CMAX = BIG ? kCountBig : kCountMax;
-  constexpr int kRegion = BIG ? CMAX * 12 : 2 * kSelectLds;
+  constexpr int kRegion = CMAX * 12;
   __shared__ uint32_t skey_[BIG ? 1 : kSelectLds];
   __shared__ __align__(16) int ssz_[BIG ? 1 : kSelectLds];   // cluster sizes: every pass of the selection reads them
   __shared__ unsigned selbits_[BIG ? 1 : kSelectLds / 32];   // the active set, one bit per cluster
@@ -760,7 +775,7 @@ __global__ __launch_bounds__(1024) void select_kernel(View v, const void* Q, int
       skey_[i] = i < M ? orderable(v.score[(size_t)u * v.Mcap + i]) : 0u;
       if (i < M) ssz_[i] = v.csz[(size_t)u * v.Mcap + i];
     }
-    if (tid < kSelectLds / 32) selbits_[tid] = 0u;
+    for (int i = tid; i < kSelectLds / 32; i += 1024) selbits_[i] = 0u;
   }
   // |q_g| of every head, one wavefront per head (only where the scores came from the matrix cores)
   SelectExact ex{0.f, Q};
@@ -781,7 +796,7 @@ __global__ __launch_bounds__(1024) void select_kernel(View v, const void* Q, int
     ex.eps = score_eps(v, qb, __int_as_float(v.rmax2[u]));
   }
   const SelectLds s{BIG ? nullptr : skey_, BIG ? nullptr : ssz_, region, hist, srt, sm, misc, nullptr, 0, BIG ? nullptr : selbits_};
-  select_phase<1024, CMAX>(v, u, M, budget, s, ex);
+  select_phase<1024, CMAX, BIG ? 8 : kSelectLds / 1024>(v, u, M, budget, s, ex);
 }
 
 // ------------------------------------------------------------------------------------------- attention

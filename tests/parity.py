@@ -139,7 +139,7 @@ def compare_retrieval(ix: binding.Index, o: Oracle, tally: Tally, what="", gathe
             dirty.add(ou)
             continue
         # same set.  The order in which the clusters are attended is the library's own: ascending id, or, where the
-        # selection keeps its keys in memory (more than 8192 clusters), the oracle's score order up to the bound
+        # selection keeps its keys in memory (more than 16384 clusters), the oracle's score order up to the bound
         if len(gsel) > 1 and not (np.diff(gsel) > 0).all():
             s_in_order = sc_all[gsel]
             slack = (score_bound(ix, Q[ou], o.search_copy(ou)) if Q is not None else 0.0) * 2 + 1.2e-7 * np.abs(s_in_order).max()
