@@ -192,6 +192,7 @@ def test_splits_of_degenerate_large_clusters(dtype, step_call):
 
 @pytest.mark.parametrize("name,sample,steps,iters", [
     ("llama3_8b", [0, 131, 255], 1280, None),     # what the benchmark times
+    ("llama3_8b", [0, 100, 255], 8256, None),     # ... over its whole horizon (warm-up and timed steps)
     ("batched16", [0, 77, 127], 96, None),
     ("qwen25_7b", [0, 58, 111], 512, None),
     ("long131k", [6], 96, 3),                     # separate kernels, 4 workgroups per unit in gather + attention
@@ -200,7 +201,7 @@ def test_full_size_configurations_on_sampled_units(name, sample, steps, iters):
     # all units of the configuration, default launch shape, one whole-step call per step; the oracle follows
     # a few of the units (k-means shortened where the oracle's prefill would take minutes)
     s = CONFIGS[name] if iters is None else CONFIGS[name].scaled(kmeans_iters=iters)
-    r = parity.run_full_size(s, sample, steps, check_every=32, full_every=256)
+    r = parity.run_full_size(s, sample, steps, check_every=32 if steps < 4096 else 64, full_every=256 if steps < 4096 else 512)
     say("full size, %s:" % name, r)
     assert r["splits"] > 0 or name in ("batched16", "long131k")
 
