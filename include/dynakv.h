@@ -31,8 +31,9 @@
  *               the nearest cluster among all candidates within the error bound of the best, and
  *               the budget cut among all clusters whose score lies within the bound of the cut.
  *               The selected set therefore is the one of exact arithmetic; the order in which the
- *               selected clusters are attended follows the float32 scores.  Ties go to the lowest
- *               index.  Attention uses matrix cores with float32 accumulation.
+ *               selected clusters are attended is the library's own (ascending id; descending
+ *               float32 score where max_clusters > 16384).  Ties go to the lowest index.
+ *               Attention uses matrix cores with float32 accumulation.
  */
 #ifndef DYNAKV_H
 #define DYNAKV_H
@@ -80,7 +81,7 @@ typedef enum {
 #define DYNAKV_ERR_TOKENS 1   /* append refused: max_tokens or page pool exhausted            */
 #define DYNAKV_ERR_CLUSTERS 2 /* split refused: max_clusters reached (cluster stays flagged)   */
 #define DYNAKV_ERR_SPLIT_SIZE 4 /* split refused: cluster larger than the split kernel handles */
-#define DYNAKV_ERR_SELECT 8   /* retrieval cut short: more clusters selected than the selection can order */
+#define DYNAKV_ERR_SELECT 8   /* retrieval cut short: max_clusters > 16384 and more than 4096 clusters selected */
 #define DYNAKV_ERR_INIT 16    /* dynakv_build_index: an initial position out of range or given twice */
 #define DYNAKV_ERR_IMPORT 32  /* dynakv_import_state: inconsistent sizes; the unit keeps its previous state */
 #define DYNAKV_ERR_PLACE 64   /* dynakv_place_by_coretrieval: the unit is not as dynakv_build_index left it; not re-placed */
