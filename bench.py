@@ -346,6 +346,9 @@ def main():
         "roofline": roof,
         "prefill": {"ms": prefill_ms, "kmeans_algorithmic_tflops": kmeans_flop / (prefill_ms * 1e-3) / 1e12,
                     "frac_of_mfma_peak": kmeans_flop / (prefill_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS,
+                    # the other bound of the k-means (it applies below about 312 initial clusters): every iteration
+                    # must read the keys once
+                    "frac_of_hbm_peak": spec.kmeans_iters * U * spec.prefill * d * esz / (prefill_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                     "chunked_second_half": chunked},
         "index": {"clusters_mean": float(state["n_clusters"].float().mean()), "clusters_max": int(state["n_clusters"].max()),
                   "splits": int(c1[:, 0].sum()),
